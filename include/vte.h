@@ -1,0 +1,405 @@
+/*
+ * vte.h — C ABI of the late-binding runtime and its fixed-structure kernels
+ * for one MI355X (gfx950, 256 CUs in 8 XCDs).
+ *
+ * What the library does, in the paper's terms:
+ *   - an *immutable operation descriptor* D_k holds a kernel entry, the values
+ *     of its launch arguments (pointers by value), grid and block dimensions,
+ *     dynamic LDS bytes and attributes (Sec. 4.2, "Immutable Operation
+ *     Descriptors").  Nothing in scheduling ever modifies one;
+ *   - a *physical context* (pCtx) is one replaceable allocation of compute
+ *     units: here a HIP stream created with a CU mask (Sec. 3.4 names
+ *     CU-masked queues as the AMD primitive; Sec. 4.3 defines the pCtx, its
+ *     four states and the bounded, pre-created hierarchical pool);
+ *   - a *virtual stream* keeps the logical order of the launches submitted to
+ *     it as a chain of completion tokens (Sec. 4.2, "Token-Based Logical
+ *     Dependencies");
+ *   - the *dispatcher* binds each logically ready launch to an eligible,
+ *     non-conflicting pCtx proposed by a policy, re-validates the proposal,
+ *     submits the descriptor unchanged and propagates completion (Sec. 4.4);
+ *   - the policy is three callbacks Pick / Select / Prepare (Sec. 4.5).
+ * Because the grid, block shape and floating-point reduction tree of every
+ * kernel below are functions of the problem shape only, the output bits of a
+ * descriptor are the same on every pCtx (the parallel-structure invariant,
+ * Sec. 3.1).  The *_splitk / *_reshaped descriptors are the negative control:
+ * their structure is derived from a CU count (Sec. 2.3, C~_k = g(C_k, R_k)).
+ *
+ * Conventions
+ *   - every function returns int: VTE_OK (0) or a negative VTE_E* code; no
+ *     exception crosses the boundary.  vte_last_error() returns a thread-local
+ *     message for the last failure on the calling thread, vte_last_hip_error()
+ *     the HIP error code behind a VTE_EHIP.
+ *   - "device pointer" = address in the HBM of the device given to vte_init,
+ *     owned by the caller, who keeps the buffer alive and free of races until
+ *     the launch's token is done (Sec. 4.2: contents of referenced memory and
+ *     their synchronisation stay under application control).  "host pointer"
+ *     = ordinary process memory.  The library never allocates or frees device
+ *     memory on the launch path; descriptors, streams, events and tokens are
+ *     owned by the library.
+ *   - bf16 tensors are raw 16-bit patterns (upper half of an IEEE binary32),
+ *     row-major, innermost dimension contiguous.
+ *   - thread safety: every call may be made from any thread; one internal
+ *     dispatcher thread per vte_ctx does policy-driven binding and completion
+ *     polling (Sec. 6: client-side submission thread, batched event polling).
+ */
+#ifndef VTE_H_
+#define VTE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* ---- error codes ---------------------------------------------------------- */
+enum {
+  VTE_OK = 0,
+  VTE_EINVAL = -1,    /* bad argument (null pointer, shape not supported, bad id) */
+  VTE_ENOMEM = -2,    /* host allocation failed */
+  VTE_EHIP = -3,      /* a HIP call failed; see vte_last_hip_error() */
+  VTE_EBUSY = -4,     /* lease conflict, closed gate or reservation held by another owner */
+  VTE_ENOTREADY = -5, /* a predecessor token is not yet satisfied */
+  VTE_EINCOMPAT = -6, /* the pCtx cannot run the descriptor unchanged */
+  VTE_ESTATE = -7,    /* call not valid in the current state (e.g. fake-only hook on HIP backend) */
+  VTE_ETIMEOUT = -8   /* a bounded wait expired */
+};
+
+const char* vte_last_error(void);
+int vte_last_hip_error(void);
+
+/* ---- opaque handles ------------------------------------------------------- */
+typedef struct vte_ctx vte_ctx;         /* one device + pool + dispatcher */
+typedef struct vte_desc vte_desc;       /* immutable launch descriptor D_k */
+typedef struct vte_vstream vte_vstream; /* logical stream of a virtual context */
+typedef uint64_t vte_token;             /* completion token; 0 = "already satisfied" */
+
+/* ---- pool configuration (Sec. 4.3, "Hierarchical pCtx Pool") --------------- */
+enum { VTE_BACKEND_HIP = 0, VTE_BACKEND_FAKE = 1 };
+/* STRICT: an op is bound only after the host has observed every predecessor's
+ * completion (Sec. 4.4, "Readiness Before Binding").  PIPELINED: up to
+ * `lookahead` successors of in-flight ops are bound early and the edge is kept
+ * on the device (stream order on the same pCtx, an event wait across pCtxs);
+ * descriptors, H and therefore output bits are the same in both modes. */
+enum { VTE_MODE_STRICT = 0, VTE_MODE_PIPELINED = 1 };
+/* STRIPED: mask bit i is handed to hipExtStreamCreateWithCUMask unchanged; on
+ * MI355X consecutive bits fall on consecutive XCDs, so a run of w bits is w/8
+ * CUs on each of the 8 XCDs.  It is the only layout offered. */
+enum { VTE_LAYOUT_STRIPED = 0 };
+
+typedef struct vte_pool_cfg {
+  int backend;         /* VTE_BACKEND_* */
+  int total_cus;       /* 0 = ask the device (HIP) / 256 (FAKE) */
+  int leaf_cus;        /* minimum allocation unit; 0 = 32 */
+  int layout;          /* VTE_LAYOUT_STRIPED */
+  int with_remainders; /* 1: pre-create one remainder pCtx per non-root node */
+  int mode;            /* VTE_MODE_* */
+  int lookahead;       /* PIPELINED: max unfinished ops bound ahead per vstream; 0 = 16 */
+  int stats_capacity;  /* ring size of per-op records kept for vte_stats_read; 0 = 65536 */
+} vte_pool_cfg;
+
+/* Fills *cfg with the defaults (HIP, device CU count, leaf 32, remainders, STRICT). */
+int vte_pool_cfg_default(vte_pool_cfg* cfg);
+
+/* Creates the context on `device`: builds the pool tree, pre-creates one
+ * CU-masked stream per pCtx and starts the dispatcher thread.  Nothing is
+ * created on the dispatch path afterwards.  FAKE backend: no HIP call at all;
+ * launches are logged and complete when vte_fake_complete() says so. */
+int vte_init(vte_ctx** out, int device, const vte_pool_cfg* cfg);
+/* Waits for all submitted work, stops the dispatcher, destroys streams/events.
+ * Descriptors and vstreams still alive are destroyed too. */
+int vte_shutdown(vte_ctx* ctx);
+
+/* ---- pCtx pool introspection ------------------------------------------------ */
+enum { VTE_PCTX_NODE = 0, VTE_PCTX_REMAINDER = 1 };
+enum { VTE_PCTX_IDLE = 0, VTE_PCTX_LEASED = 1, VTE_PCTX_DRAINING = 2, VTE_PCTX_RESERVED = 3 };
+
+typedef struct vte_pctx_info {
+  int id;
+  int kind;          /* VTE_PCTX_NODE | VTE_PCTX_REMAINDER */
+  int width;         /* number of CUs */
+  int level;         /* NODE: depth in the tree (0 = root); REMAINDER: level of its node */
+  int parent;        /* NODE: parent node id or -1; REMAINDER: the node it complements */
+  int child[2];      /* NODE: children or -1,-1 (leaf); REMAINDER: -1,-1 */
+  int remainder;     /* NODE: id of the pCtx spanning every other CU, -1 for the root */
+  int state;         /* VTE_PCTX_* */
+  int gate_open;     /* 1 = admits new operations */
+  int outstanding;   /* submitted, not yet observed complete */
+  int reserved_for;  /* vstream id holding (or waiting for) a reservation, else -1 */
+  uint32_t mask[8];  /* CU mask, bit i of word i/32 */
+} vte_pctx_info;
+
+int vte_pool_count(vte_ctx* ctx, int* count);
+int vte_pool_info(vte_ctx* ctx, int pctx_id, vte_pctx_info* info);
+/* First pCtx of kind NODE with this width (lowest id), or the n-th with `index`. */
+int vte_pool_find(vte_ctx* ctx, int kind, int width, int index, int* pctx_id);
+/* 1 if the two pCtxs share a CU.  Decided by walking the hierarchy, not by
+ * comparing masks (tests compare it with the mask intersection). */
+int vte_pool_conflict(vte_ctx* ctx, int pctx_a, int pctx_b, int* conflict);
+/* The hipStream_t behind a pCtx (HIP backend), so device allocations and copies
+ * made elsewhere can be ordered against it.  Owned by the library. */
+int vte_pctx_native_stream(vte_ctx* ctx, int pctx_id, void** hip_stream);
+
+/* ---- descriptors: one typed constructor per fixed-structure kernel ---------- */
+/* All constructors copy the argument VALUES now (pointer values included) and
+ * derive grid/block/LDS from the shape alone — never from a CU count.  The only
+ * HIP call they make is a one-time attribute on kernels that need more than
+ * 48 KiB of LDS.  *out is owned by the caller (vte_desc_destroy) and must outlive
+ * every launch made from it.  A descriptor may be launched any number of times. */
+
+/* y[r,i] = bf16( x[r,i] * rsqrt(mean_j x[r,j]^2 + eps) * gamma[i] ), fp32 sum of
+ * squares in a fixed tree, one rounding at the end.  x,y: device [rows,cols]
+ * bf16; gamma: device [cols] bf16.  cols % 8 == 0, cols <= 16384.
+ * (Operator family: Sec. 1 / Sec. 2.3 "reductions".) */
+int vte_desc_rmsnorm(vte_ctx* ctx, const void* x, const void* gamma, void* y, int rows,
+                     int cols, float eps, vte_desc** out);
+/* y = (x - mu) * rsqrt(var + eps) * gamma + beta, biased variance, two fixed-tree
+ * fp32 reductions (mean, then centred squares).  Same layout and limits. (Sec. 1) */
+int vte_desc_layernorm(vte_ctx* ctx, const void* x, const void* gamma, const void* beta,
+                       void* y, int rows, int cols, float eps, vte_desc** out);
+
+enum { VTE_EPI_NONE = 0, VTE_EPI_SILU_MUL = 1 };
+/* Y[b,n] = bf16( sum_k W[n,k] X[b,k] ).  W: device [N,K] bf16 (each output's K
+ * contiguous); X: device [B,K] bf16; Y: device [B,N] bf16.  1 <= B <= 16,
+ * K % 8 == 0.  fp32 accumulation in a tree that depends on K only: a K-tile of
+ * 256 is 32 lanes x 8 contiguous elements, a lane adds its tiles in ascending
+ * order, then one fixed butterfly over lanes.
+ * epilogue SILU_MUL: N must be even; rows [0,N/2) are gate, [N/2,N) up;
+ * Y is [B,N/2] = bf16( silu(g_fp32) * u_fp32 ).  (Sec. 1 "GEMV"; Sec. 2.3.) */
+int vte_desc_gemv(vte_ctx* ctx, const void* W, const void* X, void* Y, int B, int N, int K,
+                  int epilogue, vte_desc** out);
+
+/* logits[b,v] = sum_k W[v,k] H[b,k] in fp32 (never rounded to bf16);
+ * tok[b] = lowest v attaining the maximum (NaN never wins; all-NaN -> 0).
+ * W: device [V,K] bf16; H: device [B,K] bf16; tok: device [B] int32;
+ * logits_or_null: device [B,V] fp32 or NULL; workspace: device buffer of
+ * vte_lmhead_workspace_bytes() bytes, zero-filled by the caller before the
+ * first launch and private to launches of this descriptor that do not overlap
+ * in time.  (Sec. 7.1 / 7.2: LM-head logits and the greedy token.) */
+int vte_lmhead_workspace_bytes(int B, int V, int K, size_t* bytes);
+int vte_desc_lmhead_argmax(vte_ctx* ctx, const void* W, const void* H, int32_t* tok,
+                           float* logits_or_null, void* workspace, int B, int V, int K,
+                           vte_desc** out);
+
+/* The work decomposition of a GEMV-family descriptor, spelled out.  It is part
+ * of the submitted structure C_k: chosen from the shape by vte_gemv_default_plan,
+ * or given by the caller, and frozen in the descriptor.  rows_in_flight: weight
+ * rows a wave streams at once (2, 4 or 8; rows_in_flight * batch tile <= 64);
+ * waves: waves per workgroup (4, 8 or 16); groups: row groups a wave walks
+ * through; kc: K elements of X staged in LDS at a time (multiple of 512).
+ * The reduction tree of an output does not depend on any of them. */
+typedef struct vte_gemv_plan {
+  int rows_in_flight, waves, groups, kc;
+} vte_gemv_plan;
+int vte_gemv_default_plan(int B, int N, int K, int epilogue, int S, vte_gemv_plan* plan);
+int vte_desc_gemv_planned(vte_ctx* ctx, const void* W, const void* X, void* Y, int B, int N, int K,
+                          int epilogue, const vte_gemv_plan* plan, vte_desc** out);
+int vte_desc_lmhead_argmax_planned(vte_ctx* ctx, const void* W, const void* H, int32_t* tok,
+                                   float* logits_or_null, void* workspace, int B, int V, int K,
+                                   const vte_gemv_plan* plan, vte_desc** out);
+
+/* H[b,:] = E[tok[b],:].  E: device [V,K] bf16; tok: device [B] int32 (values in
+ * [0,V), clamped otherwise); H: device [B,K] bf16.  K % 8 == 0. */
+int vte_desc_gather(vte_ctx* ctx, const void* E, const int32_t* tok, void* H, int B, int V,
+                    int K, vte_desc** out);
+
+/* C = A * Bm^T, bf16 in, fp32 MFMA accumulation, bf16 out.  A: device [M,K];
+ * Bm: device [N,K]; C: device [M,N].  M,N % 256 == 0, K % 64 == 0.  Fixed 2-D
+ * tile grid, no split-K.  (The background training-shaped co-tenant; Sec. 7.5
+ * uses a BF16 GEMM as its probe.) */
+int vte_desc_gemm(vte_ctx* ctx, const void* A, const void* Bm, void* C, int M, int N, int K,
+                  vte_desc** out);
+
+/* ---- reshaping baselines (the negative control, Sec. 2.3 / Sec. 7.1) -------- */
+/* GEMV whose K range is cut into S contiguous chunks (S = active CUs / 32 in the
+ * experiments); the S fp32 partial sums of an output are written to the
+ * workspace and added in chunk order by whichever chunk-block finishes last.
+ * Same lanes, same instructions — only the grouping changes with S.
+ * workspace: device, vte_splitk_workspace_bytes(), zero-filled by the caller
+ * before the first launch, private to non-overlapping launches. */
+int vte_splitk_workspace_bytes(int B, int N, int S, size_t* bytes);
+int vte_desc_gemv_splitk(vte_ctx* ctx, const void* W, const void* X, void* Y, void* workspace,
+                         int B, int N, int K, int epilogue, int S, vte_desc** out);
+/* LM head with the same split: `workspace` as for vte_desc_lmhead_argmax,
+ * `partials` a second device buffer of vte_splitk_workspace_bytes(B,V,S). */
+int vte_desc_lmhead_argmax_splitk(vte_ctx* ctx, const void* W, const void* H, int32_t* tok,
+                                  float* logits_or_null, void* workspace, void* partials,
+                                  int B, int V, int K, int S, vte_desc** out);
+/* RMSNorm whose threads-per-row is derived from a CU count (64 threads per 32
+ * active CUs, clamped to [64,512]), which regroups the sum of squares. */
+int vte_desc_rmsnorm_reshaped(vte_ctx* ctx, const void* x, const void* gamma, void* y,
+                              int rows, int cols, float eps, int active_cus, vte_desc** out);
+
+/* ---- descriptor inspection --------------------------------------------------- */
+enum {
+  VTE_K_RMSNORM = 1, VTE_K_LAYERNORM = 2, VTE_K_GEMV = 3, VTE_K_LMHEAD = 4, VTE_K_GATHER = 5,
+  VTE_K_GEMM = 6, VTE_K_GEMV_SPLITK = 7, VTE_K_LMHEAD_SPLITK = 8, VTE_K_RMSNORM_RESHAPED = 9
+};
+typedef struct vte_desc_view {
+  int kernel;           /* VTE_K_* */
+  uint32_t grid[3];
+  uint32_t block[3];
+  uint32_t lds_bytes;   /* dynamic LDS */
+  uint32_t arg_bytes;   /* size of the copied argument block */
+  uint64_t hash;        /* FNV-1a over kernel, grid, block, lds and the argument bytes */
+  uint64_t profile_key; /* equal for descriptors of the same kernel and shape */
+  uint64_t bytes;       /* algorithmic HBM bytes of one launch */
+  uint64_t flops;       /* algorithmic flops of one launch */
+} vte_desc_view;
+int vte_desc_info(const vte_desc* desc, vte_desc_view* view);
+/* Copies min(cap, arg_bytes) bytes of the argument block to `dst` (host). */
+int vte_desc_args(const vte_desc* desc, void* dst, size_t cap);
+int vte_desc_destroy(vte_desc* desc);
+
+/* ---- explicit binding (tests, width sweeps, profiling) ------------------------ */
+/* Submits `desc` unchanged on pCtx `pctx_id` from the calling thread.  Bypasses
+ * the policy but not validation: VTE_EINCOMPAT if the pCtx cannot run it,
+ * VTE_EBUSY if the pCtx conflicts with another active lease, its gate is closed
+ * or it is reserved for a vstream.  Has no logical predecessor.  *token_out
+ * (may be NULL) is satisfied when the launch has completed. */
+int vte_bind_and_launch(vte_ctx* ctx, const vte_desc* desc, int pctx_id, vte_token* token_out);
+
+/* ---- virtual streams and policy-driven dispatch ------------------------------ */
+enum { VTE_CLASS_LATENCY = 0, VTE_CLASS_BEST_EFFORT = 1 };
+int vte_vstream_create(vte_ctx* ctx, int klass, vte_vstream** out);
+int vte_vstream_destroy(vte_vstream* vs); /* waits for its tail first */
+int vte_vstream_id(const vte_vstream* vs, int* id);
+/* Restricts the vstream's launches to one pCtx (the fixed-binding baseline);
+ * pctx_id = -1 removes the restriction. */
+int vte_vstream_pin(vte_vstream* vs, int pctx_id);
+/* The new op depends on the stream's tail token and becomes the new tail; an
+ * empty stream's tail is already satisfied (Sec. 4.2). */
+int vte_submit(vte_vstream* vs, const vte_desc* desc, vte_token* token_out);
+/* As vte_submit, with extra predecessor tokens from other vstreams (the edges an
+ * event wait would add; each token is an immutable completion point). */
+int vte_submit_after(vte_vstream* vs, const vte_desc* desc, const vte_token* deps, int n_deps,
+                     vte_token* token_out);
+int vte_token_query(vte_ctx* ctx, vte_token token, int* done);
+int vte_token_wait(vte_ctx* ctx, vte_token token);
+int vte_vstream_sync(vte_vstream* vs); /* waits on the stream tail */
+int vte_device_sync(vte_ctx* ctx);     /* waits on every vstream tail and explicit launch */
+
+/* ---- lease control used by policies (Sec. 4.3) -------------------------------- */
+/* LEASED -> DRAINING: outstanding work continues, nothing new is admitted; at
+ * zero outstanding the pCtx becomes IDLE (or RESERVED if a reservation waits). */
+int vte_pctx_close_gate(vte_ctx* ctx, int pctx_id);
+/* Holds the pCtx for `vs`: excluded, with every overlapping pCtx, from all other
+ * leases.  If overlapping work is still running the reservation is pending and
+ * takes effect when it has drained (VTE_OK either way; VTE_EBUSY if another
+ * vstream already holds or awaits a reservation that overlaps). */
+int vte_pctx_reserve(vte_ctx* ctx, int pctx_id, vte_vstream* vs);
+int vte_pctx_unreserve(vte_ctx* ctx, int pctx_id);
+
+/* ---- policy interface (Sec. 4.5) ------------------------------------------------ */
+typedef struct vte_ready_op {
+  vte_token token;
+  int vstream;          /* id, -1 for explicit launches */
+  int klass;            /* VTE_CLASS_* */
+  int pinned_pctx;      /* -1 if the vstream is not pinned */
+  uint64_t age;         /* submission sequence number (smaller = older) */
+  int pred_pctx;        /* PIPELINED: pCtx of an unfinished predecessor, else -1 */
+  vte_desc_view desc;
+} vte_ready_op;
+
+typedef struct vte_pool_view {     /* S: states, leases, reservations, gates */
+  int count;
+  const vte_pctx_info* pctx;       /* valid during the callback only */
+  int ready_by_class[2];           /* ready ops per class */
+  int inflight_by_class[2];        /* submitted, unfinished ops per class */
+} vte_pool_view;
+
+typedef struct vte_hint {          /* lookahead hint h */
+  int vstream;                     /* who will need the resources */
+  int want_width;                  /* CUs wanted */
+  double ready_in_s;               /* expected time until the op is ready */
+  double deadline_in_s;            /* <= 0: none */
+} vte_hint;
+
+typedef struct vte_prepare_plan {  /* R */
+  int target_pctx;                 /* -1: nothing to do */
+  int reserve;                     /* 1: reserve target for the hint's vstream */
+  int n_close;                     /* gates to close (only pCtxs overlapping target are accepted) */
+  int close[32];
+} vte_prepare_plan;
+
+typedef struct vte_policy_vtbl {
+  /* Pick(Q,S): index into ready[0..n) or -1 to defer. */
+  int (*pick)(void* user, const vte_ready_op* ready, int n, const vte_pool_view* S);
+  /* Select(o,E,S): one id out of eligible[0..n) or -1 to leave o ready. */
+  int (*select)(void* user, const vte_ready_op* op, const int* eligible, int n,
+                const vte_pool_view* S);
+  /* Prepare(h,S): fills *plan; may be NULL. */
+  int (*prepare)(void* user, const vte_hint* hint, const vte_pool_view* S, vte_prepare_plan* plan);
+} vte_policy_vtbl;
+
+/* Installs callbacks (called on the dispatcher thread with the runtime lock
+ * held: they must not call back into the library).  NULL restores the default. */
+int vte_set_policy(vte_ctx* ctx, const vte_policy_vtbl* vtbl, void* user);
+
+/* Built-in policies.
+ *  WIDEST      oldest ready op first; the widest eligible pCtx (pinned pCtx if pinned).
+ *  QUEUE_STATE launch-granular sharing from the instantaneous queue state and the
+ *              width profiles: a LATENCY op takes the narrowest pCtx whose
+ *              profiled time is within `slack` of its best; a BEST_EFFORT op
+ *              takes the widest pCtx that leaves `keep_free_cus` CUs unclaimed
+ *              while LATENCY ops are ready or in flight, and the widest of
+ *              all otherwise. */
+enum { VTE_POLICY_WIDEST = 0, VTE_POLICY_QUEUE_STATE = 1 };
+int vte_set_builtin_policy(vte_ctx* ctx, int which, double slack, int keep_free_cus);
+
+/* Gives the policy a lookahead hint; the plan it returns is validated and
+ * applied (gates closed, reservation placed or left pending). */
+int vte_hint_submit(vte_ctx* ctx, const vte_hint* hint);
+
+/* ---- width profiles T^_o(m) (Sec. 5, "Performance Profiles") ----------------- */
+/* Times `desc` alone on one pCtx of every width the pool exposes (warmup + reps
+ * launches each, device events) and stores seconds per launch under the
+ * descriptor's profile_key.  Must be called while nothing else is in flight. */
+int vte_profile_measure(vte_ctx* ctx, const vte_desc* desc, int warmup, int reps);
+int vte_profile_set(vte_ctx* ctx, uint64_t profile_key, int width, double seconds);
+/* VTE_EINVAL if no profile exists for (key,width). */
+int vte_profile_get(vte_ctx* ctx, uint64_t profile_key, int width, double* seconds);
+
+/* ---- statistics ------------------------------------------------------------------ */
+typedef struct vte_op_record {
+  vte_token token;
+  int vstream, klass, kernel, pctx, width;
+  double t_submit;   /* host seconds since vte_init: op handed to the library */
+  double t_ready;    /* predecessors satisfied (STRICT) or bindable (PIPELINED) */
+  double t_bound;    /* descriptor submitted to the backend stream */
+  double t_done;     /* completion observed by the dispatcher */
+} vte_op_record;
+typedef struct vte_stats_t {
+  uint64_t submitted, completed, leases_opened, leases_reused, lease_conflicts,
+      stale_proposals, submit_failures, gates_closed, reservations;
+} vte_stats_t;
+int vte_stats(vte_ctx* ctx, vte_stats_t* out);
+/* Copies up to `cap` most recent completed-op records, oldest first; *n_out = count. */
+int vte_stats_read(vte_ctx* ctx, vte_op_record* dst, int cap, int* n_out);
+int vte_stats_reset(vte_ctx* ctx);
+
+/* ---- fake backend hooks (VTE_BACKEND_FAKE only; VTE_ESTATE otherwise) ---------- */
+/* With the fake backend a submitted op stays in flight until completed here. */
+int vte_fake_complete(vte_ctx* ctx, vte_token token);
+int vte_fake_set_autocomplete(vte_ctx* ctx, int on); /* 1: ops complete as soon as submitted */
+int vte_fake_fail_next_submits(vte_ctx* ctx, int n); /* next n backend submissions fail */
+typedef struct vte_fake_log_entry {
+  vte_token token;
+  int pctx;
+  uint64_t desc_hash;  /* hash of the descriptor bytes as seen by the backend */
+  int waited_on_pctx;  /* device-side wait inserted on this pCtx's stream, or -1 */
+} vte_fake_log_entry;
+int vte_fake_log(vte_ctx* ctx, vte_fake_log_entry* dst, int cap, int* n_out);
+
+/* Blocks until the dispatcher has nothing left to do without outside input
+ * (no ready op it could bind, no unobserved completion).  For tests. */
+int vte_dispatcher_quiesce(vte_ctx* ctx);
+
+/* ---- device utilities -------------------------------------------------------------- */
+/* Host seconds since vte_init on the library's clock (the one the records use). */
+int vte_now(vte_ctx* ctx, double* seconds);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VTE_H_ */

@@ -1,0 +1,130 @@
+// HIP backend: a pCtx is a stream created with a CU mask; a completion is an
+// event recorded right after the launch (Sec. 3.4: CU-masked queues are the AMD
+// primitive; Sec. 6: events polled in batches).
+#include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
+
+#include <vector>
+
+#include "runtime.h"
+
+namespace vte {
+namespace {
+
+#define VTE_HIP(call)                                                        \
+  do {                                                                       \
+    hipError_t e_ = (call);                                                  \
+    if (e_ != hipSuccess) {                                                  \
+      set_error(std::string(#call) + ": " + hipGetErrorString(e_), (int)e_); \
+      return VTE_EHIP;                                                       \
+    }                                                                        \
+  } while (0)
+
+class HipBackend : public Backend {
+ public:
+  ~HipBackend() override {
+    for (hipEvent_t e : free_events_) (void)hipEventDestroy(e);
+  }
+  bool is_fake() const override { return false; }
+  int init(int device, int* cu_count) override {
+    device_ = device;
+    int n = 0;
+    VTE_HIP(hipGetDeviceCount(&n));
+    if (device < 0 || device >= n) { set_error("no such device"); return VTE_EINVAL; }
+    VTE_HIP(hipSetDevice(device));
+    hipDeviceProp_t prop;
+    VTE_HIP(hipGetDeviceProperties(&prop, device));
+    if (cu_count && *cu_count <= 0) *cu_count = prop.multiProcessorCount;
+    max_lds_ = static_cast<uint32_t>(prop.sharedMemPerBlock);
+    return VTE_OK;
+  }
+  int make_current() override { VTE_HIP(hipSetDevice(device_)); return VTE_OK; }
+  int create_stream(const uint32_t* mask, int words, void** stream) override {
+    hipStream_t s;
+    VTE_HIP(hipExtStreamCreateWithCUMask(&s, static_cast<uint32_t>(words), mask));
+    *stream = s;
+    return VTE_OK;
+  }
+  void destroy_stream(void* stream) override { (void)hipStreamDestroy(static_cast<hipStream_t>(stream)); }
+
+  int submit(const vte_desc* d, void* stream, int, vte_token, void** completion) override {
+    hipEvent_t ev;
+    if (free_events_.empty()) {
+      VTE_HIP(hipEventCreateWithFlags(&ev, hipEventDisableTiming));
+    } else {
+      ev = free_events_.back();
+      free_events_.pop_back();
+    }
+    int rc = launch(d, static_cast<hipStream_t>(stream));
+    if (rc != VTE_OK) { free_events_.push_back(ev); return rc; }
+    hipError_t e = hipEventRecord(ev, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) {
+      free_events_.push_back(ev);
+      set_error(std::string("hipEventRecord: ") + hipGetErrorString(e), (int)e);
+      return VTE_EHIP;
+    }
+    *completion = ev;
+    return VTE_OK;
+  }
+  int wait_on(void* stream, void* completion, int) override {
+    VTE_HIP(hipStreamWaitEvent(static_cast<hipStream_t>(stream), static_cast<hipEvent_t>(completion), 0));
+    return VTE_OK;
+  }
+  bool is_done(void* completion) override {
+    return hipEventQuery(static_cast<hipEvent_t>(completion)) != hipErrorNotReady;
+  }
+  void release(void* completion) override { free_events_.push_back(static_cast<hipEvent_t>(completion)); }
+  int sync_stream(void* stream) override { VTE_HIP(hipStreamSynchronize(static_cast<hipStream_t>(stream))); return VTE_OK; }
+
+  int time_launches(const vte_desc* d, void* stream, int warmup, int reps, double* sec) override {
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipEvent_t a, b;
+    VTE_HIP(hipEventCreate(&a));
+    VTE_HIP(hipEventCreate(&b));
+    int rc = VTE_OK;
+    for (int i = 0; i < warmup && rc == VTE_OK; ++i) rc = launch(d, s);
+    if (rc == VTE_OK) {
+      VTE_HIP(hipEventRecord(a, s));
+      for (int i = 0; i < reps && rc == VTE_OK; ++i) rc = launch(d, s);
+      VTE_HIP(hipEventRecord(b, s));
+      VTE_HIP(hipStreamSynchronize(s));
+      float ms = 0.f;
+      VTE_HIP(hipEventElapsedTime(&ms, a, b));
+      *sec = static_cast<double>(ms) * 1e-3 / (reps > 0 ? reps : 1);
+    }
+    (void)hipEventDestroy(a);
+    (void)hipEventDestroy(b);
+    return rc;
+  }
+
+  int prepare_kernel(const vte_desc* d) override {
+    if (d->lds_bytes > max_lds_) { set_error("descriptor needs more LDS than a workgroup may have"); return VTE_EINCOMPAT; }
+    if (d->lds_bytes > 48 * 1024) {
+      VTE_HIP(hipFuncSetAttribute(d->entry, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(d->lds_bytes)));
+    }
+    return VTE_OK;
+  }
+
+ private:
+  // The one place a kernel is launched: entry, dimensions and the argument bytes
+  // come from the descriptor as they are.
+  int launch(const vte_desc* d, hipStream_t s) {
+    void* params[1] = {const_cast<unsigned char*>(d->args)};
+    hipError_t e = hipLaunchKernel(d->entry, dim3(d->grid[0], d->grid[1], d->grid[2]),
+                                   dim3(d->block[0], d->block[1], d->block[2]), params, d->lds_bytes, s);
+    if (e != hipSuccess) {
+      set_error(std::string("hipLaunchKernel: ") + hipGetErrorString(e), (int)e);
+      return VTE_EHIP;
+    }
+    return VTE_OK;
+  }
+  int device_ = 0;
+  uint32_t max_lds_ = 65536;
+  std::vector<hipEvent_t> free_events_;
+};
+
+}  // namespace
+
+Backend* make_hip_backend() { return new HipBackend(); }
+
+}  // namespace vte

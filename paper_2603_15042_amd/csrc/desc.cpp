@@ -1,0 +1,347 @@
+// Descriptor constructors: turn a problem shape into an immutable launch
+// descriptor D_k (Sec. 4.2).  Every grid, block, LDS size and work split below is
+// a function of the shape arguments only.  Nothing here looks at the device, at
+// the pool or at a CU count, except the *_reshaped / *_splitk baselines, whose
+// caller passes a CU-derived parameter on purpose (Sec. 2.3).
+#include <cstring>
+#include <new>
+
+#include "kargs.h"
+#include "runtime.h"
+
+extern "C" {
+const void* vte_norm_entry(int threads, int layer);
+const void* vte_gemv_entry_b1(int, int, int, int);
+const void* vte_gemv_entry_b2(int, int, int, int);
+const void* vte_gemv_entry_b4(int, int, int, int);
+const void* vte_gemv_entry_b8(int, int, int, int);
+const void* vte_gemv_entry_b16(int, int, int, int);
+const void* vte_gather_entry();
+const void* vte_gemm_entry();
+unsigned vte_gemm_lds_bytes();
+unsigned vte_gemm_threads();
+}
+
+namespace vte {
+
+uint64_t fnv1a(const void* data, size_t n, uint64_t h) {
+  const unsigned char* p = static_cast<const unsigned char*>(data);
+  for (size_t i = 0; i < n; ++i) { h ^= p[i]; h *= 1099511628211ull; }
+  return h;
+}
+
+uint64_t desc_hash(const vte_desc* d) {
+  uint64_t h = fnv1a(&d->kernel, sizeof d->kernel);
+  h = fnv1a(&d->entry, sizeof d->entry, h);
+  h = fnv1a(d->grid, sizeof d->grid, h);
+  h = fnv1a(d->block, sizeof d->block, h);
+  h = fnv1a(&d->lds_bytes, sizeof d->lds_bytes, h);
+  h = fnv1a(&d->arg_bytes, sizeof d->arg_bytes, h);
+  return fnv1a(d->args, d->arg_bytes, h);
+}
+
+namespace {
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+template <class Args>
+int finish_desc(vte_ctx* ctx, int kernel, const void* entry, const Args& a, uint32_t gx, uint32_t gy,
+                uint32_t threads, uint32_t lds, uint64_t shape_key, uint64_t bytes, uint64_t flops,
+                vte_desc** out) {
+  static_assert(sizeof(Args) <= sizeof(vte_desc::args), "argument block too large");
+  if (!entry) { set_error("no kernel instance for this configuration"); return VTE_EINVAL; }
+  if (gx == 0 || gy == 0 || gx > 0x7fffffffu || gy > 65535u) { set_error("grid out of range"); return VTE_EINVAL; }
+  vte_desc* d = new (std::nothrow) vte_desc;
+  if (!d) { set_error("out of host memory"); return VTE_ENOMEM; }
+  std::memset(d, 0, sizeof *d);
+  d->ctx = ctx;
+  d->kernel = kernel;
+  d->entry = entry;
+  d->grid[0] = gx; d->grid[1] = gy; d->grid[2] = 1;
+  d->block[0] = threads; d->block[1] = 1; d->block[2] = 1;
+  d->lds_bytes = lds;
+  d->arg_bytes = sizeof(Args);
+  std::memcpy(d->args, &a, sizeof(Args));
+  d->bytes = bytes;
+  d->flops = flops;
+  uint64_t k = fnv1a(&kernel, sizeof kernel);
+  k = fnv1a(d->grid, sizeof d->grid, k);
+  k = fnv1a(d->block, sizeof d->block, k);
+  d->profile_key = fnv1a(&shape_key, sizeof shape_key, k);
+  d->hash = desc_hash(d);
+  int rc = ctx->backend->prepare_kernel(d);
+  if (rc != VTE_OK) { delete d; return rc; }
+  {
+    std::lock_guard<std::mutex> lk(ctx->mu);
+    ctx->descs.push_back(d);
+  }
+  *out = d;
+  return VTE_OK;
+}
+
+int norm_threads(int cols) {
+  const int chunks = cols / 8;
+  int t = 64;
+  while (t < 256 && t < chunks) t *= 2;  // 64, 128, 256: one chunk per thread up to 2048 columns
+  return t;
+}
+
+int build_norm(vte_ctx* ctx, int kernel, bool layer, const void* x, const void* gamma, const void* beta,
+               void* y, int rows, int cols, float eps, int threads, vte_desc** out) {
+  if (!ctx || !out || !x || !gamma || !y || (layer && !beta)) { set_error("norm: null argument"); return VTE_EINVAL; }
+  if (rows <= 0 || cols <= 0 || cols % 8 != 0 || cols > 16384) { set_error("norm: need rows > 0, cols % 8 == 0, cols <= 16384"); return VTE_EINVAL; }
+  if (!aligned16(x) || !aligned16(gamma) || !aligned16(y) || (layer && !aligned16(beta))) { set_error("norm: pointers must be 16-byte aligned"); return VTE_EINVAL; }
+  while (cols > 64 * threads && threads < 512) threads *= 2;  // at most 8 chunks of 8 per thread
+  if (cols > 64 * threads) { set_error("norm: row too long for this thread count"); return VTE_EINVAL; }
+  NormArgs a{};
+  a.x = static_cast<const uint16_t*>(x);
+  a.gamma = static_cast<const uint16_t*>(gamma);
+  a.beta = static_cast<const uint16_t*>(beta);
+  a.y = static_cast<uint16_t*>(y);
+  a.rows = rows; a.cols = cols; a.eps = eps; a.inv_cols = 1.0f / static_cast<float>(cols);
+  const uint64_t shape = (static_cast<uint64_t>(rows) << 32) | static_cast<uint32_t>(cols);
+  const uint64_t bytes = static_cast<uint64_t>(rows) * cols * 4 + static_cast<uint64_t>(cols) * (layer ? 4 : 2);
+  return finish_desc(ctx, kernel, vte_norm_entry(threads, layer ? 1 : 0), a, static_cast<uint32_t>(rows), 1,
+                     static_cast<uint32_t>(threads), 0, shape, bytes, static_cast<uint64_t>(rows) * cols * 4, out);
+}
+
+const void* gemv_entry(int bt, int rw, int waves, int epi) {
+  switch (bt) {
+    case 1: return vte_gemv_entry_b1(bt, rw, waves, epi);
+    case 2: return vte_gemv_entry_b2(bt, rw, waves, epi);
+    case 4: return vte_gemv_entry_b4(bt, rw, waves, epi);
+    case 8: return vte_gemv_entry_b8(bt, rw, waves, epi);
+    case 16: return vte_gemv_entry_b16(bt, rw, waves, epi);
+  }
+  return nullptr;
+}
+
+int batch_tile(int B) { int bt = 1; while (bt < B) bt *= 2; return bt; }
+
+// outputs = logical outputs per batch row (N, or N/2 with the SiLU epilogue)
+int plan_gemv(int B, int outputs, int K, int epi, int S, vte_gemv_plan* p) {
+  if (B < 1 || B > 16 || outputs < 1 || K < 8 || S < 1) return VTE_EINVAL;
+  const int bt = batch_tile(B);
+  int rw = 4, waves = 8;
+  auto blocks = [&](int rw_, int waves_) {
+    const int r = (epi == VTE_EPI_SILU_MUL) ? rw_ / 2 : rw_;
+    return (outputs + waves_ * r - 1) / (waves_ * r);
+  };
+  while (blocks(rw, waves) < 512 && waves > 4) waves /= 2;
+  while (blocks(rw, waves) < 512 && rw > 2) rw /= 2;
+  const int kps = K / S;
+  const int kpad = (kps + 511) & ~511;
+  const int kc_max = 32768 / bt;  // 64 KiB of LDS for X
+  const int kc = kpad < kc_max ? kpad : kc_max;
+  int groups = 1;
+  if (kc >= kps) {  // X fits at once: a block may walk several row groups
+    const int r = (epi == VTE_EPI_SILU_MUL) ? rw / 2 : rw;
+    groups = outputs / (waves * r * 1024);
+    groups = groups < 1 ? 1 : (groups > 8 ? 8 : groups);
+  }
+  p->rows_in_flight = rw; p->waves = waves; p->groups = groups; p->kc = kc;
+  return VTE_OK;
+}
+
+struct GemvBuild {
+  int kernel, epi_kernel;  // VTE_K_*, EPI_* of the kernel template
+  const void *W, *X; void* Y; float* logits; int32_t* tok; void* ws; void* partials;
+  int B, N, K, epilogue, S;
+  const vte_gemv_plan* plan;
+};
+
+int build_gemv(vte_ctx* ctx, const GemvBuild& g, vte_desc** out) {
+  if (!ctx || !out || !g.W || !g.X) { set_error("gemv: null argument"); return VTE_EINVAL; }
+  const bool lm = (g.epi_kernel == 2);
+  if (!lm && !g.Y) { set_error("gemv: null output"); return VTE_EINVAL; }
+  if (lm && (!g.tok || !g.ws)) { set_error("lmhead: tok and workspace are required"); return VTE_EINVAL; }
+  if (g.B < 1 || g.B > 16 || g.N < 1 || g.K < 8 || g.K % 8 != 0) { set_error("gemv: need 1 <= B <= 16, N >= 1, K % 8 == 0"); return VTE_EINVAL; }
+  if (g.S < 1 || g.S > 64 || g.K % (g.S * 8) != 0) { set_error("gemv: K must split into S chunks of a multiple of 8"); return VTE_EINVAL; }
+  if (g.S > 1 && (!g.partials || !g.ws)) { set_error("split-K: partials and workspace are required"); return VTE_EINVAL; }
+  if (g.epilogue == VTE_EPI_SILU_MUL && (g.N % 2 != 0)) { set_error("gemv: SiLU-mul needs an even N"); return VTE_EINVAL; }
+  if (g.epilogue != VTE_EPI_NONE && g.epilogue != VTE_EPI_SILU_MUL) { set_error("gemv: unknown epilogue"); return VTE_EINVAL; }
+  if (!aligned16(g.W) || !aligned16(g.X)) { set_error("gemv: W and X must be 16-byte aligned"); return VTE_EINVAL; }
+  const int n_out = (g.epilogue == VTE_EPI_SILU_MUL) ? g.N / 2 : g.N;
+  vte_gemv_plan p;
+  if (g.plan) p = *g.plan;
+  else if (plan_gemv(g.B, n_out, g.K, g.epilogue, g.S, &p) != VTE_OK) { set_error("gemv: no plan"); return VTE_EINVAL; }
+  const int bt = batch_tile(g.B);
+  const int kps = g.K / g.S;
+  if (p.kc <= 0 || p.kc % 512 != 0 || p.groups < 1 || static_cast<int64_t>(bt) * p.kc * 2 > 160 * 1024 - 1024) {
+    set_error("gemv plan: kc must be a positive multiple of 512 and X must fit in LDS"); return VTE_EINVAL;
+  }
+  (void)kps;
+  const int r = (g.epi_kernel == 1) ? p.rows_in_flight / 2 : p.rows_in_flight;
+  if (r < 1) { set_error("gemv plan: rows_in_flight too small for this epilogue"); return VTE_EINVAL; }
+  const int per_block = p.waves * r * p.groups;
+  const uint32_t gx = static_cast<uint32_t>((n_out + per_block - 1) / per_block);
+  GemvArgs a{};
+  a.W = static_cast<const uint16_t*>(g.W);
+  a.X = static_cast<const uint16_t*>(g.X);
+  a.Y = static_cast<uint16_t*>(g.Y);
+  a.logits = g.logits; a.tok = g.tok;
+  a.ws = static_cast<uint32_t*>(g.ws);
+  a.partials = static_cast<float*>(g.partials);
+  a.B = g.B; a.N = g.N; a.K = g.K; a.n_out = n_out;
+  a.groups = p.groups; a.kc = p.kc; a.S = g.S; a.k_per_split = g.K / g.S;
+  const uint64_t shape = fnv1a(&a.B, sizeof(int) * 8);
+  uint64_t bytes = 2ull * g.N * g.K + 2ull * g.B * g.K + (lm ? 4ull * g.B : 2ull * g.B * n_out);
+  if (lm && g.logits) bytes += 4ull * g.B * g.N;
+  const uint64_t flops = 2ull * g.B * g.N * g.K;
+  return finish_desc(ctx, g.kernel, gemv_entry(bt, p.rows_in_flight, p.waves, g.epi_kernel), a, gx,
+                     static_cast<uint32_t>(g.S), static_cast<uint32_t>(p.waves * 64),
+                     static_cast<uint32_t>(bt * p.kc * 2), shape, bytes, flops, out);
+}
+
+// grid.x of the LM head for (B,V,K,S): sizes the workspace
+int lmhead_blocks(int B, int V, int K, int S, const vte_gemv_plan* plan) {
+  vte_gemv_plan p;
+  if (plan) p = *plan;
+  else if (plan_gemv(B, V, K, VTE_EPI_NONE, S, &p) != VTE_OK) return -1;
+  const int per_block = p.waves * p.rows_in_flight * p.groups;
+  return (V + per_block - 1) / per_block;
+}
+
+}  // namespace
+}  // namespace vte
+
+using namespace vte;
+
+extern "C" {
+
+int vte_desc_rmsnorm(vte_ctx* ctx, const void* x, const void* gamma, void* y, int rows, int cols, float eps,
+                     vte_desc** out) {
+  return build_norm(ctx, VTE_K_RMSNORM, false, x, gamma, nullptr, y, rows, cols, eps, norm_threads(cols), out);
+}
+
+int vte_desc_layernorm(vte_ctx* ctx, const void* x, const void* gamma, const void* beta, void* y, int rows,
+                       int cols, float eps, vte_desc** out) {
+  return build_norm(ctx, VTE_K_LAYERNORM, true, x, gamma, beta, y, rows, cols, eps, norm_threads(cols), out);
+}
+
+int vte_desc_rmsnorm_reshaped(vte_ctx* ctx, const void* x, const void* gamma, void* y, int rows, int cols,
+                              float eps, int active_cus, vte_desc** out) {
+  if (active_cus < 1) { set_error("rmsnorm_reshaped: active_cus must be positive"); return VTE_EINVAL; }
+  int t = 64 * (active_cus / 32);
+  t = t < 64 ? 64 : (t > 512 ? 512 : t);
+  int p2 = 64;
+  while (p2 * 2 <= t) p2 *= 2;
+  return build_norm(ctx, VTE_K_RMSNORM_RESHAPED, false, x, gamma, nullptr, y, rows, cols, eps, p2, out);
+}
+
+int vte_gemv_default_plan(int B, int N, int K, int epilogue, int S, vte_gemv_plan* plan) {
+  if (!plan) { set_error("null plan"); return VTE_EINVAL; }
+  const int n_out = (epilogue == VTE_EPI_SILU_MUL) ? N / 2 : N;
+  int rc = plan_gemv(B, n_out, K, epilogue, S < 1 ? 1 : S, plan);
+  if (rc != VTE_OK) set_error("gemv plan: need 1 <= B <= 16, N >= 1, K >= 8");
+  return rc;
+}
+
+int vte_desc_gemv(vte_ctx* ctx, const void* W, const void* X, void* Y, int B, int N, int K, int epilogue,
+                  vte_desc** out) {
+  GemvBuild g{VTE_K_GEMV, epilogue == VTE_EPI_SILU_MUL ? 1 : 0, W, X, Y, nullptr, nullptr, nullptr, nullptr,
+              B, N, K, epilogue, 1, nullptr};
+  return build_gemv(ctx, g, out);
+}
+
+int vte_desc_gemv_planned(vte_ctx* ctx, const void* W, const void* X, void* Y, int B, int N, int K,
+                          int epilogue, const vte_gemv_plan* plan, vte_desc** out) {
+  GemvBuild g{VTE_K_GEMV, epilogue == VTE_EPI_SILU_MUL ? 1 : 0, W, X, Y, nullptr, nullptr, nullptr, nullptr,
+              B, N, K, epilogue, 1, plan};
+  return build_gemv(ctx, g, out);
+}
+
+// split-K workspace: [tickets: one uint32 per possible row block, rounded up][fp32 partials [S][BT][N]]
+static size_t splitk_ticket_bytes(int N) { return ((static_cast<size_t>(N) / 2 + 2) * 4 + 255) & ~static_cast<size_t>(255); }
+
+int vte_splitk_workspace_bytes(int B, int N, int S, size_t* bytes) {
+  if (!bytes || B < 1 || B > 16 || N < 1 || S < 1) { set_error("splitk workspace: bad argument"); return VTE_EINVAL; }
+  *bytes = splitk_ticket_bytes(N) + static_cast<size_t>(S) * batch_tile(B) * N * 4;
+  return VTE_OK;
+}
+
+int vte_desc_gemv_splitk(vte_ctx* ctx, const void* W, const void* X, void* Y, void* workspace, int B, int N,
+                         int K, int epilogue, int S, vte_desc** out) {
+  if (!workspace || N < 1) { set_error("split-K: workspace is required"); return VTE_EINVAL; }
+  void* partials = static_cast<unsigned char*>(workspace) + splitk_ticket_bytes(N);
+  GemvBuild g{VTE_K_GEMV_SPLITK, epilogue == VTE_EPI_SILU_MUL ? 1 : 0, W, X, Y, nullptr, nullptr, workspace,
+              partials, B, N, K, epilogue, S, nullptr};
+  return build_gemv(ctx, g, out);
+}
+
+int vte_lmhead_workspace_bytes(int B, int V, int K, size_t* bytes) {
+  if (!bytes) { set_error("null bytes"); return VTE_EINVAL; }
+  // sized for the finest plan any S could pick: one block per 8 rows
+  (void)K;
+  if (B < 1 || B > 16 || V < 1) { set_error("lmhead workspace: bad argument"); return VTE_EINVAL; }
+  const size_t blocks = static_cast<size_t>(V + 7) / 8 + 1;
+  *bytes = 4 * (1 + blocks + blocks * batch_tile(B) * 2) + 256;
+  return VTE_OK;
+}
+
+int vte_desc_lmhead_argmax(vte_ctx* ctx, const void* W, const void* H, int32_t* tok, float* logits_or_null,
+                           void* workspace, int B, int V, int K, vte_desc** out) {
+  GemvBuild g{VTE_K_LMHEAD, 2, W, H, nullptr, logits_or_null, tok, workspace, nullptr, B, V, K, VTE_EPI_NONE, 1, nullptr};
+  return build_gemv(ctx, g, out);
+}
+
+int vte_desc_lmhead_argmax_planned(vte_ctx* ctx, const void* W, const void* H, int32_t* tok,
+                                   float* logits_or_null, void* workspace, int B, int V, int K,
+                                   const vte_gemv_plan* plan, vte_desc** out) {
+  GemvBuild g{VTE_K_LMHEAD, 2, W, H, nullptr, logits_or_null, tok, workspace, nullptr, B, V, K, VTE_EPI_NONE, 1, plan};
+  return build_gemv(ctx, g, out);
+}
+
+int vte_desc_lmhead_argmax_splitk(vte_ctx* ctx, const void* W, const void* H, int32_t* tok,
+                                  float* logits_or_null, void* workspace, void* partials, int B, int V, int K,
+                                  int S, vte_desc** out) {
+  GemvBuild g{VTE_K_LMHEAD_SPLITK, 2, W, H, nullptr, logits_or_null, tok, workspace, partials, B, V, K,
+              VTE_EPI_NONE, S, nullptr};
+  return build_gemv(ctx, g, out);
+}
+
+int vte_desc_gather(vte_ctx* ctx, const void* E, const int32_t* tok, void* H, int B, int V, int K, vte_desc** out) {
+  if (!ctx || !out || !E || !tok || !H) { set_error("gather: null argument"); return VTE_EINVAL; }
+  if (B < 1 || B > 65535 || V < 1 || K < 8 || K % 8 != 0) { set_error("gather: need 1 <= B <= 65535, V >= 1, K % 8 == 0"); return VTE_EINVAL; }
+  if (!aligned16(E) || !aligned16(H)) { set_error("gather: E and H must be 16-byte aligned"); return VTE_EINVAL; }
+  GatherArgs a{static_cast<const uint16_t*>(E), tok, static_cast<uint16_t*>(H), B, V, K};
+  const uint32_t gx = static_cast<uint32_t>((K / 8 + 255) / 256);
+  const uint64_t shape = (static_cast<uint64_t>(B) << 32) | static_cast<uint32_t>(K);
+  return finish_desc(ctx, VTE_K_GATHER, vte_gather_entry(), a, gx, static_cast<uint32_t>(B), 256, 0, shape,
+                     4ull * B * K + 4ull * B, 0, out);
+}
+
+int vte_desc_gemm(vte_ctx* ctx, const void* A, const void* Bm, void* C, int M, int N, int K, vte_desc** out) {
+  if (!ctx || !out || !A || !Bm || !C) { set_error("gemm: null argument"); return VTE_EINVAL; }
+  if (M < 256 || N < 256 || K < 64 || M % 256 != 0 || N % 256 != 0 || K % 64 != 0) { set_error("gemm: need M,N % 256 == 0 and K % 64 == 0"); return VTE_EINVAL; }
+  if (!aligned16(A) || !aligned16(Bm) || !aligned16(C)) { set_error("gemm: pointers must be 16-byte aligned"); return VTE_EINVAL; }
+  GemmArgs a{static_cast<const uint16_t*>(A), static_cast<const uint16_t*>(Bm), static_cast<uint16_t*>(C), M, N, K, M / 256, N / 256};
+  const uint64_t tiles = static_cast<uint64_t>(a.tiles_m) * a.tiles_n;
+  if (tiles > 0x7fffffffull) { set_error("gemm: too many tiles"); return VTE_EINVAL; }
+  const uint64_t shape = fnv1a(&a.M, sizeof(int) * 3);
+  return finish_desc(ctx, VTE_K_GEMM, vte_gemm_entry(), a, static_cast<uint32_t>(tiles), 1, vte_gemm_threads(),
+                     vte_gemm_lds_bytes(), shape,
+                     2ull * (static_cast<uint64_t>(M) * K + static_cast<uint64_t>(N) * K + static_cast<uint64_t>(M) * N),
+                     2ull * M * N * K, out);
+}
+
+int vte_desc_info(const vte_desc* d, vte_desc_view* v) {
+  if (!d || !v) { set_error("desc_info: null argument"); return VTE_EINVAL; }
+  v->kernel = d->kernel;
+  for (int i = 0; i < 3; ++i) { v->grid[i] = d->grid[i]; v->block[i] = d->block[i]; }
+  v->lds_bytes = d->lds_bytes;
+  v->arg_bytes = d->arg_bytes;
+  v->hash = desc_hash(d);  // recomputed from the bytes as they are now
+  v->profile_key = d->profile_key;
+  v->bytes = d->bytes;
+  v->flops = d->flops;
+  return VTE_OK;
+}
+
+int vte_desc_args(const vte_desc* d, void* dst, size_t cap) {
+  if (!d || !dst) { set_error("desc_args: null argument"); return VTE_EINVAL; }
+  std::memcpy(dst, d->args, cap < d->arg_bytes ? cap : d->arg_bytes);
+  return VTE_OK;
+}
+
+}  // extern "C"

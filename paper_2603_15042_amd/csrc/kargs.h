@@ -1,0 +1,48 @@
+// Argument blocks of the fixed-structure kernels.  A descriptor stores one of
+// these by value (pointer values included) and the kernel receives exactly those
+// bytes, so "submitting the descriptor unchanged" is a memcpy-level statement
+// (Sec. 4.2, "Immutable Operation Descriptors").
+#pragma once
+#include <stdint.h>
+
+struct NormArgs {
+  const uint16_t* x;
+  const uint16_t* gamma;
+  const uint16_t* beta;   // LayerNorm only
+  uint16_t* y;
+  int rows, cols;
+  float eps;
+  float inv_cols;
+};
+
+// GEMV family: plain, SiLU-mul, LM head (+argmax), and the split-K baselines.
+struct GemvArgs {
+  const uint16_t* W;      // [N,K] bf16, K contiguous
+  const uint16_t* X;      // [B,K] bf16
+  uint16_t* Y;            // [B,N_out] bf16 (null for LM head)
+  float* logits;          // LM head: [B,N] fp32 or null
+  int32_t* tok;           // LM head: [B]
+  uint32_t* ws;           // LM head: block partials + ticket; split-K: tickets
+  float* partials;        // split-K: [S][B][N] fp32
+  int B, N, K;
+  int n_out;              // outputs per batch row (N, or N/2 with SiLU-mul)
+  int groups;             // row groups each wave walks through
+  int kc;                 // K elements of X staged in LDS at a time
+  int S;                  // K split (1 = fixed structure)
+  int k_per_split;        // K / S
+};
+
+struct GatherArgs {
+  const uint16_t* E;
+  const int32_t* tok;
+  uint16_t* H;
+  int B, V, K;
+};
+
+struct GemmArgs {
+  const uint16_t* A;      // [M,K]
+  const uint16_t* Bm;     // [N,K]
+  uint16_t* C;            // [M,N]
+  int M, N, K;
+  int tiles_m, tiles_n;
+};

@@ -1,0 +1,111 @@
+// RMSNorm / LayerNorm with a reduction tree fixed by the row length alone
+// (operator family: Sec. 1 and Sec. 2.3 of the paper; reshaped variant: the
+// negative control of Sec. 7.1).
+//
+// One workgroup of T threads per row.  Thread t owns the 8-element chunks
+// t, t+T, t+2T, ... of the row (128-bit loads, coalesced across the wave) and
+// keeps them in registers, so the row is read from HBM exactly once.
+// Reduction tree of a row sum:
+//   1. a thread adds the squares of its elements in ascending index order;
+//   2. the 64 lanes of a wave are combined by the fixed butterfly wave_sum();
+//   3. wave partials go through LDS and every thread adds them in wave order.
+// T is chosen from the row length on the host (never from a CU count), except in
+// the *_reshaped descriptor where the caller derives it from a CU count on
+// purpose.
+#include "dev_util.h"
+#include "kargs.h"
+
+constexpr int kMaxChunks = 8;  // per thread: cols <= 8 * 8 * T
+
+template <int T>
+__device__ __forceinline__ float block_sum(float v, float* red) {
+  v = wave_sum(v);
+  constexpr int NW = T / 64;
+  if constexpr (NW == 1) return v;
+  const int wave = threadIdx.x >> 6;
+  __syncthreads();  // red[] may still be read from a previous reduction
+  if ((threadIdx.x & 63) == 0) red[wave] = v;
+  __syncthreads();
+  float s = red[0];
+#pragma unroll
+  for (int w = 1; w < NW; ++w) s += red[w];
+  return s;
+}
+
+template <int T, bool LAYER>
+__global__ __launch_bounds__(T) void norm_kernel(const NormArgs a) {
+  __shared__ float red[T / 64];
+  const int row = blockIdx.x;
+  if (row >= a.rows) return;
+  const int nchunks = a.cols >> 3;
+  const uint16_t* xr = a.x + static_cast<size_t>(row) * a.cols;
+  uint16_t* yr = a.y + static_cast<size_t>(row) * a.cols;
+
+  u32x4 xv[kMaxChunks];
+#pragma unroll
+  for (int j = 0; j < kMaxChunks; ++j) {
+    const int c = threadIdx.x + j * T;
+    xv[j] = (c < nchunks) ? ld16(xr + c * 8) : u32x4{0u, 0u, 0u, 0u};
+  }
+
+  float mu = 0.f;
+  if constexpr (LAYER) {
+    float s = 0.f;
+#pragma unroll
+    for (int j = 0; j < kMaxChunks; ++j) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        s += bf16_lo(xv[j][e]);
+        s += bf16_hi(xv[j][e]);
+      }
+    }
+    mu = block_sum<T>(s, red) * a.inv_cols;
+  }
+
+  float ss = 0.f;
+#pragma unroll
+  for (int j = 0; j < kMaxChunks; ++j) {
+    const bool live = (threadIdx.x + j * T) < nchunks;  // padding must not add (0-mu)^2
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float lo = bf16_lo(xv[j][e]) - mu, hi = bf16_hi(xv[j][e]) - mu;
+      ss = live ? fmaf(lo, lo, ss) : ss;
+      ss = live ? fmaf(hi, hi, ss) : ss;
+    }
+  }
+  ss = block_sum<T>(ss, red);
+  const float rstd = 1.0f / sqrtf(ss * a.inv_cols + a.eps);
+
+#pragma unroll
+  for (int j = 0; j < kMaxChunks; ++j) {
+    const int c = threadIdx.x + j * T;
+    if (c < nchunks) {
+      const u32x4 g = ld16(a.gamma + c * 8);
+      u32x4 b = u32x4{0u, 0u, 0u, 0u};
+      if constexpr (LAYER) b = ld16(a.beta + c * 8);
+      u32x4 o;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        float lo = (bf16_lo(xv[j][e]) - mu) * rstd * bf16_lo(g[e]);
+        float hi = (bf16_hi(xv[j][e]) - mu) * rstd * bf16_hi(g[e]);
+        if constexpr (LAYER) {
+          lo += bf16_lo(b[e]);
+          hi += bf16_hi(b[e]);
+        }
+        o[e] = pack_bf16(lo, hi);
+      }
+      st16(yr + c * 8, o);
+    }
+  }
+}
+
+// Host side: kernel entry for a thread count (64, 128, 256 or 512).
+extern "C" const void* vte_norm_entry(int threads, int layer) {
+  switch (threads) {
+    case 64:  return layer ? (const void*)norm_kernel<64, true>  : (const void*)norm_kernel<64, false>;
+    case 128: return layer ? (const void*)norm_kernel<128, true> : (const void*)norm_kernel<128, false>;
+    case 256: return layer ? (const void*)norm_kernel<256, true> : (const void*)norm_kernel<256, false>;
+    case 512: return layer ? (const void*)norm_kernel<512, true> : (const void*)norm_kernel<512, false>;
+  }
+  return nullptr;
+}

@@ -1,0 +1,908 @@
+// The late-binding runtime: pool realisation, virtual streams with token
+// chains, the policy-driven dispatcher with validation, lease state machine and
+// completion propagation (Sec. 4.2 - 4.5 of the paper), behind the C ABI.
+#include "runtime.h"
+
+#include <algorithm>
+#include <cstring>
+#include <new>
+
+#include "backend_fake.h"
+
+namespace vte {
+
+static thread_local std::string g_err;
+static thread_local int g_hip_err = 0;
+void set_error(const std::string& msg, int hip_code) {
+  g_err = msg;
+  g_hip_err = hip_code;
+}
+
+namespace {
+
+using Lock = std::unique_lock<std::mutex>;
+
+void bump(vte_ctx* c) {  // runtime lock held: something changed from outside
+  ++c->change_seq;
+  c->cv_work.notify_all();
+}
+
+bool token_done(vte_ctx* c, vte_token t) {
+  if (t == 0) return true;
+  return c->live.find(t) == c->live.end();
+}
+
+void fill_info(const Pool& pool, int id, vte_pctx_info* o) {
+  const Pctx& p = pool.at(id);
+  std::memset(o, 0, sizeof *o);
+  o->id = p.id; o->kind = p.kind; o->width = p.width; o->level = p.level; o->parent = p.parent;
+  o->child[0] = p.child[0]; o->child[1] = p.child[1]; o->remainder = p.remainder;
+  o->state = p.state; o->gate_open = p.gate_open ? 1 : 0; o->outstanding = p.outstanding;
+  o->reserved_for = p.reserved_for;
+  for (size_t w = 0; w < p.mask.size() && w < 8; ++w) o->mask[w] = p.mask[w];
+}
+
+// ---- lease state machine (Sec. 4.3 "pCtx Lifecycle") ---------------------------
+
+// Can `vs` (or an explicit launch, vs = -1) put one more op on pCtx `id` now?
+int can_admit(vte_ctx* c, int id, int vs) {
+  const Pctx& p = c->pool.at(id);
+  if (p.state == kDraining || !p.gate_open) { set_error("pCtx gate is closed (draining)"); return VTE_EBUSY; }
+  if (p.reserved_for >= 0 && p.reserved_for != vs) { set_error("pCtx is reserved for another vstream"); return VTE_EBUSY; }
+  if (p.state == kLeased) {  // lease reuse by its holder: conflicts were excluded when it was opened
+    if (p.holder != vs) { set_error("pCtx is leased to another vstream"); return VTE_EBUSY; }
+    return VTE_OK;
+  }
+  if (c->pool.conflicts_with_active(id, vs)) { set_error("pCtx overlaps an active lease or reservation"); return VTE_EBUSY; }
+  return VTE_OK;
+}
+
+void admit(vte_ctx* c, int id, int vs) {
+  Pctx& p = c->pool.at(id);
+  if (p.state == kIdle || p.state == kReserved) {
+    p.state = kLeased;
+    p.holder = vs;
+    p.gate_open = true;
+    p.reservation_pending = false;
+    c->pool.set_active(id, true);
+    ++c->stats.leases_opened;
+  } else {
+    ++c->stats.leases_reused;
+  }
+  ++p.outstanding;
+}
+
+// A pending reservation takes effect once nothing else overlapping is active.
+void settle_reservations(vte_ctx* c) {
+  for (int id = 0; id < c->pool.size(); ++id) {
+    Pctx& p = c->pool.at(id);
+    if (!p.reservation_pending || p.state != kIdle) continue;
+    if (!c->pool.conflicts_with_active(id, p.reserved_for)) {
+      p.reservation_pending = false;
+      p.state = kReserved;
+    }
+  }
+}
+
+void retire_one(vte_ctx* c, int id) {
+  Pctx& p = c->pool.at(id);
+  --p.outstanding;
+  if (p.outstanding > 0) return;
+  // lease released: back to idle, or to reserved when held for a vstream
+  p.gate_open = true;
+  if (p.reserved_for >= 0) {
+    if (c->pool.conflicts_with_active(id, p.reserved_for)) {
+      p.state = kIdle;
+      p.reservation_pending = true;  // stays active so nothing unrelated moves in
+    } else {
+      p.state = kReserved;
+      p.reservation_pending = false;
+    }
+  } else {
+    p.state = kIdle;
+    c->pool.set_active(id, false);
+  }
+  settle_reservations(c);
+}
+
+// ---- completion propagation (Sec. 4.4) -------------------------------------------
+
+void record_op(vte_ctx* c, const Op* op) {
+  if (c->ring.empty()) return;
+  vte_op_record& r = c->ring[(c->ring_head + c->ring_count) % c->ring.size()];
+  if (c->ring_count == c->ring.size()) c->ring_head = (c->ring_head + 1) % c->ring.size();
+  else ++c->ring_count;
+  r.token = op->tok; r.vstream = op->vs; r.klass = op->klass; r.kernel = op->desc->kernel;
+  r.pctx = op->pctx; r.width = c->pool.at(op->pctx).width;
+  r.t_submit = op->t_submit; r.t_ready = op->t_ready; r.t_bound = op->t_bound; r.t_done = op->t_done;
+}
+
+void complete_op(vte_ctx* c, Op* op) {
+  op->state = kDone;
+  op->t_done = c->now();
+  c->backend->release(op->completion);
+  op->completion = nullptr;
+  retire_one(c, op->pctx);
+  if (op->vs >= 0) {
+    vte_vstream* vs = c->vstreams[op->vs];
+    --vs->unfinished_bound;
+  }
+  --c->inflight_by_class[op->klass];
+  ++c->stats.completed;
+  record_op(c, op);
+  c->live.erase(op->tok);  // the token is now satisfied
+  delete op;
+}
+
+// Poll completions: within a pCtx ops finish in submission order, so only the
+// oldest in-flight op of each pCtx is queried until it is done.
+bool poll_completions(vte_ctx* c) {
+  bool any = false;
+  std::vector<char> blocked(c->pool.size(), 0);
+  for (size_t i = 0; i < c->inflight.size();) {
+    Op* op = c->inflight[i];
+    if (!blocked[op->pctx] && c->backend->is_done(op->completion)) {
+      c->inflight.erase(c->inflight.begin() + i);
+      complete_op(c, op);
+      any = true;
+    } else {
+      blocked[op->pctx] = 1;
+      ++i;
+    }
+  }
+  if (any) c->cv_done.notify_all();
+  return any;
+}
+
+// ---- readiness (Sec. 4.4 "Readiness Before Binding") -----------------------------
+
+// STRICT: every predecessor token satisfied.  PIPELINED: every predecessor is
+// satisfied or already bound to a backend stream, and the vstream has fewer than
+// `lookahead` bound-but-unfinished ops.
+bool bindable(vte_ctx* c, const vte_vstream* vs, const Op* op, int* pred_pctx) {
+  *pred_pctx = -1;
+  const bool pipelined = c->cfg.mode == VTE_MODE_PIPELINED;
+  if (pipelined && vs && vs->unfinished_bound >= c->cfg.lookahead) return false;
+  for (vte_token t : op->deps) {
+    if (t == 0) continue;
+    auto it = c->live.find(t);
+    if (it == c->live.end()) continue;  // satisfied
+    if (!pipelined) return false;
+    if (it->second->state != kInflight) return false;
+    *pred_pctx = it->second->pctx;
+  }
+  return true;
+}
+
+// ---- built-in policies (Sec. 5) -----------------------------------------------------
+
+double profile_time(vte_ctx* c, uint64_t key, int width) {
+  auto it = c->profiles.find({key, width});
+  return it == c->profiles.end() ? -1.0 : it->second;
+}
+
+int builtin_pick(vte_ctx*, const vte_ready_op* ready, int n, const vte_pool_view*) {
+  int best = -1;
+  for (int i = 0; i < n; ++i) {
+    if (best < 0) { best = i; continue; }
+    // latency class first, then oldest
+    if (ready[i].klass < ready[best].klass || (ready[i].klass == ready[best].klass && ready[i].age < ready[best].age)) best = i;
+  }
+  return best;
+}
+
+int widest(const vte_ready_op* op, const int* el, int n, const vte_pool_view* S, int max_width) {
+  int best = -1;
+  for (int i = 0; i < n; ++i) {
+    const vte_pctx_info& p = S->pctx[el[i]];
+    if (p.width > max_width) continue;
+    if (best < 0) { best = el[i]; continue; }
+    const vte_pctx_info& b = S->pctx[best];
+    if (p.width > b.width || (p.width == b.width && el[i] == op->pred_pctx)) best = el[i];
+  }
+  return best;
+}
+
+int builtin_select(vte_ctx* c, const vte_ready_op* op, const int* el, int n, const vte_pool_view* S) {
+  if (n == 0) return -1;
+  const int total = c->pool.total_cus();
+  if (c->builtin == VTE_POLICY_WIDEST) return widest(op, el, n, S, total);
+  // QUEUE_STATE
+  if (op->klass == VTE_CLASS_LATENCY) {
+    double best_t = -1;
+    for (int i = 0; i < n; ++i) {
+      const double t = profile_time(c, op->desc.profile_key, S->pctx[el[i]].width);
+      if (t > 0 && (best_t < 0 || t < best_t)) best_t = t;
+    }
+    if (best_t < 0) return widest(op, el, n, S, total);  // no profile: take what scales best
+    int pick = -1;
+    for (int i = 0; i < n; ++i) {
+      const vte_pctx_info& p = S->pctx[el[i]];
+      const double t = profile_time(c, op->desc.profile_key, p.width);
+      if (t <= 0 || t > best_t * (1.0 + c->slack)) continue;
+      if (pick < 0 || p.width < S->pctx[pick].width ||
+          (p.width == S->pctx[pick].width && el[i] == op->pred_pctx)) pick = el[i];
+    }
+    return pick >= 0 ? pick : widest(op, el, n, S, total);
+  }
+  const bool latency_active = S->ready_by_class[VTE_CLASS_LATENCY] + S->inflight_by_class[VTE_CLASS_LATENCY] > 0;
+  int cap = latency_active ? total - c->keep_free : total;
+  int p = widest(op, el, n, S, cap);
+  return p;
+}
+
+// ---- binding and submission (Sec. 4.4) ----------------------------------------------
+
+bool compatible(const vte_desc* d, const Pctx& p) {
+  // every pCtx is a CU subset of the same device: a descriptor runs unchanged on
+  // any of them as long as one workgroup fits one CU
+  const uint64_t threads = static_cast<uint64_t>(d->block[0]) * d->block[1] * d->block[2];
+  return p.width >= 1 && threads >= 1 && threads <= 1024 && d->lds_bytes <= 160u * 1024u;
+}
+
+// Validate the proposal, open or reuse the lease, submit the descriptor
+// unchanged, record it as outstanding.  Commit only after a successful submit.
+int bind_and_submit(vte_ctx* c, Op* op, int pctx) {
+  if (pctx < 0 || pctx >= c->pool.size()) { set_error("no such pCtx"); return VTE_EINVAL; }
+  Pctx& p = c->pool.at(pctx);
+  if (!compatible(op->desc, p)) { set_error("pCtx cannot run the descriptor unchanged"); return VTE_EINCOMPAT; }
+  int rc = can_admit(c, pctx, op->vs);
+  if (rc != VTE_OK) { ++c->stats.lease_conflicts; return rc; }
+  // device-side edges for predecessors still running on other pCtxs (PIPELINED)
+  for (vte_token t : op->deps) {
+    auto it = c->live.find(t);
+    if (it == c->live.end() || it->second->state != kInflight) continue;
+    if (it->second->pctx == pctx) continue;  // same backend stream: stream order
+    rc = c->backend->wait_on(p.stream, it->second->completion, it->second->pctx);
+    if (rc != VTE_OK) return rc;
+  }
+  void* completion = nullptr;
+  rc = c->backend->submit(op->desc, p.stream, pctx, op->tok, &completion);
+  if (rc != VTE_OK) { ++c->stats.submit_failures; return rc; }  // op stays ready
+  admit(c, pctx, op->vs);
+  op->pctx = pctx;
+  op->completion = completion;
+  op->state = kInflight;
+  op->t_bound = c->now();
+  c->inflight.push_back(op);
+  ++c->inflight_by_class[op->klass];
+  if (op->vs >= 0) ++c->vstreams[op->vs]->unfinished_bound;
+  return VTE_OK;
+}
+
+// One dispatch round: gather the ready heads, let the policy pick and select,
+// validate, submit.  Returns true if something was bound.
+bool dispatch_round(vte_ctx* c) {
+  std::vector<vte_ready_op> ready;
+  std::vector<Op*> ready_ops;
+  for (vte_vstream* vs : c->vstreams) {
+    if (!vs || vs->queue.empty()) continue;
+    Op* op = vs->queue.front();
+    int pred = -1;
+    if (!bindable(c, vs, op, &pred)) continue;
+    if (!op->ready_marked) { op->ready_marked = true; op->t_ready = c->now(); }
+    vte_ready_op r;
+    std::memset(&r, 0, sizeof r);
+    r.token = op->tok; r.vstream = vs->id; r.klass = vs->klass; r.pinned_pctx = vs->pinned;
+    r.age = op->age; r.pred_pctx = pred;
+    vte_desc_info(op->desc, &r.desc);
+    ready.push_back(r);
+    ready_ops.push_back(op);
+  }
+  if (ready.empty()) return false;
+
+  std::vector<vte_pctx_info> infos(c->pool.size());
+  for (int i = 0; i < c->pool.size(); ++i) fill_info(c->pool, i, &infos[i]);
+  vte_pool_view S;
+  S.count = c->pool.size();
+  S.pctx = infos.data();
+  S.ready_by_class[0] = S.ready_by_class[1] = 0;
+  for (auto& r : ready) ++S.ready_by_class[r.klass];
+  S.inflight_by_class[0] = c->inflight_by_class[0];
+  S.inflight_by_class[1] = c->inflight_by_class[1];
+
+  bool bound_any = false;
+  // each ready op gets at most one proposal per round
+  std::vector<char> tried(ready.size(), 0);
+  for (size_t round = 0; round < ready.size(); ++round) {
+    std::vector<vte_ready_op> q;
+    std::vector<int> qi;
+    for (size_t i = 0; i < ready.size(); ++i)
+      if (!tried[i]) { q.push_back(ready[i]); qi.push_back(static_cast<int>(i)); }
+    if (q.empty()) break;
+    int pick = c->custom_policy && c->policy.pick
+                   ? c->policy.pick(c->policy_user, q.data(), static_cast<int>(q.size()), &S)
+                   : builtin_pick(c, q.data(), static_cast<int>(q.size()), &S);
+    if (pick < 0 || pick >= static_cast<int>(q.size())) break;  // policy defers
+    const int ri = qi[pick];
+    tried[ri] = 1;
+    Op* op = ready_ops[ri];
+    const vte_ready_op& ro = ready[ri];
+    // E: non-conflicting pCtxs that can run the op unchanged
+    std::vector<int> eligible;
+    for (int id = 0; id < c->pool.size(); ++id) {
+      if (ro.pinned_pctx >= 0 && id != ro.pinned_pctx) continue;
+      if (!compatible(op->desc, c->pool.at(id))) continue;
+      if (can_admit(c, id, op->vs) != VTE_OK) continue;
+      eligible.push_back(id);
+    }
+    if (eligible.empty()) continue;
+    int sel = c->custom_policy && c->policy.select
+                  ? c->policy.select(c->policy_user, &ro, eligible.data(), static_cast<int>(eligible.size()), &S)
+                  : builtin_select(c, &ro, eligible.data(), static_cast<int>(eligible.size()), &S);
+    if (sel < 0) continue;
+    // the proposal is tentative: it must be one of E and still valid
+    if (std::find(eligible.begin(), eligible.end(), sel) == eligible.end()) { ++c->stats.stale_proposals; continue; }
+    int rc = bind_and_submit(c, op, sel);
+    if (rc != VTE_OK) continue;  // op remains ready for rescheduling
+    c->vstreams[op->vs]->queue.pop_front();
+    bound_any = true;
+    for (int i = 0; i < c->pool.size(); ++i) fill_info(c->pool, i, &infos[i]);
+    --S.ready_by_class[ro.klass];
+    S.inflight_by_class[0] = c->inflight_by_class[0];
+    S.inflight_by_class[1] = c->inflight_by_class[1];
+  }
+  return bound_any;
+}
+
+void dispatcher_main(vte_ctx* c) {
+  c->backend->make_current();
+  Lock lk(c->mu);
+  while (true) {
+    const uint64_t seen = c->change_seq;
+    bool progress = poll_completions(c);
+    // keep binding while ops become bindable (PIPELINED chains, freed leases)
+    while (dispatch_round(c)) progress = true;
+    if (c->stop && c->live.empty()) break;
+    if (progress) continue;
+    if (c->change_seq == seen) {
+      c->quiesced_seq = seen;
+      c->cv_done.notify_all();
+    }
+    if (!c->inflight.empty() && !c->backend->is_fake()) {
+      // device work outstanding: poll again soon, letting callers in
+      lk.unlock();
+      std::this_thread::yield();
+      lk.lock();
+    } else if (c->change_seq == seen) {
+      // nothing can change without outside input (or a policy that deferred)
+      bool pending = false;
+      for (vte_vstream* vs : c->vstreams) if (vs && !vs->queue.empty()) pending = true;
+      if (pending && c->inflight.empty()) c->cv_work.wait_for(lk, std::chrono::microseconds(200));
+      else c->cv_work.wait(lk, [&] { return c->change_seq != seen || c->stop; });
+    }
+  }
+}
+
+vte_ctx* ctx_of(vte_vstream* vs) { return vs ? vs->ctx : nullptr; }
+
+}  // namespace
+}  // namespace vte
+
+using namespace vte;
+
+extern "C" {
+
+const char* vte_last_error(void) { return g_err.c_str(); }
+int vte_last_hip_error(void) { return g_hip_err; }
+
+int vte_pool_cfg_default(vte_pool_cfg* cfg) {
+  if (!cfg) { set_error("null cfg"); return VTE_EINVAL; }
+  std::memset(cfg, 0, sizeof *cfg);
+  cfg->backend = VTE_BACKEND_HIP;
+  cfg->leaf_cus = 32;
+  cfg->layout = VTE_LAYOUT_STRIPED;
+  cfg->with_remainders = 1;
+  cfg->mode = VTE_MODE_STRICT;
+  cfg->lookahead = 16;
+  cfg->stats_capacity = 65536;
+  return VTE_OK;
+}
+
+int vte_init(vte_ctx** out, int device, const vte_pool_cfg* user_cfg) {
+  if (!out) { set_error("null out"); return VTE_EINVAL; }
+  vte_pool_cfg cfg;
+  vte_pool_cfg_default(&cfg);
+  if (user_cfg) cfg = *user_cfg;
+  if (cfg.leaf_cus <= 0) cfg.leaf_cus = 32;
+  if (cfg.lookahead <= 0) cfg.lookahead = 16;
+  if (cfg.stats_capacity <= 0) cfg.stats_capacity = 65536;
+  if (cfg.layout != VTE_LAYOUT_STRIPED) { set_error("only VTE_LAYOUT_STRIPED is offered"); return VTE_EINVAL; }
+  if (cfg.mode != VTE_MODE_STRICT && cfg.mode != VTE_MODE_PIPELINED) { set_error("unknown mode"); return VTE_EINVAL; }
+  if (cfg.backend != VTE_BACKEND_HIP && cfg.backend != VTE_BACKEND_FAKE) { set_error("unknown backend"); return VTE_EINVAL; }
+  vte_ctx* c = new (std::nothrow) vte_ctx;
+  if (!c) { set_error("out of host memory"); return VTE_ENOMEM; }
+  c->cfg = cfg;
+  c->device = device;
+  c->t0 = std::chrono::steady_clock::now();
+  c->backend = cfg.backend == VTE_BACKEND_FAKE ? make_fake_backend() : make_hip_backend();
+  int cus = cfg.total_cus;
+  int rc = c->backend->init(device, &cus);
+  if (rc != VTE_OK) { delete c->backend; delete c; return rc; }
+  c->cfg.total_cus = cus;
+  std::string err;
+  if (cus > 256) { set_error("more than 256 CUs are not supported"); delete c->backend; delete c; return VTE_EINVAL; }
+  if (!c->pool.build(cus, cfg.leaf_cus, cfg.with_remainders != 0, &err)) {
+    set_error(err); delete c->backend; delete c; return VTE_EINVAL;
+  }
+  // pre-create every pCtx's backend stream: nothing is created on the dispatch path
+  for (int id = 0; id < c->pool.size(); ++id) {
+    Pctx& p = c->pool.at(id);
+    rc = c->backend->create_stream(p.mask.data(), static_cast<int>(p.mask.size()), &p.stream);
+    if (rc != VTE_OK) {
+      for (int j = 0; j < id; ++j) c->backend->destroy_stream(c->pool.at(j).stream);
+      delete c->backend; delete c; return rc;
+    }
+  }
+  c->ring.resize(static_cast<size_t>(cfg.stats_capacity));
+  c->dispatcher = std::thread(dispatcher_main, c);
+  *out = c;
+  return VTE_OK;
+}
+
+int vte_device_sync(vte_ctx* c) {
+  if (!c) { set_error("null ctx"); return VTE_EINVAL; }
+  Lock lk(c->mu);
+  // waits on every token issued so far (all vstream tails and explicit launches)
+  const vte_token upto = c->next_token;
+  c->cv_done.wait(lk, [&] {
+    for (auto& kv : c->live) if (kv.first < upto) return false;
+    return true;
+  });
+  return VTE_OK;
+}
+
+int vte_shutdown(vte_ctx* c) {
+  if (!c) { set_error("null ctx"); return VTE_EINVAL; }
+  if (!c->backend->is_fake()) vte_device_sync(c);
+  {
+    Lock lk(c->mu);
+    if (c->backend->is_fake()) {
+      // nothing will complete by itself: finish what is in flight, drop the rest
+      auto* fb = static_cast<FakeBackend*>(c->backend);
+      fb->autocomplete = true;
+      for (Op* op : c->inflight) fb->complete(op->tok);
+      for (vte_vstream* vs : c->vstreams) {
+        if (!vs) continue;
+        for (Op* op : vs->queue) { c->live.erase(op->tok); delete op; }
+        vs->queue.clear();
+      }
+    }
+    c->stop = true;
+    bump(c);
+  }
+  c->dispatcher.join();
+  for (int id = 0; id < c->pool.size(); ++id) c->backend->destroy_stream(c->pool.at(id).stream);
+  for (vte_vstream* vs : c->vstreams) delete vs;
+  for (vte_desc* d : c->descs) delete d;
+  delete c->backend;
+  delete c;
+  return VTE_OK;
+}
+
+int vte_pool_count(vte_ctx* c, int* count) {
+  if (!c || !count) { set_error("null argument"); return VTE_EINVAL; }
+  *count = c->pool.size();
+  return VTE_OK;
+}
+
+int vte_pool_info(vte_ctx* c, int id, vte_pctx_info* info) {
+  if (!c || !info || id < 0 || id >= c->pool.size()) { set_error("pool_info: bad argument"); return VTE_EINVAL; }
+  Lock lk(c->mu);
+  fill_info(c->pool, id, info);
+  return VTE_OK;
+}
+
+int vte_pool_find(vte_ctx* c, int kind, int width, int index, int* pctx_id) {
+  if (!c || !pctx_id || index < 0) { set_error("pool_find: bad argument"); return VTE_EINVAL; }
+  for (int id = 0; id < c->pool.size(); ++id) {
+    const Pctx& p = c->pool.at(id);
+    if (p.kind == kind && p.width == width && index-- == 0) { *pctx_id = id; return VTE_OK; }
+  }
+  set_error("pool_find: no such pCtx");
+  return VTE_EINVAL;
+}
+
+int vte_pool_conflict(vte_ctx* c, int a, int b, int* conflict) {
+  if (!c || !conflict || a < 0 || b < 0 || a >= c->pool.size() || b >= c->pool.size()) { set_error("pool_conflict: bad argument"); return VTE_EINVAL; }
+  *conflict = c->pool.overlaps(a, b) ? 1 : 0;
+  return VTE_OK;
+}
+
+int vte_pctx_native_stream(vte_ctx* c, int id, void** s) {
+  if (!c || !s || id < 0 || id >= c->pool.size()) { set_error("native_stream: bad argument"); return VTE_EINVAL; }
+  *s = c->pool.at(id).stream;
+  return VTE_OK;
+}
+
+int vte_desc_destroy(vte_desc* d) {
+  if (!d) { set_error("null desc"); return VTE_EINVAL; }
+  vte_ctx* c = d->ctx;
+  {
+    Lock lk(c->mu);
+    for (auto& kv : c->live)
+      if (kv.second->desc == d) { set_error("descriptor still has launches in flight"); return VTE_EBUSY; }
+    c->descs.erase(std::remove(c->descs.begin(), c->descs.end(), d), c->descs.end());
+  }
+  delete d;
+  return VTE_OK;
+}
+
+int vte_bind_and_launch(vte_ctx* c, const vte_desc* d, int pctx, vte_token* tok_out) {
+  if (!c || !d) { set_error("bind_and_launch: null argument"); return VTE_EINVAL; }
+  if (d->ctx != c) { set_error("descriptor belongs to another context"); return VTE_EINVAL; }
+  Lock lk(c->mu);
+  Op* op = new (std::nothrow) Op;
+  if (!op) { set_error("out of host memory"); return VTE_ENOMEM; }
+  op->tok = c->next_token;
+  op->desc = d;
+  op->vs = -1;
+  op->klass = VTE_CLASS_LATENCY;
+  op->age = c->next_age;
+  op->t_submit = op->t_ready = c->now();
+  c->backend->make_current();
+  int rc = bind_and_submit(c, op, pctx);
+  if (rc != VTE_OK) { delete op; return rc; }
+  ++c->next_token;
+  ++c->next_age;
+  c->live[op->tok] = op;
+  ++c->stats.submitted;
+  if (tok_out) *tok_out = op->tok;
+  bump(c);
+  return VTE_OK;
+}
+
+int vte_vstream_create(vte_ctx* c, int klass, vte_vstream** out) {
+  if (!c || !out || (klass != VTE_CLASS_LATENCY && klass != VTE_CLASS_BEST_EFFORT)) { set_error("vstream_create: bad argument"); return VTE_EINVAL; }
+  vte_vstream* vs = new (std::nothrow) vte_vstream;
+  if (!vs) { set_error("out of host memory"); return VTE_ENOMEM; }
+  Lock lk(c->mu);
+  vs->ctx = c;
+  vs->klass = klass;
+  vs->id = static_cast<int>(c->vstreams.size());
+  c->vstreams.push_back(vs);
+  *out = vs;
+  return VTE_OK;
+}
+
+int vte_vstream_id(const vte_vstream* vs, int* id) {
+  if (!vs || !id) { set_error("null argument"); return VTE_EINVAL; }
+  *id = vs->id;
+  return VTE_OK;
+}
+
+int vte_vstream_pin(vte_vstream* vs, int pctx) {
+  vte_ctx* c = ctx_of(vs);
+  if (!c || pctx < -1 || pctx >= c->pool.size()) { set_error("vstream_pin: bad argument"); return VTE_EINVAL; }
+  Lock lk(c->mu);
+  vs->pinned = pctx;
+  bump(c);
+  return VTE_OK;
+}
+
+int vte_submit_after(vte_vstream* vs, const vte_desc* d, const vte_token* deps, int n_deps, vte_token* tok_out) {
+  vte_ctx* c = ctx_of(vs);
+  if (!c || !d || n_deps < 0 || (n_deps > 0 && !deps)) { set_error("submit: bad argument"); return VTE_EINVAL; }
+  if (d->ctx != c) { set_error("descriptor belongs to another context"); return VTE_EINVAL; }
+  Lock lk(c->mu);
+  if (!vs->alive) { set_error("vstream was destroyed"); return VTE_EINVAL; }
+  for (int i = 0; i < n_deps; ++i)
+    if (deps[i] >= c->next_token) { set_error("dependency on a token that was never issued"); return VTE_EINVAL; }
+  Op* op = new (std::nothrow) Op;
+  if (!op) { set_error("out of host memory"); return VTE_ENOMEM; }
+  op->tok = c->next_token++;
+  op->desc = d;
+  op->vs = vs->id;
+  op->klass = vs->klass;
+  op->age = c->next_age++;
+  op->t_submit = c->now();
+  op->deps.push_back(vs->tail);  // stream order: depends on the tail, becomes the tail
+  for (int i = 0; i < n_deps; ++i) op->deps.push_back(deps[i]);
+  vs->tail = op->tok;
+  vs->queue.push_back(op);
+  c->live[op->tok] = op;
+  ++c->stats.submitted;
+  if (tok_out) *tok_out = op->tok;
+  bump(c);
+  return VTE_OK;
+}
+
+int vte_submit(vte_vstream* vs, const vte_desc* d, vte_token* tok_out) {
+  return vte_submit_after(vs, d, nullptr, 0, tok_out);
+}
+
+int vte_token_query(vte_ctx* c, vte_token t, int* done) {
+  if (!c || !done) { set_error("null argument"); return VTE_EINVAL; }
+  Lock lk(c->mu);
+  if (t >= c->next_token) { set_error("token was never issued"); return VTE_EINVAL; }
+  *done = token_done(c, t) ? 1 : 0;
+  return VTE_OK;
+}
+
+int vte_token_wait(vte_ctx* c, vte_token t) {
+  if (!c) { set_error("null ctx"); return VTE_EINVAL; }
+  Lock lk(c->mu);
+  if (t >= c->next_token) { set_error("token was never issued"); return VTE_EINVAL; }
+  c->cv_done.wait(lk, [&] { return token_done(c, t); });
+  return VTE_OK;
+}
+
+int vte_vstream_sync(vte_vstream* vs) {
+  vte_ctx* c = ctx_of(vs);
+  if (!c) { set_error("null vstream"); return VTE_EINVAL; }
+  vte_token t;
+  {
+    Lock lk(c->mu);
+    t = vs->tail;
+  }
+  return vte_token_wait(c, t);
+}
+
+int vte_vstream_destroy(vte_vstream* vs) {
+  vte_ctx* c = ctx_of(vs);
+  if (!c) { set_error("null vstream"); return VTE_EINVAL; }
+  if (!c->backend->is_fake()) vte_vstream_sync(vs);
+  Lock lk(c->mu);
+  if (!vs->queue.empty() || vs->unfinished_bound > 0) { set_error("vstream still has work"); return VTE_EBUSY; }
+  vs->alive = false;  // the slot stays so ids remain stable; freed at shutdown
+  for (int id = 0; id < c->pool.size(); ++id) {
+    Pctx& p = c->pool.at(id);
+    if (p.reserved_for == vs->id) {
+      p.reserved_for = -1; p.reservation_pending = false;
+      if (p.state == kReserved) p.state = kIdle;
+      if (p.state == kIdle) c->pool.set_active(id, false);
+    }
+  }
+  settle_reservations(c);
+  bump(c);
+  return VTE_OK;
+}
+
+// ---- lease control ------------------------------------------------------------------
+
+int vte_pctx_close_gate(vte_ctx* c, int id) {
+  if (!c || id < 0 || id >= c->pool.size()) { set_error("close_gate: bad argument"); return VTE_EINVAL; }
+  Lock lk(c->mu);
+  Pctx& p = c->pool.at(id);
+  if (p.state == kLeased) {
+    p.state = kDraining;  // outstanding work continues, no new admissions
+    p.gate_open = false;
+    ++c->stats.gates_closed;
+  }
+  bump(c);
+  return VTE_OK;
+}
+
+int vte_pctx_reserve(vte_ctx* c, int id, vte_vstream* vs) {
+  if (!c || !vs || vs->ctx != c || id < 0 || id >= c->pool.size()) { set_error("reserve: bad argument"); return VTE_EINVAL; }
+  Lock lk(c->mu);
+  Pctx& p = c->pool.at(id);
+  if (p.reserved_for >= 0 && p.reserved_for != vs->id) { set_error("pCtx is reserved for another vstream"); return VTE_EBUSY; }
+  std::vector<int> ov;
+  c->pool.active_overlapping(id, &ov);
+  for (int o : ov) {
+    const Pctx& q = c->pool.at(o);
+    if (q.reserved_for >= 0 && q.reserved_for != vs->id) { set_error("overlaps a reservation of another vstream"); return VTE_EBUSY; }
+  }
+  p.reserved_for = vs->id;
+  ++c->stats.reservations;
+  if (p.state == kIdle) {
+    c->pool.set_active(id, true);  // from now on unrelated leases are excluded
+    if (ov.empty()) { p.state = kReserved; p.reservation_pending = false; }
+    else p.reservation_pending = true;  // waits for overlapping work to drain
+  }
+  // leased / draining: becomes RESERVED when its outstanding count reaches zero
+  bump(c);
+  return VTE_OK;
+}
+
+int vte_pctx_unreserve(vte_ctx* c, int id) {
+  if (!c || id < 0 || id >= c->pool.size()) { set_error("unreserve: bad argument"); return VTE_EINVAL; }
+  Lock lk(c->mu);
+  Pctx& p = c->pool.at(id);
+  p.reserved_for = -1;
+  p.reservation_pending = false;
+  if (p.state == kReserved) p.state = kIdle;
+  if (p.state == kIdle) c->pool.set_active(id, false);
+  settle_reservations(c);
+  bump(c);
+  return VTE_OK;
+}
+
+// ---- policy -----------------------------------------------------------------------------
+
+int vte_set_policy(vte_ctx* c, const vte_policy_vtbl* vtbl, void* user) {
+  if (!c) { set_error("null ctx"); return VTE_EINVAL; }
+  Lock lk(c->mu);
+  if (vtbl) { c->policy = *vtbl; c->policy_user = user; c->custom_policy = true; }
+  else { c->custom_policy = false; std::memset(&c->policy, 0, sizeof c->policy); c->policy_user = nullptr; }
+  bump(c);
+  return VTE_OK;
+}
+
+int vte_set_builtin_policy(vte_ctx* c, int which, double slack, int keep_free_cus) {
+  if (!c || (which != VTE_POLICY_WIDEST && which != VTE_POLICY_QUEUE_STATE) || slack < 0 || keep_free_cus < 0) {
+    set_error("set_builtin_policy: bad argument"); return VTE_EINVAL;
+  }
+  Lock lk(c->mu);
+  c->custom_policy = false;
+  c->builtin = which;
+  c->slack = slack;
+  c->keep_free = keep_free_cus;
+  bump(c);
+  return VTE_OK;
+}
+
+int vte_hint_submit(vte_ctx* c, const vte_hint* hint) {
+  if (!c || !hint) { set_error("null argument"); return VTE_EINVAL; }
+  Lock lk(c->mu);
+  if (hint->vstream < 0 || hint->vstream >= static_cast<int>(c->vstreams.size())) { set_error("hint: no such vstream"); return VTE_EINVAL; }
+  std::vector<vte_pctx_info> infos(c->pool.size());
+  for (int i = 0; i < c->pool.size(); ++i) fill_info(c->pool, i, &infos[i]);
+  vte_pool_view S{};
+  S.count = c->pool.size();
+  S.pctx = infos.data();
+  S.inflight_by_class[0] = c->inflight_by_class[0];
+  S.inflight_by_class[1] = c->inflight_by_class[1];
+  vte_prepare_plan plan;
+  std::memset(&plan, 0, sizeof plan);
+  plan.target_pctx = -1;
+  if (c->custom_policy && c->policy.prepare) {
+    c->policy.prepare(c->policy_user, hint, &S, &plan);
+  } else {
+    // default Prepare: the narrowest pCtx at least as wide as wanted with the
+    // fewest overlapping active leases; close those gates, reserve the target
+    int best = -1; size_t best_ov = 0;
+    for (int id = 0; id < c->pool.size(); ++id) {
+      const Pctx& p = c->pool.at(id);
+      if (p.width < hint->want_width) continue;
+      if (p.reserved_for >= 0 && p.reserved_for != hint->vstream) continue;
+      std::vector<int> ov; c->pool.active_overlapping(id, &ov);
+      if (best < 0 || p.width < c->pool.at(best).width || (p.width == c->pool.at(best).width && ov.size() < best_ov)) { best = id; best_ov = ov.size(); }
+    }
+    if (best >= 0) {
+      plan.target_pctx = best; plan.reserve = 1;
+      std::vector<int> ov; c->pool.active_overlapping(best, &ov);
+      for (int o : ov) if (plan.n_close < 32 && c->pool.at(o).state == kLeased && o != best) plan.close[plan.n_close++] = o;
+    }
+  }
+  // validate the plan before touching physical state
+  if (plan.target_pctx < 0) return VTE_OK;
+  if (plan.target_pctx >= c->pool.size() || plan.n_close < 0 || plan.n_close > 32) { ++c->stats.stale_proposals; set_error("prepare: plan rejected"); return VTE_EINVAL; }
+  vte_vstream* vs = c->vstreams[hint->vstream];
+  for (int i = 0; i < plan.n_close; ++i) {
+    const int o = plan.close[i];
+    if (o < 0 || o >= c->pool.size() || !c->pool.overlaps(o, plan.target_pctx)) { ++c->stats.stale_proposals; continue; }
+    Pctx& q = c->pool.at(o);
+    if (q.state == kLeased && o != plan.target_pctx) { q.state = kDraining; q.gate_open = false; ++c->stats.gates_closed; }
+  }
+  lk.unlock();
+  if (plan.reserve) return vte_pctx_reserve(c, plan.target_pctx, vs);
+  return VTE_OK;
+}
+
+// ---- profiles --------------------------------------------------------------------------
+
+int vte_profile_set(vte_ctx* c, uint64_t key, int width, double seconds) {
+  if (!c || width <= 0 || !(seconds > 0)) { set_error("profile_set: bad argument"); return VTE_EINVAL; }
+  Lock lk(c->mu);
+  c->profiles[{key, width}] = seconds;
+  return VTE_OK;
+}
+
+int vte_profile_get(vte_ctx* c, uint64_t key, int width, double* seconds) {
+  if (!c || !seconds) { set_error("null argument"); return VTE_EINVAL; }
+  Lock lk(c->mu);
+  const double t = profile_time(c, key, width);
+  if (t < 0) { set_error("no profile for this key and width"); return VTE_EINVAL; }
+  *seconds = t;
+  return VTE_OK;
+}
+
+int vte_profile_measure(vte_ctx* c, const vte_desc* d, int warmup, int reps) {
+  if (!c || !d || d->ctx != c || warmup < 0 || reps < 1) { set_error("profile_measure: bad argument"); return VTE_EINVAL; }
+  if (c->backend->is_fake()) { set_error("profiles cannot be measured on the fake backend"); return VTE_ESTATE; }
+  vte_device_sync(c);
+  Lock lk(c->mu);
+  if (!c->inflight.empty()) { set_error("profile_measure needs an idle device"); return VTE_EBUSY; }
+  c->backend->make_current();
+  std::vector<int> seen;
+  for (int id = 0; id < c->pool.size(); ++id) {
+    const Pctx& p = c->pool.at(id);
+    if (std::find(seen.begin(), seen.end(), p.width) != seen.end()) continue;
+    seen.push_back(p.width);
+    double sec = 0;
+    int rc = c->backend->time_launches(d, p.stream, warmup, reps, &sec);
+    if (rc != VTE_OK) return rc;
+    c->profiles[{d->profile_key, p.width}] = sec;
+  }
+  return VTE_OK;
+}
+
+// ---- statistics -----------------------------------------------------------------------
+
+int vte_stats(vte_ctx* c, vte_stats_t* out) {
+  if (!c || !out) { set_error("null argument"); return VTE_EINVAL; }
+  Lock lk(c->mu);
+  *out = c->stats;
+  return VTE_OK;
+}
+
+int vte_stats_read(vte_ctx* c, vte_op_record* dst, int cap, int* n_out) {
+  if (!c || !dst || cap < 0 || !n_out) { set_error("stats_read: bad argument"); return VTE_EINVAL; }
+  Lock lk(c->mu);
+  const size_t n = std::min<size_t>(static_cast<size_t>(cap), c->ring_count);
+  const size_t first = c->ring_count - n;
+  for (size_t i = 0; i < n; ++i) dst[i] = c->ring[(c->ring_head + first + i) % c->ring.size()];
+  *n_out = static_cast<int>(n);
+  return VTE_OK;
+}
+
+int vte_stats_reset(vte_ctx* c) {
+  if (!c) { set_error("null ctx"); return VTE_EINVAL; }
+  Lock lk(c->mu);
+  std::memset(&c->stats, 0, sizeof c->stats);
+  c->ring_head = c->ring_count = 0;
+  return VTE_OK;
+}
+
+// ---- fake backend hooks ------------------------------------------------------------------
+
+static FakeBackend* fake_of(vte_ctx* c) {
+  if (!c) { set_error("null ctx"); return nullptr; }
+  if (!c->backend->is_fake()) { set_error("only valid with the fake backend"); return nullptr; }
+  return static_cast<FakeBackend*>(c->backend);
+}
+
+int vte_fake_complete(vte_ctx* c, vte_token t) {
+  FakeBackend* fb = fake_of(c);
+  if (!fb) return c ? VTE_ESTATE : VTE_EINVAL;
+  Lock lk(c->mu);
+  if (!fb->complete(t)) { set_error("fake_complete: token is not in flight"); return VTE_EINVAL; }
+  bump(c);
+  return VTE_OK;
+}
+
+int vte_fake_set_autocomplete(vte_ctx* c, int on) {
+  FakeBackend* fb = fake_of(c);
+  if (!fb) return c ? VTE_ESTATE : VTE_EINVAL;
+  Lock lk(c->mu);
+  fb->autocomplete = on != 0;
+  return VTE_OK;
+}
+
+int vte_fake_fail_next_submits(vte_ctx* c, int n) {
+  FakeBackend* fb = fake_of(c);
+  if (!fb) return c ? VTE_ESTATE : VTE_EINVAL;
+  Lock lk(c->mu);
+  fb->fail_next = n;
+  return VTE_OK;
+}
+
+int vte_fake_log(vte_ctx* c, vte_fake_log_entry* dst, int cap, int* n_out) {
+  FakeBackend* fb = fake_of(c);
+  if (!fb) return c ? VTE_ESTATE : VTE_EINVAL;
+  if (!dst || !n_out || cap < 0) { set_error("fake_log: bad argument"); return VTE_EINVAL; }
+  Lock lk(c->mu);
+  const int n = std::min<int>(cap, static_cast<int>(fb->log.size()));
+  for (int i = 0; i < n; ++i) dst[i] = fb->log[i];
+  *n_out = n;
+  return VTE_OK;
+}
+
+int vte_dispatcher_quiesce(vte_ctx* c) {
+  if (!c) { set_error("null ctx"); return VTE_EINVAL; }
+  Lock lk(c->mu);
+  bump(c);  // force one more full pass after everything the caller did
+  const uint64_t want = c->change_seq;
+  c->cv_done.wait(lk, [&] { return c->quiesced_seq >= want && c->quiesced_seq != ~0ull; });
+  return VTE_OK;
+}
+
+int vte_now(vte_ctx* c, double* seconds) {
+  if (!c || !seconds) { set_error("null argument"); return VTE_EINVAL; }
+  *seconds = c->now();
+  return VTE_OK;
+}
+
+}  // extern "C"

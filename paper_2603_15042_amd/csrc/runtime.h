@@ -1,0 +1,137 @@
+// Internal types of the late-binding runtime: descriptors, backends, ops,
+// virtual streams and the context that ties them to the pCtx pool.
+#pragma once
+#include <atomic>
+#include <chrono>
+#include <condition_variable>
+#include <cstdint>
+#include <deque>
+#include <map>
+#include <mutex>
+#include <string>
+#include <thread>
+#include <unordered_map>
+#include <vector>
+
+#include "../../include/vte.h"
+#include "pool.h"
+
+// Immutable launch descriptor D_k (Sec. 4.2).  Every field is written once by a
+// constructor in desc.cpp; the dispatcher and the backends only ever see it
+// through a pointer to const.
+struct vte_desc {
+  vte_ctx* ctx;
+  int kernel;
+  const void* entry;  // kernel entry (host stub address)
+  uint32_t grid[3];
+  uint32_t block[3];
+  uint32_t lds_bytes;
+  uint32_t arg_bytes;
+  alignas(16) unsigned char args[160];
+  uint64_t hash;
+  uint64_t profile_key;
+  uint64_t bytes;
+  uint64_t flops;
+};
+
+namespace vte {
+
+void set_error(const std::string& msg, int hip_code = 0);
+uint64_t fnv1a(const void* data, size_t n, uint64_t h = 1469598103934665603ull);
+uint64_t desc_hash(const vte_desc* d);
+
+// What a pCtx needs from the device side.  HIP: CU-masked streams and events.
+// FAKE: a log, with completions driven by the test.
+class Backend {
+ public:
+  virtual ~Backend() {}
+  virtual bool is_fake() const = 0;
+  virtual int init(int device, int* cu_count) = 0;
+  virtual int make_current() = 0;  // bind the device to the calling thread
+  virtual int create_stream(const uint32_t* mask, int words, void** stream) = 0;
+  virtual void destroy_stream(void* stream) = 0;
+  // Submit the descriptor unchanged on `stream`, then record a completion.
+  virtual int submit(const vte_desc* d, void* stream, int pctx, vte_token tok, void** completion) = 0;
+  // Make later work on `stream` wait (on the device) for `completion`.
+  virtual int wait_on(void* stream, void* completion, int completion_pctx) = 0;
+  virtual bool is_done(void* completion) = 0;
+  virtual void release(void* completion) = 0;
+  virtual int sync_stream(void* stream) = 0;
+  // Seconds per launch of `d` on `stream`, device-timed.
+  virtual int time_launches(const vte_desc* d, void* stream, int warmup, int reps, double* sec) = 0;
+  virtual int prepare_kernel(const vte_desc* d) = 0;  // one-time per-kernel attributes
+};
+
+Backend* make_hip_backend();
+Backend* make_fake_backend();
+
+enum OpState { kWaiting = 0, kInflight = 1, kDone = 2 };
+
+struct Op {
+  vte_token tok = 0;
+  const vte_desc* desc = nullptr;
+  int vs = -1;
+  int klass = 0;
+  uint64_t age = 0;
+  std::vector<vte_token> deps;
+  int state = kWaiting;
+  int pctx = -1;
+  void* completion = nullptr;
+  bool ready_marked = false;
+  double t_submit = 0, t_ready = 0, t_bound = 0, t_done = 0;
+};
+
+}  // namespace vte
+
+struct vte_vstream {
+  vte_ctx* ctx;
+  int id;
+  int klass;
+  int pinned = -1;
+  vte_token tail = 0;
+  std::deque<vte::Op*> queue;  // submitted, not yet bound, in order
+  int unfinished_bound = 0;    // bound (in flight) ops of this stream
+  bool alive = true;
+};
+
+struct vte_ctx {
+  vte_pool_cfg cfg;
+  int device = 0;
+  vte::Backend* backend = nullptr;
+  vte::Pool pool;
+
+  std::mutex mu;
+  std::condition_variable cv_work;  // dispatcher sleeps here
+  std::condition_variable cv_done;  // waiters sleep here
+  std::thread dispatcher;
+  bool stop = false;
+  uint64_t change_seq = 0;    // bumped by every outside input
+  uint64_t quiesced_seq = ~0ull;
+
+  vte_token next_token = 1;
+  uint64_t next_age = 0;
+  std::unordered_map<vte_token, vte::Op*> live;  // not yet done
+  std::vector<vte::Op*> inflight;                // in bind order
+  std::vector<vte_vstream*> vstreams;
+  std::vector<vte_desc*> descs;
+  int inflight_by_class[2] = {0, 0};
+
+  vte_policy_vtbl policy{};
+  void* policy_user = nullptr;
+  bool custom_policy = false;
+  int builtin = VTE_POLICY_WIDEST;
+  double slack = 0.1;
+  int keep_free = 0;
+
+  std::map<std::pair<uint64_t, int>, double> profiles;
+
+  vte_stats_t stats{};
+  std::vector<vte_op_record> ring;
+  size_t ring_head = 0, ring_count = 0;
+
+  // fake backend state lives in the backend; log mirrored here for the API
+  std::chrono::steady_clock::time_point t0;
+  double now() const {
+    return std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
+  }
+};
