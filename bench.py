@@ -1,0 +1,150 @@
+"""Benchmark of the decode hot path on one MI355X.
+
+A step is one pass of the Llama-8B-shaped decode chain at batch 8 (gather,
+RMSNorm, QKV, O, gate/up+SiLU, down, LM head + argmax: seven immutable
+descriptors submitted to a virtual stream and late-bound by the dispatcher), on
+synthetic weights resident in HBM.  Prints one JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--batch", type=int, default=8)
+    ap.add_argument("--mode", choices=("pipelined", "strict"), default="pipelined")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-width-sweep", action="store_true")
+    ap.add_argument("--small", action="store_true", help="reduced shapes (debugging only; not a valid result)")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2603_15042_amd import harness as H, inputs, vte
+    if not os.path.exists(vte.LIB_PATH):
+        from paper_2603_15042_amd import build as b
+        b.build()
+
+    shp = inputs.DecodeShapes(D=1024, Nqkv=1536, F=3584, V=32064) if a.small else inputs.DecodeShapes()
+    B = a.batch
+    t0 = time.time()
+    w = inputs.decode_weights(0, shp)
+    tok0 = inputs.tokens(0, inputs.T_TOK0, B, shp.V)
+    gen_s = time.time() - t0
+
+    cfg = vte.vte_pool_cfg_default()
+    cfg.mode = vte.VTE_MODE_PIPELINED if a.mode == "pipelined" else vte.VTE_MODE_STRICT
+    cfg.lookahead = 64
+    cfg.device_timing_mask = 1 << vte.VTE_K_LMHEAD
+    torch.zeros(1, device="cuda")
+    ctx = vte.vte_init(0, cfg)
+    wd = H.upload_weights(w)
+    ch = H.DecodeChain(ctx, wd, shp, B, feedback=True)
+    vs = vte.vte_vstream_create(ctx, vte.VTE_CLASS_LATENCY)
+
+    def run(steps, vstream):
+        for _ in range(steps):
+            ch.submit_step(vstream)
+        vte.vte_vstream_sync(vstream)
+
+    ch.set_tokens(tok0)
+    run(a.warmup, vs)
+    vte.vte_device_sync(ctx)
+    torch.cuda.synchronize()
+    vte.vte_stats_reset(ctx)
+    t1 = time.perf_counter()
+    run(a.steps, vs)
+    vte.vte_device_sync(ctx)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t1
+    recs = vte.vte_stats_read(ctx)
+    lm = [r.gpu_seconds for r in recs if r.kernel == vte.VTE_K_LMHEAD and r.gpu_seconds > 0]
+    lm_bytes = vte.vte_desc_info(ch.desc["lmhead"]).bytes
+    lm_avg = float(np.mean(lm)) if lm else float("nan")
+    step_bytes = ch.bytes_per_step
+    value = step_bytes * a.steps / dt / 1e9
+    tokens_end = ch.tok.cpu().numpy().copy()
+
+    out = {
+        "metric": "GEMV/RMSNorm HBM GB/s (% peak) per CU width; bit mismatches across widths (=0)",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": round(dt / a.steps * 1e3, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "Llama-8B-shaped decode chain (RMSNorm 4096 -> QKV 4096x6144 -> O 4096x4096 -> "
+                               "gate/up 4096x2x14336 SiLU -> down 14336x4096 -> LM head 4096x128256 + argmax), "
+                               "batch %d, full width (256 CUs), %s binding" % (B, a.mode),
+                   "batch": B, "bytes_per_step": int(step_bytes), "small_shapes": bool(a.small)},
+        "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
+        "roofline": {"bound": "hbm", "kernel": "lm-head GEMV + argmax", "achieved": round(lm_bytes / lm_avg / 1e9, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(lm_bytes / lm_avg / 1e9 / HBM_PEAK_GBS, 4),
+                     "avg_kernel_us": round(lm_avg * 1e6, 2), "launches_timed": len(lm), "traffic": None},
+    }
+
+    # ---- per CU width: throughput and bit mismatches (outside the timed region) -------------
+    if not a.no_width_sweep:
+        per_width, mism = {}, 0
+        ref_snap = None
+        for width in (256, 128, 64, 32):
+            p = H.pctx_of_width(ctx, width)
+            v = vte.vte_vstream_create(ctx, vte.VTE_CLASS_LATENCY)
+            vte.vte_vstream_pin(v, p)
+            ch.set_tokens(tok0)
+            n = max(8, a.steps // 8)
+            run(4, v)
+            ch.set_tokens(tok0)
+            t = time.perf_counter()
+            run(n, v)
+            e = time.perf_counter() - t
+            snap = ch.snapshot()
+            snap["tok"] = ch.tok.cpu().numpy().copy()
+            if ref_snap is None:
+                ref_snap = snap
+            else:
+                for k in ("n", "qkv", "o", "act", "d"):
+                    mism += H.mismatched_bits(ref_snap[k], snap[k])[1]
+                mism += H.mismatched_bits(ref_snap["tok"].astype(np.uint32), snap["tok"].astype(np.uint32))[1]
+            gbs = step_bytes * n / e / 1e9
+            per_width[str(width)] = {"GB/s": round(gbs, 1), "pct_peak": round(100 * gbs / HBM_PEAK_GBS, 2),
+                                     "ms_per_step": round(e / n * 1e3, 4)}
+            vte.vte_vstream_destroy(v)
+        out["per_width"] = per_width
+        out["bit_mismatches_across_widths"] = int(mism)
+
+    # ---- the oracle timed on the host cores (a baseline for scale only) -----------------------
+    if not a.no_cpu_baseline:
+        import oracle
+        thr = oracle.default_threads()
+        t = time.perf_counter()
+        o = oracle.decode_step(w, tok0, shp, threads=thr)
+        ct = time.perf_counter() - t
+        out["cpu_baseline"] = {"value": round(step_bytes / ct / 1e9, 3), "unit": "GB/s", "cores": thr, "kind": "oracle",
+                               "sample": "1 decode step at batch %d (all seven operators, double precision), %.1f s" % (B, ct)}
+        # first GPU step from the same tokens must pick the oracle's tokens
+        ch.set_tokens(tok0)
+        run(1, vs)
+        out["first_step_tokens_match_oracle"] = bool(np.array_equal(ch.tok.cpu().numpy(), o["next"]))
+    out["gen_seconds"] = round(gen_s, 1)
+    out["final_tokens_checksum"] = int(tokens_end.astype(np.int64).sum())
+    vte.vte_vstream_destroy(vs)
+    ch.close()
+    vte.vte_shutdown(ctx)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

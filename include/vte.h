@@ -96,6 +96,8 @@ typedef struct vte_pool_cfg {
   int mode;            /* VTE_MODE_* */
   int lookahead;       /* PIPELINED: max unfinished ops bound ahead per vstream; 0 = 16 */
   int stats_capacity;  /* ring size of per-op records kept for vte_stats_read; 0 = 65536 */
+  unsigned device_timing_mask; /* bit k set: launches of kernel VTE_K_k are bracketed by timing events
+                                  on their own stream and vte_op_record.gpu_seconds is filled */
 } vte_pool_cfg;
 
 /* Fills *cfg with the defaults (HIP, device CU count, leaf 32, remainders, STRICT). */
@@ -168,6 +170,13 @@ enum { VTE_EPI_NONE = 0, VTE_EPI_SILU_MUL = 1 };
  * Y is [B,N/2] = bf16( silu(g_fp32) * u_fp32 ).  (Sec. 1 "GEMV"; Sec. 2.3.) */
 int vte_desc_gemv(vte_ctx* ctx, const void* W, const void* X, void* Y, int B, int N, int K,
                   int epilogue, vte_desc** out);
+
+/* The same GEMV reading X rows ldx elements apart and writing Y rows ldy
+ * elements apart (ldx >= K, ldx % 8 == 0, ldy >= outputs per row): lets a launch
+ * consume a column slice of a wider activation tensor in place.  The reduction
+ * tree is that of vte_desc_gemv. */
+int vte_desc_gemv_strided(vte_ctx* ctx, const void* W, const void* X, int ldx, void* Y, int ldy,
+                          int B, int N, int K, int epilogue, vte_desc** out);
 
 /* logits[b,v] = sum_k W[v,k] H[b,k] in fp32 (never rounded to bf16);
  * tok[b] = lowest v attaining the maximum (NaN never wins; all-NaN -> 0).
@@ -368,6 +377,7 @@ typedef struct vte_op_record {
   double t_ready;    /* predecessors satisfied (STRICT) or bindable (PIPELINED) */
   double t_bound;    /* descriptor submitted to the backend stream */
   double t_done;     /* completion observed by the dispatcher */
+  double gpu_seconds; /* device time of the launch (event pair on its stream), or -1 */
 } vte_op_record;
 typedef struct vte_stats_t {
   uint64_t submitted, completed, leases_opened, leases_reused, lease_conflicts,

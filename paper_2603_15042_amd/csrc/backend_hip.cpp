@@ -24,6 +24,7 @@ class HipBackend : public Backend {
  public:
   ~HipBackend() override {
     for (hipEvent_t e : free_events_) (void)hipEventDestroy(e);
+    for (hipEvent_t e : free_timing_events_) (void)hipEventDestroy(e);
   }
   bool is_fake() const override { return false; }
   int init(int device, int* cu_count) override {
@@ -47,33 +48,64 @@ class HipBackend : public Backend {
   }
   void destroy_stream(void* stream) override { (void)hipStreamDestroy(static_cast<hipStream_t>(stream)); }
 
-  int submit(const vte_desc* d, void* stream, int, vte_token, void** completion) override {
-    hipEvent_t ev;
-    if (free_events_.empty()) {
-      VTE_HIP(hipEventCreateWithFlags(&ev, hipEventDisableTiming));
-    } else {
-      ev = free_events_.back();
-      free_events_.pop_back();
-    }
-    int rc = launch(d, static_cast<hipStream_t>(stream));
-    if (rc != VTE_OK) { free_events_.push_back(ev); return rc; }
-    hipError_t e = hipEventRecord(ev, static_cast<hipStream_t>(stream));
-    if (e != hipSuccess) {
-      free_events_.push_back(ev);
-      set_error(std::string("hipEventRecord: ") + hipGetErrorString(e), (int)e);
-      return VTE_EHIP;
-    }
-    *completion = ev;
+  // A completion is an event recorded behind the launch; a timed one also owns an
+  // event recorded in front of it, both with timing enabled.
+  struct Completion {
+    hipEvent_t done = nullptr;
+    hipEvent_t start = nullptr;  // timed launches only
+  };
+  int get_event(bool timing, hipEvent_t* ev) {
+    std::vector<hipEvent_t>& pool = timing ? free_timing_events_ : free_events_;
+    if (!pool.empty()) { *ev = pool.back(); pool.pop_back(); return VTE_OK; }
+    VTE_HIP(hipEventCreateWithFlags(ev, timing ? hipEventDefault : hipEventDisableTiming));
     return VTE_OK;
   }
+  void put_event(bool timing, hipEvent_t ev) { (timing ? free_timing_events_ : free_events_).push_back(ev); }
+
+  int submit(const vte_desc* d, void* stream, int, vte_token, bool timed, void** completion) override {
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    Completion* c = new Completion;
+    int rc = get_event(timed, &c->done);
+    if (rc == VTE_OK && timed) rc = get_event(true, &c->start);
+    auto fail = [&](int code) {
+      if (c->done) put_event(timed, c->done);
+      if (c->start) put_event(true, c->start);
+      delete c;
+      return code;
+    };
+    if (rc != VTE_OK) return fail(rc);
+    if (timed) {
+      hipError_t e = hipEventRecord(c->start, s);
+      if (e != hipSuccess) { set_error(std::string("hipEventRecord: ") + hipGetErrorString(e), (int)e); return fail(VTE_EHIP); }
+    }
+    rc = launch(d, s);
+    if (rc != VTE_OK) return fail(rc);
+    hipError_t e = hipEventRecord(c->done, s);
+    if (e != hipSuccess) { set_error(std::string("hipEventRecord: ") + hipGetErrorString(e), (int)e); return fail(VTE_EHIP); }
+    *completion = c;
+    return VTE_OK;
+  }
+  double elapsed(void* completion) override {
+    Completion* c = static_cast<Completion*>(completion);
+    if (!c->start) return -1.0;
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, c->start, c->done) != hipSuccess) return -1.0;
+    return static_cast<double>(ms) * 1e-3;
+  }
   int wait_on(void* stream, void* completion, int) override {
-    VTE_HIP(hipStreamWaitEvent(static_cast<hipStream_t>(stream), static_cast<hipEvent_t>(completion), 0));
+    VTE_HIP(hipStreamWaitEvent(static_cast<hipStream_t>(stream), static_cast<Completion*>(completion)->done, 0));
     return VTE_OK;
   }
   bool is_done(void* completion) override {
-    return hipEventQuery(static_cast<hipEvent_t>(completion)) != hipErrorNotReady;
+    return hipEventQuery(static_cast<Completion*>(completion)->done) != hipErrorNotReady;
   }
-  void release(void* completion) override { free_events_.push_back(static_cast<hipEvent_t>(completion)); }
+  void release(void* completion) override {
+    Completion* c = static_cast<Completion*>(completion);
+    const bool timed = c->start != nullptr;
+    put_event(timed, c->done);
+    if (c->start) put_event(true, c->start);
+    delete c;
+  }
   int sync_stream(void* stream) override { VTE_HIP(hipStreamSynchronize(static_cast<hipStream_t>(stream))); return VTE_OK; }
 
   int time_launches(const vte_desc* d, void* stream, int warmup, int reps, double* sec) override {
@@ -121,6 +153,7 @@ class HipBackend : public Backend {
   int device_ = 0;
   uint32_t max_lds_ = 65536;
   std::vector<hipEvent_t> free_events_;
+  std::vector<hipEvent_t> free_timing_events_;
 };
 
 }  // namespace

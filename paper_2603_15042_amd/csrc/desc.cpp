@@ -148,6 +148,7 @@ struct GemvBuild {
   const void *W, *X; void* Y; float* logits; int32_t* tok; void* ws; void* partials;
   int B, N, K, epilogue, S;
   const vte_gemv_plan* plan;
+  int ldx = 0, ldy = 0;  // 0 = dense
 };
 
 int build_gemv(vte_ctx* ctx, const GemvBuild& g, vte_desc** out) {
@@ -183,8 +184,11 @@ int build_gemv(vte_ctx* ctx, const GemvBuild& g, vte_desc** out) {
   a.ws = static_cast<uint32_t*>(g.ws);
   a.partials = static_cast<float*>(g.partials);
   a.B = g.B; a.N = g.N; a.K = g.K; a.n_out = n_out;
+  a.ldx = g.ldx > 0 ? g.ldx : g.K;
+  a.ldy = g.ldy > 0 ? g.ldy : n_out;
+  if (a.ldx < g.K || a.ldx % 8 != 0 || a.ldy < n_out) { set_error("gemv: need ldx >= K, ldx % 8 == 0, ldy >= outputs per row"); return VTE_EINVAL; }
   a.groups = p.groups; a.kc = p.kc; a.S = g.S; a.k_per_split = g.K / g.S;
-  const uint64_t shape = fnv1a(&a.B, sizeof(int) * 8);
+  const uint64_t shape = fnv1a(&a.B, sizeof(int) * 10);
   uint64_t bytes = 2ull * g.N * g.K + 2ull * g.B * g.K + (lm ? 4ull * g.B : 2ull * g.B * n_out);
   if (lm && g.logits) bytes += 4ull * g.B * g.N;
   const uint64_t flops = 2ull * g.B * g.N * g.K;
@@ -241,6 +245,15 @@ int vte_desc_gemv(vte_ctx* ctx, const void* W, const void* X, void* Y, int B, in
                   vte_desc** out) {
   GemvBuild g{VTE_K_GEMV, epilogue == VTE_EPI_SILU_MUL ? 1 : 0, W, X, Y, nullptr, nullptr, nullptr, nullptr,
               B, N, K, epilogue, 1, nullptr};
+  return build_gemv(ctx, g, out);
+}
+
+int vte_desc_gemv_strided(vte_ctx* ctx, const void* W, const void* X, int ldx, void* Y, int ldy, int B, int N,
+                          int K, int epilogue, vte_desc** out) {
+  GemvBuild g{VTE_K_GEMV, epilogue == VTE_EPI_SILU_MUL ? 1 : 0, W, X, Y, nullptr, nullptr, nullptr, nullptr,
+              B, N, K, epilogue, 1, nullptr};
+  g.ldx = ldx;
+  g.ldy = ldy;
   return build_gemv(ctx, g, out);
 }
 

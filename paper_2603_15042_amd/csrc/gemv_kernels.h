@@ -36,7 +36,7 @@ __device__ __forceinline__ void stage_x(uint16_t* xs, const GemvArgs& a, int k0,
   for (int i = threadIdx.x; i < total; i += blockDim.x) {
     const int b = i / chunks_per_row, c = i - b * chunks_per_row;
     u32x4 v = u32x4{0u, 0u, 0u, 0u};
-    if (b < a.B && c * 8 < klen) v = ld16(a.X + static_cast<size_t>(b) * a.K + k0 + c * 8);
+    if (b < a.B && c * 8 < klen) v = ld16(a.X + static_cast<size_t>(b) * a.ldx + k0 + c * 8);
     *reinterpret_cast<u32x4*>(xs + b * a.kc + c * 8) = v;
   }
 }
@@ -72,12 +72,12 @@ __global__ __launch_bounds__(WAVES * 64, gemv_occupancy(BT, RW)) void gemv_kerne
   auto finish = [&](int out0, float v) {
     if constexpr (EPI == EPI_NONE) {
       const int n = out0 + my_r;
-      if (my_live && n < a.n_out) a.Y[static_cast<size_t>(my_b) * a.n_out + n] = (uint16_t)f32_to_bf16(v);
+      if (my_live && n < a.n_out) a.Y[static_cast<size_t>(my_b) * a.ldy + n] = (uint16_t)f32_to_bf16(v);
     } else if constexpr (EPI == EPI_SILU) {
       const float u = __shfl(v, lane + R * BT, 64);  // the up row of the same output
       const int n = out0 + my_r;
       if (my_live && my_r < R && n < a.n_out)
-        a.Y[static_cast<size_t>(my_b) * a.n_out + n] = (uint16_t)f32_to_bf16(silu_f32(v) * u);
+        a.Y[static_cast<size_t>(my_b) * a.ldy + n] = (uint16_t)f32_to_bf16(silu_f32(v) * u);
     } else {
       const int n = out0 + my_r;
       if (my_live && n < a.N) {

@@ -25,6 +25,7 @@ struct GemvArgs {
   uint32_t* ws;           // LM head: block partials + ticket; split-K: tickets
   float* partials;        // split-K: [S][B][N] fp32
   int B, N, K;
+  int ldx, ldy;           // row strides of X and Y in elements (K and n_out when dense)
   int n_out;              // outputs per batch row (N, or N/2 with SiLU-mul)
   int groups;             // row groups each wave walks through
   int kc;                 // K elements of X staged in LDS at a time

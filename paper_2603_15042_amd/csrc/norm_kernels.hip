@@ -59,7 +59,7 @@ __global__ __launch_bounds__(T) void norm_kernel(const NormArgs a) {
         s += bf16_hi(xv[j][e]);
       }
     }
-    mu = block_sum<T>(s, red) * a.inv_cols;
+    mu = block_sum<T>(s, red) / static_cast<float>(a.cols);  // a true division: exact when the mean is representable
   }
 
   float ss = 0.f;
@@ -74,7 +74,7 @@ __global__ __launch_bounds__(T) void norm_kernel(const NormArgs a) {
     }
   }
   ss = block_sum<T>(ss, red);
-  const float rstd = 1.0f / sqrtf(ss * a.inv_cols + a.eps);
+  const float rstd = 1.0f / sqrtf(ss / static_cast<float>(a.cols) + a.eps);
 
 #pragma unroll
   for (int j = 0; j < kMaxChunks; ++j) {

@@ -115,11 +115,13 @@ void record_op(vte_ctx* c, const Op* op) {
   r.token = op->tok; r.vstream = op->vs; r.klass = op->klass; r.kernel = op->desc->kernel;
   r.pctx = op->pctx; r.width = c->pool.at(op->pctx).width;
   r.t_submit = op->t_submit; r.t_ready = op->t_ready; r.t_bound = op->t_bound; r.t_done = op->t_done;
+  r.gpu_seconds = op->gpu_seconds;
 }
 
 void complete_op(vte_ctx* c, Op* op) {
   op->state = kDone;
   op->t_done = c->now();
+  op->gpu_seconds = c->backend->elapsed(op->completion);
   c->backend->release(op->completion);
   op->completion = nullptr;
   retire_one(c, op->pctx);
@@ -257,7 +259,8 @@ int bind_and_submit(vte_ctx* c, Op* op, int pctx) {
     if (rc != VTE_OK) return rc;
   }
   void* completion = nullptr;
-  rc = c->backend->submit(op->desc, p.stream, pctx, op->tok, &completion);
+  const bool timed = (c->cfg.device_timing_mask >> op->desc->kernel) & 1u;
+  rc = c->backend->submit(op->desc, p.stream, pctx, op->tok, timed, &completion);
   if (rc != VTE_OK) { ++c->stats.submit_failures; return rc; }  // op stays ready
   admit(c, pctx, op->vs);
   op->pctx = pctx;

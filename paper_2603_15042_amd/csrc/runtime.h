@@ -51,7 +51,9 @@ class Backend {
   virtual int create_stream(const uint32_t* mask, int words, void** stream) = 0;
   virtual void destroy_stream(void* stream) = 0;
   // Submit the descriptor unchanged on `stream`, then record a completion.
-  virtual int submit(const vte_desc* d, void* stream, int pctx, vte_token tok, void** completion) = 0;
+  // `timed`: bracket the launch with timing events; elapsed() then gives its device time.
+  virtual int submit(const vte_desc* d, void* stream, int pctx, vte_token tok, bool timed, void** completion) = 0;
+  virtual double elapsed(void* completion) = 0;  // seconds, -1 if the launch was not timed
   // Make later work on `stream` wait (on the device) for `completion`.
   virtual int wait_on(void* stream, void* completion, int completion_pctx) = 0;
   virtual bool is_done(void* completion) = 0;
@@ -78,7 +80,7 @@ struct Op {
   int pctx = -1;
   void* completion = nullptr;
   bool ready_marked = false;
-  double t_submit = 0, t_ready = 0, t_bound = 0, t_done = 0;
+  double t_submit = 0, t_ready = 0, t_bound = 0, t_done = 0, gpu_seconds = -1;
 };
 
 }  // namespace vte

@@ -1,0 +1,161 @@
+"""Harness around the C ABI: device buffers (torch, plumbing only), the decode
+chain as a list of immutable descriptors, bit-level comparison helpers.
+
+Nothing here computes any part of the method: tensors are moved, descriptors are
+built and submitted, outputs are compared.
+"""
+import numpy as np
+import torch
+
+from . import inputs, vte
+
+WIDTHS = (32, 64, 128, 256)
+
+
+def to_dev(bits_or_array):
+    """numpy uint16 (bf16 bits) / int32 / float32 -> torch tensor on cuda:0 (same bits)."""
+    a = np.ascontiguousarray(bits_or_array)
+    if a.dtype == np.uint16:
+        a = a.view(np.int16)
+    return torch.from_numpy(a).cuda()
+
+
+def dev_empty(shape, dtype=torch.int16):
+    return torch.empty(shape, dtype=dtype, device="cuda")
+
+
+def dev_zeros_bytes(nbytes):
+    return torch.zeros((nbytes + 3) // 4, dtype=torch.int32, device="cuda")
+
+
+def to_bits(t):
+    """torch int16 tensor -> numpy uint16 bit patterns."""
+    return t.detach().cpu().numpy().view(np.uint16)
+
+
+def mismatched_bits(a, b):
+    """(elements that differ, bits that differ) between two same-shape raw arrays."""
+    a = np.ascontiguousarray(a)
+    b = np.ascontiguousarray(b)
+    ua = a.view(np.uint16 if a.dtype.itemsize == 2 else np.uint32)
+    ub = b.view(ua.dtype)
+    x = ua ^ ub
+    nbits = int(np.unpackbits(x.view(np.uint8)).sum())
+    return int(np.count_nonzero(x)), nbits
+
+
+def make_ctx(mode=vte.VTE_MODE_PIPELINED, lookahead=32, device=0):
+    cfg = vte.vte_pool_cfg_default()
+    cfg.mode = mode
+    cfg.lookahead = lookahead
+    torch.cuda.init()
+    torch.zeros(1, device="cuda")  # make sure the primary context exists before streams are created
+    return vte.vte_init(device, cfg)
+
+
+def pctx_of_width(ctx, width, index=0):
+    """First pCtx of this width: a tree node if there is one, else a remainder."""
+    try:
+        return vte.vte_pool_find(ctx, vte.VTE_PCTX_NODE, width, index)
+    except vte.VteError:
+        return vte.vte_pool_find(ctx, vte.VTE_PCTX_REMAINDER, width, index)
+
+
+def run_on(ctx, desc, pctx_id):
+    tok = vte.vte_bind_and_launch(ctx, desc, pctx_id)
+    vte.vte_token_wait(ctx, tok)
+
+
+class DecodeChain:
+    """The Llama-shaped single-layer decode chain as seven immutable descriptors:
+    gather, RMSNorm, QKV, O (on the Q slice of QKV), gate/up+SiLU, down, LM head + argmax.
+    splitk=S builds the reshaped variant of every GEMV instead (the negative control)."""
+
+    NAMES = ("gather", "rmsnorm", "qkv", "o", "gateup", "down", "lmhead")
+
+    def __init__(self, ctx, weights_dev, shp, B, eps=1e-6, want_logits=False, splitk=None, rms_active_cus=None,
+                 feedback=False):
+        self.ctx, self.shp, self.B = ctx, shp, B
+        D, Nq, F, V = shp.D, shp.Nqkv, shp.F, shp.V
+        w = self.w = weights_dev
+        self.tok = torch.zeros(B, dtype=torch.int32, device="cuda")
+        self.h0, self.n = dev_empty((B, D)), dev_empty((B, D))
+        self.qkv, self.o = dev_empty((B, Nq)), dev_empty((B, D))
+        self.act, self.d = dev_empty((B, F)), dev_empty((B, D))
+        # feedback: the LM head writes the token buffer the next step's gather reads (free-running decode)
+        self.next = self.tok if feedback else torch.zeros(B, dtype=torch.int32, device="cuda")
+        self.logits = torch.zeros((B, V), dtype=torch.float32, device="cuda") if want_logits else None
+        self.ws = dev_zeros_bytes(vte.vte_lmhead_workspace_bytes(B, V, D))
+        self.extra = []
+        d = self.desc = {}
+        d["gather"] = vte.vte_desc_gather(ctx, w["E"], self.tok, self.h0, B, V, D)
+        if rms_active_cus is None:
+            d["rmsnorm"] = vte.vte_desc_rmsnorm(ctx, self.h0, w["gamma"], self.n, B, D, eps)
+        else:
+            d["rmsnorm"] = vte.vte_desc_rmsnorm_reshaped(ctx, self.h0, w["gamma"], self.n, B, D, eps, rms_active_cus)
+        if splitk is None:
+            d["qkv"] = vte.vte_desc_gemv(ctx, w["Wqkv"], self.n, self.qkv, B, Nq, D)
+            # the O projection consumes the Q slice (first D columns) of qkv in place
+            d["o"] = vte.vte_desc_gemv_strided(ctx, w["Wo"], self.qkv, Nq, self.o, D, B, D, D)
+            d["gateup"] = vte.vte_desc_gemv(ctx, w["Wgu"], self.o, self.act, B, 2 * F, D, vte.VTE_EPI_SILU_MUL)
+            d["down"] = vte.vte_desc_gemv(ctx, w["Wd"], self.act, self.d, B, D, F)
+            d["lmhead"] = vte.vte_desc_lmhead_argmax(ctx, w["Wlm"], self.d, self.next, self.logits, self.ws, B, V, D)
+        else:
+            S = splitk
+            self.q = dev_empty((B, D))
+
+            def ws(n):
+                t = dev_zeros_bytes(vte.vte_splitk_workspace_bytes(B, n, S))
+                self.extra.append(t)
+                return t
+            d["qkv"] = vte.vte_desc_gemv_splitk(ctx, w["Wqkv"], self.n, self.qkv, ws(Nq), B, Nq, D, 0, S)
+            # split-K has no strided form: Q is the first D rows of Wqkv applied again, into its own buffer
+            d["q"] = vte.vte_desc_gemv_splitk(ctx, w["Wqkv"], self.n, self.q, ws(D), B, D, D, 0, S)
+            d["o"] = vte.vte_desc_gemv_splitk(ctx, w["Wo"], self.q, self.o, ws(D), B, D, D, 0, S)
+            d["gateup"] = vte.vte_desc_gemv_splitk(ctx, w["Wgu"], self.o, self.act, ws(2 * F), B, 2 * F, D,
+                                                   vte.VTE_EPI_SILU_MUL, S)
+            d["down"] = vte.vte_desc_gemv_splitk(ctx, w["Wd"], self.act, self.d, ws(D), B, D, F, 0, S)
+            d["lmhead"] = vte.vte_desc_lmhead_argmax_splitk(ctx, w["Wlm"], self.d, self.next, self.logits, self.ws,
+                                                            ws(V), B, V, D, S)
+        self.order = [k for k in ("gather", "rmsnorm", "qkv", "q", "o", "gateup", "down", "lmhead") if k in d]
+        self.bytes_per_step = sum(vte.vte_desc_info(d[k]).bytes for k in self.order if k != "q")
+
+    def set_tokens(self, toks):
+        self.tok.copy_(torch.from_numpy(np.ascontiguousarray(toks, dtype=np.int32)))
+        torch.cuda.synchronize()
+
+    def submit_step(self, vs):
+        """Submits one step (7 launches) to a vstream; returns the last token."""
+        last = 0
+        for k in self.order:
+            last = vte.vte_submit(vs, self.desc[k])
+        return last
+
+    def run_step_on(self, pctx_ids):
+        """One step with every launch bound explicitly: pctx_ids is an id or one id per launch."""
+        if isinstance(pctx_ids, int):
+            pctx_ids = [pctx_ids] * len(self.order)
+        for k, p in zip(self.order, pctx_ids):
+            run_on(self.ctx, self.desc[k], p)
+
+    def advance(self):
+        """tok <- next (device copy on torch's stream, ordered by the caller's syncs)."""
+        self.tok.copy_(self.next)
+        torch.cuda.synchronize()
+
+    def snapshot(self):
+        torch.cuda.synchronize()
+        out = {k: to_bits(getattr(self, k)) for k in ("h0", "n", "qkv", "o", "act", "d")}
+        out["next"] = self.next.cpu().numpy().copy()
+        if self.logits is not None:
+            out["logits"] = self.logits.cpu().numpy().copy()
+        return out
+
+    def close(self):
+        for dd in self.desc.values():
+            vte.vte_desc_destroy(dd)
+        self.desc = {}
+
+
+def upload_weights(weights_np):
+    return {k: to_dev(v) for k, v in weights_np.items()}

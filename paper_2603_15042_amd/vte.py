@@ -32,7 +32,7 @@ class VteError(RuntimeError):
 
 class vte_pool_cfg(C.Structure):
     _fields_ = [(n, C.c_int) for n in ("backend", "total_cus", "leaf_cus", "layout", "with_remainders", "mode",
-                                        "lookahead", "stats_capacity")]
+                                        "lookahead", "stats_capacity")] + [("device_timing_mask", C.c_uint)]
 
 
 class vte_pctx_info(C.Structure):
@@ -83,7 +83,7 @@ class vte_policy_vtbl(C.Structure):
 class vte_op_record(C.Structure):
     _fields_ = [("token", C.c_uint64), ("vstream", C.c_int), ("klass", C.c_int), ("kernel", C.c_int),
                 ("pctx", C.c_int), ("width", C.c_int), ("t_submit", C.c_double), ("t_ready", C.c_double),
-                ("t_bound", C.c_double), ("t_done", C.c_double)]
+                ("t_bound", C.c_double), ("t_done", C.c_double), ("gpu_seconds", C.c_double)]
 
 
 class vte_stats_t(C.Structure):
@@ -101,7 +101,7 @@ EXPORTS = [
     "vte_last_error", "vte_last_hip_error", "vte_pool_cfg_default", "vte_init", "vte_shutdown", "vte_pool_count",
     "vte_pool_info", "vte_pool_find", "vte_pool_conflict", "vte_pctx_native_stream", "vte_desc_rmsnorm",
     "vte_desc_layernorm", "vte_desc_gemv", "vte_lmhead_workspace_bytes", "vte_desc_lmhead_argmax",
-    "vte_gemv_default_plan", "vte_desc_gemv_planned", "vte_desc_lmhead_argmax_planned", "vte_desc_gather",
+    "vte_desc_gemv_strided", "vte_gemv_default_plan", "vte_desc_gemv_planned", "vte_desc_lmhead_argmax_planned", "vte_desc_gather",
     "vte_desc_gemm", "vte_splitk_workspace_bytes", "vte_desc_gemv_splitk", "vte_desc_lmhead_argmax_splitk",
     "vte_desc_rmsnorm_reshaped", "vte_desc_info", "vte_desc_args", "vte_desc_destroy", "vte_bind_and_launch",
     "vte_vstream_create", "vte_vstream_destroy", "vte_vstream_id", "vte_vstream_pin", "vte_submit",
@@ -228,6 +228,11 @@ def vte_gemv_default_plan(B, N, K, epilogue=VTE_EPI_NONE, S=1):
 
 def vte_desc_gemv(ctx, W, X, Y, B, N, K, epilogue=VTE_EPI_NONE):
     return _desc_call(load().vte_desc_gemv, ctx, _ptr(W), _ptr(X), _ptr(Y), int(B), int(N), int(K), int(epilogue))
+
+
+def vte_desc_gemv_strided(ctx, W, X, ldx, Y, ldy, B, N, K, epilogue=VTE_EPI_NONE):
+    return _desc_call(load().vte_desc_gemv_strided, ctx, _ptr(W), _ptr(X), int(ldx), _ptr(Y), int(ldy), int(B), int(N),
+                      int(K), int(epilogue))
 
 
 def vte_desc_gemv_planned(ctx, W, X, Y, B, N, K, epilogue, plan):

@@ -1,0 +1,398 @@
+"""GPU parity: every kernel through the C ABI against the CPU oracle, and the
+invariant itself (bitwise equality across CU widths).  Needs an MI355X."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+import oracle
+from paper_2603_15042_amd import inputs, vte
+from gpu_common import bf16_close, f64
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def H():
+    from paper_2603_15042_amd import harness
+    return harness
+
+
+@pytest.fixture(scope="module")
+def ctx(H):
+    c = H.make_ctx(vte.VTE_MODE_STRICT)
+    yield c
+    vte.vte_shutdown(c)
+
+
+def all_pctx(ctx):
+    return list(range(vte.vte_pool_count(ctx)))
+
+
+def widths_of(ctx):
+    return {i: vte.vte_pool_info(ctx, i).width for i in all_pctx(ctx)}
+
+
+def run_everywhere(H, ctx, desc, out_tensor, pctxs=None):
+    """Runs desc on each pCtx, returns {pctx: output bits}; output is poisoned between runs."""
+    res = {}
+    for p in (pctxs or all_pctx(ctx)):
+        out_tensor.fill_(0x7FC1 if out_tensor.dtype == torch.int16 else -1)
+        torch.cuda.synchronize()
+        H.run_on(ctx, desc, p)
+        torch.cuda.synchronize()
+        res[p] = out_tensor.cpu().numpy().copy()
+    return res
+
+
+def assert_all_equal(res):
+    vals = list(res.values())
+    for v in vals[1:]:
+        assert np.array_equal(vals[0].view(np.uint8), v.view(np.uint8))
+    return vals[0]
+
+
+# ---------- pool on the device --------------------------------------------------------------
+def test_pool_is_precreated_with_every_width(ctx):
+    w = sorted(set(widths_of(ctx).values()))
+    assert w == [32, 64, 128, 192, 224, 256]
+    assert vte.vte_pool_count(ctx) == 27
+    assert all(vte.vte_pctx_native_stream(ctx, i) for i in all_pctx(ctx))
+
+
+# ---------- RMSNorm / LayerNorm ---------------------------------------------------------------
+@pytest.mark.parametrize("rows,cols", [(8, 1024), (1, 8), (5, 1000), (3, 4096), (2, 16384), (300, 2048)])
+def test_rmsnorm_parity_and_width_invariance(H, ctx, rows, cols):
+    x, g = inputs.rmsnorm_case(seed=0, rows=rows, cols=cols)
+    dx, dg, dy = H.to_dev(x), H.to_dev(g), H.dev_empty((rows, cols))
+    d = vte.vte_desc_rmsnorm(ctx, dx, dg, dy, rows, cols, 1e-6)
+    res = run_everywhere(H, ctx, d, dy)
+    y = assert_all_equal(res).view(np.uint16)           # 0 mismatched bits on all 27 pCtxs
+    bf16_close(y, oracle.rmsnorm(x, g, 1e-6), "rmsnorm %dx%d" % (rows, cols))
+    vte.vte_desc_destroy(d)
+
+
+def test_rmsnorm_closed_forms_on_gpu(H, ctx):
+    n = 1024
+    sign = np.where(np.arange(n) % 3 == 0, -1.0, 1.0).astype(np.float32)
+    x = np.stack([sign, np.zeros(n, np.float32), 4 * sign, np.eye(n, dtype=np.float32)[17] * 3])
+    xb, gb = inputs.bf16_bits(x), inputs.bf16_bits(np.ones(n, np.float32))
+    dx, dg, dy = H.to_dev(xb), H.to_dev(gb), H.dev_empty((4, n))
+    d = vte.vte_desc_rmsnorm(ctx, dx, dg, dy, 4, n, 1e-6)
+    H.run_on(ctx, d, H.pctx_of_width(ctx, 256))
+    y = f64(H.to_bits(dy))
+    assert np.array_equal(y[0], sign)                   # unit-RMS row -> exactly +-1
+    assert np.all(y[1] == 0)                            # zero row stays zero (eps keeps it finite)
+    assert np.array_equal(y[2], sign)                   # scale invariance at bf16 precision
+    assert y[3, 17] == 32.0 and np.count_nonzero(y[3]) == 1   # one-hot -> sqrt(n)
+    vte.vte_desc_destroy(d)
+
+
+@pytest.mark.parametrize("rows,cols", [(8, 1024), (4, 96), (2, 4096), (3, 8192)])
+def test_layernorm_parity_and_width_invariance(H, ctx, rows, cols):
+    x, g, b = inputs.layernorm_case(seed=1, rows=rows, cols=cols)
+    dx, dg, db, dy = H.to_dev(x), H.to_dev(g), H.to_dev(b), H.dev_empty((rows, cols))
+    d = vte.vte_desc_layernorm(ctx, dx, dg, db, dy, rows, cols, 1e-6)
+    res = run_everywhere(H, ctx, d, dy)
+    y = assert_all_equal(res).view(np.uint16)
+    bf16_close(y, oracle.layernorm(x, g, b, 1e-6), "layernorm")
+    # constant row -> beta exactly
+    xc = inputs.bf16_bits(np.full((rows, cols), 2.5, np.float32))
+    dx.copy_(H.to_dev(xc))
+    H.run_on(ctx, d, 0)
+    assert H.mismatched_bits(H.to_bits(dy), np.ascontiguousarray(np.broadcast_to(b, (rows, cols)))) == (0, 0)
+    vte.vte_desc_destroy(d)
+
+
+def test_rmsnorm_reshaped_drifts_on_random_and_not_on_exact_inputs(H, ctx):
+    rows, cols = 64, 4096
+    x, g = inputs.rmsnorm_case(seed=3, rows=rows, cols=cols)
+    dx, dg, dy = H.to_dev(x), H.to_dev(g), H.dev_empty((rows, cols))
+    outs = {}
+    for w in (32, 64, 128, 256):
+        d = vte.vte_desc_rmsnorm_reshaped(ctx, dx, dg, dy, rows, cols, 1e-6, w)
+        H.run_on(ctx, d, H.pctx_of_width(ctx, w))
+        outs[w] = H.to_bits(dy).copy()
+        bf16_close(outs[w], oracle.rmsnorm(x, g, 1e-6), "reshaped rmsnorm")   # still correct, just not bit-stable
+        vte.vte_desc_destroy(d)
+    drift = [H.mismatched_bits(outs[256], outs[w])[1] for w in (32, 64, 128)]
+    assert sum(drift) > 0, "regrouping the sum of squares should move some bits on random data"
+    # exact inputs: every partial sum is exact in fp32, so every grouping gives the same bits
+    xi = inputs.int_bf16(3, inputs.T_X, (rows, cols), -4, 4)
+    dx.copy_(H.to_dev(xi))
+    outs = {}
+    for w in (32, 256):
+        d = vte.vte_desc_rmsnorm_reshaped(ctx, dx, dg, dy, rows, cols, 1e-6, w)
+        H.run_on(ctx, d, H.pctx_of_width(ctx, w))
+        outs[w] = H.to_bits(dy).copy()
+        vte.vte_desc_destroy(d)
+    assert H.mismatched_bits(outs[32], outs[256]) == (0, 0)
+
+
+# ---------- GEMV -------------------------------------------------------------------------------
+@pytest.mark.parametrize("B,N,K", [(1, 4096, 4096), (4, 4096, 4096), (8, 4096, 4096), (3, 37, 520), (5, 1, 8),
+                                   (16, 1000, 1024), (2, 260, 14336), (8, 513, 2048)])
+def test_gemv_parity_and_width_invariance(H, ctx, B, N, K):
+    W, X = inputs.gemv_case(seed=0, B=B, N=N, K=K)
+    dW, dX, dY = H.to_dev(W), H.to_dev(X), H.dev_empty((B, N))
+    d = vte.vte_desc_gemv(ctx, dW, dX, dY, B, N, K)
+    pct = [H.pctx_of_width(ctx, w) for w in (32, 64, 128, 192, 224, 256)] + [H.pctx_of_width(ctx, 32, 7)]
+    res = run_everywhere(H, ctx, d, dY, pct)
+    y = assert_all_equal(res).view(np.uint16)
+    err, ulps = bf16_close(y, oracle.gemv(W, X), "gemv B%d %dx%d" % (B, N, K))
+    assert err <= 2e-2                                   # |y| < 8 here: the literal tolerance holds
+    vte.vte_desc_destroy(d)
+
+
+def test_gemv_identity_permutation_and_exact_inputs(H, ctx):
+    K = 1024
+    X = inputs.normal_bf16(7, inputs.T_XB, (4, K))
+    perm = np.random.default_rng(0).permutation(K)
+    P = np.zeros((K, K), np.float32)
+    P[np.arange(K), perm] = 1.0
+    dW, dX, dY = H.to_dev(inputs.bf16_bits(P)), H.to_dev(X), H.dev_empty((4, K))
+    d = vte.vte_desc_gemv(ctx, dW, dX, dY, 4, K, K)
+    H.run_on(ctx, d, H.pctx_of_width(ctx, 64))
+    assert np.array_equal(H.to_bits(dY), X[:, perm])     # bit-exact: all other products are zero
+    vte.vte_desc_destroy(d)
+    # small integers: every fp32 partial sum is exact -> GPU == oracle bitwise, whatever the tree
+    W = inputs.int_bf16(3, inputs.T_W, (300, 4096), -8, 8)
+    Xi = inputs.int_bf16(3, inputs.T_XB, (8, 4096), -8, 8, -2)
+    dW, dX, dY = H.to_dev(W), H.to_dev(Xi), H.dev_empty((8, 300))
+    d = vte.vte_desc_gemv(ctx, dW, dX, dY, 8, 300, 4096)
+    H.run_on(ctx, d, H.pctx_of_width(ctx, 128))
+    assert np.array_equal(H.to_bits(dY), oracle.f64_to_bf16(oracle.gemv(W, Xi)))
+    vte.vte_desc_destroy(d)
+
+
+@pytest.mark.parametrize("B", [1, 8])
+def test_gemv_splitk_reshaping_drifts_and_fixed_does_not(H, ctx, B):
+    N = K = 4096
+    W, X = inputs.gemv_case(seed=0, B=B, N=N, K=K)
+    dW, dX, dY = H.to_dev(W), H.to_dev(X), H.dev_empty((B, N))
+    fixed = vte.vte_desc_gemv(ctx, dW, dX, dY, B, N, K)
+    H.run_on(ctx, fixed, H.pctx_of_width(ctx, 256))
+    y_fixed = H.to_bits(dY).copy()
+    ref = oracle.gemv(W, X)
+    drift = {}
+    for w in (32, 64, 128, 256):
+        S = w // 32
+        ws = H.dev_zeros_bytes(vte.vte_splitk_workspace_bytes(B, N, S))
+        d = vte.vte_desc_gemv_splitk(ctx, dW, dX, dY, ws, B, N, K, 0, S)
+        for rep in range(2):                             # second launch checks the tickets were reset
+            dY.fill_(0)
+            H.run_on(ctx, d, H.pctx_of_width(ctx, w))
+            y = H.to_bits(dY).copy()
+            bf16_close(y, ref, "split-K S=%d" % S)
+            if rep == 0:
+                first = y
+            assert np.array_equal(first, y)
+        drift[w] = H.mismatched_bits(y_fixed, y)
+        vte.vte_desc_destroy(d)
+    assert drift[32] == (0, 0)                           # S = 1 is the fixed structure
+    print("split-K drift of bf16 outputs (elements, bits) vs fixed, B=%d:" % B, drift)
+    # bf16 rounding hides most fp32-level regrouping (a flip needs the sum to sit within ~1e-7 of
+    # a rounding boundary), so the unrounded fp32 sums are compared as well: same W and X through
+    # the LM-head form of the kernel, which stores its fp32 accumulators
+    tok = torch.zeros(B, dtype=torch.int32, device="cuda")
+    lg = torch.zeros((B, N), dtype=torch.float32, device="cuda")
+    ws = H.dev_zeros_bytes(vte.vte_lmhead_workspace_bytes(B, N, K))
+    d = vte.vte_desc_lmhead_argmax(ctx, dW, dX, tok, lg, ws, B, N, K)
+    H.run_on(ctx, d, H.pctx_of_width(ctx, 256))
+    lg_fixed, tok_fixed = lg.cpu().numpy().copy(), tok.cpu().numpy().copy()
+    vte.vte_desc_destroy(d)
+    assert np.abs(lg_fixed - ref).max() < 1e-4
+    drift32 = {}
+    for w in (32, 64, 128, 256):
+        S = w // 32
+        part = H.dev_zeros_bytes(vte.vte_splitk_workspace_bytes(B, N, S))
+        d = vte.vte_desc_lmhead_argmax_splitk(ctx, dW, dX, tok, lg, ws, part, B, N, K, S)
+        H.run_on(ctx, d, H.pctx_of_width(ctx, w))
+        drift32[w] = H.mismatched_bits(lg_fixed, lg.cpu().numpy())
+        assert np.abs(lg.cpu().numpy() - ref).max() < 1e-4
+        vte.vte_desc_destroy(d)
+    print("split-K drift of fp32 sums (elements, bits) vs fixed, B=%d:" % B, drift32)
+    assert drift32[32] == (0, 0)
+    assert all(drift32[w][1] > 0 for w in (64, 128, 256))   # regrouping moves bits on random data
+    # negative control: exact inputs -> no drift for any S
+    Wi = inputs.int_bf16(5, inputs.T_W, (N, K), -8, 8)
+    Xi = inputs.int_bf16(5, inputs.T_XB, (B, K), -8, 8, -2)
+    dW.copy_(H.to_dev(Wi))
+    dX.copy_(H.to_dev(Xi))
+    H.run_on(ctx, fixed, H.pctx_of_width(ctx, 256))
+    y_fixed = H.to_bits(dY).copy()
+    for S in (2, 8):
+        ws = H.dev_zeros_bytes(vte.vte_splitk_workspace_bytes(B, N, S))
+        d = vte.vte_desc_gemv_splitk(ctx, dW, dX, dY, ws, B, N, K, 0, S)
+        H.run_on(ctx, d, H.pctx_of_width(ctx, 32 * S))
+        assert H.mismatched_bits(y_fixed, H.to_bits(dY)) == (0, 0)
+        vte.vte_desc_destroy(d)
+    vte.vte_desc_destroy(fixed)
+
+
+@pytest.mark.parametrize("B,F,K", [(2, 50, 256), (8, 1000, 1024), (4, 14336, 4096)])
+def test_gate_up_silu_epilogue(H, ctx, B, F, K):
+    W = inputs.normal_bf16(4, inputs.T_WGU, (2 * F, K), 0.0, 2.0 * K ** -0.5)
+    X = inputs.normal_bf16(4, inputs.T_XB, (B, K))
+    dW, dX, dY = H.to_dev(W), H.to_dev(X), H.dev_empty((B, F))
+    d = vte.vte_desc_gemv(ctx, dW, dX, dY, B, 2 * F, K, vte.VTE_EPI_SILU_MUL)
+    res = run_everywhere(H, ctx, d, dY, [H.pctx_of_width(ctx, w) for w in (32, 128, 256)])
+    y = assert_all_equal(res).view(np.uint16)
+    bf16_close(y, oracle.gemv_silu_mul(W, X), "gate/up")
+    vte.vte_desc_destroy(d)
+
+
+def test_strided_gemv_reads_a_column_slice(H, ctx):
+    B, N, K, ld = 4, 96, 512, 768
+    W = inputs.normal_bf16(2, inputs.T_W, (N, K), 0.0, K ** -0.5)
+    Xw = inputs.normal_bf16(2, inputs.T_XB, (B, ld))
+    dW, dX, dY = H.to_dev(W), H.to_dev(Xw), H.dev_empty((B, N))
+    d = vte.vte_desc_gemv_strided(ctx, dW, dX, ld, dY, N, B, N, K)
+    H.run_on(ctx, d, 0)
+    bf16_close(H.to_bits(dY), oracle.gemv(W, np.ascontiguousarray(Xw[:, :K])), "strided")
+    vte.vte_desc_destroy(d)
+
+
+# ---------- LM head + argmax -----------------------------------------------------------------------
+@pytest.mark.parametrize("B,V,K", [(1, 1, 64), (2, 7, 64), (4, 1000, 256), (8, 4097, 1024), (16, 2049, 512)])
+def test_lmhead_logits_and_token(H, ctx, B, V, K):
+    W = inputs.normal_bf16(6, inputs.T_WLM, (V, K), 0.0, 0.02)
+    Hh = inputs.normal_bf16(6, inputs.T_XB, (B, K))
+    plant = [0, V - 1, V // 2, min(V - 1, 63), min(V - 1, 64)]
+    for b in range(min(B, len(plant))):                  # planted maxima at block boundaries
+        W[plant[b]] = oracle.f64_to_bf16(0.25 * f64(Hh[b]))
+    dW, dH = H.to_dev(W), H.to_dev(Hh)
+    tok = torch.full((B,), -7, dtype=torch.int32, device="cuda")
+    logits = torch.zeros((B, V), dtype=torch.float32, device="cuda")
+    ws = H.dev_zeros_bytes(vte.vte_lmhead_workspace_bytes(B, V, K))
+    d = vte.vte_desc_lmhead_argmax(ctx, dW, dH, tok, logits, ws, B, V, K)
+    ref_logits, ref_tok, margin = oracle.lmhead_argmax(W, Hh)
+    got = {}
+    for p in [H.pctx_of_width(ctx, w) for w in (32, 64, 128, 256)]:
+        tok.fill_(-7)
+        H.run_on(ctx, d, p)
+        torch.cuda.synchronize()
+        got[p] = (tok.cpu().numpy().copy(), logits.cpu().numpy().copy())
+    first = next(iter(got.values()))
+    for t, l in got.values():
+        assert np.array_equal(t, first[0]) and np.array_equal(l.view(np.uint32), first[1].view(np.uint32))
+    eps_logit = np.abs(first[1].astype(np.float64) - ref_logits).max()
+    assert eps_logit < 1e-4
+    for b in range(B):
+        assert first[0][b] == ref_tok[b] or margin[b] <= 2 * eps_logit
+    # the token is the argmax of the GPU's own logits with ties to the lowest index
+    assert np.array_equal(first[0], oracle.argmax(first[1].astype(np.float64))[0])
+    vte.vte_desc_destroy(d)
+
+
+def test_lmhead_ties_go_to_lowest_index(H, ctx):
+    B, V, K = 2, 600, 128
+    W = inputs.normal_bf16(8, inputs.T_WLM, (V, K), 0.0, 0.02)
+    Hh = inputs.normal_bf16(8, inputs.T_XB, (B, K))
+    row = oracle.f64_to_bf16(0.5 * f64(Hh[0]))
+    for v in (599, 131, 300):                            # identical rows -> bitwise identical logits
+        W[v] = row
+    dW, dH = H.to_dev(W), H.to_dev(Hh)
+    tok = torch.zeros(B, dtype=torch.int32, device="cuda")
+    ws = H.dev_zeros_bytes(vte.vte_lmhead_workspace_bytes(B, V, K))
+    d = vte.vte_desc_lmhead_argmax(ctx, dW, dH, tok, None, ws, B, V, K)
+    H.run_on(ctx, d, 3)
+    assert tok.cpu().numpy()[0] == 131
+    assert tok.cpu().numpy()[0] == oracle.lmhead_argmax(W, Hh)[1][0]
+    vte.vte_desc_destroy(d)
+
+
+# ---------- gather ------------------------------------------------------------------------------------
+def test_gather(H, ctx):
+    V, K, B = 500, 4096, 16
+    E = inputs.normal_bf16(1, inputs.T_EMB, (V, K))
+    t = np.array([499, 0, 7, 7] + list(range(12)), np.int32)
+    dE, dt, dH = H.to_dev(E), H.to_dev(t), H.dev_empty((B, K))
+    d = vte.vte_desc_gather(ctx, dE, dt, dH, B, V, K)
+    res = run_everywhere(H, ctx, d, dH, [0, 5, H.pctx_of_width(ctx, 256)])
+    assert np.array_equal(assert_all_equal(res).view(np.uint16), oracle.gather(E, t))
+    vte.vte_desc_destroy(d)
+
+
+# ---------- MFMA GEMM ---------------------------------------------------------------------------------
+@pytest.mark.parametrize("M,N,K", [(256, 256, 64), (512, 256, 192), (512, 512, 512), (1024, 768, 1024)])
+def test_gemm_parity_and_width_invariance(H, ctx, M, N, K):
+    A = inputs.normal_bf16(0, inputs.T_GEMM_A, (M, K))
+    Bm = inputs.normal_bf16(0, inputs.T_GEMM_B, (N, K))
+    dA, dB, dC = H.to_dev(A), H.to_dev(Bm), H.dev_empty((M, N))
+    d = vte.vte_desc_gemm(ctx, dA, dB, dC, M, N, K)
+    res = run_everywhere(H, ctx, d, dC, [H.pctx_of_width(ctx, w) for w in (32, 64, 128, 224, 256)])
+    c = assert_all_equal(res).view(np.uint16)
+    ref = oracle.gemm_rows(A, Bm, np.arange(M))
+    err = np.abs(f64(c) - ref)
+    assert np.all(err <= 2.0 ** -8 * np.abs(ref) * (1 + 1e-2) + 1e-2), err.max()
+    vte.vte_desc_destroy(d)
+
+
+# ---------- the decode chain --------------------------------------------------------------------------
+@pytest.fixture(scope="module")
+def small_chain(H, ctx):
+    shp = inputs.DecodeShapes(D=512, Nqkv=768, F=1792, V=4099)
+    w = inputs.decode_weights(11, shp)
+    for k in ("Wqkv", "Wo", "Wgu", "Wd"):                # keep activations O(1) through the short chain
+        w[k] = inputs.normal_bf16(11, 100 + len(k), w[k].shape, 0.0, 1.5 * w[k].shape[1] ** -0.5)
+    return shp, w, H.upload_weights(w)
+
+
+@pytest.mark.parametrize("B", [1, 3, 8, 16])
+def test_chain_teacher_forced_per_operator(H, ctx, small_chain, B):
+    shp, w, wd = small_chain
+    ch = H.DecodeChain(ctx, wd, shp, B, want_logits=True)
+    tok = inputs.tokens(11, inputs.T_TOK0, B, shp.V)
+    p256 = H.pctx_of_width(ctx, 256)
+    near = 0
+    for step in range(6):
+        ch.set_tokens(tok)
+        ch.run_step_on(p256)
+        s = ch.snapshot()
+        o = oracle.decode_step(w, tok, shp, want_logits=True)
+        assert np.array_equal(s["h0"], o["h0"])
+        # each operator is checked on the GPU's own inputs, so errors do not compound
+        bf16_close(s["n"], oracle.rmsnorm(s["h0"], w["gamma"]), "n")
+        bf16_close(s["qkv"], oracle.gemv(w["Wqkv"], s["n"]), "qkv")
+        bf16_close(s["o"], oracle.gemv(w["Wo"], np.ascontiguousarray(s["qkv"][:, :shp.D])), "o")
+        bf16_close(s["act"], oracle.gemv_silu_mul(w["Wgu"], s["o"]), "act")
+        bf16_close(s["d"], oracle.gemv(w["Wd"], s["act"]), "d")
+        lg, t_ref, margin = oracle.lmhead_argmax(w["Wlm"], s["d"])
+        eps_logit = np.abs(s["logits"].astype(np.float64) - lg).max()
+        assert eps_logit < 1e-3
+        for b in range(B):
+            if s["next"][b] != t_ref[b]:
+                assert margin[b] <= 2 * eps_logit
+                near += 1
+        tok = o["next"]                                   # teacher forcing with the oracle's stream
+    assert near <= 1
+    ch.close()
+
+
+def test_chain_bits_do_not_depend_on_allocation(H, ctx, small_chain):
+    shp, w, wd = small_chain
+    B = 8
+    ch = H.DecodeChain(ctx, wd, shp, B, want_logits=True)
+    tok0 = inputs.tokens(3, inputs.T_TOK0, B, shp.V)
+    rng = np.random.default_rng(0)
+    ids = all_pctx(ctx)
+
+    def replay(choice):
+        toks, tok = [], tok0
+        for step in range(8):
+            ch.set_tokens(tok)
+            ch.run_step_on(choice(step))
+            s = ch.snapshot()
+            toks.append((s["next"].copy(), s["logits"].copy(), s["d"].copy()))
+            tok = s["next"]
+        return toks
+
+    base = replay(lambda s: H.pctx_of_width(ctx, 256))
+    for trial in range(4):                                # a different pCtx for every launch
+        other = replay(lambda s: [int(rng.choice(ids)) for _ in ch.order])
+        for (t0, l0, d0), (t1, l1, d1) in zip(base, other):
+            assert np.array_equal(t0, t1)
+            assert np.array_equal(l0.view(np.uint32), l1.view(np.uint32))
+            assert np.array_equal(d0, d1)
+    ch.close()
