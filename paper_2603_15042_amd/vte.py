@@ -121,6 +121,9 @@ def load():
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise ImportError("%s not found: run `python -m paper_2603_15042_amd.build` first" % LIB_PATH)
+        # torch ships its own HIP runtime: it has to be in the process first, so that the
+        # library binds to that copy and both see the same device state
+        import torch  # noqa: F401
         L = C.CDLL(LIB_PATH)
         for name in EXPORTS:
             getattr(L, name).restype = C.c_int
