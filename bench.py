@@ -25,6 +25,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--batch", type=int, default=8)
     ap.add_argument("--mode", choices=("pipelined", "strict"), default="pipelined")
+    ap.add_argument("--no-kernel-timing", action="store_true", help="do not bracket the LM head with device events")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-width-sweep", action="store_true")
     ap.add_argument("--small", action="store_true", help="reduced shapes (debugging only; not a valid result)")
@@ -50,7 +51,7 @@ def main():
     cfg = vte.vte_pool_cfg_default()
     cfg.mode = vte.VTE_MODE_PIPELINED if a.mode == "pipelined" else vte.VTE_MODE_STRICT
     cfg.lookahead = 64
-    cfg.device_timing_mask = 1 << vte.VTE_K_LMHEAD
+    cfg.device_timing_mask = 0 if a.no_kernel_timing else 1 << vte.VTE_K_LMHEAD
     torch.zeros(1, device="cuda")
     ctx = vte.vte_init(0, cfg)
     wd = H.upload_weights(w)

@@ -163,9 +163,10 @@ int vte_desc_layernorm(vte_ctx* ctx, const void* x, const void* gamma, const voi
 enum { VTE_EPI_NONE = 0, VTE_EPI_SILU_MUL = 1 };
 /* Y[b,n] = bf16( sum_k W[n,k] X[b,k] ).  W: device [N,K] bf16 (each output's K
  * contiguous); X: device [B,K] bf16; Y: device [B,N] bf16.  1 <= B <= 16,
- * K % 8 == 0.  fp32 accumulation in a tree that depends on K only: a K-tile of
- * 256 is 32 lanes x 8 contiguous elements, a lane adds its tiles in ascending
- * order, then one fixed butterfly over lanes.
+ * K % 8 == 0, K <= 32768.  fp32 accumulation in a tree that depends on K only:
+ * a K-tile of 256 is 32 lanes x 8 contiguous elements; a lane adds the products
+ * of its slice in ascending order, a fixed butterfly adds the 64 lanes of a
+ * wave, and the per-slice sums are added in ascending K order.
  * epilogue SILU_MUL: N must be even; rows [0,N/2) are gate, [N/2,N) up;
  * Y is [B,N/2] = bf16( silu(g_fp32) * u_fp32 ).  (Sec. 1 "GEMV"; Sec. 2.3.) */
 int vte_desc_gemv(vte_ctx* ctx, const void* W, const void* X, void* Y, int B, int N, int K,
@@ -178,8 +179,12 @@ int vte_desc_gemv(vte_ctx* ctx, const void* W, const void* X, void* Y, int B, in
 int vte_desc_gemv_strided(vte_ctx* ctx, const void* W, const void* X, int ldx, void* Y, int ldy,
                           int B, int N, int K, int epilogue, vte_desc** out);
 
-/* logits[b,v] = sum_k W[v,k] H[b,k] in fp32 (never rounded to bf16);
- * tok[b] = lowest v attaining the maximum (NaN never wins; all-NaN -> 0).
+/* The greedy token takes two launches: the LM head, then vte_desc_argmax_finish
+ * built from it and submitted right behind it.
+ * LM head: logits[b,v] = sum_k W[v,k] H[b,k] in fp32 (never rounded to bf16),
+ * and per workgroup the best (value, lowest index) candidate of each batch row,
+ * left in the workspace.  Finish: tok[b] = lowest v attaining the maximum over
+ * all candidates (NaN never wins; all-NaN -> 0).
  * W: device [V,K] bf16; H: device [B,K] bf16; tok: device [B] int32;
  * logits_or_null: device [B,V] fp32 or NULL; workspace: device buffer of
  * vte_lmhead_workspace_bytes() bytes, zero-filled by the caller before the
@@ -189,16 +194,25 @@ int vte_lmhead_workspace_bytes(int B, int V, int K, size_t* bytes);
 int vte_desc_lmhead_argmax(vte_ctx* ctx, const void* W, const void* H, int32_t* tok,
                            float* logits_or_null, void* workspace, int B, int V, int K,
                            vte_desc** out);
+/* Second stage: reads the candidates `lmhead` (an LM-head descriptor, fixed or
+ * split-K) leaves in its workspace and writes its tok[].  Comparison of
+ * (value, index) pairs is a total order, so no reduction order is involved. */
+int vte_desc_argmax_finish(vte_ctx* ctx, const vte_desc* lmhead, vte_desc** out);
 
 /* The work decomposition of a GEMV-family descriptor, spelled out.  It is part
  * of the submitted structure C_k: chosen from the shape by vte_gemv_default_plan,
- * or given by the caller, and frozen in the descriptor.  rows_in_flight: weight
- * rows a wave streams at once (2, 4 or 8; rows_in_flight * batch tile <= 64);
- * waves: waves per workgroup (4, 8 or 16); groups: row groups a wave walks
- * through; kc: K elements of X staged in LDS at a time (multiple of 512).
- * The reduction tree of an output does not depend on any of them. */
+ * or given by the caller, and frozen in the descriptor.
+ *   batch_tile  batch rows the kernel is built for (1,2,4,8,16; >= B)
+ *   rows        weight rows a wave streams at once (rows * batch_tile in {16,32,64})
+ *   ksteps      512-element K steps per wave: a workgroup has
+ *               ceil(ceil(K/S/512) / ksteps) waves, one per K-slice
+ *   prefetch    1: the next row group's loads are issued before the current one is reduced
+ *   max_waves   8 or 16: the register budget the kernel was compiled for
+ *   groups      row groups a workgroup walks through
+ * Only combinations the library was built with are accepted.  The reduction tree
+ * of an output depends on K and ksteps alone — never on the device. */
 typedef struct vte_gemv_plan {
-  int rows_in_flight, waves, groups, kc;
+  int batch_tile, rows, ksteps, prefetch, max_waves, groups;
 } vte_gemv_plan;
 int vte_gemv_default_plan(int B, int N, int K, int epilogue, int S, vte_gemv_plan* plan);
 int vte_desc_gemv_planned(vte_ctx* ctx, const void* W, const void* X, void* Y, int B, int N, int K,
@@ -242,7 +256,8 @@ int vte_desc_rmsnorm_reshaped(vte_ctx* ctx, const void* x, const void* gamma, vo
 /* ---- descriptor inspection --------------------------------------------------- */
 enum {
   VTE_K_RMSNORM = 1, VTE_K_LAYERNORM = 2, VTE_K_GEMV = 3, VTE_K_LMHEAD = 4, VTE_K_GATHER = 5,
-  VTE_K_GEMM = 6, VTE_K_GEMV_SPLITK = 7, VTE_K_LMHEAD_SPLITK = 8, VTE_K_RMSNORM_RESHAPED = 9
+  VTE_K_GEMM = 6, VTE_K_GEMV_SPLITK = 7, VTE_K_LMHEAD_SPLITK = 8, VTE_K_RMSNORM_RESHAPED = 9,
+  VTE_K_ARGMAX_FINISH = 10
 };
 typedef struct vte_desc_view {
   int kernel;           /* VTE_K_* */

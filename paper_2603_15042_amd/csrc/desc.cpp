@@ -11,12 +11,13 @@
 
 extern "C" {
 const void* vte_norm_entry(int threads, int layer);
-const void* vte_gemv_entry_b1(int, int, int, int);
-const void* vte_gemv_entry_b2(int, int, int, int);
-const void* vte_gemv_entry_b4(int, int, int, int);
-const void* vte_gemv_entry_b8(int, int, int, int);
-const void* vte_gemv_entry_b16(int, int, int, int);
+const void* vte_gemv_entry_b1(int, int, int, int, int, int);
+const void* vte_gemv_entry_b2(int, int, int, int, int, int);
+const void* vte_gemv_entry_b4(int, int, int, int, int, int);
+const void* vte_gemv_entry_b8(int, int, int, int, int, int);
+const void* vte_gemv_entry_b16(int, int, int, int, int, int);
 const void* vte_gather_entry();
+const void* vte_argmax_finish_entry();
 const void* vte_gemm_entry();
 unsigned vte_gemm_lds_bytes();
 unsigned vte_gemm_threads();
@@ -105,41 +106,56 @@ int build_norm(vte_ctx* ctx, int kernel, bool layer, const void* x, const void* 
                      static_cast<uint32_t>(threads), 0, shape, bytes, static_cast<uint64_t>(rows) * cols * 4, out);
 }
 
-const void* gemv_entry(int bt, int rw, int waves, int epi) {
-  switch (bt) {
-    case 1: return vte_gemv_entry_b1(bt, rw, waves, epi);
-    case 2: return vte_gemv_entry_b2(bt, rw, waves, epi);
-    case 4: return vte_gemv_entry_b4(bt, rw, waves, epi);
-    case 8: return vte_gemv_entry_b8(bt, rw, waves, epi);
-    case 16: return vte_gemv_entry_b16(bt, rw, waves, epi);
+const void* gemv_entry(const vte_gemv_plan& p, int epi) {
+  switch (p.batch_tile) {
+    case 1: return vte_gemv_entry_b1(1, p.rows, p.ksteps, p.prefetch, p.max_waves, epi);
+    case 2: return vte_gemv_entry_b2(2, p.rows, p.ksteps, p.prefetch, p.max_waves, epi);
+    case 4: return vte_gemv_entry_b4(4, p.rows, p.ksteps, p.prefetch, p.max_waves, epi);
+    case 8: return vte_gemv_entry_b8(8, p.rows, p.ksteps, p.prefetch, p.max_waves, epi);
+    case 16: return vte_gemv_entry_b16(16, p.rows, p.ksteps, p.prefetch, p.max_waves, epi);
   }
   return nullptr;
 }
 
 int batch_tile(int B) { int bt = 1; while (bt < B) bt *= 2; return bt; }
 
-// outputs = logical outputs per batch row (N, or N/2 with the SiLU epilogue)
-int plan_gemv(int B, int outputs, int K, int epi, int S, vte_gemv_plan* p) {
-  if (B < 1 || B > 16 || outputs < 1 || K < 8 || S < 1) return VTE_EINVAL;
-  const int bt = batch_tile(B);
-  int rw = 4, waves = 8;
-  auto blocks = [&](int rw_, int waves_) {
-    const int r = (epi == VTE_EPI_SILU_MUL) ? rw_ / 2 : rw_;
-    return (outputs + waves_ * r - 1) / (waves_ * r);
-  };
-  while (blocks(rw, waves) < 512 && waves > 4) waves /= 2;
-  while (blocks(rw, waves) < 512 && rw > 2) rw /= 2;
-  const int kps = K / S;
-  const int kpad = (kps + 511) & ~511;
-  const int kc_max = 32768 / bt;  // 64 KiB of LDS for X
-  const int kc = kpad < kc_max ? kpad : kc_max;
-  int groups = 1;
-  if (kc >= kps) {  // X fits at once: a block may walk several row groups
-    const int r = (epi == VTE_EPI_SILU_MUL) ? rw / 2 : rw;
-    groups = outputs / (waves * r * 1024);
-    groups = groups < 1 ? 1 : (groups > 8 ? 8 : groups);
+int plan_waves(const vte_gemv_plan& p, int k_per_split) {
+  const int nsteps = (k_per_split + 511) / 512;
+  return (nsteps + p.ksteps - 1) / p.ksteps;
+}
+
+// Default decomposition, from the shape alone.  outputs = logical outputs per
+// batch row (N, or N/2 with the SiLU epilogue); kps = K / S.
+int plan_gemv(int B, int outputs, int kps, int epi, vte_gemv_plan* p) {
+  if (B < 1 || B > 16 || outputs < 1 || kps < 8) return VTE_EINVAL;
+  const int nsteps = (kps + 511) / 512;
+  if (nsteps > 64) return VTE_EINVAL;
+  int bt = batch_tile(B);
+  int r, ks, pf = 1, mw = 8;
+  if (nsteps > 16 && bt < 4) bt = 4;  // long rows: the wider tile keeps the per-wave slice in registers
+  if (bt <= 2) {
+    r = 16; ks = 1; mw = nsteps > 8 ? 16 : 8;
+  } else if (bt == 4) {
+    if (nsteps <= 1) { r = 16; ks = 1; }
+    else if (nsteps <= 16) { r = 8; ks = 2; }
+    else if (nsteps <= 32) { r = 4; ks = 4; }
+    else { r = 4; ks = 4; pf = 0; }
+    if ((nsteps + ks - 1) / ks > 8) { r = 4; ks = 2; mw = 16; }
+  } else if (bt == 8) {
+    if (nsteps <= 1) { r = 8; ks = 1; }
+    else if (nsteps <= 16) { r = 8; ks = 2; }
+    else { r = 2; ks = 4; }
+    if ((nsteps + ks - 1) / ks > 8) { r = 4; ks = 2; mw = 16; }
+  } else {
+    if (nsteps <= 1) { r = 4; ks = 1; }
+    else { r = 4; ks = 2; }
+    if ((nsteps + ks - 1) / ks > 8) { r = 2; ks = 2; mw = 16; }
   }
-  p->rows_in_flight = rw; p->waves = waves; p->groups = groups; p->kc = kc;
+  if ((nsteps + ks - 1) / ks > mw) return VTE_EINVAL;
+  const int rout = (epi == VTE_EPI_SILU_MUL) ? r / 2 : r;
+  int groups = outputs / (rout * 2048);
+  groups = groups < 1 ? 1 : (groups > 4 ? 4 : groups);
+  p->batch_tile = bt; p->rows = r; p->ksteps = ks; p->prefetch = pf; p->max_waves = mw; p->groups = groups;
   return VTE_OK;
 }
 
@@ -165,16 +181,15 @@ int build_gemv(vte_ctx* ctx, const GemvBuild& g, vte_desc** out) {
   const int n_out = (g.epilogue == VTE_EPI_SILU_MUL) ? g.N / 2 : g.N;
   vte_gemv_plan p;
   if (g.plan) p = *g.plan;
-  else if (plan_gemv(g.B, n_out, g.K, g.epilogue, g.S, &p) != VTE_OK) { set_error("gemv: no plan"); return VTE_EINVAL; }
-  const int bt = batch_tile(g.B);
+  else if (plan_gemv(g.B, n_out, g.K / g.S, g.epilogue, &p) != VTE_OK) { set_error("gemv: K / S must be at most 32768"); return VTE_EINVAL; }
   const int kps = g.K / g.S;
-  if (p.kc <= 0 || p.kc % 512 != 0 || p.groups < 1 || static_cast<int64_t>(bt) * p.kc * 2 > 160 * 1024 - 1024) {
-    set_error("gemv plan: kc must be a positive multiple of 512 and X must fit in LDS"); return VTE_EINVAL;
+  const int waves = plan_waves(p, kps);
+  if (p.batch_tile < g.B || p.groups < 1 || p.rows < 1 || p.ksteps < 1 || waves < 1 || waves > p.max_waves) {
+    set_error("gemv plan: batch_tile >= B, groups >= 1 and ceil(K/S/512/ksteps) <= max_waves are required"); return VTE_EINVAL;
   }
-  (void)kps;
-  const int r = (g.epi_kernel == 1) ? p.rows_in_flight / 2 : p.rows_in_flight;
-  if (r < 1) { set_error("gemv plan: rows_in_flight too small for this epilogue"); return VTE_EINVAL; }
-  const int per_block = p.waves * r * p.groups;
+  const int rout = (g.epi_kernel == 1) ? p.rows / 2 : p.rows;
+  if (rout < 1) { set_error("gemv plan: the SiLU epilogue needs an even number of rows"); return VTE_EINVAL; }
+  const int per_block = rout * p.groups;
   const uint32_t gx = static_cast<uint32_t>((n_out + per_block - 1) / per_block);
   GemvArgs a{};
   a.W = static_cast<const uint16_t*>(g.W);
@@ -187,23 +202,13 @@ int build_gemv(vte_ctx* ctx, const GemvBuild& g, vte_desc** out) {
   a.ldx = g.ldx > 0 ? g.ldx : g.K;
   a.ldy = g.ldy > 0 ? g.ldy : n_out;
   if (a.ldx < g.K || a.ldx % 8 != 0 || a.ldy < n_out) { set_error("gemv: need ldx >= K, ldx % 8 == 0, ldy >= outputs per row"); return VTE_EINVAL; }
-  a.groups = p.groups; a.kc = p.kc; a.S = g.S; a.k_per_split = g.K / g.S;
-  const uint64_t shape = fnv1a(&a.B, sizeof(int) * 10);
+  a.groups = p.groups; a.S = g.S; a.k_per_split = kps; a.bt = p.batch_tile;
+  const uint64_t shape = fnv1a(&a.B, sizeof(int) * 9);
   uint64_t bytes = 2ull * g.N * g.K + 2ull * g.B * g.K + (lm ? 4ull * g.B : 2ull * g.B * n_out);
   if (lm && g.logits) bytes += 4ull * g.B * g.N;
   const uint64_t flops = 2ull * g.B * g.N * g.K;
-  return finish_desc(ctx, g.kernel, gemv_entry(bt, p.rows_in_flight, p.waves, g.epi_kernel), a, gx,
-                     static_cast<uint32_t>(g.S), static_cast<uint32_t>(p.waves * 64),
-                     static_cast<uint32_t>(bt * p.kc * 2), shape, bytes, flops, out);
-}
-
-// grid.x of the LM head for (B,V,K,S): sizes the workspace
-int lmhead_blocks(int B, int V, int K, int S, const vte_gemv_plan* plan) {
-  vte_gemv_plan p;
-  if (plan) p = *plan;
-  else if (plan_gemv(B, V, K, VTE_EPI_NONE, S, &p) != VTE_OK) return -1;
-  const int per_block = p.waves * p.rows_in_flight * p.groups;
-  return (V + per_block - 1) / per_block;
+  return finish_desc(ctx, g.kernel, gemv_entry(p, g.epi_kernel), a, gx, static_cast<uint32_t>(g.S),
+                     static_cast<uint32_t>(waves * 64), 0, shape, bytes, flops, out);
 }
 
 }  // namespace
@@ -236,8 +241,9 @@ int vte_desc_rmsnorm_reshaped(vte_ctx* ctx, const void* x, const void* gamma, vo
 int vte_gemv_default_plan(int B, int N, int K, int epilogue, int S, vte_gemv_plan* plan) {
   if (!plan) { set_error("null plan"); return VTE_EINVAL; }
   const int n_out = (epilogue == VTE_EPI_SILU_MUL) ? N / 2 : N;
-  int rc = plan_gemv(B, n_out, K, epilogue, S < 1 ? 1 : S, plan);
-  if (rc != VTE_OK) set_error("gemv plan: need 1 <= B <= 16, N >= 1, K >= 8");
+  if (S < 1 || K % S != 0) { set_error("gemv plan: S must divide K"); return VTE_EINVAL; }
+  int rc = plan_gemv(B, n_out, K / S, epilogue, plan);
+  if (rc != VTE_OK) set_error("gemv plan: need 1 <= B <= 16, N >= 1, 8 <= K / S <= 32768");
   return rc;
 }
 
@@ -265,11 +271,11 @@ int vte_desc_gemv_planned(vte_ctx* ctx, const void* W, const void* X, void* Y, i
 }
 
 // split-K workspace: [tickets: one uint32 per possible row block, rounded up][fp32 partials [S][BT][N]]
-static size_t splitk_ticket_bytes(int N) { return ((static_cast<size_t>(N) / 2 + 2) * 4 + 255) & ~static_cast<size_t>(255); }
+static size_t splitk_ticket_bytes(int N) { return ((static_cast<size_t>(N) + 2) * 4 + 255) & ~static_cast<size_t>(255); }
 
 int vte_splitk_workspace_bytes(int B, int N, int S, size_t* bytes) {
   if (!bytes || B < 1 || B > 16 || N < 1 || S < 1) { set_error("splitk workspace: bad argument"); return VTE_EINVAL; }
-  *bytes = splitk_ticket_bytes(N) + static_cast<size_t>(S) * batch_tile(B) * N * 4;
+  *bytes = splitk_ticket_bytes(N) + static_cast<size_t>(S) * 16 * N * 4;  // partials [S][batch tile <= 16][N]
   return VTE_OK;
 }
 
@@ -284,11 +290,11 @@ int vte_desc_gemv_splitk(vte_ctx* ctx, const void* W, const void* X, void* Y, vo
 
 int vte_lmhead_workspace_bytes(int B, int V, int K, size_t* bytes) {
   if (!bytes) { set_error("null bytes"); return VTE_EINVAL; }
-  // sized for the finest plan any S could pick: one block per 8 rows
+  // sized for the finest decomposition there is: one workgroup per output row, batch tile 16
   (void)K;
   if (B < 1 || B > 16 || V < 1) { set_error("lmhead workspace: bad argument"); return VTE_EINVAL; }
-  const size_t blocks = static_cast<size_t>(V + 7) / 8 + 1;
-  *bytes = 4 * (1 + blocks + blocks * batch_tile(B) * 2) + 256;
+  const size_t blocks = static_cast<size_t>(V) + 1;
+  *bytes = 4 * (1 + blocks + blocks * 16 * 2) + 256;
   return VTE_OK;
 }
 
@@ -311,6 +317,25 @@ int vte_desc_lmhead_argmax_splitk(vte_ctx* ctx, const void* W, const void* H, in
   GemvBuild g{VTE_K_LMHEAD_SPLITK, 2, W, H, nullptr, logits_or_null, tok, workspace, partials, B, V, K,
               VTE_EPI_NONE, S, nullptr};
   return build_gemv(ctx, g, out);
+}
+
+int vte_desc_argmax_finish(vte_ctx* ctx, const vte_desc* lmhead, vte_desc** out) {
+  if (!ctx || !lmhead || !out) { set_error("argmax_finish: null argument"); return VTE_EINVAL; }
+  if (lmhead->ctx != ctx || (lmhead->kernel != VTE_K_LMHEAD && lmhead->kernel != VTE_K_LMHEAD_SPLITK)) {
+    set_error("argmax_finish: needs an LM-head descriptor of this context"); return VTE_EINVAL;
+  }
+  GemvArgs g;
+  std::memcpy(&g, lmhead->args, sizeof g);
+  // candidates sit behind the ticket words: [1 + grid.x] uint32, then [grid.x][batch tile][2]
+  ArgmaxFinishArgs a{};
+  a.pairs = g.ws + 1 + lmhead->grid[0];
+  a.tok = g.tok;
+  a.nblocks = static_cast<int>(lmhead->grid[0]);
+  a.bt = g.bt;
+  a.B = g.B;
+  const uint64_t shape = (static_cast<uint64_t>(a.nblocks) << 32) | static_cast<uint32_t>(a.B * 64 + a.bt);
+  return finish_desc(ctx, VTE_K_ARGMAX_FINISH, vte_argmax_finish_entry(), a, static_cast<uint32_t>(a.B), 1, 256, 0,
+                     shape, 8ull * a.nblocks * a.B + 4ull * a.B, 0, out);
 }
 
 int vte_desc_gather(vte_ctx* ctx, const void* E, const int32_t* tok, void* H, int B, int V, int K, vte_desc** out) {

@@ -1,22 +1,10 @@
 // GEMV kernels for a batch tile of 16 rows (see gemv_kernels.h).
 #include "gemv_kernels.h"
 #define VTE_GEMV_CASES(BT) \
-  VTE_GEMV_CASE(16, 2, 4, 0) \
-  VTE_GEMV_CASE(16, 2, 4, 1) \
-  VTE_GEMV_CASE(16, 2, 4, 2) \
-  VTE_GEMV_CASE(16, 2, 8, 0) \
-  VTE_GEMV_CASE(16, 2, 8, 1) \
-  VTE_GEMV_CASE(16, 2, 8, 2) \
-  VTE_GEMV_CASE(16, 2, 16, 0) \
-  VTE_GEMV_CASE(16, 2, 16, 1) \
-  VTE_GEMV_CASE(16, 2, 16, 2) \
-  VTE_GEMV_CASE(16, 4, 4, 0) \
-  VTE_GEMV_CASE(16, 4, 4, 1) \
-  VTE_GEMV_CASE(16, 4, 4, 2) \
-  VTE_GEMV_CASE(16, 4, 8, 0) \
-  VTE_GEMV_CASE(16, 4, 8, 1) \
-  VTE_GEMV_CASE(16, 4, 8, 2) \
-  VTE_GEMV_CASE(16, 4, 16, 0) \
-  VTE_GEMV_CASE(16, 4, 16, 1) \
-  VTE_GEMV_CASE(16, 4, 16, 2)
+  VTE_GEMV_CASE(16, 4, 2, 1, 8) \
+  VTE_GEMV_CASE(16, 4, 1, 1, 8) \
+  VTE_GEMV_CASE(16, 2, 2, 1, 8) \
+  VTE_GEMV_CASE(16, 2, 2, 1, 16) \
+  VTE_GEMV_CASE(16, 4, 1, 1, 16) \
+  VTE_GEMV_CASE(16, 2, 1, 1, 16)
 VTE_GEMV_ENTRY_FOR_BT(16)

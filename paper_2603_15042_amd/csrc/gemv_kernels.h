@@ -3,178 +3,207 @@
 // greedy token: Sec. 7.1 / 7.2 of the paper).
 //
 // Work decomposition (all of it a function of the shape, none of the CU count):
-//   * a wave owns RW weight rows at a time ("row group") and walks `groups` of
-//     them; a block is WAVES waves; grid.x = ceil(rows / (WAVES*R*groups));
 //   * K is cut into tiles of 256 = 32 lanes x 8 contiguous bf16 (one 128-bit
-//     load per lane); a wave covers two tiles per load instruction, lane l
-//     taking elements [512 i + 8 l, 512 i + 8 l + 8) for i = 0, 1, ...;
-//   * X is staged in LDS (kc elements of every batch row at a time) and read
-//     back with conflict-free 128-bit reads, once per batch row per group of
-//     RW weight loads.
+//     load per lane); a wave covers two tiles (512 elements) per load
+//     instruction ("k-step"), lane l taking elements [512 i + 8 l, +8);
+//   * a workgroup is one wave per K-slice of KS consecutive k-steps: wave w owns
+//     k-steps [w KS, (w+1) KS) and keeps its slice of X in registers for the
+//     whole launch, so X costs no LDS or cache traffic in the hot loop;
+//   * the workgroup walks `groups` row groups of R weight rows; the waves of a
+//     workgroup together read each row contiguously, once, with R*KS 128-bit
+//     loads per lane in flight (and the next group's loads behind them).
 // Reduction tree of one output, fixed by K:
-//   1. within a lane: v_dot2 over the 4 bf16 pairs of a load in order, tiles in
-//      ascending order, one fp32 accumulator per (row, batch row);
-//   2. across the 64 lanes: the butterfly of wave_sum();
-//   3. split-K baseline only: S partial sums added in chunk order.
-// Epilogues: bf16 store; silu(gate)*up on the fp32 sums; fp32 logits + argmax.
+//   1. within a lane: v_dot2 over the 4 bf16 pairs of a load in order, the KS
+//      k-steps of the slice in ascending order, one fp32 accumulator;
+//   2. across the 64 lanes of the wave: partner distances 32, 16 (lane-half and
+//      row swaps), then 8, 4, 2, 1 (row rotations); the R*BT sums of a group
+//      are reduced together so that the swaps halve the live values each time,
+//      but every sum goes through exactly this butterfly;
+//   3. across the waves (K-slices) of the workgroup in ascending slice order,
+//      through LDS;
+//   4. split-K baseline only: S chunk sums added in chunk order.
+// Epilogues: bf16 store; silu(gate)*up on the fp32 sums; fp32 logits + per-workgroup
+// argmax candidates (value, lowest index), one pair per batch row.
 #pragma once
 #include "dev_util.h"
 #include "kargs.h"
 #include <limits.h>
 
 enum { EPI_NONE = 0, EPI_SILU = 1, EPI_ARGMAX = 2 };
+constexpr int kMaxWaves = 16;
 
 __device__ __forceinline__ float silu_f32(float g) { return g / (1.0f + expf(-g)); }
 
-// Stage X[b, k0 : k0+klen) for every batch row into LDS rows of `kc` elements;
-// positions up to the next multiple of 512 and batch rows >= B are zero-filled.
-template <int BT>
-__device__ __forceinline__ void stage_x(uint16_t* xs, const GemvArgs& a, int k0, int klen) {
-  const int kpad = (klen + 511) & ~511;
-  const int chunks_per_row = kpad >> 3;
-  const int total = BT * chunks_per_row;
-  for (int i = threadIdx.x; i < total; i += blockDim.x) {
-    const int b = i / chunks_per_row, c = i - b * chunks_per_row;
-    u32x4 v = u32x4{0u, 0u, 0u, 0u};
-    if (b < a.B && c * 8 < klen) v = ld16(a.X + static_cast<size_t>(b) * a.ldx + k0 + c * 8);
-    *reinterpret_cast<u32x4*>(xs + b * a.kc + c * 8) = v;
+template <int CTRL>
+__device__ __forceinline__ float dpp_mov(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
+// Sum over the 16 lanes of a row by rotations 8, 4, 2, 1: every lane of the row
+// ends with the same bits.
+__device__ __forceinline__ float row_allsum(float v) {
+  v += dpp_mov<0x128>(v);
+  v += dpp_mov<0x124>(v);
+  v += dpp_mov<0x122>(v);
+  v += dpp_mov<0x121>(v);
+  return v;
+}
+// a <- {a.lanes[0:32), b.lanes[0:32)}, b <- {a.lanes[32:64), b.lanes[32:64)}; returns a + b:
+// lanes < 32 hold a[l] + a[l+32], lanes >= 32 hold b[l-32] + b[l].
+// (Written as an instruction because the two-result builtin of this compiler
+// returns its first result twice; the s_nop covers the VALU-write -> swap hazard.)
+__device__ __forceinline__ float swap_add32(float a, float b) {
+  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+  return a + b;
+}
+// Same with rows of 16 lanes: odd rows of a swap with even rows of b.
+__device__ __forceinline__ float swap_add16(float a, float b) {
+  asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+  return a + b;
+}
+// Butterfly-sums NV per-lane values over the wave; lane l ends with the total of
+// value value_of_lane<NV>(l) (or nothing if that is -1).
+template <int NV>
+__device__ __forceinline__ float reduce_values(float (&v)[NV], int lane) {
+  static_assert(NV == 16 || NV == 32 || NV == 64, "");
+  float a[NV / 2];
+#pragma unroll
+  for (int j = 0; j < NV / 2; ++j) a[j] = swap_add32(v[j], v[j + NV / 2]);
+  float b[NV / 4];
+#pragma unroll
+  for (int j = 0; j < NV / 4; ++j) b[j] = swap_add16(a[j], a[j + NV / 4]);
+  float mine = 0.f;
+#pragma unroll
+  for (int j = 0; j < NV / 4; ++j) {
+    const float t = row_allsum(b[j]);
+    if ((lane & 15) == j) mine = t;
   }
+  return mine;
+}
+template <int NV>
+__device__ __forceinline__ int value_of_lane(int l) {
+  return ((l & 15) < NV / 4) ? (l & 15) + (NV / 4) * ((l >> 4) & 1) + (NV / 2) * (l >> 5) : -1;
 }
 
-// Waves per SIMD the register allocation aims at (more rows in flight -> fewer waves).
-constexpr int gemv_occupancy(int bt, int rw) { return rw * bt <= 16 ? 4 : (rw * bt <= 32 ? 3 : 2); }
-
-template <int BT, int RW, int WAVES, int EPI>
-__global__ __launch_bounds__(WAVES * 64, gemv_occupancy(BT, RW)) void gemv_kernel(const GemvArgs a) {
-  static_assert(RW * BT <= 64, "one lane per (row, batch row) in the epilogue");
-  static_assert(EPI != EPI_SILU || (RW % 2 == 0), "gate and up rows come in pairs");
-  constexpr int R = (EPI == EPI_SILU) ? RW / 2 : RW;  // outputs per wave per group
-  extern __shared__ __align__(16) uint8_t smem[];
-  uint16_t* xs = reinterpret_cast<uint16_t*>(smem);
-  __shared__ float s_bv[WAVES][BT];
-  __shared__ int s_bi[WAVES][BT];
+template <int BT, int R, int KS, bool PF, int MAXW, int EPI>
+__global__ __launch_bounds__(MAXW * 64) void gemv_kernel(const GemvArgs a) {
+  constexpr int NV = R * BT;  // sums per wave per group
+  static_assert(NV == 16 || NV == 32 || NV == 64, "R * BT must be 16, 32 or 64");
+  static_assert(EPI != EPI_SILU || (R % 2 == 0), "gate and up rows come in pairs");
+  constexpr int ROUT = (EPI == EPI_SILU) ? R / 2 : R;  // outputs per group
+  __shared__ float part[2][MAXW][NV];
+  __shared__ float s_bv[MAXW][BT];
+  __shared__ int s_bi[MAXW][BT];
   __shared__ int s_last;
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // uniform: row bases stay scalar
+  const int nw = blockDim.x >> 6;
   const int split = blockIdx.y;
   const int k_begin = split * a.k_per_split;
   const int k_end = k_begin + a.k_per_split;
-  const bool multi_chunk = a.kc < a.k_per_split;
-  // lane i < RW*BT finishes (row r = i / BT, batch row b = i % BT)
-  const int my_r = lane / BT, my_b = lane % BT;
-  const bool my_live = lane < RW * BT && my_b < a.B;
 
-  float best_v = -INFINITY;
-  int best_i = INT_MAX;
+  // this wave's slice of X, for every batch row, in registers
+  u32x4 xs[KS][BT];
+  int koff[KS];
+#pragma unroll
+  for (int s = 0; s < KS; ++s) {
+    koff[s] = k_begin + (wave * KS + s) * 512 + lane * 8;
+#pragma unroll
+    for (int b = 0; b < BT; ++b)
+      xs[s][b] = (koff[s] < k_end && b < a.B) ? ld16(a.X + static_cast<size_t>(b) * a.ldx + koff[s])
+                                              : u32x4{0u, 0u, 0u, 0u};
+  }
 
-  // ---- finish: lane-distributed fp32 totals -> epilogue ------------------------
-  auto finish = [&](int out0, float v) {
-    if constexpr (EPI == EPI_NONE) {
-      const int n = out0 + my_r;
-      if (my_live && n < a.n_out) a.Y[static_cast<size_t>(my_b) * a.ldy + n] = (uint16_t)f32_to_bf16(v);
-    } else if constexpr (EPI == EPI_SILU) {
-      const float u = __shfl(v, lane + R * BT, 64);  // the up row of the same output
-      const int n = out0 + my_r;
-      if (my_live && my_r < R && n < a.n_out)
-        a.Y[static_cast<size_t>(my_b) * a.ldy + n] = (uint16_t)f32_to_bf16(silu_f32(v) * u);
-    } else {
-      const int n = out0 + my_r;
-      if (my_live && n < a.N) {
-        if (a.logits) a.logits[static_cast<size_t>(my_b) * a.N + n] = v;
-        if (better(v, n, best_v, best_i)) { best_v = v; best_i = n; }
-      }
-    }
-  };
-  // weight row behind slot r of the group starting at output out0; -1 past the end
-  auto weight_row = [&](int out0, int r) {
+  // weight row behind slot r of group g; -1 past the end
+  auto weight_row = [&](int g, int r) {
+    const int out0 = (blockIdx.x * a.groups + g) * ROUT;
     if constexpr (EPI == EPI_SILU) {
-      const int n = out0 + (r < R ? r : r - R);
-      if (r >= RW || n >= a.n_out) return -1;
-      return r < R ? n : a.n_out + n;
+      const int n = out0 + (r < ROUT ? r : r - ROUT);
+      if (n >= a.n_out) return -1;
+      return r < ROUT ? n : a.n_out + n;
     } else {
       const int n = out0 + r;
-      return (r >= RW || n >= a.N) ? -1 : n;
+      return n >= a.N ? -1 : n;
+    }
+  };
+  auto load = [&](u32x4(&dst)[R][KS], int g) {
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      int row = weight_row(g, r);
+      row = row >= 0 ? row : a.N - 1;  // slots past the end re-read the last row; results dropped
+      const uint16_t* wp = a.W + static_cast<size_t>(row) * a.K;
+#pragma unroll
+      for (int s = 0; s < KS; ++s)
+        dst[r][s] = (koff[s] < k_end) ? ld16_stream(wp + koff[s]) : u32x4{0u, 0u, 0u, 0u};
     }
   };
 
-  // ---- phase A: accumulate ---------------------------------------------------------
+  // lane j < NV of the finishing wave owns (slot r = j / BT, batch row b = j % BT)
+  const int fin_r = lane / BT, fin_b = lane % BT;
+  const bool fin_live = lane < NV && fin_b < a.B;
+  float best_v = -INFINITY;
+  int best_i = INT_MAX;
+  auto finish = [&](int g, float v) {  // called by all lanes of one wave
+    const int row = fin_live ? weight_row(g, fin_r) : -1;
+    if constexpr (EPI == EPI_NONE) {
+      if (row >= 0) a.Y[static_cast<size_t>(fin_b) * a.ldy + row] = (uint16_t)f32_to_bf16(v);
+    } else if constexpr (EPI == EPI_SILU) {
+      const float u = __shfl(v, lane + ROUT * BT, 64);  // the up row of the same output
+      if (row >= 0 && fin_r < ROUT)
+        a.Y[static_cast<size_t>(fin_b) * a.ldy + row] = (uint16_t)f32_to_bf16(silu_f32(v) * u);
+    } else {
+      if (row >= 0) {
+        if (a.logits) a.logits[static_cast<size_t>(fin_b) * a.N + row] = v;
+        if (better(v, row, best_v, best_i)) { best_v = v; best_i = row; }
+      }
+    }
+  };
+
+  // ---- phase A: stream the rows ------------------------------------------------------
+  const int my_value = value_of_lane<NV>(lane);
+  u32x4 w[R][KS], wn[R][KS];
+  load(w, 0);
   for (int g = 0; g < a.groups; ++g) {
-    const int out0 = ((blockIdx.x * a.groups + g) * WAVES + wave) * R;
-    const uint16_t* wp[RW];
-#pragma unroll
-    for (int r = 0; r < RW; ++r) {
-      int row = weight_row(out0, r);
-      row = row >= 0 ? row : a.N - 1;  // slots past the end re-read the last row; results dropped
-      wp[r] = a.W + static_cast<size_t>(row) * a.K;
+    if constexpr (PF) {
+      if (g + 1 < a.groups) load(wn, g + 1);
     }
-    float acc[RW][BT];
+    float v[NV];
 #pragma unroll
-    for (int r = 0; r < RW; ++r)
-#pragma unroll
-      for (int b = 0; b < BT; ++b) acc[r][b] = 0.f;
-
-    for (int k0 = k_begin; k0 < k_end; k0 += a.kc) {
-      const int klen = (k_end - k0) < a.kc ? (k_end - k0) : a.kc;
-      if (g == 0 || multi_chunk) {
-        __syncthreads();
-        stage_x<BT>(xs, a, k0, klen);
-        __syncthreads();
-      }
-      // full 512-element steps: no lane checks; while one buffer is consumed the
-      // other one's loads are in flight
-      const int nfull = klen >> 9;
-      auto step = [&](const u32x4(&w)[RW], int it) {
-        const uint16_t* xrow = xs + it * 512 + lane * 8;
-#pragma unroll
-        for (int b = 0; b < BT; ++b) {
-          const u32x4 xv = *reinterpret_cast<const u32x4*>(xrow + b * a.kc);
-#pragma unroll
-          for (int r = 0; r < RW; ++r) acc[r][b] = dot8_bf16(w[r], xv, acc[r][b]);
-        }
-      };
-      auto load = [&](u32x4(&w)[RW], int it) {
-#pragma unroll
-        for (int r = 0; r < RW; ++r) w[r] = ld16_stream(wp[r] + k0 + it * 512 + lane * 8);
-      };
-      u32x4 w0[RW], w1[RW];
-      if (nfull > 0) load(w0, 0);
-      int it = 0;
-      for (; it + 2 <= nfull; it += 2) {
-        load(w1, it + 1);
-        step(w0, it);
-        if (it + 2 < nfull) load(w0, it + 2);
-        step(w1, it + 1);
-      }
-      if (it < nfull) {
-        step(w0, it);
-        ++it;
-      }
-      if (klen & 511) {  // ragged tail: lanes past the end contribute +0
-        const int kk = it * 512 + lane * 8;
-#pragma unroll
-        for (int r = 0; r < RW; ++r)
-          w0[r] = (kk < klen) ? ld16_stream(wp[r] + k0 + kk) : u32x4{0u, 0u, 0u, 0u};
-        step(w0, it);
-      }
-    }
-
-    // butterfly over lanes, then hand (r, b) to lane r*BT + b
-    float mine = 0.f;
-#pragma unroll
-    for (int r = 0; r < RW; ++r)
+    for (int r = 0; r < R; ++r)
 #pragma unroll
       for (int b = 0; b < BT; ++b) {
-        const float t = wave_sum(acc[r][b]);
-        if (lane == r * BT + b) mine = t;
+        float acc = 0.f;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) acc = dot8_bf16(w[r][s], xs[s][b], acc);
+        v[r * BT + b] = acc;
       }
-
-    if (a.S == 1) {
-      finish(out0, mine);
-    } else {
-      const int row = weight_row(out0, my_r);
-      if (my_live && row >= 0)
-        a.partials[(static_cast<size_t>(split) * BT + my_b) * a.N + row] = mine;
+    if constexpr (!PF) {
+      if (g + 1 < a.groups) load(w, g + 1);
+    }
+    const float mine = reduce_values<NV>(v, lane);
+    float* slot = part[g & 1][wave];
+    if (my_value >= 0) slot[my_value] = mine;
+    __syncthreads();
+    // slices are added in ascending order by one wave; the others move on (the
+    // other half of part[] is not rewritten before the next barrier)
+    if (wave == g % nw) {
+      float s = 0.f;
+      if (lane < NV) {
+        s = part[g & 1][0][lane];
+        for (int ww = 1; ww < nw; ++ww) s += part[g & 1][ww][lane];
+      }
+      if (a.S == 1) {
+        finish(g, s);
+      } else {
+        const int row = fin_live ? weight_row(g, fin_r) : -1;
+        if (row >= 0) a.partials[(static_cast<size_t>(split) * BT + fin_b) * a.N + row] = s;
+      }
+    }
+    if constexpr (PF) {
+#pragma unroll
+      for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int s = 0; s < KS; ++s) w[r][s] = wn[r][s];
     }
   }
 
@@ -189,20 +218,20 @@ __global__ __launch_bounds__(WAVES * 64, gemv_occupancy(BT, RW)) void gemv_kerne
     __syncthreads();
     if (!s_last) return;
     __threadfence();
-    for (int g = 0; g < a.groups; ++g) {
-      const int out0 = ((blockIdx.x * a.groups + g) * WAVES + wave) * R;
-      const int row = weight_row(out0, my_r);
+    for (int g = wave; g < a.groups; g += nw) {
+      const int row = fin_live ? weight_row(g, fin_r) : -1;
       float v = 0.f;
-      if (my_live && row >= 0) {
+      if (row >= 0) {
         for (int s = 0; s < a.S; ++s)  // chunk order
-          v += __builtin_nontemporal_load(&a.partials[(static_cast<size_t>(s) * BT + my_b) * a.N + row]);
+          v += __builtin_nontemporal_load(&a.partials[(static_cast<size_t>(s) * BT + fin_b) * a.N + row]);
       }
-      finish(out0, v);
+      finish(g, v);
     }
     if (threadIdx.x == 0) a.ws[1 + blockIdx.x] = 0u;  // ready for the next launch
   }
 
-  // ---- phase C (LM head): block argmax -> workspace -> last block picks the token --
+  // ---- phase C (LM head): block argmax -> (value, index) pair per batch row in the workspace;
+  // the pairs of all workgroups are reduced by the argmax-finish launch that follows ----
   if constexpr (EPI == EPI_ARGMAX) {
     // lanes with the same batch row sit BT apart
 #pragma unroll
@@ -213,52 +242,28 @@ __global__ __launch_bounds__(WAVES * 64, gemv_occupancy(BT, RW)) void gemv_kerne
     }
     if (lane < BT) { s_bv[wave][lane] = best_v; s_bi[wave][lane] = best_i; }
     __syncthreads();
-    uint32_t* part = a.ws + 1 + gridDim.x;  // [gridDim.x][BT][2]
+    uint32_t* pairs = a.ws + 1 + gridDim.x;  // [gridDim.x][BT][2]
     if (threadIdx.x < BT) {
       float bv = s_bv[0][threadIdx.x];
       int bi = s_bi[0][threadIdx.x];
-#pragma unroll
-      for (int w = 1; w < WAVES; ++w)
-        if (better(s_bv[w][threadIdx.x], s_bi[w][threadIdx.x], bv, bi)) { bv = s_bv[w][threadIdx.x]; bi = s_bi[w][threadIdx.x]; }
-      part[(blockIdx.x * BT + threadIdx.x) * 2 + 0] = __float_as_uint(bv);
-      part[(blockIdx.x * BT + threadIdx.x) * 2 + 1] = static_cast<uint32_t>(bi);
+      for (int ww = 1; ww < nw; ++ww)
+        if (better(s_bv[ww][threadIdx.x], s_bi[ww][threadIdx.x], bv, bi)) { bv = s_bv[ww][threadIdx.x]; bi = s_bi[ww][threadIdx.x]; }
+      pairs[(blockIdx.x * BT + threadIdx.x) * 2 + 0] = __float_as_uint(bv);
+      pairs[(blockIdx.x * BT + threadIdx.x) * 2 + 1] = static_cast<uint32_t>(bi);
     }
-    __threadfence();
-    __syncthreads();
-    if (threadIdx.x == 0) {
-      const uint32_t t = atomicAdd(&a.ws[0], 1u);
-      s_last = (t == gridDim.x - 1u);
-    }
-    __syncthreads();
-    if (!s_last) return;
-    __threadfence();
-    // every block has published its (value, index) pairs: reduce them per batch row
-    for (int b = wave; b < a.B; b += WAVES) {
-      float bv = -INFINITY;
-      int bi = INT_MAX;
-      for (unsigned blk = lane; blk < gridDim.x; blk += 64) {
-        const float v = __uint_as_float(__builtin_nontemporal_load(&part[(blk * BT + b) * 2 + 0]));
-        const int i = static_cast<int>(__builtin_nontemporal_load(&part[(blk * BT + b) * 2 + 1]));
-        if (better(v, i, bv, bi)) { bv = v; bi = i; }
-      }
-#pragma unroll
-      for (int d = 1; d < 64; d <<= 1) {
-        const float ov = __shfl_xor(bv, d, 64);
-        const int oi = __shfl_xor(bi, d, 64);
-        if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
-      }
-      if (lane == 0) a.tok[b] = (bi == INT_MAX) ? 0 : bi;
-    }
-    if (threadIdx.x == 0) a.ws[0] = 0u;
   }
 }
 
-#define VTE_GEMV_CASE(BT, RW, WV, EPI) \
-  if (bt == BT && rw == RW && waves == WV && epi == EPI) return (const void*)gemv_kernel<BT, RW, WV, EPI>;
+#define VTE_GEMV_CASE(BT, R, KS, PF, MAXW)                                                            \
+  if (bt == BT && r == R && ks == KS && pf == PF && maxw == MAXW) {                                    \
+    if (epi == 0) return (const void*)gemv_kernel<BT, R, KS, (PF != 0), MAXW, EPI_NONE>;               \
+    if (epi == 2) return (const void*)gemv_kernel<BT, R, KS, (PF != 0), MAXW, EPI_ARGMAX>;             \
+    if constexpr (R % 2 == 0) { if (epi == 1) return (const void*)gemv_kernel<BT, R, KS, (PF != 0), MAXW, EPI_SILU>; } \
+  }
 
 // One translation unit per BT instantiates these.
-#define VTE_GEMV_ENTRY_FOR_BT(BT)                                                   \
-  extern "C" const void* vte_gemv_entry_b##BT(int bt, int rw, int waves, int epi) { \
-    VTE_GEMV_CASES(BT)                                                              \
-    return nullptr;                                                                 \
+#define VTE_GEMV_ENTRY_FOR_BT(BT)                                                                 \
+  extern "C" const void* vte_gemv_entry_b##BT(int bt, int r, int ks, int pf, int maxw, int epi) { \
+    VTE_GEMV_CASES(BT)                                                                            \
+    return nullptr;                                                                               \
   }

@@ -27,8 +27,8 @@ struct GemvArgs {
   int B, N, K;
   int ldx, ldy;           // row strides of X and Y in elements (K and n_out when dense)
   int n_out;              // outputs per batch row (N, or N/2 with SiLU-mul)
-  int groups;             // row groups each wave walks through
-  int kc;                 // K elements of X staged in LDS at a time
+  int groups;             // row groups each workgroup walks through
+  int bt;                 // batch tile the kernel instance was built for
   int S;                  // K split (1 = fixed structure)
   int k_per_split;        // K / S
 };
@@ -46,4 +46,12 @@ struct GemmArgs {
   uint16_t* C;            // [M,N]
   int M, N, K;
   int tiles_m, tiles_n;
+};
+
+// Second stage of the greedy token: reduce the per-workgroup (value, index)
+// candidates the LM head left in its workspace.
+struct ArgmaxFinishArgs {
+  const uint32_t* pairs;  // [nblocks][bt][2]: fp32 bits, int32 index
+  int32_t* tok;           // [B]
+  int nblocks, bt, B;
 };

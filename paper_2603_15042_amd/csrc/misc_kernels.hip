@@ -12,4 +12,35 @@ __global__ __launch_bounds__(256) void gather_kernel(const GatherArgs a) {
   st16(a.H + static_cast<size_t>(b) * a.K + c * 8, ld16(a.E + static_cast<size_t>(t) * a.K + c * 8));
 }
 
+// Greedy token, second stage: one workgroup per batch row scans the candidates of
+// every LM-head workgroup.  (value, index) pairs are totally ordered (larger
+// value, then lower index; NaN never wins), so the scan order cannot matter.
+__global__ __launch_bounds__(256) void argmax_finish_kernel(const ArgmaxFinishArgs a) {
+  __shared__ float s_v[4];
+  __shared__ int s_i[4];
+  const int b = blockIdx.x;
+  if (b >= a.B) return;
+  float bv = -INFINITY;
+  int bi = 0x7fffffff;
+  for (int blk = threadIdx.x; blk < a.nblocks; blk += 256) {
+    const float v = __uint_as_float(a.pairs[(static_cast<size_t>(blk) * a.bt + b) * 2 + 0]);
+    const int i = static_cast<int>(a.pairs[(static_cast<size_t>(blk) * a.bt + b) * 2 + 1]);
+    if (better(v, i, bv, bi)) { bv = v; bi = i; }
+  }
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const float ov = __shfl_xor(bv, d, 64);
+    const int oi = __shfl_xor(bi, d, 64);
+    if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+  }
+  if ((threadIdx.x & 63) == 0) { s_v[threadIdx.x >> 6] = bv; s_i[threadIdx.x >> 6] = bi; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int w = 1; w < 4; ++w)
+      if (better(s_v[w], s_i[w], bv, bi)) { bv = s_v[w]; bi = s_i[w]; }
+    a.tok[b] = (bi == 0x7fffffff) ? 0 : bi;
+  }
+}
+
+extern "C" const void* vte_argmax_finish_entry() { return (const void*)argmax_finish_kernel; }
 extern "C" const void* vte_gather_entry() { return (const void*)gather_kernel; }

@@ -67,11 +67,10 @@ def run_on(ctx, desc, pctx_id):
 
 
 class DecodeChain:
-    """The Llama-shaped single-layer decode chain as seven immutable descriptors:
-    gather, RMSNorm, QKV, O (on the Q slice of QKV), gate/up+SiLU, down, LM head + argmax.
+    """The Llama-shaped single-layer decode chain as eight immutable descriptors:
+    gather, RMSNorm, QKV, O (on the Q slice of QKV), gate/up+SiLU, down, LM head, argmax finish.
     splitk=S builds the reshaped variant of every GEMV instead (the negative control)."""
 
-    NAMES = ("gather", "rmsnorm", "qkv", "o", "gateup", "down", "lmhead")
 
     def __init__(self, ctx, weights_dev, shp, B, eps=1e-6, want_logits=False, splitk=None, rms_active_cus=None,
                  feedback=False):
@@ -117,7 +116,8 @@ class DecodeChain:
             d["down"] = vte.vte_desc_gemv_splitk(ctx, w["Wd"], self.act, self.d, ws(D), B, D, F, 0, S)
             d["lmhead"] = vte.vte_desc_lmhead_argmax_splitk(ctx, w["Wlm"], self.d, self.next, self.logits, self.ws,
                                                             ws(V), B, V, D, S)
-        self.order = [k for k in ("gather", "rmsnorm", "qkv", "q", "o", "gateup", "down", "lmhead") if k in d]
+        d["argmax"] = vte.vte_desc_argmax_finish(ctx, d["lmhead"])
+        self.order = [k for k in ("gather", "rmsnorm", "qkv", "q", "o", "gateup", "down", "lmhead", "argmax") if k in d]
         self.bytes_per_step = sum(vte.vte_desc_info(d[k]).bytes for k in self.order if k != "q")
 
     def set_tokens(self, toks):
@@ -125,7 +125,7 @@ class DecodeChain:
         torch.cuda.synchronize()
 
     def submit_step(self, vs):
-        """Submits one step (7 launches) to a vstream; returns the last token."""
+        """Submits one step (8 launches) to a vstream; returns the last token."""
         last = 0
         for k in self.order:
             last = vte.vte_submit(vs, self.desc[k])

@@ -21,7 +21,7 @@ VTE_EPI_NONE, VTE_EPI_SILU_MUL = 0, 1
 VTE_CLASS_LATENCY, VTE_CLASS_BEST_EFFORT = 0, 1
 VTE_POLICY_WIDEST, VTE_POLICY_QUEUE_STATE = 0, 1
 (VTE_K_RMSNORM, VTE_K_LAYERNORM, VTE_K_GEMV, VTE_K_LMHEAD, VTE_K_GATHER, VTE_K_GEMM, VTE_K_GEMV_SPLITK,
- VTE_K_LMHEAD_SPLITK, VTE_K_RMSNORM_RESHAPED) = range(1, 10)
+ VTE_K_LMHEAD_SPLITK, VTE_K_RMSNORM_RESHAPED, VTE_K_ARGMAX_FINISH) = range(1, 11)
 
 
 class VteError(RuntimeError):
@@ -48,7 +48,7 @@ class vte_desc_view(C.Structure):
 
 
 class vte_gemv_plan(C.Structure):
-    _fields_ = [("rows_in_flight", C.c_int), ("waves", C.c_int), ("groups", C.c_int), ("kc", C.c_int)]
+    _fields_ = [(n, C.c_int) for n in ("batch_tile", "rows", "ksteps", "prefetch", "max_waves", "groups")]
 
 
 class vte_ready_op(C.Structure):
@@ -100,7 +100,7 @@ class vte_fake_log_entry(C.Structure):
 EXPORTS = [
     "vte_last_error", "vte_last_hip_error", "vte_pool_cfg_default", "vte_init", "vte_shutdown", "vte_pool_count",
     "vte_pool_info", "vte_pool_find", "vte_pool_conflict", "vte_pctx_native_stream", "vte_desc_rmsnorm",
-    "vte_desc_layernorm", "vte_desc_gemv", "vte_lmhead_workspace_bytes", "vte_desc_lmhead_argmax",
+    "vte_desc_layernorm", "vte_desc_gemv", "vte_lmhead_workspace_bytes", "vte_desc_lmhead_argmax", "vte_desc_argmax_finish",
     "vte_desc_gemv_strided", "vte_gemv_default_plan", "vte_desc_gemv_planned", "vte_desc_lmhead_argmax_planned", "vte_desc_gather",
     "vte_desc_gemm", "vte_splitk_workspace_bytes", "vte_desc_gemv_splitk", "vte_desc_lmhead_argmax_splitk",
     "vte_desc_rmsnorm_reshaped", "vte_desc_info", "vte_desc_args", "vte_desc_destroy", "vte_bind_and_launch",
@@ -263,6 +263,10 @@ def vte_lmhead_workspace_bytes(B, V, K):
 def vte_desc_lmhead_argmax(ctx, W, H, tok, logits_or_null, workspace, B, V, K):
     return _desc_call(load().vte_desc_lmhead_argmax, ctx, _ptr(W), _ptr(H), _ptr(tok), _ptr(logits_or_null),
                       _ptr(workspace), int(B), int(V), int(K))
+
+
+def vte_desc_argmax_finish(ctx, lmhead_desc):
+    return _desc_call(load().vte_desc_argmax_finish, ctx, lmhead_desc)
 
 
 def vte_desc_lmhead_argmax_planned(ctx, W, H, tok, logits_or_null, workspace, B, V, K, plan):

@@ -213,7 +213,11 @@ def test_gemv_splitk_reshaping_drifts_and_fixed_does_not(H, ctx, B):
         vte.vte_desc_destroy(d)
     print("split-K drift of fp32 sums (elements, bits) vs fixed, B=%d:" % B, drift32)
     assert drift32[32] == (0, 0)
-    assert all(drift32[w][1] > 0 for w in (64, 128, 256))   # regrouping moves bits on random data
+    # S = 2 always regroups the per-slice sums.  A larger S coincides with the fixed tree exactly
+    # when K/S equals the fixed kernel's own K-slice (adding one-slice chunks in order IS the fixed
+    # order): S = 8 at batch <= 2 (512-wide slices), S = 4 at batch 8 (1024-wide slices).
+    assert drift32[64][1] > 0                               # regrouping moves bits on random data
+    assert sum(1 for w in (64, 128, 256) if drift32[w][1] > 0) >= 2
     # negative control: exact inputs -> no drift for any S
     Wi = inputs.int_bf16(5, inputs.T_W, (N, K), -8, 8)
     Xi = inputs.int_bf16(5, inputs.T_XB, (B, K), -8, 8, -2)
@@ -266,11 +270,13 @@ def test_lmhead_logits_and_token(H, ctx, B, V, K):
     logits = torch.zeros((B, V), dtype=torch.float32, device="cuda")
     ws = H.dev_zeros_bytes(vte.vte_lmhead_workspace_bytes(B, V, K))
     d = vte.vte_desc_lmhead_argmax(ctx, dW, dH, tok, logits, ws, B, V, K)
+    fin = vte.vte_desc_argmax_finish(ctx, d)
     ref_logits, ref_tok, margin = oracle.lmhead_argmax(W, Hh)
     got = {}
     for p in [H.pctx_of_width(ctx, w) for w in (32, 64, 128, 256)]:
         tok.fill_(-7)
         H.run_on(ctx, d, p)
+        H.run_on(ctx, fin, p)
         torch.cuda.synchronize()
         got[p] = (tok.cpu().numpy().copy(), logits.cpu().numpy().copy())
     first = next(iter(got.values()))
@@ -297,6 +303,7 @@ def test_lmhead_ties_go_to_lowest_index(H, ctx):
     ws = H.dev_zeros_bytes(vte.vte_lmhead_workspace_bytes(B, V, K))
     d = vte.vte_desc_lmhead_argmax(ctx, dW, dH, tok, None, ws, B, V, K)
     H.run_on(ctx, d, 3)
+    H.run_on(ctx, vte.vte_desc_argmax_finish(ctx, d), 5)
     assert tok.cpu().numpy()[0] == 131
     assert tok.cpu().numpy()[0] == oracle.lmhead_argmax(W, Hh)[1][0]
     vte.vte_desc_destroy(d)
