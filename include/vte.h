@@ -87,12 +87,19 @@ enum { VTE_MODE_STRICT = 0, VTE_MODE_PIPELINED = 1 };
  * CUs on each of the 8 XCDs.  It is the only layout offered. */
 enum { VTE_LAYOUT_STRIPED = 0 };
 
+/* Every pCtx is a hardware queue.  An MI355X process that keeps more than about
+ * 22 compute queues alive is time-sliced by the queue scheduler (measured: 11 ms
+ * stalls of the running queue every ~50 ms from 24 queues on), so the default
+ * pool is the full tree (15 nodes for 256 CUs / 32) plus one remainder per tree
+ * level: 17 queues.  ALL gives every non-root node its remainder (27 queues). */
+enum { VTE_REMAINDERS_NONE = 0, VTE_REMAINDERS_ALL = 1, VTE_REMAINDERS_PER_LEVEL = 2 };
+
 typedef struct vte_pool_cfg {
   int backend;         /* VTE_BACKEND_* */
   int total_cus;       /* 0 = ask the device (HIP) / 256 (FAKE) */
   int leaf_cus;        /* minimum allocation unit; 0 = 32 */
   int layout;          /* VTE_LAYOUT_STRIPED */
-  int with_remainders; /* 1: pre-create one remainder pCtx per non-root node */
+  int with_remainders; /* VTE_REMAINDERS_*: which nodes get a pre-created remainder pCtx */
   int mode;            /* VTE_MODE_* */
   int lookahead;       /* PIPELINED: max unfinished ops bound ahead per vstream; 0 = 16 */
   int stats_capacity;  /* ring size of per-op records kept for vte_stats_read; 0 = 65536 */
@@ -100,7 +107,7 @@ typedef struct vte_pool_cfg {
                                   on their own stream and vte_op_record.gpu_seconds is filled */
 } vte_pool_cfg;
 
-/* Fills *cfg with the defaults (HIP, device CU count, leaf 32, remainders, STRICT). */
+/* Fills *cfg with the defaults (HIP, device CU count, leaf 32, one remainder per level, STRICT). */
 int vte_pool_cfg_default(vte_pool_cfg* cfg);
 
 /* Creates the context on `device`: builds the pool tree, pre-creates one

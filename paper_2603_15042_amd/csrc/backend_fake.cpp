@@ -7,7 +7,7 @@ int FakeBackend::wait_on(void*, void*, int completion_pctx) {
   return VTE_OK;
 }
 
-int FakeBackend::submit(const vte_desc* d, void*, int pctx, vte_token tok, bool, void** completion) {
+int FakeBackend::submit(const vte_desc* d, void*, int pctx, vte_token tok, bool, bool, void** completion) {
   if (fail_next > 0) {
     --fail_next;
     pending_wait_ = -1;

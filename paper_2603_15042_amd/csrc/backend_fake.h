@@ -18,7 +18,9 @@ class FakeBackend : public Backend {
     *stream = reinterpret_cast<void*>(static_cast<uintptr_t>(++streams_)); return VTE_OK;
   }
   void destroy_stream(void*) override {}
-  int submit(const vte_desc* d, void* stream, int pctx, vte_token tok, bool timed, void** completion) override;
+  int submit(const vte_desc* d, void* stream, int pctx, vte_token tok, bool timed, bool record_now,
+             void** completion) override;  // always records: tests complete launches one by one
+  int record(void*, void**) override { return VTE_ESTATE; }
   double elapsed(void*) override { return -1.0; }
   int wait_on(void* stream, void* completion, int completion_pctx) override;
   bool is_done(void* c) override { return static_cast<Completion*>(c)->done; }

@@ -4,6 +4,9 @@
 #include <hip/hip_runtime.h>
 #include <hip/hip_ext.h>
 
+#include <chrono>
+#include <cstdio>
+#include <cstdlib>
 #include <vector>
 
 #include "runtime.h"
@@ -19,6 +22,23 @@ namespace {
       return VTE_EHIP;                                                       \
     }                                                                        \
   } while (0)
+
+// With VTE_TRACE_SLOW_CALLS=<microseconds> in the environment, any HIP call made on
+// the dispatch path that takes longer is reported on stderr.
+struct SlowCall {
+  const char* what;
+  std::chrono::steady_clock::time_point t0;
+  static double limit_us() {
+    static const double v = [] { const char* e = getenv("VTE_TRACE_SLOW_CALLS"); return e ? atof(e) : 0.0; }();
+    return v;
+  }
+  explicit SlowCall(const char* w) : what(w) { if (limit_us() > 0) t0 = std::chrono::steady_clock::now(); }
+  ~SlowCall() {
+    if (limit_us() <= 0) return;
+    const double us = std::chrono::duration<double, std::micro>(std::chrono::steady_clock::now() - t0).count();
+    if (us > limit_us()) fprintf(stderr, "[vte] %s took %.1f us\n", what, us);
+  }
+};
 
 class HipBackend : public Backend {
  public:
@@ -62,8 +82,11 @@ class HipBackend : public Backend {
   }
   void put_event(bool timing, hipEvent_t ev) { (timing ? free_timing_events_ : free_events_).push_back(ev); }
 
-  int submit(const vte_desc* d, void* stream, int, vte_token, bool timed, void** completion) override {
+  int submit(const vte_desc* d, void* stream, int, vte_token, bool timed, bool record_now,
+             void** completion) override {
     hipStream_t s = static_cast<hipStream_t>(stream);
+    *completion = nullptr;
+    if (!timed && !record_now) return launch(d, s);
     Completion* c = new Completion;
     int rc = get_event(timed, &c->done);
     if (rc == VTE_OK && timed) rc = get_event(true, &c->start);
@@ -85,6 +108,21 @@ class HipBackend : public Backend {
     *completion = c;
     return VTE_OK;
   }
+  int record(void* stream, void** completion) override {
+    Completion* c = new Completion;
+    int rc = get_event(false, &c->done);
+    if (rc != VTE_OK) { delete c; return rc; }
+    SlowCall sc("hipEventRecord");
+    hipError_t e = hipEventRecord(c->done, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) {
+      put_event(false, c->done);
+      delete c;
+      set_error(std::string("hipEventRecord: ") + hipGetErrorString(e), (int)e);
+      return VTE_EHIP;
+    }
+    *completion = c;
+    return VTE_OK;
+  }
   double elapsed(void* completion) override {
     Completion* c = static_cast<Completion*>(completion);
     if (!c->start) return -1.0;
@@ -97,6 +135,7 @@ class HipBackend : public Backend {
     return VTE_OK;
   }
   bool is_done(void* completion) override {
+    SlowCall sc("hipEventQuery");
     return hipEventQuery(static_cast<Completion*>(completion)->done) != hipErrorNotReady;
   }
   void release(void* completion) override {
@@ -142,6 +181,7 @@ class HipBackend : public Backend {
   // come from the descriptor as they are.
   int launch(const vte_desc* d, hipStream_t s) {
     void* params[1] = {const_cast<unsigned char*>(d->args)};
+    SlowCall sc("hipLaunchKernel");
     hipError_t e = hipLaunchKernel(d->entry, dim3(d->grid[0], d->grid[1], d->grid[2]),
                                    dim3(d->block[0], d->block[1], d->block[2]), params, d->lds_bytes, s);
     if (e != hipSuccess) {

@@ -30,7 +30,7 @@ int Pool::add_node(int lo, int hi, int parent, int level, int leaf_cus) {
   return id;
 }
 
-bool Pool::build(int total_cus, int leaf_cus, bool with_remainders, std::string* err) {
+bool Pool::build(int total_cus, int leaf_cus, int remainders, std::string* err) {
   p_.clear();
   active_nodes_ = active_remainders_ = 0;
   active_rem_ids_.clear();
@@ -45,11 +45,11 @@ bool Pool::build(int total_cus, int leaf_cus, bool with_remainders, std::string*
   leaves_ = leaves;
   words_ = (total_cus + 31) / 32;
   root_ = add_node(0, leaves, -1, 0, leaf_cus);
-  if (!with_remainders) return true;
+  if (remainders == 0) return true;
   const int nodes = size();
+  std::vector<char> level_done(64, 0);
   for (int id = 0; id < nodes; ++id) {
     if (id == root_) continue;  // nothing would be left (or less than a leaf)
-    const int rem_width = total_ - p_[id].width;
     // a child of the root is complemented by its sibling when the tree covers
     // the whole device: link instead of creating a duplicate allocation
     if (p_[id].parent == root_ && leaves_ * leaf_ == total_) {
@@ -57,6 +57,11 @@ bool Pool::build(int total_cus, int leaf_cus, bool with_remainders, std::string*
       p_[id].remainder = (par.child[0] == id) ? par.child[1] : par.child[0];
       continue;
     }
+    if (remainders == 2) {  // bounded variant: only the first node of every level gets one
+      if (level_done[p_[id].level]) continue;
+      level_done[p_[id].level] = 1;
+    }
+    const int rem_width = total_ - p_[id].width;
     const int rid = size();
     p_.emplace_back();
     Pctx& r = p_[rid];

@@ -42,7 +42,8 @@ class Pool {
  public:
   // total_cus CUs, minimum unit leaf_cus; leaves = largest power of two not above
   // total/leaf.  CUs beyond leaves*leaf belong to remainders only.
-  bool build(int total_cus, int leaf_cus, bool with_remainders, std::string* err);
+  // remainders: 0 none, 1 one per non-root node, 2 one per tree level (for the first node of the level)
+  bool build(int total_cus, int leaf_cus, int remainders, std::string* err);
 
   int size() const { return static_cast<int>(p_.size()); }
   Pctx& at(int id) { return p_[id]; }

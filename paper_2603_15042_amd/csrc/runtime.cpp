@@ -121,9 +121,12 @@ void record_op(vte_ctx* c, const Op* op) {
 void complete_op(vte_ctx* c, Op* op) {
   op->state = kDone;
   op->t_done = c->now();
-  op->gpu_seconds = c->backend->elapsed(op->completion);
-  c->backend->release(op->completion);
-  op->completion = nullptr;
+  if (op->completion) {
+    op->gpu_seconds = c->backend->elapsed(op->completion);
+    c->backend->release(op->completion);
+    op->completion = nullptr;
+  }
+  if (c->lazy_tail[op->pctx] == op) c->lazy_tail[op->pctx] = nullptr;
   retire_one(c, op->pctx);
   if (op->vs >= 0) {
     vte_vstream* vs = c->vstreams[op->vs];
@@ -136,24 +139,55 @@ void complete_op(vte_ctx* c, Op* op) {
   delete op;
 }
 
-// Poll completions: within a pCtx ops finish in submission order, so only the
-// oldest in-flight op of each pCtx is queried until it is done.
+// Poll completions.  Within a pCtx launches finish in submission order, so the
+// newest completion record that is done retires every older launch of that pCtx,
+// recorded or not, and nothing behind a record that is not done is looked at.
 bool poll_completions(vte_ctx* c) {
-  bool any = false;
-  std::vector<char> blocked(c->pool.size(), 0);
-  for (size_t i = 0; i < c->inflight.size();) {
+  if (c->inflight.empty()) return false;
+  const int np = c->pool.size();
+  std::vector<int> frontier(np, -1);
+  std::vector<char> blocked(np, 0);
+  for (size_t i = 0; i < c->inflight.size(); ++i) {
     Op* op = c->inflight[i];
-    if (!blocked[op->pctx] && c->backend->is_done(op->completion)) {
-      c->inflight.erase(c->inflight.begin() + i);
-      complete_op(c, op);
-      any = true;
-    } else {
-      blocked[op->pctx] = 1;
-      ++i;
+    if (blocked[op->pctx] || !op->completion) continue;
+    if (c->backend->is_done(op->completion)) frontier[op->pctx] = static_cast<int>(i);
+    else blocked[op->pctx] = 1;
+  }
+  bool any = false;
+  std::vector<Op*> keep;
+  keep.reserve(c->inflight.size());
+  std::vector<Op*> done;
+  for (size_t i = 0; i < c->inflight.size(); ++i) {
+    Op* op = c->inflight[i];
+    if (static_cast<int>(i) <= frontier[op->pctx]) done.push_back(op);
+    else keep.push_back(op);
+  }
+  if (!done.empty()) {
+    c->inflight.swap(keep);
+    for (Op* op : done) complete_op(c, op);
+    any = true;
+    c->cv_done.notify_all();
+  }
+  return any;
+}
+
+// Give the newest unrecorded launch of a pCtx a completion record when it is
+// needed to observe progress: nothing recorded is pending on that pCtx, eight or
+// more launches have piled up behind the last record, or a caller is waiting.
+void flush_records(vte_ctx* c) {
+  const int np = c->pool.size();
+  std::vector<int> recorded(np, 0), lazy(np, 0);
+  for (Op* op : c->inflight) (op->completion ? recorded : lazy)[op->pctx]++;
+  for (int p = 0; p < np; ++p) {
+    Op* op = c->lazy_tail[p];
+    if (!op) continue;
+    if (recorded[p] > 0 && lazy[p] < 8 && c->waiters == 0) continue;
+    void* comp = nullptr;
+    if (c->backend->record(c->pool.at(p).stream, &comp) == VTE_OK) {
+      op->completion = comp;
+      c->lazy_tail[p] = nullptr;
     }
   }
-  if (any) c->cv_done.notify_all();
-  return any;
 }
 
 // ---- readiness (Sec. 4.4 "Readiness Before Binding") -----------------------------
@@ -244,7 +278,7 @@ bool compatible(const vte_desc* d, const Pctx& p) {
 
 // Validate the proposal, open or reuse the lease, submit the descriptor
 // unchanged, record it as outstanding.  Commit only after a successful submit.
-int bind_and_submit(vte_ctx* c, Op* op, int pctx) {
+int bind_and_submit(vte_ctx* c, Op* op, int pctx, bool record_now) {
   if (pctx < 0 || pctx >= c->pool.size()) { set_error("no such pCtx"); return VTE_EINVAL; }
   Pctx& p = c->pool.at(pctx);
   if (!compatible(op->desc, p)) { set_error("pCtx cannot run the descriptor unchanged"); return VTE_EINCOMPAT; }
@@ -254,17 +288,28 @@ int bind_and_submit(vte_ctx* c, Op* op, int pctx) {
   for (vte_token t : op->deps) {
     auto it = c->live.find(t);
     if (it == c->live.end() || it->second->state != kInflight) continue;
-    if (it->second->pctx == pctx) continue;  // same backend stream: stream order
-    rc = c->backend->wait_on(p.stream, it->second->completion, it->second->pctx);
+    Op* pred = it->second;
+    if (pred->pctx == pctx) continue;  // same backend stream: stream order
+    if (!pred->completion) {  // not recorded yet: record the predecessor stream's current end
+      Op* tail = c->lazy_tail[pred->pctx] ? c->lazy_tail[pred->pctx] : pred;
+      void* comp = nullptr;
+      rc = c->backend->record(c->pool.at(pred->pctx).stream, &comp);
+      if (rc != VTE_OK) return rc;
+      tail->completion = comp;
+      c->lazy_tail[pred->pctx] = nullptr;
+      pred = tail;
+    }
+    rc = c->backend->wait_on(p.stream, pred->completion, pred->pctx);
     if (rc != VTE_OK) return rc;
   }
   void* completion = nullptr;
   const bool timed = (c->cfg.device_timing_mask >> op->desc->kernel) & 1u;
-  rc = c->backend->submit(op->desc, p.stream, pctx, op->tok, timed, &completion);
+  rc = c->backend->submit(op->desc, p.stream, pctx, op->tok, timed, record_now, &completion);
   if (rc != VTE_OK) { ++c->stats.submit_failures; return rc; }  // op stays ready
   admit(c, pctx, op->vs);
   op->pctx = pctx;
   op->completion = completion;
+  c->lazy_tail[pctx] = completion ? nullptr : op;  // a record also covers older launches of the pCtx
   op->state = kInflight;
   op->t_bound = c->now();
   c->inflight.push_back(op);
@@ -336,7 +381,7 @@ bool dispatch_round(vte_ctx* c) {
     if (sel < 0) continue;
     // the proposal is tentative: it must be one of E and still valid
     if (std::find(eligible.begin(), eligible.end(), sel) == eligible.end()) { ++c->stats.stale_proposals; continue; }
-    int rc = bind_and_submit(c, op, sel);
+    int rc = bind_and_submit(c, op, sel, c->cfg.mode != VTE_MODE_PIPELINED);
     if (rc != VTE_OK) continue;  // op remains ready for rescheduling
     c->vstreams[op->vs]->queue.pop_front();
     bound_any = true;
@@ -356,6 +401,7 @@ void dispatcher_main(vte_ctx* c) {
     bool progress = poll_completions(c);
     // keep binding while ops become bindable (PIPELINED chains, freed leases)
     while (dispatch_round(c)) progress = true;
+    flush_records(c);  // PIPELINED: one completion record per burst and pCtx instead of one per launch
     if (c->stop && c->live.empty()) break;
     if (progress) continue;
     if (c->change_seq == seen) {
@@ -395,7 +441,7 @@ int vte_pool_cfg_default(vte_pool_cfg* cfg) {
   cfg->backend = VTE_BACKEND_HIP;
   cfg->leaf_cus = 32;
   cfg->layout = VTE_LAYOUT_STRIPED;
-  cfg->with_remainders = 1;
+  cfg->with_remainders = VTE_REMAINDERS_PER_LEVEL;
   cfg->mode = VTE_MODE_STRICT;
   cfg->lookahead = 16;
   cfg->stats_capacity = 65536;
@@ -425,7 +471,8 @@ int vte_init(vte_ctx** out, int device, const vte_pool_cfg* user_cfg) {
   c->cfg.total_cus = cus;
   std::string err;
   if (cus > 256) { set_error("more than 256 CUs are not supported"); delete c->backend; delete c; return VTE_EINVAL; }
-  if (!c->pool.build(cus, cfg.leaf_cus, cfg.with_remainders != 0, &err)) {
+  if (cfg.with_remainders < 0 || cfg.with_remainders > 2) { set_error("with_remainders must be 0, 1 or 2"); delete c->backend; delete c; return VTE_EINVAL; }
+  if (!c->pool.build(cus, cfg.leaf_cus, cfg.with_remainders, &err)) {
     set_error(err); delete c->backend; delete c; return VTE_EINVAL;
   }
   // pre-create every pCtx's backend stream: nothing is created on the dispatch path
@@ -438,6 +485,7 @@ int vte_init(vte_ctx** out, int device, const vte_pool_cfg* user_cfg) {
     }
   }
   c->ring.resize(static_cast<size_t>(cfg.stats_capacity));
+  c->lazy_tail.assign(c->pool.size(), nullptr);
   c->dispatcher = std::thread(dispatcher_main, c);
   *out = c;
   return VTE_OK;
@@ -448,10 +496,13 @@ int vte_device_sync(vte_ctx* c) {
   Lock lk(c->mu);
   // waits on every token issued so far (all vstream tails and explicit launches)
   const vte_token upto = c->next_token;
+  ++c->waiters;
+  bump(c);
   c->cv_done.wait(lk, [&] {
     for (auto& kv : c->live) if (kv.first < upto) return false;
     return true;
   });
+  --c->waiters;
   return VTE_OK;
 }
 
@@ -544,7 +595,7 @@ int vte_bind_and_launch(vte_ctx* c, const vte_desc* d, int pctx, vte_token* tok_
   op->age = c->next_age;
   op->t_submit = op->t_ready = c->now();
   c->backend->make_current();
-  int rc = bind_and_submit(c, op, pctx);
+  int rc = bind_and_submit(c, op, pctx, true);
   if (rc != VTE_OK) { delete op; return rc; }
   ++c->next_token;
   ++c->next_age;
@@ -626,7 +677,11 @@ int vte_token_wait(vte_ctx* c, vte_token t) {
   if (!c) { set_error("null ctx"); return VTE_EINVAL; }
   Lock lk(c->mu);
   if (t >= c->next_token) { set_error("token was never issued"); return VTE_EINVAL; }
+  if (token_done(c, t)) return VTE_OK;
+  ++c->waiters;
+  bump(c);  // the dispatcher records completions eagerly while somebody waits
   c->cv_done.wait(lk, [&] { return token_done(c, t); });
+  --c->waiters;
   return VTE_OK;
 }
 

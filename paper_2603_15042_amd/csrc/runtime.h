@@ -52,7 +52,11 @@ class Backend {
   virtual void destroy_stream(void* stream) = 0;
   // Submit the descriptor unchanged on `stream`, then record a completion.
   // `timed`: bracket the launch with timing events; elapsed() then gives its device time.
-  virtual int submit(const vte_desc* d, void* stream, int pctx, vte_token tok, bool timed, void** completion) = 0;
+  // `record_now` false: no completion is recorded (*completion = nullptr); a later record() on
+  // the same stream covers this launch too, since a stream completes in order.
+  virtual int submit(const vte_desc* d, void* stream, int pctx, vte_token tok, bool timed, bool record_now,
+                     void** completion) = 0;
+  virtual int record(void* stream, void** completion) = 0;
   virtual double elapsed(void* completion) = 0;  // seconds, -1 if the launch was not timed
   // Make later work on `stream` wait (on the device) for `completion`.
   virtual int wait_on(void* stream, void* completion, int completion_pctx) = 0;
@@ -114,9 +118,11 @@ struct vte_ctx {
   uint64_t next_age = 0;
   std::unordered_map<vte_token, vte::Op*> live;  // not yet done
   std::vector<vte::Op*> inflight;                // in bind order
+  std::vector<vte::Op*> lazy_tail;               // per pCtx: newest in-flight op without a completion record
   std::vector<vte_vstream*> vstreams;
   std::vector<vte_desc*> descs;
   int inflight_by_class[2] = {0, 0};
+  int waiters = 0;  // callers blocked in a wait
 
   vte_policy_vtbl policy{};
   void* policy_user = nullptr;

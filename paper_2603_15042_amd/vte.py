@@ -15,6 +15,7 @@ VTE_OK, VTE_EINVAL, VTE_ENOMEM, VTE_EHIP, VTE_EBUSY, VTE_ENOTREADY, VTE_EINCOMPA
 VTE_BACKEND_HIP, VTE_BACKEND_FAKE = 0, 1
 VTE_MODE_STRICT, VTE_MODE_PIPELINED = 0, 1
 VTE_LAYOUT_STRIPED = 0
+VTE_REMAINDERS_NONE, VTE_REMAINDERS_ALL, VTE_REMAINDERS_PER_LEVEL = 0, 1, 2
 VTE_PCTX_NODE, VTE_PCTX_REMAINDER = 0, 1
 VTE_PCTX_IDLE, VTE_PCTX_LEASED, VTE_PCTX_DRAINING, VTE_PCTX_RESERVED = 0, 1, 2, 3
 VTE_EPI_NONE, VTE_EPI_SILU_MUL = 0, 1

@@ -56,7 +56,7 @@ def assert_all_equal(res):
 def test_pool_is_precreated_with_every_width(ctx):
     w = sorted(set(widths_of(ctx).values()))
     assert w == [32, 64, 128, 192, 224, 256]
-    assert vte.vte_pool_count(ctx) == 27
+    assert vte.vte_pool_count(ctx) == 17          # full tree + one remainder per level: stays under the queue limit
     assert all(vte.vte_pctx_native_stream(ctx, i) for i in all_pctx(ctx))
 
 

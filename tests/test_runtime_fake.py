@@ -17,9 +17,10 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 A = 0x100000  # fake, 16-byte aligned "device" addresses: never dereferenced on the fake backend
 
 
-def make_ctx(mode=vte.VTE_MODE_STRICT, total=256, leaf=32, lookahead=16):
+def make_ctx(mode=vte.VTE_MODE_STRICT, total=256, leaf=32, lookahead=16, remainders=vte.VTE_REMAINDERS_ALL):
     cfg = vte.vte_pool_cfg_default()
     cfg.backend = vte.VTE_BACKEND_FAKE
+    cfg.with_remainders = remainders
     cfg.total_cus = total
     cfg.leaf_cus = leaf
     cfg.mode = mode
@@ -103,6 +104,28 @@ def test_pool_shape_on_mi355x_numbers(ctx):
     leaf = [p for p in nodes if p.width == 32][3]
     m = mask_int(leaf)
     assert m == ((1 << 32) - 1) << (m & -m).bit_length() - 1
+
+
+def test_bounded_pool_keeps_one_remainder_per_level():
+    cfg = vte.vte_pool_cfg_default()
+    assert cfg.with_remainders == vte.VTE_REMAINDERS_PER_LEVEL       # the default stays under the queue limit
+    c = make_ctx(remainders=vte.VTE_REMAINDERS_PER_LEVEL)
+    try:
+        ps = infos(c)
+        assert len(ps) == 17
+        rems = [p for p in ps if p.kind == vte.VTE_PCTX_REMAINDER]
+        assert sorted(p.width for p in rems) == [192, 224]
+        assert sorted(set(p.width for p in ps)) == [32, 64, 128, 192, 224, 256]
+        for r in rems:                                                 # still the exact complement of its node
+            assert mask_int(r) == ((1 << 256) - 1) & ~mask_int(ps[r.parent])
+        for a in ps:
+            for b in ps:
+                assert vte.vte_pool_conflict(c, a.id, b.id) == bool(mask_int(a) & mask_int(b))
+    finally:
+        vte.vte_shutdown(c)
+    c = make_ctx(remainders=vte.VTE_REMAINDERS_NONE)
+    assert vte.vte_pool_count(c) == 15
+    vte.vte_shutdown(c)
 
 
 def test_pool_reproduces_the_papers_remainder_example():
