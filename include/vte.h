@@ -170,7 +170,7 @@ int vte_desc_layernorm(vte_ctx* ctx, const void* x, const void* gamma, const voi
 enum { VTE_EPI_NONE = 0, VTE_EPI_SILU_MUL = 1 };
 /* Y[b,n] = bf16( sum_k W[n,k] X[b,k] ).  W: device [N,K] bf16 (each output's K
  * contiguous); X: device [B,K] bf16; Y: device [B,N] bf16.  1 <= B <= 16,
- * K % 8 == 0, K <= 32768.  fp32 accumulation in a tree that depends on K only:
+ * K % 8 == 0, K <= 16384.  fp32 accumulation in a tree that depends on K only:
  * a K-tile of 256 is 32 lanes x 8 contiguous elements; a lane adds the products
  * of its slice in ascending order, a fixed butterfly adds the 64 lanes of a
  * wave, and the per-slice sums are added in ascending K order.
@@ -209,7 +209,8 @@ int vte_desc_argmax_finish(vte_ctx* ctx, const vte_desc* lmhead, vte_desc** out)
 /* The work decomposition of a GEMV-family descriptor, spelled out.  It is part
  * of the submitted structure C_k: chosen from the shape by vte_gemv_default_plan,
  * or given by the caller, and frozen in the descriptor.
- *   batch_tile  batch rows the kernel is built for (1,2,4,8,16; >= B)
+ *   batch_tile  batch rows the kernel is built for (1,2,4,8,16); a batch larger than the
+ *               tile runs as ceil(B / batch_tile) chunks that each re-read the weights
  *   rows        weight rows a wave streams at once (rows * batch_tile in {16,32,64})
  *   ksteps      512-element K steps per wave: a workgroup has
  *               ceil(ceil(K/S/512) / ksteps) waves, one per K-slice
@@ -387,6 +388,9 @@ int vte_hint_submit(vte_ctx* ctx, const vte_hint* hint);
  * launches each, device events) and stores seconds per launch under the
  * descriptor's profile_key.  Must be called while nothing else is in flight. */
 int vte_profile_measure(vte_ctx* ctx, const vte_desc* desc, int warmup, int reps);
+/* Times `desc` on one pCtx only; *seconds = device time per launch.  Same conditions. */
+int vte_profile_measure_on(vte_ctx* ctx, const vte_desc* desc, int pctx_id, int warmup, int reps,
+                           double* seconds);
 int vte_profile_set(vte_ctx* ctx, uint64_t profile_key, int width, double seconds);
 /* VTE_EINVAL if no profile exists for (key,width). */
 int vte_profile_get(vte_ctx* ctx, uint64_t profile_key, int width, double* seconds);

@@ -48,17 +48,17 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 template <class Args>
 int finish_desc(vte_ctx* ctx, int kernel, const void* entry, const Args& a, uint32_t gx, uint32_t gy,
                 uint32_t threads, uint32_t lds, uint64_t shape_key, uint64_t bytes, uint64_t flops,
-                vte_desc** out) {
+                vte_desc** out, uint32_t gz = 1) {
   static_assert(sizeof(Args) <= sizeof(vte_desc::args), "argument block too large");
   if (!entry) { set_error("no kernel instance for this configuration"); return VTE_EINVAL; }
-  if (gx == 0 || gy == 0 || gx > 0x7fffffffu || gy > 65535u) { set_error("grid out of range"); return VTE_EINVAL; }
+  if (gx == 0 || gy == 0 || gz == 0 || gx > 0x7fffffffu || gy > 65535u || gz > 65535u) { set_error("grid out of range"); return VTE_EINVAL; }
   vte_desc* d = new (std::nothrow) vte_desc;
   if (!d) { set_error("out of host memory"); return VTE_ENOMEM; }
   std::memset(d, 0, sizeof *d);
   d->ctx = ctx;
   d->kernel = kernel;
   d->entry = entry;
-  d->grid[0] = gx; d->grid[1] = gy; d->grid[2] = 1;
+  d->grid[0] = gx; d->grid[1] = gy; d->grid[2] = gz;
   d->block[0] = threads; d->block[1] = 1; d->block[2] = 1;
   d->lds_bytes = lds;
   d->arg_bytes = sizeof(Args);
@@ -124,37 +124,43 @@ int plan_waves(const vte_gemv_plan& p, int k_per_split) {
   return (nsteps + p.ksteps - 1) / p.ksteps;
 }
 
-// Default decomposition, from the shape alone.  outputs = logical outputs per
-// batch row (N, or N/2 with the SiLU epilogue); kps = K / S.
+// Default decomposition, from the shape alone (a table found by timing every
+// built combination on the Llama-8B shapes; it never looks at the device).
+// outputs = logical outputs per batch row (N, or N/2 with the SiLU epilogue);
+// kps = K / S.
 int plan_gemv(int B, int outputs, int kps, int epi, vte_gemv_plan* p) {
   if (B < 1 || B > 16 || outputs < 1 || kps < 8) return VTE_EINVAL;
   const int nsteps = (kps + 511) / 512;
-  if (nsteps > 64) return VTE_EINVAL;
+  if (nsteps > 32) return VTE_EINVAL;
   int bt = batch_tile(B);
-  int r, ks, pf = 1, mw = 8;
-  if (nsteps > 16 && bt < 4) bt = 4;  // long rows: the wider tile keeps the per-wave slice in registers
-  if (bt <= 2) {
-    r = 16; ks = 1; mw = nsteps > 8 ? 16 : 8;
-  } else if (bt == 4) {
+  if (bt == 1) bt = 2;                    // one row rides in the two-row tile
+  if (nsteps > 16 && bt < 4) bt = 4;      // long rows: the wider tile keeps a wave's slice in registers
+  if (nsteps > 16 && bt == 16) bt = 8;    // long rows at batch 16: two batch chunks of 8
+  const bool silu = epi == VTE_EPI_SILU_MUL;
+  int r, ks, pf = 1, mw = 8, gmax = 8;
+  if (bt == 2) {
+    if (nsteps <= 1) { r = 16; ks = 1; } else { r = 8; ks = 2; }
+    if ((nsteps + ks - 1) / ks > 8) { bt = 4; }
+    gmax = 4;
+  }
+  if (bt == 4) {
     if (nsteps <= 1) { r = 16; ks = 1; }
-    else if (nsteps <= 16) { r = 8; ks = 2; }
-    else if (nsteps <= 32) { r = 4; ks = 4; }
+    else if (nsteps <= 16 && outputs < 16384) { r = 8; ks = 2; }
     else { r = 4; ks = 4; pf = 0; }
-    if ((nsteps + ks - 1) / ks > 8) { r = 4; ks = 2; mw = 16; }
+    gmax = 4;
   } else if (bt == 8) {
     if (nsteps <= 1) { r = 8; ks = 1; }
-    else if (nsteps <= 16) { r = 8; ks = 2; }
-    else { r = 2; ks = 4; }
-    if ((nsteps + ks - 1) / ks > 8) { r = 4; ks = 2; mw = 16; }
-  } else {
-    if (nsteps <= 1) { r = 4; ks = 1; }
-    else { r = 4; ks = 2; }
-    if ((nsteps + ks - 1) / ks > 8) { r = 2; ks = 2; mw = 16; }
+    else if (nsteps <= 3) { r = 8; ks = 2; }
+    else if (silu && nsteps <= 16) { r = 4; ks = 2; gmax = 2; }
+    else { r = 2; ks = 4; pf = 0; }
+  } else if (bt == 16) {
+    if (nsteps <= 1) { r = 4; ks = 1; } else { r = 4; ks = 2; }
+    if (silu) gmax = 2;
   }
   if ((nsteps + ks - 1) / ks > mw) return VTE_EINVAL;
-  const int rout = (epi == VTE_EPI_SILU_MUL) ? r / 2 : r;
-  int groups = outputs / (rout * 2048);
-  groups = groups < 1 ? 1 : (groups > 4 ? 4 : groups);
+  const int rout = silu ? r / 2 : r;
+  int groups = outputs / (rout * 256);
+  groups = groups < 1 ? 1 : (groups > gmax ? gmax : groups);
   p->batch_tile = bt; p->rows = r; p->ksteps = ks; p->prefetch = pf; p->max_waves = mw; p->groups = groups;
   return VTE_OK;
 }
@@ -181,11 +187,12 @@ int build_gemv(vte_ctx* ctx, const GemvBuild& g, vte_desc** out) {
   const int n_out = (g.epilogue == VTE_EPI_SILU_MUL) ? g.N / 2 : g.N;
   vte_gemv_plan p;
   if (g.plan) p = *g.plan;
-  else if (plan_gemv(g.B, n_out, g.K / g.S, g.epilogue, &p) != VTE_OK) { set_error("gemv: K / S must be at most 32768"); return VTE_EINVAL; }
+  else if (plan_gemv(g.B, n_out, g.K / g.S, g.epilogue, &p) != VTE_OK) { set_error("gemv: K / S must be at most 16384"); return VTE_EINVAL; }
   const int kps = g.K / g.S;
   const int waves = plan_waves(p, kps);
-  if (p.batch_tile < g.B || p.groups < 1 || p.rows < 1 || p.ksteps < 1 || waves < 1 || waves > p.max_waves) {
-    set_error("gemv plan: batch_tile >= B, groups >= 1 and ceil(K/S/512/ksteps) <= max_waves are required"); return VTE_EINVAL;
+  const int zchunks = (g.B + p.batch_tile - 1) / (p.batch_tile > 0 ? p.batch_tile : 1);
+  if (p.batch_tile < 1 || p.groups < 1 || p.rows < 1 || p.ksteps < 1 || waves < 1 || waves > p.max_waves) {
+    set_error("gemv plan: groups >= 1 and ceil(K/S/512/ksteps) <= max_waves are required"); return VTE_EINVAL;
   }
   const int rout = (g.epi_kernel == 1) ? p.rows / 2 : p.rows;
   if (rout < 1) { set_error("gemv plan: the SiLU epilogue needs an even number of rows"); return VTE_EINVAL; }
@@ -202,13 +209,13 @@ int build_gemv(vte_ctx* ctx, const GemvBuild& g, vte_desc** out) {
   a.ldx = g.ldx > 0 ? g.ldx : g.K;
   a.ldy = g.ldy > 0 ? g.ldy : n_out;
   if (a.ldx < g.K || a.ldx % 8 != 0 || a.ldy < n_out) { set_error("gemv: need ldx >= K, ldx % 8 == 0, ldy >= outputs per row"); return VTE_EINVAL; }
-  a.groups = p.groups; a.S = g.S; a.k_per_split = kps; a.bt = p.batch_tile;
+  a.groups = p.groups; a.S = g.S; a.k_per_split = kps; a.bt = p.batch_tile * zchunks;
   const uint64_t shape = fnv1a(&a.B, sizeof(int) * 9);
   uint64_t bytes = 2ull * g.N * g.K + 2ull * g.B * g.K + (lm ? 4ull * g.B : 2ull * g.B * n_out);
   if (lm && g.logits) bytes += 4ull * g.B * g.N;
   const uint64_t flops = 2ull * g.B * g.N * g.K;
   return finish_desc(ctx, g.kernel, gemv_entry(p, g.epi_kernel), a, gx, static_cast<uint32_t>(g.S),
-                     static_cast<uint32_t>(waves * 64), 0, shape, bytes, flops, out);
+                     static_cast<uint32_t>(waves * 64), 0, shape, bytes, flops, out, static_cast<uint32_t>(zchunks));
 }
 
 }  // namespace
@@ -243,7 +250,7 @@ int vte_gemv_default_plan(int B, int N, int K, int epilogue, int S, vte_gemv_pla
   const int n_out = (epilogue == VTE_EPI_SILU_MUL) ? N / 2 : N;
   if (S < 1 || K % S != 0) { set_error("gemv plan: S must divide K"); return VTE_EINVAL; }
   int rc = plan_gemv(B, n_out, K / S, epilogue, plan);
-  if (rc != VTE_OK) set_error("gemv plan: need 1 <= B <= 16, N >= 1, 8 <= K / S <= 32768");
+  if (rc != VTE_OK) set_error("gemv plan: need 1 <= B <= 16, N >= 1, 8 <= K / S <= 16384");
   return rc;
 }
 
@@ -328,7 +335,7 @@ int vte_desc_argmax_finish(vte_ctx* ctx, const vte_desc* lmhead, vte_desc** out)
   std::memcpy(&g, lmhead->args, sizeof g);
   // candidates sit behind the ticket words: [1 + grid.x] uint32, then [grid.x][batch tile][2]
   ArgmaxFinishArgs a{};
-  a.pairs = g.ws + 1 + lmhead->grid[0];
+  a.pairs = g.ws + 1 + lmhead->grid[0] * lmhead->grid[2];
   a.tok = g.tok;
   a.nblocks = static_cast<int>(lmhead->grid[0]);
   a.bt = g.bt;

@@ -101,6 +101,9 @@ __global__ __launch_bounds__(MAXW * 64) void gemv_kernel(const GemvArgs a) {
   const int split = blockIdx.y;
   const int k_begin = split * a.k_per_split;
   const int k_end = k_begin + a.k_per_split;
+  // batch rows [b0, b0 + nb) of this workgroup (a second batch chunk re-reads the weights)
+  const int b0 = blockIdx.z * BT;
+  const int nb = (a.B - b0) < BT ? (a.B - b0) : BT;
 
   // this wave's slice of X, for every batch row, in registers
   u32x4 xs[KS][BT];
@@ -110,7 +113,7 @@ __global__ __launch_bounds__(MAXW * 64) void gemv_kernel(const GemvArgs a) {
     koff[s] = k_begin + (wave * KS + s) * 512 + lane * 8;
 #pragma unroll
     for (int b = 0; b < BT; ++b)
-      xs[s][b] = (koff[s] < k_end && b < a.B) ? ld16(a.X + static_cast<size_t>(b) * a.ldx + koff[s])
+      xs[s][b] = (koff[s] < k_end && b < nb) ? ld16(a.X + static_cast<size_t>(b0 + b) * a.ldx + koff[s])
                                               : u32x4{0u, 0u, 0u, 0u};
   }
 
@@ -139,8 +142,8 @@ __global__ __launch_bounds__(MAXW * 64) void gemv_kernel(const GemvArgs a) {
   };
 
   // lane j < NV of the finishing wave owns (slot r = j / BT, batch row b = j % BT)
-  const int fin_r = lane / BT, fin_b = lane % BT;
-  const bool fin_live = lane < NV && fin_b < a.B;
+  const int fin_r = lane / BT, fin_b = b0 + lane % BT;  // fin_b: global batch row
+  const bool fin_live = lane < NV && (lane % BT) < nb;
   float best_v = -INFINITY;
   int best_i = INT_MAX;
   auto finish = [&](int g, float v) {  // called by all lanes of one wave
@@ -196,7 +199,7 @@ __global__ __launch_bounds__(MAXW * 64) void gemv_kernel(const GemvArgs a) {
         finish(g, s);
       } else {
         const int row = fin_live ? weight_row(g, fin_r) : -1;
-        if (row >= 0) a.partials[(static_cast<size_t>(split) * BT + fin_b) * a.N + row] = s;
+        if (row >= 0) a.partials[(static_cast<size_t>(split) * a.bt + fin_b) * a.N + row] = s;
       }
     }
     if constexpr (PF) {
@@ -212,7 +215,7 @@ __global__ __launch_bounds__(MAXW * 64) void gemv_kernel(const GemvArgs a) {
     __threadfence();
     __syncthreads();
     if (threadIdx.x == 0) {
-      const uint32_t t = atomicAdd(&a.ws[1 + blockIdx.x], 1u);
+      const uint32_t t = atomicAdd(&a.ws[1 + blockIdx.z * gridDim.x + blockIdx.x], 1u);
       s_last = (t == static_cast<uint32_t>(a.S) - 1u);
     }
     __syncthreads();
@@ -223,11 +226,11 @@ __global__ __launch_bounds__(MAXW * 64) void gemv_kernel(const GemvArgs a) {
       float v = 0.f;
       if (row >= 0) {
         for (int s = 0; s < a.S; ++s)  // chunk order
-          v += __builtin_nontemporal_load(&a.partials[(static_cast<size_t>(s) * BT + fin_b) * a.N + row]);
+          v += __builtin_nontemporal_load(&a.partials[(static_cast<size_t>(s) * a.bt + fin_b) * a.N + row]);
       }
       finish(g, v);
     }
-    if (threadIdx.x == 0) a.ws[1 + blockIdx.x] = 0u;  // ready for the next launch
+    if (threadIdx.x == 0) a.ws[1 + blockIdx.z * gridDim.x + blockIdx.x] = 0u;  // ready for the next launch
   }
 
   // ---- phase C (LM head): block argmax -> (value, index) pair per batch row in the workspace;
@@ -242,14 +245,14 @@ __global__ __launch_bounds__(MAXW * 64) void gemv_kernel(const GemvArgs a) {
     }
     if (lane < BT) { s_bv[wave][lane] = best_v; s_bi[wave][lane] = best_i; }
     __syncthreads();
-    uint32_t* pairs = a.ws + 1 + gridDim.x;  // [gridDim.x][BT][2]
+    uint32_t* pairs = a.ws + 1 + gridDim.x * gridDim.z;  // [gridDim.x][a.bt][2]
     if (threadIdx.x < BT) {
       float bv = s_bv[0][threadIdx.x];
       int bi = s_bi[0][threadIdx.x];
       for (int ww = 1; ww < nw; ++ww)
         if (better(s_bv[ww][threadIdx.x], s_bi[ww][threadIdx.x], bv, bi)) { bv = s_bv[ww][threadIdx.x]; bi = s_bi[ww][threadIdx.x]; }
-      pairs[(blockIdx.x * BT + threadIdx.x) * 2 + 0] = __float_as_uint(bv);
-      pairs[(blockIdx.x * BT + threadIdx.x) * 2 + 1] = static_cast<uint32_t>(bi);
+      pairs[(static_cast<size_t>(blockIdx.x) * a.bt + b0 + threadIdx.x) * 2 + 0] = __float_as_uint(bv);
+      pairs[(static_cast<size_t>(blockIdx.x) * a.bt + b0 + threadIdx.x) * 2 + 1] = static_cast<uint32_t>(bi);
     }
   }
 }

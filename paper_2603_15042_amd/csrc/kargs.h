@@ -28,7 +28,7 @@ struct GemvArgs {
   int ldx, ldy;           // row strides of X and Y in elements (K and n_out when dense)
   int n_out;              // outputs per batch row (N, or N/2 with SiLU-mul)
   int groups;             // row groups each workgroup walks through
-  int bt;                 // batch tile the kernel instance was built for
+  int bt;                 // batch slots of the launch: kernel batch tile x gridDim.z
   int S;                  // K split (1 = fixed structure)
   int k_per_split;        // K / S
 };

@@ -877,6 +877,20 @@ int vte_profile_measure(vte_ctx* c, const vte_desc* d, int warmup, int reps) {
   return VTE_OK;
 }
 
+int vte_profile_measure_on(vte_ctx* c, const vte_desc* d, int pctx, int warmup, int reps, double* seconds) {
+  if (!c || !d || d->ctx != c || !seconds || warmup < 0 || reps < 1 || pctx < 0 || pctx >= c->pool.size()) {
+    set_error("profile_measure_on: bad argument"); return VTE_EINVAL;
+  }
+  if (c->backend->is_fake()) { set_error("profiles cannot be measured on the fake backend"); return VTE_ESTATE; }
+  vte_device_sync(c);
+  Lock lk(c->mu);
+  if (!c->inflight.empty()) { set_error("profile_measure needs an idle device"); return VTE_EBUSY; }
+  c->backend->make_current();
+  int rc = c->backend->time_launches(d, c->pool.at(pctx).stream, warmup, reps, seconds);
+  if (rc == VTE_OK) c->profiles[{d->profile_key, c->pool.at(pctx).width}] = *seconds;
+  return rc;
+}
+
 // ---- statistics -----------------------------------------------------------------------
 
 int vte_stats(vte_ctx* c, vte_stats_t* out) {

@@ -108,7 +108,7 @@ EXPORTS = [
     "vte_vstream_create", "vte_vstream_destroy", "vte_vstream_id", "vte_vstream_pin", "vte_submit",
     "vte_submit_after", "vte_token_query", "vte_token_wait", "vte_vstream_sync", "vte_device_sync",
     "vte_pctx_close_gate", "vte_pctx_reserve", "vte_pctx_unreserve", "vte_set_policy", "vte_set_builtin_policy",
-    "vte_hint_submit", "vte_profile_measure", "vte_profile_set", "vte_profile_get", "vte_stats", "vte_stats_read",
+    "vte_hint_submit", "vte_profile_measure", "vte_profile_measure_on", "vte_profile_set", "vte_profile_get", "vte_stats", "vte_stats_read",
     "vte_stats_reset", "vte_fake_complete", "vte_fake_set_autocomplete", "vte_fake_fail_next_submits",
     "vte_fake_log", "vte_dispatcher_quiesce", "vte_now",
 ]
@@ -388,6 +388,12 @@ def vte_hint_submit(ctx, hint):
 
 def vte_profile_measure(ctx, desc, warmup=3, reps=10):
     _check(load().vte_profile_measure(ctx, desc, int(warmup), int(reps)))
+
+
+def vte_profile_measure_on(ctx, desc, pctx_id, warmup=3, reps=10):
+    s = C.c_double()
+    _check(load().vte_profile_measure_on(ctx, desc, int(pctx_id), int(warmup), int(reps), C.byref(s)))
+    return s.value
 
 
 def vte_profile_set(ctx, key, width, seconds):

@@ -213,11 +213,10 @@ def test_gemv_splitk_reshaping_drifts_and_fixed_does_not(H, ctx, B):
         vte.vte_desc_destroy(d)
     print("split-K drift of fp32 sums (elements, bits) vs fixed, B=%d:" % B, drift32)
     assert drift32[32] == (0, 0)
-    # S = 2 always regroups the per-slice sums.  A larger S coincides with the fixed tree exactly
-    # when K/S equals the fixed kernel's own K-slice (adding one-slice chunks in order IS the fixed
-    # order): S = 8 at batch <= 2 (512-wide slices), S = 4 at batch 8 (1024-wide slices).
-    assert drift32[64][1] > 0                               # regrouping moves bits on random data
-    assert sum(1 for w in (64, 128, 256) if drift32[w][1] > 0) >= 2
+    # An S coincides with the fixed tree exactly when K/S equals the fixed kernel's own K-slice
+    # (adding one-slice chunks in order IS the fixed order): S = 2 at batch 8 (2048-wide slices),
+    # S = 4 at batch 1 (1024-wide slices).  Every other S regroups the sum.
+    assert sum(1 for w in (64, 128, 256) if drift32[w][1] > 0) >= 2   # regrouping moves bits on random data
     # negative control: exact inputs -> no drift for any S
     Wi = inputs.int_bf16(5, inputs.T_W, (N, K), -8, 8)
     Xi = inputs.int_bf16(5, inputs.T_XB, (B, K), -8, 8, -2)
