@@ -1,9 +1,9 @@
 """Benchmark of the decode hot path on one MI355X.
 
-A step is one pass of the Llama-8B-shaped decode chain at batch 8 (gather,
-RMSNorm, QKV, O, gate/up+SiLU, down, LM head + argmax: seven immutable
-descriptors submitted to a virtual stream and late-bound by the dispatcher), on
-synthetic weights resident in HBM.  Prints one JSON line.
+A step is one pass of the Llama-8B-shaped decode chain at batch 8 (embedding
+gather fused into RMSNorm, QKV, O, gate/up+SiLU, down, LM head, argmax finish:
+seven immutable descriptors submitted to a virtual stream and late-bound by the
+dispatcher), on synthetic weights resident in HBM.  Prints one JSON line.
 """
 import argparse
 import json
@@ -28,6 +28,8 @@ def main():
     ap.add_argument("--no-kernel-timing", action="store_true", help="do not bracket the LM head with device events")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-width-sweep", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run three 1 GiB device-to-device copies (a known-size reference for HBM byte counters)")
     ap.add_argument("--small", action="store_true", help="reduced shapes (debugging only; not a valid result)")
     a = ap.parse_args()
     if a.gpus != 1:
@@ -55,7 +57,7 @@ def main():
     torch.zeros(1, device="cuda")
     ctx = vte.vte_init(0, cfg)
     wd = H.upload_weights(w)
-    ch = H.DecodeChain(ctx, wd, shp, B, feedback=True)
+    ch = H.DecodeChain(ctx, wd, shp, B, feedback=True, fused_gather=True)
     vs = vte.vte_vstream_create(ctx, vte.VTE_CLASS_LATENCY)
 
     def run(steps, vstream):
@@ -80,6 +82,13 @@ def main():
     step_bytes = ch.bytes_per_step
     value = step_bytes * a.steps / dt / 1e9
     tokens_end = ch.tok.cpu().numpy().copy()
+    if a.calibration_copy:
+        src = torch.zeros(1 << 30, dtype=torch.int8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     out = {
         "metric": "GEMV/RMSNorm HBM GB/s (% peak) per CU width; bit mismatches across widths (=0)",

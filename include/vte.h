@@ -162,6 +162,12 @@ int vte_pctx_native_stream(vte_ctx* ctx, int pctx_id, void** hip_stream);
  * (Operator family: Sec. 1 / Sec. 2.3 "reductions".) */
 int vte_desc_rmsnorm(vte_ctx* ctx, const void* x, const void* gamma, void* y, int rows,
                      int cols, float eps, vte_desc** out);
+/* The same RMSNorm with the embedding gather fused in front: row b of the input
+ * is E[tok[b], :] (E: device [V,cols] bf16; tok: device [B] int32, clamped to
+ * [0,V)); h_or_null: optional device [B,cols] copy of the gathered rows.  One
+ * launch instead of gather + norm; the arithmetic and its tree are unchanged. */
+int vte_desc_rmsnorm_gather(vte_ctx* ctx, const void* E, const int32_t* tok, const void* gamma, void* y,
+                            void* h_or_null, int B, int V, int cols, float eps, vte_desc** out);
 /* y = (x - mu) * rsqrt(var + eps) * gamma + beta, biased variance, two fixed-tree
  * fp32 reductions (mean, then centred squares).  Same layout and limits. (Sec. 1) */
 int vte_desc_layernorm(vte_ctx* ctx, const void* x, const void* gamma, const void* beta,
@@ -265,7 +271,7 @@ int vte_desc_rmsnorm_reshaped(vte_ctx* ctx, const void* x, const void* gamma, vo
 enum {
   VTE_K_RMSNORM = 1, VTE_K_LAYERNORM = 2, VTE_K_GEMV = 3, VTE_K_LMHEAD = 4, VTE_K_GATHER = 5,
   VTE_K_GEMM = 6, VTE_K_GEMV_SPLITK = 7, VTE_K_LMHEAD_SPLITK = 8, VTE_K_RMSNORM_RESHAPED = 9,
-  VTE_K_ARGMAX_FINISH = 10
+  VTE_K_ARGMAX_FINISH = 10, VTE_K_RMSNORM_GATHER = 11
 };
 typedef struct vte_desc_view {
   int kernel;           /* VTE_K_* */

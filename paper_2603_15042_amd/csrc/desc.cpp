@@ -88,7 +88,8 @@ int norm_threads(int cols) {
 }
 
 int build_norm(vte_ctx* ctx, int kernel, bool layer, const void* x, const void* gamma, const void* beta,
-               void* y, int rows, int cols, float eps, int threads, vte_desc** out) {
+               void* y, int rows, int cols, float eps, int threads, vte_desc** out,
+               const int32_t* tok = nullptr, void* h_out = nullptr, int V = 0) {
   if (!ctx || !out || !x || !gamma || !y || (layer && !beta)) { set_error("norm: null argument"); return VTE_EINVAL; }
   if (rows <= 0 || cols <= 0 || cols % 8 != 0 || cols > 16384) { set_error("norm: need rows > 0, cols % 8 == 0, cols <= 16384"); return VTE_EINVAL; }
   if (!aligned16(x) || !aligned16(gamma) || !aligned16(y) || (layer && !aligned16(beta))) { set_error("norm: pointers must be 16-byte aligned"); return VTE_EINVAL; }
@@ -100,6 +101,8 @@ int build_norm(vte_ctx* ctx, int kernel, bool layer, const void* x, const void* 
   a.beta = static_cast<const uint16_t*>(beta);
   a.y = static_cast<uint16_t*>(y);
   a.rows = rows; a.cols = cols; a.eps = eps; a.inv_cols = 1.0f / static_cast<float>(cols);
+  a.tok = tok; a.h_out = static_cast<uint16_t*>(h_out); a.V = V;
+  if (h_out && !aligned16(h_out)) { set_error("norm: pointers must be 16-byte aligned"); return VTE_EINVAL; }
   const uint64_t shape = (static_cast<uint64_t>(rows) << 32) | static_cast<uint32_t>(cols);
   const uint64_t bytes = static_cast<uint64_t>(rows) * cols * 4 + static_cast<uint64_t>(cols) * (layer ? 4 : 2);
   return finish_desc(ctx, kernel, vte_norm_entry(threads, layer ? 1 : 0), a, static_cast<uint32_t>(rows), 1,
@@ -230,6 +233,13 @@ int vte_desc_rmsnorm(vte_ctx* ctx, const void* x, const void* gamma, void* y, in
   return build_norm(ctx, VTE_K_RMSNORM, false, x, gamma, nullptr, y, rows, cols, eps, norm_threads(cols), out);
 }
 
+int vte_desc_rmsnorm_gather(vte_ctx* ctx, const void* E, const int32_t* tok, const void* gamma, void* y,
+                            void* h_or_null, int B, int V, int cols, float eps, vte_desc** out) {
+  if (!tok || V < 1) { set_error("rmsnorm_gather: tok and V >= 1 are required"); return VTE_EINVAL; }
+  return build_norm(ctx, VTE_K_RMSNORM_GATHER, false, E, gamma, nullptr, y, B, cols, eps, norm_threads(cols), out,
+                    tok, h_or_null, V);
+}
+
 int vte_desc_layernorm(vte_ctx* ctx, const void* x, const void* gamma, const void* beta, void* y, int rows,
                        int cols, float eps, vte_desc** out) {
   return build_norm(ctx, VTE_K_LAYERNORM, true, x, gamma, beta, y, rows, cols, eps, norm_threads(cols), out);
@@ -341,7 +351,7 @@ int vte_desc_argmax_finish(vte_ctx* ctx, const vte_desc* lmhead, vte_desc** out)
   a.bt = g.bt;
   a.B = g.B;
   const uint64_t shape = (static_cast<uint64_t>(a.nblocks) << 32) | static_cast<uint32_t>(a.B * 64 + a.bt);
-  return finish_desc(ctx, VTE_K_ARGMAX_FINISH, vte_argmax_finish_entry(), a, static_cast<uint32_t>(a.B), 1, 256, 0,
+  return finish_desc(ctx, VTE_K_ARGMAX_FINISH, vte_argmax_finish_entry(), a, static_cast<uint32_t>(a.B), 1, 1024, 0,
                      shape, 8ull * a.nblocks * a.B + 4ull * a.B, 0, out);
 }
 

@@ -245,14 +245,16 @@ __global__ __launch_bounds__(MAXW * 64) void gemv_kernel(const GemvArgs a) {
     }
     if (lane < BT) { s_bv[wave][lane] = best_v; s_bi[wave][lane] = best_i; }
     __syncthreads();
-    uint32_t* pairs = a.ws + 1 + gridDim.x * gridDim.z;  // [gridDim.x][a.bt][2]
+    // candidates: values [a.bt][gridDim.x] then indices [a.bt][gridDim.x], so the finish reads rows
+    uint32_t* cand_v = a.ws + 1 + gridDim.x * gridDim.z;
+    uint32_t* cand_i = cand_v + static_cast<size_t>(a.bt) * gridDim.x;
     if (threadIdx.x < BT) {
       float bv = s_bv[0][threadIdx.x];
       int bi = s_bi[0][threadIdx.x];
       for (int ww = 1; ww < nw; ++ww)
         if (better(s_bv[ww][threadIdx.x], s_bi[ww][threadIdx.x], bv, bi)) { bv = s_bv[ww][threadIdx.x]; bi = s_bi[ww][threadIdx.x]; }
-      pairs[(static_cast<size_t>(blockIdx.x) * a.bt + b0 + threadIdx.x) * 2 + 0] = __float_as_uint(bv);
-      pairs[(static_cast<size_t>(blockIdx.x) * a.bt + b0 + threadIdx.x) * 2 + 1] = static_cast<uint32_t>(bi);
+      cand_v[static_cast<size_t>(b0 + threadIdx.x) * gridDim.x + blockIdx.x] = __float_as_uint(bv);
+      cand_i[static_cast<size_t>(b0 + threadIdx.x) * gridDim.x + blockIdx.x] = static_cast<uint32_t>(bi);
     }
   }
 }

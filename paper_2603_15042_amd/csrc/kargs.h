@@ -10,7 +10,9 @@ struct NormArgs {
   const uint16_t* gamma;
   const uint16_t* beta;   // LayerNorm only
   uint16_t* y;
-  int rows, cols;
+  const int32_t* tok;     // fused gather: row r is x[tok[r], :] (x = embedding table of V rows); else null
+  uint16_t* h_out;        // fused gather: optional copy of the gathered rows
+  int rows, cols, V;
   float eps;
   float inv_cols;
 };
@@ -51,7 +53,7 @@ struct GemmArgs {
 // Second stage of the greedy token: reduce the per-workgroup (value, index)
 // candidates the LM head left in its workspace.
 struct ArgmaxFinishArgs {
-  const uint32_t* pairs;  // [nblocks][bt][2]: fp32 bits, int32 index
+  const uint32_t* pairs;  // values [bt][nblocks] (fp32 bits), then indices [bt][nblocks]
   int32_t* tok;           // [B]
   int nblocks, bt, B;
 };

@@ -15,17 +15,29 @@ __global__ __launch_bounds__(256) void gather_kernel(const GatherArgs a) {
 // Greedy token, second stage: one workgroup per batch row scans the candidates of
 // every LM-head workgroup.  (value, index) pairs are totally ordered (larger
 // value, then lower index; NaN never wins), so the scan order cannot matter.
-__global__ __launch_bounds__(256) void argmax_finish_kernel(const ArgmaxFinishArgs a) {
-  __shared__ float s_v[4];
-  __shared__ int s_i[4];
+__global__ __launch_bounds__(1024) void argmax_finish_kernel(const ArgmaxFinishArgs a) {
+  __shared__ float s_v[16];
+  __shared__ int s_i[16];
   const int b = blockIdx.x;
   if (b >= a.B) return;
+  const uint32_t* cv = a.pairs + static_cast<size_t>(b) * a.nblocks;
+  const uint32_t* ci = a.pairs + static_cast<size_t>(a.bt) * a.nblocks + static_cast<size_t>(b) * a.nblocks;
   float bv = -INFINITY;
   int bi = 0x7fffffff;
-  for (int blk = threadIdx.x; blk < a.nblocks; blk += 256) {
-    const float v = __uint_as_float(a.pairs[(static_cast<size_t>(blk) * a.bt + b) * 2 + 0]);
-    const int i = static_cast<int>(a.pairs[(static_cast<size_t>(blk) * a.bt + b) * 2 + 1]);
-    if (better(v, i, bv, bi)) { bv = v; bi = i; }
+  // eight independent candidates per thread and pass: all loads of a pass are in flight together
+  for (int base = 0; base < a.nblocks; base += 8 * 1024) {
+    float v[8];
+    int idx[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int blk = base + j * 1024 + threadIdx.x;
+      const bool in = blk < a.nblocks;
+      v[j] = in ? __uint_as_float(cv[blk]) : -INFINITY;
+      idx[j] = in ? static_cast<int>(ci[blk]) : 0x7fffffff;
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if (better(v[j], idx[j], bv, bi)) { bv = v[j]; bi = idx[j]; }
   }
 #pragma unroll
   for (int d = 1; d < 64; d <<= 1) {
@@ -36,7 +48,7 @@ __global__ __launch_bounds__(256) void argmax_finish_kernel(const ArgmaxFinishAr
   if ((threadIdx.x & 63) == 0) { s_v[threadIdx.x >> 6] = bv; s_i[threadIdx.x >> 6] = bi; }
   __syncthreads();
   if (threadIdx.x == 0) {
-    for (int w = 1; w < 4; ++w)
+    for (int w = 1; w < 16; ++w)
       if (better(s_v[w], s_i[w], bv, bi)) { bv = s_v[w]; bi = s_i[w]; }
     a.tok[b] = (bi == 0x7fffffff) ? 0 : bi;
   }

@@ -2,6 +2,8 @@
 // (operator family: Sec. 1 and Sec. 2.3 of the paper; reshaped variant: the
 // negative control of Sec. 7.1).
 //
+// With a token list the input row is fetched from an embedding table (gather
+// fused into the norm); the arithmetic is the same.
 // One workgroup of T threads per row.  Thread t owns the 8-element chunks
 // t, t+T, t+2T, ... of the row (128-bit loads, coalesced across the wave) and
 // keeps them in registers, so the row is read from HBM exactly once.
@@ -38,7 +40,12 @@ __global__ __launch_bounds__(T) void norm_kernel(const NormArgs a) {
   const int row = blockIdx.x;
   if (row >= a.rows) return;
   const int nchunks = a.cols >> 3;
-  const uint16_t* xr = a.x + static_cast<size_t>(row) * a.cols;
+  size_t src_row = row;
+  if (a.tok) {  // fused embedding gather: the row comes from the table
+    int t = a.tok[row];
+    src_row = t < 0 ? 0 : (t >= a.V ? a.V - 1 : t);
+  }
+  const uint16_t* xr = a.x + src_row * a.cols;
   uint16_t* yr = a.y + static_cast<size_t>(row) * a.cols;
 
   u32x4 xv[kMaxChunks];
@@ -46,6 +53,7 @@ __global__ __launch_bounds__(T) void norm_kernel(const NormArgs a) {
   for (int j = 0; j < kMaxChunks; ++j) {
     const int c = threadIdx.x + j * T;
     xv[j] = (c < nchunks) ? ld16(xr + c * 8) : u32x4{0u, 0u, 0u, 0u};
+    if (a.h_out && c < nchunks) st16(a.h_out + static_cast<size_t>(row) * a.cols + c * 8, xv[j]);
   }
 
   float mu = 0.f;

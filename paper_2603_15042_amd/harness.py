@@ -73,7 +73,7 @@ class DecodeChain:
 
 
     def __init__(self, ctx, weights_dev, shp, B, eps=1e-6, want_logits=False, splitk=None, rms_active_cus=None,
-                 feedback=False):
+                 feedback=False, fused_gather=False):
         self.ctx, self.shp, self.B = ctx, shp, B
         D, Nq, F, V = shp.D, shp.Nqkv, shp.F, shp.V
         w = self.w = weights_dev
@@ -87,8 +87,13 @@ class DecodeChain:
         self.ws = dev_zeros_bytes(vte.vte_lmhead_workspace_bytes(B, V, D))
         self.extra = []
         d = self.desc = {}
-        d["gather"] = vte.vte_desc_gather(ctx, w["E"], self.tok, self.h0, B, V, D)
-        if rms_active_cus is None:
+        if fused_gather:  # gather folded into the norm launch (h0 still written, for inspection)
+            d["rmsnorm"] = vte.vte_desc_rmsnorm_gather(ctx, w["E"], self.tok, w["gamma"], self.n, self.h0, B, V, D, eps)
+        else:
+            d["gather"] = vte.vte_desc_gather(ctx, w["E"], self.tok, self.h0, B, V, D)
+        if fused_gather:
+            pass
+        elif rms_active_cus is None:
             d["rmsnorm"] = vte.vte_desc_rmsnorm(ctx, self.h0, w["gamma"], self.n, B, D, eps)
         else:
             d["rmsnorm"] = vte.vte_desc_rmsnorm_reshaped(ctx, self.h0, w["gamma"], self.n, B, D, eps, rms_active_cus)

@@ -376,6 +376,24 @@ def test_chain_teacher_forced_per_operator(H, ctx, small_chain, B):
     ch.close()
 
 
+def test_fused_gather_norm_equals_two_launches(H, ctx, small_chain):
+    shp, w, wd = small_chain
+    B = 5
+    tok = inputs.tokens(9, inputs.T_TOK0, B, shp.V)
+    snaps = []
+    for fused in (False, True):
+        ch = H.DecodeChain(ctx, wd, shp, B, want_logits=True, fused_gather=fused)
+        assert len(ch.order) == (7 if fused else 8)
+        ch.set_tokens(tok)
+        ch.run_step_on(H.pctx_of_width(ctx, 64 if fused else 256))
+        snaps.append(ch.snapshot())
+        ch.close()
+    for k in ("h0", "n", "qkv", "o", "act", "d", "next"):
+        assert np.array_equal(snaps[0][k], snaps[1][k]), k
+    assert np.array_equal(snaps[0]["logits"].view(np.uint32), snaps[1]["logits"].view(np.uint32))
+    assert np.array_equal(snaps[0]["h0"], w["E"][tok])
+
+
 def test_chain_bits_do_not_depend_on_allocation(H, ctx, small_chain):
     shp, w, wd = small_chain
     B = 8
