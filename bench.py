@@ -18,11 +18,23 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 
 
+def _counter_traffic():
+    """HBM bytes per LM-head launch from the committed rocprofv3 counter summary (None if absent)."""
+    path = os.path.join(ROOT, "profiles", "decode_chain_b8_hbm_counters.txt")
+    try:
+        for line in open(path):
+            if line.startswith("lmhead_traffic_bytes_per_launch="):
+                return int(line.split("=")[1])
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=400)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=300)
     ap.add_argument("--batch", type=int, default=8)
     ap.add_argument("--mode", choices=("pipelined", "strict"), default="pipelined")
     ap.add_argument("--no-kernel-timing", action="store_true", help="do not bracket the LM head with device events")
@@ -95,14 +107,15 @@ def main():
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": round(dt / a.steps * 1e3, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "Llama-8B-shaped decode chain (RMSNorm 4096 -> QKV 4096x6144 -> O 4096x4096 -> "
-                               "gate/up 4096x2x14336 SiLU -> down 14336x4096 -> LM head 4096x128256 + argmax), "
-                               "batch %d, full width (256 CUs), %s binding" % (B, a.mode),
+        "config": {"workload": "Llama-8B-shaped decode chain (gather+RMSNorm 4096 -> QKV 4096x6144 -> O 4096x4096 -> "
+                               "gate/up 4096x2x14336 SiLU -> down 14336x4096 -> LM head 4096x128256 -> argmax), "
+                               "batch %d, 7 launches per step, full width (256 CUs), %s binding" % (B, a.mode),
                    "batch": B, "bytes_per_step": int(step_bytes), "small_shapes": bool(a.small)},
         "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
         "roofline": {"bound": "hbm", "kernel": "lm-head GEMV + argmax", "achieved": round(lm_bytes / lm_avg / 1e9, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(lm_bytes / lm_avg / 1e9 / HBM_PEAK_GBS, 4),
-                     "avg_kernel_us": round(lm_avg * 1e6, 2), "launches_timed": len(lm), "traffic": None},
+                     "avg_kernel_us": round(lm_avg * 1e6, 2), "launches_timed": len(lm), "traffic": _counter_traffic(),
+                     "algorithmic_bytes_per_launch": int(lm_bytes)},
     }
 
     # ---- per CU width: throughput and bit mismatches (outside the timed region) -------------
@@ -135,19 +148,49 @@ def main():
         out["per_width"] = per_width
         out["bit_mismatches_across_widths"] = int(mism)
 
+    # ---- other batch sizes of the same chain, full width (outside the timed region) -------------
+    if not a.no_width_sweep:
+        per_batch = {}
+        for b2 in (1, 4, 16):
+            c2 = H.DecodeChain(ctx, wd, shp, b2, feedback=True, fused_gather=True)
+            c2.set_tokens(inputs.tokens(0, inputs.T_TOK0, b2, shp.V))
+            n = max(50, a.steps // 4)
+            for _ in range(20):
+                c2.submit_step(vs)
+            vte.vte_vstream_sync(vs)
+            t = time.perf_counter()
+            for _ in range(n):
+                c2.submit_step(vs)
+            vte.vte_vstream_sync(vs)
+            e = time.perf_counter() - t
+            gbs = c2.bytes_per_step * n / e / 1e9
+            per_batch[str(b2)] = {"GB/s": round(gbs, 1), "pct_peak": round(100 * gbs / HBM_PEAK_GBS, 2),
+                                  "ms_per_step": round(e / n * 1e3, 4)}
+            c2.close()
+        out["per_batch"] = per_batch
+
     # ---- the oracle timed on the host cores (a baseline for scale only) -----------------------
     if not a.no_cpu_baseline:
         import oracle
         thr = oracle.default_threads()
         t = time.perf_counter()
-        o = oracle.decode_step(w, tok0, shp, threads=thr)
-        ct = time.perf_counter() - t
-        out["cpu_baseline"] = {"value": round(step_bytes / ct / 1e9, 3), "unit": "GB/s", "cores": thr, "kind": "oracle",
-                               "sample": "1 decode step at batch %d (all seven operators, double precision), %.1f s" % (B, ct)}
-        # first GPU step from the same tokens must pick the oracle's tokens
+        tok_c, n_cpu, first = tok0, 0, None
+        while True:                                   # free-running oracle decode, about 10 s of CPU work
+            o = oracle.decode_step(w, tok_c, shp, threads=thr)
+            first = first if first is not None else o["next"].copy()
+            tok_c = o["next"]
+            n_cpu += 1
+            ct = time.perf_counter() - t
+            if ct > 10.0 or n_cpu >= 64:
+                break
+        out["cpu_baseline"] = {"value": round(step_bytes * n_cpu / ct / 1e9, 3), "unit": "GB/s", "cores": thr,
+                               "kind": "oracle",
+                               "sample": "%d free-running decode steps at batch %d (whole chain, double precision), "
+                                         "%.1f s" % (n_cpu, B, ct)}
+        # the GPU chain from the same start tokens must pick the oracle's tokens
         ch.set_tokens(tok0)
         run(1, vs)
-        out["first_step_tokens_match_oracle"] = bool(np.array_equal(ch.tok.cpu().numpy(), o["next"]))
+        out["first_step_tokens_match_oracle"] = bool(np.array_equal(ch.tok.cpu().numpy(), first))
     out["gen_seconds"] = round(gen_s, 1)
     out["final_tokens_checksum"] = int(tokens_end.astype(np.int64).sum())
     vte.vte_vstream_destroy(vs)
