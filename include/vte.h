@@ -377,11 +377,13 @@ int vte_set_policy(vte_ctx* ctx, const vte_policy_vtbl* vtbl, void* user);
 /* Built-in policies.
  *  WIDEST      oldest ready op first; the widest eligible pCtx (pinned pCtx if pinned).
  *  QUEUE_STATE launch-granular sharing from the instantaneous queue state and the
- *              width profiles: a LATENCY op takes the narrowest pCtx whose
- *              profiled time is within `slack` of its best; a BEST_EFFORT op
+ *              width profiles: a LATENCY op stays on its predecessor's pCtx if the
+ *              profiled time there is within `slack` of the best eligible one, else
+ *              takes the narrowest eligible pCtx within `slack`; a BEST_EFFORT op
  *              takes the widest pCtx that leaves `keep_free_cus` CUs unclaimed
- *              while LATENCY ops are ready or in flight, and the widest of
- *              all otherwise. */
+ *              while LATENCY ops are ready or in flight, and the widest of all
+ *              otherwise — waiting for its own narrower lease to drain when that is
+ *              all that stands between it and a wider pCtx. */
 enum { VTE_POLICY_WIDEST = 0, VTE_POLICY_QUEUE_STATE = 1 };
 int vte_set_builtin_policy(vte_ctx* ctx, int which, double slack, int keep_free_cus);
 

@@ -256,15 +256,35 @@ int builtin_select(vte_ctx* c, const vte_ready_op* op, const int* el, int n, con
       const vte_pctx_info& p = S->pctx[el[i]];
       const double t = profile_time(c, op->desc.profile_key, p.width);
       if (t <= 0 || t > best_t * (1.0 + c->slack)) continue;
-      if (pick < 0 || p.width < S->pctx[pick].width ||
-          (p.width == S->pctx[pick].width && el[i] == op->pred_pctx)) pick = el[i];
+      if (el[i] == op->pred_pctx) return el[i];  // good enough and keeps the edge in stream order
+      if (pick < 0 || p.width < S->pctx[pick].width) pick = el[i];
     }
     return pick >= 0 ? pick : widest(op, el, n, S, total);
   }
   const bool latency_active = S->ready_by_class[VTE_CLASS_LATENCY] + S->inflight_by_class[VTE_CLASS_LATENCY] > 0;
-  int cap = latency_active ? total - c->keep_free : total;
-  int p = widest(op, el, n, S, cap);
-  return p;
+  const int cap = latency_active ? total - c->keep_free : total;
+  const int now = widest(op, el, n, S, cap);
+  // A wider allocation may be blocked only by this vstream's own (narrower) lease:
+  // then leave the op ready until that lease has drained rather than renewing it.
+  int later = -1;
+  for (int id = 0; id < c->pool.size(); ++id) {
+    const Pctx& p = c->pool.at(id);
+    if (p.width > cap || (now >= 0 && p.width <= S->pctx[now].width)) continue;
+    if (op->pinned_pctx >= 0 && id != op->pinned_pctx) continue;
+    if (p.reserved_for >= 0 && p.reserved_for != op->vstream) continue;
+    if (p.state == kDraining) continue;
+    std::vector<int> ov;
+    c->pool.active_overlapping(id, &ov);
+    bool own_only = true;
+    for (int o : ov) {
+      const Pctx& q = c->pool.at(o);
+      if (!(q.state == kLeased && q.holder == op->vstream)) { own_only = false; break; }
+    }
+    if (p.state == kLeased && p.holder != op->vstream) own_only = false;
+    if (own_only && (later < 0 || p.width > c->pool.at(later).width)) later = id;
+  }
+  if (later >= 0) return -1;
+  return now;
 }
 
 // ---- binding and submission (Sec. 4.4) ----------------------------------------------

@@ -1,0 +1,329 @@
+"""The paper's experiments on this path, on one MI355X, through the C ABI.
+
+    python -m paper_2603_15042_amd.experiments determinism [--trials 1000] [--replays 100]
+    python -m paper_2603_15042_amd.experiments cotenancy   [--seconds 3] [--gap-ms 60]
+
+determinism  Sec. 7.1 "Determinism Protocol" / Sec. 7.2: matched-input trials of a reduction
+             (RMSNorm 8x1024) and a GEMV (4096x4096, batch 1/4/8) with only the physical
+             allocation varied (random pCtx per trial, a GEMM co-tenant on the complement),
+             against the reshaping treatment (threads per row / split-K derived from the CU
+             count); then one decode state replayed with both treatments.
+cotenancy    the mixed training-inference setting (Sec. 7.3.2) in synthetic form: a stream of
+             8192^3 bf16 GEMMs as best-effort tenant, bursts of 128 decode steps at batch 8 as
+             latency tenant; solo, fixed 128/128 split, and late-bound with lookahead hints.
+Prints one JSON object.  Plumbing only: every number comes from launches of the library's
+descriptors.
+"""
+import argparse
+import json
+import sys
+import time
+
+import numpy as np
+import torch
+
+from . import harness as H
+from . import inputs, vte
+
+
+def _rand_pctx(rng, ctx):
+    return int(rng.integers(0, vte.vte_pool_count(ctx)))
+
+
+def _complement_launch(ctx, gemm_desc, pctx):
+    """Starts the co-tenant GEMM on the widest pCtx that does not overlap `pctx` (if there is one)."""
+    best, bw = -1, 0
+    for i in range(vte.vte_pool_count(ctx)):
+        if not vte.vte_pool_conflict(ctx, i, pctx):
+            w = vte.vte_pool_info(ctx, i).width
+            if w > bw:
+                best, bw = i, w
+    if best < 0:
+        return None
+    try:
+        return vte.vte_bind_and_launch(ctx, gemm_desc, best)
+    except vte.VteError:
+        return None
+
+
+def determinism(trials, replays, seed0=0):
+    ctx = H.make_ctx(vte.VTE_MODE_STRICT)
+    rng = np.random.default_rng(seed0)
+    out = {}
+    M = 2048
+    gA = H.to_dev(inputs.normal_bf16(0, inputs.T_GEMM_A, (M, M)))
+    gB = H.to_dev(inputs.normal_bf16(0, inputs.T_GEMM_B, (M, M)))
+    gC = H.dev_empty((M, M))
+    gemm = vte.vte_desc_gemm(ctx, gA, gB, gC, M, M, M)
+    p256 = H.pctx_of_width(ctx, 256)
+    widths = (32, 64, 128, 256)
+
+    # ---- operator 1: the reduction (RMSNorm 8 x 1024) -------------------------------------------
+    rows, cols = 8, 1024
+    dx, dg, dy = H.dev_empty((rows, cols)), H.dev_empty((cols,)), H.dev_empty((rows, cols))
+    fixed = vte.vte_desc_rmsnorm(ctx, dx, dg, dy, rows, cols, 1e-6)
+    resh = {w: vte.vte_desc_rmsnorm_reshaped(ctx, dx, dg, dy, rows, cols, 1e-6, w) for w in widths}
+    r = {"trials": trials, "fixed_mismatched_bits": 0, "fixed_trials_with_mismatch": 0,
+         "reshaped_mismatched_bits": 0, "reshaped_trials_with_mismatch": 0, "reshaped_max_abs_diff": 0.0}
+    for t in range(trials):
+        x, g = inputs.rmsnorm_case(seed=seed0 + t, rows=rows, cols=cols)
+        dx.copy_(H.to_dev(x)); dg.copy_(H.to_dev(g))
+        torch.cuda.synchronize()
+        H.run_on(ctx, fixed, p256)
+        ref = H.to_bits(dy).copy()
+        p = _rand_pctx(rng, ctx)
+        co = _complement_launch(ctx, gemm, p)
+        H.run_on(ctx, fixed, p)
+        got = H.to_bits(dy).copy()
+        if co:
+            vte.vte_token_wait(ctx, co)
+        e, b = H.mismatched_bits(ref, got)
+        r["fixed_mismatched_bits"] += b
+        r["fixed_trials_with_mismatch"] += int(b > 0)
+        w = widths[int(rng.integers(0, 4))]
+        H.run_on(ctx, resh[256], p256)
+        ref_r = H.to_bits(dy).copy()
+        H.run_on(ctx, resh[w], H.pctx_of_width(ctx, w))
+        got_r = H.to_bits(dy).copy()
+        e, b = H.mismatched_bits(ref_r, got_r)
+        r["reshaped_mismatched_bits"] += b
+        r["reshaped_trials_with_mismatch"] += int(b > 0)
+        d = np.abs(inputs.bf16_to_f32(ref_r) - inputs.bf16_to_f32(got_r)).max()
+        r["reshaped_max_abs_diff"] = max(r["reshaped_max_abs_diff"], float(d))
+    out["rmsnorm_8x1024"] = r
+
+    # ---- operator 2: GEMV 4096 x 4096 (fp32 sums kept through the LM-head form) --------------------
+    N = K = 4096
+    W0 = inputs.normal_bf16(seed0, inputs.T_W, (N, K), 0.0, K ** -0.5)
+    dW = H.to_dev(W0)
+    for B in (1, 4, 8):
+        dX, dY = H.dev_empty((B, K)), H.dev_empty((B, N))
+        tok = torch.zeros(B, dtype=torch.int32, device="cuda")
+        lg = torch.zeros((B, N), dtype=torch.float32, device="cuda")
+        ws = H.dev_zeros_bytes(vte.vte_lmhead_workspace_bytes(B, N, K))
+        fixed = vte.vte_desc_gemv(ctx, dW, dX, dY, B, N, K)
+        fixed32 = vte.vte_desc_lmhead_argmax(ctx, dW, dX, tok, lg, ws, B, N, K)
+        sk, sk32 = {}, {}
+        for w in widths:
+            S = w // 32
+            sk[w] = vte.vte_desc_gemv_splitk(ctx, dW, dX, dY, H.dev_zeros_bytes(vte.vte_splitk_workspace_bytes(B, N, S)),
+                                             B, N, K, 0, S)
+            sk32[w] = vte.vte_desc_lmhead_argmax_splitk(ctx, dW, dX, tok, lg, ws,
+                                                        H.dev_zeros_bytes(vte.vte_splitk_workspace_bytes(B, N, S)),
+                                                        B, N, K, S)
+        r = {"trials": trials, "fixed_mismatched_bits_bf16": 0, "fixed_mismatched_bits_fp32": 0,
+             "reshaped_mismatched_bits_bf16": 0, "reshaped_mismatched_bits_fp32": 0,
+             "reshaped_trials_with_mismatch_bf16": 0, "reshaped_trials_with_mismatch_fp32": 0,
+             "reshaped_max_abs_diff_fp32": 0.0}
+        for t in range(trials):
+            X = inputs.normal_bf16(seed0 + t, inputs.T_XB, (B, K))
+            dX.copy_(H.to_dev(X))
+            torch.cuda.synchronize()
+            H.run_on(ctx, fixed, p256); ref = H.to_bits(dY).copy()
+            H.run_on(ctx, fixed32, p256); ref32 = lg.cpu().numpy().copy()
+            p = _rand_pctx(rng, ctx)
+            co = _complement_launch(ctx, gemm, p)
+            H.run_on(ctx, fixed, p); got = H.to_bits(dY).copy()
+            H.run_on(ctx, fixed32, p); got32 = lg.cpu().numpy().copy()
+            if co:
+                vte.vte_token_wait(ctx, co)
+            r["fixed_mismatched_bits_bf16"] += H.mismatched_bits(ref, got)[1]
+            r["fixed_mismatched_bits_fp32"] += H.mismatched_bits(ref32, got32)[1]
+            w = widths[int(rng.integers(0, 4))]
+            pw = H.pctx_of_width(ctx, w)
+            H.run_on(ctx, sk[w], pw); got = H.to_bits(dY).copy()
+            H.run_on(ctx, sk32[w], pw); got32 = lg.cpu().numpy().copy()
+            b16, b32 = H.mismatched_bits(ref, got)[1], H.mismatched_bits(ref32, got32)[1]
+            r["reshaped_mismatched_bits_bf16"] += b16
+            r["reshaped_mismatched_bits_fp32"] += b32
+            r["reshaped_trials_with_mismatch_bf16"] += int(b16 > 0)
+            r["reshaped_trials_with_mismatch_fp32"] += int(b32 > 0)
+            r["reshaped_max_abs_diff_fp32"] = max(r["reshaped_max_abs_diff_fp32"], float(np.abs(ref32 - got32).max()))
+        out["gemv_4096x4096_B%d" % B] = r
+
+    # ---- decoding level: one state replayed (reduced vocabulary keeps it short) ------------------------
+    shp = inputs.DecodeShapes(D=4096, Nqkv=6144, F=14336, V=32064)
+    w = inputs.decode_weights(seed0, shp)
+    wd = H.upload_weights(w)
+    B = 8
+    tok0 = inputs.tokens(seed0, inputs.T_TOK0, B, shp.V)
+    base = H.DecodeChain(ctx, wd, shp, B, want_logits=True)
+    base.set_tokens(tok0)
+    base.run_step_on(p256)
+    s0 = base.snapshot()
+    chains = {S: H.DecodeChain(ctx, wd, shp, B, want_logits=True, splitk=S, rms_active_cus=32 * S) for S in (1, 2, 4, 8)}
+    r = {"replays": replays, "fixed_logit_mismatched_bits": 0, "fixed_token_flips": 0,
+         "reshaped_logit_mismatched_bits": 0, "reshaped_token_flips": 0, "reshaped_max_logit_diff": 0.0,
+         "reshaped_replays_with_logit_drift": 0}
+    chains[1].set_tokens(tok0)
+    chains[1].run_step_on(H.pctx_of_width(ctx, 32))
+    s1 = chains[1].snapshot()
+    r["split1_equals_fixed"] = bool(np.array_equal(s1["logits"].view(np.uint32), s0["logits"].view(np.uint32)))
+    for t in range(replays):
+        ids = [_rand_pctx(rng, ctx) for _ in base.order]
+        base.set_tokens(tok0)
+        base.run_step_on(ids)
+        s = base.snapshot()
+        r["fixed_logit_mismatched_bits"] += H.mismatched_bits(s0["logits"], s["logits"])[1]
+        r["fixed_token_flips"] += int(np.count_nonzero(s0["next"] != s["next"]))
+        S = (1, 2, 4, 8)[int(rng.integers(0, 4))]
+        c = chains[S]
+        c.set_tokens(tok0)
+        c.run_step_on(H.pctx_of_width(ctx, 32 * S))
+        s = c.snapshot()
+        b = H.mismatched_bits(s0["logits"], s["logits"])[1]
+        r["reshaped_logit_mismatched_bits"] += b
+        r["reshaped_replays_with_logit_drift"] += int(b > 0)
+        r["reshaped_token_flips"] += int(np.count_nonzero(s0["next"] != s["next"]))
+        r["reshaped_max_logit_diff"] = max(r["reshaped_max_logit_diff"], float(np.abs(s0["logits"] - s["logits"]).max()))
+    top2 = np.sort(s0["logits"], axis=1)[:, -2:]
+    r["min_top2_margin_of_state"] = float((top2[:, 1] - top2[:, 0]).min())
+    out["decode_state_replay_B8_V32064"] = r
+    vte.vte_shutdown(ctx)
+    return out
+
+
+# ----------------------------------------------------------------------------------------------------
+def cotenancy(seconds, gap_ms, steps_per_burst=128, lead_ms=3.0):
+    shp = inputs.DecodeShapes()
+    w = inputs.decode_weights(0, shp)
+    B, M = 8, 8192
+    cfg = vte.vte_pool_cfg_default()
+    cfg.mode = vte.VTE_MODE_PIPELINED
+    cfg.lookahead = 16
+    torch.zeros(1, device="cuda")
+    ctx = vte.vte_init(0, cfg)
+    wd = H.upload_weights(w)
+    ch = H.DecodeChain(ctx, wd, shp, B, feedback=True, fused_gather=True)
+    gA = H.to_dev(inputs.normal_bf16(0, inputs.T_GEMM_A, (M, M)))
+    gB = H.to_dev(inputs.normal_bf16(0, inputs.T_GEMM_B, (M, M)))
+    gC = H.dev_empty((M, M))
+    gemm = vte.vte_desc_gemm(ctx, gA, gB, gC, M, M, M)
+    tok0 = inputs.tokens(0, inputs.T_TOK0, B, shp.V)
+    lat = vte.vte_vstream_create(ctx, vte.VTE_CLASS_LATENCY)
+    be = vte.vte_vstream_create(ctx, vte.VTE_CLASS_BEST_EFFORT)
+    a128 = vte.vte_pool_find(ctx, vte.VTE_PCTX_NODE, 128, 0)
+    b128 = vte.vte_pool_find(ctx, vte.VTE_PCTX_NODE, 128, 1)
+
+    # width profiles of every recurring launch (Sec. 5 "Performance Profiles")
+    prof = {}
+    for k in ch.order:
+        vte.vte_profile_measure(ctx, ch.desc[k], 2, 5)
+        key = vte.vte_desc_info(ch.desc[k]).profile_key
+        prof[k] = {wd_: round(vte.vte_profile_get(ctx, key, wd_) * 1e6, 2) for wd_ in (32, 64, 128, 192, 224, 256)}
+    vte.vte_profile_measure(ctx, gemm, 1, 3)
+    key = vte.vte_desc_info(gemm).profile_key
+    prof["gemm"] = {wd_: round(vte.vte_profile_get(ctx, key, wd_) * 1e6, 1) for wd_ in (32, 64, 128, 192, 224, 256)}
+
+    def run(mode, with_gemm=True, with_decode=True):
+        """mode: 'solo' | 'fixed' | 'late' | 'late_nohint'.  Returns dict of raw measurements."""
+        vte.vte_device_sync(ctx)
+        vte.vte_stats_reset(ctx)
+        vte.vte_vstream_pin(lat, a128 if mode == "fixed" else -1)
+        vte.vte_vstream_pin(be, b128 if mode == "fixed" else -1)
+        vte.vte_set_builtin_policy(ctx, vte.VTE_POLICY_QUEUE_STATE if mode.startswith("late") else vte.VTE_POLICY_WIDEST,
+                                   0.6, 128 if mode.startswith("late") else 0)
+        ch.set_tokens(tok0)
+        gemm_q, gemm_done = [], 0
+        bursts, burst_times = 0, []
+        t_start = time.perf_counter()
+        next_burst = t_start + 0.005
+        hinted = False
+        state, tail, t_burst0 = "idle", 0, 0.0
+        while True:
+            now = time.perf_counter()
+            if now - t_start > seconds and state == "idle":
+                break
+            if with_gemm:
+                while gemm_q and vte.vte_token_query(ctx, gemm_q[0]):
+                    gemm_q.pop(0)
+                    gemm_done += 1
+                while len(gemm_q) < 2:
+                    gemm_q.append(vte.vte_submit(be, gemm))
+            if with_decode:
+                if state == "idle":
+                    if mode == "late" and not hinted and now >= next_burst - lead_ms * 1e-3:
+                        vte.vte_hint_submit(ctx, vte.vte_hint(vte.vte_vstream_id(lat), 128, lead_ms * 1e-3, 0.0))
+                        hinted = True
+                    if now >= next_burst:
+                        t_burst0 = time.perf_counter()
+                        for _ in range(steps_per_burst):
+                            tail = ch.submit_step(lat)
+                        state = "busy"
+                elif vte.vte_token_query(ctx, tail):
+                    burst_times.append(time.perf_counter() - t_burst0)
+                    bursts += 1
+                    state = "idle"
+                    if hinted:
+                        for i in range(vte.vte_pool_count(ctx)):
+                            if vte.vte_pool_info(ctx, i).reserved_for == vte.vte_vstream_id(lat):
+                                vte.vte_pctx_unreserve(ctx, i)
+                        hinted = False
+                    next_burst = time.perf_counter() + gap_ms * 1e-3
+            time.sleep(0.0001)
+        elapsed = time.perf_counter() - t_start
+        for t in gemm_q:
+            vte.vte_token_wait(ctx, t)
+        vte.vte_device_sync(ctx)
+        recs = vte.vte_stats_read(ctx)
+        ends = np.array(sorted(r.t_done for r in recs if r.kernel == vte.VTE_K_ARGMAX_FINISH))
+        step_lat = np.diff(ends) if len(ends) > 1 else np.array([0.0])
+        step_lat = step_lat[step_lat < 0.5 * gap_ms * 1e-3 + 0.02] if len(step_lat) else step_lat  # drop inter-burst gaps
+        starts = {}
+        for r in recs:
+            starts.setdefault(r.vstream, []).append(r)
+        # first-step latency of each burst: submit of its first op to completion of its first argmax
+        lat_recs = sorted((r for r in recs if r.klass == vte.VTE_CLASS_LATENCY), key=lambda r: r.token)
+        first_lat = []
+        per = len(ch.order)
+        for i in range(0, len(lat_recs) - per + 1, per * steps_per_burst):
+            first_lat.append(lat_recs[i + per - 1].t_done - lat_recs[i].t_submit)
+        gw = [r.width for r in recs if r.klass == vte.VTE_CLASS_BEST_EFFORT]
+        dw = [r.width for r in recs if r.klass == vte.VTE_CLASS_LATENCY]
+        return {"elapsed_s": elapsed, "gemm_done": gemm_done, "gemm_per_s": gemm_done / elapsed, "bursts": bursts,
+                "burst_ms_mean": float(np.mean(burst_times) * 1e3) if burst_times else None,
+                "step_ms_p50": float(np.percentile(step_lat, 50) * 1e3) if len(step_lat) > 1 else None,
+                "step_ms_p99": float(np.percentile(step_lat, 99) * 1e3) if len(step_lat) > 1 else None,
+                "first_step_ms_mean": float(np.mean(first_lat) * 1e3) if first_lat else None,
+                "first_step_ms_max": float(np.max(first_lat) * 1e3) if first_lat else None,
+                "gemm_widths": {str(k): int(v) for k, v in zip(*np.unique(gw, return_counts=True))} if gw else {},
+                "decode_widths": {str(k): int(v) for k, v in zip(*np.unique(dw, return_counts=True))} if dw else {},
+                "final_tokens": ch.tok.cpu().numpy().tolist()}
+
+    res = {"profiles_us": prof, "gap_ms": gap_ms, "steps_per_burst": steps_per_burst, "lead_ms": lead_ms}
+    res["solo_gemm"] = run("solo", with_decode=False)
+    res["solo_decode"] = run("solo", with_gemm=False)
+    for mode in ("fixed", "late", "late_nohint"):
+        res[mode] = run(mode)
+    g0 = res["solo_gemm"]["gemm_per_s"]
+    d0 = res["solo_decode"]["burst_ms_mean"]
+    for mode in ("fixed", "late", "late_nohint"):
+        r = res[mode]
+        r["norm_gemm"] = r["gemm_per_s"] / g0
+        r["norm_decode"] = d0 / r["burst_ms_mean"] if r["burst_ms_mean"] else None
+        r["aggregate_normalized_throughput"] = r["norm_gemm"] + (r["norm_decode"] or 0.0)
+        # the decode token stream is a pure function of (tokens, bursts run): compare with a solo replay
+    res["gemm_tflops_solo"] = 2 * M ** 3 * g0 / 1e12
+    vte.vte_shutdown(ctx)
+    return res
+
+
+def main(argv=None):
+    ap = argparse.ArgumentParser()
+    sub = ap.add_subparsers(dest="cmd", required=True)
+    d = sub.add_parser("determinism")
+    d.add_argument("--trials", type=int, default=1000)
+    d.add_argument("--replays", type=int, default=100)
+    c = sub.add_parser("cotenancy")
+    c.add_argument("--seconds", type=float, default=3.0)
+    c.add_argument("--gap-ms", type=float, default=60.0)
+    a = ap.parse_args(argv)
+    if a.cmd == "determinism":
+        out = determinism(a.trials, a.replays)
+    else:
+        out = cotenancy(a.seconds, a.gap_ms)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
