@@ -377,13 +377,16 @@ int vte_set_policy(vte_ctx* ctx, const vte_policy_vtbl* vtbl, void* user);
 /* Built-in policies.
  *  WIDEST      oldest ready op first; the widest eligible pCtx (pinned pCtx if pinned).
  *  QUEUE_STATE launch-granular sharing from the instantaneous queue state and the
- *              width profiles: a LATENCY op stays on its predecessor's pCtx if the
- *              profiled time there is within `slack` of the best eligible one, else
- *              takes the narrowest eligible pCtx within `slack`; a BEST_EFFORT op
- *              takes the widest pCtx that leaves `keep_free_cus` CUs unclaimed
- *              while LATENCY ops are ready or in flight, and the widest of all
- *              otherwise — waiting for its own narrower lease to drain when that is
- *              all that stands between it and a wider pCtx. */
+ *              width profiles.  A LATENCY op is placed by the profiled time of its
+ *              recurring chain (the sum over the distinct descriptors its vstream
+ *              submitted lately): it stays on its predecessor's pCtx while that is
+ *              within `slack` of the best candidate, else takes the fastest pCtx
+ *              when no BEST_EFFORT work is ready or in flight and the narrowest
+ *              within `slack` when there is.  A BEST_EFFORT op takes the widest
+ *              pCtx that leaves `keep_free_cus` CUs unclaimed while LATENCY ops are
+ *              ready or in flight, and the widest of all otherwise.  In both
+ *              classes an op stays ready, rather than settling for less, when the
+ *              pCtx it should get is blocked only by leases of its own vstream. */
 enum { VTE_POLICY_WIDEST = 0, VTE_POLICY_QUEUE_STATE = 1 };
 int vte_set_builtin_policy(vte_ctx* ctx, int which, double slack, int keep_free_cus);
 

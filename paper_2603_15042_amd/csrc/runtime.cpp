@@ -239,51 +239,92 @@ int widest(const vte_ready_op* op, const int* el, int n, const vte_pool_view* S,
   return best;
 }
 
+// True when pCtx `id` could take an op of `op`'s vstream were it not for leases
+// that this same vstream holds on overlapping pCtxs: those drain on their own.
+bool blocked_by_own_leases_only(vte_ctx* c, int id, const vte_ready_op* op) {
+  const Pctx& p = c->pool.at(id);
+  if (op->pinned_pctx >= 0 && id != op->pinned_pctx) return false;
+  if (p.reserved_for >= 0 && p.reserved_for != op->vstream) return false;
+  if (p.state == kDraining || p.state == kLeased || !p.gate_open) return false;
+  std::vector<int> ov;
+  c->pool.active_overlapping(id, &ov);
+  bool own_lease = false;
+  for (int o : ov) {
+    const Pctx& q = c->pool.at(o);
+    const bool only_reservation = q.state == kReserved || (q.state == kIdle && q.reservation_pending);
+    if (only_reservation && q.reserved_for == op->vstream) continue;  // its own reservation does not block it
+    if (!(q.state == kLeased && q.holder == op->vstream)) return false;
+    own_lease = true;
+  }
+  return own_lease;
+}
+
+// Profiled time at `width` of the recurring chain the op belongs to: the sum over
+// the descriptors its vstream submitted lately (Sec. 5 "Performance Profiles").
+// A width that lacks a profile for any of them gives -1.
+double chain_time(vte_ctx* c, const vte_ready_op* op, int width) {
+  double sum = 0;
+  bool own = false;
+  if (op->vstream >= 0 && op->vstream < static_cast<int>(c->vstreams.size()) && c->vstreams[op->vstream]) {
+    for (uint64_t key : c->vstreams[op->vstream]->recent_keys) {
+      const double t = profile_time(c, key, width);
+      if (key == op->desc.profile_key) { own = true; if (t <= 0) return -1.0; }
+      if (t > 0) sum += t;
+    }
+  }
+  if (!own) {
+    const double t = profile_time(c, op->desc.profile_key, width);
+    if (t <= 0) return -1.0;
+    sum += t;
+  }
+  return sum;
+}
+
 int builtin_select(vte_ctx* c, const vte_ready_op* op, const int* el, int n, const vte_pool_view* S) {
   if (n == 0) return -1;
   const int total = c->pool.total_cus();
   if (c->builtin == VTE_POLICY_WIDEST) return widest(op, el, n, S, total);
   // QUEUE_STATE
   if (op->klass == VTE_CLASS_LATENCY) {
+    // best chain time over what is eligible now or will be once this vstream's own leases drain
     double best_t = -1;
     for (int i = 0; i < n; ++i) {
-      const double t = profile_time(c, op->desc.profile_key, S->pctx[el[i]].width);
+      const double t = chain_time(c, op, S->pctx[el[i]].width);
       if (t > 0 && (best_t < 0 || t < best_t)) best_t = t;
     }
     if (best_t < 0) return widest(op, el, n, S, total);  // no profile: take what scales best
+    double best_later = -1;
+    for (int id = 0; id < c->pool.size(); ++id) {
+      if (!blocked_by_own_leases_only(c, id, op)) continue;
+      const double t = chain_time(c, op, c->pool.at(id).width);
+      if (t > 0 && (best_later < 0 || t < best_later)) best_later = t;
+    }
+    if (best_later > 0 && best_later < best_t) best_t = best_later;
+    // alone on the device the chain takes the fastest width; sharing it, the narrowest within `slack`
+    const bool sharing = S->ready_by_class[VTE_CLASS_BEST_EFFORT] + S->inflight_by_class[VTE_CLASS_BEST_EFFORT] > 0;
+    const double limit = best_t * (1.0 + (sharing ? c->slack : 0.02));
     int pick = -1;
     for (int i = 0; i < n; ++i) {
       const vte_pctx_info& p = S->pctx[el[i]];
-      const double t = profile_time(c, op->desc.profile_key, p.width);
-      if (t <= 0 || t > best_t * (1.0 + c->slack)) continue;
+      const double t = chain_time(c, op, p.width);
+      if (t <= 0 || t > limit) continue;
       if (el[i] == op->pred_pctx) return el[i];  // good enough and keeps the edge in stream order
-      if (pick < 0 || p.width < S->pctx[pick].width) pick = el[i];
+      if (pick < 0 || (sharing ? p.width < S->pctx[pick].width : t < chain_time(c, op, S->pctx[pick].width))) pick = el[i];
     }
-    return pick >= 0 ? pick : widest(op, el, n, S, total);
+    if (pick >= 0) return pick;
+    if (best_later > 0 && best_later <= limit) return -1;  // a good pCtx frees up as soon as this vstream's in-flight ops retire
+    return widest(op, el, n, S, total);
   }
   const bool latency_active = S->ready_by_class[VTE_CLASS_LATENCY] + S->inflight_by_class[VTE_CLASS_LATENCY] > 0;
   const int cap = latency_active ? total - c->keep_free : total;
   const int now = widest(op, el, n, S, cap);
   // A wider allocation may be blocked only by this vstream's own (narrower) lease:
   // then leave the op ready until that lease has drained rather than renewing it.
-  int later = -1;
   for (int id = 0; id < c->pool.size(); ++id) {
     const Pctx& p = c->pool.at(id);
     if (p.width > cap || (now >= 0 && p.width <= S->pctx[now].width)) continue;
-    if (op->pinned_pctx >= 0 && id != op->pinned_pctx) continue;
-    if (p.reserved_for >= 0 && p.reserved_for != op->vstream) continue;
-    if (p.state == kDraining) continue;
-    std::vector<int> ov;
-    c->pool.active_overlapping(id, &ov);
-    bool own_only = true;
-    for (int o : ov) {
-      const Pctx& q = c->pool.at(o);
-      if (!(q.state == kLeased && q.holder == op->vstream)) { own_only = false; break; }
-    }
-    if (p.state == kLeased && p.holder != op->vstream) own_only = false;
-    if (own_only && (later < 0 || p.width > c->pool.at(later).width)) later = id;
+    if (blocked_by_own_leases_only(c, id, op)) return -1;
   }
-  if (later >= 0) return -1;
   return now;
 }
 
@@ -674,6 +715,11 @@ int vte_submit_after(vte_vstream* vs, const vte_desc* d, const vte_token* deps, 
   for (int i = 0; i < n_deps; ++i) op->deps.push_back(deps[i]);
   vs->tail = op->tok;
   vs->queue.push_back(op);
+  auto& rk = vs->recent_keys;  // move-to-front list of the chain's distinct descriptors
+  auto kit = std::find(rk.begin(), rk.end(), d->profile_key);
+  if (kit != rk.end()) rk.erase(kit);
+  rk.insert(rk.begin(), d->profile_key);
+  if (rk.size() > 16) rk.pop_back();
   c->live[op->tok] = op;
   ++c->stats.submitted;
   if (tok_out) *tok_out = op->tok;

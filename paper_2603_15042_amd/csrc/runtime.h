@@ -97,6 +97,7 @@ struct vte_vstream {
   vte_token tail = 0;
   std::deque<vte::Op*> queue;  // submitted, not yet bound, in order
   int unfinished_bound = 0;    // bound (in flight) ops of this stream
+  std::vector<uint64_t> recent_keys;  // profile keys of the last distinct descriptors submitted (newest first)
   bool alive = true;
 };
 

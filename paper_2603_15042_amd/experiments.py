@@ -222,10 +222,10 @@ def cotenancy(seconds, gap_ms, steps_per_burst=128, lead_ms=3.0):
         vte.vte_vstream_pin(lat, a128 if mode == "fixed" else -1)
         vte.vte_vstream_pin(be, b128 if mode == "fixed" else -1)
         vte.vte_set_builtin_policy(ctx, vte.VTE_POLICY_QUEUE_STATE if mode.startswith("late") else vte.VTE_POLICY_WIDEST,
-                                   0.6, 128 if mode.startswith("late") else 0)
+                                   0.7, 128 if mode.startswith("late") else 0)
         ch.set_tokens(tok0)
         gemm_q, gemm_done = [], 0
-        bursts, burst_times = 0, []
+        bursts, burst_times, burst_tokens = 0, [], []
         t_start = time.perf_counter()
         next_burst = t_start + 0.005
         hinted = False
@@ -253,6 +253,7 @@ def cotenancy(seconds, gap_ms, steps_per_burst=128, lead_ms=3.0):
                 elif vte.vte_token_query(ctx, tail):
                     burst_times.append(time.perf_counter() - t_burst0)
                     bursts += 1
+                    burst_tokens.append(ch.tok.cpu().numpy().tolist())   # outside the timed burst
                     state = "idle"
                     if hinted:
                         for i in range(vte.vte_pool_count(ctx)):
@@ -266,12 +267,6 @@ def cotenancy(seconds, gap_ms, steps_per_burst=128, lead_ms=3.0):
             vte.vte_token_wait(ctx, t)
         vte.vte_device_sync(ctx)
         recs = vte.vte_stats_read(ctx)
-        ends = np.array(sorted(r.t_done for r in recs if r.kernel == vte.VTE_K_ARGMAX_FINISH))
-        step_lat = np.diff(ends) if len(ends) > 1 else np.array([0.0])
-        step_lat = step_lat[step_lat < 0.5 * gap_ms * 1e-3 + 0.02] if len(step_lat) else step_lat  # drop inter-burst gaps
-        starts = {}
-        for r in recs:
-            starts.setdefault(r.vstream, []).append(r)
         # first-step latency of each burst: submit of its first op to completion of its first argmax
         lat_recs = sorted((r for r in recs if r.klass == vte.VTE_CLASS_LATENCY), key=lambda r: r.token)
         first_lat = []
@@ -282,13 +277,13 @@ def cotenancy(seconds, gap_ms, steps_per_burst=128, lead_ms=3.0):
         dw = [r.width for r in recs if r.klass == vte.VTE_CLASS_LATENCY]
         return {"elapsed_s": elapsed, "gemm_done": gemm_done, "gemm_per_s": gemm_done / elapsed, "bursts": bursts,
                 "burst_ms_mean": float(np.mean(burst_times) * 1e3) if burst_times else None,
-                "step_ms_p50": float(np.percentile(step_lat, 50) * 1e3) if len(step_lat) > 1 else None,
-                "step_ms_p99": float(np.percentile(step_lat, 99) * 1e3) if len(step_lat) > 1 else None,
+                "burst_ms_max": float(np.max(burst_times) * 1e3) if burst_times else None,
+                "step_ms_mean": float(np.mean(burst_times) * 1e3 / steps_per_burst) if burst_times else None,
                 "first_step_ms_mean": float(np.mean(first_lat) * 1e3) if first_lat else None,
                 "first_step_ms_max": float(np.max(first_lat) * 1e3) if first_lat else None,
                 "gemm_widths": {str(k): int(v) for k, v in zip(*np.unique(gw, return_counts=True))} if gw else {},
                 "decode_widths": {str(k): int(v) for k, v in zip(*np.unique(dw, return_counts=True))} if dw else {},
-                "final_tokens": ch.tok.cpu().numpy().tolist()}
+                "burst_tokens": burst_tokens}
 
     res = {"profiles_us": prof, "gap_ms": gap_ms, "steps_per_burst": steps_per_burst, "lead_ms": lead_ms}
     res["solo_gemm"] = run("solo", with_decode=False)
@@ -302,7 +297,17 @@ def cotenancy(seconds, gap_ms, steps_per_burst=128, lead_ms=3.0):
         r["norm_gemm"] = r["gemm_per_s"] / g0
         r["norm_decode"] = d0 / r["burst_ms_mean"] if r["burst_ms_mean"] else None
         r["aggregate_normalized_throughput"] = r["norm_gemm"] + (r["norm_decode"] or 0.0)
-        # the decode token stream is a pure function of (tokens, bursts run): compare with a solo replay
+    # the token stream is a function of the start tokens and the number of steps run alone:
+    # whatever widths a mode used, the tokens after burst i must equal the solo run's
+    ref = res["solo_decode"]["burst_tokens"]
+    for mode in ("fixed", "late", "late_nohint"):
+        got = res[mode]["burst_tokens"]
+        m = min(len(ref), len(got))
+        res[mode]["bursts_compared"] = m
+        res[mode]["bursts_with_token_mismatch"] = sum(int(ref[i] != got[i]) for i in range(m))
+    for mode in ("solo_gemm", "solo_decode", "fixed", "late", "late_nohint"):
+        bt = res[mode].pop("burst_tokens")
+        res[mode]["final_tokens"] = bt[-1] if bt else None
     res["gemm_tflops_solo"] = 2 * M ** 3 * g0 / 1e12
     vte.vte_shutdown(ctx)
     return res

@@ -480,22 +480,55 @@ def test_queue_state_policy_uses_profiles(ctx):
     vte.vte_set_builtin_policy(ctx, vte.VTE_POLICY_QUEUE_STATE, 0.1, 0)
     lat, be = vte.vte_vstream_create(ctx, vte.VTE_CLASS_LATENCY), vte.vte_vstream_create(ctx, vte.VTE_CLASS_BEST_EFFORT)
     ps = infos(ctx)
-    t1 = vte.vte_submit(lat, d)                      # narrowest width within 10% of the best: 128
-    vte.vte_dispatcher_quiesce(ctx)
-    p1 = vte.vte_fake_log(ctx)[-1].pctx
-    assert ps[p1].width == 128
-    t2 = vte.vte_submit(be, g)                       # best effort takes the widest that is left
-    vte.vte_dispatcher_quiesce(ctx)
-    p2 = vte.vte_fake_log(ctx)[-1].pctx
-    assert ps[p2].width == 128 and p2 == ps[p1].remainder
-    vte.vte_fake_complete(ctx, t1)
-    vte.vte_fake_complete(ctx, t2)
-    vte.vte_device_sync(ctx)
-    t3 = vte.vte_submit(be, g)                       # nothing latency-critical around: whole device
+    t0 = vte.vte_submit(lat, d)                      # alone on the device: the fastest width
     vte.vte_dispatcher_quiesce(ctx)
     assert ps[vte.vte_fake_log(ctx)[-1].pctx].width == 256
-    vte.vte_fake_complete(ctx, t3)
+    vte.vte_fake_complete(ctx, t0)
     vte.vte_device_sync(ctx)
+    g1 = vte.vte_submit(be, g)                       # nothing latency-critical around: whole device
+    g2 = vte.vte_submit(be, g)                       # (waits for g1 in stream order)
+    vte.vte_dispatcher_quiesce(ctx)
+    assert ps[vte.vte_fake_log(ctx)[-1].pctx].width == 256
+    t1 = vte.vte_submit(lat, d)                      # everything overlaps the root lease: stays ready
+    vte.vte_dispatcher_quiesce(ctx)
+    assert vte.vte_fake_log(ctx)[-1].token == g1
+    vte.vte_fake_complete(ctx, g1)
+    vte.vte_token_wait(ctx, g1)
+    vte.vte_dispatcher_quiesce(ctx)
+    log = {e.token: e.pctx for e in vte.vte_fake_log(ctx)}
+    p1, p2 = log[t1], log[g2]
+    assert ps[p1].width == 128                       # sharing: narrowest width within 10% of the best
+    assert ps[p2].width == 128 and p2 == ps[p1].remainder   # best effort takes the widest that is left
+    vte.vte_fake_complete(ctx, t1)
+    vte.vte_fake_complete(ctx, g2)
+    vte.vte_device_sync(ctx)
+
+
+def test_queue_state_policy_keeps_a_chain_on_one_width(pctx):
+    """The width decision is taken for the recurring chain, not per launch: a tiny
+    launch does not drag the heavy ones onto a narrow pCtx, and a launch whose good
+    pCtx is blocked only by its own vstream's lease waits for that lease to drain."""
+    c = pctx
+    small = norm_desc(c)
+    big = vte.vte_desc_gemm(c, A, A, A, 512, 512, 512)
+    ks, kb = vte.vte_desc_info(small).profile_key, vte.vte_desc_info(big).profile_key
+    for w in (32, 64, 128, 192, 224, 256):
+        vte.vte_profile_set(c, ks, w, 4e-6)                      # flat: launch-bound
+        vte.vte_profile_set(c, kb, w, 100e-6 * 256 / w)          # scales with width
+    vte.vte_set_builtin_policy(c, vte.VTE_POLICY_QUEUE_STATE, 0.1, 0)
+    lat = vte.vte_vstream_create(c, vte.VTE_CLASS_LATENCY)
+    ps = infos(c)
+    toks = []
+    for _ in range(3):
+        toks += [vte.vte_submit(lat, small), vte.vte_submit(lat, big)]
+    vte.vte_dispatcher_quiesce(c)
+    log = vte.vte_fake_log(c)
+    assert [e.token for e in log] == toks and {ps[e.pctx].width for e in log[1:]} == {256}
+    first = log[0].pctx                                          # bound before the chain was known
+    for t in toks:
+        vte.vte_fake_complete(c, t)
+    vte.vte_vstream_sync(lat)
+    assert ps[first].width in (32, 256)
 
 
 # ---------- pipelined binding -----------------------------------------------------------------------
