@@ -223,10 +223,17 @@ int vte_desc_argmax_finish(vte_ctx* ctx, const vte_desc* lmhead, vte_desc** out)
  *   prefetch    1: the next row group's loads are issued before the current one is reduced
  *   max_waves   8 or 16: the register budget the kernel was compiled for
  *   groups      row groups a workgroup walks through
+ *   kind        VTE_GEMV_DOT2: the fields above.  VTE_GEMV_MFMA (matrix-core tiles of 16
+ *               weight rows x 16 batch columns): batch_tile = 16; rows = 16 x the tiles
+ *               accumulated at once; ksteps = number of 128-element blocks per K chunk;
+ *               the workgroup has min(max_waves, chunks) waves that take the chunks
+ *               round-robin; prefetch = blocks the loads run ahead; groups as above
  * Only combinations the library was built with are accepted.  The reduction tree
- * of an output depends on K and ksteps alone — never on the device. */
+ * of an output depends on K and the plan alone — never on the device. */
+enum { VTE_GEMV_DOT2 = 0, VTE_GEMV_MFMA = 1 };
 typedef struct vte_gemv_plan {
   int batch_tile, rows, ksteps, prefetch, max_waves, groups;
+  int kind;
 } vte_gemv_plan;
 int vte_gemv_default_plan(int B, int N, int K, int epilogue, int S, vte_gemv_plan* plan);
 int vte_desc_gemv_planned(vte_ctx* ctx, const void* W, const void* X, void* Y, int B, int N, int K,

@@ -16,6 +16,7 @@ const void* vte_gemv_entry_b2(int, int, int, int, int, int);
 const void* vte_gemv_entry_b4(int, int, int, int, int, int);
 const void* vte_gemv_entry_b8(int, int, int, int, int, int);
 const void* vte_gemv_entry_b16(int, int, int, int, int, int);
+const void* vte_gemv_entry_mfma(int, int, int, int, int, int, int);
 const void* vte_gather_entry();
 const void* vte_argmax_finish_entry();
 const void* vte_gemm_entry();
@@ -109,7 +110,13 @@ int build_norm(vte_ctx* ctx, int kernel, bool layer, const void* x, const void* 
                      static_cast<uint32_t>(threads), 0, shape, bytes, static_cast<uint64_t>(rows) * cols * 4, out);
 }
 
-const void* gemv_entry(const vte_gemv_plan& p, int epi) {
+const void* gemv_entry(const vte_gemv_plan& p, int epi, int k_per_split) {
+  if (p.kind == VTE_GEMV_MFMA) {
+    if (p.ksteps < 1) return nullptr;
+    const int kc = 128 * p.ksteps;
+    return vte_gemv_entry_mfma(p.ksteps, p.rows / 16, p.prefetch, p.max_waves, k_per_split % kc == 0 ? 1 : 0,
+                               (k_per_split + kc - 1) / kc <= p.max_waves ? 1 : 0, epi);
+  }
   switch (p.batch_tile) {
     case 1: return vte_gemv_entry_b1(1, p.rows, p.ksteps, p.prefetch, p.max_waves, epi);
     case 2: return vte_gemv_entry_b2(2, p.rows, p.ksteps, p.prefetch, p.max_waves, epi);
@@ -123,6 +130,11 @@ const void* gemv_entry(const vte_gemv_plan& p, int epi) {
 int batch_tile(int B) { int bt = 1; while (bt < B) bt *= 2; return bt; }
 
 int plan_waves(const vte_gemv_plan& p, int k_per_split) {
+  if (p.kind == VTE_GEMV_MFMA) {  // waves share the K chunks round-robin
+    if (p.ksteps < 1) return 0;
+    const int nchunks = (k_per_split + 128 * p.ksteps - 1) / (128 * p.ksteps);
+    return nchunks < p.max_waves ? nchunks : p.max_waves;
+  }
   const int nsteps = (k_per_split + 511) / 512;
   return (nsteps + p.ksteps - 1) / p.ksteps;
 }
@@ -133,13 +145,24 @@ int plan_waves(const vte_gemv_plan& p, int k_per_split) {
 // kps = K / S.
 int plan_gemv(int B, int outputs, int kps, int epi, vte_gemv_plan* p) {
   if (B < 1 || B > 16 || outputs < 1 || kps < 8) return VTE_EINVAL;
+  const bool silu = epi == VTE_EPI_SILU_MUL;
+  if (B >= 5 && outputs >= (silu ? 8 : 16)) {
+    // Batch 5 and up: matrix-core tiles (the dot-product kernels are ALU-bound there).
+    // Large outputs walk several rounds so that X is fetched once per many rows.
+    const int tiles = (outputs + (silu ? 8 : 16) - 1) / (silu ? 8 : 16);
+    int g = 1, nb = 2, mw = 8, rounds = 1;
+    if (tiles >= 4096) { mw = 4; nb = 4; if (B <= 8) { g = 2; rounds = 4; } else { g = 4; rounds = 2; } }
+    else if (tiles >= 1024) { g = 8; }
+    p->batch_tile = 16; p->rows = 16 * g; p->ksteps = 4; p->prefetch = nb; p->max_waves = mw; p->groups = rounds;
+    p->kind = VTE_GEMV_MFMA;
+    return VTE_OK;
+  }
   const int nsteps = (kps + 511) / 512;
   if (nsteps > 32) return VTE_EINVAL;
   int bt = batch_tile(B);
   if (bt == 1) bt = 2;                    // one row rides in the two-row tile
   if (nsteps > 16 && bt < 4) bt = 4;      // long rows: the wider tile keeps a wave's slice in registers
   if (nsteps > 16 && bt == 16) bt = 8;    // long rows at batch 16: two batch chunks of 8
-  const bool silu = epi == VTE_EPI_SILU_MUL;
   int r, ks, pf = 1, mw = 8, gmax = 8;
   if (bt == 2) {
     if (nsteps <= 1) { r = 16; ks = 1; } else { r = 8; ks = 2; }
@@ -165,6 +188,7 @@ int plan_gemv(int B, int outputs, int kps, int epi, vte_gemv_plan* p) {
   int groups = outputs / (rout * 256);
   groups = groups < 1 ? 1 : (groups > gmax ? gmax : groups);
   p->batch_tile = bt; p->rows = r; p->ksteps = ks; p->prefetch = pf; p->max_waves = mw; p->groups = groups;
+  p->kind = VTE_GEMV_DOT2;
   return VTE_OK;
 }
 
@@ -193,10 +217,15 @@ int build_gemv(vte_ctx* ctx, const GemvBuild& g, vte_desc** out) {
   else if (plan_gemv(g.B, n_out, g.K / g.S, g.epilogue, &p) != VTE_OK) { set_error("gemv: K / S must be at most 16384"); return VTE_EINVAL; }
   const int kps = g.K / g.S;
   const int waves = plan_waves(p, kps);
+  const bool mfma = p.kind == VTE_GEMV_MFMA;
+  if (p.kind != VTE_GEMV_DOT2 && !mfma) { set_error("gemv plan: unknown kind"); return VTE_EINVAL; }
+  if (mfma && n_out < (g.epi_kernel == 1 ? 8 : 16)) { set_error("gemv plan: the MFMA kind needs at least one full tile of outputs (16, or 8 with SiLU-mul)"); return VTE_EINVAL; }
+  if (mfma && (p.batch_tile != 16 || p.rows < 16 || p.rows % 16 != 0)) { set_error("gemv plan: the MFMA kind has batch_tile 16 and rows a multiple of 16"); return VTE_EINVAL; }
   const int zchunks = (g.B + p.batch_tile - 1) / (p.batch_tile > 0 ? p.batch_tile : 1);
   if (p.batch_tile < 1 || p.groups < 1 || p.rows < 1 || p.ksteps < 1 || waves < 1 || waves > p.max_waves) {
     set_error("gemv plan: groups >= 1 and ceil(K/S/512/ksteps) <= max_waves are required"); return VTE_EINVAL;
   }
+  if (!gemv_entry(p, g.epi_kernel, kps)) { set_error("gemv plan: this combination is not built"); return VTE_EINVAL; }
   const int rout = (g.epi_kernel == 1) ? p.rows / 2 : p.rows;
   if (rout < 1) { set_error("gemv plan: the SiLU epilogue needs an even number of rows"); return VTE_EINVAL; }
   const int per_block = rout * p.groups;
@@ -217,7 +246,7 @@ int build_gemv(vte_ctx* ctx, const GemvBuild& g, vte_desc** out) {
   uint64_t bytes = 2ull * g.N * g.K + 2ull * g.B * g.K + (lm ? 4ull * g.B : 2ull * g.B * n_out);
   if (lm && g.logits) bytes += 4ull * g.B * g.N;
   const uint64_t flops = 2ull * g.B * g.N * g.K;
-  return finish_desc(ctx, g.kernel, gemv_entry(p, g.epi_kernel), a, gx, static_cast<uint32_t>(g.S),
+  return finish_desc(ctx, g.kernel, gemv_entry(p, g.epi_kernel, kps), a, gx, static_cast<uint32_t>(g.S),
                      static_cast<uint32_t>(waves * 64), 0, shape, bytes, flops, out, static_cast<uint32_t>(zchunks));
 }
 

@@ -21,6 +21,7 @@ VTE_PCTX_IDLE, VTE_PCTX_LEASED, VTE_PCTX_DRAINING, VTE_PCTX_RESERVED = 0, 1, 2, 
 VTE_EPI_NONE, VTE_EPI_SILU_MUL = 0, 1
 VTE_CLASS_LATENCY, VTE_CLASS_BEST_EFFORT = 0, 1
 VTE_POLICY_WIDEST, VTE_POLICY_QUEUE_STATE = 0, 1
+VTE_GEMV_DOT2, VTE_GEMV_MFMA = 0, 1
 (VTE_K_RMSNORM, VTE_K_LAYERNORM, VTE_K_GEMV, VTE_K_LMHEAD, VTE_K_GATHER, VTE_K_GEMM, VTE_K_GEMV_SPLITK,
  VTE_K_LMHEAD_SPLITK, VTE_K_RMSNORM_RESHAPED, VTE_K_ARGMAX_FINISH, VTE_K_RMSNORM_GATHER) = range(1, 12)
 
@@ -49,7 +50,7 @@ class vte_desc_view(C.Structure):
 
 
 class vte_gemv_plan(C.Structure):
-    _fields_ = [(n, C.c_int) for n in ("batch_tile", "rows", "ksteps", "prefetch", "max_waves", "groups")]
+    _fields_ = [(n, C.c_int) for n in ("batch_tile", "rows", "ksteps", "prefetch", "max_waves", "groups", "kind")]
 
 
 class vte_ready_op(C.Structure):
