@@ -168,6 +168,16 @@ int vte_desc_rmsnorm(vte_ctx* ctx, const void* x, const void* gamma, void* y, in
  * launch instead of gather + norm; the arithmetic and its tree are unchanged. */
 int vte_desc_rmsnorm_gather(vte_ctx* ctx, const void* E, const int32_t* tok, const void* gamma, void* y,
                             void* h_or_null, int B, int V, int cols, float eps, vte_desc** out);
+/* The decode loop's step boundary in one launch: finishes the greedy token of
+ * the LM-head launch before it (tok[b] = lowest index attaining the maximum over
+ * the candidates `lmhead` leaves in its workspace; NaN never wins, all-NaN -> 0),
+ * gathers E[tok[b], :] and applies the RMSNorm above.  tok_out_or_null: optional
+ * device [B] int32 that also receives the tokens.  B is the LM head's batch.
+ * Replaces vte_desc_argmax_finish + vte_desc_rmsnorm_gather between two steps;
+ * the token and the norm bits are the same. (Sec. 7.1 / 7.2) */
+int vte_desc_rmsnorm_gather_argmax(vte_ctx* ctx, const void* E, const vte_desc* lmhead,
+                                   int32_t* tok_out_or_null, const void* gamma, void* y, void* h_or_null,
+                                   int V, int cols, float eps, vte_desc** out);
 /* y = (x - mu) * rsqrt(var + eps) * gamma + beta, biased variance, two fixed-tree
  * fp32 reductions (mean, then centred squares).  Same layout and limits. (Sec. 1) */
 int vte_desc_layernorm(vte_ctx* ctx, const void* x, const void* gamma, const void* beta,
@@ -278,7 +288,7 @@ int vte_desc_rmsnorm_reshaped(vte_ctx* ctx, const void* x, const void* gamma, vo
 enum {
   VTE_K_RMSNORM = 1, VTE_K_LAYERNORM = 2, VTE_K_GEMV = 3, VTE_K_LMHEAD = 4, VTE_K_GATHER = 5,
   VTE_K_GEMM = 6, VTE_K_GEMV_SPLITK = 7, VTE_K_LMHEAD_SPLITK = 8, VTE_K_RMSNORM_RESHAPED = 9,
-  VTE_K_ARGMAX_FINISH = 10, VTE_K_RMSNORM_GATHER = 11
+  VTE_K_ARGMAX_FINISH = 10, VTE_K_RMSNORM_GATHER = 11, VTE_K_RMSNORM_GATHER_ARGMAX = 12
 };
 typedef struct vte_desc_view {
   int kernel;           /* VTE_K_* */

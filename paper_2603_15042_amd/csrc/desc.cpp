@@ -90,7 +90,8 @@ int norm_threads(int cols) {
 
 int build_norm(vte_ctx* ctx, int kernel, bool layer, const void* x, const void* gamma, const void* beta,
                void* y, int rows, int cols, float eps, int threads, vte_desc** out,
-               const int32_t* tok = nullptr, void* h_out = nullptr, int V = 0) {
+               const int32_t* tok = nullptr, void* h_out = nullptr, int V = 0, const uint32_t* cand = nullptr,
+               int nblocks = 0, int cand_bt = 0, int32_t* tok_out = nullptr) {
   if (!ctx || !out || !x || !gamma || !y || (layer && !beta)) { set_error("norm: null argument"); return VTE_EINVAL; }
   if (rows <= 0 || cols <= 0 || cols % 8 != 0 || cols > 16384) { set_error("norm: need rows > 0, cols % 8 == 0, cols <= 16384"); return VTE_EINVAL; }
   if (!aligned16(x) || !aligned16(gamma) || !aligned16(y) || (layer && !aligned16(beta))) { set_error("norm: pointers must be 16-byte aligned"); return VTE_EINVAL; }
@@ -103,9 +104,12 @@ int build_norm(vte_ctx* ctx, int kernel, bool layer, const void* x, const void* 
   a.y = static_cast<uint16_t*>(y);
   a.rows = rows; a.cols = cols; a.eps = eps; a.inv_cols = 1.0f / static_cast<float>(cols);
   a.tok = tok; a.h_out = static_cast<uint16_t*>(h_out); a.V = V;
+  a.cand = cand; a.nblocks = nblocks; a.cand_bt = cand_bt; a.tok_out = tok_out;
   if (h_out && !aligned16(h_out)) { set_error("norm: pointers must be 16-byte aligned"); return VTE_EINVAL; }
-  const uint64_t shape = (static_cast<uint64_t>(rows) << 32) | static_cast<uint32_t>(cols);
-  const uint64_t bytes = static_cast<uint64_t>(rows) * cols * 4 + static_cast<uint64_t>(cols) * (layer ? 4 : 2);
+  const int shape_v[3] = {rows, cols, nblocks};
+  const uint64_t shape = nblocks ? fnv1a(shape_v, sizeof shape_v) : ((static_cast<uint64_t>(rows) << 32) | static_cast<uint32_t>(cols));
+  const uint64_t bytes = static_cast<uint64_t>(rows) * cols * 4 + static_cast<uint64_t>(cols) * (layer ? 4 : 2) +
+                         (cand ? 8ull * nblocks * rows + 4ull * rows : 0);
   return finish_desc(ctx, kernel, vte_norm_entry(threads, layer ? 1 : 0), a, static_cast<uint32_t>(rows), 1,
                      static_cast<uint32_t>(threads), 0, shape, bytes, static_cast<uint64_t>(rows) * cols * 4, out);
 }
@@ -267,6 +271,20 @@ int vte_desc_rmsnorm_gather(vte_ctx* ctx, const void* E, const int32_t* tok, con
   if (!tok || V < 1) { set_error("rmsnorm_gather: tok and V >= 1 are required"); return VTE_EINVAL; }
   return build_norm(ctx, VTE_K_RMSNORM_GATHER, false, E, gamma, nullptr, y, B, cols, eps, norm_threads(cols), out,
                     tok, h_or_null, V);
+}
+
+int vte_desc_rmsnorm_gather_argmax(vte_ctx* ctx, const void* E, const vte_desc* lmhead, int32_t* tok_out_or_null,
+                                   const void* gamma, void* y, void* h_or_null, int V, int cols, float eps,
+                                   vte_desc** out) {
+  if (!ctx || !lmhead || V < 1) { set_error("rmsnorm_gather_argmax: lmhead and V >= 1 are required"); return VTE_EINVAL; }
+  if (lmhead->ctx != ctx || (lmhead->kernel != VTE_K_LMHEAD && lmhead->kernel != VTE_K_LMHEAD_SPLITK)) {
+    set_error("rmsnorm_gather_argmax: needs an LM-head descriptor of this context"); return VTE_EINVAL;
+  }
+  GemvArgs g;
+  std::memcpy(&g, lmhead->args, sizeof g);
+  const uint32_t* cand = g.ws + 1 + lmhead->grid[0] * lmhead->grid[2];
+  return build_norm(ctx, VTE_K_RMSNORM_GATHER_ARGMAX, false, E, gamma, nullptr, y, g.B, cols, eps, norm_threads(cols),
+                    out, nullptr, h_or_null, V, cand, static_cast<int>(lmhead->grid[0]), g.bt, tok_out_or_null);
 }
 
 int vte_desc_layernorm(vte_ctx* ctx, const void* x, const void* gamma, const void* beta, void* y, int rows,

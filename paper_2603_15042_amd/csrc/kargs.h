@@ -15,6 +15,11 @@ struct NormArgs {
   int rows, cols, V;
   float eps;
   float inv_cols;
+  // fused greedy-token finish: the token of row r is first reduced from the
+  // (value, index) candidates an LM-head launch left behind (else null)
+  const uint32_t* cand;   // values [cand_bt][nblocks] (fp32 bits), then indices [cand_bt][nblocks]
+  int32_t* tok_out;       // optional: where the finished tokens are also stored
+  int nblocks, cand_bt;
 };
 
 // GEMV family: plain, SiLU-mul, LM head (+argmax), and the split-K baselines.

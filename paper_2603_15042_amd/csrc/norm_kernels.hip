@@ -3,7 +3,9 @@
 // negative control of Sec. 7.1).
 //
 // With a token list the input row is fetched from an embedding table (gather
-// fused into the norm); the arithmetic is the same.
+// fused into the norm); the arithmetic is the same.  The token may also come
+// straight from the candidates of the LM-head launch before (greedy-token finish
+// fused in as well: Sec. 7.1 / 7.2 decode loop, one launch fewer per step).
 // One workgroup of T threads per row.  Thread t owns the 8-element chunks
 // t, t+T, t+2T, ... of the row (128-bit loads, coalesced across the wave) and
 // keeps them in registers, so the row is read from HBM exactly once.
@@ -16,6 +18,7 @@
 // purpose.
 #include "dev_util.h"
 #include "kargs.h"
+#include <limits.h>
 
 constexpr int kMaxChunks = 8;  // per thread: cols <= 8 * 8 * T
 
@@ -37,11 +40,41 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
 template <int T, bool LAYER>
 __global__ __launch_bounds__(T) void norm_kernel(const NormArgs a) {
   __shared__ float red[T / 64];
+  __shared__ float s_cv[T / 64];
+  __shared__ int s_ci[T / 64];
   const int row = blockIdx.x;
   if (row >= a.rows) return;
   const int nchunks = a.cols >> 3;
   size_t src_row = row;
-  if (a.tok) {  // fused embedding gather: the row comes from the table
+  if (a.cand) {
+    // greedy token of this batch row: best (value, lowest index) over the candidates;
+    // the comparison is a total order, so the order of the reduction does not matter
+    const uint32_t* cv = a.cand + static_cast<size_t>(row) * a.nblocks;
+    const uint32_t* ci = a.cand + static_cast<size_t>(a.cand_bt) * a.nblocks + static_cast<size_t>(row) * a.nblocks;
+    float bv = -INFINITY;
+    int bi = INT_MAX;
+    for (int blk = threadIdx.x; blk < a.nblocks; blk += T) {
+      const float v = __uint_as_float(cv[blk]);
+      const int i = static_cast<int>(ci[blk]);
+      if (better(v, i, bv, bi)) { bv = v; bi = i; }
+    }
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      const float ov = __shfl_xor(bv, d, 64);
+      const int oi = __shfl_xor(bi, d, 64);
+      if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+    }
+    if ((threadIdx.x & 63) == 0) { s_cv[threadIdx.x >> 6] = bv; s_ci[threadIdx.x >> 6] = bi; }
+    __syncthreads();
+    bv = s_cv[0];
+    bi = s_ci[0];
+#pragma unroll
+    for (int w = 1; w < T / 64; ++w)
+      if (better(s_cv[w], s_ci[w], bv, bi)) { bv = s_cv[w]; bi = s_ci[w]; }
+    int t = (bi == INT_MAX) ? 0 : bi;  // all-NaN row
+    if (threadIdx.x == 0 && a.tok_out) a.tok_out[row] = t;
+    src_row = t < 0 ? 0 : (t >= a.V ? a.V - 1 : t);
+  } else if (a.tok) {  // fused embedding gather: the row comes from the table
     int t = a.tok[row];
     src_row = t < 0 ? 0 : (t >= a.V ? a.V - 1 : t);
   }

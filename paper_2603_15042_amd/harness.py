@@ -67,13 +67,15 @@ def run_on(ctx, desc, pctx_id):
 
 
 class DecodeChain:
-    """The Llama-shaped single-layer decode chain as eight immutable descriptors:
-    gather, RMSNorm, QKV, O (on the Q slice of QKV), gate/up+SiLU, down, LM head, argmax finish.
-    splitk=S builds the reshaped variant of every GEMV instead (the negative control)."""
-
+    """The Llama-shaped single-layer decode chain as immutable descriptors:
+    gather, RMSNorm, QKV, O (on the Q slice of QKV), gate/up+SiLU, down, LM head, argmax finish
+    (eight launches; seven with fused_gather).  splitk=S builds the reshaped variant of every
+    GEMV instead (the negative control).  fused_argmax adds the step-boundary descriptor that
+    finishes the previous step's token, gathers and normalises in one launch: a burst is then
+    first step (7 launches, no finish) + later steps (6 launches each) + one finish at the end."""
 
     def __init__(self, ctx, weights_dev, shp, B, eps=1e-6, want_logits=False, splitk=None, rms_active_cus=None,
-                 feedback=False, fused_gather=False):
+                 feedback=False, fused_gather=False, fused_argmax=False):
         self.ctx, self.shp, self.B = ctx, shp, B
         D, Nq, F, V = shp.D, shp.Nqkv, shp.F, shp.V
         w = self.w = weights_dev
@@ -123,7 +125,16 @@ class DecodeChain:
                                                             ws(V), B, V, D, S)
         d["argmax"] = vte.vte_desc_argmax_finish(ctx, d["lmhead"])
         self.order = [k for k in ("gather", "rmsnorm", "qkv", "q", "o", "gateup", "down", "lmhead", "argmax") if k in d]
-        self.bytes_per_step = sum(vte.vte_desc_info(d[k]).bytes for k in self.order if k != "q")
+        self.fused_argmax = fused_argmax
+        if fused_argmax:
+            d["boundary"] = vte.vte_desc_rmsnorm_gather_argmax(ctx, w["E"], d["lmhead"], self.next, w["gamma"], self.n,
+                                                               self.h0, V, D, eps)
+            body = [k for k in self.order if k not in ("gather", "rmsnorm", "argmax")]
+            self.order_first = [k for k in self.order if k != "argmax"]
+            self.order_next = ["boundary"] + body
+            self.bytes_per_step = sum(vte.vte_desc_info(d[k]).bytes for k in self.order_next if k != "q")
+        else:
+            self.bytes_per_step = sum(vte.vte_desc_info(d[k]).bytes for k in self.order if k != "q")
 
     def set_tokens(self, toks):
         self.tok.copy_(torch.from_numpy(np.ascontiguousarray(toks, dtype=np.int32)))
@@ -135,6 +146,19 @@ class DecodeChain:
         for k in self.order:
             last = vte.vte_submit(vs, self.desc[k])
         return last
+
+    def submit_burst(self, vs, steps):
+        """Submits `steps` free-running steps; with fused_argmax the step boundary is one launch
+        and the last token is finished by one extra launch at the end.  Returns the last token."""
+        last = 0
+        if not self.fused_argmax:
+            for _ in range(steps):
+                last = self.submit_step(vs)
+            return last
+        for i in range(steps):
+            for k in (self.order_first if i == 0 else self.order_next):
+                last = vte.vte_submit(vs, self.desc[k])
+        return vte.vte_submit(vs, self.desc["argmax"])
 
     def run_step_on(self, pctx_ids):
         """One step with every launch bound explicitly: pctx_ids is an id or one id per launch."""

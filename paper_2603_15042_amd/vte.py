@@ -23,7 +23,8 @@ VTE_CLASS_LATENCY, VTE_CLASS_BEST_EFFORT = 0, 1
 VTE_POLICY_WIDEST, VTE_POLICY_QUEUE_STATE = 0, 1
 VTE_GEMV_DOT2, VTE_GEMV_MFMA = 0, 1
 (VTE_K_RMSNORM, VTE_K_LAYERNORM, VTE_K_GEMV, VTE_K_LMHEAD, VTE_K_GATHER, VTE_K_GEMM, VTE_K_GEMV_SPLITK,
- VTE_K_LMHEAD_SPLITK, VTE_K_RMSNORM_RESHAPED, VTE_K_ARGMAX_FINISH, VTE_K_RMSNORM_GATHER) = range(1, 12)
+ VTE_K_LMHEAD_SPLITK, VTE_K_RMSNORM_RESHAPED, VTE_K_ARGMAX_FINISH, VTE_K_RMSNORM_GATHER,
+ VTE_K_RMSNORM_GATHER_ARGMAX) = range(1, 13)
 
 
 class VteError(RuntimeError):
@@ -102,7 +103,7 @@ class vte_fake_log_entry(C.Structure):
 EXPORTS = [
     "vte_last_error", "vte_last_hip_error", "vte_pool_cfg_default", "vte_init", "vte_shutdown", "vte_pool_count",
     "vte_pool_info", "vte_pool_find", "vte_pool_conflict", "vte_pctx_native_stream", "vte_desc_rmsnorm",
-    "vte_desc_rmsnorm_gather",
+    "vte_desc_rmsnorm_gather", "vte_desc_rmsnorm_gather_argmax",
     "vte_desc_layernorm", "vte_desc_gemv", "vte_lmhead_workspace_bytes", "vte_desc_lmhead_argmax", "vte_desc_argmax_finish",
     "vte_desc_gemv_strided", "vte_gemv_default_plan", "vte_desc_gemv_planned", "vte_desc_lmhead_argmax_planned", "vte_desc_gather",
     "vte_desc_gemm", "vte_splitk_workspace_bytes", "vte_desc_gemv_splitk", "vte_desc_lmhead_argmax_splitk",
@@ -219,6 +220,11 @@ def vte_desc_rmsnorm(ctx, x, gamma, y, rows, cols, eps):
 def vte_desc_rmsnorm_gather(ctx, E, tok, gamma, y, h_or_null, B, V, cols, eps):
     return _desc_call(load().vte_desc_rmsnorm_gather, ctx, _ptr(E), _ptr(tok), _ptr(gamma), _ptr(y), _ptr(h_or_null),
                       int(B), int(V), int(cols), C.c_float(eps))
+
+
+def vte_desc_rmsnorm_gather_argmax(ctx, E, lmhead, tok_out_or_null, gamma, y, h_or_null, V, cols, eps):
+    return _desc_call(load().vte_desc_rmsnorm_gather_argmax, ctx, _ptr(E), lmhead, _ptr(tok_out_or_null), _ptr(gamma),
+                      _ptr(y), _ptr(h_or_null), int(V), int(cols), C.c_float(eps))
 
 
 def vte_desc_layernorm(ctx, x, gamma, beta, y, rows, cols, eps):

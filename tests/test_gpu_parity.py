@@ -256,6 +256,65 @@ def test_strided_gemv_reads_a_column_slice(H, ctx):
     vte.vte_desc_destroy(d)
 
 
+# ---------- matrix-core GEMV plans (batch 5-16) ---------------------------------------------------------
+MFMA_PLANS = [(1, 2, 8, 1), (2, 4, 4, 3), (4, 2, 8, 2), (8, 2, 8, 1), (4, 4, 4, 1), (8, 4, 4, 2), (2, 2, 4, 2)]
+
+
+@pytest.mark.parametrize("G,NB,MW,rounds", MFMA_PLANS)
+@pytest.mark.parametrize("B,N,K", [(5, 530, 2088), (8, 48, 4096), (16, 2100, 512), (13, 32, 14336)])
+def test_gemv_mfma_plans(H, ctx, G, NB, MW, rounds, B, N, K):
+    """Every built matrix-core decomposition, on shapes with ragged row tiles, a ragged
+    K tail and several chunks per wave: plain, SiLU-mul and LM-head epilogues against
+    the oracle, bit-equal on a narrow and the full-width pCtx."""
+    plan = vte.vte_gemv_plan(16, 16 * G, 4, NB, MW, rounds, vte.VTE_GEMV_MFMA)
+    W = inputs.normal_bf16(11, inputs.T_W, (N, K), 0.0, K ** -0.5)
+    X = inputs.normal_bf16(11, inputs.T_XB, (B, K))
+    dW, dX = H.to_dev(W), H.to_dev(X)
+    pct = [H.pctx_of_width(ctx, 32, 3), H.pctx_of_width(ctx, 256)]
+    ref = oracle.gemv(W, X)
+    dY = H.dev_empty((B, N))
+    d = vte.vte_desc_gemv_planned(ctx, dW, dX, dY, B, N, K, vte.VTE_EPI_NONE, plan)
+    y = assert_all_equal(run_everywhere(H, ctx, d, dY, pct)).view(np.uint16)
+    bf16_close(y, ref, "mfma gemv")
+    vte.vte_desc_destroy(d)
+    dY2 = H.dev_empty((B, N // 2))
+    d = vte.vte_desc_gemv_planned(ctx, dW, dX, dY2, B, N, K, vte.VTE_EPI_SILU_MUL, plan)
+    y = assert_all_equal(run_everywhere(H, ctx, d, dY2, pct)).view(np.uint16)
+    bf16_close(y, oracle.gemv_silu_mul(W, X), "mfma gate/up")
+    vte.vte_desc_destroy(d)
+    tok = torch.full((B,), -7, dtype=torch.int32, device="cuda")
+    logits = torch.zeros((B, N), dtype=torch.float32, device="cuda")
+    ws = H.dev_zeros_bytes(vte.vte_lmhead_workspace_bytes(B, N, K))
+    d = vte.vte_desc_lmhead_argmax_planned(ctx, dW, dX, tok, logits, ws, B, N, K, plan)
+    fin = vte.vte_desc_argmax_finish(ctx, d)
+    got = []
+    for p_ in pct:
+        tok.fill_(-7)
+        logits.zero_()
+        H.run_on(ctx, d, p_)
+        H.run_on(ctx, fin, p_)
+        torch.cuda.synchronize()
+        got.append((tok.cpu().numpy().copy(), logits.cpu().numpy().copy()))
+    assert np.array_equal(got[0][0], got[1][0]) and np.array_equal(got[0][1].view(np.uint32), got[1][1].view(np.uint32))
+    assert np.abs(got[0][1].astype(np.float64) - ref).max() < 1e-4 * max(1.0, np.abs(ref).max())
+    assert np.array_equal(got[0][0], oracle.argmax(got[0][1].astype(np.float64))[0])
+    vte.vte_desc_destroy(d)
+    vte.vte_desc_destroy(fin)
+
+
+def test_gemv_mfma_plan_is_the_default_from_batch_5_and_rejects_what_is_not_built(H, ctx):
+    assert vte.vte_gemv_default_plan(4, 4096, 4096).kind == vte.VTE_GEMV_DOT2
+    p = vte.vte_gemv_default_plan(5, 4096, 4096)
+    assert p.kind == vte.VTE_GEMV_MFMA and p.batch_tile == 16 and p.rows % 16 == 0
+    assert vte.vte_gemv_default_plan(8, 8, 4096).kind == vte.VTE_GEMV_DOT2        # less than one tile of outputs
+    W, X, Y = H.dev_empty((64, 512)), H.dev_empty((8, 512)), H.dev_empty((8, 64))
+    for bad in (vte.vte_gemv_plan(16, 48, 4, 2, 8, 1, vte.VTE_GEMV_MFMA),       # 3 tiles at once: not built
+                vte.vte_gemv_plan(8, 16, 4, 2, 8, 1, vte.VTE_GEMV_MFMA),        # batch tile is 16
+                vte.vte_gemv_plan(16, 16, 4, 2, 8, 1, 7)):                      # unknown kind
+        with pytest.raises(vte.VteError):
+            vte.vte_desc_gemv_planned(ctx, W, X, Y, 8, 64, 512, vte.VTE_EPI_NONE, bad)
+
+
 # ---------- LM head + argmax -----------------------------------------------------------------------
 @pytest.mark.parametrize("B,V,K", [(1, 1, 64), (2, 7, 64), (4, 1000, 256), (8, 4097, 1024), (16, 2049, 512)])
 def test_lmhead_logits_and_token(H, ctx, B, V, K):
@@ -392,6 +451,43 @@ def test_fused_gather_norm_equals_two_launches(H, ctx, small_chain):
         assert np.array_equal(snaps[0][k], snaps[1][k]), k
     assert np.array_equal(snaps[0]["logits"].view(np.uint32), snaps[1]["logits"].view(np.uint32))
     assert np.array_equal(snaps[0]["h0"], w["E"][tok])
+
+
+@pytest.mark.parametrize("B", [3, 8, 16])
+def test_fused_step_boundary_equals_finish_then_gather_norm(H, ctx, small_chain, B):
+    """A burst whose step boundary is one launch (finish the token, gather, normalise) leaves the
+    same tokens and the same activations as the chain with a separate finish and gather+norm."""
+    shp, w, wd = small_chain
+    tok = inputs.tokens(13, inputs.T_TOK0, B, shp.V)
+    steps = 6
+    snaps, toks = [], []
+    for fused in (False, True):
+        ch = H.DecodeChain(ctx, wd, shp, B, want_logits=True, feedback=True, fused_gather=True, fused_argmax=fused)
+        if fused:
+            assert len(ch.order_next) == 6 and ch.order_next[0] == "boundary"
+        ch.set_tokens(tok)
+        vs = vte.vte_vstream_create(ctx, vte.VTE_CLASS_LATENCY)
+        vte.vte_vstream_pin(vs, H.pctx_of_width(ctx, 64 if fused else 256))
+        ch.submit_burst(vs, steps)
+        vte.vte_vstream_sync(vs)
+        snaps.append(ch.snapshot())
+        toks.append(ch.tok.cpu().numpy().copy())
+        vte.vte_vstream_destroy(vs)
+        ch.close()
+    assert np.array_equal(toks[0], toks[1])
+    for k in ("h0", "n", "qkv", "o", "act", "d"):
+        assert np.array_equal(snaps[0][k], snaps[1][k]), k
+    assert np.array_equal(snaps[0]["logits"].view(np.uint32), snaps[1]["logits"].view(np.uint32))
+    # the tokens really moved: six steps from random start tokens do not stand still
+    assert not np.array_equal(toks[0], tok)
+
+
+def test_fused_step_boundary_rejects_a_non_lmhead_descriptor(H, ctx, small_chain):
+    shp, w, wd = small_chain
+    ch = H.DecodeChain(ctx, wd, shp, 2, fused_gather=True)
+    with pytest.raises(vte.VteError):
+        vte.vte_desc_rmsnorm_gather_argmax(ctx, wd["E"], ch.desc["qkv"], None, wd["gamma"], ch.n, None, shp.V, shp.D, 1e-6)
+    ch.close()
 
 
 def test_chain_bits_do_not_depend_on_allocation(H, ctx, small_chain):
