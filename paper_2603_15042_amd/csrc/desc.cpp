@@ -150,13 +150,17 @@ int plan_waves(const vte_gemv_plan& p, int k_per_split) {
 int plan_gemv(int B, int outputs, int kps, int epi, vte_gemv_plan* p) {
   if (B < 1 || B > 16 || outputs < 1 || kps < 8) return VTE_EINVAL;
   const bool silu = epi == VTE_EPI_SILU_MUL;
-  if (B >= 5 && outputs >= (silu ? 8 : 16)) {
-    // Batch 5 and up: matrix-core tiles (the dot-product kernels are ALU-bound there).
-    // Large outputs walk several rounds so that X is fetched once per many rows.
-    const int tiles = (outputs + (silu ? 8 : 16) - 1) / (silu ? 8 : 16);
+  const int tile_out = silu ? 8 : 16;
+  const int tiles = (outputs + tile_out - 1) / tile_out;
+  if (outputs >= tile_out && (B >= 5 || (B >= 3 && silu && tiles >= 1024))) {
+    // Batch 5 and up (and the wide SiLU projection from batch 3): matrix-core tiles; the
+    // dot-product kernels are ALU-bound there.  Found by timing every built combination
+    // on the Llama-8B shapes.  Large outputs walk several rounds so that X is fetched once
+    // per many rows.
     int g = 1, nb = 2, mw = 8, rounds = 1;
     if (tiles >= 4096) { mw = 4; nb = 4; if (B <= 8) { g = 2; rounds = 4; } else { g = 4; rounds = 2; } }
     else if (tiles >= 1024) { g = 8; }
+    else if (tiles > 256 && kps <= 8192) { nb = 4; mw = 4; }
     p->batch_tile = 16; p->rows = 16 * g; p->ksteps = 4; p->prefetch = nb; p->max_waves = mw; p->groups = rounds;
     p->kind = VTE_GEMV_MFMA;
     return VTE_OK;
