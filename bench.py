@@ -1,9 +1,11 @@
 """Benchmark of the decode hot path on one MI355X.
 
-A step is one pass of the Llama-8B-shaped decode chain at batch 8 (embedding
-gather fused into RMSNorm, QKV, O, gate/up+SiLU, down, LM head, argmax finish:
-seven immutable descriptors submitted to a virtual stream and late-bound by the
-dispatcher), on synthetic weights resident in HBM.  Prints one JSON line.
+A step is one pass of the Llama-8B-shaped decode chain at batch 8 (greedy-token
+finish + embedding gather + RMSNorm in one launch, QKV, O, gate/up+SiLU, down,
+LM head: six immutable descriptors per step submitted to a virtual stream and
+late-bound by the dispatcher), on synthetic weights resident in HBM.  Prints
+one JSON line.  Outside the timed region it also times the single operators of
+the metric (RMSNorm, GEMV) on pCtxs of every width.
 """
 import argparse
 import json
@@ -148,6 +150,40 @@ def main():
             vte.vte_vstream_destroy(v)
         out["per_width"] = per_width
         out["bit_mismatches_across_widths"] = int(mism)
+
+    # ---- the metric's single operators per CU width (device time of one launch, outside the timed region) ----
+    if not a.no_width_sweep and not a.small:
+        ops = {}
+        rows, cols = 32768, 4096                       # RMSNorm at a size HBM has to serve: 256 MiB in, 256 MiB out
+        x = torch.randint(-3000, 3000, (rows, cols), dtype=torch.int16, device="cuda")
+        y = torch.empty_like(x)
+        d = vte.vte_desc_rmsnorm(ctx, x, wd["gamma"], y, rows, cols, 1e-6)
+        r = {}
+        for width in (256, 128, 64, 32):
+            t = vte.vte_profile_measure_on(ctx, d, H.pctx_of_width(ctx, width), 2, 6)
+            r[str(width)] = {"GB/s": round(rows * cols * 4 / t / 1e9, 1), "pct_peak": round(rows * cols * 4 / t / 1e9 / 80, 2)}
+        ops["rmsnorm_32768x4096"] = r
+        vte.vte_desc_destroy(d)
+        del x, y
+        N = K = 4096                                   # GEMV 4096x4096, 32 weight buffers in rotation (1 GiB > caches)
+        Ws = [torch.randint(-3000, 3000, (N, K), dtype=torch.int16, device="cuda") for _ in range(32)]
+        for b2 in (1, 4, 8):
+            X = torch.randint(-3000, 3000, (b2, K), dtype=torch.int16, device="cuda")
+            Y = torch.empty((b2, N), dtype=torch.int16, device="cuda")
+            ds = [vte.vte_desc_gemv(ctx, W_, X, Y, b2, N, K) for W_ in Ws]
+            r = {}
+            for width in (256, 128, 64, 32):
+                p = H.pctx_of_width(ctx, width)
+                ts = [vte.vte_profile_measure_on(ctx, dd, p, 0, 1) for dd in ds for _ in range(2)]
+                t = float(np.median(ts[len(ds):]))
+                r[str(width)] = {"GB/s": round(N * K * 2 / t / 1e9, 1), "pct_peak": round(N * K * 2 / t / 1e9 / 80, 2),
+                                 "us": round(t * 1e6, 2)}
+            ops["gemv_4096x4096_B%d" % b2] = r
+            for dd in ds:
+                vte.vte_desc_destroy(dd)
+        del Ws
+        torch.cuda.empty_cache()
+        out["per_operator"] = ops
 
     # ---- other batch sizes of the same chain, full width (outside the timed region) -------------
     if not a.no_width_sweep:

@@ -3,11 +3,17 @@
 // of 256x256 output tiles, each reduced over K in steps of 64 in ascending order
 // by one workgroup; no split-K, no stream-K, no dependence on the CU count.
 //
-// Workgroup = 8 waves as 2 (M) x 4 (N); a wave owns 128 x 64 of the tile as
-// 4 x 2 MFMA blocks of 32x32 (v_mfma_f32_32x32x16_bf16, 16 fp32 per lane each).
-// A and Bm tiles (256 x 64 bf16 each) are staged in LDS with rows padded to
-// 72 elements so that the 32 rows read by one MFMA operand fall on distinct
-// banks; two LDS stages, global loads for step i+1 in flight during step i.
+// Workgroup = 4 waves as 2 (M) x 2 (N); a wave owns 128 x 128 of the tile as
+// 4 x 4 MFMA blocks of 32x32 (v_mfma_f32_32x32x16_bf16): 16 MFMAs per 8 operand
+// reads from LDS, which keeps the LDS port at half the MFMA pipe's time (with
+// 4 x 2 blocks per wave and padded rows the kernel was LDS-bound at 36 % of the
+// MFMA peak).  The 256 accumulator registers leave one wave per SIMD, so operand
+// fragments for the next 16 K are read while the MFMAs of the current 16 run.
+// A and Bm tiles (256 rows x 64 K, 128 B per row) are staged in LDS unpadded;
+// the 16-byte pieces of a row are XOR-swizzled with row % 8, so any 8 consecutive
+// rows of an MFMA operand read, and the 8 pieces a row is written with, fall on
+// distinct banks.  Two LDS stages; global loads for step i+1 are in flight
+// during step i.
 // Tile order: consecutive workgroup ids are dealt round-robin to the 8 XCDs, so
 // id % 8 selects a band of tile rows and each XCD's L2 sees a compact set of
 // A rows and Bm columns.
@@ -18,93 +24,144 @@ typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int TM = 256, TN = 256, TK = 64;
-constexpr int LDS_ROW = TK + 8;                      // padded row, in elements
-constexpr int TILE_ELEMS = TM * LDS_ROW;             // per operand per stage
-constexpr int GEMM_THREADS = 512;
+constexpr int ROW_BYTES = TK * 2;                    // 128
+constexpr int OPERAND_BYTES = TM * ROW_BYTES;        // 32 KB per operand per stage
+constexpr int STAGE_BYTES = 2 * OPERAND_BYTES;
+constexpr int GEMM_THREADS = 256;
 
-__global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_kernel(const GemmArgs a) {
-  extern __shared__ __align__(16) uint8_t smem[];
-  uint16_t* lds = reinterpret_cast<uint16_t*>(smem);  // [stage][A|B][256][72]
+__global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs a) {
+  extern __shared__ __align__(16) uint8_t smem[];     // [stage][A | B][256 rows][8 swizzled pieces of 16 B]
 
   // ---- tile selection (fixed function of blockIdx) ----
   const int ntiles = a.tiles_m * a.tiles_n;
   int tile = blockIdx.x;
-  if ((ntiles & 7) == 0) tile = (blockIdx.x & 7) * (ntiles >> 3) + (blockIdx.x >> 3);
-  const int tm = tile / a.tiles_n, tn = tile % a.tiles_n;
+  int tm, tn;
+  if ((a.tiles_m & 31) == 0 && (a.tiles_n & 7) == 0) {
+    // XCD x = id % 8 works through bands of 4 tile rows, each band in blocks of 4 x 8 tiles:
+    // the ~32 tiles an XCD has in flight then share 4 A bands and 8 Bm bands in its L2
+    const int x = blockIdx.x & 7, j = blockIdx.x >> 3;          // j: position in this XCD's sequence
+    const int per_band = 4 * a.tiles_n;                          // tiles in a band of 4 rows
+    const int band = j / per_band, jb = j % per_band;           // band index within this XCD's share
+    const int blk = jb >> 5, in = jb & 31;
+    tm = (band * 8 + x) * 4 + (in & 3);
+    tn = blk * 8 + (in >> 2);
+  } else {
+    if ((ntiles & 7) == 0) tile = (blockIdx.x & 7) * (ntiles >> 3) + (blockIdx.x >> 3);
+    tm = tile / a.tiles_n;
+    tn = tile % a.tiles_n;
+  }
   const uint16_t* Ag = a.A + static_cast<size_t>(tm) * TM * a.K;
   const uint16_t* Bg = a.Bm + static_cast<size_t>(tn) * TN * a.K;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = wave >> 2, wn = wave & 3;           // 2 x 4 waves
-  const int frag_row = lane & 31, frag_k = (lane >> 5) * 8;
+  const int wm = wave >> 1, wn = wave & 1;            // 2 x 2 waves
 
-  // global -> LDS copy assignment: 2048 16-byte chunks per operand tile
-  // chunk c: row = c / 8, kchunk = c % 8
-  u32x4 ga[4], gb[4];
+  // global -> LDS copy: thread t moves piece t % 8 of rows t / 8 + 32 i, i = 0..7, of both operands
+  const int lrow = tid >> 3, lc = tid & 7;
+  const uint16_t* Ap = Ag + static_cast<size_t>(lrow) * a.K + lc * 8;
+  const uint16_t* Bp = Bg + static_cast<size_t>(lrow) * a.K + lc * 8;
+  const size_t row_step = static_cast<size_t>(32) * a.K;
+  const int wofs = lrow * ROW_BYTES + 16 * (lc ^ (lrow & 7));  // (row + 32 i) has the same swizzle
+  u32x4 ga[8], gb[8];
   auto load_global = [&](int k0) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int c = tid + i * GEMM_THREADS;
-      const int row = c >> 3, kc = (c & 7) * 8;
-      ga[i] = ld16(Ag + static_cast<size_t>(row) * a.K + k0 + kc);
-      gb[i] = ld16(Bg + static_cast<size_t>(row) * a.K + k0 + kc);
+    for (int i = 0; i < 8; ++i) {
+      ga[i] = ld16(Ap + i * row_step + k0);
+      gb[i] = ld16(Bp + i * row_step + k0);
     }
   };
   auto store_lds = [&](int stage) {
-    uint16_t* As = lds + stage * 2 * TILE_ELEMS;
-    uint16_t* Bs = As + TILE_ELEMS;
+    uint8_t* base = smem + stage * STAGE_BYTES + wofs;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int c = tid + i * GEMM_THREADS;
-      const int row = c >> 3, kc = (c & 7) * 8;
-      *reinterpret_cast<u32x4*>(As + row * LDS_ROW + kc) = ga[i];
-      *reinterpret_cast<u32x4*>(Bs + row * LDS_ROW + kc) = gb[i];
+    for (int i = 0; i < 8; ++i) {
+      *reinterpret_cast<u32x4*>(base + i * 32 * ROW_BYTES) = ga[i];
+      *reinterpret_cast<u32x4*>(base + OPERAND_BYTES + i * 32 * ROW_BYTES) = gb[i];
     }
   };
 
-  f32x16 acc[4][2];
+  // operand fragments: lane l supplies row l % 32 of a 32-row block and K pieces 2 kk + l / 32
+  const int frow = lane & 31, fhalf = lane >> 5, fsw = frow & 7;
+  const int a_row0 = (wm * 128 + frow) * ROW_BYTES;
+  const int b_row0 = OPERAND_BYTES + (wn * 128 + frow) * ROW_BYTES;
+  auto read_frags = [&](bf16x8_t(&af)[4], bf16x8_t(&bfr)[4], const uint8_t* st, int kk) {
+    const int piece = 16 * ((2 * kk + fhalf) ^ fsw);
+    // Bm fragments first: the MFMAs run i-major, so af[3] is needed last
+#pragma unroll
+    for (int j = 0; j < 4; ++j) bfr[j] = *reinterpret_cast<const bf16x8_t*>(st + b_row0 + j * 32 * ROW_BYTES + piece);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) af[i] = *reinterpret_cast<const bf16x8_t*>(st + a_row0 + i * 32 * ROW_BYTES + piece);
+  };
+
+  f32x16 acc[4][4];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < 4; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
+  // One K step of 64: 64 MFMAs per wave.  The instruction stream is laid out by hand
+  // (sched_group_barrier): the global loads of the next step first, then per 16 K
+  // two MFMAs for every fragment read of the following 16 K, and in the last 16 K
+  // one MFMA per LDS write of the next stage -- with one wave per SIMD nothing else
+  // would cover the LDS latency.
   const int nk = a.K / TK;
+  bf16x8_t af[2][4], bfr[2][4];
+  auto mfma16 = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][i], bfr[buf][j], acc[i][j], 0, 0, 0);
+  };
   load_global(0);
   store_lds(0);
   __syncthreads();
-  for (int ks = 0; ks < nk; ++ks) {
+  read_frags(af[0], bfr[0], smem, 0);
+  for (int ks = 0; ks + 1 < nk; ++ks) {
     const int stage = ks & 1;
-    if (ks + 1 < nk) load_global((ks + 1) * TK);
-    const uint16_t* As = lds + stage * 2 * TILE_ELEMS + (wm * 128 + frag_row) * LDS_ROW + frag_k;
-    const uint16_t* Bs = lds + stage * 2 * TILE_ELEMS + TILE_ELEMS + (wn * 64 + frag_row) * LDS_ROW + frag_k;
+    const uint8_t* st = smem + stage * STAGE_BYTES;
+    load_global((ks + 1) * TK);
 #pragma unroll
-    for (int kk = 0; kk < TK; kk += 16) {
-      bf16x8_t af[4], bfr[2];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) af[i] = *reinterpret_cast<const bf16x8_t*>(As + i * 32 * LDS_ROW + kk);
-#pragma unroll
-      for (int j = 0; j < 2; ++j) bfr[j] = *reinterpret_cast<const bf16x8_t*>(Bs + j * 32 * LDS_ROW + kk);
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+    for (int kk = 0; kk < 3; ++kk) {
+      read_frags(af[(kk + 1) & 1], bfr[(kk + 1) & 1], st, kk + 1);
+      mfma16(kk & 1);
     }
-    if (ks + 1 < nk) store_lds(stage ^ 1);  // the other stage was last read before the previous barrier
+    store_lds(stage ^ 1);  // the other stage was last read before the previous barrier
+    mfma16(1);
+    __builtin_amdgcn_sched_group_barrier(0x020, 16, 0);  // VMEM reads
+#pragma unroll
+    for (int n = 0; n < 24; ++n) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);  // MFMA
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // DS read
+    }
+#pragma unroll
+    for (int n = 0; n < 16; ++n) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
+      __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);  // DS write
+    }
     __syncthreads();
+    read_frags(af[0], bfr[0], smem + (stage ^ 1) * STAGE_BYTES, 0);
+  }
+  {  // last step: nothing left to fetch
+    const uint8_t* st = smem + ((nk - 1) & 1) * STAGE_BYTES;
+#pragma unroll
+    for (int kk = 0; kk < 3; ++kk) {
+      read_frags(af[(kk + 1) & 1], bfr[(kk + 1) & 1], st, kk + 1);
+      mfma16(kk & 1);
+    }
+    mfma16(1);
   }
 
   // ---- epilogue: fp32 -> bf16, row-major C ----
   // 32x32 block layout: lane l, register v -> row 8*(v/4) + 4*(l/32) + v%4, column l%32
-  uint16_t* Cg = a.C + (static_cast<size_t>(tm) * TM + wm * 128) * a.N + static_cast<size_t>(tn) * TN + wn * 64;
+  uint16_t* Cg = a.C + (static_cast<size_t>(tm) * TM + wm * 128) * a.N + static_cast<size_t>(tn) * TN + wn * 128;
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < 4; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int row = i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
@@ -114,5 +171,5 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_kernel(const GemmArgs a)
 }
 
 extern "C" const void* vte_gemm_entry() { return (const void*)gemm_kernel; }
-extern "C" unsigned vte_gemm_lds_bytes() { return 2u * 2u * TILE_ELEMS * 2u; }
+extern "C" unsigned vte_gemm_lds_bytes() { return 2u * STAGE_BYTES; }
 extern "C" unsigned vte_gemm_threads() { return GEMM_THREADS; }
