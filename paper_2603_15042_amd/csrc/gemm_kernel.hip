@@ -12,8 +12,11 @@
 // A and Bm tiles (256 rows x 64 K, 128 B per row) are staged in LDS unpadded;
 // the 16-byte pieces of a row are XOR-swizzled with row % 8, so any 8 consecutive
 // rows of an MFMA operand read, and the 8 pieces a row is written with, fall on
-// distinct banks.  Two LDS stages; global loads for step i+1 are in flight
-// during step i.
+// distinct banks.  Two LDS stages; the tiles of step i+1 are loaded straight into
+// the other stage (global_load_lds, no register stop, no LDS write instructions)
+// while step i computes.  LDS moves 64 B per cycle and CU with 128-bit accesses
+// (measured), which is exactly what 4 x 4 blocks need at the full MFMA rate, so every
+// LDS cycle saved counts.
 // Tile order: consecutive workgroup ids are dealt round-robin to the 8 XCDs, so
 // id % 8 selects a band of tile rows and each XCD's L2 sees a compact set of
 // A rows and Bm columns.
@@ -58,26 +61,23 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs a) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 1, wn = wave & 1;            // 2 x 2 waves
 
-  // global -> LDS copy: thread t moves piece t % 8 of rows t / 8 + 32 i, i = 0..7, of both operands
-  const int lrow = tid >> 3, lc = tid & 7;
-  const uint16_t* Ap = Ag + static_cast<size_t>(lrow) * a.K + lc * 8;
-  const uint16_t* Bp = Bg + static_cast<size_t>(lrow) * a.K + lc * 8;
-  const size_t row_step = static_cast<size_t>(32) * a.K;
-  const int wofs = lrow * ROW_BYTES + 16 * (lc ^ (lrow & 7));  // (row + 32 i) has the same swizzle
-  u32x4 ga[8], gb[8];
-  auto load_global = [&](int k0) {
+  // global -> LDS copy without a register stop (global_load_lds_dwordx4: lane L of a wave
+  // instruction lands at the instruction's LDS base + 16 L).  One instruction fills 8 rows;
+  // lane L fetches, for row L / 8, the piece that belongs in slot L % 8 of the swizzled row.
+  // Wave w fills rows [64 w, 64 w + 64) of both operands: 16 instructions per K step.
+  const int grow = lane >> 3;                                   // row within the 8-row group
+  const int gpiece = (lane & 7) ^ grow;                         // (row & 7) == grow: groups start at multiples of 8
+  const uint16_t* Ap = Ag + static_cast<size_t>(wave * 64 + grow) * a.K + gpiece * 8;
+  const uint16_t* Bp = Bg + static_cast<size_t>(wave * 64 + grow) * a.K + gpiece * 8;
+  const size_t group_step = static_cast<size_t>(8) * a.K;
+  typedef const __attribute__((address_space(1))) void* gptr_t;
+  typedef __attribute__((address_space(3))) void* lptr_t;
+  auto fill_stage = [&](int stage, int k0) {
+    uint8_t* base = smem + stage * STAGE_BYTES + wave * 64 * ROW_BYTES;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      ga[i] = ld16(Ap + i * row_step + k0);
-      gb[i] = ld16(Bp + i * row_step + k0);
-    }
-  };
-  auto store_lds = [&](int stage) {
-    uint8_t* base = smem + stage * STAGE_BYTES + wofs;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      *reinterpret_cast<u32x4*>(base + i * 32 * ROW_BYTES) = ga[i];
-      *reinterpret_cast<u32x4*>(base + OPERAND_BYTES + i * 32 * ROW_BYTES) = gb[i];
+      __builtin_amdgcn_global_load_lds((gptr_t)(Ap + i * group_step + k0), (lptr_t)(base + i * 8 * ROW_BYTES), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((gptr_t)(Bp + i * group_step + k0), (lptr_t)(base + OPERAND_BYTES + i * 8 * ROW_BYTES), 16, 0, 0);
     }
   };
 
@@ -103,10 +103,10 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs a) {
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
   // One K step of 64: 64 MFMAs per wave.  The instruction stream is laid out by hand
-  // (sched_group_barrier): the global loads of the next step first, then per 16 K
-  // two MFMAs for every fragment read of the following 16 K, and in the last 16 K
-  // one MFMA per LDS write of the next stage -- with one wave per SIMD nothing else
-  // would cover the LDS latency.
+  // (sched_group_barrier): the LDS fills of the next step first, then two MFMAs for
+  // every fragment read of the following 16 K -- with one wave per SIMD nothing else
+  // would cover the LDS latency.  The last 16 MFMAs of a step need registers only, so
+  // the compiler may run them behind the barrier, over the first reads of the next stage.
   const int nk = a.K / TK;
   bf16x8_t af[2][4], bfr[2][4];
   auto mfma16 = [&](int buf) {
@@ -116,32 +116,28 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs a) {
       for (int j = 0; j < 4; ++j)
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][i], bfr[buf][j], acc[i][j], 0, 0, 0);
   };
-  load_global(0);
-  store_lds(0);
+  fill_stage(0, 0);
+  __builtin_amdgcn_s_waitcnt(0);  // everything outstanding, the LDS fills included
   __syncthreads();
   read_frags(af[0], bfr[0], smem, 0);
   for (int ks = 0; ks + 1 < nk; ++ks) {
     const int stage = ks & 1;
     const uint8_t* st = smem + stage * STAGE_BYTES;
-    load_global((ks + 1) * TK);
+    fill_stage(stage ^ 1, (ks + 1) * TK);  // the other stage was last read before the previous barrier
 #pragma unroll
     for (int kk = 0; kk < 3; ++kk) {
       read_frags(af[(kk + 1) & 1], bfr[(kk + 1) & 1], st, kk + 1);
       mfma16(kk & 1);
     }
-    store_lds(stage ^ 1);  // the other stage was last read before the previous barrier
     mfma16(1);
-    __builtin_amdgcn_sched_group_barrier(0x020, 16, 0);  // VMEM reads
+    __builtin_amdgcn_sched_group_barrier(0x020, 16, 0);  // the LDS fills (VMEM)
 #pragma unroll
     for (int n = 0; n < 24; ++n) {
       __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);  // MFMA
       __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // DS read
     }
-#pragma unroll
-    for (int n = 0; n < 16; ++n) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
-      __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);  // DS write
-    }
+    __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);
+    __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
     read_frags(af[0], bfr[0], smem + (stage ^ 1) * STAGE_BYTES, 0);
   }
