@@ -404,8 +404,45 @@ int vte_set_policy(vte_ctx* ctx, const vte_policy_vtbl* vtbl, void* user);
  *              ready or in flight, and the widest of all otherwise.  In both
  *              classes an op stays ready, rather than settling for less, when the
  *              pCtx it should get is blocked only by leases of its own vstream. */
-enum { VTE_POLICY_WIDEST = 0, VTE_POLICY_QUEUE_STATE = 1 };
+enum { VTE_POLICY_WIDEST = 0, VTE_POLICY_QUEUE_STATE = 1, VTE_POLICY_TPUT_PLAN = 2, VTE_POLICY_TPOT_FIRST = 3 };
+/*  TPUT_PLAN   the Throughput-Oriented policy (Sec. 5, Algorithm 1): every round plans
+ *              all ready ops together.  MinBind gives as many of them as possible, in
+ *              age order (one head per vstream), a minimum-size pCtx that overlaps no
+ *              other assignment; then the feasible expansion with the largest marginal
+ *              gain G_o(p,p') = (P_o(m(p')) - P_o(m(p))) / (m(p') - m(p)),
+ *              P_o(m) = T^_o(m_min) / T^_o(m), is applied until none is positive.  An op
+ *              without a profile counts as scaling perfectly.  Pick returns the next
+ *              planned op, Select returns A[o]; an op planned onto a pCtx that only
+ *              leases of its own vstream block stays ready until they drain.  `slack`
+ *              and `keep_free_cus` are unused.
+ *  TPOT_FIRST  TPUT_PLAN for everything except vstreams with a TPOT target
+ *              (vte_vstream_set_tpot).  Each of those gets an exclusive standing pCtx
+ *              once the ops of one token have been submitted (they define its chain):
+ *              the narrowest node whose profiled token time times (1 + slack) meets the
+ *              target (the whole device if none does).  The next-token deadline is the
+ *              previous token's completion plus the target; completion is predicted
+ *              from the profiles of the ops in flight and queued.  When the token is
+ *              at risk on the standing pCtx, Prepare closes the gates of overlapping
+ *              leases of other vstreams and reserves the smallest wider pCtx predicted
+ *              to meet the deadline (the widest if none is); Pick takes at-risk decodes
+ *              by earliest deadline and Select binds them to the prepared pCtx, or to
+ *              the standing one while preparation is incomplete.  The wider pCtx is
+ *              given back at a token boundary once the standing one suffices. */
 int vte_set_builtin_policy(vte_ctx* ctx, int which, double slack, int keep_free_cus);
+
+/* Declares `vs` a decode stream with a time-per-output-token target: every
+ * `ops_per_token` completed ops are one token.  tpot_seconds = 0 removes the target
+ * and releases its reservations.  VTE_EBUSY while the vstream has work. */
+int vte_vstream_set_tpot(vte_vstream* vs, double tpot_seconds, int ops_per_token);
+typedef struct vte_tpot_info {
+  double tpot_seconds;
+  int ops_per_token;
+  int standing_pctx;    /* -1 until profiles exist to size it from */
+  int escalated_pctx;   /* wider pCtx currently prepared, or -1 */
+  int at_risk;
+  uint64_t tokens_done, deadline_misses, escalations;
+} vte_tpot_info;
+int vte_vstream_tpot_info(vte_vstream* vs, vte_tpot_info* out);
 
 /* Gives the policy a lookahead hint; the plan it returns is validated and
  * applied (gates closed, reservation placed or left pending). */

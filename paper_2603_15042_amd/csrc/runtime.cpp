@@ -2,6 +2,7 @@
 // chains, the policy-driven dispatcher with validation, lease state machine and
 // completion propagation (Sec. 4.2 - 4.5 of the paper), behind the C ABI.
 #include "runtime.h"
+#include "planner.h"
 
 #include <algorithm>
 #include <cstring>
@@ -105,6 +106,46 @@ void retire_one(vte_ctx* c, int id) {
   settle_reservations(c);
 }
 
+// ---- lease control with the runtime lock held (Sec. 4.3) -------------------------
+
+void close_gate_locked(vte_ctx* c, int id) {
+  Pctx& p = c->pool.at(id);
+  if (p.state == kLeased) {
+    p.state = kDraining;  // outstanding work continues, no new admissions
+    p.gate_open = false;
+    ++c->stats.gates_closed;
+  }
+}
+
+int reserve_locked(vte_ctx* c, int id, int vs) {
+  Pctx& p = c->pool.at(id);
+  if (p.reserved_for >= 0 && p.reserved_for != vs) { set_error("pCtx is reserved for another vstream"); return VTE_EBUSY; }
+  std::vector<int> ov;
+  c->pool.active_overlapping(id, &ov);
+  for (int o : ov) {
+    const Pctx& q = c->pool.at(o);
+    if (q.reserved_for >= 0 && q.reserved_for != vs) { set_error("overlaps a reservation of another vstream"); return VTE_EBUSY; }
+  }
+  p.reserved_for = vs;
+  ++c->stats.reservations;
+  if (p.state == kIdle) {
+    c->pool.set_active(id, true);  // from now on unrelated leases are excluded
+    if (ov.empty()) { p.state = kReserved; p.reservation_pending = false; }
+    else p.reservation_pending = true;  // waits for overlapping work to drain
+  }
+  // leased / draining: becomes RESERVED when its outstanding count reaches zero
+  return VTE_OK;
+}
+
+void unreserve_locked(vte_ctx* c, int id) {
+  Pctx& p = c->pool.at(id);
+  p.reserved_for = -1;
+  p.reservation_pending = false;
+  if (p.state == kReserved) p.state = kIdle;
+  if (p.state == kIdle) c->pool.set_active(id, false);
+  settle_reservations(c);
+}
+
 // ---- completion propagation (Sec. 4.4) -------------------------------------------
 
 void record_op(vte_ctx* c, const Op* op) {
@@ -131,6 +172,14 @@ void complete_op(vte_ctx* c, Op* op) {
   if (op->vs >= 0) {
     vte_vstream* vs = c->vstreams[op->vs];
     --vs->unfinished_bound;
+    if (vs->tpot > 0) {
+      ++vs->ops_done;
+      if (vs->ops_done % static_cast<uint64_t>(vs->ops_per_token) == 0) {  // a token is out
+        ++vs->tokens_done;
+        if (vs->t_ref >= 0 && op->t_done > vs->t_ref + vs->tpot) ++vs->deadline_misses;
+        vs->t_ref = op->t_done;
+      }
+    }
   }
   --c->inflight_by_class[op->klass];
   ++c->stats.completed;
@@ -379,6 +428,19 @@ int bind_and_submit(vte_ctx* c, Op* op, int pctx, bool record_now) {
   return VTE_OK;
 }
 
+// E: non-conflicting pCtxs that can run the op unchanged
+void eligible_set(vte_ctx* c, const Op* op, int pinned, std::vector<int>* out) {
+  out->clear();
+  for (int id = 0; id < c->pool.size(); ++id) {
+    if (pinned >= 0 && id != pinned) continue;
+    if (!compatible(op->desc, c->pool.at(id))) continue;
+    if (can_admit(c, id, op->vs) != VTE_OK) continue;
+    out->push_back(id);
+  }
+}
+
+bool planned_round(vte_ctx* c, const std::vector<vte_ready_op>& ready, const std::vector<Op*>& ready_ops);
+
 // One dispatch round: gather the ready heads, let the policy pick and select,
 // validate, submit.  Returns true if something was bound.
 bool dispatch_round(vte_ctx* c) {
@@ -399,6 +461,7 @@ bool dispatch_round(vte_ctx* c) {
     ready_ops.push_back(op);
   }
   if (ready.empty()) return false;
+  if (!c->custom_policy && c->builtin >= VTE_POLICY_TPUT_PLAN) return planned_round(c, ready, ready_ops);
 
   std::vector<vte_pctx_info> infos(c->pool.size());
   for (int i = 0; i < c->pool.size(); ++i) fill_info(c->pool, i, &infos[i]);
@@ -427,14 +490,8 @@ bool dispatch_round(vte_ctx* c) {
     tried[ri] = 1;
     Op* op = ready_ops[ri];
     const vte_ready_op& ro = ready[ri];
-    // E: non-conflicting pCtxs that can run the op unchanged
     std::vector<int> eligible;
-    for (int id = 0; id < c->pool.size(); ++id) {
-      if (ro.pinned_pctx >= 0 && id != ro.pinned_pctx) continue;
-      if (!compatible(op->desc, c->pool.at(id))) continue;
-      if (can_admit(c, id, op->vs) != VTE_OK) continue;
-      eligible.push_back(id);
-    }
+    eligible_set(c, op, ro.pinned_pctx, &eligible);
     if (eligible.empty()) continue;
     int sel = c->custom_policy && c->policy.select
                   ? c->policy.select(c->policy_user, &ro, eligible.data(), static_cast<int>(eligible.size()), &S)
@@ -454,12 +511,211 @@ bool dispatch_round(vte_ctx* c) {
   return bound_any;
 }
 
+// ---- plan-driven policies (Sec. 5: Throughput-Oriented, TPOT-First) ---------------------
+
+// Seconds the ops of `vs` that belong to its current token are predicted to need
+// from now: ops already in flight at the width they run on, queued ones at
+// `width`.  Ops the application has not submitted yet are unknown and count as 0.
+double tpot_remaining(vte_ctx* c, const vte_vstream* vs, int width) {
+  int left = vs->ops_per_token - static_cast<int>(vs->ops_done % static_cast<uint64_t>(vs->ops_per_token));
+  double sum = 0;
+  for (const Op* op : c->inflight) {
+    if (left <= 0) break;
+    if (op->vs != vs->id) continue;
+    const double t = profile_time(c, op->desc->profile_key, c->pool.at(op->pctx).width);
+    if (t > 0) sum += t;
+    --left;
+  }
+  for (const Op* op : vs->queue) {
+    if (left <= 0) break;
+    const double t = profile_time(c, op->desc->profile_key, width);
+    if (t > 0) sum += t;
+    --left;
+  }
+  return sum;
+}
+
+// Profiled time of one token of `vs` at `width`: the sum over the distinct
+// descriptors of its recurring chain; -1 while any of them lacks a profile.
+double tpot_token_time(vte_ctx* c, const vte_vstream* vs, int width) {
+  if (vs->recent_keys.empty()) return -1.0;
+  double sum = 0;
+  for (uint64_t key : vs->recent_keys) {
+    const double t = profile_time(c, key, width);
+    if (t <= 0) return -1.0;
+    sum += t;
+  }
+  return sum;
+}
+
+bool reservable_for(vte_ctx* c, int id, int vs) {
+  const Pctx& p = c->pool.at(id);
+  if (p.reserved_for >= 0 && p.reserved_for != vs) return false;
+  std::vector<int> ov;
+  c->pool.active_overlapping(id, &ov);
+  for (int o : ov) {
+    const Pctx& q = c->pool.at(o);
+    if (q.reserved_for >= 0 && q.reserved_for != vs) return false;
+  }
+  return true;
+}
+
+// TPOT-First bookkeeping, run by the dispatcher before every dispatch round: the
+// standing reservation, the next-token deadline d_o = (previous token's
+// completion) + target, the prediction on the standing pCtx including queued
+// decode work, and Prepare when the token is at risk.
+void tpot_maintain(vte_ctx* c) {
+  const double now = c->now();
+  for (vte_vstream* vs : c->vstreams) {
+    if (!vs || !vs->alive || vs->tpot <= 0) continue;
+    // standing pCtx: the narrowest width whose profiled token time meets the target
+    if (vs->standing < 0) {
+      if (vs->ops_submitted < static_cast<uint64_t>(vs->ops_per_token)) continue;  // the chain of one token is not known yet
+      int want = -1;
+      std::vector<int> widths;
+      for (int id = 0; id < c->pool.size(); ++id)
+        if (c->pool.at(id).kind == kNode) widths.push_back(c->pool.at(id).width);
+      std::sort(widths.begin(), widths.end());
+      widths.erase(std::unique(widths.begin(), widths.end()), widths.end());
+      bool profiled = false;
+      for (int w : widths) {
+        const double t = tpot_token_time(c, vs, w);
+        if (t <= 0) continue;
+        profiled = true;
+        if (t * (1.0 + c->slack) <= vs->tpot) { want = w; break; }
+      }
+      if (!profiled) continue;                 // nothing to size it from yet
+      if (want < 0) want = c->pool.total_cus();  // no width meets the target: the whole device
+      for (int id = c->pool.size() - 1; id >= 0 && vs->standing < 0; --id) {
+        const Pctx& p = c->pool.at(id);
+        if (p.kind != kNode || p.width != want || !reservable_for(c, id, vs->id)) continue;
+        if (reserve_locked(c, id, vs->id) == VTE_OK) vs->standing = id;
+      }
+      if (vs->standing < 0) continue;
+    }
+    const bool idle = vs->queue.empty() && vs->unfinished_bound == 0;
+    const uint64_t token_now = vs->ops_done / static_cast<uint64_t>(vs->ops_per_token);
+    const int w_st = c->pool.at(vs->standing).width;
+    const double deadline = vs->t_ref + vs->tpot;
+    const bool at_risk = !idle && vs->t_ref >= 0 && now + tpot_remaining(c, vs, w_st) > deadline;
+    vs->at_risk = at_risk;
+    if (vs->escalated >= 0) {
+      // give the wider pCtx back at a token boundary once the standing one suffices again
+      if (idle || (!at_risk && token_now > vs->escalated_token)) {
+        unreserve_locked(c, vs->escalated);
+        vs->escalated = -1;
+      }
+      continue;
+    }
+    if (!at_risk) continue;
+    // Prepare: the smallest wider pCtx predicted to meet the deadline (the widest if none does)
+    int target = -1;
+    bool target_meets = false;
+    for (int id = 0; id < c->pool.size(); ++id) {
+      const Pctx& p = c->pool.at(id);
+      if (p.width <= w_st || !c->pool.overlaps(id, vs->standing) || !reservable_for(c, id, vs->id)) continue;
+      const bool meets = now + tpot_remaining(c, vs, p.width) <= deadline;
+      bool better;
+      if (target < 0) better = true;
+      else if (meets != target_meets) better = meets;
+      else better = meets ? p.width < c->pool.at(target).width : p.width > c->pool.at(target).width;
+      if (better) { target = id; target_meets = meets; }
+    }
+    if (target < 0) continue;
+    std::vector<int> ov;
+    c->pool.active_overlapping(target, &ov);
+    for (int o : ov) {
+      const Pctx& q = c->pool.at(o);
+      if (q.state == kLeased && q.holder != vs->id) close_gate_locked(c, o);  // drain overlapping best-effort work
+    }
+    if (reserve_locked(c, target, vs->id) == VTE_OK) {
+      vs->escalated = target;
+      vs->escalated_token = token_now;
+      ++vs->escalations;
+    }
+  }
+}
+
+// One dispatch round of the plan-driven policies.  TPOT-First places the decode
+// ops of vstreams with a target first (earliest deadline, at-risk first) on their
+// prepared or standing pCtx; everything else follows the Throughput-Oriented plan:
+// Pick returns the next planned op in age order, Select returns A[o].
+bool planned_round(vte_ctx* c, const std::vector<vte_ready_op>& ready, const std::vector<Op*>& ready_ops) {
+  const int n = static_cast<int>(ready.size());
+  bool bound_any = false;
+  std::vector<char> handled(n, 0);
+  auto bind = [&](int i, int pctx) {
+    Op* op = ready_ops[i];
+    if (bind_and_submit(c, op, pctx, c->cfg.mode != VTE_MODE_PIPELINED) != VTE_OK) return false;
+    c->vstreams[op->vs]->queue.pop_front();
+    bound_any = true;
+    return true;
+  };
+
+  if (c->builtin == VTE_POLICY_TPOT_FIRST) {
+    std::vector<int> dec;
+    for (int i = 0; i < n; ++i) {
+      const vte_vstream* vs = c->vstreams[ready[i].vstream];
+      if (vs->tpot > 0 && vs->standing >= 0 && ready[i].pinned_pctx < 0) dec.push_back(i);
+    }
+    std::stable_sort(dec.begin(), dec.end(), [&](int a, int b) {
+      const vte_vstream* va = c->vstreams[ready[a].vstream];
+      const vte_vstream* vb = c->vstreams[ready[b].vstream];
+      if (va->at_risk != vb->at_risk) return va->at_risk;
+      return va->t_ref + va->tpot < vb->t_ref + vb->tpot;
+    });
+    for (int i : dec) {
+      handled[i] = 1;
+      const vte_vstream* vs = c->vstreams[ready[i].vstream];
+      std::vector<int> el;
+      eligible_set(c, ready_ops[i], -1, &el);
+      auto has = [&](int id) { return id >= 0 && std::find(el.begin(), el.end(), id) != el.end(); };
+      if (vs->escalated >= 0) {
+        if (has(vs->escalated)) { bind(i, vs->escalated); continue; }
+        // blocked only by this vstream's own in-flight ops: it frees up as they retire
+        if (blocked_by_own_leases_only(c, vs->escalated, &ready[i])) continue;
+        // preparation incomplete (overlapping work still drains): use what is available
+      }
+      if (has(vs->standing)) bind(i, vs->standing);
+      // else defer: the standing pCtx is exclusive, so this only waits for the vstream's own work
+    }
+  }
+
+  std::vector<int> idx;
+  std::vector<PlanOp> ops;
+  for (int i = 0; i < n; ++i) {
+    if (handled[i]) continue;
+    PlanOp po;
+    po.age = ready[i].age;
+    po.pred_pctx = ready[i].pred_pctx;
+    eligible_set(c, ready_ops[i], ready[i].pinned_pctx, &po.eligible);
+    for (int id = 0; id < c->pool.size(); ++id)
+      if (blocked_by_own_leases_only(c, id, &ready[i])) po.later.push_back(id);
+    idx.push_back(i);
+    ops.push_back(po);
+  }
+  if (ops.empty()) return bound_any;
+  const std::vector<int> A = tput_plan(c->pool, ops, [&](int o, int width) {
+    return profile_time(c, ready[idx[o]].desc.profile_key, width);
+  });
+  std::vector<int> order(ops.size());
+  for (size_t o = 0; o < order.size(); ++o) order[o] = static_cast<int>(o);
+  std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return ops[a].age < ops[b].age; });
+  for (int o : order) {
+    if (A[o] < 0) continue;
+    if (std::find(ops[o].eligible.begin(), ops[o].eligible.end(), A[o]) == ops[o].eligible.end()) continue;  // waits for its own lease
+    bind(idx[o], A[o]);
+  }
+  return bound_any;
+}
+
 void dispatcher_main(vte_ctx* c) {
   c->backend->make_current();
   Lock lk(c->mu);
   while (true) {
     const uint64_t seen = c->change_seq;
     bool progress = poll_completions(c);
+    if (!c->custom_policy && c->builtin == VTE_POLICY_TPOT_FIRST) tpot_maintain(c);
     // keep binding while ops become bindable (PIPELINED chains, freed leases)
     while (dispatch_round(c)) progress = true;
     flush_records(c);  // PIPELINED: one completion record per burst and pCtx instead of one per launch
@@ -713,6 +969,8 @@ int vte_submit_after(vte_vstream* vs, const vte_desc* d, const vte_token* deps, 
   op->t_submit = c->now();
   op->deps.push_back(vs->tail);  // stream order: depends on the tail, becomes the tail
   for (int i = 0; i < n_deps; ++i) op->deps.push_back(deps[i]);
+  if (vs->tpot > 0 && vs->queue.empty() && vs->unfinished_bound == 0) vs->t_ref = op->t_submit;  // the clock of an idle stream starts now
+  ++vs->ops_submitted;
   vs->tail = op->tok;
   vs->queue.push_back(op);
   auto& rk = vs->recent_keys;  // move-to-front list of the chain's distinct descriptors
@@ -787,12 +1045,7 @@ int vte_vstream_destroy(vte_vstream* vs) {
 int vte_pctx_close_gate(vte_ctx* c, int id) {
   if (!c || id < 0 || id >= c->pool.size()) { set_error("close_gate: bad argument"); return VTE_EINVAL; }
   Lock lk(c->mu);
-  Pctx& p = c->pool.at(id);
-  if (p.state == kLeased) {
-    p.state = kDraining;  // outstanding work continues, no new admissions
-    p.gate_open = false;
-    ++c->stats.gates_closed;
-  }
+  close_gate_locked(c, id);
   bump(c);
   return VTE_OK;
 }
@@ -800,36 +1053,51 @@ int vte_pctx_close_gate(vte_ctx* c, int id) {
 int vte_pctx_reserve(vte_ctx* c, int id, vte_vstream* vs) {
   if (!c || !vs || vs->ctx != c || id < 0 || id >= c->pool.size()) { set_error("reserve: bad argument"); return VTE_EINVAL; }
   Lock lk(c->mu);
-  Pctx& p = c->pool.at(id);
-  if (p.reserved_for >= 0 && p.reserved_for != vs->id) { set_error("pCtx is reserved for another vstream"); return VTE_EBUSY; }
-  std::vector<int> ov;
-  c->pool.active_overlapping(id, &ov);
-  for (int o : ov) {
-    const Pctx& q = c->pool.at(o);
-    if (q.reserved_for >= 0 && q.reserved_for != vs->id) { set_error("overlaps a reservation of another vstream"); return VTE_EBUSY; }
-  }
-  p.reserved_for = vs->id;
-  ++c->stats.reservations;
-  if (p.state == kIdle) {
-    c->pool.set_active(id, true);  // from now on unrelated leases are excluded
-    if (ov.empty()) { p.state = kReserved; p.reservation_pending = false; }
-    else p.reservation_pending = true;  // waits for overlapping work to drain
-  }
-  // leased / draining: becomes RESERVED when its outstanding count reaches zero
-  bump(c);
-  return VTE_OK;
+  const int rc = reserve_locked(c, id, vs->id);
+  if (rc == VTE_OK) bump(c);
+  return rc;
 }
 
 int vte_pctx_unreserve(vte_ctx* c, int id) {
   if (!c || id < 0 || id >= c->pool.size()) { set_error("unreserve: bad argument"); return VTE_EINVAL; }
   Lock lk(c->mu);
-  Pctx& p = c->pool.at(id);
-  p.reserved_for = -1;
-  p.reservation_pending = false;
-  if (p.state == kReserved) p.state = kIdle;
-  if (p.state == kIdle) c->pool.set_active(id, false);
-  settle_reservations(c);
+  unreserve_locked(c, id);
   bump(c);
+  return VTE_OK;
+}
+
+// ---- TPOT target of a decode vstream (Sec. 5, TPOT-First) ----------------------------------
+
+int vte_vstream_set_tpot(vte_vstream* vs, double tpot_seconds, int ops_per_token) {
+  vte_ctx* c = ctx_of(vs);
+  if (!c || tpot_seconds < 0 || (tpot_seconds > 0 && ops_per_token < 1)) { set_error("set_tpot: bad argument"); return VTE_EINVAL; }
+  Lock lk(c->mu);
+  if (!vs->alive) { set_error("vstream was destroyed"); return VTE_EINVAL; }
+  if (!vs->queue.empty() || vs->unfinished_bound > 0) { set_error("set_tpot: the vstream has work"); return VTE_EBUSY; }
+  if (vs->escalated >= 0) { unreserve_locked(c, vs->escalated); vs->escalated = -1; }
+  if (vs->standing >= 0) { unreserve_locked(c, vs->standing); vs->standing = -1; }
+  vs->tpot = tpot_seconds;
+  vs->ops_per_token = tpot_seconds > 0 ? ops_per_token : 0;
+  vs->ops_done = vs->ops_submitted = vs->tokens_done = vs->deadline_misses = vs->escalations = 0;
+  vs->t_ref = -1;
+  vs->at_risk = false;
+  bump(c);
+  return VTE_OK;
+}
+
+int vte_vstream_tpot_info(vte_vstream* vs, vte_tpot_info* out) {
+  vte_ctx* c = ctx_of(vs);
+  if (!c || !out) { set_error("tpot_info: bad argument"); return VTE_EINVAL; }
+  Lock lk(c->mu);
+  std::memset(out, 0, sizeof *out);
+  out->tpot_seconds = vs->tpot;
+  out->ops_per_token = vs->ops_per_token;
+  out->standing_pctx = vs->standing;
+  out->escalated_pctx = vs->escalated;
+  out->at_risk = vs->at_risk ? 1 : 0;
+  out->tokens_done = vs->tokens_done;
+  out->deadline_misses = vs->deadline_misses;
+  out->escalations = vs->escalations;
   return VTE_OK;
 }
 
@@ -845,7 +1113,7 @@ int vte_set_policy(vte_ctx* c, const vte_policy_vtbl* vtbl, void* user) {
 }
 
 int vte_set_builtin_policy(vte_ctx* c, int which, double slack, int keep_free_cus) {
-  if (!c || (which != VTE_POLICY_WIDEST && which != VTE_POLICY_QUEUE_STATE) || slack < 0 || keep_free_cus < 0) {
+  if (!c || which < VTE_POLICY_WIDEST || which > VTE_POLICY_TPOT_FIRST || slack < 0 || keep_free_cus < 0) {
     set_error("set_builtin_policy: bad argument"); return VTE_EINVAL;
   }
   Lock lk(c->mu);

@@ -98,6 +98,18 @@ struct vte_vstream {
   std::deque<vte::Op*> queue;  // submitted, not yet bound, in order
   int unfinished_bound = 0;    // bound (in flight) ops of this stream
   std::vector<uint64_t> recent_keys;  // profile keys of the last distinct descriptors submitted (newest first)
+  // TPOT-First (Sec. 5): per-token deadline bookkeeping; tpot <= 0: none
+  double tpot = 0;
+  int ops_per_token = 0;
+  int standing = -1;          // exclusive standing pCtx (reserved for this vstream), or -1
+  int escalated = -1;         // wider pCtx reserved while a token is at risk, or -1
+  uint64_t ops_submitted = 0; // ops submitted since the target was set
+  uint64_t ops_done = 0;      // completed ops since the target was set
+  double t_ref = -1;          // completion of the previous token (or submission into an idle stream)
+  uint64_t escalations = 0;
+  uint64_t escalated_token = 0;  // token index at which `escalated` was reserved
+  uint64_t tokens_done = 0, deadline_misses = 0;
+  bool at_risk = false;       // the current token is predicted to miss its deadline on the standing pCtx
   bool alive = true;
 };
 

@@ -20,7 +20,7 @@ VTE_PCTX_NODE, VTE_PCTX_REMAINDER = 0, 1
 VTE_PCTX_IDLE, VTE_PCTX_LEASED, VTE_PCTX_DRAINING, VTE_PCTX_RESERVED = 0, 1, 2, 3
 VTE_EPI_NONE, VTE_EPI_SILU_MUL = 0, 1
 VTE_CLASS_LATENCY, VTE_CLASS_BEST_EFFORT = 0, 1
-VTE_POLICY_WIDEST, VTE_POLICY_QUEUE_STATE = 0, 1
+VTE_POLICY_WIDEST, VTE_POLICY_QUEUE_STATE, VTE_POLICY_TPUT_PLAN, VTE_POLICY_TPOT_FIRST = 0, 1, 2, 3
 VTE_GEMV_DOT2, VTE_GEMV_MFMA = 0, 1
 (VTE_K_RMSNORM, VTE_K_LAYERNORM, VTE_K_GEMV, VTE_K_LMHEAD, VTE_K_GATHER, VTE_K_GEMM, VTE_K_GEMV_SPLITK,
  VTE_K_LMHEAD_SPLITK, VTE_K_RMSNORM_RESHAPED, VTE_K_ARGMAX_FINISH, VTE_K_RMSNORM_GATHER,
@@ -95,6 +95,12 @@ class vte_stats_t(C.Structure):
                                            "reservations")]
 
 
+class vte_tpot_info(C.Structure):
+    _fields_ = [("tpot_seconds", C.c_double), ("ops_per_token", C.c_int), ("standing_pctx", C.c_int),
+                ("escalated_pctx", C.c_int), ("at_risk", C.c_int), ("tokens_done", C.c_uint64),
+                ("deadline_misses", C.c_uint64), ("escalations", C.c_uint64)]
+
+
 class vte_fake_log_entry(C.Structure):
     _fields_ = [("token", C.c_uint64), ("pctx", C.c_int), ("desc_hash", C.c_uint64), ("waited_on_pctx", C.c_int)]
 
@@ -113,7 +119,7 @@ EXPORTS = [
     "vte_pctx_close_gate", "vte_pctx_reserve", "vte_pctx_unreserve", "vte_set_policy", "vte_set_builtin_policy",
     "vte_hint_submit", "vte_profile_measure", "vte_profile_measure_on", "vte_profile_set", "vte_profile_get", "vte_stats", "vte_stats_read",
     "vte_stats_reset", "vte_fake_complete", "vte_fake_set_autocomplete", "vte_fake_fail_next_submits",
-    "vte_fake_log", "vte_dispatcher_quiesce", "vte_now",
+    "vte_fake_log", "vte_dispatcher_quiesce", "vte_now", "vte_vstream_set_tpot", "vte_vstream_tpot_info",
 ]
 
 _lib = None
@@ -393,6 +399,16 @@ def vte_set_policy(ctx, vtbl, user=None):
 
 def vte_set_builtin_policy(ctx, which, slack=0.1, keep_free_cus=0):
     _check(load().vte_set_builtin_policy(ctx, int(which), C.c_double(slack), int(keep_free_cus)))
+
+
+def vte_vstream_set_tpot(vs, tpot_seconds, ops_per_token):
+    _check(load().vte_vstream_set_tpot(vs, C.c_double(tpot_seconds), int(ops_per_token)))
+
+
+def vte_vstream_tpot_info(vs):
+    out = vte_tpot_info()
+    _check(load().vte_vstream_tpot_info(vs, C.byref(out)))
+    return out
 
 
 def vte_hint_submit(ctx, hint):
