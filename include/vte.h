@@ -329,6 +329,9 @@ int vte_submit(vte_vstream* vs, const vte_desc* desc, vte_token* token_out);
  * event wait would add; each token is an immutable completion point). */
 int vte_submit_after(vte_vstream* vs, const vte_desc* desc, const vte_token* deps, int n_deps,
                      vte_token* token_out);
+/* vte_submit for descs[0..n) in order, validated as a whole before the first is
+ * submitted; *last_out (may be NULL) = token of the last op submitted. */
+int vte_submit_batch(vte_vstream* vs, const vte_desc* const* descs, int n, vte_token* last_out);
 int vte_token_query(vte_ctx* ctx, vte_token token, int* done);
 int vte_token_wait(vte_ctx* ctx, vte_token token);
 int vte_vstream_sync(vte_vstream* vs); /* waits on the stream tail */

@@ -535,12 +535,12 @@ double tpot_remaining(vte_ctx* c, const vte_vstream* vs, int width) {
   return sum;
 }
 
-// Profiled time of one token of `vs` at `width`: the sum over the distinct
-// descriptors of its recurring chain; -1 while any of them lacks a profile.
+// Profiled time of one token of `vs` at `width`: the sum over the last
+// ops_per_token ops it submitted; -1 while any of them lacks a profile.
 double tpot_token_time(vte_ctx* c, const vte_vstream* vs, int width) {
-  if (vs->recent_keys.empty()) return -1.0;
+  if (vs->token_keys.empty()) return -1.0;
   double sum = 0;
-  for (uint64_t key : vs->recent_keys) {
+  for (uint64_t key : vs->token_keys) {
     const double t = profile_time(c, key, width);
     if (t <= 0) return -1.0;
     sum += t;
@@ -951,11 +951,8 @@ int vte_vstream_pin(vte_vstream* vs, int pctx) {
   return VTE_OK;
 }
 
-int vte_submit_after(vte_vstream* vs, const vte_desc* d, const vte_token* deps, int n_deps, vte_token* tok_out) {
-  vte_ctx* c = ctx_of(vs);
-  if (!c || !d || n_deps < 0 || (n_deps > 0 && !deps)) { set_error("submit: bad argument"); return VTE_EINVAL; }
-  if (d->ctx != c) { set_error("descriptor belongs to another context"); return VTE_EINVAL; }
-  Lock lk(c->mu);
+// runtime lock held
+static int submit_locked(vte_ctx* c, vte_vstream* vs, const vte_desc* d, const vte_token* deps, int n_deps, vte_token* tok_out) {
   if (!vs->alive) { set_error("vstream was destroyed"); return VTE_EINVAL; }
   for (int i = 0; i < n_deps; ++i)
     if (deps[i] >= c->next_token) { set_error("dependency on a token that was never issued"); return VTE_EINVAL; }
@@ -971,6 +968,10 @@ int vte_submit_after(vte_vstream* vs, const vte_desc* d, const vte_token* deps, 
   for (int i = 0; i < n_deps; ++i) op->deps.push_back(deps[i]);
   if (vs->tpot > 0 && vs->queue.empty() && vs->unfinished_bound == 0) vs->t_ref = op->t_submit;  // the clock of an idle stream starts now
   ++vs->ops_submitted;
+  if (vs->tpot > 0) {
+    vs->token_keys.push_back(d->profile_key);
+    if (vs->token_keys.size() > static_cast<size_t>(vs->ops_per_token)) vs->token_keys.pop_front();
+  }
   vs->tail = op->tok;
   vs->queue.push_back(op);
   auto& rk = vs->recent_keys;  // move-to-front list of the chain's distinct descriptors
@@ -981,12 +982,38 @@ int vte_submit_after(vte_vstream* vs, const vte_desc* d, const vte_token* deps, 
   c->live[op->tok] = op;
   ++c->stats.submitted;
   if (tok_out) *tok_out = op->tok;
-  bump(c);
   return VTE_OK;
+}
+
+int vte_submit_after(vte_vstream* vs, const vte_desc* d, const vte_token* deps, int n_deps, vte_token* tok_out) {
+  vte_ctx* c = ctx_of(vs);
+  if (!c || !d || n_deps < 0 || (n_deps > 0 && !deps)) { set_error("submit: bad argument"); return VTE_EINVAL; }
+  if (d->ctx != c) { set_error("descriptor belongs to another context"); return VTE_EINVAL; }
+  Lock lk(c->mu);
+  const int rc = submit_locked(c, vs, d, deps, n_deps, tok_out);
+  if (rc == VTE_OK) bump(c);
+  return rc;
 }
 
 int vte_submit(vte_vstream* vs, const vte_desc* d, vte_token* tok_out) {
   return vte_submit_after(vs, d, nullptr, 0, tok_out);
+}
+
+int vte_submit_batch(vte_vstream* vs, const vte_desc* const* descs, int n, vte_token* last_out) {
+  vte_ctx* c = ctx_of(vs);
+  if (!c || !descs || n < 1) { set_error("submit_batch: bad argument"); return VTE_EINVAL; }
+  for (int i = 0; i < n; ++i)
+    if (!descs[i] || descs[i]->ctx != c) { set_error("submit_batch: null descriptor or one of another context"); return VTE_EINVAL; }
+  Lock lk(c->mu);  // the dispatcher sees the whole batch at once
+  if (!vs->alive) { set_error("vstream was destroyed"); return VTE_EINVAL; }
+  vte_token last = 0;
+  for (int i = 0; i < n; ++i) {
+    const int rc = submit_locked(c, vs, descs[i], nullptr, 0, &last);
+    if (rc != VTE_OK) { if (i > 0) bump(c); return rc; }  // out of memory: earlier ops stay submitted
+    if (last_out) *last_out = last;
+  }
+  bump(c);
+  return VTE_OK;
 }
 
 int vte_token_query(vte_ctx* c, vte_token t, int* done) {
@@ -1081,6 +1108,7 @@ int vte_vstream_set_tpot(vte_vstream* vs, double tpot_seconds, int ops_per_token
   vs->ops_done = vs->ops_submitted = vs->tokens_done = vs->deadline_misses = vs->escalations = 0;
   vs->t_ref = -1;
   vs->at_risk = false;
+  vs->token_keys.clear();
   bump(c);
   return VTE_OK;
 }

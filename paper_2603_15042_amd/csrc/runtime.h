@@ -104,6 +104,7 @@ struct vte_vstream {
   int standing = -1;          // exclusive standing pCtx (reserved for this vstream), or -1
   int escalated = -1;         // wider pCtx reserved while a token is at risk, or -1
   uint64_t ops_submitted = 0; // ops submitted since the target was set
+  std::deque<uint64_t> token_keys;  // profile keys of the last ops_per_token ops submitted: one token's chain
   uint64_t ops_done = 0;      // completed ops since the target was set
   double t_ref = -1;          // completion of the previous token (or submission into an idle stream)
   uint64_t escalations = 0;

@@ -186,5 +186,55 @@ class DecodeChain:
         self.desc = {}
 
 
+class LayeredDecode:
+    """L copies of the decode layer (RMSNorm, QKV, O on the Q slice, gate/up+SiLU, down), each with its
+    own weights, between one embedding gather and one LM head + greedy token that feeds back into the
+    token buffer: 5L + 2 launches per step.  Every batch is built at a fixed batch size B, so a row's
+    result does not depend on which other rows share the launch.  Activation buffers are per instance,
+    weights are shared between instances."""
+
+    def __init__(self, ctx, layers_dev, head_dev, shp, B, eps=1e-6):
+        self.ctx, self.shp, self.B, self.L = ctx, shp, B, len(layers_dev)
+        D, Nq, F, V = shp.D, shp.Nqkv, shp.F, shp.V
+        self.tok = torch.zeros(B, dtype=torch.int32, device="cuda")
+        self.n, self.qkv, self.o = dev_empty((B, D)), dev_empty((B, Nq)), dev_empty((B, D))
+        self.act, self.d = dev_empty((B, F)), dev_empty((B, D))
+        self.ws = dev_zeros_bytes(vte.vte_lmhead_workspace_bytes(B, V, D))
+        ds = self.descs = []
+        for l, w in enumerate(layers_dev):
+            if l == 0:
+                ds.append(vte.vte_desc_rmsnorm_gather(ctx, head_dev["E"], self.tok, w["gamma"], self.n, None, B, V, D, eps))
+            else:
+                ds.append(vte.vte_desc_rmsnorm(ctx, self.d, w["gamma"], self.n, B, D, eps))
+            ds.append(vte.vte_desc_gemv(ctx, w["Wqkv"], self.n, self.qkv, B, Nq, D))
+            ds.append(vte.vte_desc_gemv_strided(ctx, w["Wo"], self.qkv, Nq, self.o, D, B, D, D))
+            ds.append(vte.vte_desc_gemv(ctx, w["Wgu"], self.o, self.act, B, 2 * F, D, vte.VTE_EPI_SILU_MUL))
+            ds.append(vte.vte_desc_gemv(ctx, w["Wd"], self.act, self.d, B, D, F))
+        lm = vte.vte_desc_lmhead_argmax(ctx, head_dev["Wlm"], self.d, self.tok, None, self.ws, B, V, D)
+        ds.append(lm)
+        ds.append(vte.vte_desc_argmax_finish(ctx, lm))
+        self.step = vte.desc_array(ds)
+        self.ops_per_step = len(ds)
+        self.bytes_per_step = sum(vte.vte_desc_info(d).bytes for d in ds)
+
+    def distinct_descs(self):
+        """One descriptor per distinct profile key (kernel and shape), in chain order."""
+        seen, out = set(), []
+        for d in self.descs:
+            k = vte.vte_desc_info(d).profile_key
+            if k not in seen:
+                seen.add(k)
+                out.append(d)
+        return out
+
+    def submit_step(self, vs):
+        return vte.vte_submit_batch(vs, self.step)
+
+    def close(self):
+        for d in self.descs:
+            vte.vte_desc_destroy(d)
+        self.descs = []
+
+
 def upload_weights(weights_np):
     return {k: to_dev(v) for k, v in weights_np.items()}

@@ -119,7 +119,7 @@ EXPORTS = [
     "vte_pctx_close_gate", "vte_pctx_reserve", "vte_pctx_unreserve", "vte_set_policy", "vte_set_builtin_policy",
     "vte_hint_submit", "vte_profile_measure", "vte_profile_measure_on", "vte_profile_set", "vte_profile_get", "vte_stats", "vte_stats_read",
     "vte_stats_reset", "vte_fake_complete", "vte_fake_set_autocomplete", "vte_fake_fail_next_submits",
-    "vte_fake_log", "vte_dispatcher_quiesce", "vte_now", "vte_vstream_set_tpot", "vte_vstream_tpot_info",
+    "vte_fake_log", "vte_dispatcher_quiesce", "vte_now", "vte_vstream_set_tpot", "vte_vstream_tpot_info", "vte_submit_batch",
 ]
 
 _lib = None
@@ -352,6 +352,18 @@ def vte_vstream_pin(vs, pctx_id):
 def vte_submit(vs, desc):
     tok = C.c_uint64()
     _check(load().vte_submit(vs, desc, C.byref(tok)))
+    return tok.value
+
+
+def desc_array(descs):
+    """A C array of descriptor handles for vte_submit_batch (build once, submit many times)."""
+    return (C.c_void_p * len(descs))(*[d if isinstance(d, int) else d.value for d in descs])
+
+
+def vte_submit_batch(vs, arr):
+    """arr: desc_array(...).  Returns the token of the last op."""
+    tok = C.c_uint64()
+    _check(load().vte_submit_batch(vs, arr, len(arr), C.byref(tok)))
     return tok.value
 
 

@@ -322,3 +322,32 @@ def test_set_tpot_rejects_bad_arguments_and_busy_streams():
             vte.vte_set_builtin_policy(c, 4)
     finally:
         vte.vte_shutdown(c)
+
+
+def test_submit_batch_is_a_chain_seen_at_once():
+    c = make_ctx(vte.VTE_MODE_PIPELINED)
+    try:
+        d1 = vte.vte_desc_rmsnorm(c, A, A, A, 8, 1024, 1e-6)
+        d2 = vte.vte_desc_gemv(c, A, A, A, 8, 4096, 4096, 0)
+        vs = vte.vte_vstream_create(c)
+        arr = vte.desc_array([d1, d2, d1, d2])
+        last = vte.vte_submit_batch(vs, arr)
+        vte.vte_dispatcher_quiesce(c)
+        log = vte.vte_fake_log(c)
+        assert [e.token for e in log] == [last - 3, last - 2, last - 1, last]   # stream order, consecutive tokens
+        h1, h2 = vte.vte_desc_info(d1).hash, vte.vte_desc_info(d2).hash
+        assert [e.desc_hash for e in log] == [h1, h2, h1, h2]
+        assert len({e.pctx for e in log}) == 1
+        finish(c, [e.token for e in log])
+        other = make_ctx()
+        try:
+            foreign = vte.vte_desc_rmsnorm(other, A, A, A, 8, 1024, 1e-6)
+            with pytest.raises(vte.VteError) as e:
+                vte.vte_submit_batch(vs, vte.desc_array([d1, foreign]))
+            assert e.value.code == vte.VTE_EINVAL
+            vte.vte_dispatcher_quiesce(c)
+            assert len(vte.vte_fake_log(c)) == 4               # validated as a whole: nothing was submitted
+        finally:
+            vte.vte_shutdown(other)
+    finally:
+        vte.vte_shutdown(c)
