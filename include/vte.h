@@ -105,6 +105,9 @@ typedef struct vte_pool_cfg {
   int stats_capacity;  /* ring size of per-op records kept for vte_stats_read; 0 = 65536 */
   unsigned device_timing_mask; /* bit k set: launches of kernel VTE_K_k are bracketed by timing events
                                   on their own stream and vte_op_record.gpu_seconds is filled */
+  int dispatch_pipes;  /* compute pipes the device deals its queues to, round-robin in creation order
+                          (measured: 4 on MI355X); 0 = 4.  Queues are created in an order that puts
+                          disjoint pCtxs on different pipes where it can (Sec. 4.3, bounded pool). */
 } vte_pool_cfg;
 
 /* Fills *cfg with the defaults (HIP, device CU count, leaf 32, one remainder per level, STRICT). */
@@ -136,10 +139,15 @@ typedef struct vte_pctx_info {
   int outstanding;   /* submitted, not yet observed complete */
   int reserved_for;  /* vstream id holding (or waiting for) a reservation, else -1 */
   uint32_t mask[8];  /* CU mask, bit i of word i/32 */
+  int pipe;          /* dispatch pipe of its queue; pCtxs on one pipe dispatch one kernel at a time */
 } vte_pctx_info;
 
 int vte_pool_count(vte_ctx* ctx, int* count);
 int vte_pool_info(vte_ctx* ctx, int pctx_id, vte_pctx_info* info);
+/* The order in which the backend queues were created: ids[k] is the pCtx whose queue
+ * was the k-th, or -1 for a placeholder queue; the k-th queue sits on pipe
+ * k % dispatch_pipes.  Copies min(cap, *n_out) entries. */
+int vte_pool_creation_order(vte_ctx* ctx, int* ids, int cap, int* n_out);
 /* First pCtx of kind NODE with this width (lowest id), or the n-th with `index`. */
 int vte_pool_find(vte_ctx* ctx, int kind, int width, int index, int* pctx_id);
 /* 1 if the two pCtxs share a CU.  Decided by walking the hierarchy, not by
@@ -422,9 +430,12 @@ enum { VTE_POLICY_WIDEST = 0, VTE_POLICY_QUEUE_STATE = 1, VTE_POLICY_TPUT_PLAN =
  *              (vte_vstream_set_tpot).  Each of those gets an exclusive standing pCtx
  *              once the ops of one token have been submitted (they define its chain):
  *              the narrowest node whose profiled token time times (1 + slack) meets the
- *              target (the whole device if none does).  The next-token deadline is the
+ *              target (the whole device if none does), lowest pool ids first; a stream
+ *              idle for two target periods gives it back until its next submission.  The next-token deadline is the
  *              previous token's completion plus the target; completion is predicted
- *              from the profiles of the ops in flight and queued.  When the token is
+ *              from the profiles of the ops in flight and queued, scaled by a running
+ *              average of how much slower than its solo profile the stream's last tokens
+ *              ran (sharing HBM and caches with co-tenants).  When the token is
  *              at risk on the standing pCtx, Prepare closes the gates of overlapping
  *              leases of other vstreams and reserves the smallest wider pCtx predicted
  *              to meet the deadline (the widest if none is); Pick takes at-risk decodes

@@ -33,15 +33,30 @@ std::vector<int> tput_plan(const Pool& pool, const std::vector<PlanOp>& ops, con
     return true;
   };
 
+  // progress on `p` counts half when its queue shares a dispatch pipe with another tenant
+  auto shares_pipe = [&](int o, int p) {
+    const int pipe = pool.at(p).pipe;
+    if ((ops[o].busy_pipes >> pipe) & 1u) return true;
+    for (int q = 0; q < n; ++q)
+      if (q != o && A[q] >= 0 && pool.at(A[q]).pipe == pipe) return true;
+    return false;
+  };
+  auto progress = [&](int o, int p) {
+    return plan_progress(pool, time, o, pool.at(p).width) * (shares_pipe(o, p) ? 0.5 : 1.0);
+  };
+
   // MinBind: oldest first, the narrowest eligible pCtx that overlaps nothing assigned so far
-  // (equal widths: the predecessor's pCtx, then the lowest id, which packs leaves from one side)
+  // (equal widths: a free pipe, the predecessor's pCtx, then the lowest id, which packs leaves from one side)
   for (int o : order) {
     int best = -1;
     for (int p : ops[o].eligible) {
       if (!free_of_others(o, p)) continue;
       if (best < 0) { best = p; continue; }
       const int wb = pool.at(best).width, wp = pool.at(p).width;
-      if (wp < wb || (wp == wb && p == ops[o].pred_pctx && best != ops[o].pred_pctx)) best = p;
+      if (wp != wb) { if (wp < wb) best = p; continue; }
+      const bool sb = shares_pipe(o, best), sp = shares_pipe(o, p);
+      if (sp != sb) { if (!sp) best = p; continue; }
+      if (p == ops[o].pred_pctx && best != ops[o].pred_pctx) best = p;
     }
     A[o] = best;
   }
@@ -53,11 +68,11 @@ std::vector<int> tput_plan(const Pool& pool, const std::vector<PlanOp>& ops, con
     for (int o : order) {
       if (A[o] < 0) continue;
       const int m = pool.at(A[o]).width;
-      const double P = plan_progress(pool, time, o, m);
+      const double P = progress(o, A[o]);
       auto consider = [&](int p) {
         const int m2 = pool.at(p).width;
         if (m2 <= m || !free_of_others(o, p)) return;
-        const double g = (plan_progress(pool, time, o, m2) - P) / (m2 - m);
+        const double g = (progress(o, p) - P) / (m2 - m);
         if (g > best_g * (1 + 1e-12) && g > 0) { best_g = g; best_o = o; best_p = p; }
       };
       for (int p : ops[o].eligible) consider(p);

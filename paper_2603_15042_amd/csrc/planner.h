@@ -3,7 +3,9 @@
 // the largest number of ready ops a minimum-size, non-overlapping pCtx in age
 // order, then the feasible expansion with the largest marginal gain
 //   G_o(p, p') = (P_o(m(p')) - P_o(m(p))) / (m(p') - m(p)),  P_o(m) = T^_o(m_min) / T^_o(m)
-// is applied until none has positive gain.  Host logic only (no HIP).
+// is applied until none has positive gain.  An op whose pCtx shares a dispatch pipe
+// with another tenant takes turns with it, so its progress there counts half.
+// Host logic only (no HIP).
 #pragma once
 #include <cstdint>
 #include <functional>
@@ -18,6 +20,7 @@ struct PlanOp {
   int pred_pctx = -1;          // preferred among equals (keeps a stream edge in stream order)
   std::vector<int> eligible;   // pCtxs the op can take now
   std::vector<int> later;      // pCtxs blocked only by leases of the op's own vstream
+  uint32_t busy_pipes = 0;     // dispatch pipes that leases of other vstreams are using
 };
 
 // time(op index, width) = profiled seconds, or <= 0 when unknown (then the op is

@@ -80,6 +80,65 @@ bool Pool::build(int total_cus, int leaf_cus, int remainders, std::string* err) 
   return true;
 }
 
+void Pool::assign_pipes(int pipes) {
+  pipes_ = std::max(1, pipes);
+  const int n = size();
+  std::vector<int> order(n), color(n, -1);
+  for (int i = 0; i < n; ++i) order[i] = i;
+  std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return p_[a].width > p_[b].width; });
+  auto weight = [&](int a, int b) {
+    int w = std::min(p_[a].width, p_[b].width);
+    if (p_[a].remainder == b || p_[b].remainder == a) w *= 4;  // a node and its complement are the pair meant to run together
+    return w;
+  };
+  auto pick = [&](int x) {
+    int best = 0;
+    long best_cost = -1;
+    int best_used = 0;
+    for (int c = 0; c < pipes_; ++c) {
+      long cost = 0;
+      int used = 0;
+      for (int q = 0; q < n; ++q) {
+        if (q == x || color[q] != c) continue;
+        ++used;
+        if (!overlaps(x, q)) cost += weight(x, q);
+      }
+      if (best_cost < 0 || cost < best_cost || (cost == best_cost && used < best_used)) { best = c; best_cost = cost; best_used = used; }
+    }
+    return best;
+  };
+  for (int x : order) color[x] = pick(x);
+  for (int pass = 0; pass < 8; ++pass) {  // local improvement until nothing moves
+    bool moved = false;
+    for (int x : order) {
+      const int c = pick(x);
+      if (c != color[x]) { color[x] = c; moved = true; }
+    }
+    if (!moved) break;
+  }
+  // relabel: most used pipe first, so the creation order needs no (or few) placeholders
+  std::vector<int> count(pipes_, 0), label(pipes_), rank(pipes_);
+  for (int i = 0; i < n; ++i) ++count[color[i]];
+  for (int c = 0; c < pipes_; ++c) label[c] = c;
+  std::stable_sort(label.begin(), label.end(), [&](int a, int b) { return count[a] > count[b]; });
+  for (int r = 0; r < pipes_; ++r) rank[label[r]] = r;
+  for (int i = 0; i < n; ++i) p_[i].pipe = rank[color[i]];
+}
+
+std::vector<int> Pool::creation_order() const {
+  std::vector<std::vector<int>> by_pipe(pipes_);
+  for (int i = 0; i < size(); ++i) by_pipe[p_[i].pipe].push_back(i);
+  std::vector<size_t> next(pipes_, 0);
+  std::vector<int> out;
+  int left = size();
+  for (int k = 0; left > 0; ++k) {
+    const int c = k % pipes_;
+    if (next[c] < by_pipe[c].size()) { out.push_back(by_pipe[c][next[c]++]); --left; }
+    else out.push_back(-1);
+  }
+  return out;
+}
+
 bool Pool::is_ancestor_or_self(int anc, int node) const {
   for (int n = node; n >= 0; n = p_[n].parent)
     if (n == anc) return true;

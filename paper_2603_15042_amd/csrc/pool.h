@@ -25,6 +25,7 @@ struct Pctx {
   int remainder = -1;       // node: pCtx covering every other CU (-1 for the root)
   int leaf_lo = 0, leaf_hi = 0;  // node: leaves [lo,hi)
   std::vector<uint32_t> mask;    // one bit per CU
+  int pipe = 0;                  // dispatch pipe its queue is meant to land on (see assign_pipes)
   // ---- dynamic state (guarded by the runtime lock) ----
   int state = kIdle;
   bool gate_open = true;
@@ -70,10 +71,24 @@ class Pool {
 
   bool is_ancestor_or_self(int anc, int node) const;  // both NODE ids
 
+  // The command processor dispatches from a fixed number of pipes, and queues on
+  // the same pipe dispatch one kernel at a time: two disjoint pCtxs whose queues
+  // share a pipe do not overlap in time however many CUs are free.  Gives every
+  // pCtx a pipe in [0,pipes) so that disjoint pCtxs share one as little as
+  // possible: a node and the remainder that complements it weigh most, then
+  // pairs by the width of the narrower one.  Pipe labels are ordered by how many
+  // pCtxs use them, most first.
+  void assign_pipes(int pipes);
+  // Order in which to create the backend queues so that the k-th queue created
+  // (they are dealt to pipes round-robin) belongs to a pCtx of pipe k % pipes;
+  // -1 entries are placeholder queues that keep the rotation in step.
+  std::vector<int> creation_order() const;
+  int pipes() const { return pipes_; }
+
  private:
   int add_node(int lo, int hi, int parent, int level, int leaf_cus);
   std::vector<Pctx> p_;
-  int total_ = 0, leaf_ = 0, leaves_ = 0, words_ = 0, root_ = -1;
+  int total_ = 0, leaf_ = 0, leaves_ = 0, words_ = 0, root_ = -1, pipes_ = 1;
   int active_nodes_ = 0;       // number of active NODE pCtxs
   int active_remainders_ = 0;  // number of active REMAINDER pCtxs
   std::vector<int> active_rem_ids_;

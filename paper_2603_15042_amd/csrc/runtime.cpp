@@ -41,6 +41,7 @@ void fill_info(const Pool& pool, int id, vte_pctx_info* o) {
   o->state = p.state; o->gate_open = p.gate_open ? 1 : 0; o->outstanding = p.outstanding;
   o->reserved_for = p.reserved_for;
   for (size_t w = 0; w < p.mask.size() && w < 8; ++w) o->mask[w] = p.mask[w];
+  o->pipe = p.pipe;
 }
 
 // ---- lease state machine (Sec. 4.3 "pCtx Lifecycle") ---------------------------
@@ -146,6 +147,8 @@ void unreserve_locked(vte_ctx* c, int id) {
   settle_reservations(c);
 }
 
+double tpot_token_time(vte_ctx* c, const vte_vstream* vs, int width);
+
 // ---- completion propagation (Sec. 4.4) -------------------------------------------
 
 void record_op(vte_ctx* c, const Op* op) {
@@ -177,8 +180,17 @@ void complete_op(vte_ctx* c, Op* op) {
       if (vs->ops_done % static_cast<uint64_t>(vs->ops_per_token) == 0) {  // a token is out
         ++vs->tokens_done;
         if (vs->t_ref >= 0 && op->t_done > vs->t_ref + vs->tpot) ++vs->deadline_misses;
+        if (vs->t_ref >= 0 && vs->standing >= 0) {
+          // how much slower than its solo profile the token ran (co-tenants share HBM and caches)
+          const double solo = tpot_token_time(c, vs, c->pool.at(vs->standing).width);
+          if (solo > 0) {
+            const double f = std::min(8.0, std::max(1.0, (op->t_done - vs->t_ref) / solo));
+            vs->slowdown += 0.25 * (f - vs->slowdown);
+          }
+        }
         vs->t_ref = op->t_done;
       }
+      if (vs->queue.empty() && vs->unfinished_bound == 0) vs->t_idle = op->t_done;
     }
   }
   --c->inflight_by_class[op->klass];
@@ -532,7 +544,7 @@ double tpot_remaining(vte_ctx* c, const vte_vstream* vs, int width) {
     if (t > 0) sum += t;
     --left;
   }
-  return sum;
+  return sum * vs->slowdown;  // profiles are solo times; the factor is what sharing has cost lately
 }
 
 // Profiled time of one token of `vs` at `width`: the sum over the last
@@ -571,6 +583,7 @@ void tpot_maintain(vte_ctx* c) {
     // standing pCtx: the narrowest width whose profiled token time meets the target
     if (vs->standing < 0) {
       if (vs->ops_submitted < static_cast<uint64_t>(vs->ops_per_token)) continue;  // the chain of one token is not known yet
+      if (vs->queue.empty() && vs->unfinished_bound == 0) continue;                // idle: holds nothing
       int want = -1;
       std::vector<int> widths;
       for (int id = 0; id < c->pool.size(); ++id)
@@ -586,14 +599,37 @@ void tpot_maintain(vte_ctx* c) {
       }
       if (!profiled) continue;                 // nothing to size it from yet
       if (want < 0) want = c->pool.total_cus();  // no width meets the target: the whole device
-      for (int id = c->pool.size() - 1; id >= 0 && vs->standing < 0; --id) {
-        const Pctx& p = c->pool.at(id);
-        if (p.kind != kNode || p.width != want || !reservable_for(c, id, vs->id)) continue;
-        if (reserve_locked(c, id, vs->id) == VTE_OK) vs->standing = id;
+      // a pipe no other vstream holds or has reserved, then the lowest id: standing pCtxs pack from
+      // one side, so a pre-created remainder covers the rest
+      uint32_t taken = 0;
+      for (int id = 0; id < c->pool.size(); ++id) {
+        const Pctx& q = c->pool.at(id);
+        const bool mine = q.reserved_for == vs->id || (q.state == kLeased && q.holder == vs->id);
+        if (q.active_self && !mine) taken |= 1u << q.pipe;
       }
+      for (int pass = 0; pass < 2 && vs->standing < 0; ++pass)
+        for (int id = 0; id < c->pool.size() && vs->standing < 0; ++id) {
+          const Pctx& p = c->pool.at(id);
+          if (p.kind != kNode || p.width != want || !reservable_for(c, id, vs->id)) continue;
+          if (pass == 0 && ((taken >> p.pipe) & 1u)) continue;
+          if (reserve_locked(c, id, vs->id) == VTE_OK) vs->standing = id;
+        }
       if (vs->standing < 0) continue;
+      // exclusive: leases of other vstreams that overlap it take nothing new and drain
+      std::vector<int> ov;
+      c->pool.active_overlapping(vs->standing, &ov);
+      for (int o : ov) {
+        const Pctx& q = c->pool.at(o);
+        if (q.state == kLeased && q.holder != vs->id) close_gate_locked(c, o);
+      }
     }
     const bool idle = vs->queue.empty() && vs->unfinished_bound == 0;
+    if (idle && vs->escalated < 0 && vs->t_idle >= 0 && now - vs->t_idle > 2 * vs->tpot) {
+      // nothing for two token periods: the CUs go back until the next submission sizes it again
+      unreserve_locked(c, vs->standing);
+      vs->standing = -1;
+      continue;
+    }
     const uint64_t token_now = vs->ops_done / static_cast<uint64_t>(vs->ops_per_token);
     const int w_st = c->pool.at(vs->standing).width;
     const double deadline = vs->t_ref + vs->tpot;
@@ -689,12 +725,21 @@ bool planned_round(vte_ctx* c, const std::vector<vte_ready_op>& ready, const std
     po.age = ready[i].age;
     po.pred_pctx = ready[i].pred_pctx;
     eligible_set(c, ready_ops[i], ready[i].pinned_pctx, &po.eligible);
-    for (int id = 0; id < c->pool.size(); ++id)
+    for (int id = 0; id < c->pool.size(); ++id) {
       if (blocked_by_own_leases_only(c, id, &ready[i])) po.later.push_back(id);
+      const Pctx& q = c->pool.at(id);  // pipes other vstreams are dispatching on
+      if ((q.state == kLeased || q.state == kDraining) && q.holder != ready[i].vstream) po.busy_pipes |= 1u << q.pipe;
+    }
     idx.push_back(i);
     ops.push_back(po);
   }
   if (ops.empty()) return bound_any;
+  // age-aware: while an older op has nowhere to go, a younger one does not renew its vstream's
+  // lease; the lease drains and the next round plans both together
+  uint64_t oldest_starved = ~0ull;
+  for (size_t o = 0; o < ops.size(); ++o)
+    if (ops[o].eligible.empty() && ops[o].later.empty() && ready[idx[o]].pinned_pctx < 0)
+      oldest_starved = std::min(oldest_starved, ops[o].age);
   const std::vector<int> A = tput_plan(c->pool, ops, [&](int o, int width) {
     return profile_time(c, ready[idx[o]].desc.profile_key, width);
   });
@@ -704,6 +749,7 @@ bool planned_round(vte_ctx* c, const std::vector<vte_ready_op>& ready, const std
   for (int o : order) {
     if (A[o] < 0) continue;
     if (std::find(ops[o].eligible.begin(), ops[o].eligible.end(), A[o]) == ops[o].eligible.end()) continue;  // waits for its own lease
+    if (ops[o].age > oldest_starved && c->pool.at(A[o]).state == kLeased) continue;
     bind(idx[o], A[o]);
   }
   return bound_any;
@@ -792,12 +838,26 @@ int vte_init(vte_ctx** out, int device, const vte_pool_cfg* user_cfg) {
   if (!c->pool.build(cus, cfg.leaf_cus, cfg.with_remainders, &err)) {
     set_error(err); delete c->backend; delete c; return VTE_EINVAL;
   }
-  // pre-create every pCtx's backend stream: nothing is created on the dispatch path
-  for (int id = 0; id < c->pool.size(); ++id) {
-    Pctx& p = c->pool.at(id);
-    rc = c->backend->create_stream(p.mask.data(), static_cast<int>(p.mask.size()), &p.stream);
+  // pre-create every pCtx's backend stream: nothing is created on the dispatch path.
+  // The device deals queues to its dispatch pipes in creation order, so the order
+  // decides which pCtxs can dispatch side by side.
+  if (cfg.dispatch_pipes < 0 || cfg.dispatch_pipes > 32) { set_error("dispatch_pipes must be in [0,32]"); delete c->backend; delete c; return VTE_EINVAL; }
+  c->pool.assign_pipes(cfg.dispatch_pipes == 0 ? 4 : cfg.dispatch_pipes);
+  c->cfg.dispatch_pipes = c->pool.pipes();
+  for (int id : c->pool.creation_order()) {
+    void* s = nullptr;
+    if (id >= 0) {
+      Pctx& p = c->pool.at(id);
+      rc = c->backend->create_stream(p.mask.data(), static_cast<int>(p.mask.size()), &s);
+      if (rc == VTE_OK) p.stream = s;
+    } else {  // placeholder that keeps the rotation in step; never used
+      const Pctx& p = c->pool.at(c->pool.root());
+      rc = c->backend->create_stream(p.mask.data(), static_cast<int>(p.mask.size()), &s);
+      if (rc == VTE_OK) c->placeholder_streams.push_back(s);
+    }
     if (rc != VTE_OK) {
-      for (int j = 0; j < id; ++j) c->backend->destroy_stream(c->pool.at(j).stream);
+      for (int j = 0; j < c->pool.size(); ++j) if (c->pool.at(j).stream) c->backend->destroy_stream(c->pool.at(j).stream);
+      for (void* d : c->placeholder_streams) c->backend->destroy_stream(d);
       delete c->backend; delete c; return rc;
     }
   }
@@ -844,6 +904,7 @@ int vte_shutdown(vte_ctx* c) {
   }
   c->dispatcher.join();
   for (int id = 0; id < c->pool.size(); ++id) c->backend->destroy_stream(c->pool.at(id).stream);
+  for (void* d : c->placeholder_streams) c->backend->destroy_stream(d);
   for (vte_vstream* vs : c->vstreams) delete vs;
   for (vte_desc* d : c->descs) delete d;
   delete c->backend;
@@ -861,6 +922,14 @@ int vte_pool_info(vte_ctx* c, int id, vte_pctx_info* info) {
   if (!c || !info || id < 0 || id >= c->pool.size()) { set_error("pool_info: bad argument"); return VTE_EINVAL; }
   Lock lk(c->mu);
   fill_info(c->pool, id, info);
+  return VTE_OK;
+}
+
+int vte_pool_creation_order(vte_ctx* c, int* ids, int cap, int* n_out) {
+  if (!c || !ids || cap < 0 || !n_out) { set_error("creation_order: bad argument"); return VTE_EINVAL; }
+  const std::vector<int> order = c->pool.creation_order();
+  *n_out = static_cast<int>(order.size());
+  for (int i = 0; i < cap && i < *n_out; ++i) ids[i] = order[i];
   return VTE_OK;
 }
 
@@ -1108,6 +1177,8 @@ int vte_vstream_set_tpot(vte_vstream* vs, double tpot_seconds, int ops_per_token
   vs->ops_done = vs->ops_submitted = vs->tokens_done = vs->deadline_misses = vs->escalations = 0;
   vs->t_ref = -1;
   vs->at_risk = false;
+  vs->slowdown = 1.0;
+  vs->t_idle = -1;
   vs->token_keys.clear();
   bump(c);
   return VTE_OK;

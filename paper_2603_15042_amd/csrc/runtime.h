@@ -110,6 +110,8 @@ struct vte_vstream {
   uint64_t escalations = 0;
   uint64_t escalated_token = 0;  // token index at which `escalated` was reserved
   uint64_t tokens_done = 0, deadline_misses = 0;
+  double slowdown = 1.0;      // EWMA of observed token time / solo-profiled token time, in [1, 8]
+  double t_idle = -1;         // when the stream last ran out of work
   bool at_risk = false;       // the current token is predicted to miss its deadline on the standing pCtx
   bool alive = true;
 };
@@ -119,6 +121,7 @@ struct vte_ctx {
   int device = 0;
   vte::Backend* backend = nullptr;
   vte::Pool pool;
+  std::vector<void*> placeholder_streams;  // queues created only to keep the pipe rotation in step
 
   std::mutex mu;
   std::condition_variable cv_work;  // dispatcher sleeps here

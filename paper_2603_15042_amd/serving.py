@@ -6,8 +6,10 @@ production traces; this is a seeded synthetic stand-in with the stated distribut
 
 Requests arrive by a Poisson process, carry a prompt length (it only sizes the host-to-device copy
 that precedes the first decode step), an output length and a start token.  Up to 64 run at once,
-in four chunks of 16 rows; a chunk is one virtual stream stepping its own copy of the chain's
-activations over shared weights.  Every launch is built at batch 16, so a row's arithmetic does not
+in four chunks of 16 rows, each stepping its own copy of the chain's activations over shared
+weights; two chunks share a virtual stream and take turns on it.  Five tenants would be one too many:
+the device dispatches from four pipes and queues on one pipe run one kernel at a time, so the sweep
+keeps to two decode streams and the co-tenant.  Every launch is built at batch 16, so a row's arithmetic does not
 depend on what shares the launch, and a request's token stream is a function of its start token
 alone: every observed transition token -> next token is checked against the same row computed alone
 on the full-width pCtx with nothing else running.
@@ -23,7 +25,7 @@ import torch
 
 from . import harness as H, inputs, vte
 
-CHUNK, MAX_CHUNKS = 16, 4
+CHUNK, MAX_CHUNKS, STREAMS = 16, 4, 2   # four chunks of 16 rows on two virtual streams
 WIDTHS = (32, 64, 128, 192, 224, 256)
 
 
@@ -69,9 +71,13 @@ class Server:
         gB = H.to_dev(inputs.normal_bf16(0, inputs.T_GEMM_B, (M, M)))
         self.gbuf = (gA, gB, H.dev_empty((M, M)))
         self.gemm = vte.vte_desc_gemm(ctx, gA, gB, self.gbuf[2], M, M, M)
-        self.vs = [vte.vte_vstream_create(ctx, vte.VTE_CLASS_LATENCY) for _ in range(MAX_CHUNKS)]
+        self.vs = [vte.vte_vstream_create(ctx, vte.VTE_CLASS_LATENCY) for _ in range(STREAMS)]
         self.be = vte.vte_vstream_create(ctx, vte.VTE_CLASS_BEST_EFFORT)
         self.root = vte.vte_pool_find(ctx, vte.VTE_PCTX_NODE, 256)
+        # torch work in the serving loop stays off the null stream, which would order itself against
+        # every CU-masked stream: token reads and writes go through a non-blocking stream of their own
+        self.io_stream = torch.cuda.Stream()
+        self.pin_tok = [torch.zeros(CHUNK, dtype=torch.int32).pin_memory() for _ in range(MAX_CHUNKS)]
         self.copy_stream = torch.cuda.Stream()
         self.stage = torch.empty(MAX_CHUNKS * CHUNK * 2048, dtype=torch.int32, device="cuda")
         self.pinned = torch.zeros(2048, dtype=torch.int32).pin_memory()
@@ -87,6 +93,20 @@ class Server:
         vte.vte_device_sync(self.ctx)
         vte.vte_shutdown(self.ctx)
 
+    def read_tokens(self, c):
+        """Chunk c's token buffer -> its pinned host image (the chunk must have no step in flight)."""
+        with torch.cuda.stream(self.io_stream):
+            self.pin_tok[c].copy_(self.chains[c].tok, non_blocking=True)
+        self.io_stream.synchronize()
+        return self.pin_tok[c].numpy()
+
+    def write_tokens(self, c, toks=None):
+        if toks is not None:
+            self.pin_tok[c].numpy()[:] = toks
+        with torch.cuda.stream(self.io_stream):
+            self.chains[c].tok.copy_(self.pin_tok[c], non_blocking=True)
+        self.io_stream.synchronize()
+
     # -- the reference: each token's successor, the row computed alone at full width --------------
     def reference_next(self, toks):
         todo = sorted({int(t) for t in toks} - set(self.next_of))
@@ -98,26 +118,27 @@ class Server:
             part = todo[i:i + CHUNK]
             buf = np.zeros(CHUNK, dtype=np.int32)
             buf[:len(part)] = part
-            ch.tok.copy_(torch.from_numpy(buf))
-            torch.cuda.synchronize()
+            self.write_tokens(0, buf)
             vte.vte_token_wait(self.ctx, ch.submit_step(vs))
-            nxt = ch.tok.cpu().numpy()
+            nxt = self.read_tokens(0).copy()
             for t, n in zip(part, nxt):
                 self.next_of[t] = int(n)
         vte.vte_vstream_pin(vs, -1)
 
     # -- one run of a trace under a policy ---------------------------------------------------------
     def run(self, trace, seconds, mode, tpot_target=0.050, with_gemm=True):
-        """mode: 'solo' (no co-tenant, widest) | 'fixed' (decode pinned to one half, GEMM to the other)
-        | 'tput' (Throughput-Oriented plan) | 'tpot' (TPOT-First)."""
+        """mode: 'solo' (no co-tenant, widest) | 'fixed' (decode streams pinned to the quarters of one half, GEMM to the other half)
+        | 'tput' (Throughput-Oriented plan) | 'tpot' (TPOT-First).  Chunk c runs on stream c % STREAMS."""
         ctx = self.ctx
         vte.vte_device_sync(ctx)
         vte.vte_stats_reset(ctx)
-        leaves = [vte.vte_pool_find(ctx, vte.VTE_PCTX_NODE, 32, i) for i in range(MAX_CHUNKS)]
+        quarters = [vte.vte_pool_find(ctx, vte.VTE_PCTX_NODE, 64, i) for i in range(STREAMS)]
         half1 = vte.vte_pool_find(ctx, vte.VTE_PCTX_NODE, 128, 1)
+        per_stream = MAX_CHUNKS // STREAMS
         for i, vs in enumerate(self.vs):
-            vte.vte_vstream_set_tpot(vs, tpot_target if mode == "tpot" else 0.0, self.chains[i].ops_per_step)
-            vte.vte_vstream_pin(vs, leaves[i] if mode == "fixed" else -1)
+            # a stream's "token" is one chunk step; its chunks alternate, so a request sees per_stream of them per token
+            vte.vte_vstream_set_tpot(vs, tpot_target / per_stream if mode == "tpot" else 0.0, self.chains[i].ops_per_step)
+            vte.vte_vstream_pin(vs, quarters[i] if mode == "fixed" else -1)
         vte.vte_vstream_pin(self.be, half1 if mode == "fixed" else -1)
         policy = {"solo": vte.VTE_POLICY_WIDEST, "fixed": vte.VTE_POLICY_WIDEST, "tput": vte.VTE_POLICY_TPUT_PLAN,
                   "tpot": vte.VTE_POLICY_TPOT_FIRST}[mode]
@@ -156,7 +177,7 @@ class Server:
                     if not vte.vte_token_query(ctx, tail[c]):
                         continue
                     t_done = time.perf_counter() - t0
-                    toks = ch.tok.cpu().numpy()
+                    toks = self.read_tokens(c)
                     for s, ri in enumerate(slots[c]):
                         if ri < 0:
                             continue
@@ -169,21 +190,20 @@ class Server:
                     steps += 1
                 if now >= seconds:
                     continue
-                new = []
+                new = False
+                # fill the lowest chunks first: a chunk admits only while every chunk before it is full
+                lower_full = all(ri >= 0 for k in range(c) for ri in slots[k])
                 for s in range(CHUNK):
-                    # fill the lowest chunks first: a chunk starts only when the ones before it are full
-                    if slots[c][s] < 0 and pending and reqs[pending[0]]["copied"].query():
+                    if lower_full and slots[c][s] < 0 and pending and reqs[pending[0]]["copied"].query():
                         ri = pending.pop(0)
                         slots[c][s] = ri
                         reqs[ri]["t_admit"] = now
-                        new.append((s, reqs[ri]["tok0"]))
+                        self.pin_tok[c].numpy()[s] = reqs[ri]["tok0"]   # the host image holds the step's tokens
+                        new = True
                 if new:
-                    idx = torch.tensor([s for s, _ in new], dtype=torch.long, device="cuda")
-                    val = torch.tensor([t for _, t in new], dtype=torch.int32, device="cuda")
-                    ch.tok.index_copy_(0, idx, val)
-                    torch.cuda.synchronize()
+                    self.write_tokens(c)
                 if any(ri >= 0 for ri in slots[c]):
-                    tail[c] = ch.submit_step(self.vs[c])
+                    tail[c] = ch.submit_step(self.vs[c % STREAMS])
                     busy[c] = True
             time.sleep(0.00005)
         elapsed = time.perf_counter() - t0

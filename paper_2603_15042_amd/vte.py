@@ -35,13 +35,14 @@ class VteError(RuntimeError):
 
 class vte_pool_cfg(C.Structure):
     _fields_ = [(n, C.c_int) for n in ("backend", "total_cus", "leaf_cus", "layout", "with_remainders", "mode",
-                                        "lookahead", "stats_capacity")] + [("device_timing_mask", C.c_uint)]
+                                        "lookahead", "stats_capacity")] + [("device_timing_mask", C.c_uint),
+                                                                           ("dispatch_pipes", C.c_int)]
 
 
 class vte_pctx_info(C.Structure):
     _fields_ = [("id", C.c_int), ("kind", C.c_int), ("width", C.c_int), ("level", C.c_int), ("parent", C.c_int),
                 ("child", C.c_int * 2), ("remainder", C.c_int), ("state", C.c_int), ("gate_open", C.c_int),
-                ("outstanding", C.c_int), ("reserved_for", C.c_int), ("mask", C.c_uint32 * 8)]
+                ("outstanding", C.c_int), ("reserved_for", C.c_int), ("mask", C.c_uint32 * 8), ("pipe", C.c_int)]
 
 
 class vte_desc_view(C.Structure):
@@ -119,7 +120,7 @@ EXPORTS = [
     "vte_pctx_close_gate", "vte_pctx_reserve", "vte_pctx_unreserve", "vte_set_policy", "vte_set_builtin_policy",
     "vte_hint_submit", "vte_profile_measure", "vte_profile_measure_on", "vte_profile_set", "vte_profile_get", "vte_stats", "vte_stats_read",
     "vte_stats_reset", "vte_fake_complete", "vte_fake_set_autocomplete", "vte_fake_fail_next_submits",
-    "vte_fake_log", "vte_dispatcher_quiesce", "vte_now", "vte_vstream_set_tpot", "vte_vstream_tpot_info", "vte_submit_batch",
+    "vte_fake_log", "vte_dispatcher_quiesce", "vte_now", "vte_vstream_set_tpot", "vte_vstream_tpot_info", "vte_submit_batch", "vte_pool_creation_order",
 ]
 
 _lib = None
@@ -193,6 +194,13 @@ def vte_pool_info(ctx, pctx_id):
     info = vte_pctx_info()
     _check(load().vte_pool_info(ctx, int(pctx_id), C.byref(info)))
     return info
+
+
+def vte_pool_creation_order(ctx):
+    arr = (C.c_int * 64)()
+    n = C.c_int()
+    _check(load().vte_pool_creation_order(ctx, arr, 64, C.byref(n)))
+    return [arr[i] for i in range(min(n.value, 64))]
 
 
 def vte_pool_find(ctx, kind, width, index=0):

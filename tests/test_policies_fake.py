@@ -351,3 +351,76 @@ def test_submit_batch_is_a_chain_seen_at_once():
             vte.vte_shutdown(other)
     finally:
         vte.vte_shutdown(c)
+
+
+# ---------- dispatch pipes ---------------------------------------------------------------------------
+@pytest.mark.parametrize("remainders", [vte.VTE_REMAINDERS_NONE, vte.VTE_REMAINDERS_PER_LEVEL, vte.VTE_REMAINDERS_ALL])
+def test_disjoint_pctxs_meant_to_run_together_sit_on_different_pipes(remainders):
+    c = make_ctx(remainders=remainders)
+    try:
+        ps = infos(c)
+        assert all(0 <= p.pipe < 4 for p in ps)
+        nodes = lambda w: [p for p in ps if p.kind == vte.VTE_PCTX_NODE and p.width == w]
+        assert len({p.pipe for p in nodes(128)}) == 2                  # the two halves
+        assert len({p.pipe for p in nodes(64)}) == 4                   # the four quarters
+        for q in nodes(64):                                            # a quarter and the opposite half
+            other = [h for h in nodes(128) if not vte.vte_pool_conflict(c, h.id, q.id)][0]
+            assert q.pipe != other.pipe
+        for p in ps:                                                   # a node and the remainder that complements it
+            if p.kind == vte.VTE_PCTX_NODE and p.remainder >= 0:
+                assert ps[p.remainder].pipe != p.pipe, (p.id, p.remainder)
+        # queues are dealt to pipes in creation order: the k-th created belongs to pipe k % 4
+        order = vte.vte_pool_creation_order(c)
+        assert sorted(i for i in order if i >= 0) == list(range(len(ps)))
+        assert all(i < 0 or ps[i].pipe == k % 4 for k, i in enumerate(order))
+        assert sum(1 for i in order if i < 0) <= 3                     # few placeholder queues
+    finally:
+        vte.vte_shutdown(c)
+
+
+def test_tput_plan_avoids_a_pipe_another_tenant_dispatches_on():
+    c = make_ctx(remainders=vte.VTE_REMAINDERS_NONE)
+    try:
+        ps = infos(c)
+        flat = vte.vte_desc_rmsnorm(c, A, A, A, 8, 1024, 1e-6)
+        set_profile(c, flat, lambda w: 4e-6)                           # flat profile: stays on a leaf
+        leaves = [p for p in ps if p.width == 32]
+        busy = leaves[0]
+        other = vte.vte_vstream_create(c, vte.VTE_CLASS_BEST_EFFORT)
+        vte.vte_vstream_pin(other, busy.id)
+        vte.vte_set_builtin_policy(c, vte.VTE_POLICY_TPUT_PLAN)
+        t0 = vte.vte_submit(other, flat)
+        vte.vte_dispatcher_quiesce(c)
+        vs = vte.vte_vstream_create(c, vte.VTE_CLASS_BEST_EFFORT)
+        t1 = vte.vte_submit(vs, flat)
+        vte.vte_dispatcher_quiesce(c)
+        got = ps[bound(c)[t1]]
+        assert got.width == 32 and got.pipe != busy.pipe
+        finish(c, [t0, t1])
+    finally:
+        vte.vte_shutdown(c)
+
+
+def test_tput_plan_does_not_renew_a_lease_while_an_older_op_has_nowhere_to_go():
+    c = make_ctx(vte.VTE_MODE_PIPELINED)
+    try:
+        d = vte.vte_desc_gemv(c, A, A, A, 1, 4096, 4096, 0)
+        set_profile(c, d, lambda w: 1e-3 * 32 / w)
+        vte.vte_set_builtin_policy(c, vte.VTE_POLICY_TPUT_PLAN)
+        hog, late = vte.vte_vstream_create(c, vte.VTE_CLASS_BEST_EFFORT), vte.vte_vstream_create(c, vte.VTE_CLASS_BEST_EFFORT)
+        t1 = vte.vte_submit(hog, d)
+        vte.vte_dispatcher_quiesce(c)
+        ps = infos(c)
+        assert ps[bound(c)[t1]].width == 256                 # alone: the whole device
+        t_late = vte.vte_submit(late, d)                     # nothing is left for it ...
+        t2 = vte.vte_submit(hog, d)                          # ... and the holder's next op could reuse the lease
+        vte.vte_dispatcher_quiesce(c)
+        assert t_late not in bound(c) and t2 not in bound(c)  # it does not: the older op waits, so the lease drains
+        vte.vte_fake_complete(c, t1)
+        vte.vte_token_wait(c, t1)
+        vte.vte_dispatcher_quiesce(c)
+        b = bound(c)
+        assert ps[b[t_late]].width + ps[b[t2]].width == 256 and not vte.vte_pool_conflict(c, b[t_late], b[t2])   # planned together
+        finish(c, [t_late, t2])
+    finally:
+        vte.vte_shutdown(c)
