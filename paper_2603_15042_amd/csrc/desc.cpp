@@ -11,6 +11,8 @@
 
 extern "C" {
 const void* vte_norm_entry(int threads, int layer);
+const void* vte_norm_rows_entry(int chunks, int layer);
+int vte_norm_rows_per_block(void);
 const void* vte_gemv_entry_b1(int, int, int, int, int, int);
 const void* vte_gemv_entry_b2(int, int, int, int, int, int);
 const void* vte_gemv_entry_b4(int, int, int, int, int, int);
@@ -106,10 +108,19 @@ int build_norm(vte_ctx* ctx, int kernel, bool layer, const void* x, const void* 
   a.tok = tok; a.h_out = static_cast<uint16_t*>(h_out); a.V = V;
   a.cand = cand; a.nblocks = nblocks; a.cand_bt = cand_bt; a.tok_out = tok_out;
   if (h_out && !aligned16(h_out)) { set_error("norm: pointers must be 16-byte aligned"); return VTE_EINVAL; }
+  // many short rows and nothing fused in: one wave per row (structure from rows and cols alone)
+  const bool by_wave = kernel != VTE_K_RMSNORM_RESHAPED && !tok && !cand && !h_out && rows >= 512 && cols <= 4096;
   const int shape_v[3] = {rows, cols, nblocks};
   const uint64_t shape = nblocks ? fnv1a(shape_v, sizeof shape_v) : ((static_cast<uint64_t>(rows) << 32) | static_cast<uint32_t>(cols));
   const uint64_t bytes = static_cast<uint64_t>(rows) * cols * 4 + static_cast<uint64_t>(cols) * (layer ? 4 : 2) +
                          (cand ? 8ull * nblocks * rows + 4ull * rows : 0);
+  if (by_wave) {
+    const int chunks = cols <= 1024 ? 2 : (cols <= 2048 ? 4 : 8);
+    const int per_block = vte_norm_rows_per_block();
+    return finish_desc(ctx, kernel, vte_norm_rows_entry(chunks, layer ? 1 : 0), a,
+                       static_cast<uint32_t>((rows + per_block - 1) / per_block), 1, 256, 0, shape, bytes,
+                       static_cast<uint64_t>(rows) * cols * 4, out);
+  }
   return finish_desc(ctx, kernel, vte_norm_entry(threads, layer ? 1 : 0), a, static_cast<uint32_t>(rows), 1,
                      static_cast<uint32_t>(threads), 0, shape, bytes, static_cast<uint64_t>(rows) * cols * 4, out);
 }

@@ -61,7 +61,8 @@ def test_pool_is_precreated_with_every_width(ctx):
 
 
 # ---------- RMSNorm / LayerNorm ---------------------------------------------------------------
-@pytest.mark.parametrize("rows,cols", [(8, 1024), (1, 8), (5, 1000), (3, 4096), (2, 16384), (300, 2048)])
+@pytest.mark.parametrize("rows,cols", [(8, 1024), (1, 8), (5, 1000), (3, 4096), (2, 16384), (300, 2048),
+                                       (1000, 4096), (515, 520), (777, 1536), (512, 8), (600, 4104)])   # from 512 rows: one wave per row
 def test_rmsnorm_parity_and_width_invariance(H, ctx, rows, cols):
     x, g = inputs.rmsnorm_case(seed=0, rows=rows, cols=cols)
     dx, dg, dy = H.to_dev(x), H.to_dev(g), H.dev_empty((rows, cols))
@@ -88,7 +89,7 @@ def test_rmsnorm_closed_forms_on_gpu(H, ctx):
     vte.vte_desc_destroy(d)
 
 
-@pytest.mark.parametrize("rows,cols", [(8, 1024), (4, 96), (2, 4096), (3, 8192)])
+@pytest.mark.parametrize("rows,cols", [(8, 1024), (4, 96), (2, 4096), (3, 8192), (1001, 4096), (530, 1000)])
 def test_layernorm_parity_and_width_invariance(H, ctx, rows, cols):
     x, g, b = inputs.layernorm_case(seed=1, rows=rows, cols=cols)
     dx, dg, db, dy = H.to_dev(x), H.to_dev(g), H.to_dev(b), H.dev_empty((rows, cols))
