@@ -183,6 +183,22 @@ def main():
                 vte.vte_desc_destroy(dd)
         del Ws
         torch.cuda.empty_cache()
+        M = 8192                                       # the co-tenant: bf16 MFMA GEMM 8192^3, N(0,1) inputs
+        gA = H.to_dev(inputs.normal_bf16(0, inputs.T_GEMM_A, (M, M)))
+        gB = H.to_dev(inputs.normal_bf16(0, inputs.T_GEMM_B, (M, M)))
+        gC = H.dev_empty((M, M))
+        d = vte.vte_desc_gemm(ctx, gA, gB, gC, M, M, M)
+        r = {}
+        for width in (256, 128, 64, 32):
+            t = vte.vte_profile_measure_on(ctx, d, H.pctx_of_width(ctx, width), 1, 4 if width >= 128 else 2)
+            r[str(width)] = {"TFLOP/s": round(2.0 * M ** 3 / t / 1e12, 1), "pct_mfma_peak": round(2.0 * M ** 3 / t / 1e12 / 25.0, 2),
+                             "ms": round(t * 1e3, 3)}
+        ops["gemm_8192_bf16"] = r
+        ops["gemm_8192_bf16"]["roofline"] = {"bound": "mfma", "achieved": r["256"]["TFLOP/s"], "peak": 2500.0, "unit": "TFLOP/s",
+                                             "frac": round(r["256"]["TFLOP/s"] / 2500.0, 4)}
+        vte.vte_desc_destroy(d)
+        del gA, gB, gC
+        torch.cuda.empty_cache()
         out["per_operator"] = ops
 
     # ---- other batch sizes of the same chain, full width (outside the timed region) -------------

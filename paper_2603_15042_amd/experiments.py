@@ -313,6 +313,22 @@ def cotenancy(seconds, gap_ms, steps_per_burst=128, lead_ms=3.0):
     return res
 
 
+def gemm_widths(reps, M=8192):
+    """The co-tenant GEMM alone on one pCtx of every width: device time per launch (the profiling target)."""
+    torch.zeros(1, device="cuda")
+    ctx = H.make_ctx()
+    gA = H.to_dev(inputs.normal_bf16(0, inputs.T_GEMM_A, (M, M)))
+    gB = H.to_dev(inputs.normal_bf16(0, inputs.T_GEMM_B, (M, M)))
+    gC = H.dev_empty((M, M))
+    d = vte.vte_desc_gemm(ctx, gA, gB, gC, M, M, M)
+    out = {"M": M, "reps": reps, "widths": {}}
+    for width in (256, 224, 192, 128, 64, 32):
+        t = vte.vte_profile_measure_on(ctx, d, H.pctx_of_width(ctx, width), 1, reps)
+        out["widths"][str(width)] = {"ms": t * 1e3, "TFLOP/s": 2.0 * M ** 3 / t / 1e12, "pct_of_2.5_PFLOP/s": 2.0 * M ** 3 / t / 2.5e13}
+    vte.vte_shutdown(ctx)
+    return out
+
+
 def main(argv=None):
     ap = argparse.ArgumentParser()
     sub = ap.add_subparsers(dest="cmd", required=True)
@@ -322,9 +338,13 @@ def main(argv=None):
     c = sub.add_parser("cotenancy")
     c.add_argument("--seconds", type=float, default=3.0)
     c.add_argument("--gap-ms", type=float, default=60.0)
+    g = sub.add_parser("gemm")
+    g.add_argument("--reps", type=int, default=5)
     a = ap.parse_args(argv)
     if a.cmd == "determinism":
         out = determinism(a.trials, a.replays)
+    elif a.cmd == "gemm":
+        out = gemm_widths(a.reps)
     else:
         out = cotenancy(a.seconds, a.gap_ms)
     print(json.dumps(out))

@@ -381,7 +381,7 @@ def test_gather(H, ctx):
 
 
 # ---------- MFMA GEMM ---------------------------------------------------------------------------------
-@pytest.mark.parametrize("M,N,K", [(256, 256, 64), (512, 256, 192), (512, 512, 512), (1024, 768, 1024)])
+@pytest.mark.parametrize("M,N,K", [(256, 256, 64), (256, 512, 128), (512, 256, 192), (512, 512, 512), (1024, 768, 1024), (256, 256, 4160)])
 def test_gemm_parity_and_width_invariance(H, ctx, M, N, K):
     A = inputs.normal_bf16(0, inputs.T_GEMM_A, (M, K))
     Bm = inputs.normal_bf16(0, inputs.T_GEMM_B, (N, K))
