@@ -329,6 +329,41 @@ def gemm_widths(reps, M=8192):
     return out
 
 
+def operators_by_width(reps):
+    """The metric's bandwidth-bound operators alone on one pCtx of every width, `reps` launches each, in a fixed
+    order (width-major: 256, 128, 64, 32; per width RMSNorm 32768x4096, GEMV 4096x4096 batch 8 over 8 weight
+    buffers in rotation, LM head 128256x4096 batch 8): the target of the per-width kernel trace."""
+    torch.zeros(1, device="cuda")
+    ctx = H.make_ctx()
+    rows, cols, N, V, B = 32768, 4096, 4096, 128256, 8
+    x = torch.randint(-3000, 3000, (rows, cols), dtype=torch.int16, device="cuda")
+    y = torch.empty_like(x)
+    g = H.to_dev(inputs.uniform_bf16(0, inputs.T_GAMMA, (cols,), 0.5, 1.5))
+    d_norm = vte.vte_desc_rmsnorm(ctx, x, g, y, rows, cols, 1e-6)
+    Ws = [torch.randint(-3000, 3000, (N, cols), dtype=torch.int16, device="cuda") for _ in range(8)]
+    X = torch.randint(-3000, 3000, (B, cols), dtype=torch.int16, device="cuda")
+    Y = torch.empty((B, N), dtype=torch.int16, device="cuda")
+    d_gemv = [vte.vte_desc_gemv(ctx, W_, X, Y, B, N, cols) for W_ in Ws]
+    Wlm = torch.randint(-3000, 3000, (V, cols), dtype=torch.int16, device="cuda")
+    tok = torch.zeros(B, dtype=torch.int32, device="cuda")
+    ws = H.dev_zeros_bytes(vte.vte_lmhead_workspace_bytes(B, V, cols))
+    d_lm = vte.vte_desc_lmhead_argmax(ctx, Wlm, X, tok, None, ws, B, V, cols)
+    out = {"reps": reps, "order": ["rmsnorm_32768x4096", "gemv_4096x4096_B8", "lmhead_128256x4096_B8"], "widths": {}}
+    for width in (256, 128, 64, 32):
+        p = H.pctx_of_width(ctx, width)
+        r = {}
+        t = vte.vte_profile_measure_on(ctx, d_norm, p, 0, reps)
+        r["rmsnorm_32768x4096"] = {"us": t * 1e6, "GB/s": vte.vte_desc_info(d_norm).bytes / t / 1e9}
+        ts = [vte.vte_profile_measure_on(ctx, d_gemv[i % 8], p, 0, 1) for i in range(reps)]
+        t = float(np.median(ts))
+        r["gemv_4096x4096_B8"] = {"us": t * 1e6, "GB/s": vte.vte_desc_info(d_gemv[0]).bytes / t / 1e9}
+        t = vte.vte_profile_measure_on(ctx, d_lm, p, 0, reps)
+        r["lmhead_128256x4096_B8"] = {"us": t * 1e6, "GB/s": vte.vte_desc_info(d_lm).bytes / t / 1e9}
+        out["widths"][str(width)] = r
+    vte.vte_shutdown(ctx)
+    return out
+
+
 def main(argv=None):
     ap = argparse.ArgumentParser()
     sub = ap.add_subparsers(dest="cmd", required=True)
@@ -340,11 +375,15 @@ def main(argv=None):
     c.add_argument("--gap-ms", type=float, default=60.0)
     g = sub.add_parser("gemm")
     g.add_argument("--reps", type=int, default=5)
+    o = sub.add_parser("operators")
+    o.add_argument("--reps", type=int, default=8)
     a = ap.parse_args(argv)
     if a.cmd == "determinism":
         out = determinism(a.trials, a.replays)
     elif a.cmd == "gemm":
         out = gemm_widths(a.reps)
+    elif a.cmd == "operators":
+        out = operators_by_width(a.reps)
     else:
         out = cotenancy(a.seconds, a.gap_ms)
     print(json.dumps(out))
