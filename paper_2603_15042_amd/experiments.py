@@ -364,6 +364,50 @@ def operators_by_width(reps):
     return out
 
 
+def overhead(launches):
+    """Dispatch overhead in kind (Sec. 7.5): the paper's probe is a BF16 GEMM of shape (512, 8192, 28672).
+    Native = the same descriptor launched back to back on the 256-CU stream by the backend itself (no
+    dispatcher); STRICT / PIPELINED = the same launches through a virtual stream and the dispatcher;
+    on-demand = what creating the pool's CU-masked streams costs (they are pre-created once)."""
+    out = {"launches": launches}
+    M, N, K = 512, 8192, 28672
+    res = {}
+    for mode, name in ((vte.VTE_MODE_STRICT, "strict"), (vte.VTE_MODE_PIPELINED, "pipelined")):
+        t0 = time.perf_counter()
+        ctx = H.make_ctx(mode, lookahead=32)
+        t_init = time.perf_counter() - t0
+        gA = H.to_dev(inputs.normal_bf16(0, inputs.T_GEMM_A, (M, K)))
+        gB = H.to_dev(inputs.normal_bf16(0, inputs.T_GEMM_B, (N, K)))
+        gC = H.dev_empty((M, N))
+        d = vte.vte_desc_gemm(ctx, gA, gB, gC, M, N, K)
+        root = vte.vte_pool_find(ctx, vte.VTE_PCTX_NODE, 256)
+        native = vte.vte_profile_measure_on(ctx, d, root, 10, launches)
+        vs = vte.vte_vstream_create(ctx, vte.VTE_CLASS_LATENCY)
+        vte.vte_set_builtin_policy(ctx, vte.VTE_POLICY_WIDEST)
+        arr = vte.desc_array([d] * launches)
+        vte.vte_token_wait(ctx, vte.vte_submit_batch(vs, vte.desc_array([d] * 10)))
+        t = time.perf_counter()
+        vte.vte_token_wait(ctx, vte.vte_submit_batch(vs, arr))
+        through = (time.perf_counter() - t) / launches
+        # a short kernel shows the per-launch cost itself
+        x = H.dev_empty((8, 4096)); g = H.dev_empty((4096,)); y = H.dev_empty((8, 4096))
+        dn = vte.vte_desc_rmsnorm(ctx, x, g, y, 8, 4096, 1e-6)
+        native_s = vte.vte_profile_measure_on(ctx, dn, root, 10, launches)
+        arr_s = vte.desc_array([dn] * launches)
+        vte.vte_token_wait(ctx, vte.vte_submit_batch(vs, vte.desc_array([dn] * 10)))
+        t = time.perf_counter()
+        vte.vte_token_wait(ctx, vte.vte_submit_batch(vs, arr_s))
+        through_s = (time.perf_counter() - t) / launches
+        res[name] = {"gemm_native_us": native * 1e6, "gemm_through_runtime_us": through * 1e6,
+                     "gemm_overhead_pct": 100 * (through / native - 1),
+                     "norm_native_us": native_s * 1e6, "norm_through_runtime_us": through_s * 1e6,
+                     "pool_creation_ms": t_init * 1e3, "pool_streams": vte.vte_pool_count(ctx),
+                     "per_stream_creation_ms": t_init * 1e3 / vte.vte_pool_count(ctx)}
+        vte.vte_shutdown(ctx)
+    out.update(res)
+    return out
+
+
 def main(argv=None):
     ap = argparse.ArgumentParser()
     sub = ap.add_subparsers(dest="cmd", required=True)
@@ -375,6 +419,8 @@ def main(argv=None):
     c.add_argument("--gap-ms", type=float, default=60.0)
     g = sub.add_parser("gemm")
     g.add_argument("--reps", type=int, default=5)
+    ov = sub.add_parser("overhead")
+    ov.add_argument("--launches", type=int, default=200)
     o = sub.add_parser("operators")
     o.add_argument("--reps", type=int, default=8)
     a = ap.parse_args(argv)
@@ -384,6 +430,8 @@ def main(argv=None):
         out = gemm_widths(a.reps)
     elif a.cmd == "operators":
         out = operators_by_width(a.reps)
+    elif a.cmd == "overhead":
+        out = overhead(a.launches)
     else:
         out = cotenancy(a.seconds, a.gap_ms)
     print(json.dumps(out))
