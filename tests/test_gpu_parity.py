@@ -73,6 +73,28 @@ def test_rmsnorm_parity_and_width_invariance(H, ctx, rows, cols):
     vte.vte_desc_destroy(d)
 
 
+@pytest.mark.parametrize("rows,cols", [(8, 1024), (5, 1000), (3, 4096), (2, 16384), (300, 2048), (1000, 4096), (515, 520), (777, 1536)])
+def test_rmsnorm_bits_equal_the_documented_tree(H, ctx, rows, cols):
+    """The kernel's output is the bits of the tree its header documents, emulated in float32 on the CPU."""
+    import tree_emulator
+    x, g = inputs.rmsnorm_case(seed=5, rows=rows, cols=cols)
+    dx, dg, dy = H.to_dev(x), H.to_dev(g), H.dev_empty((rows, cols))
+    d = vte.vte_desc_rmsnorm(ctx, dx, dg, dy, rows, cols, 1e-6)
+    H.run_on(ctx, d, H.pctx_of_width(ctx, 64))
+    assert H.mismatched_bits(H.to_bits(dy), tree_emulator.rmsnorm_bits(x, g, 1e-6)) == (0, 0)
+    vte.vte_desc_destroy(d)
+    if rows < 512:
+        # a regrouped sum (the reshaped baseline's thread count) is another tree: the emulator follows it too
+        for cus in (32, 256):
+            t = 64 * (cus // 32)
+            if cols > 64 * t:
+                continue
+            d = vte.vte_desc_rmsnorm_reshaped(ctx, dx, dg, dy, rows, cols, 1e-6, cus)
+            H.run_on(ctx, d, H.pctx_of_width(ctx, 256))
+            assert H.mismatched_bits(H.to_bits(dy), tree_emulator.rmsnorm_bits(x, g, 1e-6, threads=t)) == (0, 0)
+            vte.vte_desc_destroy(d)
+
+
 def test_rmsnorm_closed_forms_on_gpu(H, ctx):
     n = 1024
     sign = np.where(np.arange(n) % 3 == 0, -1.0, 1.0).astype(np.float32)
