@@ -94,11 +94,13 @@ __global__ __launch_bounds__(MAXW * 64) void gemv_mfma_kernel(const GemvArgs a) 
   auto load_block = [&](u32x4(&dst)[4], int rd, int ch, int g, int bi) {
     const int kb = k_begin + ch * KC + bi * 128;
     const int soff = ((tile_start(rd, g) - tile_start(0, 0)) * a.K + k_begin + ch * KC) * 2;
+    // K tail: a piece past k_end is not fetched at all (behind the last row of W it would lie
+    // outside the allocation).  The range check of a buffer load looks at the per-lane offset
+    // only, so such a lane gets an offset beyond the resource and reads zeros.
+    const uint32_t vo = (ALLFULL || kb + lp * 8 < k_end) ? voff : 0x80000000u;
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs_w[t], voff, soff + bi * 256, 2);  // streaming
-      dst[t] = (ALLFULL || kb + lp * 8 < k_end) ? v : zero;
-    }
+    for (int t = 0; t < 4; ++t)
+      dst[t] = __builtin_amdgcn_raw_buffer_load_b128(rs_w[t], vo, soff + bi * 256, 2);  // streaming
   };
   auto load_x = [&](int ch) {
     const int soff = (k_begin + ch * KC) * 2;
@@ -106,8 +108,8 @@ __global__ __launch_bounds__(MAXW * 64) void gemv_mfma_kernel(const GemvArgs a) 
     for (int bi = 0; bi < NBK; ++bi)
 #pragma unroll
       for (int s = 0; s < 4; ++s) {
-        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs_x, voff_x, soff + (bi * 128 + s * 32) * 2, 0);
-        xs[bi][s] = (ALLFULL || k_begin + ch * KC + bi * 128 + s * 32 + q * 8 < k_end) ? v : zero;
+        const uint32_t vo = (ALLFULL || k_begin + ch * KC + bi * 128 + s * 32 + q * 8 < k_end) ? voff_x : 0x80000000u;
+        xs[bi][s] = __builtin_amdgcn_raw_buffer_load_b128(rs_x, vo, soff + (bi * 128 + s * 32) * 2, 0);
       }
   };
 

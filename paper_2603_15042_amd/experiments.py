@@ -59,6 +59,7 @@ def determinism(trials, replays, seed0=0):
     widths = (32, 64, 128, 256)
 
     # ---- operator 1: the reduction (RMSNorm 8 x 1024) -------------------------------------------
+    print("determinism: RMSNorm 8x1024, %d trials" % trials, file=sys.stderr, flush=True)
     rows, cols = 8, 1024
     dx, dg, dy = H.dev_empty((rows, cols)), H.dev_empty((cols,)), H.dev_empty((rows, cols))
     fixed = vte.vte_desc_rmsnorm(ctx, dx, dg, dy, rows, cols, 1e-6)
@@ -97,6 +98,7 @@ def determinism(trials, replays, seed0=0):
     W0 = inputs.normal_bf16(seed0, inputs.T_W, (N, K), 0.0, K ** -0.5)
     dW = H.to_dev(W0)
     for B in (1, 4, 8):
+        print("determinism: GEMV 4096x4096 batch %d, %d trials" % (B, trials), file=sys.stderr, flush=True)
         dX, dY = H.dev_empty((B, K)), H.dev_empty((B, N))
         tok = torch.zeros(B, dtype=torch.int32, device="cuda")
         lg = torch.zeros((B, N), dtype=torch.float32, device="cuda")
@@ -142,6 +144,7 @@ def determinism(trials, replays, seed0=0):
         out["gemv_4096x4096_B%d" % B] = r
 
     # ---- decoding level: one state replayed (reduced vocabulary keeps it short) ------------------------
+    print("determinism: decode state replay, %d replays" % replays, file=sys.stderr, flush=True)
     shp = inputs.DecodeShapes(D=4096, Nqkv=6144, F=14336, V=32064)
     w = inputs.decode_weights(seed0, shp)
     wd = H.upload_weights(w)
@@ -160,6 +163,8 @@ def determinism(trials, replays, seed0=0):
     s1 = chains[1].snapshot()
     r["split1_equals_fixed"] = bool(np.array_equal(s1["logits"].view(np.uint32), s0["logits"].view(np.uint32)))
     for t in range(replays):
+        if t % 20 == 0:
+            print("determinism: replay %d" % t, file=sys.stderr, flush=True)
         ids = [_rand_pctx(rng, ctx) for _ in base.order]
         base.set_tokens(tok0)
         base.run_step_on(ids)

@@ -256,6 +256,25 @@ def test_gemv_splitk_reshaping_drifts_and_fixed_does_not(H, ctx, B):
     vte.vte_desc_destroy(fixed)
 
 
+def test_k_tail_pieces_are_not_fetched_behind_the_last_row(H, ctx):
+    """Down-projection shape split 8 ways: K / S = 1792 is no multiple of the 512-element chunk of the
+    matrix-core kernel, and the weight tensor (56 x 2 MiB exactly) ends where its allocation ends.  The
+    pieces of the last chunk that lie past the end of a split must not be loaded: behind the last row
+    they are outside the tensor."""
+    B, N, K, S = 8, 4096, 14336, 8
+    W = inputs.normal_bf16(6, inputs.T_WD, (N, K), 0.0, K ** -0.5)
+    X = inputs.normal_bf16(6, inputs.T_XB, (B, K))
+    torch.cuda.empty_cache()
+    dW, dX, dY = H.to_dev(W), H.to_dev(X), H.dev_empty((B, N))
+    ws = H.dev_zeros_bytes(vte.vte_splitk_workspace_bytes(B, N, S))
+    d = vte.vte_desc_gemv_splitk(ctx, dW, dX, dY, ws, B, N, K, 0, S)
+    H.run_on(ctx, d, H.pctx_of_width(ctx, 256))
+    rows = np.array([0, 1, 2047, 4094, 4095])
+    ref = oracle.gemv(W[rows], X)
+    bf16_close(H.to_bits(dY)[:, rows], ref, "split-K with a K tail")
+    vte.vte_desc_destroy(d)
+
+
 @pytest.mark.parametrize("B,F,K", [(2, 50, 256), (8, 1000, 1024), (4, 14336, 4096)])
 def test_gate_up_silu_epilogue(H, ctx, B, F, K):
     W = inputs.normal_bf16(4, inputs.T_WGU, (2 * F, K), 0.0, 2.0 * K ** -0.5)
