@@ -193,7 +193,8 @@ int vte_desc_layernorm(vte_ctx* ctx, const void* x, const void* gamma, const voi
 
 enum { VTE_EPI_NONE = 0, VTE_EPI_SILU_MUL = 1 };
 /* Y[b,n] = bf16( sum_k W[n,k] X[b,k] ).  W: device [N,K] bf16 (each output's K
- * contiguous); X: device [B,K] bf16; Y: device [B,N] bf16.  1 <= B <= 16,
+ * contiguous); X: device [B,K] bf16; Y: device [B,N] bf16.  1 <= B <= 32
+ * (from 17 up N must hold at least one tile of 16 outputs, 8 with SILU_MUL),
  * K % 8 == 0, K <= 16384.  fp32 accumulation in a tree that depends on K only:
  * a K-tile of 256 is 32 lanes x 8 contiguous elements; a lane adds the products
  * of its slice in ascending order, a fixed butterfly adds the 64 lanes of a

@@ -19,6 +19,7 @@ const void* vte_gemv_entry_b4(int, int, int, int, int, int);
 const void* vte_gemv_entry_b8(int, int, int, int, int, int);
 const void* vte_gemv_entry_b16(int, int, int, int, int, int);
 const void* vte_gemv_entry_mfma(int, int, int, int, int, int, int);
+const void* vte_gemv_entry_mfma32(int, int, int, int, int, int, int);
 const void* vte_gather_entry();
 const void* vte_argmax_finish_entry();
 const void* vte_gemm_entry();
@@ -129,8 +130,9 @@ const void* gemv_entry(const vte_gemv_plan& p, int epi, int k_per_split) {
   if (p.kind == VTE_GEMV_MFMA) {
     if (p.ksteps < 1) return nullptr;
     const int kc = 128 * p.ksteps;
-    return vte_gemv_entry_mfma(p.ksteps, p.rows / 16, p.prefetch, p.max_waves, k_per_split % kc == 0 ? 1 : 0,
-                               (k_per_split + kc - 1) / kc <= p.max_waves ? 1 : 0, epi);
+    return (p.batch_tile == 32 ? vte_gemv_entry_mfma32 : vte_gemv_entry_mfma)(
+        p.ksteps, p.rows / 16, p.prefetch, p.max_waves, k_per_split % kc == 0 ? 1 : 0,
+        (k_per_split + kc - 1) / kc <= p.max_waves ? 1 : 0, epi);
   }
   switch (p.batch_tile) {
     case 1: return vte_gemv_entry_b1(1, p.rows, p.ksteps, p.prefetch, p.max_waves, epi);
@@ -159,10 +161,24 @@ int plan_waves(const vte_gemv_plan& p, int k_per_split) {
 // outputs = logical outputs per batch row (N, or N/2 with the SiLU epilogue);
 // kps = K / S.
 int plan_gemv(int B, int outputs, int kps, int epi, vte_gemv_plan* p) {
-  if (B < 1 || B > 16 || outputs < 1 || kps < 8) return VTE_EINVAL;
+  if (B < 1 || B > 32 || outputs < 1 || kps < 8) return VTE_EINVAL;
   const bool silu = epi == VTE_EPI_SILU_MUL;
   const int tile_out = silu ? 8 : 16;
   const int tiles = (outputs + tile_out - 1) / tile_out;
+  if (B > 16) {
+    // Batch 17 to 32: two column tiles per weight tile, four waves (a wave holds X for 32 rows).
+    // Fewer than one full tile of outputs is not offered at this batch.
+    if (outputs < tile_out) return VTE_EINVAL;
+    // Found by timing the built combinations on the Llama-8B shapes at batch 24 and 32: eight waves
+    // (X of a 4096-wide row loaded once per workgroup) and rounds for the wide outputs.
+    int g = 1, nb = 2, rounds = 1, mw = 8;
+    if (tiles >= 4096) { g = 2; rounds = 8; }
+    else if (tiles >= 1024) { g = 2; rounds = 4; }
+    else if (tiles > 256) { g = 2; mw = 4; }
+    p->batch_tile = 32; p->rows = 16 * g; p->ksteps = 4; p->prefetch = nb; p->max_waves = mw; p->groups = rounds;
+    p->kind = VTE_GEMV_MFMA;
+    return VTE_OK;
+  }
   if (outputs >= tile_out && (B >= 5 || (B >= 3 && silu && tiles >= 1024))) {
     // Batch 5 and up (and the wide SiLU projection from batch 3): matrix-core tiles; the
     // dot-product kernels are ALU-bound there.  Found by timing every built combination
@@ -224,7 +240,7 @@ int build_gemv(vte_ctx* ctx, const GemvBuild& g, vte_desc** out) {
   const bool lm = (g.epi_kernel == 2);
   if (!lm && !g.Y) { set_error("gemv: null output"); return VTE_EINVAL; }
   if (lm && (!g.tok || !g.ws)) { set_error("lmhead: tok and workspace are required"); return VTE_EINVAL; }
-  if (g.B < 1 || g.B > 16 || g.N < 1 || g.K < 8 || g.K % 8 != 0) { set_error("gemv: need 1 <= B <= 16, N >= 1, K % 8 == 0"); return VTE_EINVAL; }
+  if (g.B < 1 || g.B > 32 || g.N < 1 || g.K < 8 || g.K % 8 != 0) { set_error("gemv: need 1 <= B <= 32, N >= 1, K % 8 == 0"); return VTE_EINVAL; }
   if (g.S < 1 || g.S > 64 || g.K % (g.S * 8) != 0) { set_error("gemv: K must split into S chunks of a multiple of 8"); return VTE_EINVAL; }
   if (g.S > 1 && (!g.partials || !g.ws)) { set_error("split-K: partials and workspace are required"); return VTE_EINVAL; }
   if (g.epilogue == VTE_EPI_SILU_MUL && (g.N % 2 != 0)) { set_error("gemv: SiLU-mul needs an even N"); return VTE_EINVAL; }
@@ -239,7 +255,9 @@ int build_gemv(vte_ctx* ctx, const GemvBuild& g, vte_desc** out) {
   const bool mfma = p.kind == VTE_GEMV_MFMA;
   if (p.kind != VTE_GEMV_DOT2 && !mfma) { set_error("gemv plan: unknown kind"); return VTE_EINVAL; }
   if (mfma && n_out < (g.epi_kernel == 1 ? 8 : 16)) { set_error("gemv plan: the MFMA kind needs at least one full tile of outputs (16, or 8 with SiLU-mul)"); return VTE_EINVAL; }
-  if (mfma && (p.batch_tile != 16 || p.rows < 16 || p.rows % 16 != 0)) { set_error("gemv plan: the MFMA kind has batch_tile 16 and rows a multiple of 16"); return VTE_EINVAL; }
+  if (mfma && ((p.batch_tile != 16 && p.batch_tile != 32) || p.rows < 16 || p.rows % 16 != 0)) { set_error("gemv plan: the MFMA kind has batch_tile 16 or 32 and rows a multiple of 16"); return VTE_EINVAL; }
+  if (mfma && g.B > p.batch_tile) { set_error("gemv plan: the MFMA kind takes the whole batch in one tile (B <= batch_tile)"); return VTE_EINVAL; }
+  if (!mfma && g.B > 16) { set_error("gemv plan: batch 17 to 32 needs the MFMA kind with batch_tile 32"); return VTE_EINVAL; }
   const int zchunks = (g.B + p.batch_tile - 1) / (p.batch_tile > 0 ? p.batch_tile : 1);
   if (p.batch_tile < 1 || p.groups < 1 || p.rows < 1 || p.ksteps < 1 || waves < 1 || waves > p.max_waves) {
     set_error("gemv plan: groups >= 1 and ceil(K/S/512/ksteps) <= max_waves are required"); return VTE_EINVAL;
@@ -322,7 +340,7 @@ int vte_gemv_default_plan(int B, int N, int K, int epilogue, int S, vte_gemv_pla
   const int n_out = (epilogue == VTE_EPI_SILU_MUL) ? N / 2 : N;
   if (S < 1 || K % S != 0) { set_error("gemv plan: S must divide K"); return VTE_EINVAL; }
   int rc = plan_gemv(B, n_out, K / S, epilogue, plan);
-  if (rc != VTE_OK) set_error("gemv plan: need 1 <= B <= 16, N >= 1, 8 <= K / S <= 16384");
+  if (rc != VTE_OK) set_error("gemv plan: need 1 <= B <= 32 (from 17: at least one full tile of outputs), N >= 1, 8 <= K / S <= 16384");
   return rc;
 }
 
@@ -353,8 +371,8 @@ int vte_desc_gemv_planned(vte_ctx* ctx, const void* W, const void* X, void* Y, i
 static size_t splitk_ticket_bytes(int N) { return ((static_cast<size_t>(N) + 2) * 4 + 255) & ~static_cast<size_t>(255); }
 
 int vte_splitk_workspace_bytes(int B, int N, int S, size_t* bytes) {
-  if (!bytes || B < 1 || B > 16 || N < 1 || S < 1) { set_error("splitk workspace: bad argument"); return VTE_EINVAL; }
-  *bytes = splitk_ticket_bytes(N) + static_cast<size_t>(S) * 16 * N * 4;  // partials [S][batch tile <= 16][N]
+  if (!bytes || B < 1 || B > 32 || N < 1 || S < 1) { set_error("splitk workspace: bad argument"); return VTE_EINVAL; }
+  *bytes = splitk_ticket_bytes(N) + static_cast<size_t>(S) * (B > 16 ? 32 : 16) * N * 4;  // partials [S][batch tile][N]
   return VTE_OK;
 }
 
@@ -371,9 +389,9 @@ int vte_lmhead_workspace_bytes(int B, int V, int K, size_t* bytes) {
   if (!bytes) { set_error("null bytes"); return VTE_EINVAL; }
   // sized for the finest decomposition there is: one workgroup per output row, batch tile 16
   (void)K;
-  if (B < 1 || B > 16 || V < 1) { set_error("lmhead workspace: bad argument"); return VTE_EINVAL; }
+  if (B < 1 || B > 32 || V < 1) { set_error("lmhead workspace: bad argument"); return VTE_EINVAL; }
   const size_t blocks = static_cast<size_t>(V) + 1;
-  *bytes = 4 * (1 + blocks + blocks * 16 * 2) + 256;
+  *bytes = 4 * (1 + blocks + blocks * (B > 16 ? 32 : 16) * 2) + 256;
   return VTE_OK;
 }
 

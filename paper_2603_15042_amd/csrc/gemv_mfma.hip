@@ -1,303 +1,12 @@
-// Skinny-batch GEMV on the matrix cores: Y[b, n] = sum_k W[n, k] X[b, k] for up to
-// 16 batch rows, 16 weight rows per v_mfma_f32_16x16x32_bf16 tile
-// (operator family: Sec. 1 "GEMV", Sec. 2.3; LM-head logits and greedy token:
-// Sec. 7.1 / 7.2 of the paper).
-//
-// From batch 8 up the dot-product kernels are bound by vector-ALU issue, not by
-// HBM; one MFMA consumes a full 1 KB wave load of weights in a few cycles, so the
-// same stream becomes memory-bound again.
-//
-// Work decomposition (a function of the shape and the plan, never of the CU count):
-//   * K is cut into chunks of KC = 128 NBK elements; wave w of a workgroup owns
-//     chunks w, w + nw, ... and keeps the chunk of X in registers (as MFMA B
-//     operand: lane (c = l % 16, q = l / 16) holds 8 consecutive K elements of
-//     batch row c per MFMA step, the quarters q taking 8 of the step's 32 each);
-//   * the workgroup walks `groups` rounds of G row tiles of 16 weight rows; a wave
-//     streams its K range of every tile in blocks of 16 rows x 128 K (4 KB).  With
-//     one chunk per wave X is loaded once per workgroup, so rounds are what keeps
-//     the X re-reads (L2 -> CU traffic that competes with the weight stream) small;
-//   * a block is fetched with four coalesced wave loads (4 rows x 256 B each; the
-//     MFMA operand layout itself would make every load touch 16 cache lines,
-//     which the texture addresser cannot sustain), transposed through a 4 KB
-//     wave-private LDS area (16-byte pieces XOR-swizzled by row, conflict-free
-//     both ways) and consumed by four MFMAs;
-//   * loads run NB blocks ahead of the MFMAs, across tile and chunk boundaries.
-// Reduction tree of one output, fixed by K and the plan:
-//   1. inside one MFMA: the hardware's own order over its 32 K positions;
-//   2. along a wave's chunk, then along its chunks: the accumulator operand, in
-//      ascending K;
-//   3. across the waves of the workgroup in ascending wave order, through LDS
-//      (after each round: every wave leaves its partial tiles in its own LDS
-//      area, all threads of the workgroup add and store, then the next round);
-//   4. split-K baseline only: S chunk sums added in chunk order.
-#include "gemv_kernels.h"
-
-typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
-typedef float f32x4_t __attribute__((ext_vector_type(4)));
-
-template <int NBK, int G, int NB, int MAXW, bool ALLFULL, bool ONECHUNK, int EPI>
-__global__ __launch_bounds__(MAXW * 64) void gemv_mfma_kernel(const GemvArgs a) {
-  constexpr int KC = 128 * NBK;
-  constexpr int T = G * NBK;  // blocks of one chunk, tile-major
-  static_assert(NB <= T && T % NB == 0, "the load window must divide a chunk's blocks");
-  constexpr int ROUT = (EPI == EPI_SILU) ? 8 : 16;  // outputs per tile: gate rows 0-7 pair with up rows 8-15
-  constexpr int WAVE_LDS = (G > 4 ? G : 4) * 64;     // 16-byte units per wave: transpose area, later G partial tiles
-  __shared__ u32x4 stage_all[MAXW * WAVE_LDS];
-  __shared__ float s_bv[MAXW][16];
-  __shared__ int s_bi[MAXW][16];
-  __shared__ int s_last;
-
-  const int lane = threadIdx.x & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int nw = blockDim.x >> 6;
-  const int c = lane & 15, q = lane >> 4;    // MFMA operand coordinates
-  const int lr = lane >> 4, lp = lane & 15;  // load coordinates: row within a 4-row group, 16-byte piece of 256 B
-  const int split = blockIdx.y;
-  const int k_begin = split * a.k_per_split;
-  const int k_end = k_begin + a.k_per_split;
-  const int nchunks = (a.k_per_split + KC - 1) / KC;
-  u32x4* stage = stage_all + wave * WAVE_LDS;
-
-  // First weight row of the 4-row group u of tile g (wave-uniform, so the loads
-  // take a scalar base and one per-lane offset).  A tile that would run past the
-  // end is moved up to end at the last row; the rows it then shares with its
-  // predecessor are computed twice and stored once (by the predecessor).
-  auto tile_first = [&](int rd, int g) { return ((blockIdx.x * a.groups + rd) * G + g) * ROUT; };
-  auto tile_start = [&](int rd, int g) {
-    const int out0 = tile_first(rd, g);
-    const int last = ((EPI == EPI_SILU) ? a.n_out : a.N) - ROUT;
-    return out0 < last ? out0 : last;
-  };
-  // Loads go through buffer resources: a scalar base, a scalar offset per 4-row
-  // group and block, one per-lane offset for the whole launch.  The scalar part
-  // stays below 32 bits because it is relative to the workgroup's first tile.
-  constexpr int kRsrcFlags = 0x00020000;  // raw 32-bit data format
-  // one resource per 4-row group of a tile (with the SiLU epilogue groups 2, 3 are the up rows)
-  const uint16_t* wbase = a.W + static_cast<size_t>(tile_start(0, 0)) * a.K;
-  __amdgpu_buffer_rsrc_t rs_w[4];
-#pragma unroll
-  for (int u = 0; u < 4; ++u) {
-    const size_t row = (EPI == EPI_SILU) ? (u < 2 ? 4 * u : static_cast<size_t>(a.n_out) + 4 * (u - 2)) : 4 * u;
-    rs_w[u] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(wbase + row * a.K), 0, 0x7fffffff, kRsrcFlags);
-  }
-  const uint32_t voff = (static_cast<uint32_t>(lr) * a.K + lp * 8) * 2u;  // bytes
-  // X: rows past B lie outside the resource and read as zero
-  const __amdgpu_buffer_rsrc_t rs_x = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<uint16_t*>(a.X), 0, static_cast<int>((static_cast<uint32_t>(a.B - 1) * a.ldx + a.K) * 2u), kRsrcFlags);
-  const uint32_t voff_x = c < a.B ? (static_cast<uint32_t>(c) * a.ldx + q * 8) * 2u : 0x80000000u;
-
-  f32x4_t acc[G];
-  const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
-
-  u32x4 wbuf[NB][4];
-  u32x4 xs[NBK][4];
-  auto load_block = [&](u32x4(&dst)[4], int rd, int ch, int g, int bi) {
-    const int kb = k_begin + ch * KC + bi * 128;
-    const int soff = ((tile_start(rd, g) - tile_start(0, 0)) * a.K + k_begin + ch * KC) * 2;
-    // K tail: a piece past k_end is not fetched at all (behind the last row of W it would lie
-    // outside the allocation).  The range check of a buffer load looks at the per-lane offset
-    // only, so such a lane gets an offset beyond the resource and reads zeros.
-    const uint32_t vo = (ALLFULL || kb + lp * 8 < k_end) ? voff : 0x80000000u;
-#pragma unroll
-    for (int t = 0; t < 4; ++t)
-      dst[t] = __builtin_amdgcn_raw_buffer_load_b128(rs_w[t], vo, soff + bi * 256, 2);  // streaming
-  };
-  auto load_x = [&](int ch) {
-    const int soff = (k_begin + ch * KC) * 2;
-#pragma unroll
-    for (int bi = 0; bi < NBK; ++bi)
-#pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        const uint32_t vo = (ALLFULL || k_begin + ch * KC + bi * 128 + s * 32 + q * 8 < k_end) ? voff_x : 0x80000000u;
-        xs[bi][s] = __builtin_amdgcn_raw_buffer_load_b128(rs_x, vo, soff + (bi * 128 + s * 32) * 2, 0);
-      }
-  };
-
-  // the finishing part of a round: a thread owns four consecutive tile rows of one
-  // batch row of one tile
-  float best_v = -INFINITY;
-  int best_i = INT_MAX;
-  auto epilogue = [&](int rd, int g, int col, int qq, const float(&s)[4], const float(&u)[4]) {
-    if (col >= a.B) return;
-    const int first = tile_first(rd, g);  // rows below belong to the previous tile
-    const int out0 = tile_start(rd, g) + 4 * qq;
-#pragma unroll
-    for (int v = 0; v < 4; ++v) {
-      const int n = out0 + v;
-      if (n < first) continue;
-      if constexpr (EPI == EPI_NONE) {
-        if (n < a.N) a.Y[static_cast<size_t>(col) * a.ldy + n] = (uint16_t)f32_to_bf16(s[v]);
-      } else if constexpr (EPI == EPI_SILU) {
-        if (n < a.n_out) a.Y[static_cast<size_t>(col) * a.ldy + n] = (uint16_t)f32_to_bf16(silu_f32(s[v]) * u[v]);
-      } else {
-        if (n < a.N) {
-          if (a.logits) a.logits[static_cast<size_t>(col) * a.N + n] = s[v];
-          if (better(s[v], n, best_v, best_i)) { best_v = s[v]; best_i = n; }
-        }
-      }
-    }
-  };
-  constexpr int QOUT = (EPI == EPI_SILU) ? 2 : 4;  // quarters that own outputs
-  float* part_all = reinterpret_cast<float*>(stage_all);
-  constexpr int WAVE_F = WAVE_LDS * 4;  // floats per wave area
-
-  const bool active = wave < nchunks;
-  if (active) {
-    if constexpr (ONECHUNK) load_x(wave);
-#pragma unroll
-    for (int t = 0; t < NB; ++t) load_block(wbuf[t], 0, wave, t / NBK, t % NBK);
-  }
-  for (int rd = 0; rd < a.groups; ++rd) {
-#pragma unroll
-    for (int g = 0; g < G; ++g) acc[g] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-    if (active) {
-      int ch = wave;
-      while (true) {
-        if constexpr (!ONECHUNK) load_x(ch);
-        const int chn = ch + nw;
-        const bool more = !ONECHUNK && chn < nchunks;  // ONECHUNK: the launch has no more chunks than waves
-        const bool next_round = rd + 1 < a.groups;
-#pragma unroll
-        for (int t = 0; t < T; ++t) {
-          const int g = t / NBK, bi = t % NBK, slot = t % NB;
-          // keep the written order (the scheduler would otherwise sink the loads
-          // next to their uses and leave two or three in flight)
-          __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-          for (int u = 0; u < 4; ++u) {
-            const int r = 4 * u + lr;
-            stage[r * 16 + (lp ^ r)] = wbuf[slot][u];
-          }
-          // the slot is free again: request the block NB positions ahead (next
-          // tile, next chunk of this round, or the first chunk of the next round)
-          if (t + NB < T) load_block(wbuf[slot], rd, ch, (t + NB) / NBK, (t + NB) % NBK);
-          else if (more) load_block(wbuf[slot], rd, chn, (t + NB - T) / NBK, (t + NB - T) % NBK);
-          else if (next_round) load_block(wbuf[slot], rd + 1, wave, (t + NB - T) / NBK, (t + NB - T) % NBK);
-          __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-          __builtin_amdgcn_wave_barrier();
-          __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-          u32x4 av[4];
-#pragma unroll
-          for (int s = 0; s < 4; ++s) av[s] = stage[c * 16 + ((4 * s + q) ^ c)];
-#pragma unroll
-          for (int s = 0; s < 4; ++s)
-            acc[g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, av[s]),
-                                                             __builtin_bit_cast(bf16x8_t, xs[bi][s]), acc[g], 0, 0, 0);
-          __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-          __builtin_amdgcn_wave_barrier();
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        if (ONECHUNK || !more) break;
-        ch = chn;
-      }
-    }
-
-    // wave partial tiles -> the wave's own LDS area (its transposes of this round are
-    // done): lane (c, q), register v holds tile row 4 q + v of batch row c
-#pragma unroll
-    for (int g = 0; g < G; ++g)
-#pragma unroll
-      for (int v = 0; v < 4; ++v) part_all[wave * WAVE_F + (g * 4 + v) * 64 + lane] = acc[g][v];
-    __syncthreads();
-    for (int f = threadIdx.x; f < G * 64; f += blockDim.x) {
-      const int g = f >> 6, ln = f & 63, col = ln & 15, qq = ln >> 4;
-      if (qq >= QOUT) continue;
-      float s[4], u[4] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        const float* pp = part_all + (g * 4 + v) * 64 + ln;
-        float t = pp[0];
-        for (int w = 1; w < nw; ++w) t += pp[w * WAVE_F];  // ascending wave (K) order
-        s[v] = t;
-        if constexpr (EPI == EPI_SILU) {
-          float t2 = pp[32];
-          for (int w = 1; w < nw; ++w) t2 += pp[w * WAVE_F + 32];
-          u[v] = t2;
-        }
-      }
-      if (a.S == 1) {
-        epilogue(rd, g, col, qq, s, u);
-      } else if (col < a.B) {
-        const int first = tile_first(rd, g);
-        const int out0 = tile_start(rd, g) + 4 * qq;
-        float* pp = a.partials + (static_cast<size_t>(split) * a.bt + col) * a.N;
-#pragma unroll
-        for (int v = 0; v < 4; ++v) {
-          const int n = out0 + v;
-          if (n < first) continue;
-          if constexpr (EPI == EPI_SILU) {
-            if (n < a.n_out) { pp[n] = s[v]; pp[a.n_out + n] = u[v]; }
-          } else {
-            if (n < a.N) pp[n] = s[v];
-          }
-        }
-      }
-    }
-    __syncthreads();  // the LDS areas are transposition space again
-  }
-
-  // ---- split-K baseline: the last chunk-block of this row block adds the chunk sums ----
-  if (a.S > 1) {
-    __threadfence();
-    __syncthreads();
-    if (threadIdx.x == 0) {
-      const uint32_t t = atomicAdd(&a.ws[1 + blockIdx.x], 1u);
-      s_last = (t == static_cast<uint32_t>(a.S) - 1u);
-    }
-    __syncthreads();
-    if (!s_last) return;
-    __threadfence();
-    for (int f = threadIdx.x; f < a.groups * G * 64; f += blockDim.x) {
-      const int rd = f / (G * 64), g = (f >> 6) % G, ln = f & 63, col = ln & 15, qq = ln >> 4;
-      if (qq >= QOUT || col >= a.B) continue;
-      const int first = tile_first(rd, g);
-      const int out0 = tile_start(rd, g) + 4 * qq;
-      float s[4] = {0.f, 0.f, 0.f, 0.f}, u[4] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        const int n = out0 + v;
-        const bool live = n >= first && ((EPI == EPI_SILU) ? n < a.n_out : n < a.N);
-        if (!live) continue;
-        for (int sp = 0; sp < a.S; ++sp) {  // chunk order
-          const float* pp = a.partials + (static_cast<size_t>(sp) * a.bt + col) * a.N;
-          s[v] += __builtin_nontemporal_load(pp + n);
-          if constexpr (EPI == EPI_SILU) u[v] += __builtin_nontemporal_load(pp + a.n_out + n);
-        }
-      }
-      epilogue(rd, g, col, qq, s, u);
-    }
-    if (threadIdx.x == 0) a.ws[1 + blockIdx.x] = 0u;  // ready for the next launch
-  }
-
-  // ---- LM head: workgroup argmax -> one (value, index) candidate per batch row ----
-  if constexpr (EPI == EPI_ARGMAX) {
-    // a thread's batch row is lane % 16 in every pass of the finishing loop
-#pragma unroll
-    for (int d = 16; d < 64; d <<= 1) {
-      const float ov = __shfl_xor(best_v, d, 64);
-      const int oi = __shfl_xor(best_i, d, 64);
-      if (better(ov, oi, best_v, best_i)) { best_v = ov; best_i = oi; }
-    }
-    if (lane < 16) { s_bv[wave][lane] = best_v; s_bi[wave][lane] = best_i; }
-    __syncthreads();
-    uint32_t* cand_v = a.ws + 1 + gridDim.x;
-    uint32_t* cand_i = cand_v + static_cast<size_t>(a.bt) * gridDim.x;
-    if (threadIdx.x < 16 && static_cast<int>(threadIdx.x) < a.B) {
-      float bv = s_bv[0][threadIdx.x];
-      int bi = s_bi[0][threadIdx.x];
-      for (int w = 1; w < nw; ++w)
-        if (better(s_bv[w][threadIdx.x], s_bi[w][threadIdx.x], bv, bi)) { bv = s_bv[w][threadIdx.x]; bi = s_bi[w][threadIdx.x]; }
-      cand_v[static_cast<size_t>(threadIdx.x) * gridDim.x + blockIdx.x] = __float_as_uint(bv);
-      cand_i[static_cast<size_t>(threadIdx.x) * gridDim.x + blockIdx.x] = static_cast<uint32_t>(bi);
-    }
-  }
-}
+// Matrix-core GEMV, one column tile (batch <= 16): the instantiations (see gemv_mfma_kernel.h).
+#include "gemv_mfma_kernel.h"
+#define VTE_MFMA_CT 1
 
 #define VTE_MFMA_EPI(NBK, G, NB, MAXW, AF, OC)                                                       \
   {                                                                                                 \
-    if (epi == 0) return (const void*)gemv_mfma_kernel<NBK, G, NB, MAXW, AF, OC, EPI_NONE>;         \
-    if (epi == 1) return (const void*)gemv_mfma_kernel<NBK, G, NB, MAXW, AF, OC, EPI_SILU>;         \
-    if (epi == 2) return (const void*)gemv_mfma_kernel<NBK, G, NB, MAXW, AF, OC, EPI_ARGMAX>;       \
+    if (epi == 0) return (const void*)gemv_mfma_kernel<NBK, G, NB, MAXW, AF, OC, EPI_NONE, VTE_MFMA_CT>;         \
+    if (epi == 1) return (const void*)gemv_mfma_kernel<NBK, G, NB, MAXW, AF, OC, EPI_SILU, VTE_MFMA_CT>;         \
+    if (epi == 2) return (const void*)gemv_mfma_kernel<NBK, G, NB, MAXW, AF, OC, EPI_ARGMAX, VTE_MFMA_CT>;       \
   }
 #define VTE_MFMA_CASE(NBK, G, NB, MAXW)                                  \
   if (nbk == NBK && g == G && nb == NB && maxw == MAXW) {                \

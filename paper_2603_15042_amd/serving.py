@@ -6,8 +6,9 @@ production traces; this is a seeded synthetic stand-in with the stated distribut
 
 Requests arrive by a Poisson process, carry a prompt length (it only sizes the host-to-device copy
 that precedes the first decode step), an output length and a start token.  Up to 64 run at once,
-in four chunks of 16 rows, each stepping its own copy of the chain's activations over shared
-weights; two chunks share a virtual stream and take turns on it.  Five tenants would be one too many:
+in chunks of 16 rows (four of them; or two of 32 with --chunk 32, which reads the weights half as
+often), each stepping its own copy of the chain's activations over shared weights; the chunks are
+dealt to two virtual streams and take turns on theirs.  Five tenants would be one too many:
 the device dispatches from four pipes and queues on one pipe run one kernel at a time, so the sweep
 keeps to two decode streams and the co-tenant.  Every launch is built at batch 16, so a row's arithmetic does not
 depend on what shares the launch, and a request's token stream is a function of its start token
@@ -25,7 +26,7 @@ import torch
 
 from . import harness as H, inputs, vte
 
-CHUNK, MAX_CHUNKS, STREAMS = 16, 4, 2   # four chunks of 16 rows on two virtual streams
+MAX_ROWS, STREAMS = 64, 2   # at most 64 requests at once, in chunks of 16 (or 32) rows on two virtual streams
 WIDTHS = (32, 64, 128, 192, 224, 256)
 
 
@@ -54,7 +55,9 @@ def layer_weights(seed, shp, layers):
 
 
 class Server:
-    def __init__(self, layers, small=False, lookahead=32):
+    def __init__(self, layers, small=False, lookahead=32, chunk=16):
+        assert chunk in (16, 32)
+        self.chunk, self.nchunks = chunk, MAX_ROWS // chunk
         self.shp = inputs.DecodeShapes(D=512, Nqkv=768, F=1792, V=4099) if small else inputs.DecodeShapes()
         cfg = vte.vte_pool_cfg_default()
         cfg.mode = vte.VTE_MODE_PIPELINED
@@ -64,7 +67,7 @@ class Server:
         t0 = time.time()
         self.layers, self.head = layer_weights(0, self.shp, layers)
         self.gen_seconds = time.time() - t0
-        self.chains = [H.LayeredDecode(ctx, self.layers, self.head, self.shp, CHUNK) for _ in range(MAX_CHUNKS)]
+        self.chains = [H.LayeredDecode(ctx, self.layers, self.head, self.shp, chunk) for _ in range(self.nchunks)]
         M = 1024 if small else 8192
         self.M = M
         gA = H.to_dev(inputs.normal_bf16(0, inputs.T_GEMM_A, (M, M)))
@@ -77,9 +80,9 @@ class Server:
         # torch work in the serving loop stays off the null stream, which would order itself against
         # every CU-masked stream: token reads and writes go through a non-blocking stream of their own
         self.io_stream = torch.cuda.Stream()
-        self.pin_tok = [torch.zeros(CHUNK, dtype=torch.int32).pin_memory() for _ in range(MAX_CHUNKS)]
+        self.pin_tok = [torch.zeros(chunk, dtype=torch.int32).pin_memory() for _ in range(self.nchunks)]
         self.copy_stream = torch.cuda.Stream()
-        self.stage = torch.empty(MAX_CHUNKS * CHUNK * 2048, dtype=torch.int32, device="cuda")
+        self.stage = torch.empty(MAX_ROWS * 2048, dtype=torch.int32, device="cuda")
         self.pinned = torch.zeros(2048, dtype=torch.int32).pin_memory()
         self.next_of = {}      # token -> next token, computed alone at full width
         self.profiles = {}
@@ -114,6 +117,7 @@ class Server:
         vte.vte_device_sync(self.ctx)
         vte.vte_set_builtin_policy(self.ctx, vte.VTE_POLICY_WIDEST)
         vte.vte_vstream_pin(vs, self.root)
+        CHUNK = self.chunk
         for i in range(0, len(todo), CHUNK):
             part = todo[i:i + CHUNK]
             buf = np.zeros(CHUNK, dtype=np.int32)
@@ -130,6 +134,7 @@ class Server:
         """mode: 'solo' (no co-tenant, widest) | 'fixed' (decode streams pinned to the quarters of one half, GEMM to the other half)
         | 'tput' (Throughput-Oriented plan) | 'tpot' (TPOT-First).  Chunk c runs on stream c % STREAMS."""
         ctx = self.ctx
+        CHUNK, MAX_CHUNKS = self.chunk, self.nchunks
         vte.vte_device_sync(ctx)
         vte.vte_stats_reset(ctx)
         quarters = [vte.vte_pool_find(ctx, vte.VTE_PCTX_NODE, 64, i) for i in range(STREAMS)]
@@ -262,9 +267,9 @@ class Server:
         return result
 
 
-def sweep(rates, seconds, layers, small=False, modes=("fixed", "tput", "tpot"), seed=0):
-    srv = Server(layers, small=small)
-    out = {"layers": layers, "seconds_per_rate": seconds, "seed": seed, "slo_ms": 50.0, "gen_seconds": srv.gen_seconds,
+def sweep(rates, seconds, layers, small=False, modes=("fixed", "tput", "tpot"), seed=0, chunk=16):
+    srv = Server(layers, small=small, chunk=chunk)
+    out = {"layers": layers, "chunk_rows": chunk, "seconds_per_rate": seconds, "seed": seed, "slo_ms": 50.0, "gen_seconds": srv.gen_seconds,
            "ops_per_step": srv.chains[0].ops_per_step, "bytes_per_step": srv.chains[0].bytes_per_step,
            "profiles_us": srv.profiles, "rates": {}}
     try:
@@ -300,9 +305,10 @@ def main(argv=None):
     ap.add_argument("--layers", type=int, default=32)
     ap.add_argument("--small", action="store_true")
     ap.add_argument("--modes", default="fixed,tput,tpot")
+    ap.add_argument("--chunk", type=int, default=16, help="rows per launch: 16, or 32 (two column tiles per weight tile)")
     ap.add_argument("--out", default=None)
     a = ap.parse_args(argv)
-    res = sweep([float(x) for x in a.rates.split(",")], a.seconds, a.layers, a.small, tuple(a.modes.split(",")))
+    res = sweep([float(x) for x in a.rates.split(",")], a.seconds, a.layers, a.small, tuple(a.modes.split(",")), chunk=a.chunk)
     text = json.dumps(res)
     if a.out:
         with open(a.out, "w") as f:

@@ -256,6 +256,73 @@ def test_gemv_splitk_reshaping_drifts_and_fixed_does_not(H, ctx, B):
     vte.vte_desc_destroy(fixed)
 
 
+@pytest.mark.parametrize("B,N,K", [(17, 4096, 4096), (32, 4096, 4096), (24, 513, 2048), (32, 37, 520), (20, 16, 8), (32, 260, 14336)])
+def test_gemv_batch_17_to_32_parity_and_width_invariance(H, ctx, B, N, K):
+    """Two column tiles per weight tile: same parity bar, same bits on every pCtx, and a row's result
+    is the one it has in a batch of 16 (the column tiles run the same chain)."""
+    W, X = inputs.gemv_case(seed=2, B=B, N=N, K=K)
+    dW, dX, dY = H.to_dev(W), H.to_dev(X), H.dev_empty((B, N))
+    d = vte.vte_desc_gemv(ctx, dW, dX, dY, B, N, K)
+    res = run_everywhere(H, ctx, d, dY, [H.pctx_of_width(ctx, w) for w in (32, 64, 128, 224, 256)])
+    y = assert_all_equal(res).view(np.uint16)
+    bf16_close(y, oracle.gemv(W, X), "gemv B=%d" % B)
+    vte.vte_desc_destroy(d)
+    if N >= 16:
+        # rows 1..16 as a batch of 16 through the one-tile kernel with the same K chunking and wave count
+        p32 = vte.vte_gemv_default_plan(B, N, K, 0, 1)
+        plan = vte.vte_gemv_default_plan(16, N, K, 0, 1)
+        if plan.kind == vte.VTE_GEMV_MFMA and plan.ksteps == p32.ksteps:
+            dX16, dY16 = H.to_dev(np.ascontiguousarray(X[1:17])), H.dev_empty((16, N))
+            plan.max_waves, plan.rows, plan.prefetch, plan.groups = p32.max_waves, p32.rows, p32.prefetch, p32.groups
+            try:
+                d16 = vte.vte_desc_gemv_planned(ctx, dW, dX16, dY16, 16, N, K, 0, plan)
+            except vte.VteError:
+                d16 = None                         # this combination is not built for one tile
+            if d16 is not None:
+                H.run_on(ctx, d16, H.pctx_of_width(ctx, 256))
+                assert np.array_equal(H.to_bits(dY16), y[1:17])
+                vte.vte_desc_destroy(d16)
+
+
+@pytest.mark.parametrize("B,F,K", [(32, 1000, 1024), (20, 14336, 4096)])
+def test_gate_up_silu_batch_17_to_32(H, ctx, B, F, K):
+    W = inputs.normal_bf16(4, inputs.T_WGU, (2 * F, K), 0.0, 2.0 * K ** -0.5)
+    X = inputs.normal_bf16(4, inputs.T_XB, (B, K))
+    dW, dX, dY = H.to_dev(W), H.to_dev(X), H.dev_empty((B, F))
+    d = vte.vte_desc_gemv(ctx, dW, dX, dY, B, 2 * F, K, vte.VTE_EPI_SILU_MUL)
+    res = run_everywhere(H, ctx, d, dY, [H.pctx_of_width(ctx, w) for w in (32, 256)])
+    y = assert_all_equal(res).view(np.uint16)
+    bf16_close(y, oracle.gemv_silu_mul(W, X), "silu B=%d" % B)
+    vte.vte_desc_destroy(d)
+
+
+@pytest.mark.parametrize("B,V,K", [(32, 4099, 512), (19, 32064, 4096)])
+def test_lmhead_batch_17_to_32_tokens_and_logits(H, ctx, B, V, K):
+    W = inputs.normal_bf16(8, inputs.T_WLM, (V, K), 0.0, 0.02)
+    X = inputs.normal_bf16(8, inputs.T_XB, (B, K))
+    dW, dX = H.to_dev(W), H.to_dev(X)
+    tok = torch.zeros(B, dtype=torch.int32, device="cuda")
+    lg = torch.zeros((B, V), dtype=torch.float32, device="cuda")
+    ws = H.dev_zeros_bytes(vte.vte_lmhead_workspace_bytes(B, V, K))
+    d = vte.vte_desc_lmhead_argmax(ctx, dW, dX, tok, lg, ws, B, V, K)
+    fin = vte.vte_desc_argmax_finish(ctx, d)
+    outs = []
+    for w in (256, 32):
+        tok.zero_()
+        torch.cuda.synchronize()
+        H.run_on(ctx, d, H.pctx_of_width(ctx, w))
+        H.run_on(ctx, fin, H.pctx_of_width(ctx, w))
+        outs.append((lg.cpu().numpy().copy(), tok.cpu().numpy().copy()))
+    assert np.array_equal(outs[0][0].view(np.uint32), outs[1][0].view(np.uint32)) and np.array_equal(outs[0][1], outs[1][1])
+    ref, t_ref, margin = oracle.lmhead_argmax(W, X)
+    eps_l = np.abs(outs[0][0] - ref).max()
+    assert eps_l < 1e-3
+    assert np.array_equal(outs[0][1], np.argmax(outs[0][0], axis=1))          # the token is the argmax of the GPU's own logits
+    assert all(outs[0][1][b] == t_ref[b] or margin[b] <= 2 * eps_l for b in range(B))
+    vte.vte_desc_destroy(fin)
+    vte.vte_desc_destroy(d)
+
+
 def test_k_tail_pieces_are_not_fetched_behind_the_last_row(H, ctx):
     """Down-projection shape split 8 ways: K / S = 1792 is no multiple of the 512-element chunk of the
     matrix-core kernel, and the weight tensor (56 x 2 MiB exactly) ends where its allocation ends.  The

@@ -9,8 +9,9 @@ from paper_2603_15042_amd import harness as H, serving, vte
 pytestmark = pytest.mark.gpu
 
 
-def test_row_result_is_independent_of_batch_neighbours_and_position():
-    srv = serving.Server(layers=2, small=True)
+@pytest.mark.parametrize("chunk", [16, 32])
+def test_row_result_is_independent_of_batch_neighbours_and_position(chunk):
+    srv = serving.Server(layers=2, small=True, chunk=chunk)
     try:
         rng = np.random.RandomState(3)
         toks = rng.randint(0, srv.shp.V, size=40)
@@ -24,8 +25,9 @@ def test_row_result_is_independent_of_batch_neighbours_and_position():
         srv.close()
 
 
-def test_serving_policies_reproduce_solo_tokens():
-    out = serving.sweep([60.0], 1.0, layers=2, small=True, modes=("fixed", "tput", "tpot"))
+@pytest.mark.parametrize("chunk", [16, 32])
+def test_serving_policies_reproduce_solo_tokens(chunk):
+    out = serving.sweep([60.0], 1.0, layers=2, small=True, modes=("fixed", "tput", "tpot"), chunk=chunk)
     res = out["rates"]["60.0"]
     for mode in ("solo", "fixed", "tput", "tpot"):
         r = res[mode]
