@@ -268,6 +268,13 @@ int vte_desc_lmhead_argmax_planned(vte_ctx* ctx, const void* W, const void* H, i
 int vte_desc_gather(vte_ctx* ctx, const void* E, const int32_t* tok, void* H, int B, int V,
                     int K, vte_desc** out);
 
+/* Data movement as operations of a virtual stream (Sec. 4.2: memory operations are
+ * nodes of the same dependency graph as kernels).  dst, src: device pointers, 16-byte
+ * aligned; bytes a positive multiple of 16; the ranges must not overlap.  The launch
+ * geometry follows from `bytes` alone.  memset32 stores the 32-bit `value` repeatedly. */
+int vte_desc_memcpy(vte_ctx* ctx, void* dst, const void* src, size_t bytes, vte_desc** out);
+int vte_desc_memset32(vte_ctx* ctx, void* dst, uint32_t value, size_t bytes, vte_desc** out);
+
 /* C = A * Bm^T, bf16 in, fp32 MFMA accumulation, bf16 out.  A: device [M,K];
  * Bm: device [N,K]; C: device [M,N].  M,N % 256 == 0, K % 64 == 0.  Fixed 2-D
  * tile grid, no split-K.  (The background training-shaped co-tenant; Sec. 7.5
@@ -299,7 +306,8 @@ int vte_desc_rmsnorm_reshaped(vte_ctx* ctx, const void* x, const void* gamma, vo
 enum {
   VTE_K_RMSNORM = 1, VTE_K_LAYERNORM = 2, VTE_K_GEMV = 3, VTE_K_LMHEAD = 4, VTE_K_GATHER = 5,
   VTE_K_GEMM = 6, VTE_K_GEMV_SPLITK = 7, VTE_K_LMHEAD_SPLITK = 8, VTE_K_RMSNORM_RESHAPED = 9,
-  VTE_K_ARGMAX_FINISH = 10, VTE_K_RMSNORM_GATHER = 11, VTE_K_RMSNORM_GATHER_ARGMAX = 12
+  VTE_K_ARGMAX_FINISH = 10, VTE_K_RMSNORM_GATHER = 11, VTE_K_RMSNORM_GATHER_ARGMAX = 12,
+  VTE_K_MEMCPY = 13, VTE_K_MEMSET = 14
 };
 typedef struct vte_desc_view {
   int kernel;           /* VTE_K_* */
@@ -343,6 +351,13 @@ int vte_submit_after(vte_vstream* vs, const vte_desc* desc, const vte_token* dep
 /* vte_submit for descs[0..n) in order, validated as a whole before the first is
  * submitted; *last_out (may be NULL) = token of the last op submitted. */
 int vte_submit_batch(vte_vstream* vs, const vte_desc* const* descs, int n, vte_token* last_out);
+/* Events (Sec. 4.2, "Token-Based Logical Dependencies"): recording captures the stream's
+ * current tail as an immutable completion point (0, already satisfied, for an empty
+ * stream); work submitted to the recorded stream later does not move it.  Waiting makes
+ * every op submitted to `vs` from now on depend on that point, whichever stream it came
+ * from (a token of this context that was issued; VTE_EINVAL otherwise). */
+int vte_event_record(vte_vstream* vs, vte_token* event_out);
+int vte_vstream_wait_event(vte_vstream* vs, vte_token event);
 int vte_token_query(vte_ctx* ctx, vte_token token, int* done);
 int vte_token_wait(vte_ctx* ctx, vte_token token);
 int vte_vstream_sync(vte_vstream* vs); /* waits on the stream tail */

@@ -12,6 +12,8 @@
 extern "C" {
 const void* vte_norm_entry(int threads, int layer);
 const void* vte_norm_rows_entry(int chunks, int layer);
+const void* vte_copy_entry();
+const void* vte_fill_entry();
 int vte_norm_rows_per_block(void);
 const void* vte_gemv_entry_b1(int, int, int, int, int, int);
 const void* vte_gemv_entry_b2(int, int, int, int, int, int);
@@ -444,6 +446,26 @@ int vte_desc_gather(vte_ctx* ctx, const void* E, const int32_t* tok, void* H, in
   const uint64_t shape = (static_cast<uint64_t>(B) << 32) | static_cast<uint32_t>(K);
   return finish_desc(ctx, VTE_K_GATHER, vte_gather_entry(), a, gx, static_cast<uint32_t>(B), 256, 0, shape,
                      4ull * B * K + 4ull * B, 0, out);
+}
+
+int vte_desc_memcpy(vte_ctx* ctx, void* dst, const void* src, size_t bytes, vte_desc** out) {
+  if (!ctx || !out || !dst || !src) { set_error("memcpy: null argument"); return VTE_EINVAL; }
+  if (bytes == 0 || bytes % 16 != 0 || !aligned16(dst) || !aligned16(src)) { set_error("memcpy: need bytes > 0, bytes % 16 == 0, 16-byte aligned pointers"); return VTE_EINVAL; }
+  const size_t blocks = (bytes + 16383) / 16384;
+  if (blocks > 0x7fffffffull) { set_error("memcpy: too large for one launch"); return VTE_EINVAL; }
+  CopyArgs a{static_cast<const unsigned char*>(src), static_cast<unsigned char*>(dst), bytes};
+  return finish_desc(ctx, VTE_K_MEMCPY, vte_copy_entry(), a, static_cast<uint32_t>(blocks), 1, 256, 0,
+                     static_cast<uint64_t>(bytes), 2ull * bytes, 0, out);
+}
+
+int vte_desc_memset32(vte_ctx* ctx, void* dst, uint32_t value, size_t bytes, vte_desc** out) {
+  if (!ctx || !out || !dst) { set_error("memset: null argument"); return VTE_EINVAL; }
+  if (bytes == 0 || bytes % 16 != 0 || !aligned16(dst)) { set_error("memset: need bytes > 0, bytes % 16 == 0, a 16-byte aligned pointer"); return VTE_EINVAL; }
+  const size_t blocks = (bytes + 16383) / 16384;
+  if (blocks > 0x7fffffffull) { set_error("memset: too large for one launch"); return VTE_EINVAL; }
+  FillArgs a{static_cast<unsigned char*>(dst), bytes, value};
+  return finish_desc(ctx, VTE_K_MEMSET, vte_fill_entry(), a, static_cast<uint32_t>(blocks), 1, 256, 0,
+                     static_cast<uint64_t>(bytes), 1ull * bytes, 0, out);
 }
 
 int vte_desc_gemm(vte_ctx* ctx, const void* A, const void* Bm, void* C, int M, int N, int K, vte_desc** out) {

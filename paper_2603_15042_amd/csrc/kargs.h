@@ -3,6 +3,7 @@
 // bytes, so "submitting the descriptor unchanged" is a memcpy-level statement
 // (Sec. 4.2, "Immutable Operation Descriptors").
 #pragma once
+#include <stddef.h>
 #include <stdint.h>
 
 struct NormArgs {
@@ -45,6 +46,18 @@ struct GatherArgs {
   const int32_t* tok;
   uint16_t* H;
   int B, V, K;
+};
+
+struct CopyArgs {
+  const unsigned char* src;
+  unsigned char* dst;
+  size_t bytes;           // multiple of 16
+};
+
+struct FillArgs {
+  unsigned char* dst;
+  size_t bytes;           // multiple of 16
+  uint32_t value;
 };
 
 struct GemmArgs {

@@ -54,5 +54,30 @@ __global__ __launch_bounds__(1024) void argmax_finish_kernel(const ArgmaxFinishA
   }
 }
 
+// Device-to-device copy and 32-bit fill as launches of their own (the data-movement nodes of a
+// virtual-stream graph, Sec. 4.2): 16 bytes per thread and pass, four passes per workgroup, grid from
+// the byte count alone.
+__global__ __launch_bounds__(256) void copy_kernel(const CopyArgs a) {
+  const size_t base = (static_cast<size_t>(blockIdx.x) * 4 * 256 + threadIdx.x) * 16;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const size_t off = base + static_cast<size_t>(j) * 256 * 16;
+    if (off < a.bytes)
+      *reinterpret_cast<u32x4*>(a.dst + off) = *reinterpret_cast<const u32x4*>(a.src + off);
+  }
+}
+
+__global__ __launch_bounds__(256) void fill_kernel(const FillArgs a) {
+  const size_t base = (static_cast<size_t>(blockIdx.x) * 4 * 256 + threadIdx.x) * 16;
+  const u32x4 v = u32x4{a.value, a.value, a.value, a.value};
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const size_t off = base + static_cast<size_t>(j) * 256 * 16;
+    if (off < a.bytes) *reinterpret_cast<u32x4*>(a.dst + off) = v;
+  }
+}
+
+extern "C" const void* vte_copy_entry() { return (const void*)copy_kernel; }
+extern "C" const void* vte_fill_entry() { return (const void*)fill_kernel; }
 extern "C" const void* vte_argmax_finish_entry() { return (const void*)argmax_finish_kernel; }
 extern "C" const void* vte_gather_entry() { return (const void*)gather_kernel; }

@@ -1035,6 +1035,8 @@ static int submit_locked(vte_ctx* c, vte_vstream* vs, const vte_desc* d, const v
   op->t_submit = c->now();
   op->deps.push_back(vs->tail);  // stream order: depends on the tail, becomes the tail
   for (int i = 0; i < n_deps; ++i) op->deps.push_back(deps[i]);
+  for (vte_token t : vs->waited_events) op->deps.push_back(t);  // stream-level waits: this op carries them, later ops follow it
+  vs->waited_events.clear();
   if (vs->tpot > 0 && vs->queue.empty() && vs->unfinished_bound == 0) vs->t_ref = op->t_submit;  // the clock of an idle stream starts now
   ++vs->ops_submitted;
   if (vs->tpot > 0) {
@@ -1082,6 +1084,24 @@ int vte_submit_batch(vte_vstream* vs, const vte_desc* const* descs, int n, vte_t
     if (last_out) *last_out = last;
   }
   bump(c);
+  return VTE_OK;
+}
+
+int vte_event_record(vte_vstream* vs, vte_token* event_out) {
+  vte_ctx* c = ctx_of(vs);
+  if (!c || !event_out) { set_error("event_record: bad argument"); return VTE_EINVAL; }
+  Lock lk(c->mu);
+  *event_out = vs->tail;
+  return VTE_OK;
+}
+
+int vte_vstream_wait_event(vte_vstream* vs, vte_token event) {
+  vte_ctx* c = ctx_of(vs);
+  if (!c) { set_error("wait_event: null vstream"); return VTE_EINVAL; }
+  Lock lk(c->mu);
+  if (!vs->alive) { set_error("vstream was destroyed"); return VTE_EINVAL; }
+  if (event >= c->next_token) { set_error("wait_event: token was never issued"); return VTE_EINVAL; }
+  if (event != 0 && !token_done(c, event)) vs->waited_events.push_back(event);
   return VTE_OK;
 }
 

@@ -96,6 +96,7 @@ struct vte_vstream {
   int pinned = -1;
   vte_token tail = 0;
   std::deque<vte::Op*> queue;  // submitted, not yet bound, in order
+  std::vector<vte_token> waited_events;  // events waited on since the last submission: the next op depends on them
   int unfinished_bound = 0;    // bound (in flight) ops of this stream
   std::vector<uint64_t> recent_keys;  // profile keys of the last distinct descriptors submitted (newest first)
   // TPOT-First (Sec. 5): per-token deadline bookkeeping; tpot <= 0: none

@@ -488,6 +488,39 @@ def test_gather(H, ctx):
     vte.vte_desc_destroy(d)
 
 
+def test_memcpy_and_memset_launches(H, ctx):
+    n = 3 * 16384 + 4096 + 16                                # several workgroups and a ragged last one
+    src = torch.randint(-2 ** 31, 2 ** 31 - 1, (n // 4 + 8,), dtype=torch.int32, device="cuda")
+    dst = torch.zeros_like(src)
+    d = vte.vte_desc_memcpy(ctx, dst, src, n)
+    res = []
+    for w in (256, 32):
+        dst.zero_()
+        torch.cuda.synchronize()
+        H.run_on(ctx, d, H.pctx_of_width(ctx, w))
+        res.append(dst.cpu().numpy().copy())
+    ref = src.cpu().numpy().copy()
+    ref[n // 4:] = 0                                         # nothing past the byte count is written
+    assert np.array_equal(res[0], ref) and np.array_equal(res[1], ref)
+    m = vte.vte_desc_memset32(ctx, dst, 0x3f803f80, n)
+    H.run_on(ctx, m, H.pctx_of_width(ctx, 64))
+    got = dst.cpu().numpy().view(np.uint32)
+    assert np.all(got[:n // 4] == 0x3f803f80) and np.all(got[n // 4:] == 0)
+    # as operations of two virtual streams ordered by an event: fill, then copy the filled buffer
+    a, b = vte.vte_vstream_create(ctx), vte.vte_vstream_create(ctx)
+    out = torch.zeros_like(src)
+    fill = vte.vte_desc_memset32(ctx, dst, 0x12345678, n)
+    copy = vte.vte_desc_memcpy(ctx, out, dst, n)
+    vte.vte_submit(a, fill)
+    vte.vte_vstream_wait_event(b, vte.vte_event_record(a))
+    vte.vte_token_wait(ctx, vte.vte_submit(b, copy))
+    assert np.all(out.cpu().numpy().view(np.uint32)[:n // 4] == 0x12345678)
+    for vs in (a, b):
+        vte.vte_vstream_destroy(vs)
+    for dd in (d, m, fill, copy):
+        vte.vte_desc_destroy(dd)
+
+
 # ---------- MFMA GEMM ---------------------------------------------------------------------------------
 @pytest.mark.parametrize("M,N,K", [(256, 256, 64), (256, 512, 128), (512, 256, 192), (512, 512, 512), (1024, 768, 1024), (256, 256, 4160)])
 def test_gemm_parity_and_width_invariance(H, ctx, M, N, K):

@@ -598,3 +598,62 @@ def test_out_of_order_completion_across_pctxs(ctx):
     vte.vte_device_sync(ctx)
     with pytest.raises(vte.VteError):
         vte.vte_fake_complete(ctx, ta)               # not in flight any more
+
+
+# ---------- events and data-movement descriptors (Sec. 4.2) ----------------------------------------
+def test_event_is_an_immutable_completion_point_and_wait_orders_a_stream(ctx):
+    a, b = vte.vte_vstream_create(ctx), vte.vte_vstream_create(ctx)
+    d = norm_desc(ctx)
+    assert vte.vte_event_record(a) == 0                      # empty stream: already satisfied
+    vte.vte_vstream_wait_event(b, 0)                         # waiting on it adds nothing
+    n0 = vte.vte_pool_find(ctx, vte.VTE_PCTX_NODE, 128, 0)
+    n1 = vte.vte_pool_find(ctx, vte.VTE_PCTX_NODE, 128, 1)
+    vte.vte_vstream_pin(a, n0)
+    vte.vte_vstream_pin(b, n1)
+    ta1 = vte.vte_submit(a, d)
+    ev = vte.vte_event_record(a)                             # generation: the tail as of now
+    assert ev == ta1
+    ta2 = vte.vte_submit(a, d)                               # later work on `a` does not move the event
+    assert vte.vte_event_record(a) == ta2
+    vte.vte_vstream_wait_event(b, ev)
+    tb1 = vte.vte_submit(b, d)                               # carries the wait ...
+    tb2 = vte.vte_submit(b, d)                               # ... and tb2 follows tb1 in stream order
+    vte.vte_dispatcher_quiesce(ctx)
+    assert [e.token for e in vte.vte_fake_log(ctx)] == [ta1]
+    vte.vte_fake_complete(ctx, ta1)
+    vte.vte_token_wait(ctx, ta1)
+    vte.vte_dispatcher_quiesce(ctx)
+    assert sorted(e.token for e in vte.vte_fake_log(ctx)) == sorted([ta1, ta2, tb1])   # tb1 did not wait for ta2
+    for t in (ta2, tb1):
+        vte.vte_fake_complete(ctx, t)
+    vte.vte_token_wait(ctx, tb1)
+    vte.vte_dispatcher_quiesce(ctx)
+    assert vte.vte_fake_log(ctx)[-1].token == tb2
+    vte.vte_fake_complete(ctx, tb2)
+    vte.vte_device_sync(ctx)
+    with pytest.raises(vte.VteError):
+        vte.vte_vstream_wait_event(b, 10 ** 9)               # never issued
+    vte.vte_vstream_wait_event(b, ta1)                       # satisfied long ago: nothing to wait for
+    t = vte.vte_submit(b, d)
+    vte.vte_dispatcher_quiesce(ctx)
+    assert vte.vte_fake_log(ctx)[-1].token == t
+    vte.vte_fake_complete(ctx, t)
+    vte.vte_device_sync(ctx)
+
+
+def test_memcpy_and_memset_descriptors(ctx):
+    d = vte.vte_desc_memcpy(ctx, A + 0x100000, A, 1 << 20)
+    v = vte.vte_desc_info(d)
+    assert v.kernel == vte.VTE_K_MEMCPY and list(v.grid) == [64, 1, 1] and list(v.block) == [256, 1, 1] and v.bytes == 2 << 20
+    m = vte.vte_desc_memset32(ctx, A, 0xDEADBEEF, 48)
+    v = vte.vte_desc_info(m)
+    assert v.kernel == vte.VTE_K_MEMSET and list(v.grid) == [1, 1, 1] and v.bytes == 48
+    args = vte.vte_desc_args(m)
+    assert int.from_bytes(args[0:8], "little") == A and int.from_bytes(args[8:16], "little") == 48
+    assert int.from_bytes(args[16:20], "little") == 0xDEADBEEF
+    for call in (lambda: vte.vte_desc_memcpy(ctx, A, A + 0x1000, 0), lambda: vte.vte_desc_memcpy(ctx, A, A + 0x1000, 24),
+                 lambda: vte.vte_desc_memcpy(ctx, A + 4, A + 0x1000, 32), lambda: vte.vte_desc_memset32(ctx, A + 8, 0, 32),
+                 lambda: vte.vte_desc_memset32(ctx, None, 0, 32)):
+        with pytest.raises(vte.VteError) as e:
+            call()
+        assert e.value.code == vte.VTE_EINVAL
