@@ -153,6 +153,17 @@ def lmhead_argmax(W, H, want_logits=True, threads=None):
     return logits, tok, margin
 
 
+def softmax_prob(logits, tok):
+    """Softmax probability of tok[b] under logits[b, :] (float32 values taken as exact), in double."""
+    lg = np.ascontiguousarray(logits, dtype=np.float32)
+    tk = np.ascontiguousarray(tok, dtype=np.int32)
+    B, V = lg.shape
+    out = np.empty(B, dtype=np.float64)
+    _load().orc_softmax_prob(ctypes.c_void_p(lg.ctypes.data), ctypes.c_void_p(tk.ctypes.data), _i64(B), _i64(V),
+                             ctypes.c_void_p(out.ctypes.data))
+    return out
+
+
 def gather(E, tok):
     E, pe = _u16(E)
     tok = np.ascontiguousarray(tok, dtype=np.int32)

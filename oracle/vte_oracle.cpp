@@ -255,6 +255,24 @@ void orc_gemm_cols(const uint16_t* A, const uint16_t* Bm, int64_t M, int64_t K,
   });
 }
 
+// ---- softmax probability of a given token (Sec. 7.2: the decode replay records the
+// softmax probability of the sampled token next to the token itself) -----------------
+// p[b] = exp(l[b, tok[b]]) / sum_v exp(l[b, v]), evaluated as exp(l - m) with m the row
+// maximum (the shift cancels; it only keeps exp in range).  logits: [B, V] float (the
+// fp32 logits a launch stored, taken as exact values).  A token outside [0, V) gives 0.
+void orc_softmax_prob(const float* logits, const int32_t* tok, int64_t B, int64_t V, double* p) {
+  for (int64_t b = 0; b < B; ++b) {
+    const float* l = logits + b * V;
+    double m = -INFINITY;
+    for (int64_t v = 0; v < V; ++v)
+      if (static_cast<double>(l[v]) > m) m = l[v];
+    double sum = 0.0;
+    for (int64_t v = 0; v < V; ++v) sum += std::exp(static_cast<double>(l[v]) - m);
+    const int64_t t = tok[b];
+    p[b] = (t >= 0 && t < V) ? std::exp(static_cast<double>(l[t]) - m) / sum : 0.0;
+  }
+}
+
 // ---- one decode step of the Llama-shaped chain -----------------------------------
 // Rounds to bf16 exactly where the chain stores a bf16 tensor between two
 // launches; everything between two such points is evaluated in double.

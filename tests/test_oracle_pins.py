@@ -359,3 +359,44 @@ def test_decode_step_is_the_listed_composition():
     assert np.array_equal(o["next"], np.argmax(lg, axis=1))
     assert np.count_nonzero(f(o["act"])) > 0.9 * o["act"].size
     assert logits.shape == (3, shp.V)
+
+
+# ---------- softmax probability of a token (Sec. 7.2) ---------------------------------------------
+def test_softmax_prob_closed_forms():
+    V = 1000
+    # all logits equal -> 1 / V, whatever the level
+    for level in (0.0, -50.0, 80.0):
+        p = oracle.softmax_prob(np.full((2, V), level, np.float32), [0, V - 1])
+        assert np.allclose(p, 1.0 / V, rtol=1e-14)
+    # two live entries with logits 0 and ln 3, everything else -inf -> 1/4 and 3/4
+    lg = np.full((2, V), -np.inf, np.float32)
+    lg[:, 7] = 0.0
+    lg[:, 900] = np.float32(np.log(3.0))
+    p = oracle.softmax_prob(lg, [7, 900])
+    ln3 = float(np.float32(np.log(3.0)))
+    assert abs(p[0] - 1.0 / (1.0 + np.exp(ln3))) < 1e-15 and abs(p[1] - np.exp(ln3) / (1.0 + np.exp(ln3))) < 1e-15
+    assert abs(p.sum() - 1.0) < 1e-15
+    assert oracle.softmax_prob(lg, [3, 3]).tolist() == [0.0, 0.0]      # a dead entry has probability 0
+    # one live entry -> 1; a token outside the vocabulary -> 0
+    one = np.full((1, 64), -np.inf, np.float32)
+    one[0, 5] = 12.5
+    assert oracle.softmax_prob(one, [5])[0] == 1.0
+    assert oracle.softmax_prob(one, [64])[0] == 0.0 and oracle.softmax_prob(one, [-1])[0] == 0.0
+
+
+def test_softmax_prob_against_an_independent_evaluation():
+    import scipy.special
+    rng = np.random.default_rng(4)
+    lg = (rng.standard_normal((5, 4097)) * 8).astype(np.float32)
+    tok = rng.integers(0, 4097, size=5)
+    ref = scipy.special.softmax(lg.astype(np.float64), axis=1)[np.arange(5), tok]
+    got = oracle.softmax_prob(lg, tok)
+    assert np.allclose(got, ref, rtol=1e-12, atol=0)
+    # shifting a row by a constant changes nothing (logits on a 2^-10 grid, so the shifted float32 values are exact)
+    grid = (rng.integers(-8192, 8192, size=(5, 4097)) / 1024.0).astype(np.float32)
+    shifted = (grid.astype(np.float64) + 64.0).astype(np.float32)
+    assert np.array_equal(shifted.astype(np.float64) - 64.0, grid.astype(np.float64))
+    assert np.allclose(oracle.softmax_prob(shifted, tok), oracle.softmax_prob(grid, tok), rtol=1e-12)
+    # the probabilities of all tokens of a row sum to one
+    row = lg[:1].repeat(64, axis=0)
+    assert abs(oracle.softmax_prob(row, np.arange(64)).sum() - scipy.special.softmax(lg[0].astype(np.float64))[:64].sum()) < 1e-13
