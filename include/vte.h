@@ -268,6 +268,15 @@ int vte_desc_lmhead_argmax_planned(vte_ctx* ctx, const void* W, const void* H, i
 int vte_desc_gather(vte_ctx* ctx, const void* E, const int32_t* tok, void* H, int B, int V,
                     int K, vte_desc** out);
 
+/* prob[b] = softmax(logits[b,:])[tok[b]] = exp(l[tok] - max) / sum_v exp(l[v] - max), fp32, for
+ * the fp32 logits an LM-head launch stored (Sec. 7.2: the decode replay records the softmax
+ * probability next to the token).  logits: device [B,V] fp32; tok: device [B] int32; prob:
+ * device [B] fp32; a token outside [0,V) gives 0.  One workgroup per row; the sum's tree
+ * depends on V alone (thread t adds elements t, t+1024, ... in order, fixed butterfly over a
+ * wave, wave partials in wave order). */
+int vte_desc_softmax_prob(vte_ctx* ctx, const float* logits, const int32_t* tok, float* prob, int B, int V,
+                          vte_desc** out);
+
 /* Data movement as operations of a virtual stream (Sec. 4.2: memory operations are
  * nodes of the same dependency graph as kernels).  dst, src: device pointers, 16-byte
  * aligned; bytes a positive multiple of 16; the ranges must not overlap.  The launch
@@ -307,7 +316,7 @@ enum {
   VTE_K_RMSNORM = 1, VTE_K_LAYERNORM = 2, VTE_K_GEMV = 3, VTE_K_LMHEAD = 4, VTE_K_GATHER = 5,
   VTE_K_GEMM = 6, VTE_K_GEMV_SPLITK = 7, VTE_K_LMHEAD_SPLITK = 8, VTE_K_RMSNORM_RESHAPED = 9,
   VTE_K_ARGMAX_FINISH = 10, VTE_K_RMSNORM_GATHER = 11, VTE_K_RMSNORM_GATHER_ARGMAX = 12,
-  VTE_K_MEMCPY = 13, VTE_K_MEMSET = 14
+  VTE_K_MEMCPY = 13, VTE_K_MEMSET = 14, VTE_K_SOFTMAX_PROB = 15
 };
 typedef struct vte_desc_view {
   int kernel;           /* VTE_K_* */

@@ -13,6 +13,7 @@ extern "C" {
 const void* vte_norm_entry(int threads, int layer);
 const void* vte_norm_rows_entry(int chunks, int layer);
 const void* vte_copy_entry();
+const void* vte_softmax_prob_entry();
 const void* vte_fill_entry();
 int vte_norm_rows_per_block(void);
 const void* vte_gemv_entry_b1(int, int, int, int, int, int);
@@ -446,6 +447,16 @@ int vte_desc_gather(vte_ctx* ctx, const void* E, const int32_t* tok, void* H, in
   const uint64_t shape = (static_cast<uint64_t>(B) << 32) | static_cast<uint32_t>(K);
   return finish_desc(ctx, VTE_K_GATHER, vte_gather_entry(), a, gx, static_cast<uint32_t>(B), 256, 0, shape,
                      4ull * B * K + 4ull * B, 0, out);
+}
+
+int vte_desc_softmax_prob(vte_ctx* ctx, const float* logits, const int32_t* tok, float* prob, int B, int V,
+                          vte_desc** out) {
+  if (!ctx || !out || !logits || !tok || !prob) { set_error("softmax_prob: null argument"); return VTE_EINVAL; }
+  if (B < 1 || B > 65535 || V < 1) { set_error("softmax_prob: need 1 <= B <= 65535, V >= 1"); return VTE_EINVAL; }
+  SoftmaxArgs a{logits, tok, prob, B, V};
+  const uint64_t shape = (static_cast<uint64_t>(B) << 32) | static_cast<uint32_t>(V);
+  return finish_desc(ctx, VTE_K_SOFTMAX_PROB, vte_softmax_prob_entry(), a, static_cast<uint32_t>(B), 1, 1024, 0, shape,
+                     8ull * B * V + 8ull * B, 4ull * B * V, out);
 }
 
 int vte_desc_memcpy(vte_ctx* ctx, void* dst, const void* src, size_t bytes, vte_desc** out) {

@@ -60,6 +60,13 @@ struct FillArgs {
   uint32_t value;
 };
 
+struct SoftmaxArgs {
+  const float* logits;    // [B,V] fp32
+  const int32_t* tok;     // [B]
+  float* prob;            // [B]
+  int B, V;
+};
+
 struct GemmArgs {
   const uint16_t* A;      // [M,K]
   const uint16_t* Bm;     // [N,K]

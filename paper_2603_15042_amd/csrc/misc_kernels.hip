@@ -77,6 +77,41 @@ __global__ __launch_bounds__(256) void fill_kernel(const FillArgs a) {
   }
 }
 
+// Softmax probability of the chosen token under the fp32 logits of an LM-head launch (Sec. 7.2:
+// the decode replay records it next to the token).  One workgroup of 1024 threads per batch row.
+// The maximum is exact whatever the order.  Tree of the sum of exp(l - max), fixed by V: thread t
+// adds elements t, t + 1024, ... in ascending order, the 64 lanes of a wave are combined by
+// wave_sum(), the 16 wave partials are added in wave order.  p = exp(l[tok] - max) / sum.
+__global__ __launch_bounds__(1024) void softmax_prob_kernel(const SoftmaxArgs a) {
+  __shared__ float red[16];
+  const int b = blockIdx.x;
+  if (b >= a.B) return;
+  const float* l = a.logits + static_cast<size_t>(b) * a.V;
+  float m = -INFINITY;
+  for (int v = threadIdx.x; v < a.V; v += 1024) m = fmaxf(m, l[v]);  // fmaxf drops a NaN operand
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) m = fmaxf(m, __shfl_xor(m, d, 64));
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
+  __syncthreads();
+  m = red[0];
+#pragma unroll
+  for (int w = 1; w < 16; ++w) m = fmaxf(m, red[w]);
+  __syncthreads();
+  float s = 0.f;
+  for (int v = threadIdx.x; v < a.V; v += 1024) s += expf(l[v] - m);
+  s = wave_sum(s);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float tot = red[0];
+#pragma unroll
+    for (int w = 1; w < 16; ++w) tot += red[w];
+    const int t = a.tok[b];
+    a.prob[b] = (t >= 0 && t < a.V) ? expf(l[t] - m) / tot : 0.f;
+  }
+}
+
+extern "C" const void* vte_softmax_prob_entry() { return (const void*)softmax_prob_kernel; }
 extern "C" const void* vte_copy_entry() { return (const void*)copy_kernel; }
 extern "C" const void* vte_fill_entry() { return (const void*)fill_kernel; }
 extern "C" const void* vte_argmax_finish_entry() { return (const void*)argmax_finish_kernel; }

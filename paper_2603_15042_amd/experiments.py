@@ -153,11 +153,19 @@ def determinism(trials, replays, seed0=0):
     base = H.DecodeChain(ctx, wd, shp, B, want_logits=True)
     base.set_tokens(tok0)
     base.run_step_on(p256)
+    # the replay also records the softmax probability of the greedy token (Sec. 7.2)
+    prob = torch.zeros(B, dtype=torch.float32, device="cuda")
+    d_prob = vte.vte_desc_softmax_prob(ctx, base.logits, base.next, prob, B, shp.V)
+    H.run_on(ctx, d_prob, p256)
+    p0 = prob.cpu().numpy().copy()
     s0 = base.snapshot()
     chains = {S: H.DecodeChain(ctx, wd, shp, B, want_logits=True, splitk=S, rms_active_cus=32 * S) for S in (1, 2, 4, 8)}
     r = {"replays": replays, "fixed_logit_mismatched_bits": 0, "fixed_token_flips": 0,
          "reshaped_logit_mismatched_bits": 0, "reshaped_token_flips": 0, "reshaped_max_logit_diff": 0.0,
-         "reshaped_replays_with_logit_drift": 0}
+         "reshaped_replays_with_logit_drift": 0, "fixed_prob_mismatched_bits": 0, "reshaped_max_prob_diff": 0.0,
+         "greedy_token_prob_min": float(p0.min()), "greedy_token_prob_max": float(p0.max())}
+    probs_r = {S: torch.zeros(B, dtype=torch.float32, device="cuda") for S in chains}
+    d_prob_r = {S: vte.vte_desc_softmax_prob(ctx, chains[S].logits, chains[S].next, probs_r[S], B, shp.V) for S in chains}
     chains[1].set_tokens(tok0)
     chains[1].run_step_on(H.pctx_of_width(ctx, 32))
     s1 = chains[1].snapshot()
@@ -168,14 +176,18 @@ def determinism(trials, replays, seed0=0):
         ids = [_rand_pctx(rng, ctx) for _ in base.order]
         base.set_tokens(tok0)
         base.run_step_on(ids)
+        H.run_on(ctx, d_prob, _rand_pctx(rng, ctx))
         s = base.snapshot()
+        r["fixed_prob_mismatched_bits"] += H.mismatched_bits(p0, prob.cpu().numpy())[1]
         r["fixed_logit_mismatched_bits"] += H.mismatched_bits(s0["logits"], s["logits"])[1]
         r["fixed_token_flips"] += int(np.count_nonzero(s0["next"] != s["next"]))
         S = (1, 2, 4, 8)[int(rng.integers(0, 4))]
         c = chains[S]
         c.set_tokens(tok0)
         c.run_step_on(H.pctx_of_width(ctx, 32 * S))
+        H.run_on(ctx, d_prob_r[S], H.pctx_of_width(ctx, 32 * S))
         s = c.snapshot()
+        r["reshaped_max_prob_diff"] = max(r["reshaped_max_prob_diff"], float(np.abs(probs_r[S].cpu().numpy() - p0).max()))
         b = H.mismatched_bits(s0["logits"], s["logits"])[1]
         r["reshaped_logit_mismatched_bits"] += b
         r["reshaped_replays_with_logit_drift"] += int(b > 0)

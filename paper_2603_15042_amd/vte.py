@@ -24,7 +24,7 @@ VTE_POLICY_WIDEST, VTE_POLICY_QUEUE_STATE, VTE_POLICY_TPUT_PLAN, VTE_POLICY_TPOT
 VTE_GEMV_DOT2, VTE_GEMV_MFMA = 0, 1
 (VTE_K_RMSNORM, VTE_K_LAYERNORM, VTE_K_GEMV, VTE_K_LMHEAD, VTE_K_GATHER, VTE_K_GEMM, VTE_K_GEMV_SPLITK,
  VTE_K_LMHEAD_SPLITK, VTE_K_RMSNORM_RESHAPED, VTE_K_ARGMAX_FINISH, VTE_K_RMSNORM_GATHER,
- VTE_K_RMSNORM_GATHER_ARGMAX, VTE_K_MEMCPY, VTE_K_MEMSET) = range(1, 15)
+ VTE_K_RMSNORM_GATHER_ARGMAX, VTE_K_MEMCPY, VTE_K_MEMSET, VTE_K_SOFTMAX_PROB) = range(1, 16)
 
 
 class VteError(RuntimeError):
@@ -121,7 +121,7 @@ EXPORTS = [
     "vte_hint_submit", "vte_profile_measure", "vte_profile_measure_on", "vte_profile_set", "vte_profile_get", "vte_stats", "vte_stats_read",
     "vte_stats_reset", "vte_fake_complete", "vte_fake_set_autocomplete", "vte_fake_fail_next_submits",
     "vte_fake_log", "vte_dispatcher_quiesce", "vte_now", "vte_vstream_set_tpot", "vte_vstream_tpot_info", "vte_submit_batch", "vte_pool_creation_order", "vte_desc_memcpy", "vte_desc_memset32",
-    "vte_event_record", "vte_vstream_wait_event",
+    "vte_event_record", "vte_vstream_wait_event", "vte_desc_softmax_prob",
 ]
 
 _lib = None
@@ -310,6 +310,10 @@ def vte_desc_lmhead_argmax_splitk(ctx, W, H, tok, logits_or_null, workspace, par
 
 def vte_desc_gather(ctx, E, tok, H, B, V, K):
     return _desc_call(load().vte_desc_gather, ctx, _ptr(E), _ptr(tok), _ptr(H), int(B), int(V), int(K))
+
+
+def vte_desc_softmax_prob(ctx, logits, tok, prob, B, V):
+    return _desc_call(load().vte_desc_softmax_prob, ctx, _ptr(logits), _ptr(tok), _ptr(prob), int(B), int(V))
 
 
 def vte_desc_memcpy(ctx, dst, src, nbytes):

@@ -488,6 +488,27 @@ def test_gather(H, ctx):
     vte.vte_desc_destroy(d)
 
 
+@pytest.mark.parametrize("B,V", [(8, 128256), (3, 4099), (1, 1), (5, 1000), (16, 32064)])
+def test_softmax_prob_parity_and_width_invariance(H, ctx, B, V):
+    rng = np.random.default_rng(V)
+    lg = (rng.standard_normal((B, V)) * 3).astype(np.float32)
+    tok = rng.integers(0, V, size=B).astype(np.int32)
+    tok[0] = int(np.argmax(lg[0]))                       # the greedy token of a row
+    if B > 2:
+        tok[2] = V + 5                                    # outside the vocabulary -> 0
+        lg[1, : V // 2] = -np.inf                         # dead entries
+    dl, dt = torch.from_numpy(lg).cuda(), torch.from_numpy(tok).cuda()
+    dp = torch.zeros(B, dtype=torch.float32, device="cuda")
+    d = vte.vte_desc_softmax_prob(ctx, dl, dt, dp, B, V)
+    res = run_everywhere(H, ctx, d, dp, [H.pctx_of_width(ctx, w) for w in (32, 64, 128, 224, 256)])
+    p = assert_all_equal(res).view(np.float32)            # same bits on every width
+    ref = oracle.softmax_prob(lg, tok)
+    assert np.all(np.abs(p - ref) <= 5e-5 * ref + 1e-30), (p, ref)
+    if B > 2:
+        assert p[2] == 0.0
+    vte.vte_desc_destroy(d)
+
+
 def test_memcpy_and_memset_launches(H, ctx):
     n = 3 * 16384 + 4096 + 16                                # several workgroups and a ragged last one
     src = torch.randint(-2 ** 31, 2 ** 31 - 1, (n // 4 + 8,), dtype=torch.int32, device="cuda")
