@@ -557,6 +557,37 @@ def test_gemm_parity_and_width_invariance(H, ctx, M, N, K):
     vte.vte_desc_destroy(d)
 
 
+@pytest.mark.parametrize("K", [512, 8192])
+def test_gemm_full_grid_sampled_rows(H, ctx, K):
+    """The co-tenant's own size (8192 x 8192 outputs: 1024 tiles in the XCD-aware order, L2 warm-up
+    touches active), checked on sampled rows and columns the oracle computes one by one; bit-equal
+    between a 32-CU and the 256-CU pCtx."""
+    M = N = 8192
+    A = inputs.normal_bf16(0, inputs.T_GEMM_A, (M, K))
+    Bm = inputs.normal_bf16(0, inputs.T_GEMM_B, (N, K))
+    dA, dB, dC = H.to_dev(A), H.to_dev(Bm), H.dev_empty((M, N))
+    d = vte.vte_desc_gemm(ctx, dA, dB, dC, M, N, K)
+    outs = []
+    for w in ((256, 32) if K == 512 else (256,)):
+        dC.fill_(0x7FC1)
+        torch.cuda.synchronize()
+        H.run_on(ctx, d, H.pctx_of_width(ctx, w))
+        outs.append(H.to_bits(dC).copy())
+    if len(outs) == 2:
+        assert H.mismatched_bits(outs[0], outs[1]) == (0, 0)
+    rows = np.array([0, 255, 256, 4095, 4101, 8191] if K == 512 else [3, 8191])
+    ref = oracle.gemm_rows(A, Bm, rows)
+    err = np.abs(f64(outs[0][rows]) - ref)
+    assert np.all(err <= 2.0 ** -8 * np.abs(ref) * (1 + 1e-2) + 1e-2), err.max()
+    cols = np.array([0, 257, 8191])                      # columns: rows of the transposed product
+    refc = oracle.gemm_rows(Bm, A, cols)                 # [cols, M]
+    errc = np.abs(f64(outs[0][:, cols]).T - refc)
+    assert np.all(errc <= 2.0 ** -8 * np.abs(refc) * (1 + 1e-2) + 1e-2), errc.max()
+    vte.vte_desc_destroy(d)
+    del dA, dB, dC
+    torch.cuda.empty_cache()
+
+
 # ---------- the decode chain --------------------------------------------------------------------------
 @pytest.fixture(scope="module")
 def small_chain(H, ctx):
