@@ -209,7 +209,9 @@ void Pool::active_overlapping(int id, std::vector<int>* out) const {
 }
 
 bool Pool::conflicts_with_active(int id, int ignore_reserved_for) const {
-  std::vector<int> ov;
+  if (active_nodes_ + active_remainders_ == 0) return false;
+  static thread_local std::vector<int> ov;  // asked for every pCtx in every dispatch round: no allocation per call
+  ov.clear();
   active_overlapping(id, &ov);
   for (int o : ov) {
     const Pctx& q = p_[o];

@@ -47,16 +47,18 @@ void fill_info(const Pool& pool, int id, vte_pctx_info* o) {
 // ---- lease state machine (Sec. 4.3 "pCtx Lifecycle") ---------------------------
 
 // Can `vs` (or an explicit launch, vs = -1) put one more op on pCtx `id` now?
-int can_admit(vte_ctx* c, int id, int vs) {
+// `quiet`: the eligibility scan of a dispatch round asks about every pCtx; it wants the answer, not a message.
+int can_admit(vte_ctx* c, int id, int vs, bool quiet = false) {
   const Pctx& p = c->pool.at(id);
-  if (p.state == kDraining || !p.gate_open) { set_error("pCtx gate is closed (draining)"); return VTE_EBUSY; }
-  if (p.reserved_for >= 0 && p.reserved_for != vs) { set_error("pCtx is reserved for another vstream"); return VTE_EBUSY; }
-  if (p.state == kLeased) {  // lease reuse by its holder: conflicts were excluded when it was opened
-    if (p.holder != vs) { set_error("pCtx is leased to another vstream"); return VTE_EBUSY; }
-    return VTE_OK;
-  }
-  if (c->pool.conflicts_with_active(id, vs)) { set_error("pCtx overlaps an active lease or reservation"); return VTE_EBUSY; }
-  return VTE_OK;
+  const char* why = nullptr;
+  if (p.state == kDraining || !p.gate_open) why = "pCtx gate is closed (draining)";
+  else if (p.reserved_for >= 0 && p.reserved_for != vs) why = "pCtx is reserved for another vstream";
+  else if (p.state == kLeased) {  // lease reuse by its holder: conflicts were excluded when it was opened
+    if (p.holder != vs) why = "pCtx is leased to another vstream";
+  } else if (c->pool.conflicts_with_active(id, vs)) why = "pCtx overlaps an active lease or reservation";
+  if (!why) return VTE_OK;
+  if (!quiet) set_error(why);
+  return VTE_EBUSY;
 }
 
 void admit(vte_ctx* c, int id, int vs) {
@@ -446,7 +448,7 @@ void eligible_set(vte_ctx* c, const Op* op, int pinned, std::vector<int>* out) {
   for (int id = 0; id < c->pool.size(); ++id) {
     if (pinned >= 0 && id != pinned) continue;
     if (!compatible(op->desc, c->pool.at(id))) continue;
-    if (can_admit(c, id, op->vs) != VTE_OK) continue;
+    if (can_admit(c, id, op->vs, true) != VTE_OK) continue;
     out->push_back(id);
   }
 }
