@@ -422,7 +422,57 @@ def overhead(launches):
                      "per_stream_creation_ms": t_init * 1e3 / vte.vte_pool_count(ctx)}
         vte.vte_shutdown(ctx)
     out.update(res)
+    out["pools"] = overhead_pools(launches)
     return out
+
+
+def overhead_pools(launches):
+    """The pool arms of the same study: the bounded hierarchical pool (tree + one remainder per level,
+    17 queues) against a flat one that pre-creates every node's remainder as well (27 queues, more
+    than the device keeps resident at once).  Per arm: end-to-end latency of one GEMM (host clock
+    around launch + wait; median and p95) bound explicitly to the 256-CU pCtx and submitted through
+    a STRICT virtual stream, and what creating the pool takes in time, device memory and host RSS."""
+    import psutil
+    proc = psutil.Process()
+    M, N, K = 512, 8192, 28672
+    gA = H.to_dev(inputs.normal_bf16(0, inputs.T_GEMM_A, (M, K)))
+    gB = H.to_dev(inputs.normal_bf16(0, inputs.T_GEMM_B, (N, K)))
+    gC = H.dev_empty((M, N))
+    arms = {}
+    for name, rem in (("hierarchical", vte.VTE_REMAINDERS_PER_LEVEL), ("flat", vte.VTE_REMAINDERS_ALL)):
+        cfg = vte.vte_pool_cfg_default()
+        cfg.mode = vte.VTE_MODE_STRICT
+        cfg.with_remainders = rem
+        torch.cuda.synchronize()
+        free0, rss0 = torch.cuda.mem_get_info()[0], proc.memory_info().rss
+        t0 = time.perf_counter()
+        ctx = vte.vte_init(0, cfg)
+        t_init = time.perf_counter() - t0
+        free1, rss1 = torch.cuda.mem_get_info()[0], proc.memory_info().rss
+        d = vte.vte_desc_gemm(ctx, gA, gB, gC, M, N, K)
+        root = vte.vte_pool_find(ctx, vte.VTE_PCTX_NODE, 256)
+        vs = vte.vte_vstream_create(ctx, vte.VTE_CLASS_LATENCY)
+        vte.vte_set_builtin_policy(ctx, vte.VTE_POLICY_WIDEST)
+        lat = {"explicit": [], "vstream": []}
+        for i in range(10 + launches):
+            t = time.perf_counter()
+            vte.vte_token_wait(ctx, vte.vte_bind_and_launch(ctx, d, root))
+            t1 = time.perf_counter()
+            vte.vte_token_wait(ctx, vte.vte_submit(vs, d))
+            t2 = time.perf_counter()
+            if i >= 10:
+                lat["explicit"].append(t1 - t)
+                lat["vstream"].append(t2 - t1)
+        arm = {"queues": vte.vte_pool_count(ctx), "creation_ms": t_init * 1e3,
+               "device_bytes": int(free0 - free1), "host_rss_bytes": int(rss1 - rss0)}
+        for k, v in lat.items():
+            v.sort()
+            arm[k + "_median_us"] = v[len(v) // 2] * 1e6
+            arm[k + "_p95_us"] = v[min(len(v) - 1, int(0.95 * len(v)))] * 1e6
+            arm[k + "_max_us"] = v[-1] * 1e6
+        arms[name] = arm
+        vte.vte_shutdown(ctx)
+    return arms
 
 
 def main(argv=None):
