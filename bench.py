@@ -39,6 +39,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=300)
     ap.add_argument("--batch", type=int, default=8)
     ap.add_argument("--mode", choices=("pipelined", "strict"), default="pipelined")
+    ap.add_argument("--timing-stride", type=int, default=8,
+                    help="time every n-th LM-head launch of the run (1 = each; a timed launch idles its stream for a few us)")
     ap.add_argument("--no-kernel-timing", action="store_true", help="do not bracket the LM head with device events")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-width-sweep", action="store_true")
@@ -68,6 +70,7 @@ def main():
     cfg.mode = vte.VTE_MODE_PIPELINED if a.mode == "pipelined" else vte.VTE_MODE_STRICT
     cfg.lookahead = 64
     cfg.device_timing_mask = 0 if a.no_kernel_timing else 1 << vte.VTE_K_LMHEAD
+    cfg.device_timing_stride = a.timing_stride
     torch.zeros(1, device="cuda")
     ctx = vte.vte_init(0, cfg)
     wd = H.upload_weights(w)
@@ -117,7 +120,7 @@ def main():
         "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
         "roofline": {"bound": "hbm", "kernel": "lm-head GEMV + argmax", "achieved": round(lm_bytes / lm_avg / 1e9, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(lm_bytes / lm_avg / 1e9 / HBM_PEAK_GBS, 4),
-                     "avg_kernel_us": round(lm_avg * 1e6, 2), "launches_timed": len(lm), "traffic": _counter_traffic(),
+                     "avg_kernel_us": round(lm_avg * 1e6, 2), "launches_timed": len(lm), "timing_stride": a.timing_stride, "traffic": _counter_traffic(),
                      "algorithmic_bytes_per_launch": int(lm_bytes)},
     }
 

@@ -103,11 +103,16 @@ typedef struct vte_pool_cfg {
   int mode;            /* VTE_MODE_* */
   int lookahead;       /* PIPELINED: max unfinished ops bound ahead per vstream; 0 = 16 */
   int stats_capacity;  /* ring size of per-op records kept for vte_stats_read; 0 = 65536 */
-  unsigned device_timing_mask; /* bit k set: launches of kernel VTE_K_k are bracketed by timing events
-                                  on their own stream and vte_op_record.gpu_seconds is filled */
+  unsigned device_timing_mask; /* bit k set: launches of kernel VTE_K_k carry a pair of timing events on
+                                  their own stream (the kernel's begin and end on the device) and
+                                  vte_op_record.gpu_seconds is filled */
   int dispatch_pipes;  /* compute pipes the device deals its queues to, round-robin in creation order
                           (measured: 4 on MI355X); 0 = 4.  Queues are created in an order that puts
                           disjoint pCtxs on different pipes where it can (Sec. 4.3, bounded pool). */
+  int device_timing_stride; /* of the launches device_timing_mask selects, every stride-th per kernel id
+                               is timed (the first one included); 0 or 1 = all.  A timed launch keeps
+                               the stream idle for a few microseconds around it, so a sampled average
+                               disturbs a throughput measurement less. */
 } vte_pool_cfg;
 
 /* Fills *cfg with the defaults (HIP, device CU count, leaf 32, one remainder per level, STRICT). */

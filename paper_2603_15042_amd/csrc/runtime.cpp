@@ -427,7 +427,9 @@ int bind_and_submit(vte_ctx* c, Op* op, int pctx, bool record_now) {
     if (rc != VTE_OK) return rc;
   }
   void* completion = nullptr;
-  const bool timed = (c->cfg.device_timing_mask >> op->desc->kernel) & 1u;
+  bool timed = (c->cfg.device_timing_mask >> op->desc->kernel) & 1u;
+  if (timed && c->cfg.device_timing_stride > 1)
+    timed = c->timing_seen[op->desc->kernel & 31]++ % static_cast<unsigned>(c->cfg.device_timing_stride) == 0;
   rc = c->backend->submit(op->desc, p.stream, pctx, op->tok, timed, record_now, &completion);
   if (rc != VTE_OK) { ++c->stats.submit_failures; return rc; }  // op stays ready
   admit(c, pctx, op->vs);
@@ -843,6 +845,7 @@ int vte_init(vte_ctx** out, int device, const vte_pool_cfg* user_cfg) {
   // pre-create every pCtx's backend stream: nothing is created on the dispatch path.
   // The device deals queues to its dispatch pipes in creation order, so the order
   // decides which pCtxs can dispatch side by side.
+  if (cfg.device_timing_stride < 0) { set_error("device_timing_stride must not be negative"); delete c->backend; delete c; return VTE_EINVAL; }
   if (cfg.dispatch_pipes < 0 || cfg.dispatch_pipes > 32) { set_error("dispatch_pipes must be in [0,32]"); delete c->backend; delete c; return VTE_EINVAL; }
   c->pool.assign_pipes(cfg.dispatch_pipes == 0 ? 4 : cfg.dispatch_pipes);
   c->cfg.dispatch_pipes = c->pool.pipes();

@@ -136,6 +136,7 @@ struct vte_ctx {
   uint64_t next_age = 0;
   std::unordered_map<vte_token, vte::Op*> live;  // not yet done
   std::vector<vte::Op*> inflight;                // in bind order
+  unsigned timing_seen[32] = {};                 // launches of each kernel id that device_timing_mask selected so far
   std::vector<vte::Op*> lazy_tail;               // per pCtx: newest in-flight op without a completion record
   std::vector<vte_vstream*> vstreams;
   std::vector<vte_desc*> descs;

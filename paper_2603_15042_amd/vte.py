@@ -36,7 +36,8 @@ class VteError(RuntimeError):
 class vte_pool_cfg(C.Structure):
     _fields_ = [(n, C.c_int) for n in ("backend", "total_cus", "leaf_cus", "layout", "with_remainders", "mode",
                                         "lookahead", "stats_capacity")] + [("device_timing_mask", C.c_uint),
-                                                                           ("dispatch_pipes", C.c_int)]
+                                                                           ("dispatch_pipes", C.c_int),
+                                                                          ("device_timing_stride", C.c_int)]
 
 
 class vte_pctx_info(C.Structure):

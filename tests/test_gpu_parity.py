@@ -756,3 +756,4 @@ def test_chain_bits_do_not_depend_on_allocation(H, ctx, small_chain):
             assert np.array_equal(l0.view(np.uint32), l1.view(np.uint32))
             assert np.array_equal(d0, d1)
     ch.close()
+
