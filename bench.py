@@ -39,6 +39,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=300)
     ap.add_argument("--batch", type=int, default=8)
     ap.add_argument("--mode", choices=("pipelined", "strict"), default="pipelined")
+    ap.add_argument("--lookahead", type=int, default=64, help="launches bound ahead of the oldest unfinished one (pipelined binding)")
     ap.add_argument("--timing-stride", type=int, default=8,
                     help="time every n-th LM-head launch of the run (1 = each; a timed launch idles its stream for a few us)")
     ap.add_argument("--no-kernel-timing", action="store_true", help="do not bracket the LM head with device events")
@@ -68,7 +69,7 @@ def main():
 
     cfg = vte.vte_pool_cfg_default()
     cfg.mode = vte.VTE_MODE_PIPELINED if a.mode == "pipelined" else vte.VTE_MODE_STRICT
-    cfg.lookahead = 64
+    cfg.lookahead = a.lookahead
     cfg.device_timing_mask = 0 if a.no_kernel_timing else 1 << vte.VTE_K_LMHEAD
     cfg.device_timing_stride = a.timing_stride
     torch.zeros(1, device="cuda")
@@ -92,6 +93,7 @@ def main():
     torch.cuda.synchronize()
     dt = time.perf_counter() - t1
     recs = vte.vte_stats_read(ctx)
+    st = vte.vte_stats(ctx)
     lm = [r.gpu_seconds for r in recs if r.kernel == vte.VTE_K_LMHEAD and r.gpu_seconds > 0]
     lm_bytes = vte.vte_desc_info(ch.desc["lmhead"]).bytes
     lm_avg = float(np.mean(lm)) if lm else float("nan")
@@ -118,6 +120,7 @@ def main():
                                "(256 CUs), %s binding" % (B, a.mode),
                    "batch": B, "bytes_per_step": int(step_bytes), "small_shapes": bool(a.small)},
         "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
+        "launches": int(st.completed), "completion_records": int(st.completion_records),
         "roofline": {"bound": "hbm", "kernel": "lm-head GEMV + argmax", "achieved": round(lm_bytes / lm_avg / 1e9, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(lm_bytes / lm_avg / 1e9 / HBM_PEAK_GBS, 4),
                      "avg_kernel_us": round(lm_avg * 1e6, 2), "launches_timed": len(lm), "timing_stride": a.timing_stride, "traffic": _counter_traffic(),

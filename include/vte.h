@@ -518,7 +518,8 @@ typedef struct vte_op_record {
 } vte_op_record;
 typedef struct vte_stats_t {
   uint64_t submitted, completed, leases_opened, leases_reused, lease_conflicts,
-      stale_proposals, submit_failures, gates_closed, reservations;
+      stale_proposals, submit_failures, gates_closed, reservations,
+      completion_records; /* stream markers made to observe completions (PIPELINED: far fewer than launches) */
 } vte_stats_t;
 int vte_stats(vte_ctx* ctx, vte_stats_t* out);
 /* Copies up to `cap` most recent completed-op records, oldest first; *n_out = count. */

@@ -235,20 +235,33 @@ bool poll_completions(vte_ctx* c) {
 }
 
 // Give the newest unrecorded launch of a pCtx a completion record when it is
-// needed to observe progress: nothing recorded is pending on that pCtx, eight or
-// more launches have piled up behind the last record, or a caller is waiting.
+// needed to observe progress: nothing recorded is pending on that pCtx, a quarter
+// of the lookahead window (at least eight launches) has piled up behind the last
+// record, or a caller waits for a launch that no pending record covers.  A record
+// idles its stream for a few microseconds, so none is made without such a reason.
 void flush_records(vte_ctx* c) {
   const int np = c->pool.size();
   std::vector<int> recorded(np, 0), lazy(np, 0);
-  for (Op* op : c->inflight) (op->completion ? recorded : lazy)[op->pctx]++;
+  std::vector<char> covered(np, 0), urgent(np, 0);
+  for (size_t i = c->inflight.size(); i-- > 0;) {  // newest first: a record covers everything older on its pCtx
+    const Op* op = c->inflight[i];
+    if (op->completion) { ++recorded[op->pctx]; covered[op->pctx] = 1; continue; }
+    if (covered[op->pctx]) continue;
+    ++lazy[op->pctx];  // launches behind the newest record only
+    if (urgent[op->pctx]) continue;
+    if (c->waiters_all > 0 || std::find(c->awaited.begin(), c->awaited.end(), op->tok) != c->awaited.end())
+      urgent[op->pctx] = 1;
+  }
+  const int pile = std::max(8, c->cfg.lookahead / 4);
   for (int p = 0; p < np; ++p) {
     Op* op = c->lazy_tail[p];
     if (!op) continue;
-    if (recorded[p] > 0 && lazy[p] < 8 && c->waiters == 0) continue;
+    if (recorded[p] > 0 && lazy[p] < pile && !urgent[p]) continue;
     void* comp = nullptr;
     if (c->backend->record(c->pool.at(p).stream, &comp) == VTE_OK) {
       op->completion = comp;
       c->lazy_tail[p] = nullptr;
+      ++c->stats.completion_records;
     }
   }
 }
@@ -420,6 +433,7 @@ int bind_and_submit(vte_ctx* c, Op* op, int pctx, bool record_now) {
       rc = c->backend->record(c->pool.at(pred->pctx).stream, &comp);
       if (rc != VTE_OK) return rc;
       tail->completion = comp;
+      ++c->stats.completion_records;
       c->lazy_tail[pred->pctx] = nullptr;
       pred = tail;
     }
@@ -433,6 +447,7 @@ int bind_and_submit(vte_ctx* c, Op* op, int pctx, bool record_now) {
   rc = c->backend->submit(op->desc, p.stream, pctx, op->tok, timed, record_now, &completion);
   if (rc != VTE_OK) { ++c->stats.submit_failures; return rc; }  // op stays ready
   admit(c, pctx, op->vs);
+  if (completion) ++c->stats.completion_records;
   op->pctx = pctx;
   op->completion = completion;
   c->lazy_tail[pctx] = completion ? nullptr : op;  // a record also covers older launches of the pCtx
@@ -878,13 +893,13 @@ int vte_device_sync(vte_ctx* c) {
   Lock lk(c->mu);
   // waits on every token issued so far (all vstream tails and explicit launches)
   const vte_token upto = c->next_token;
-  ++c->waiters;
-  bump(c);
+  ++c->waiters_all;
+  bump(c);  // the dispatcher records a completion behind every pCtx's newest launch while somebody waits for all
   c->cv_done.wait(lk, [&] {
     for (auto& kv : c->live) if (kv.first < upto) return false;
     return true;
   });
-  --c->waiters;
+  --c->waiters_all;
   return VTE_OK;
 }
 
@@ -1123,10 +1138,10 @@ int vte_token_wait(vte_ctx* c, vte_token t) {
   Lock lk(c->mu);
   if (t >= c->next_token) { set_error("token was never issued"); return VTE_EINVAL; }
   if (token_done(c, t)) return VTE_OK;
-  ++c->waiters;
-  bump(c);  // the dispatcher records completions eagerly while somebody waits
+  c->awaited.push_back(t);
+  bump(c);  // the dispatcher sees to it that a completion record covers the awaited launch
   c->cv_done.wait(lk, [&] { return token_done(c, t); });
-  --c->waiters;
+  c->awaited.erase(std::find(c->awaited.begin(), c->awaited.end(), t));
   return VTE_OK;
 }
 

@@ -141,7 +141,8 @@ struct vte_ctx {
   std::vector<vte_vstream*> vstreams;
   std::vector<vte_desc*> descs;
   int inflight_by_class[2] = {0, 0};
-  int waiters = 0;  // callers blocked in a wait
+  std::vector<vte_token> awaited;  // tokens callers are blocked on (one entry per caller)
+  int waiters_all = 0;             // callers blocked in a wait for everything submitted so far
 
   vte_policy_vtbl policy{};
   void* policy_user = nullptr;

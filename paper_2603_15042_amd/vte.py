@@ -94,7 +94,7 @@ class vte_op_record(C.Structure):
 class vte_stats_t(C.Structure):
     _fields_ = [(n, C.c_uint64) for n in ("submitted", "completed", "leases_opened", "leases_reused",
                                            "lease_conflicts", "stale_proposals", "submit_failures", "gates_closed",
-                                           "reservations")]
+                                           "reservations", "completion_records")]
 
 
 class vte_tpot_info(C.Structure):
