@@ -198,12 +198,15 @@ int vte_desc_layernorm(vte_ctx* ctx, const void* x, const void* gamma, const voi
 
 enum { VTE_EPI_NONE = 0, VTE_EPI_SILU_MUL = 1 };
 /* Y[b,n] = bf16( sum_k W[n,k] X[b,k] ).  W: device [N,K] bf16 (each output's K
- * contiguous); X: device [B,K] bf16; Y: device [B,N] bf16.  1 <= B <= 32
+ * contiguous); X: device [B,K] bf16; Y: device [B,N] bf16.  1 <= B <= 64
  * (from 17 up N must hold at least one tile of 16 outputs, 8 with SILU_MUL),
- * K % 8 == 0, K <= 16384.  fp32 accumulation in a tree that depends on K only:
+ * K % 8 == 0, K <= 16384.  fp32 accumulation in a tree that depends on K and the
+ * plan only (vte_gemv_plan; by default chosen from B, N, K): for the small batches
  * a K-tile of 256 is 32 lanes x 8 contiguous elements; a lane adds the products
  * of its slice in ascending order, a fixed butterfly adds the 64 lanes of a
- * wave, and the per-slice sums are added in ascending K order.
+ * wave, and the per-slice sums are added in ascending K order; the matrix-core
+ * kinds accumulate 32 K positions per instruction and chain them in ascending K.
+ * The weights are read once whatever the batch.
  * epilogue SILU_MUL: N must be even; rows [0,N/2) are gate, [N/2,N) up;
  * Y is [B,N/2] = bf16( silu(g_fp32) * u_fp32 ).  (Sec. 1 "GEMV"; Sec. 2.3.) */
 int vte_desc_gemv(vte_ctx* ctx, const void* W, const void* X, void* Y, int B, int N, int K,
@@ -239,7 +242,7 @@ int vte_desc_argmax_finish(vte_ctx* ctx, const vte_desc* lmhead, vte_desc** out)
 /* The work decomposition of a GEMV-family descriptor, spelled out.  It is part
  * of the submitted structure C_k: chosen from the shape by vte_gemv_default_plan,
  * or given by the caller, and frozen in the descriptor.
- *   batch_tile  batch rows the kernel is built for (1,2,4,8,16); a batch larger than the
+ *   batch_tile  batch rows the kernel is built for (1,2,4,8,16; 32 and 64: MFMA kinds); a batch larger than the
  *               tile runs as ceil(B / batch_tile) chunks that each re-read the weights
  *   rows        weight rows a wave streams at once (rows * batch_tile in {16,32,64})
  *   ksteps      512-element K steps per wave: a workgroup has
@@ -253,10 +256,16 @@ int vte_desc_argmax_finish(vte_ctx* ctx, const vte_desc* lmhead, vte_desc** out)
  *               tile, B <= batch_tile); rows = 16 x the tiles
  *               accumulated at once; ksteps = number of 128-element blocks per K chunk;
  *               the workgroup has min(max_waves, chunks) waves that take the chunks
- *               round-robin; prefetch = blocks the loads run ahead; groups as above
+ *               round-robin; prefetch = blocks the loads run ahead; groups as above.
+ *               VTE_GEMV_MFMA_ROWS (batch 33 to 64, one pass over the weights): batch_tile
+ *               = 64 (four column tiles per weight tile); the workgroup has max_waves (4 or
+ *               8) waves that split the row tiles, not K, and share X through LDS; rows =
+ *               16 x the tiles a wave accumulates at once; prefetch = 128-element K steps
+ *               the weight loads run ahead; ksteps = 1; groups = rounds of a workgroup.
+ *               An output is one accumulator chain along K, nothing crosses a wave.
  * Only combinations the library was built with are accepted.  The reduction tree
  * of an output depends on K and the plan alone — never on the device. */
-enum { VTE_GEMV_DOT2 = 0, VTE_GEMV_MFMA = 1 };
+enum { VTE_GEMV_DOT2 = 0, VTE_GEMV_MFMA = 1, VTE_GEMV_MFMA_ROWS = 2 };
 typedef struct vte_gemv_plan {
   int batch_tile, rows, ksteps, prefetch, max_waves, groups;
   int kind;

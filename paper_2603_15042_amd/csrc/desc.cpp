@@ -23,6 +23,7 @@ const void* vte_gemv_entry_b8(int, int, int, int, int, int);
 const void* vte_gemv_entry_b16(int, int, int, int, int, int);
 const void* vte_gemv_entry_mfma(int, int, int, int, int, int, int);
 const void* vte_gemv_entry_mfma32(int, int, int, int, int, int, int);
+const void* vte_gemv_entry_rows(int, int, int, int);
 const void* vte_gather_entry();
 const void* vte_argmax_finish_entry();
 const void* vte_gemm_entry();
@@ -130,6 +131,10 @@ int build_norm(vte_ctx* ctx, int kernel, bool layer, const void* x, const void* 
 }
 
 const void* gemv_entry(const vte_gemv_plan& p, int epi, int k_per_split) {
+  if (p.kind == VTE_GEMV_MFMA_ROWS) {
+    if (p.batch_tile != 64 || p.rows < 16 || p.rows % 16 != 0) return nullptr;
+    return vte_gemv_entry_rows(p.rows / 16, p.prefetch, p.max_waves, epi);
+  }
   if (p.kind == VTE_GEMV_MFMA) {
     if (p.ksteps < 1) return nullptr;
     const int kc = 128 * p.ksteps;
@@ -150,6 +155,7 @@ const void* gemv_entry(const vte_gemv_plan& p, int epi, int k_per_split) {
 int batch_tile(int B) { int bt = 1; while (bt < B) bt *= 2; return bt; }
 
 int plan_waves(const vte_gemv_plan& p, int k_per_split) {
+  if (p.kind == VTE_GEMV_MFMA_ROWS) return p.max_waves;  // every wave walks all of K for its own row tiles
   if (p.kind == VTE_GEMV_MFMA) {  // waves share the K chunks round-robin
     if (p.ksteps < 1) return 0;
     const int nchunks = (k_per_split + 128 * p.ksteps - 1) / (128 * p.ksteps);
@@ -164,10 +170,22 @@ int plan_waves(const vte_gemv_plan& p, int k_per_split) {
 // outputs = logical outputs per batch row (N, or N/2 with the SiLU epilogue);
 // kps = K / S.
 int plan_gemv(int B, int outputs, int kps, int epi, vte_gemv_plan* p) {
-  if (B < 1 || B > 32 || outputs < 1 || kps < 8) return VTE_EINVAL;
+  if (B < 1 || B > 64 || outputs < 1 || kps < 8) return VTE_EINVAL;
   const bool silu = epi == VTE_EPI_SILU_MUL;
   const int tile_out = silu ? 8 : 16;
   const int tiles = (outputs + tile_out - 1) / tile_out;
+  if (B > 32) {
+    // Batch 33 to 64: four column tiles per weight tile; the waves of a workgroup split the row
+    // tiles, not K, and share X through LDS.  More row tiles per workgroup mean fewer fetches of
+    // X; narrow outputs keep the workgroups small so that there are enough of them.
+    if (outputs < tile_out) return VTE_EINVAL;
+    int g = 2, ka = 2, wr = 8, rounds = 1;
+    if (tiles >= 4096) rounds = 2;
+    else if (tiles < 1024) { g = 1; wr = 4; }
+    p->batch_tile = 64; p->rows = 16 * g; p->ksteps = 1; p->prefetch = ka; p->max_waves = wr; p->groups = rounds;
+    p->kind = VTE_GEMV_MFMA_ROWS;
+    return VTE_OK;
+  }
   if (B > 16) {
     // Batch 17 to 32: two column tiles per weight tile, four waves (a wave holds X for 32 rows).
     // Fewer than one full tile of outputs is not offered at this batch.
@@ -243,7 +261,7 @@ int build_gemv(vte_ctx* ctx, const GemvBuild& g, vte_desc** out) {
   const bool lm = (g.epi_kernel == 2);
   if (!lm && !g.Y) { set_error("gemv: null output"); return VTE_EINVAL; }
   if (lm && (!g.tok || !g.ws)) { set_error("lmhead: tok and workspace are required"); return VTE_EINVAL; }
-  if (g.B < 1 || g.B > 32 || g.N < 1 || g.K < 8 || g.K % 8 != 0) { set_error("gemv: need 1 <= B <= 32, N >= 1, K % 8 == 0"); return VTE_EINVAL; }
+  if (g.B < 1 || g.B > 64 || g.N < 1 || g.K < 8 || g.K % 8 != 0) { set_error("gemv: need 1 <= B <= 64, N >= 1, K % 8 == 0"); return VTE_EINVAL; }
   if (g.S < 1 || g.S > 64 || g.K % (g.S * 8) != 0) { set_error("gemv: K must split into S chunks of a multiple of 8"); return VTE_EINVAL; }
   if (g.S > 1 && (!g.partials || !g.ws)) { set_error("split-K: partials and workspace are required"); return VTE_EINVAL; }
   if (g.epilogue == VTE_EPI_SILU_MUL && (g.N % 2 != 0)) { set_error("gemv: SiLU-mul needs an even N"); return VTE_EINVAL; }
@@ -252,15 +270,22 @@ int build_gemv(vte_ctx* ctx, const GemvBuild& g, vte_desc** out) {
   const int n_out = (g.epilogue == VTE_EPI_SILU_MUL) ? g.N / 2 : g.N;
   vte_gemv_plan p;
   if (g.plan) p = *g.plan;
-  else if (plan_gemv(g.B, n_out, g.K / g.S, g.epilogue, &p) != VTE_OK) { set_error("gemv: K / S must be at most 16384"); return VTE_EINVAL; }
+  else if (plan_gemv(g.B, n_out, g.K / g.S, g.epilogue, &p) != VTE_OK) { set_error("gemv: no plan for this shape (K / S at most 16384; a batch above 16 needs a full tile of outputs)"); return VTE_EINVAL; }
   const int kps = g.K / g.S;
   const int waves = plan_waves(p, kps);
+  const bool by_rows = p.kind == VTE_GEMV_MFMA_ROWS;
+  if (by_rows) {
+    if (g.S != 1) { set_error("gemv plan: the row-split MFMA kind has no split-K variant"); return VTE_EINVAL; }
+    if (p.batch_tile != 64 || g.B > 64) { set_error("gemv plan: the row-split MFMA kind has batch_tile 64"); return VTE_EINVAL; }
+    if (n_out < (g.epi_kernel == 1 ? 8 : 16)) { set_error("gemv plan: the MFMA kinds need at least one full tile of outputs (16, or 8 with SiLU-mul)"); return VTE_EINVAL; }
+  }
   const bool mfma = p.kind == VTE_GEMV_MFMA;
-  if (p.kind != VTE_GEMV_DOT2 && !mfma) { set_error("gemv plan: unknown kind"); return VTE_EINVAL; }
+  if (p.kind != VTE_GEMV_DOT2 && !mfma && !by_rows) { set_error("gemv plan: unknown kind"); return VTE_EINVAL; }
+  if (!by_rows && g.B > 32) { set_error("gemv plan: batch 33 to 64 needs the row-split MFMA kind with batch_tile 64"); return VTE_EINVAL; }
   if (mfma && n_out < (g.epi_kernel == 1 ? 8 : 16)) { set_error("gemv plan: the MFMA kind needs at least one full tile of outputs (16, or 8 with SiLU-mul)"); return VTE_EINVAL; }
   if (mfma && ((p.batch_tile != 16 && p.batch_tile != 32) || p.rows < 16 || p.rows % 16 != 0)) { set_error("gemv plan: the MFMA kind has batch_tile 16 or 32 and rows a multiple of 16"); return VTE_EINVAL; }
   if (mfma && g.B > p.batch_tile) { set_error("gemv plan: the MFMA kind takes the whole batch in one tile (B <= batch_tile)"); return VTE_EINVAL; }
-  if (!mfma && g.B > 16) { set_error("gemv plan: batch 17 to 32 needs the MFMA kind with batch_tile 32"); return VTE_EINVAL; }
+  if (!mfma && !by_rows && g.B > 16) { set_error("gemv plan: batch 17 to 32 needs the MFMA kind with batch_tile 32"); return VTE_EINVAL; }
   const int zchunks = (g.B + p.batch_tile - 1) / (p.batch_tile > 0 ? p.batch_tile : 1);
   if (p.batch_tile < 1 || p.groups < 1 || p.rows < 1 || p.ksteps < 1 || waves < 1 || waves > p.max_waves) {
     set_error("gemv plan: groups >= 1 and ceil(K/S/512/ksteps) <= max_waves are required"); return VTE_EINVAL;
@@ -268,7 +293,7 @@ int build_gemv(vte_ctx* ctx, const GemvBuild& g, vte_desc** out) {
   if (!gemv_entry(p, g.epi_kernel, kps)) { set_error("gemv plan: this combination is not built"); return VTE_EINVAL; }
   const int rout = (g.epi_kernel == 1) ? p.rows / 2 : p.rows;
   if (rout < 1) { set_error("gemv plan: the SiLU epilogue needs an even number of rows"); return VTE_EINVAL; }
-  const int per_block = rout * p.groups;
+  const int per_block = rout * p.groups * (by_rows ? p.max_waves : 1);
   const uint32_t gx = static_cast<uint32_t>((n_out + per_block - 1) / per_block);
   GemvArgs a{};
   a.W = static_cast<const uint16_t*>(g.W);
@@ -280,6 +305,7 @@ int build_gemv(vte_ctx* ctx, const GemvBuild& g, vte_desc** out) {
   a.B = g.B; a.N = g.N; a.K = g.K; a.n_out = n_out;
   a.ldx = g.ldx > 0 ? g.ldx : g.K;
   a.ldy = g.ldy > 0 ? g.ldy : n_out;
+  if (static_cast<uint64_t>(g.B - 1) * a.ldx + g.K >= (1ull << 30)) { set_error("gemv: X spans 2 GiB or more"); return VTE_EINVAL; }
   if (a.ldx < g.K || a.ldx % 8 != 0 || a.ldy < n_out) { set_error("gemv: need ldx >= K, ldx % 8 == 0, ldy >= outputs per row"); return VTE_EINVAL; }
   a.groups = p.groups; a.S = g.S; a.k_per_split = kps; a.bt = p.batch_tile * zchunks;
   const uint64_t shape = fnv1a(&a.B, sizeof(int) * 9);
@@ -343,7 +369,7 @@ int vte_gemv_default_plan(int B, int N, int K, int epilogue, int S, vte_gemv_pla
   const int n_out = (epilogue == VTE_EPI_SILU_MUL) ? N / 2 : N;
   if (S < 1 || K % S != 0) { set_error("gemv plan: S must divide K"); return VTE_EINVAL; }
   int rc = plan_gemv(B, n_out, K / S, epilogue, plan);
-  if (rc != VTE_OK) set_error("gemv plan: need 1 <= B <= 32 (from 17: at least one full tile of outputs), N >= 1, 8 <= K / S <= 16384");
+  if (rc != VTE_OK) set_error("gemv plan: need 1 <= B <= 64 (from 17: at least one full tile of outputs), N >= 1, 8 <= K / S <= 16384");
   return rc;
 }
 
@@ -392,9 +418,9 @@ int vte_lmhead_workspace_bytes(int B, int V, int K, size_t* bytes) {
   if (!bytes) { set_error("null bytes"); return VTE_EINVAL; }
   // sized for the finest decomposition there is: one workgroup per output row, batch tile 16
   (void)K;
-  if (B < 1 || B > 32 || V < 1) { set_error("lmhead workspace: bad argument"); return VTE_EINVAL; }
+  if (B < 1 || B > 64 || V < 1) { set_error("lmhead workspace: bad argument"); return VTE_EINVAL; }
   const size_t blocks = static_cast<size_t>(V) + 1;
-  *bytes = 4 * (1 + blocks + blocks * (B > 16 ? 32 : 16) * 2) + 256;
+  *bytes = 4 * (1 + blocks + blocks * (B > 32 ? 64 : (B > 16 ? 32 : 16)) * 2) + 256;
   return VTE_OK;
 }
 

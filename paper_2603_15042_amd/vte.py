@@ -21,7 +21,7 @@ VTE_PCTX_IDLE, VTE_PCTX_LEASED, VTE_PCTX_DRAINING, VTE_PCTX_RESERVED = 0, 1, 2, 
 VTE_EPI_NONE, VTE_EPI_SILU_MUL = 0, 1
 VTE_CLASS_LATENCY, VTE_CLASS_BEST_EFFORT = 0, 1
 VTE_POLICY_WIDEST, VTE_POLICY_QUEUE_STATE, VTE_POLICY_TPUT_PLAN, VTE_POLICY_TPOT_FIRST = 0, 1, 2, 3
-VTE_GEMV_DOT2, VTE_GEMV_MFMA = 0, 1
+VTE_GEMV_DOT2, VTE_GEMV_MFMA, VTE_GEMV_MFMA_ROWS = 0, 1, 2
 (VTE_K_RMSNORM, VTE_K_LAYERNORM, VTE_K_GEMV, VTE_K_LMHEAD, VTE_K_GATHER, VTE_K_GEMM, VTE_K_GEMV_SPLITK,
  VTE_K_LMHEAD_SPLITK, VTE_K_RMSNORM_RESHAPED, VTE_K_ARGMAX_FINISH, VTE_K_RMSNORM_GATHER,
  VTE_K_RMSNORM_GATHER_ARGMAX, VTE_K_MEMCPY, VTE_K_MEMSET, VTE_K_SOFTMAX_PROB) = range(1, 16)

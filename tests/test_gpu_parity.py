@@ -323,6 +323,98 @@ def test_lmhead_batch_17_to_32_tokens_and_logits(H, ctx, B, V, K):
     vte.vte_desc_destroy(d)
 
 
+@pytest.mark.parametrize("B,N,K", [(33, 4096, 4096), (64, 4096, 4096), (48, 513, 2048), (64, 37, 520), (40, 16, 8),
+                                   (64, 260, 14336), (50, 6144, 1000), (64, 33000, 256)])
+def test_gemv_batch_33_to_64_parity_width_and_position_invariance(H, ctx, B, N, K):
+    """Four column tiles per weight tile, the waves split the rows and share X through LDS: the parity
+    bar of the other kinds, the same bits on every pCtx, and a row's result does not depend on where in
+    the batch it stands or on the rows beside it."""
+    W, X = inputs.gemv_case(seed=2, B=B, N=N, K=K)
+    dW, dX, dY = H.to_dev(W), H.to_dev(X), H.dev_empty((B, N))
+    d = vte.vte_desc_gemv(ctx, dW, dX, dY, B, N, K)
+    assert vte.vte_gemv_default_plan(B, N, K, 0, 1).kind == vte.VTE_GEMV_MFMA_ROWS
+    res = run_everywhere(H, ctx, d, dY, [H.pctx_of_width(ctx, w) for w in (32, 64, 128, 224, 256)])
+    y = assert_all_equal(res).view(np.uint16)
+    bf16_close(y, oracle.gemv(W, X), "gemv B=%d" % B)
+    vte.vte_desc_destroy(d)
+    # the batch reversed, and a smaller batch made of its odd rows: every row keeps its bits
+    Xr = np.ascontiguousarray(X[::-1])
+    dXr = H.to_dev(Xr)
+    d = vte.vte_desc_gemv(ctx, dW, dXr, dY, B, N, K)
+    dY.fill_(0x7FC1)
+    H.run_on(ctx, d, H.pctx_of_width(ctx, 256))
+    assert np.array_equal(H.to_bits(dY)[::-1], y)
+    vte.vte_desc_destroy(d)
+    odd = np.arange(1, B, 2)
+    if len(odd) > 32:
+        dXo, dYo = H.to_dev(np.ascontiguousarray(X[odd])), H.dev_empty((len(odd), N))
+        d = vte.vte_desc_gemv(ctx, dW, dXo, dYo, len(odd), N, K)
+        H.run_on(ctx, d, H.pctx_of_width(ctx, 128))
+        assert np.array_equal(H.to_bits(dYo), y[odd])
+        vte.vte_desc_destroy(d)
+
+
+@pytest.mark.parametrize("plan", [(1, 2, 4, 1), (2, 2, 4, 2), (2, 2, 8, 3), (2, 1, 8, 1), (4, 1, 4, 2), (4, 1, 8, 1)])
+def test_gemv_batch_64_every_built_row_split_plan(H, ctx, plan):
+    """Every built combination (tiles per wave, K steps ahead, waves, rounds) on a ragged shape: the
+    plan changes who computes a row, not the chain of an output along K, so all give the same bits."""
+    g, ka, wr, rounds = plan
+    B, N, K = 57, 1000, 1160
+    W, X = inputs.gemv_case(seed=9, B=B, N=N, K=K)
+    dW, dX, dY = H.to_dev(W), H.to_dev(X), H.dev_empty((B, N))
+    p = vte.vte_gemv_default_plan(B, N, K, 0, 1)
+    p.rows, p.prefetch, p.max_waves, p.groups = 16 * g, ka, wr, rounds
+    d = vte.vte_desc_gemv_planned(ctx, dW, dX, dY, B, N, K, 0, p)
+    res = run_everywhere(H, ctx, d, dY, [H.pctx_of_width(ctx, w) for w in (32, 256)])
+    y = assert_all_equal(res).view(np.uint16)
+    bf16_close(y, oracle.gemv(W, X), "gemv rows plan %s" % (plan,))
+    vte.vte_desc_destroy(d)
+    d0 = vte.vte_desc_gemv(ctx, dW, dX, dY, B, N, K)
+    dY.fill_(0x7FC1)
+    H.run_on(ctx, d0, H.pctx_of_width(ctx, 256))
+    assert np.array_equal(H.to_bits(dY), y)
+    vte.vte_desc_destroy(d0)
+
+
+@pytest.mark.parametrize("B,F,K", [(64, 1000, 1024), (40, 14336, 4096), (33, 8, 264)])
+def test_gate_up_silu_batch_33_to_64(H, ctx, B, F, K):
+    W = inputs.normal_bf16(4, inputs.T_WGU, (2 * F, K), 0.0, 2.0 * K ** -0.5)
+    X = inputs.normal_bf16(4, inputs.T_XB, (B, K))
+    dW, dX, dY = H.to_dev(W), H.to_dev(X), H.dev_empty((B, F))
+    d = vte.vte_desc_gemv(ctx, dW, dX, dY, B, 2 * F, K, vte.VTE_EPI_SILU_MUL)
+    res = run_everywhere(H, ctx, d, dY, [H.pctx_of_width(ctx, w) for w in (32, 256)])
+    y = assert_all_equal(res).view(np.uint16)
+    bf16_close(y, oracle.gemv_silu_mul(W, X), "silu B=%d" % B)
+    vte.vte_desc_destroy(d)
+
+
+@pytest.mark.parametrize("B,V,K", [(64, 4099, 512), (37, 32064, 4096), (64, 16, 128)])
+def test_lmhead_batch_33_to_64_tokens_and_logits(H, ctx, B, V, K):
+    W = inputs.normal_bf16(8, inputs.T_WLM, (V, K), 0.0, 0.02)
+    X = inputs.normal_bf16(8, inputs.T_XB, (B, K))
+    dW, dX = H.to_dev(W), H.to_dev(X)
+    tok = torch.zeros(B, dtype=torch.int32, device="cuda")
+    lg = torch.zeros((B, V), dtype=torch.float32, device="cuda")
+    ws = H.dev_zeros_bytes(vte.vte_lmhead_workspace_bytes(B, V, K))
+    d = vte.vte_desc_lmhead_argmax(ctx, dW, dX, tok, lg, ws, B, V, K)
+    fin = vte.vte_desc_argmax_finish(ctx, d)
+    outs = []
+    for w in (256, 32):
+        tok.zero_()
+        torch.cuda.synchronize()
+        H.run_on(ctx, d, H.pctx_of_width(ctx, w))
+        H.run_on(ctx, fin, H.pctx_of_width(ctx, w))
+        outs.append((lg.cpu().numpy().copy(), tok.cpu().numpy().copy()))
+    assert np.array_equal(outs[0][0].view(np.uint32), outs[1][0].view(np.uint32)) and np.array_equal(outs[0][1], outs[1][1])
+    ref, t_ref, margin = oracle.lmhead_argmax(W, X)
+    eps_l = np.abs(outs[0][0] - ref).max()
+    assert eps_l < 1e-3
+    assert np.array_equal(outs[0][1], np.argmax(outs[0][0], axis=1))          # the token is the argmax of the GPU's own logits
+    assert all(outs[0][1][b] == t_ref[b] or margin[b] <= 2 * eps_l for b in range(B))
+    vte.vte_desc_destroy(fin)
+    vte.vte_desc_destroy(d)
+
+
 def test_k_tail_pieces_are_not_fetched_behind_the_last_row(H, ctx):
     """Down-projection shape split 8 ways: K / S = 1792 is no multiple of the 512-element chunk of the
     matrix-core kernel, and the weight tensor (56 x 2 MiB exactly) ends where its allocation ends.  The

@@ -371,7 +371,7 @@ def test_bad_shapes_are_rejected(ctx):
         lambda: vte.vte_desc_rmsnorm(ctx, A, A, A, 8, 1020, 1e-6),          # cols % 8
         lambda: vte.vte_desc_rmsnorm(ctx, A, A, A, 0, 1024, 1e-6),
         lambda: vte.vte_desc_rmsnorm(ctx, A + 2, A, A, 8, 1024, 1e-6),      # alignment
-        lambda: vte.vte_desc_gemv(ctx, A, A, A, 33, 64, 64, 0),             # B > 32
+        lambda: vte.vte_desc_gemv(ctx, A, A, A, 65, 64, 64, 0),             # B > 64
         lambda: vte.vte_desc_gemv(ctx, A, A, A, 17, 8, 64, 0),              # batch 17-32 needs a full tile of outputs
         lambda: vte.vte_desc_gemv(ctx, A, A, A, 1, 63, 64, vte.VTE_EPI_SILU_MUL),
         lambda: vte.vte_desc_gemv(ctx, A, A, A, 1, 64, 60, 0),
