@@ -179,12 +179,15 @@ int plan_gemv(int B, int outputs, int kps, int epi, vte_gemv_plan* p) {
     // tiles, not K, and share X through LDS.  More row tiles per workgroup mean fewer fetches of
     // X; narrow outputs keep the workgroups small so that there are enough of them.
     if (outputs < tile_out) return VTE_EINVAL;
-    int g = 2, ka = 2, wr = 8, rounds = 1;
-    if (tiles >= 4096) rounds = 2;
-    else if (tiles < 1024) { g = 1; wr = 4; }
-    p->batch_tile = 64; p->rows = 16 * g; p->ksteps = 1; p->prefetch = ka; p->max_waves = wr; p->groups = rounds;
-    p->kind = VTE_GEMV_MFMA_ROWS;
-    return VTE_OK;
+    if (tiles >= 1024) {
+      p->batch_tile = 64; p->rows = 16 * 4; p->ksteps = 1; p->prefetch = 1; p->max_waves = 8; p->groups = 1;
+      p->kind = VTE_GEMV_MFMA_ROWS;
+      return VTE_OK;
+    }
+    // Narrow outputs have too few row tiles to fill the device without splitting K: two chunks
+    // of 32 rows (grid z) through the K-split kernel; the second pass over weights of this size
+    // is served by the caches.
+    B = 32;
   }
   if (B > 16) {
     // Batch 17 to 32: two column tiles per weight tile, four waves (a wave holds X for 32 rows).
@@ -281,10 +284,13 @@ int build_gemv(vte_ctx* ctx, const GemvBuild& g, vte_desc** out) {
   }
   const bool mfma = p.kind == VTE_GEMV_MFMA;
   if (p.kind != VTE_GEMV_DOT2 && !mfma && !by_rows) { set_error("gemv plan: unknown kind"); return VTE_EINVAL; }
-  if (!by_rows && g.B > 32) { set_error("gemv plan: batch 33 to 64 needs the row-split MFMA kind with batch_tile 64"); return VTE_EINVAL; }
+  if (g.B > 32 && !by_rows && !(mfma && p.batch_tile == 32 && g.S == 1)) {
+    set_error("gemv plan: batch 33 to 64 needs the row-split MFMA kind (batch_tile 64) or the MFMA kind with batch_tile 32 (two chunks), S = 1");
+    return VTE_EINVAL;
+  }
   if (mfma && n_out < (g.epi_kernel == 1 ? 8 : 16)) { set_error("gemv plan: the MFMA kind needs at least one full tile of outputs (16, or 8 with SiLU-mul)"); return VTE_EINVAL; }
   if (mfma && ((p.batch_tile != 16 && p.batch_tile != 32) || p.rows < 16 || p.rows % 16 != 0)) { set_error("gemv plan: the MFMA kind has batch_tile 16 or 32 and rows a multiple of 16"); return VTE_EINVAL; }
-  if (mfma && g.B > p.batch_tile) { set_error("gemv plan: the MFMA kind takes the whole batch in one tile (B <= batch_tile)"); return VTE_EINVAL; }
+  if (mfma && g.B > p.batch_tile && p.batch_tile != 32) { set_error("gemv plan: the MFMA kind with batch_tile 16 takes the whole batch in one tile"); return VTE_EINVAL; }
   if (!mfma && !by_rows && g.B > 16) { set_error("gemv plan: batch 17 to 32 needs the MFMA kind with batch_tile 32"); return VTE_EINVAL; }
   const int zchunks = (g.B + p.batch_tile - 1) / (p.batch_tile > 0 ? p.batch_tile : 1);
   if (p.batch_tile < 1 || p.groups < 1 || p.rows < 1 || p.ksteps < 1 || waves < 1 || waves > p.max_waves) {

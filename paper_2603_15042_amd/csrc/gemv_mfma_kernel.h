@@ -1,5 +1,6 @@
 // Skinny-batch GEMV on the matrix cores: Y[b, n] = sum_k W[n, k] X[b, k] for up to
-// 16 CT batch rows (CT = 1 or 2 column tiles), 16 weight rows per v_mfma_f32_16x16x32_bf16 tile
+// 16 CT batch rows per workgroup (CT = 1 or 2 column tiles; a larger batch runs as chunks of
+// 16 CT rows in grid z, each reading the weights), 16 weight rows per v_mfma_f32_16x16x32_bf16 tile
 // (operator family: Sec. 1 "GEMV", Sec. 2.3; LM-head logits and greedy token:
 // Sec. 7.1 / 7.2 of the paper).
 //
@@ -56,6 +57,7 @@ __global__ __launch_bounds__(MAXW * 64) void gemv_mfma_kernel(const GemvArgs a) 
   const int c = lane & 15, q = lane >> 4;    // MFMA operand coordinates
   const int lr = lane >> 4, lp = lane & 15;  // load coordinates: row within a 4-row group, 16-byte piece of 256 B
   const int split = blockIdx.y;
+  const int row0 = blockIdx.z * 16 * CT;  // first batch row of this workgroup (a batch above 16 CT runs as chunks in z)
   const int k_begin = split * a.k_per_split;
   const int k_end = k_begin + a.k_per_split;
   const int nchunks = (a.k_per_split + KC - 1) / KC;
@@ -87,10 +89,10 @@ __global__ __launch_bounds__(MAXW * 64) void gemv_mfma_kernel(const GemvArgs a) 
   // X: rows past B lie outside the resource and read as zero
   const __amdgpu_buffer_rsrc_t rs_x = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<uint16_t*>(a.X), 0, static_cast<int>((static_cast<uint32_t>(a.B - 1) * a.ldx + a.K) * 2u), kRsrcFlags);
-  uint32_t voff_x[CT];  // column tile ct holds batch rows 16 ct + c
+  uint32_t voff_x[CT];  // column tile ct holds batch rows row0 + 16 ct + c
 #pragma unroll
   for (int ct = 0; ct < CT; ++ct)
-    voff_x[ct] = 16 * ct + c < a.B ? (static_cast<uint32_t>(16 * ct + c) * a.ldx + q * 8) * 2u : 0x80000000u;
+    voff_x[ct] = row0 + 16 * ct + c < a.B ? (static_cast<uint32_t>(row0 + 16 * ct + c) * a.ldx + q * 8) * 2u : 0x80000000u;
 
   f32x4_t acc[G][CT];
   const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
@@ -127,7 +129,8 @@ __global__ __launch_bounds__(MAXW * 64) void gemv_mfma_kernel(const GemvArgs a) 
   int best_i[CT];
 #pragma unroll
   for (int ct = 0; ct < CT; ++ct) { best_v[ct] = -INFINITY; best_i[ct] = INT_MAX; }
-  auto epilogue = [&](int rd, int g, int col, int qq, const float(&s)[4], const float(&u)[4]) {
+  auto epilogue = [&](int rd, int g, int lcol, int qq, const float(&s)[4], const float(&u)[4]) {
+    const int col = row0 + lcol;
     if (col >= a.B) return;
     const int first = tile_first(rd, g);  // rows below belong to the previous tile
     const int out0 = tile_start(rd, g) + 4 * qq;
@@ -144,7 +147,7 @@ __global__ __launch_bounds__(MAXW * 64) void gemv_mfma_kernel(const GemvArgs a) 
           if (a.logits) a.logits[static_cast<size_t>(col) * a.N + n] = s[v];
 #pragma unroll
           for (int ct = 0; ct < CT; ++ct)  // col / 16 selects the candidate; written so that the arrays stay in registers
-            if (ct == (col >> 4) && better(s[v], n, best_v[ct], best_i[ct])) { best_v[ct] = s[v]; best_i[ct] = n; }
+            if (ct == (lcol >> 4) && better(s[v], n, best_v[ct], best_i[ct])) { best_v[ct] = s[v]; best_i[ct] = n; }
         }
       }
     }
@@ -235,10 +238,10 @@ __global__ __launch_bounds__(MAXW * 64) void gemv_mfma_kernel(const GemvArgs a) 
       }
       if (a.S == 1) {
         epilogue(rd, g, col, qq, s, u);
-      } else if (col < a.B) {
+      } else if (row0 + col < a.B) {
         const int first = tile_first(rd, g);
         const int out0 = tile_start(rd, g) + 4 * qq;
-        float* pp = a.partials + (static_cast<size_t>(split) * a.bt + col) * a.N;
+        float* pp = a.partials + (static_cast<size_t>(split) * a.bt + row0 + col) * a.N;
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
           const int n = out0 + v;
@@ -259,7 +262,7 @@ __global__ __launch_bounds__(MAXW * 64) void gemv_mfma_kernel(const GemvArgs a) 
     __threadfence();
     __syncthreads();
     if (threadIdx.x == 0) {
-      const uint32_t t = atomicAdd(&a.ws[1 + blockIdx.x], 1u);
+      const uint32_t t = atomicAdd(&a.ws[1 + blockIdx.z * gridDim.x + blockIdx.x], 1u);
       s_last = (t == static_cast<uint32_t>(a.S) - 1u);
     }
     __syncthreads();
@@ -267,7 +270,7 @@ __global__ __launch_bounds__(MAXW * 64) void gemv_mfma_kernel(const GemvArgs a) 
     __threadfence();
     for (int f = threadIdx.x; f < a.groups * G * CT * 64; f += blockDim.x) {
       const int rd = f / (G * CT * 64), gc = (f >> 6) % (G * CT), g = gc / CT, ln = f & 63, col = 16 * (gc % CT) + (ln & 15), qq = ln >> 4;
-      if (qq >= QOUT || col >= a.B) continue;
+      if (qq >= QOUT || row0 + col >= a.B) continue;
       const int first = tile_first(rd, g);
       const int out0 = tile_start(rd, g) + 4 * qq;
       float s[4] = {0.f, 0.f, 0.f, 0.f}, u[4] = {0.f, 0.f, 0.f, 0.f};
@@ -277,14 +280,14 @@ __global__ __launch_bounds__(MAXW * 64) void gemv_mfma_kernel(const GemvArgs a) 
         const bool live = n >= first && ((EPI == EPI_SILU) ? n < a.n_out : n < a.N);
         if (!live) continue;
         for (int sp = 0; sp < a.S; ++sp) {  // chunk order
-          const float* pp = a.partials + (static_cast<size_t>(sp) * a.bt + col) * a.N;
+          const float* pp = a.partials + (static_cast<size_t>(sp) * a.bt + row0 + col) * a.N;
           s[v] += __builtin_nontemporal_load(pp + n);
           if constexpr (EPI == EPI_SILU) u[v] += __builtin_nontemporal_load(pp + a.n_out + n);
         }
       }
       epilogue(rd, g, col, qq, s, u);
     }
-    if (threadIdx.x == 0) a.ws[1 + blockIdx.x] = 0u;  // ready for the next launch
+    if (threadIdx.x == 0) a.ws[1 + blockIdx.z * gridDim.x + blockIdx.x] = 0u;  // ready for the next launch
   }
 
   // ---- LM head: workgroup argmax -> one (value, index) candidate per batch row ----
@@ -301,15 +304,15 @@ __global__ __launch_bounds__(MAXW * 64) void gemv_mfma_kernel(const GemvArgs a) 
       if (lane < 16) { s_bv[wave][16 * ct + lane] = best_v[ct]; s_bi[wave][16 * ct + lane] = best_i[ct]; }
     }
     __syncthreads();
-    uint32_t* cand_v = a.ws + 1 + gridDim.x;
+    uint32_t* cand_v = a.ws + 1 + gridDim.x * gridDim.z;
     uint32_t* cand_i = cand_v + static_cast<size_t>(a.bt) * gridDim.x;
-    if (threadIdx.x < 16 * CT && static_cast<int>(threadIdx.x) < a.B) {
+    if (threadIdx.x < 16 * CT && row0 + static_cast<int>(threadIdx.x) < a.B) {
       float bv = s_bv[0][threadIdx.x];
       int bi = s_bi[0][threadIdx.x];
       for (int w = 1; w < nw; ++w)
         if (better(s_bv[w][threadIdx.x], s_bi[w][threadIdx.x], bv, bi)) { bv = s_bv[w][threadIdx.x]; bi = s_bi[w][threadIdx.x]; }
-      cand_v[static_cast<size_t>(threadIdx.x) * gridDim.x + blockIdx.x] = __float_as_uint(bv);
-      cand_i[static_cast<size_t>(threadIdx.x) * gridDim.x + blockIdx.x] = static_cast<uint32_t>(bi);
+      cand_v[static_cast<size_t>(row0 + threadIdx.x) * gridDim.x + blockIdx.x] = __float_as_uint(bv);
+      cand_i[static_cast<size_t>(row0 + threadIdx.x) * gridDim.x + blockIdx.x] = static_cast<uint32_t>(bi);
     }
   }
 }

@@ -323,32 +323,46 @@ def test_lmhead_batch_17_to_32_tokens_and_logits(H, ctx, B, V, K):
     vte.vte_desc_destroy(d)
 
 
+def rows_plan(g=2, ka=2, wr=8, rounds=1):
+    p = vte.vte_gemv_plan()
+    p.batch_tile, p.rows, p.ksteps, p.prefetch, p.max_waves, p.groups, p.kind = 64, 16 * g, 1, ka, wr, rounds, vte.VTE_GEMV_MFMA_ROWS
+    return p
+
+
+@pytest.mark.parametrize("kind", ["default", "rows"])
 @pytest.mark.parametrize("B,N,K", [(33, 4096, 4096), (64, 4096, 4096), (48, 513, 2048), (64, 37, 520), (40, 16, 8),
                                    (64, 260, 14336), (50, 6144, 1000), (64, 33000, 256)])
-def test_gemv_batch_33_to_64_parity_width_and_position_invariance(H, ctx, B, N, K):
-    """Four column tiles per weight tile, the waves split the rows and share X through LDS: the parity
-    bar of the other kinds, the same bits on every pCtx, and a row's result does not depend on where in
-    the batch it stands or on the rows beside it."""
+def test_gemv_batch_33_to_64_parity_width_and_position_invariance(H, ctx, B, N, K, kind):
+    """Batch 33 to 64 in one launch.  Wide outputs: four column tiles per weight tile, the waves split
+    the rows and share X through LDS (one pass over the weights); narrow outputs: two chunks of 32
+    rows through the K-split kernel.  Both: the parity bar of the other kinds, the same bits on every
+    pCtx, and a row's result does not depend on where in the batch it stands or on the rows beside it."""
     W, X = inputs.gemv_case(seed=2, B=B, N=N, K=K)
     dW, dX, dY = H.to_dev(W), H.to_dev(X), H.dev_empty((B, N))
-    d = vte.vte_desc_gemv(ctx, dW, dX, dY, B, N, K)
-    assert vte.vte_gemv_default_plan(B, N, K, 0, 1).kind == vte.VTE_GEMV_MFMA_ROWS
+
+    def make(x, y, b):
+        if kind == "rows":
+            return vte.vte_desc_gemv_planned(ctx, dW, x, y, b, N, K, 0, rows_plan())
+        return vte.vte_desc_gemv(ctx, dW, x, y, b, N, K)
+
+    want = vte.VTE_GEMV_MFMA_ROWS if N >= 16384 else vte.VTE_GEMV_MFMA
+    assert vte.vte_gemv_default_plan(B, N, K, 0, 1).kind == want
+    d = make(dX, dY, B)
     res = run_everywhere(H, ctx, d, dY, [H.pctx_of_width(ctx, w) for w in (32, 64, 128, 224, 256)])
     y = assert_all_equal(res).view(np.uint16)
     bf16_close(y, oracle.gemv(W, X), "gemv B=%d" % B)
     vte.vte_desc_destroy(d)
     # the batch reversed, and a smaller batch made of its odd rows: every row keeps its bits
-    Xr = np.ascontiguousarray(X[::-1])
-    dXr = H.to_dev(Xr)
-    d = vte.vte_desc_gemv(ctx, dW, dXr, dY, B, N, K)
+    dXr = H.to_dev(np.ascontiguousarray(X[::-1]))
+    d = make(dXr, dY, B)
     dY.fill_(0x7FC1)
     H.run_on(ctx, d, H.pctx_of_width(ctx, 256))
     assert np.array_equal(H.to_bits(dY)[::-1], y)
     vte.vte_desc_destroy(d)
     odd = np.arange(1, B, 2)
-    if len(odd) > 32:
+    if len(odd) > 32 or kind == "rows":
         dXo, dYo = H.to_dev(np.ascontiguousarray(X[odd])), H.dev_empty((len(odd), N))
-        d = vte.vte_desc_gemv(ctx, dW, dXo, dYo, len(odd), N, K)
+        d = make(dXo, dYo, len(odd))
         H.run_on(ctx, d, H.pctx_of_width(ctx, 128))
         assert np.array_equal(H.to_bits(dYo), y[odd])
         vte.vte_desc_destroy(d)
@@ -362,41 +376,47 @@ def test_gemv_batch_64_every_built_row_split_plan(H, ctx, plan):
     B, N, K = 57, 1000, 1160
     W, X = inputs.gemv_case(seed=9, B=B, N=N, K=K)
     dW, dX, dY = H.to_dev(W), H.to_dev(X), H.dev_empty((B, N))
-    p = vte.vte_gemv_default_plan(B, N, K, 0, 1)
-    p.rows, p.prefetch, p.max_waves, p.groups = 16 * g, ka, wr, rounds
-    d = vte.vte_desc_gemv_planned(ctx, dW, dX, dY, B, N, K, 0, p)
+    d = vte.vte_desc_gemv_planned(ctx, dW, dX, dY, B, N, K, 0, rows_plan(g, ka, wr, rounds))
     res = run_everywhere(H, ctx, d, dY, [H.pctx_of_width(ctx, w) for w in (32, 256)])
     y = assert_all_equal(res).view(np.uint16)
     bf16_close(y, oracle.gemv(W, X), "gemv rows plan %s" % (plan,))
     vte.vte_desc_destroy(d)
-    d0 = vte.vte_desc_gemv(ctx, dW, dX, dY, B, N, K)
+    d0 = vte.vte_desc_gemv_planned(ctx, dW, dX, dY, B, N, K, 0, rows_plan())
     dY.fill_(0x7FC1)
     H.run_on(ctx, d0, H.pctx_of_width(ctx, 256))
     assert np.array_equal(H.to_bits(dY), y)
     vte.vte_desc_destroy(d0)
 
 
+@pytest.mark.parametrize("kind", ["default", "rows"])
 @pytest.mark.parametrize("B,F,K", [(64, 1000, 1024), (40, 14336, 4096), (33, 8, 264)])
-def test_gate_up_silu_batch_33_to_64(H, ctx, B, F, K):
+def test_gate_up_silu_batch_33_to_64(H, ctx, B, F, K, kind):
     W = inputs.normal_bf16(4, inputs.T_WGU, (2 * F, K), 0.0, 2.0 * K ** -0.5)
     X = inputs.normal_bf16(4, inputs.T_XB, (B, K))
     dW, dX, dY = H.to_dev(W), H.to_dev(X), H.dev_empty((B, F))
-    d = vte.vte_desc_gemv(ctx, dW, dX, dY, B, 2 * F, K, vte.VTE_EPI_SILU_MUL)
+    if kind == "rows":
+        d = vte.vte_desc_gemv_planned(ctx, dW, dX, dY, B, 2 * F, K, vte.VTE_EPI_SILU_MUL, rows_plan(4, 1, 4, 2))
+    else:
+        d = vte.vte_desc_gemv(ctx, dW, dX, dY, B, 2 * F, K, vte.VTE_EPI_SILU_MUL)
     res = run_everywhere(H, ctx, d, dY, [H.pctx_of_width(ctx, w) for w in (32, 256)])
     y = assert_all_equal(res).view(np.uint16)
     bf16_close(y, oracle.gemv_silu_mul(W, X), "silu B=%d" % B)
     vte.vte_desc_destroy(d)
 
 
+@pytest.mark.parametrize("kind", ["default", "rows"])
 @pytest.mark.parametrize("B,V,K", [(64, 4099, 512), (37, 32064, 4096), (64, 16, 128)])
-def test_lmhead_batch_33_to_64_tokens_and_logits(H, ctx, B, V, K):
+def test_lmhead_batch_33_to_64_tokens_and_logits(H, ctx, B, V, K, kind):
     W = inputs.normal_bf16(8, inputs.T_WLM, (V, K), 0.0, 0.02)
     X = inputs.normal_bf16(8, inputs.T_XB, (B, K))
     dW, dX = H.to_dev(W), H.to_dev(X)
     tok = torch.zeros(B, dtype=torch.int32, device="cuda")
     lg = torch.zeros((B, V), dtype=torch.float32, device="cuda")
     ws = H.dev_zeros_bytes(vte.vte_lmhead_workspace_bytes(B, V, K))
-    d = vte.vte_desc_lmhead_argmax(ctx, dW, dX, tok, lg, ws, B, V, K)
+    if kind == "rows":
+        d = vte.vte_desc_lmhead_argmax_planned(ctx, dW, dX, tok, lg, ws, B, V, K, rows_plan(2, 2, 8, 2))
+    else:
+        d = vte.vte_desc_lmhead_argmax(ctx, dW, dX, tok, lg, ws, B, V, K)
     fin = vte.vte_desc_argmax_finish(ctx, d)
     outs = []
     for w in (256, 32):
