@@ -6,11 +6,11 @@ production traces; this is a seeded synthetic stand-in with the stated distribut
 
 Requests arrive by a Poisson process, carry a prompt length (it only sizes the host-to-device copy
 that precedes the first decode step), an output length and a start token.  Up to 64 run at once,
-in chunks of 16 rows (four of them; or two of 32 with --chunk 32, which reads the weights half as
-often), each stepping its own copy of the chain's activations over shared weights; the chunks are
+in chunks of 16 rows (four of them; or two of 32 with --chunk 32, one of 64 with --chunk 64: the
+weights are read once per launch whatever its rows), each stepping its own copy of the chain's activations over shared weights; the chunks are
 dealt to two virtual streams and take turns on theirs.  Five tenants would be one too many:
 the device dispatches from four pipes and queues on one pipe run one kernel at a time, so the sweep
-keeps to two decode streams and the co-tenant.  Every launch is built at batch 16, so a row's arithmetic does not
+keeps to two decode streams and the co-tenant.  Every launch is built at the chunk size, so a row's arithmetic does not
 depend on what shares the launch, and a request's token stream is a function of its start token
 alone: every observed transition token -> next token is checked against the same row computed alone
 on the full-width pCtx with nothing else running.
@@ -56,8 +56,9 @@ def layer_weights(seed, shp, layers):
 
 class Server:
     def __init__(self, layers, small=False, lookahead=32, chunk=16):
-        assert chunk in (16, 32)
+        assert chunk in (16, 32, 64)
         self.chunk, self.nchunks = chunk, MAX_ROWS // chunk
+        self.nstreams = min(STREAMS, self.nchunks)
         self.shp = inputs.DecodeShapes(D=512, Nqkv=768, F=1792, V=4099) if small else inputs.DecodeShapes()
         cfg = vte.vte_pool_cfg_default()
         cfg.mode = vte.VTE_MODE_PIPELINED
@@ -74,7 +75,7 @@ class Server:
         gB = H.to_dev(inputs.normal_bf16(0, inputs.T_GEMM_B, (M, M)))
         self.gbuf = (gA, gB, H.dev_empty((M, M)))
         self.gemm = vte.vte_desc_gemm(ctx, gA, gB, self.gbuf[2], M, M, M)
-        self.vs = [vte.vte_vstream_create(ctx, vte.VTE_CLASS_LATENCY) for _ in range(STREAMS)]
+        self.vs = [vte.vte_vstream_create(ctx, vte.VTE_CLASS_LATENCY) for _ in range(self.nstreams)]
         self.be = vte.vte_vstream_create(ctx, vte.VTE_CLASS_BEST_EFFORT)
         self.root = vte.vte_pool_find(ctx, vte.VTE_PCTX_NODE, 256)
         # torch work in the serving loop stays off the null stream, which would order itself against
@@ -132,14 +133,16 @@ class Server:
     # -- one run of a trace under a policy ---------------------------------------------------------
     def run(self, trace, seconds, mode, tpot_target=0.050, with_gemm=True):
         """mode: 'solo' (no co-tenant, widest) | 'fixed' (decode streams pinned to the quarters of one half, GEMM to the other half)
-        | 'tput' (Throughput-Oriented plan) | 'tpot' (TPOT-First).  Chunk c runs on stream c % STREAMS."""
+        | 'tput' (Throughput-Oriented plan) | 'tpot' (TPOT-First).  Chunk c runs on stream c % (number of streams)."""
         ctx = self.ctx
         CHUNK, MAX_CHUNKS = self.chunk, self.nchunks
         vte.vte_device_sync(ctx)
         vte.vte_stats_reset(ctx)
-        quarters = [vte.vte_pool_find(ctx, vte.VTE_PCTX_NODE, 64, i) for i in range(STREAMS)]
+        # fixed split: the decode streams share one half (its quarters; the whole half when there is one stream)
+        quarters = ([vte.vte_pool_find(ctx, vte.VTE_PCTX_NODE, 64, i) for i in range(STREAMS)] if self.nstreams > 1
+                    else [vte.vte_pool_find(ctx, vte.VTE_PCTX_NODE, 128, 0)])
         half1 = vte.vte_pool_find(ctx, vte.VTE_PCTX_NODE, 128, 1)
-        per_stream = MAX_CHUNKS // STREAMS
+        per_stream = MAX_CHUNKS // self.nstreams
         for i, vs in enumerate(self.vs):
             # a stream's "token" is one chunk step; its chunks alternate, so a request sees per_stream of them per token
             vte.vte_vstream_set_tpot(vs, tpot_target / per_stream if mode == "tpot" else 0.0, self.chains[i].ops_per_step)
@@ -208,7 +211,7 @@ class Server:
                 if new:
                     self.write_tokens(c)
                 if any(ri >= 0 for ri in slots[c]):
-                    tail[c] = ch.submit_step(self.vs[c % STREAMS])
+                    tail[c] = ch.submit_step(self.vs[c % self.nstreams])
                     busy[c] = True
             time.sleep(0.00005)
         elapsed = time.perf_counter() - t0
@@ -305,7 +308,7 @@ def main(argv=None):
     ap.add_argument("--layers", type=int, default=32)
     ap.add_argument("--small", action="store_true")
     ap.add_argument("--modes", default="fixed,tput,tpot")
-    ap.add_argument("--chunk", type=int, default=16, help="rows per launch: 16, or 32 (two column tiles per weight tile)")
+    ap.add_argument("--chunk", type=int, default=16, help="rows per launch: 16, 32 or 64")
     ap.add_argument("--out", default=None)
     a = ap.parse_args(argv)
     res = sweep([float(x) for x in a.rates.split(",")], a.seconds, a.layers, a.small, tuple(a.modes.split(",")), chunk=a.chunk)

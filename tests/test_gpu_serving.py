@@ -9,7 +9,7 @@ from paper_2603_15042_amd import harness as H, serving, vte
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("chunk", [16, 32])
+@pytest.mark.parametrize("chunk", [16, 32, 64])
 def test_row_result_is_independent_of_batch_neighbours_and_position(chunk):
     srv = serving.Server(layers=2, small=True, chunk=chunk)
     try:
@@ -25,7 +25,7 @@ def test_row_result_is_independent_of_batch_neighbours_and_position(chunk):
         srv.close()
 
 
-@pytest.mark.parametrize("chunk", [16, 32])
+@pytest.mark.parametrize("chunk", [16, 32, 64])
 def test_serving_policies_reproduce_solo_tokens(chunk):
     out = serving.sweep([60.0], 1.0, layers=2, small=True, modes=("fixed", "tput", "tpot"), chunk=chunk)
     res = out["rates"]["60.0"]
