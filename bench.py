@@ -210,7 +210,7 @@ def main():
     # ---- other batch sizes of the same chain, full width (outside the timed region) -------------
     if not a.no_width_sweep:
         per_batch = {}
-        for b2 in (1, 4, 16, 32):
+        for b2 in (1, 4, 16, 32, 64):
             c2 = H.DecodeChain(ctx, wd, shp, b2, feedback=True, fused_gather=True, fused_argmax=True)
             c2.set_tokens(inputs.tokens(0, inputs.T_TOK0, b2, shp.V))
             n = max(50, a.steps // 4)
