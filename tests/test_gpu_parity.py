@@ -742,47 +742,47 @@ def test_chain_teacher_forced_per_operator(H, ctx, small_chain, B):
 
 
 def test_full_size_chain_in_the_benchmark_configuration(H, ctx):
-    """Llama-8B shapes (V = 128256), batch 8, the launch configuration bench.py times (step boundary
-    fused, pipelined virtual stream): every operator of a step against the oracle on the GPU's own
-    inputs, the greedy tokens of three free-running steps, and the same tokens and bits from the
-    unfused chain launched explicitly on a 64-CU pCtx."""
+    """Llama-8B shapes (V = 128256), batch 8 and batch 64, the launch configuration bench.py times
+    (step boundary fused, pipelined virtual stream): every operator of a step against the oracle on
+    the GPU's own inputs, the greedy tokens of three free-running steps, and the same tokens and bits
+    from the unfused chain launched explicitly on a 64-CU pCtx."""
     shp = inputs.DecodeShapes()
     w = inputs.decode_weights(0, shp)
     wd = H.upload_weights(w)
-    B = 8
-    tok0 = inputs.tokens(0, inputs.T_TOK0, B, shp.V)
     p64 = H.pctx_of_width(ctx, 64)
-    plain = H.DecodeChain(ctx, wd, shp, B, want_logits=True)
-    plain.set_tokens(tok0)
-    plain.run_step_on(p64)
-    s = plain.snapshot()
-    assert np.array_equal(s["h0"], w["E"][tok0])
-    bf16_close(s["n"], oracle.rmsnorm(s["h0"], w["gamma"]), "n")
-    bf16_close(s["qkv"], oracle.gemv(w["Wqkv"], s["n"]), "qkv")
-    bf16_close(s["o"], oracle.gemv(w["Wo"], np.ascontiguousarray(s["qkv"][:, :shp.D])), "o")
-    bf16_close(s["act"], oracle.gemv_silu_mul(w["Wgu"], s["o"]), "act")
-    bf16_close(s["d"], oracle.gemv(w["Wd"], s["act"]), "d")
-    lg, t_ref, margin = oracle.lmhead_argmax(w["Wlm"], s["d"])
-    eps_logit = np.abs(s["logits"].astype(np.float64) - lg).max()
-    assert eps_logit < 1e-3
-    assert all(s["next"][b] == t_ref[b] or margin[b] <= 2 * eps_logit for b in range(B))
-    # three free-running steps: unfused, explicit launches vs the benchmark's fused, policy-bound form
-    toks_plain = []
-    t = tok0
-    for _ in range(3):
-        plain.set_tokens(t)
+    for B in (8, 64):
+        tok0 = inputs.tokens(0, inputs.T_TOK0, B, shp.V)
+        plain = H.DecodeChain(ctx, wd, shp, B, want_logits=True)
+        plain.set_tokens(tok0)
         plain.run_step_on(p64)
-        t = plain.snapshot()["next"]
-        toks_plain.append(t.copy())
-    fused = H.DecodeChain(ctx, wd, shp, B, feedback=True, fused_gather=True, fused_argmax=True)
-    fused.set_tokens(tok0)
-    vs = vte.vte_vstream_create(ctx)
-    vte.vte_token_wait(ctx, fused.submit_burst(vs, 3))
-    assert np.array_equal(fused.tok.cpu().numpy(), toks_plain[-1])
-    assert np.array_equal(H.to_bits(fused.d), plain.snapshot()["d"])          # same bits in the last step's activations
-    vte.vte_vstream_destroy(vs)
-    plain.close()
-    fused.close()
+        s = plain.snapshot()
+        assert np.array_equal(s["h0"], w["E"][tok0])
+        bf16_close(s["n"], oracle.rmsnorm(s["h0"], w["gamma"]), "n")
+        bf16_close(s["qkv"], oracle.gemv(w["Wqkv"], s["n"]), "qkv")
+        bf16_close(s["o"], oracle.gemv(w["Wo"], np.ascontiguousarray(s["qkv"][:, :shp.D])), "o")
+        bf16_close(s["act"], oracle.gemv_silu_mul(w["Wgu"], s["o"]), "act")
+        bf16_close(s["d"], oracle.gemv(w["Wd"], s["act"]), "d")
+        lg, t_ref, margin = oracle.lmhead_argmax(w["Wlm"], s["d"])
+        eps_logit = np.abs(s["logits"].astype(np.float64) - lg).max()
+        assert eps_logit < 1e-3
+        assert all(s["next"][b] == t_ref[b] or margin[b] <= 2 * eps_logit for b in range(B))
+        # three free-running steps: unfused, explicit launches vs the benchmark's fused, policy-bound form
+        toks_plain = []
+        t = tok0
+        for _ in range(3):
+            plain.set_tokens(t)
+            plain.run_step_on(p64)
+            t = plain.snapshot()["next"]
+            toks_plain.append(t.copy())
+        fused = H.DecodeChain(ctx, wd, shp, B, feedback=True, fused_gather=True, fused_argmax=True)
+        fused.set_tokens(tok0)
+        vs = vte.vte_vstream_create(ctx)
+        vte.vte_token_wait(ctx, fused.submit_burst(vs, 3))
+        assert np.array_equal(fused.tok.cpu().numpy(), toks_plain[-1])
+        assert np.array_equal(H.to_bits(fused.d), plain.snapshot()["d"])          # same bits in the last step's activations
+        vte.vte_vstream_destroy(vs)
+        plain.close()
+        fused.close()
     del wd
     torch.cuda.empty_cache()
 
