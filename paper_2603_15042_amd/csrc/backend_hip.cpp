@@ -97,23 +97,15 @@ class HipBackend : public Backend {
       return code;
     };
     if (rc != VTE_OK) return fail(rc);
-    if (timed) {
-      // Both events ride on the kernel's own dispatch: they take its begin and end
-      // timestamps, and no marker is queued in front of or behind it (a recorded
-      // event costs the stream about 5 us of idle time on either side).
-      void* params[1] = {const_cast<unsigned char*>(d->args)};
-      SlowCall sc("hipExtLaunchKernel");
-      hipError_t e = hipExtLaunchKernel(d->entry, dim3(d->grid[0], d->grid[1], d->grid[2]),
-                                        dim3(d->block[0], d->block[1], d->block[2]), params, d->lds_bytes, s,
-                                        c->start, c->done, 0);
-      if (e != hipSuccess) { set_error(std::string("hipExtLaunchKernel: ") + hipGetErrorString(e), (int)e); return fail(VTE_EHIP); }
-      *completion = c;
-      return VTE_OK;
-    }
-    rc = launch(d, s);
-    if (rc != VTE_OK) return fail(rc);
-    hipError_t e = hipEventRecord(c->done, s);
-    if (e != hipSuccess) { set_error(std::string("hipEventRecord: ") + hipGetErrorString(e), (int)e); return fail(VTE_EHIP); }
+    // The events ride on the kernel's own dispatch: a timed launch takes its begin and
+    // end timestamps from it, and no marker is queued in front of or behind the kernel
+    // (a recorded event costs the stream about 5 us of idle time).
+    void* params[1] = {const_cast<unsigned char*>(d->args)};
+    SlowCall sc("hipExtLaunchKernel");
+    hipError_t e = hipExtLaunchKernel(d->entry, dim3(d->grid[0], d->grid[1], d->grid[2]),
+                                      dim3(d->block[0], d->block[1], d->block[2]), params, d->lds_bytes, s,
+                                      c->start, c->done, 0);
+    if (e != hipSuccess) { set_error(std::string("hipExtLaunchKernel: ") + hipGetErrorString(e), (int)e); return fail(VTE_EHIP); }
     *completion = c;
     return VTE_OK;
   }
