@@ -53,3 +53,36 @@ def test_timed_launches_are_sampled_and_leave_the_result_alone(H, mode):
         assert np.array_equal(H.to_bits(y), H.to_bits(y_ref))
     finally:
         vte.vte_shutdown(c2)
+
+
+def test_pipelined_binding_makes_few_completion_records(H):
+    """A stream marker idles its stream for a few microseconds, so PIPELINED binding makes one only
+    where progress needs it: behind a quarter of the lookahead window, behind a launch a caller waits
+    for, or when nothing recorded is pending — not behind every launch, as STRICT binding must."""
+    rows, cols = 4096, 4096
+    dx = H.to_dev(inputs.normal_bf16(5, inputs.T_X, (rows, cols)))
+    dg = H.to_dev(inputs.normal_bf16(5, inputs.T_GAMMA, (cols,)))
+    y = H.dev_empty((rows, cols))
+    counts = {}
+    for mode in (vte.VTE_MODE_PIPELINED, vte.VTE_MODE_STRICT):
+        cfg = vte.vte_pool_cfg_default()
+        cfg.mode = mode
+        cfg.lookahead = 64
+        c = vte.vte_init(0, cfg)
+        try:
+            d = vte.vte_desc_rmsnorm(c, dx, dg, y, rows, cols, 1e-6)
+            vs = vte.vte_vstream_create(c, vte.VTE_CLASS_LATENCY)
+            vte.vte_set_builtin_policy(c, vte.VTE_POLICY_WIDEST)
+            vte.vte_stats_reset(c)
+            n = 512
+            mid = vte.vte_submit_batch(vs, vte.desc_array([d] * (n // 2)))
+            last = vte.vte_submit_batch(vs, vte.desc_array([d] * (n // 2)))
+            vte.vte_token_wait(c, mid)                    # a wait in the middle of the stream returns
+            vte.vte_token_wait(c, last)
+            st = vte.vte_stats(c)
+            assert st.completed == n
+            counts[mode] = st.completion_records
+        finally:
+            vte.vte_shutdown(c)
+    assert counts[vte.VTE_MODE_STRICT] == 512
+    assert counts[vte.VTE_MODE_PIPELINED] <= 512 // 8, counts
