@@ -258,8 +258,8 @@ int vte_desc_argmax_finish(vte_ctx* ctx, const vte_desc* lmhead, vte_desc** out)
  *               accumulated at once; ksteps = number of 128-element blocks per K chunk;
  *               the workgroup has min(max_waves, chunks) waves that take the chunks
  *               round-robin; prefetch = blocks the loads run ahead; groups as above.
- *               VTE_GEMV_MFMA_ROWS (batch 33 to 64, one pass over the weights): batch_tile
- *               = 64 (four column tiles per weight tile); the workgroup has max_waves (4 or
+ *               VTE_GEMV_MFMA_ROWS (batch 17 to 64, one pass over the weights): batch_tile
+ *               = 64 (four column tiles per weight tile) or 32 (two; B <= batch_tile); the workgroup has max_waves (4 or
  *               8) waves that split the row tiles, not K, and share X through LDS; rows =
  *               16 x the tiles a wave accumulates at once; prefetch = 128-element K steps
  *               the weight loads run ahead; ksteps = 1; groups = rounds of a workgroup.

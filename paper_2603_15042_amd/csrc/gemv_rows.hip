@@ -1,6 +1,6 @@
-// Skinny-batch GEMV on the matrix cores for 33 to 64 batch rows in one pass over the
+// Skinny-batch GEMV on the matrix cores for up to 64 batch rows in one pass over the
 // weights: Y[b, n] = sum_k W[n, k] X[b, k], four column tiles of 16 batch rows per
-// weight tile of 16 rows (v_mfma_f32_16x16x32_bf16).  Operator family: Sec. 1 "GEMV",
+// weight tile of 16 rows (v_mfma_f32_16x16x32_bf16); two for wide outputs at batch 17 to 32.  Operator family: Sec. 1 "GEMV",
 // Sec. 2.3; LM-head logits and greedy token: Sec. 7.1 / 7.2 of the paper.
 //
 // At this batch X no longer fits a wave's registers (64 rows x a 512-element chunk
@@ -11,7 +11,7 @@
 //   * a workgroup has WR waves and walks `groups` rounds; in a round wave w owns the
 //     G row tiles ((blockIdx.x groups + round) WR + w) G + g;
 //   * K advances in steps of 128 elements, the same step for every wave.  Per step the
-//     workgroup stages X[64 x 128] in LDS (16 KB, double buffered: the waves fetch the
+//     workgroup stages X[16 CT x 128] in LDS (16 KB at four column tiles, double buffered: the waves fetch the
 //     next step's part while they compute, store it after their MFMAs, and one
 //     workgroup barrier per step publishes it); a wave reads its 16 B operands of the
 //     step from there once and uses them for all its G tiles;
@@ -30,12 +30,12 @@
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
-template <int G, int KA, int WR, int EPI>
+template <int CT, int G, int KA, int WR, int EPI>
 __global__ __launch_bounds__(WR * 64) void gemv_rows_kernel(const GemvArgs a) {
-  constexpr int CT = 4;                             // column tiles: batch rows 16 ct + c
+  // CT column tiles: batch rows 16 ct + c (4 for batch 33 to 64, 2 for 17 to 32)
   constexpr int ROUT = (EPI == EPI_SILU) ? 8 : 16;  // outputs per tile: gate rows 0-7 pair with up rows 8-15
-  constexpr int XU = 16 / WR;                       // (column tile, 4-row group) units of X a wave stages per step
-  static_assert(WR == 4 || WR == 8, "X is staged as 16 units spread over the waves; 64 KB of LDS at most");
+  constexpr int XU = 4 * CT / WR;                   // (column tile, 4-row group) units of X a wave stages per step
+  static_assert((CT == 2 || CT == 4) && (WR == 4 || WR == 8), "X is staged as 4 CT units spread over the waves; 64 KB of LDS at most");
   __shared__ u32x4 xstage[2][CT * 256];   // per column tile: 16 rows x 16 pieces of 16 B, piece p of row r at r * 16 + (p ^ r)
   __shared__ u32x4 wstage_all[WR * 256];  // one 4 KB transposition area per wave (at the end: its argmax candidates)
 
@@ -263,21 +263,27 @@ __global__ __launch_bounds__(WR * 64) void gemv_rows_kernel(const GemvArgs a) {
   }
 }
 
-#define VTE_ROWS_CASE(G, KA, WR)                                                          \
-  if (g == G && ka == KA && wr == WR) {                                                   \
-    if (epi == 0) return (const void*)gemv_rows_kernel<G, KA, WR, EPI_NONE>;              \
-    if (epi == 1) return (const void*)gemv_rows_kernel<G, KA, WR, EPI_SILU>;              \
-    if (epi == 2) return (const void*)gemv_rows_kernel<G, KA, WR, EPI_ARGMAX>;            \
+#define VTE_ROWS_CASE(CT, G, KA, WR)                                                      \
+  if (ct == CT && g == G && ka == KA && wr == WR) {                                       \
+    if (epi == 0) return (const void*)gemv_rows_kernel<CT, G, KA, WR, EPI_NONE>;          \
+    if (epi == 1) return (const void*)gemv_rows_kernel<CT, G, KA, WR, EPI_SILU>;          \
+    if (epi == 2) return (const void*)gemv_rows_kernel<CT, G, KA, WR, EPI_ARGMAX>;        \
   }
 
-// g = row tiles per wave, ka = K steps the weight loads run ahead, wr = waves per workgroup;
-// nullptr when the combination is not built.
-extern "C" const void* vte_gemv_entry_rows(int g, int ka, int wr, int epi) {
-  VTE_ROWS_CASE(1, 2, 4)
-  VTE_ROWS_CASE(2, 2, 4)
-  VTE_ROWS_CASE(2, 2, 8)
-  VTE_ROWS_CASE(2, 1, 8)
-  VTE_ROWS_CASE(4, 1, 4)
-  VTE_ROWS_CASE(4, 1, 8)
+// ct = column tiles (2 or 4), g = row tiles per wave, ka = K steps the weight loads run ahead,
+// wr = waves per workgroup; nullptr when the combination is not built.
+extern "C" const void* vte_gemv_entry_rows(int ct, int g, int ka, int wr, int epi) {
+  VTE_ROWS_CASE(4, 1, 2, 4)
+  VTE_ROWS_CASE(4, 2, 2, 4)
+  VTE_ROWS_CASE(4, 2, 2, 8)
+  VTE_ROWS_CASE(4, 2, 1, 8)
+  VTE_ROWS_CASE(4, 4, 1, 4)
+  VTE_ROWS_CASE(4, 4, 1, 8)
+  VTE_ROWS_CASE(2, 2, 2, 4)
+  VTE_ROWS_CASE(2, 2, 2, 8)
+  VTE_ROWS_CASE(2, 4, 1, 4)
+  VTE_ROWS_CASE(2, 4, 1, 8)
+  VTE_ROWS_CASE(2, 4, 2, 4)
+  VTE_ROWS_CASE(2, 4, 2, 8)
   return nullptr;
 }

@@ -323,10 +323,63 @@ def test_lmhead_batch_17_to_32_tokens_and_logits(H, ctx, B, V, K):
     vte.vte_desc_destroy(d)
 
 
-def rows_plan(g=2, ka=2, wr=8, rounds=1):
+def rows_plan(g=2, ka=2, wr=8, rounds=1, bt=64):
     p = vte.vte_gemv_plan()
-    p.batch_tile, p.rows, p.ksteps, p.prefetch, p.max_waves, p.groups, p.kind = 64, 16 * g, 1, ka, wr, rounds, vte.VTE_GEMV_MFMA_ROWS
+    p.batch_tile, p.rows, p.ksteps, p.prefetch, p.max_waves, p.groups, p.kind = bt, 16 * g, 1, ka, wr, rounds, vte.VTE_GEMV_MFMA_ROWS
     return p
+
+
+@pytest.mark.parametrize("plan", [(2, 2, 4, 1), (2, 2, 8, 2), (4, 1, 4, 1), (4, 1, 8, 3), (4, 2, 4, 1), (4, 2, 8, 2)])
+def test_row_split_kind_with_two_column_tiles(H, ctx, plan):
+    """Batch 17 to 32 through the row-split kind (the default for the LM head there): plain, SiLU-mul
+    and LM head on ragged shapes, every built combination; same bits on 32 and 256 CUs, and for the
+    plain GEMV the same bits from every plan (an output is one chain along K)."""
+    g, ka, wr, rounds = plan
+    B, N, K = 29, 1000, 1160
+    W, X = inputs.gemv_case(seed=9, B=B, N=N, K=K)
+    dW, dX, dY = H.to_dev(W), H.to_dev(X), H.dev_empty((B, N))
+    d = vte.vte_desc_gemv_planned(ctx, dW, dX, dY, B, N, K, 0, rows_plan(g, ka, wr, rounds, 32))
+    y = assert_all_equal(run_everywhere(H, ctx, d, dY, [H.pctx_of_width(ctx, w) for w in (32, 256)])).view(np.uint16)
+    bf16_close(y, oracle.gemv(W, X), "gemv rows plan %s" % (plan,))
+    vte.vte_desc_destroy(d)
+    d0 = vte.vte_desc_gemv_planned(ctx, dW, dX, dY, B, N, K, 0, rows_plan(2, 2, 8, 1, 32))
+    dY.fill_(0x7FC1)
+    H.run_on(ctx, d0, H.pctx_of_width(ctx, 256))
+    assert np.array_equal(H.to_bits(dY), y)
+    vte.vte_desc_destroy(d0)
+    # the four-column-tile kernel runs the same chain: the same rows in a batch of 64 slots give the same bits
+    d4 = vte.vte_desc_gemv_planned(ctx, dW, dX, dY, B, N, K, 0, rows_plan(2, 2, 8, 1, 64))
+    dY.fill_(0x7FC1)
+    H.run_on(ctx, d4, H.pctx_of_width(ctx, 64))
+    assert np.array_equal(H.to_bits(dY), y)
+    vte.vte_desc_destroy(d4)
+    # SiLU-mul
+    F = 500
+    Wg = inputs.normal_bf16(4, inputs.T_WGU, (2 * F, K), 0.0, 2.0 * K ** -0.5)
+    dWg, dYs = H.to_dev(Wg), H.dev_empty((B, F))
+    d = vte.vte_desc_gemv_planned(ctx, dWg, dX, dYs, B, 2 * F, K, vte.VTE_EPI_SILU_MUL, rows_plan(g, ka, wr, rounds, 32))
+    ys = assert_all_equal(run_everywhere(H, ctx, d, dYs, [H.pctx_of_width(ctx, w) for w in (32, 256)])).view(np.uint16)
+    bf16_close(ys, oracle.gemv_silu_mul(Wg, X), "silu rows plan %s" % (plan,))
+    vte.vte_desc_destroy(d)
+    # LM head
+    V = 4099
+    Wl = inputs.normal_bf16(8, inputs.T_WLM, (V, K), 0.0, 0.02)
+    dWl = H.to_dev(Wl)
+    tok = torch.zeros(B, dtype=torch.int32, device="cuda")
+    lg = torch.zeros((B, V), dtype=torch.float32, device="cuda")
+    ws = H.dev_zeros_bytes(vte.vte_lmhead_workspace_bytes(B, V, K))
+    d = vte.vte_desc_lmhead_argmax_planned(ctx, dWl, dX, tok, lg, ws, B, V, K, rows_plan(g, ka, wr, rounds, 32))
+    fin = vte.vte_desc_argmax_finish(ctx, d)
+    H.run_on(ctx, d, H.pctx_of_width(ctx, 128))
+    H.run_on(ctx, fin, H.pctx_of_width(ctx, 32))
+    ref, t_ref, margin = oracle.lmhead_argmax(Wl, X)
+    l, t = lg.cpu().numpy(), tok.cpu().numpy()
+    eps_l = np.abs(l - ref).max()
+    assert eps_l < 1e-3
+    assert np.array_equal(t, np.argmax(l, axis=1))
+    assert all(t[b] == t_ref[b] or margin[b] <= 2 * eps_l for b in range(B))
+    vte.vte_desc_destroy(fin)
+    vte.vte_desc_destroy(d)
 
 
 @pytest.mark.parametrize("kind", ["default", "rows"])
@@ -742,7 +795,7 @@ def test_chain_teacher_forced_per_operator(H, ctx, small_chain, B):
 
 
 def test_full_size_chain_in_the_benchmark_configuration(H, ctx):
-    """Llama-8B shapes (V = 128256), batch 8 and batch 64, the launch configuration bench.py times
+    """Llama-8B shapes (V = 128256), batch 8, 32 and 64, the launch configuration bench.py times
     (step boundary fused, pipelined virtual stream): every operator of a step against the oracle on
     the GPU's own inputs, the greedy tokens of three free-running steps, and the same tokens and bits
     from the unfused chain launched explicitly on a 64-CU pCtx."""
@@ -750,7 +803,7 @@ def test_full_size_chain_in_the_benchmark_configuration(H, ctx):
     w = inputs.decode_weights(0, shp)
     wd = H.upload_weights(w)
     p64 = H.pctx_of_width(ctx, 64)
-    for B in (8, 64):
+    for B in (8, 32, 64):
         tok0 = inputs.tokens(0, inputs.T_TOK0, B, shp.V)
         plain = H.DecodeChain(ctx, wd, shp, B, want_logits=True)
         plain.set_tokens(tok0)
