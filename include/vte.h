@@ -253,8 +253,9 @@ int vte_desc_argmax_finish(vte_ctx* ctx, const vte_desc* lmhead, vte_desc** out)
  *   kind        VTE_GEMV_DOT2: the fields above (batch <= 16).  VTE_GEMV_MFMA (matrix-core
  *               tiles of 16 weight rows x 16 batch columns): batch_tile = 16 (B <= 16), or 32
  *               for two column tiles per weight tile (batch 17 to 32 in one tile; batch 33 to
- *               64 as two chunks of 32 rows in one launch, each reading the weights: the default
- *               for outputs too narrow to fill the device without splitting K); rows = 16 x the tiles
+ *               64 as two chunks of 32 rows in one launch, each reading the weights), or 64 for
+ *               four column tiles (batch 33 to 64; ksteps <= 2: the default for outputs too
+ *               narrow to fill the device without splitting K); rows = 16 x the tiles
  *               accumulated at once; ksteps = number of 128-element blocks per K chunk;
  *               the workgroup has min(max_waves, chunks) waves that take the chunks
  *               round-robin; prefetch = blocks the loads run ahead; groups as above.

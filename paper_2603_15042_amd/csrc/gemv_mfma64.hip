@@ -1,0 +1,29 @@
+// Matrix-core GEMV, four column tiles (narrow outputs at batch 33 to 64): the instantiations (see gemv_mfma_kernel.h).
+#include "gemv_mfma_kernel.h"
+#define VTE_MFMA_CT 4
+
+#define VTE_MFMA_EPI(NBK, G, NB, MAXW, AF, OC)                                                       \
+  {                                                                                                 \
+    if (epi == 0) return (const void*)gemv_mfma_kernel<NBK, G, NB, MAXW, AF, OC, EPI_NONE, VTE_MFMA_CT>;         \
+    if (epi == 1) return (const void*)gemv_mfma_kernel<NBK, G, NB, MAXW, AF, OC, EPI_SILU, VTE_MFMA_CT>;         \
+    if (epi == 2) return (const void*)gemv_mfma_kernel<NBK, G, NB, MAXW, AF, OC, EPI_ARGMAX, VTE_MFMA_CT>;       \
+  }
+#define VTE_MFMA_CASE(NBK, G, NB, MAXW)                                  \
+  if (nbk == NBK && g == G && nb == NB && maxw == MAXW) {                \
+    if (allfull && onechunk) VTE_MFMA_EPI(NBK, G, NB, MAXW, true, true)  \
+    if (allfull && !onechunk) VTE_MFMA_EPI(NBK, G, NB, MAXW, true, false) \
+    if (!allfull) VTE_MFMA_EPI(NBK, G, NB, MAXW, false, false)           \
+  }
+
+// nbk = 128-element blocks per K chunk, g = row tiles per workgroup, nb = blocks the
+// loads run ahead, maxw = most waves per workgroup, allfull = K / S is a multiple of
+// the chunk, onechunk = no more chunks than waves; nullptr when the combination is not built.
+// Four column tiles (batch 33 to 64): X for 64 batch rows fits a wave's registers only for a
+// 256-element chunk (128 registers), so a wave owns several chunks and re-reads X per row tile.
+extern "C" const void* vte_gemv_entry_mfma64(int nbk, int g, int nb, int maxw, int allfull, int onechunk, int epi) {
+  VTE_MFMA_CASE(2, 1, 2, 8)
+  VTE_MFMA_CASE(2, 1, 2, 4)
+  VTE_MFMA_CASE(2, 2, 2, 4)
+  VTE_MFMA_CASE(2, 2, 4, 4)
+  return nullptr;
+}

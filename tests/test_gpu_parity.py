@@ -382,20 +382,26 @@ def test_row_split_kind_with_two_column_tiles(H, ctx, plan):
     vte.vte_desc_destroy(d)
 
 
-@pytest.mark.parametrize("kind", ["default", "rows"])
+@pytest.mark.parametrize("kind", ["default", "rows", "chunks"])
 @pytest.mark.parametrize("B,N,K", [(33, 4096, 4096), (64, 4096, 4096), (48, 513, 2048), (64, 37, 520), (40, 16, 8),
                                    (64, 260, 14336), (50, 6144, 1000), (64, 33000, 256)])
 def test_gemv_batch_33_to_64_parity_width_and_position_invariance(H, ctx, B, N, K, kind):
-    """Batch 33 to 64 in one launch.  Wide outputs: four column tiles per weight tile, the waves split
-    the rows and share X through LDS (one pass over the weights); narrow outputs: two chunks of 32
-    rows through the K-split kernel.  Both: the parity bar of the other kinds, the same bits on every
-    pCtx, and a row's result does not depend on where in the batch it stands or on the rows beside it."""
+    """Batch 33 to 64 in one launch, four column tiles per weight tile.  Wide outputs: the waves split
+    the rows and share X through LDS; narrow outputs: the K-split kernel with 256-element chunks;
+    on request: two chunks of 32 rows through the two-column-tile kernel.  All: the parity bar of the
+    other kinds, the same bits on every pCtx, and a row's result does not depend on where in the batch
+    it stands or on the rows beside it."""
     W, X = inputs.gemv_case(seed=2, B=B, N=N, K=K)
     dW, dX, dY = H.to_dev(W), H.to_dev(X), H.dev_empty((B, N))
 
     def make(x, y, b):
         if kind == "rows":
             return vte.vte_desc_gemv_planned(ctx, dW, x, y, b, N, K, 0, rows_plan())
+        if kind == "chunks":
+            p32 = vte.vte_gemv_default_plan(32, N, K, 0, 1)
+            if p32.kind == vte.VTE_GEMV_MFMA_ROWS:
+                p32 = vte.vte_gemv_default_plan(32, 4096, K, 0, 1)
+            return vte.vte_desc_gemv_planned(ctx, dW, x, y, b, N, K, 0, p32)
         return vte.vte_desc_gemv(ctx, dW, x, y, b, N, K)
 
     want = vte.VTE_GEMV_MFMA_ROWS if N >= 16384 else vte.VTE_GEMV_MFMA
@@ -413,7 +419,7 @@ def test_gemv_batch_33_to_64_parity_width_and_position_invariance(H, ctx, B, N, 
     assert np.array_equal(H.to_bits(dY)[::-1], y)
     vte.vte_desc_destroy(d)
     odd = np.arange(1, B, 2)
-    if len(odd) > 32 or kind == "rows":
+    if len(odd) > 32 or kind != "default":
         dXo, dYo = H.to_dev(np.ascontiguousarray(X[odd])), H.dev_empty((len(odd), N))
         d = make(dXo, dYo, len(odd))
         H.run_on(ctx, d, H.pctx_of_width(ctx, 128))
