@@ -224,9 +224,9 @@ int plan_gemv(int B, int outputs, int kps, int epi, vte_gemv_plan* p) {
     // on the Llama-8B shapes.  Large outputs walk several rounds so that X is fetched once
     // per many rows.
     int g = 1, nb = 2, mw = 8, rounds = 1;
-    if (tiles >= 4096) { mw = 4; nb = 4; if (B <= 8) { g = 2; rounds = 4; } else { g = 4; rounds = 2; } }
+    if (tiles >= 4096) { mw = 4; if (B <= 8) { g = 2; rounds = 4; } else { g = 4; rounds = 2; } }
     else if (tiles >= 1024) { g = 8; }
-    else if (tiles > 256 && kps <= 8192) { nb = 4; mw = 4; }
+    else if (tiles > 256 && kps <= 8192) { g = 2; mw = 4; }
     p->batch_tile = 16; p->rows = 16 * g; p->ksteps = 4; p->prefetch = nb; p->max_waves = mw; p->groups = rounds;
     p->kind = VTE_GEMV_MFMA;
     return VTE_OK;

@@ -17,6 +17,8 @@
 //     streams its K range of every tile in blocks of 16 rows x 128 K (4 KB).  With
 //     one chunk per wave X is loaded once per workgroup, so rounds are what keeps
 //     the X re-reads (L2 -> CU traffic that competes with the weight stream) small;
+//     with several chunks per wave a chunk's X is requested block by block while the
+//     last row tile of the chunk before it is being multiplied;
 //   * a block is fetched with four coalesced wave loads (4 rows x 256 B each; the
 //     MFMA operand layout itself would make every load touch 16 cache lines,
 //     which the texture addresser cannot sustain), transposed through a 4 KB
@@ -110,17 +112,19 @@ __global__ __launch_bounds__(MAXW * 64) void gemv_mfma_kernel(const GemvArgs a) 
     for (int t = 0; t < 4; ++t)
       dst[t] = __builtin_amdgcn_raw_buffer_load_b128(rs_w[t], vo, soff + bi * 256, 2);  // streaming
   };
-  auto load_x = [&](int ch) {
+  auto load_x_block = [&](int ch, int bi) {
     const int soff = (k_begin + ch * KC) * 2;
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct)
 #pragma unroll
-      for (int bi = 0; bi < NBK; ++bi)
+      for (int s = 0; s < 4; ++s) {
+        const uint32_t vo = (ALLFULL || k_begin + ch * KC + bi * 128 + s * 32 + q * 8 < k_end) ? voff_x[ct] : 0x80000000u;
+        xs[ct][bi][s] = __builtin_amdgcn_raw_buffer_load_b128(rs_x, vo, soff + (bi * 128 + s * 32) * 2, 0);
+      }
+  };
+  auto load_x = [&](int ch) {
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-          const uint32_t vo = (ALLFULL || k_begin + ch * KC + bi * 128 + s * 32 + q * 8 < k_end) ? voff_x[ct] : 0x80000000u;
-          xs[ct][bi][s] = __builtin_amdgcn_raw_buffer_load_b128(rs_x, vo, soff + (bi * 128 + s * 32) * 2, 0);
-        }
+    for (int bi = 0; bi < NBK; ++bi) load_x_block(ch, bi);
   };
 
   // the finishing part of a round: a thread owns four consecutive tile rows of one
@@ -158,7 +162,7 @@ __global__ __launch_bounds__(MAXW * 64) void gemv_mfma_kernel(const GemvArgs a) 
 
   const bool active = wave < nchunks;
   if (active) {
-    if constexpr (ONECHUNK) load_x(wave);
+    load_x(wave);  // the first chunk; with several chunks per wave the next one's X follows block by block below
 #pragma unroll
     for (int t = 0; t < NB; ++t) load_block(wbuf[t], 0, wave, t / NBK, t % NBK);
   }
@@ -170,7 +174,6 @@ __global__ __launch_bounds__(MAXW * 64) void gemv_mfma_kernel(const GemvArgs a) 
     if (active) {
       int ch = wave;
       while (true) {
-        if constexpr (!ONECHUNK) load_x(ch);
         const int chn = ch + nw;
         const bool more = !ONECHUNK && chn < nchunks;  // ONECHUNK: the launch has no more chunks than waves
         const bool next_round = rd + 1 < a.groups;
@@ -202,6 +205,15 @@ __global__ __launch_bounds__(MAXW * 64) void gemv_mfma_kernel(const GemvArgs a) 
             for (int ct = 0; ct < CT; ++ct)
               acc[g][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, av[s]),
                                                                    __builtin_bit_cast(bf16x8_t, xs[ct][bi][s]), acc[g][ct], 0, 0, 0);
+          // the chunk's last row tile is done with this block of X: fetch the block of the chunk the
+          // wave turns to next (its next chunk, or its first one again in the next round), so that
+          // X is on its way a chunk pass ahead of its use
+          if constexpr (!ONECHUNK) {
+            if (g == G - 1) {
+              if (more) load_x_block(chn, bi);
+              else if (next_round) load_x_block(wave, bi);
+            }
+          }
           __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
           __builtin_amdgcn_wave_barrier();
         }
