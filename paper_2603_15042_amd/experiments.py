@@ -143,6 +143,36 @@ def determinism(trials, replays, seed0=0):
             r["reshaped_max_abs_diff_fp32"] = max(r["reshaped_max_abs_diff_fp32"], float(np.abs(ref32 - got32).max()))
         out["gemv_4096x4096_B%d" % B] = r
 
+    # ---- operator 2b: the wide batches (fixed structure only: there is no split-K baseline above batch 32) ----
+    for B, Nw in ((32, 4096), (64, 4096), (64, 32064)):
+        print("determinism: GEMV %dx4096 batch %d, %d trials" % (Nw, B, trials), file=sys.stderr, flush=True)
+        dWw = dW if Nw == N else H.to_dev(inputs.normal_bf16(seed0 + 7, inputs.T_W, (Nw, K), 0.0, K ** -0.5))
+        dX, dY = H.dev_empty((B, K)), H.dev_empty((B, Nw))
+        tok = torch.zeros(B, dtype=torch.int32, device="cuda")
+        lg = torch.zeros((B, Nw), dtype=torch.float32, device="cuda")
+        ws = H.dev_zeros_bytes(vte.vte_lmhead_workspace_bytes(B, Nw, K))
+        fixed = vte.vte_desc_gemv(ctx, dWw, dX, dY, B, Nw, K)
+        fixed32 = vte.vte_desc_lmhead_argmax(ctx, dWw, dX, tok, lg, ws, B, Nw, K)
+        plan = vte.vte_gemv_default_plan(B, Nw, K, 0, 1)
+        r = {"trials": trials, "plan_kind": int(plan.kind), "plan_batch_tile": int(plan.batch_tile),
+             "fixed_mismatched_bits_bf16": 0, "fixed_mismatched_bits_fp32": 0}
+        for t in range(trials):
+            X = inputs.normal_bf16(seed0 + t, inputs.T_XB, (B, K))
+            dX.copy_(H.to_dev(X))
+            torch.cuda.synchronize()
+            H.run_on(ctx, fixed, p256); ref = H.to_bits(dY).copy()
+            H.run_on(ctx, fixed32, p256); ref32 = lg.cpu().numpy().copy()
+            p = _rand_pctx(rng, ctx)
+            co = _complement_launch(ctx, gemm, p)
+            H.run_on(ctx, fixed, p); got = H.to_bits(dY).copy()
+            H.run_on(ctx, fixed32, p); got32 = lg.cpu().numpy().copy()
+            if co:
+                vte.vte_token_wait(ctx, co)
+            r["fixed_mismatched_bits_bf16"] += H.mismatched_bits(ref, got)[1]
+            r["fixed_mismatched_bits_fp32"] += H.mismatched_bits(ref32, got32)[1]
+        out["gemv_%dx4096_B%d" % (Nw, B)] = r
+        vte.vte_desc_destroy(fixed); vte.vte_desc_destroy(fixed32)
+
     # ---- decoding level: one state replayed (reduced vocabulary keeps it short) ------------------------
     print("determinism: decode state replay, %d replays" % replays, file=sys.stderr, flush=True)
     shp = inputs.DecodeShapes(D=4096, Nqkv=6144, F=14336, V=32064)
