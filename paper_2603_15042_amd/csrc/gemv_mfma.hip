@@ -33,5 +33,7 @@ extern "C" const void* vte_gemv_entry_mfma(int nbk, int g, int nb, int maxw, int
   VTE_MFMA_CASE(4, 1, 4, 4)
   VTE_MFMA_CASE(4, 2, 4, 4)
   VTE_MFMA_CASE(4, 4, 4, 4)
+  VTE_MFMA_CASE(8, 1, 2, 4)  // 1024-element chunks: K = 4096 is one chunk for each of four waves
+  VTE_MFMA_CASE(8, 2, 2, 4)
   return nullptr;
 }

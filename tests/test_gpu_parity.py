@@ -629,6 +629,40 @@ def test_lmhead_logits_and_token(H, ctx, B, V, K):
     vte.vte_desc_destroy(d)
 
 
+@pytest.mark.parametrize("B,V,K,g", [(8, 4099, 4096, 2), (13, 1000, 1160, 2), (16, 530, 8200, 1), (5, 2049, 1024, 2), (8, 300, 520, 1)])
+def test_lmhead_with_1024_element_chunks(H, ctx, B, V, K, g):
+    """The LM-head plan of the large vocabularies (1024-element K chunks, four waves, eight rounds) on
+    small ragged shapes: K a multiple of the chunk, with a tail, shorter than one chunk and longer than
+    the four chunks the waves hold at once; logits against the oracle, same bits at 32 and 256 CUs."""
+    W = inputs.normal_bf16(6, inputs.T_WLM, (V, K), 0.0, 0.02)
+    Hh = inputs.normal_bf16(6, inputs.T_XB, (B, K))
+    dW, dH = H.to_dev(W), H.to_dev(Hh)
+    tok = torch.full((B,), -7, dtype=torch.int32, device="cuda")
+    logits = torch.zeros((B, V), dtype=torch.float32, device="cuda")
+    ws = H.dev_zeros_bytes(vte.vte_lmhead_workspace_bytes(B, V, K))
+    plan = vte.vte_gemv_plan()
+    plan.batch_tile, plan.rows, plan.ksteps, plan.prefetch, plan.max_waves, plan.groups, plan.kind = 16, 16 * g, 8, 2, 4, 8, vte.VTE_GEMV_MFMA
+    big = vte.vte_gemv_default_plan(8, 128256, 4096, 0, 1)
+    assert (big.ksteps, big.rows, big.prefetch, big.max_waves, big.groups, big.kind) == (8, 32, 2, 4, 8, vte.VTE_GEMV_MFMA)
+    d = vte.vte_desc_lmhead_argmax_planned(ctx, dW, dH, tok, logits, ws, B, V, K, plan)
+    fin = vte.vte_desc_argmax_finish(ctx, d)
+    ref_logits, ref_tok, margin = oracle.lmhead_argmax(W, Hh)
+    got = []
+    for w in (32, 256):
+        tok.fill_(-7)
+        logits.fill_(-1.0)
+        H.run_on(ctx, d, H.pctx_of_width(ctx, w))
+        H.run_on(ctx, fin, H.pctx_of_width(ctx, w))
+        got.append((tok.cpu().numpy().copy(), logits.cpu().numpy().copy()))
+    assert np.array_equal(got[0][0], got[1][0]) and np.array_equal(got[0][1].view(np.uint32), got[1][1].view(np.uint32))
+    eps_logit = np.abs(got[0][1].astype(np.float64) - ref_logits).max()
+    assert eps_logit < 1e-4
+    assert all(got[0][0][b] == ref_tok[b] or margin[b] <= 2 * eps_logit for b in range(B))
+    assert np.array_equal(got[0][0], oracle.argmax(got[0][1].astype(np.float64))[0])
+    vte.vte_desc_destroy(fin)
+    vte.vte_desc_destroy(d)
+
+
 def test_lmhead_ties_go_to_lowest_index(H, ctx):
     B, V, K = 2, 600, 128
     W = inputs.normal_bf16(8, inputs.T_WLM, (V, K), 0.0, 0.02)
