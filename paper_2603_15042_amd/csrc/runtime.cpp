@@ -618,19 +618,22 @@ void tpot_maintain(vte_ctx* c) {
       }
       if (!profiled) continue;                 // nothing to size it from yet
       if (want < 0) want = c->pool.total_cus();  // no width meets the target: the whole device
-      // a pipe no other vstream holds or has reserved, then the lowest id: standing pCtxs pack from
-      // one side, so a pre-created remainder covers the rest
-      uint32_t taken = 0;
-      for (int id = 0; id < c->pool.size(); ++id) {
-        const Pctx& q = c->pool.at(id);
-        const bool mine = q.reserved_for == vs->id || (q.state == kLeased && q.holder == vs->id);
-        if (q.active_self && !mine) taken |= 1u << q.pipe;
-      }
+      // a pipe no other vstream will be dispatching on beside it, then the lowest id: standing pCtxs
+      // pack from one side, so a pre-created remainder covers the rest.  Leases that overlap the
+      // candidate do not count: the reservation closes their gates and they drain.
+      auto pipe_taken = [&](int cand) {
+        for (int id = 0; id < c->pool.size(); ++id) {
+          const Pctx& q = c->pool.at(id);
+          const bool mine = q.reserved_for == vs->id || (q.state == kLeased && q.holder == vs->id);
+          if (q.active_self && !mine && q.pipe == c->pool.at(cand).pipe && !c->pool.overlaps(id, cand)) return true;
+        }
+        return false;
+      };
       for (int pass = 0; pass < 2 && vs->standing < 0; ++pass)
         for (int id = 0; id < c->pool.size() && vs->standing < 0; ++id) {
           const Pctx& p = c->pool.at(id);
           if (p.kind != kNode || p.width != want || !reservable_for(c, id, vs->id)) continue;
-          if (pass == 0 && ((taken >> p.pipe) & 1u)) continue;
+          if (pass == 0 && pipe_taken(id)) continue;
           if (reserve_locked(c, id, vs->id) == VTE_OK) vs->standing = id;
         }
       if (vs->standing < 0) continue;

@@ -220,6 +220,56 @@ def test_tpot_first_sizes_an_exclusive_standing_pctx_from_profiles():
         vte.vte_shutdown(c)
 
 
+def test_tpot_first_second_standing_pctx_packs_beside_the_first_and_displaces_the_best_effort_lease():
+    """Two decode streams and a best-effort GEMM: the second standing leaf is the sibling of the first
+    (another pipe) although the GEMM's lease overlaps it and sits on that pipe — the reservation drains
+    that lease anyway — and the GEMM's next launch takes the 192-CU remainder beside the quarter."""
+    c = make_ctx()
+    try:
+        norm, head = decode_descs(c)
+        set_profile(c, norm, lambda w: 0.1)
+        set_profile(c, head, lambda w: 0.5 * 32 / w)         # a token takes 0.6 s on 32 CUs: the leaf suffices
+        gemm = vte.vte_desc_gemm(c, A, A, A, 256, 256, 64)
+        set_profile(c, gemm, lambda w: 10.0 * 32 / w)
+        vte.vte_set_builtin_policy(c, vte.VTE_POLICY_TPOT_FIRST, 0.1)
+        d1 = vte.vte_vstream_create(c, vte.VTE_CLASS_LATENCY)
+        d2 = vte.vte_vstream_create(c, vte.VTE_CLASS_LATENCY)
+        be = vte.vte_vstream_create(c, vte.VTE_CLASS_BEST_EFFORT)
+        for d in (d1, d2):
+            vte.vte_vstream_set_tpot(d, 1.0, 2)
+        t1 = [vte.vte_submit(d1, norm), vte.vte_submit(d1, head)]
+        vte.vte_dispatcher_quiesce(c)
+        st1 = vte.vte_vstream_tpot_info(d1).standing_pctx
+        ps = infos(c)
+        assert st1 >= 0 and ps[st1].width == 32
+        g1 = vte.vte_submit(be, gemm)                        # plans around the first leaf: its 224-CU complement
+        vte.vte_dispatcher_quiesce(c)
+        p_g1 = bound(c)[g1]
+        assert ps[p_g1].width == 224 and not vte.vte_pool_conflict(c, p_g1, st1)
+        t2 = [vte.vte_submit(d2, norm), vte.vte_submit(d2, head)]
+        vte.vte_dispatcher_quiesce(c)
+        st2 = vte.vte_vstream_tpot_info(d2).standing_pctx
+        assert st2 >= 0 and ps[st2].width == 32 and st2 != st1
+        assert ps[st2].parent == ps[st1].parent              # the sibling: one quarter holds both
+        assert ps[st2].pipe != ps[st1].pipe
+        assert infos(c)[p_g1].gate_open == 0                 # the GEMM's lease drains
+        vte.vte_fake_complete(c, g1)
+        vte.vte_token_wait(c, g1)
+        g2 = vte.vte_submit(be, gemm)
+        vte.vte_dispatcher_quiesce(c)
+        p_g2 = bound(c)[g2]
+        assert ps[p_g2].width == 192
+        assert len({ps[st1].pipe, ps[st2].pipe, ps[p_g2].pipe}) == 3
+        for t in t1[:1] + t2[:1]:
+            vte.vte_fake_complete(c, t)
+            vte.vte_token_wait(c, t)
+        vte.vte_dispatcher_quiesce(c)                        # the second op of each token is bound now
+        assert bound(c)[t1[1]] == st1 and bound(c)[t2[1]] == st2
+        finish(c, t1[1:] + t2[1:] + [g2])
+    finally:
+        vte.vte_shutdown(c)
+
+
 def test_tpot_first_prepares_a_wider_pctx_when_the_token_is_at_risk():
     c = make_ctx()
     try:
