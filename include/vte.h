@@ -242,8 +242,9 @@ int vte_desc_argmax_finish(vte_ctx* ctx, const vte_desc* lmhead, vte_desc** out)
 /* The work decomposition of a GEMV-family descriptor, spelled out.  It is part
  * of the submitted structure C_k: chosen from the shape by vte_gemv_default_plan,
  * or given by the caller, and frozen in the descriptor.
- *   batch_tile  batch rows the kernel is built for (1,2,4,8,16; 32 and 64: MFMA kinds); a batch larger than the
- *               tile runs as ceil(B / batch_tile) chunks that each re-read the weights
+ *   batch_tile  batch rows the kernel is built for (1,2,4,8,16; 32 and 64: MFMA kinds); a batch
+ *               larger than the tile runs as ceil(B / batch_tile) chunks that each re-read the
+ *               weights
  *   rows        weight rows a wave streams at once (rows * batch_tile in {16,32,64})
  *   ksteps      512-element K steps per wave: a workgroup has
  *               ceil(ceil(K/S/512) / ksteps) waves, one per K-slice
@@ -256,12 +257,15 @@ int vte_desc_argmax_finish(vte_ctx* ctx, const vte_desc* lmhead, vte_desc** out)
  *               64 as two chunks of 32 rows in one launch, each reading the weights), or 64 for
  *               four column tiles (batch 33 to 64; ksteps <= 2: the default for outputs too
  *               narrow to fill the device without splitting K); rows = 16 x the tiles
- *               accumulated at once; ksteps = number of 128-element blocks per K chunk;
+ *               accumulated at once; ksteps = number of 128-element blocks per K chunk (4; 8 in
+ *               the default plan of wide LM heads with K <= 4096, where four waves then hold all
+ *               of X; 2 with batch_tile 64);
  *               the workgroup has min(max_waves, chunks) waves that take the chunks
  *               round-robin; prefetch = blocks the loads run ahead; groups as above.
  *               VTE_GEMV_MFMA_ROWS (batch 17 to 64, one pass over the weights): batch_tile
- *               = 64 (four column tiles per weight tile) or 32 (two; B <= batch_tile); the workgroup has max_waves (4 or
- *               8) waves that split the row tiles, not K, and share X through LDS; rows =
+ *               = 64 (four column tiles per weight tile) or 32 (two; B <= batch_tile); the
+ *               workgroup has max_waves (4 or 8) waves that split the row tiles, not K, and
+ *               share X through LDS; rows =
  *               16 x the tiles a wave accumulates at once; prefetch = 128-element K steps
  *               the weight loads run ahead; ksteps = 1; groups = rounds of a workgroup.
  *               An output is one accumulator chain along K, nothing crosses a wave.
