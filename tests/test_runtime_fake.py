@@ -366,6 +366,50 @@ def test_structure_depends_on_shape_only():
     vte.vte_shutdown(c)
 
 
+def _plan(kind, bt, rows, ks, pf, mw, groups):
+    p = vte.vte_gemv_plan()
+    p.batch_tile, p.rows, p.ksteps, p.prefetch, p.max_waves, p.groups, p.kind = bt, rows, ks, pf, mw, groups, kind
+    return p
+
+
+def test_default_plans_by_batch_and_width_of_the_output(ctx):
+    """The decomposition is a function of (B, N, K, epilogue) alone: which kernel family serves which
+    batch, and that every default plan builds."""
+    def kind_bt(B, N, K, epi=0):
+        p = vte.vte_gemv_default_plan(B, N, K, epi, 1)
+        vte.vte_desc_destroy(vte.vte_desc_gemv(ctx, A, A, A, B, N, K, epi))
+        return p.kind, p.batch_tile
+    assert kind_bt(1, 4096, 4096)[0] == vte.VTE_GEMV_DOT2
+    assert kind_bt(8, 4096, 4096) == (vte.VTE_GEMV_MFMA, 16)
+    assert kind_bt(24, 4096, 4096) == (vte.VTE_GEMV_MFMA, 32)
+    assert kind_bt(24, 128256, 4096) == (vte.VTE_GEMV_MFMA_ROWS, 32)       # wide output: rows split, X through LDS
+    assert kind_bt(64, 4096, 14336) == (vte.VTE_GEMV_MFMA, 64)             # narrow output: K split, four column tiles
+    assert kind_bt(64, 28672, 4096, vte.VTE_EPI_SILU_MUL) == (vte.VTE_GEMV_MFMA_ROWS, 64)
+    assert kind_bt(33, 128256, 4096) == (vte.VTE_GEMV_MFMA_ROWS, 64)
+    big = vte.vte_gemv_default_plan(8, 128256, 4096, 0, 1)                 # 1024-element chunks: four waves hold all of X
+    assert (big.ksteps, big.max_waves) == (8, 4)
+    long_k = vte.vte_gemv_default_plan(8, 128256, 8192, 0, 1)              # not for longer rows
+    assert long_k.ksteps == 4
+
+
+def test_plans_that_do_not_fit_are_rejected(ctx):
+    R, M = vte.VTE_GEMV_MFMA_ROWS, vte.VTE_GEMV_MFMA
+    for B, N, K, plan in (
+        (64, 4096, 4096, _plan(R, 16, 32, 1, 2, 8, 1)),      # the row-split kind has batch_tile 32 or 64
+        (40, 4096, 4096, _plan(R, 32, 32, 1, 2, 8, 1)),      # and takes the whole batch in one tile
+        (64, 4096, 4096, _plan(R, 64, 32, 1, 3, 8, 1)),      # a combination that is not built
+        (64, 8, 4096, _plan(R, 64, 32, 1, 2, 8, 1)),         # less than one tile of outputs
+        (64, 4096, 4096, _plan(M, 16, 16, 4, 2, 8, 1)),      # batch_tile 16 takes at most 16 rows
+        (64, 4096, 4096, _plan(vte.VTE_GEMV_DOT2, 16, 4, 2, 1, 8, 1)),
+        (8, 4096, 4096, _plan(7, 16, 16, 4, 2, 8, 1)),       # unknown kind
+    ):
+        with pytest.raises(vte.VteError) as e:
+            vte.vte_desc_gemv_planned(ctx, A, A, A, B, N, K, 0, plan)
+        assert e.value.code == vte.VTE_EINVAL
+    with pytest.raises(vte.VteError):                        # no split-K baseline above batch 32
+        vte.vte_splitk_workspace_bytes(33, 4096, 2)
+
+
 def test_bad_shapes_are_rejected(ctx):
     for call in (
         lambda: vte.vte_desc_rmsnorm(ctx, A, A, A, 8, 1020, 1e-6),          # cols % 8
