@@ -183,10 +183,10 @@ int plan_gemv(int B, int outputs, int kps, int epi, vte_gemv_plan* p) {
     if (tiles >= 1024) {
       // timed on the Llama-8B shapes: the LM head takes four tiles per wave and eight waves (X is
       // fetched once per 32 tiles); the gate/up projection has too few tiles for that and runs
-      // two tiles per wave, four waves
+      // one tile per wave, eight waves
       const bool wide = tiles >= 4096;
-      p->batch_tile = 64; p->rows = 16 * (wide ? 4 : 2); p->ksteps = 1; p->prefetch = wide ? 1 : 2;
-      p->max_waves = wide ? 8 : 4; p->groups = 1;
+      p->batch_tile = 64; p->rows = 16 * (wide ? 4 : 1); p->ksteps = 1; p->prefetch = wide ? 1 : 2;
+      p->max_waves = 8; p->groups = 1;
       p->kind = VTE_GEMV_MFMA_ROWS;
       return VTE_OK;
     }

@@ -274,6 +274,7 @@ __global__ __launch_bounds__(WR * 64) void gemv_rows_kernel(const GemvArgs a) {
 // wr = waves per workgroup; nullptr when the combination is not built.
 extern "C" const void* vte_gemv_entry_rows(int ct, int g, int ka, int wr, int epi) {
   VTE_ROWS_CASE(4, 1, 2, 4)
+  VTE_ROWS_CASE(4, 1, 2, 8)
   VTE_ROWS_CASE(4, 2, 2, 4)
   VTE_ROWS_CASE(4, 2, 2, 8)
   VTE_ROWS_CASE(4, 2, 1, 8)
