@@ -536,6 +536,27 @@ def test_strided_gemv_reads_a_column_slice(H, ctx):
     vte.vte_desc_destroy(d)
 
 
+@pytest.mark.parametrize("B,N,K,ld,ldy", [(8, 6160, 264, 520, 6176), (24, 4112, 1032, 2048, 4128), (40, 16400, 264, 520, 16416),
+                                          (64, 272, 520, 1024, 288), (20, 65552, 136, 256, 65552)])
+def test_strided_gemv_in_every_kernel_family(H, ctx, B, N, K, ld, ldy):
+    """X rows ld elements apart, Y rows ldy apart, through the default plan of each family: matrix-core
+    K split with one, two and four column tiles, row split with two and four; the columns of Y between
+    N and ldy keep their poison."""
+    W = inputs.normal_bf16(2, inputs.T_W, (N, K), 0.0, K ** -0.5)
+    Xw = inputs.normal_bf16(2, inputs.T_XB, (B, ld))
+    dW, dX, dY = H.to_dev(W), H.to_dev(Xw), H.dev_empty((B, ldy))
+    dY.fill_(0x7FC1)
+    d = vte.vte_desc_gemv_strided(ctx, dW, dX, ld, dY, ldy, B, N, K)
+    out = []
+    for w in (256, 32):
+        H.run_on(ctx, d, H.pctx_of_width(ctx, w))
+        out.append(H.to_bits(dY).copy())
+    assert np.array_equal(out[0], out[1])
+    bf16_close(out[0][:, :N], oracle.gemv(W, np.ascontiguousarray(Xw[:, :K])), "strided B=%d" % B)
+    assert np.all(out[0][:, N:] == 0x7FC1)
+    vte.vte_desc_destroy(d)
+
+
 # ---------- matrix-core GEMV plans (batch 5-16) ---------------------------------------------------------
 MFMA_PLANS = [(1, 2, 8, 1), (2, 4, 4, 3), (4, 2, 8, 2), (8, 2, 8, 1), (4, 4, 4, 1), (8, 4, 4, 2), (2, 2, 4, 2)]
 
