@@ -494,6 +494,72 @@ def test_lmhead_batch_33_to_64_tokens_and_logits(H, ctx, B, V, K, kind):
     vte.vte_desc_destroy(d)
 
 
+# ---------- the matrix-core trees, emulated on the CPU ------------------------------------------------
+def _spread(Wbits, seed, binades):
+    """bf16 weights times seeded powers of two: makes the alignment inside the instruction visible."""
+    rng = np.random.default_rng(seed)
+    f = inputs.bf16_to_f32(Wbits) * np.exp2(rng.integers(-binades, binades + 1, size=Wbits.shape)).astype(np.float32)
+    return inputs.bf16_bits(f)
+
+
+@pytest.mark.parametrize("B,N,K,binades", [(40, 48, 520, 0), (64, 100, 1160, 0), (33, 37, 264, 6), (57, 64, 128, 20), (17, 32, 4096, 0)])
+def test_row_split_kernel_equals_its_emulated_tree_bit_for_bit(H, ctx, B, N, K, binades):
+    """The fp32 sums (LM-head logits) of the row-split kernel against the CPU emulation of its tree
+    (tests/tree_emulator.py: one chain of 8-product groups along K, the instruction's alignment and
+    rounding reproduced): every bit, on a narrow and on the full-width pCtx; and the bf16 outputs of
+    the plain GEMV are those sums rounded once."""
+    import tree_emulator
+    W = inputs.normal_bf16(31, inputs.T_W, (N, K), 0.0, K ** -0.5)
+    if binades:
+        W = _spread(W, 31, binades)
+    X = inputs.normal_bf16(31, inputs.T_XB, (B, K))
+    want = tree_emulator.gemv_rows_sums(W, X)
+    bt = 64 if B > 32 else 32
+    dW, dX = H.to_dev(W), H.to_dev(X)
+    tok = torch.zeros(B, dtype=torch.int32, device="cuda")
+    lg = torch.zeros((B, N), dtype=torch.float32, device="cuda")
+    ws = H.dev_zeros_bytes(vte.vte_lmhead_workspace_bytes(B, N, K))
+    d = vte.vte_desc_lmhead_argmax_planned(ctx, dW, dX, tok, lg, ws, B, N, K, rows_plan(2, 2, 8, 1, bt))
+    for w in (32, 256):
+        lg.fill_(-1.0)
+        H.run_on(ctx, d, H.pctx_of_width(ctx, w))
+        assert np.array_equal(lg.cpu().numpy().view(np.uint32), want.view(np.uint32)), w
+    vte.vte_desc_destroy(d)
+    dY = H.dev_empty((B, N))
+    d = vte.vte_desc_gemv_planned(ctx, dW, dX, dY, B, N, K, 0, rows_plan(4, 1, 4, 2, bt))
+    H.run_on(ctx, d, H.pctx_of_width(ctx, 128))
+    assert np.array_equal(H.to_bits(dY), tree_emulator._f32_to_bf16(want))
+    vte.vte_desc_destroy(d)
+
+
+@pytest.mark.parametrize("B,N,K,nbk,g,mw,binades", [(8, 64, 4096, 8, 2, 4, 0), (8, 48, 2088, 4, 1, 8, 0), (16, 40, 4096, 4, 2, 4, 0),
+                                                    (5, 32, 14336, 4, 1, 8, 0), (13, 64, 1160, 8, 1, 4, 5), (32, 48, 4096, 4, 2, 8, 0),
+                                                    (64, 32, 1032, 2, 1, 4, 0)])
+def test_k_split_kernel_equals_its_emulated_tree_bit_for_bit(H, ctx, B, N, K, nbk, g, mw, binades):
+    """The K-split matrix-core kernel (the benchmark's LM head is its 1024-element-chunk, four-wave
+    plan): wave w chains its chunks w, w + nw, ... in ascending K, the waves' sums are added in wave
+    order — emulated on the CPU and equal to the GPU's fp32 sums in every bit."""
+    import tree_emulator
+    W = inputs.normal_bf16(32, inputs.T_W, (N, K), 0.0, K ** -0.5)
+    if binades:
+        W = _spread(W, 32, binades)
+    X = inputs.normal_bf16(32, inputs.T_XB, (B, K))
+    want = tree_emulator.gemv_ksplit_sums(W, X, nbk, mw)
+    bt = 16 if B <= 16 else (32 if B <= 32 else 64)
+    plan = vte.vte_gemv_plan()
+    plan.batch_tile, plan.rows, plan.ksteps, plan.prefetch, plan.max_waves, plan.groups, plan.kind = bt, 16 * g, nbk, 2, mw, 2, vte.VTE_GEMV_MFMA
+    dW, dX = H.to_dev(W), H.to_dev(X)
+    tok = torch.zeros(B, dtype=torch.int32, device="cuda")
+    lg = torch.zeros((B, N), dtype=torch.float32, device="cuda")
+    ws = H.dev_zeros_bytes(vte.vte_lmhead_workspace_bytes(B, N, K))
+    d = vte.vte_desc_lmhead_argmax_planned(ctx, dW, dX, tok, lg, ws, B, N, K, plan)
+    for w in (64, 256):
+        lg.fill_(-1.0)
+        H.run_on(ctx, d, H.pctx_of_width(ctx, w))
+        assert np.array_equal(lg.cpu().numpy().view(np.uint32), want.view(np.uint32)), w
+    vte.vte_desc_destroy(d)
+
+
 def test_k_tail_pieces_are_not_fetched_behind_the_last_row(H, ctx):
     """Down-projection shape split 8 ways: K / S = 1792 is no multiple of the 512-element chunk of the
     matrix-core kernel, and the weight tensor (56 x 2 MiB exactly) ends where its allocation ends.  The

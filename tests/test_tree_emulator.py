@@ -1,0 +1,50 @@
+"""CPU checks of the matrix-core tree emulator (tests/tree_emulator.py) against what arithmetic fixes:
+it is test infrastructure for the GPU tests, so a slip in it must not go unnoticed here."""
+import numpy as np
+
+import oracle
+import tree_emulator as te
+from paper_2603_15042_amd import inputs
+
+
+def _bits(a):
+    return inputs.bf16_bits(np.asarray(a, np.float32))
+
+
+def test_small_integers_sum_exactly_whatever_the_grouping():
+    rng = np.random.default_rng(0)
+    W = rng.integers(-8, 9, size=(24, 200)).astype(np.float32)
+    X = rng.integers(-8, 9, size=(5, 200)).astype(np.float32)
+    exact = (X.astype(np.int64) @ W.astype(np.int64).T).astype(np.float32)
+    assert np.array_equal(te.gemv_rows_sums(_bits(W), _bits(X)), exact)
+    assert np.array_equal(te.gemv_ksplit_sums(_bits(W), _bits(X), 1, 8), exact)
+
+
+def test_zero_groups_and_a_ragged_tail_leave_the_accumulator_alone():
+    W = np.zeros((3, 40), np.float32); X = np.ones((2, 40), np.float32)
+    W[:, 3] = [1.5, -2.0, 0.25]; W[:, 36] = [4.0, 4.0, 4.0]
+    got = te.gemv_rows_sums(_bits(W), _bits(X))
+    assert np.array_equal(got, np.tile(np.array([5.5, 2.0, 4.25], np.float32), (2, 1)))
+
+
+def test_a_single_group_cuts_small_products_at_2_to_the_minus_24_of_the_largest():
+    # 1 + 2^-25: the small product lies wholly below the grid 2^(0-24) and is dropped, not rounded in
+    W = np.array([[1.0, 2.0 ** -13] + [0.0] * 6], np.float32); X = np.array([[1.0, 2.0 ** -12] + [0.0] * 6], np.float32)
+    assert te.gemv_rows_sums(_bits(W), _bits(X))[0, 0] == np.float32(1.0)
+    # 1 + 2^-23 is on the grid and survives; -(1) + ... checks the sign handling
+    X2 = np.array([[1.0, 2.0 ** -10] + [0.0] * 6], np.float32)
+    assert te.gemv_rows_sums(_bits(W), _bits(X2))[0, 0] == np.float32(1.0 + 2.0 ** -23)
+    assert te.gemv_rows_sums(_bits(-W), _bits(X2))[0, 0] == np.float32(-(1.0 + 2.0 ** -23))
+
+
+def test_emulated_sums_stay_within_the_error_bound_of_the_plain_definition():
+    N, K, B = 64, 1160, 7
+    W, X = inputs.gemv_case(seed=3, B=B, N=N, K=K)
+    ref = inputs.bf16_to_f32(W).astype(np.float64) @ inputs.bf16_to_f32(X).astype(np.float64).T   # [N, B]
+    mag = np.abs(inputs.bf16_to_f32(W)).astype(np.float64) @ np.abs(inputs.bf16_to_f32(X)).astype(np.float64).T
+    for got in (te.gemv_rows_sums(W, X), te.gemv_ksplit_sums(W, X, 4, 8), te.gemv_ksplit_sums(W, X, 8, 4)):
+        err = np.abs(got.astype(np.float64).T - ref)
+        assert np.all(err <= (K / 8 + 8) * 2.0 ** -23 * mag)          # one rounding and one cut per group of 8
+    bf16_err = np.abs(inputs.bf16_to_f32(te._f32_to_bf16(te.gemv_rows_sums(W, X))).astype(np.float64).T - ref)
+    assert np.all(bf16_err <= 2e-2)
+    assert oracle.gemv(W, X).shape == (B, N)
