@@ -14,7 +14,8 @@
 //     loads per lane in flight (and the next group's loads behind them).
 // Reduction tree of one output, fixed by K:
 //   1. within a lane: v_dot2 over the 4 bf16 pairs of a load in order, the KS
-//      k-steps of the slice in ascending order, one fp32 accumulator;
+//      k-steps of the slice in ascending order, one fp32 accumulator (what one
+//      v_dot2c_f32_bf16 does to it was measured; tests/tree_emulator.py reproduces it);
 //   2. across the 64 lanes of the wave: partner distances 32, 16 (lane-half and
 //      row swaps), then 8, 4, 2, 1 (row rotations); the R*BT sums of a group
 //      are reduced together so that the swaps halve the live values each time,

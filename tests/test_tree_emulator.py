@@ -18,6 +18,7 @@ def test_small_integers_sum_exactly_whatever_the_grouping():
     exact = (X.astype(np.int64) @ W.astype(np.int64).T).astype(np.float32)
     assert np.array_equal(te.gemv_rows_sums(_bits(W), _bits(X)), exact)
     assert np.array_equal(te.gemv_ksplit_sums(_bits(W), _bits(X), 1, 8), exact)
+    assert np.array_equal(te.gemv_dot2_sums(_bits(W), _bits(X), 1), exact)
 
 
 def test_zero_groups_and_a_ragged_tail_leave_the_accumulator_alone():
@@ -42,7 +43,7 @@ def test_emulated_sums_stay_within_the_error_bound_of_the_plain_definition():
     W, X = inputs.gemv_case(seed=3, B=B, N=N, K=K)
     ref = inputs.bf16_to_f32(W).astype(np.float64) @ inputs.bf16_to_f32(X).astype(np.float64).T   # [N, B]
     mag = np.abs(inputs.bf16_to_f32(W)).astype(np.float64) @ np.abs(inputs.bf16_to_f32(X)).astype(np.float64).T
-    for got in (te.gemv_rows_sums(W, X), te.gemv_ksplit_sums(W, X, 4, 8), te.gemv_ksplit_sums(W, X, 8, 4)):
+    for got in (te.gemv_rows_sums(W, X), te.gemv_ksplit_sums(W, X, 4, 8), te.gemv_ksplit_sums(W, X, 8, 4), te.gemv_dot2_sums(W, X, 2)):
         err = np.abs(got.astype(np.float64).T - ref)
         assert np.all(err <= (K / 8 + 8) * 2.0 ** -23 * mag)          # one rounding and one cut per group of 8
     bf16_err = np.abs(inputs.bf16_to_f32(te._f32_to_bf16(te.gemv_rows_sums(W, X))).astype(np.float64).T - ref)
