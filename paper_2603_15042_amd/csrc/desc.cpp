@@ -326,6 +326,10 @@ int build_gemv(vte_ctx* ctx, const GemvBuild& g, vte_desc** out) {
   if (rout < 1) { set_error("gemv plan: the SiLU epilogue needs an even number of rows"); return VTE_EINVAL; }
   const int per_block = rout * p.groups * (by_rows ? p.max_waves : 1);
   const uint32_t gx = static_cast<uint32_t>((n_out + per_block - 1) / per_block);
+  // the MFMA kernels address a workgroup's weight rows with 32-bit byte offsets from its first row
+  if ((mfma || by_rows) && (static_cast<uint64_t>(per_block) + 4) * g.K * 2 >= (1ull << 31)) {
+    set_error("gemv plan: the weight rows of one workgroup span 2 GiB or more (fewer groups or rows)"); return VTE_EINVAL;
+  }
   GemvArgs a{};
   a.W = static_cast<const uint16_t*>(g.W);
   a.X = static_cast<const uint16_t*>(g.X);

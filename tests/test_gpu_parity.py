@@ -167,6 +167,33 @@ def test_gemv_parity_and_width_invariance(H, ctx, B, N, K):
     vte.vte_desc_destroy(d)
 
 
+def test_gemv_weights_beyond_4_gib_are_addressed_with_64_bits(H, ctx):
+    """Maximum sizes: W = 278531 x 8192 bf16 is 4.56 GB and 2.28e9 elements, so byte offsets pass 2^32 and
+    element offsets 2^31 at row 262144, and the last tile is ragged.  Small-integer inputs make every
+    partial sum exact in fp32, so each kernel family (dot products at batch 4, K-split matrix-core tiles
+    at batch 8, row-split ones at batch 40) must equal the oracle bit for bit on the sampled rows
+    (both ends, both sides of the boundary, random ones) and the exact fp32 product everywhere."""
+    N, K = 278531, 8192
+    W = inputs.int_bf16(11, inputs.T_W, (N, K), -8, 8)
+    rows = np.unique(np.concatenate([np.arange(64), np.arange(262144 - 64, 262144 + 64), np.arange(N - 300, N),
+                                     np.random.default_rng(5).integers(0, N, 256)]))
+    dW = H.to_dev(W)
+    Wf = dW.view(torch.bfloat16).float()
+    for B in (4, 8, 40):
+        X = inputs.int_bf16(11 + B, inputs.T_XB, (B, K), -8, 8, -2)
+        dX, dY = H.to_dev(X), H.dev_empty((B, N))
+        d = vte.vte_desc_gemv(ctx, dW, dX, dY, B, N, K)
+        H.run_on(ctx, d, H.pctx_of_width(ctx, 256))
+        y = H.to_bits(dY)
+        assert np.array_equal(y[:, rows], oracle.f64_to_bf16(oracle.gemv(W[rows], X))), B
+        whole = torch.matmul(dX.view(torch.bfloat16).float(), Wf.t()).to(torch.bfloat16).view(torch.int16)
+        assert torch.equal(whole, dY), B
+        vte.vte_desc_destroy(d)
+        del whole, dX, dY
+    del dW, Wf
+    torch.cuda.empty_cache()
+
+
 def test_gemv_identity_permutation_and_exact_inputs(H, ctx):
     K = 1024
     X = inputs.normal_bf16(7, inputs.T_XB, (4, K))

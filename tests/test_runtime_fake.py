@@ -402,10 +402,12 @@ def test_plans_that_do_not_fit_are_rejected(ctx):
         (64, 4096, 4096, _plan(M, 16, 16, 4, 2, 8, 1)),      # batch_tile 16 takes at most 16 rows
         (64, 4096, 4096, _plan(vte.VTE_GEMV_DOT2, 16, 4, 2, 1, 8, 1)),
         (8, 4096, 4096, _plan(7, 16, 16, 4, 2, 8, 1)),       # unknown kind
+        (8, 4096, 1 << 26, _plan(M, 16, 16, 4, 2, 8, 1)),    # a workgroup's 16 weight rows span 2 GiB: 32-bit offsets
     ):
         with pytest.raises(vte.VteError) as e:
             vte.vte_desc_gemv_planned(ctx, A, A, A, B, N, K, 0, plan)
         assert e.value.code == vte.VTE_EINVAL
+    vte.vte_desc_destroy(vte.vte_desc_gemv_planned(ctx, A, A, A, 8, 4096, 1 << 24, 0, _plan(M, 16, 16, 4, 2, 8, 1)))
     with pytest.raises(vte.VteError):                        # no split-K baseline above batch 32
         vte.vte_splitk_workspace_bytes(33, 4096, 2)
 
