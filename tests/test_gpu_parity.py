@@ -127,6 +127,41 @@ def test_layernorm_parity_and_width_invariance(H, ctx, rows, cols):
     vte.vte_desc_destroy(d)
 
 
+@pytest.mark.parametrize("layer,rows,cols", [(False, 524357, 4096), (True, 270001, 8192)])
+def test_norms_beyond_2_to_the_31_elements(H, ctx, layer, rows, cols):
+    """Maximum sizes: more than 2^31 elements (4.3 GB in, 4.3 GB out), one wave per row (cols <= 4096) and one
+    workgroup per row.  Sampled rows (both ends, both sides of the row where element offsets pass 2^31 and
+    byte offsets 2^32, random ones) against the oracle; every row against a float32 evaluation on the GPU."""
+    x = inputs.normal_bf16(21, inputs.T_X, (rows, cols))
+    g = inputs.uniform_bf16(21, inputs.T_GAMMA, (cols,), 0.5, 1.5)
+    b = inputs.normal_bf16(21, inputs.T_BETA, (cols,), 0.0, 0.5)
+    edge = (1 << 31) // cols
+    pick = np.unique(np.concatenate([np.arange(40), np.arange(edge - 20, edge + 20), np.arange(rows - 40, rows),
+                                     np.random.default_rng(6).integers(0, rows, 100)]))
+    assert 0 <= pick.min() and pick.max() < rows and edge + 20 <= rows
+    xs = np.ascontiguousarray(x[pick])
+    dx, dg, db, dy = H.to_dev(x), H.to_dev(g), H.to_dev(b), H.dev_empty((rows, cols))
+    d = (vte.vte_desc_layernorm(ctx, dx, dg, db, dy, rows, cols, 1e-6) if layer
+         else vte.vte_desc_rmsnorm(ctx, dx, dg, dy, rows, cols, 1e-6))
+    H.run_on(ctx, d, H.pctx_of_width(ctx, 256))
+    got = dy[torch.from_numpy(pick).cuda()].cpu().numpy().view(np.uint16)
+    bf16_close(got, oracle.layernorm(xs, g, b, 1e-6) if layer else oracle.rmsnorm(xs, g, 1e-6), "norm rows")
+    gf = dg.view(torch.bfloat16).float()
+    step = 1 << 15
+    for r0 in range(0, rows, step):                        # float32 on the GPU, a slab at a time
+        xf = dx[r0:r0 + step].view(torch.bfloat16).float()
+        if layer:
+            mu = xf.mean(1, keepdim=True)
+            ref = (xf - mu) * torch.rsqrt(((xf - mu) ** 2).mean(1, keepdim=True) + 1e-6) * gf + db.view(torch.bfloat16).float()
+        else:
+            ref = xf * torch.rsqrt((xf * xf).mean(1, keepdim=True) + 1e-6) * gf
+        yf = dy[r0:r0 + step].view(torch.bfloat16).float()
+        assert bool(((yf - ref).abs() <= 2.0 ** -7 * ref.abs() + 1e-3).all()), r0
+    vte.vte_desc_destroy(d)
+    del dx, dy
+    torch.cuda.empty_cache()
+
+
 def test_rmsnorm_reshaped_drifts_on_random_and_not_on_exact_inputs(H, ctx):
     rows, cols = 64, 4096
     x, g = inputs.rmsnorm_case(seed=3, rows=rows, cols=cols)
