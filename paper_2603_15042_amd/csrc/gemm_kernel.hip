@@ -185,10 +185,10 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs a) {
     const int sb_next = sb + 2 >= NSLOT ? sb + 2 - NSLOT : sb + 2;
     const int sa_next = sa + 2 >= NSLOT ? sa + 2 - NSLOT : sa + 2;
     const int sa_after = sa + 4 >= NSLOT ? sa + 4 - NSLOT : sa + 4;
-    fill_tile(sb_next, true, (ks + 1) * TK);
-    __builtin_amdgcn_sched_barrier(0);  // the Bm fills stay the oldest loads: the wait below counts on it
-    fill_tile(sa_after, false, (ks + 2) * TK);
     touch(ks);
+    fill_tile(sb_next, true, (ks + 1) * TK);
+    __builtin_amdgcn_sched_barrier(0);  // the Bm fills stay the oldest fills: the wait below counts on it
+    fill_tile(sa_after, false, (ks + 2) * TK);
     compute_step(smem + sa * SLOT_BYTES, smem + sb * SLOT_BYTES);
 #pragma unroll
     for (int n = 0; n < 24; ++n) {
@@ -196,9 +196,14 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs a) {
       __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // DS read
     }
     __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);
-    // LDS reads done; every load but the newest nine has landed: the A tile of the step after next
-    // (8 fills) and the warm-up touch may still be out
-    __builtin_amdgcn_s_waitcnt(0x0079);
+    // LDS reads done; at most eight loads still out: the A tile of the step after next.  The
+    // warm-up touch returns to a register, the fills to LDS; the touch is issued before the
+    // step's fills so that the eight newest loads are fills and nothing but fills.  (With the
+    // touch as the newest load and vmcnt(9), blocks of 32 rows came out wrong whenever the
+    // kernel really waited here -- operands streaming from HBM at full width -- and vmcnt(8)
+    // did not cure it; with the touch first, with no touch, or with a full wait every output
+    // is exact.  A partial wait must not count across the two kinds of load.)
+    __builtin_amdgcn_s_waitcnt(0x0078);
     __builtin_amdgcn_s_barrier();  // bare: __syncthreads() carries a release fence, i.e. a wait for every load in flight
     sa = sa_next;
     sb = sb_next;
