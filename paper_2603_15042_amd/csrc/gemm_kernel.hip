@@ -17,11 +17,11 @@
 // key the slot within it.  (Swizzling with row % 8 leaves rows r and r + 8 on the
 // same banks: the bank-conflict counter then shows half of all LDS cycles stalled.)
 // The tiles are loaded straight into LDS (global_load_lds, no register stop, no LDS
-// write instructions) into a ring of five 32 KB slots, all of a CU's LDS: with two
-// whole stages the kernel was bound by the fills, which had one K step (1.3 us of
-// MFMA work) to make a round trip that takes longer under load; the ring keeps
-// 96 KB in flight and gives every A tile two steps.  Workgroups that share a band
-// also touch its lines in L2 a few steps ahead.
+// write instructions) into a ring of five 32 KB slots, all of a CU's LDS: a step
+// requests the Bm tile of the next step and the A tile of the step after next while
+// it computes, and waits for all of its loads before the barrier that ends it.
+// Workgroups that share a band touch its lines in L2 a few steps ahead, so a fill
+// is an L2 hit that returns well within a K step (1.3 us of MFMA work).
 // Tile order: consecutive workgroup ids are dealt round-robin to the 8 XCDs, so
 // id % 8 selects a band of tile rows and each XCD's L2 sees a compact set of
 // A rows and Bm columns.
@@ -93,9 +93,9 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs a) {
   typedef __attribute__((address_space(3))) void* lptr_t;
   // operand tile t of the sequence A(0), Bm(0), A(1), Bm(1), ... lives in ring slot t % 5.
   // The fills are written as instructions (LDS base in M0, one wait state before its use): with
-  // the builtin the compiler, which cannot tell the ring slots apart, makes every LDS read behind
-  // a barrier wait for ALL fills in flight, and the ring would be no deeper than two stages.  The
-  // waits are the explicit s_waitcnt below.
+  // the builtin the compiler, which cannot tell the ring slots apart, makes every LDS read wait
+  // for all fills in flight -- also the reads in the middle of a step, right behind the fills the
+  // step has just issued.  The only wait is the explicit s_waitcnt at the end of a step.
   const uint32_t smem_lds = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lptr_t)smem));
   auto fill_tile = [&](int slot, bool is_b, int k0) {
     const uint32_t base = smem_lds + slot * SLOT_BYTES + wave * 64 * ROW_BYTES;
@@ -170,9 +170,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs a) {
   };
   // Ring schedule.  Step i computes on tiles 2i (A) and 2i+1 (Bm).  At its start the slots of
   // step i-1 are free (every wave is past the barrier) and take tiles 2i+3 (Bm of the next step)
-  // and 2i+4 (A of the step after); at its end tiles 2i+2 and 2i+3 must have landed.  So a Bm tile
-  // has one step to arrive and is requested first, an A tile has two, and 96 KB are in flight
-  // instead of the 64 KB of two whole stages.
+  // and 2i+4 (A of the step after); at its end everything requested has landed.
   fill_tile(0, false, 0);
   fill_tile(1, true, 0);
   if (nk > 1) fill_tile(2, false, TK);
@@ -185,10 +183,10 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs a) {
     const int sb_next = sb + 2 >= NSLOT ? sb + 2 - NSLOT : sb + 2;
     const int sa_next = sa + 2 >= NSLOT ? sa + 2 - NSLOT : sa + 2;
     const int sa_after = sa + 4 >= NSLOT ? sa + 4 - NSLOT : sa + 4;
-    touch(ks);
     fill_tile(sb_next, true, (ks + 1) * TK);
-    __builtin_amdgcn_sched_barrier(0);  // the Bm fills stay the oldest fills: the wait below counts on it
+    __builtin_amdgcn_sched_barrier(0);  // the Bm fills go first: they are read first
     fill_tile(sa_after, false, (ks + 2) * TK);
+    touch(ks);
     compute_step(smem + sa * SLOT_BYTES, smem + sb * SLOT_BYTES);
 #pragma unroll
     for (int n = 0; n < 24; ++n) {
@@ -196,14 +194,13 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs a) {
       __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // DS read
     }
     __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);
-    // LDS reads done; at most eight loads still out: the A tile of the step after next.  The
-    // warm-up touch returns to a register, the fills to LDS; the touch is issued before the
-    // step's fills so that the eight newest loads are fills and nothing but fills.  (With the
-    // touch as the newest load and vmcnt(9), blocks of 32 rows came out wrong whenever the
-    // kernel really waited here -- operands streaming from HBM at full width -- and vmcnt(8)
-    // did not cure it; with the touch first, with no touch, or with a full wait every output
-    // is exact.  A partial wait must not count across the two kinds of load.)
-    __builtin_amdgcn_s_waitcnt(0x0078);
+    // LDS reads done, and every load of this wave has landed (vmcnt(0)), the A tile requested in
+    // this step included.  A partial wait that left that tile and the touch out -- "all but the
+    // newest nine", counting on loads retiring in issue order -- produced blocks of 32 wrong rows
+    // whenever the kernel really waited here (operands streaming from HBM at full width): register
+    // loads and LDS fills do not retire in one order.  With L2 warmed by the touches the full wait
+    // costs nothing measurable at any width.
+    __builtin_amdgcn_s_waitcnt(0x0070);
     __builtin_amdgcn_s_barrier();  // bare: __syncthreads() carries a release fence, i.e. a wait for every load in flight
     sa = sa_next;
     sb = sb_next;
