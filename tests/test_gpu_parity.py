@@ -861,6 +861,41 @@ def test_lmhead_ties_go_to_lowest_index(H, ctx):
     vte.vte_desc_destroy(d)
 
 
+@pytest.mark.parametrize("B", [1, 8, 32, 64])
+def test_lmhead_full_vocabulary_exact_logits_and_planted_ties(H, ctx, B):
+    """Small-integer weights and activations at the benchmark's LM-head shape: every logit is an exact
+    fp32 number, so all B x 128256 logits must equal the exact product in every bit (each kernel family
+    by batch); row 0's maximum is planted at three vocabulary entries, the last one included: the token
+    must be the lowest of them, and equal the oracle's on the rows it computes."""
+    V, K = 128256, 4096
+    W = inputs.int_bf16(51, inputs.T_WLM, (V, K), -8, 8)
+    X = inputs.int_bf16(51 + B, inputs.T_XB, (B, K), -2, 2)
+    best = inputs.bf16_bits(8.0 * np.sign(inputs.bf16_to_f32(X[0])))   # the largest logit row 0 can have
+    for v in (90001, 7, V - 1):
+        W[v] = best
+    dW, dX = H.to_dev(W), H.to_dev(X)
+    tok = torch.zeros(B, dtype=torch.int32, device="cuda")
+    logits = torch.empty((B, V), dtype=torch.float32, device="cuda")
+    ws = H.dev_zeros_bytes(vte.vte_lmhead_workspace_bytes(B, V, K))
+    d = vte.vte_desc_lmhead_argmax(ctx, dW, dX, tok, logits, ws, B, V, K)
+    fin = vte.vte_desc_argmax_finish(ctx, d)
+    H.run_on(ctx, d, H.pctx_of_width(ctx, 256))
+    H.run_on(ctx, fin, H.pctx_of_width(ctx, 32))
+    exact = torch.matmul(dX.view(torch.bfloat16).float(), dW.view(torch.bfloat16).float().t())
+    assert torch.equal(exact.view(torch.int32), logits.view(torch.int32))
+    top = exact.max(1, keepdim=True).values
+    ties = (exact == top).sum(1)
+    first = torch.where(exact == top, torch.arange(V, device="cuda")[None, :], V).min(1).values
+    assert torch.equal(first.to(torch.int32), tok)
+    assert int(ties[0]) >= 3 and int(tok[0]) == 7        # the planted maximum is shared by three entries
+    rows = list(range(min(B, 2)))
+    assert np.array_equal(oracle.lmhead_argmax(W, X[rows])[1], tok.cpu().numpy()[rows])
+    vte.vte_desc_destroy(fin)
+    vte.vte_desc_destroy(d)
+    del dW, exact, logits
+    torch.cuda.empty_cache()
+
+
 # ---------- gather ------------------------------------------------------------------------------------
 def test_gather(H, ctx):
     V, K, B = 500, 4096, 16
