@@ -896,6 +896,40 @@ def test_lmhead_full_vocabulary_exact_logits_and_planted_ties(H, ctx, B):
     torch.cuda.empty_cache()
 
 
+@pytest.mark.parametrize("B", [3, 8, 40])
+def test_lmhead_nan_and_infinite_logits(H, ctx, B):
+    """Degenerate logits in every kernel family: a NaN never wins, -inf never wins against a finite
+    value, +inf wins and a tie at +inf goes to the lower index, a batch row whose logits are all NaN
+    gives token 0 -- the oracle's rules."""
+    V, K = 1000, 256
+    W = inputs.normal_bf16(61, inputs.T_WLM, (V, K), 0.0, 0.02)
+    X = inputs.normal_bf16(61, inputs.T_XB, (B, K))
+    X &= 0x7FFF                                          # positive activations: an infinite weight row gives an infinite logit
+    W[17] = 0x7FC0                                       # NaN
+    W[800] = 0xFF80                                      # -inf
+    W[300] = 0x7F80                                      # +inf, twice
+    W[640] = 0x7F80
+    X[2, 5] = 0x7FC0                                     # every logit of batch row 2 is NaN
+    lg, t_ref, _ = oracle.lmhead_argmax(W, X)
+    assert t_ref[0] == 300 and t_ref[2] == 0
+    dW, dX = H.to_dev(W), H.to_dev(X)
+    tok = torch.full((B,), -1, dtype=torch.int32, device="cuda")
+    logits = torch.empty((B, V), dtype=torch.float32, device="cuda")
+    ws = H.dev_zeros_bytes(vte.vte_lmhead_workspace_bytes(B, V, K))
+    d = vte.vte_desc_lmhead_argmax(ctx, dW, dX, tok, logits, ws, B, V, K)
+    fin = vte.vte_desc_argmax_finish(ctx, d)
+    H.run_on(ctx, d, H.pctx_of_width(ctx, 64))
+    H.run_on(ctx, fin, H.pctx_of_width(ctx, 32))
+    got = logits.cpu().numpy().astype(np.float64)
+    assert np.array_equal(np.isnan(got), np.isnan(lg))
+    fin_mask = np.isfinite(lg)
+    assert np.array_equal(got[~fin_mask & ~np.isnan(lg)], lg[~fin_mask & ~np.isnan(lg)])   # the infinities, with their signs
+    assert np.abs(got[fin_mask] - lg[fin_mask]).max() < 1e-4
+    assert np.array_equal(tok.cpu().numpy(), t_ref)
+    vte.vte_desc_destroy(fin)
+    vte.vte_desc_destroy(d)
+
+
 # ---------- gather ------------------------------------------------------------------------------------
 def test_gather(H, ctx):
     V, K, B = 500, 4096, 16
