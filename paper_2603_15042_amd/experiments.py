@@ -7,7 +7,8 @@ determinism  Sec. 7.1 "Determinism Protocol" / Sec. 7.2: matched-input trials of
              (RMSNorm 8x1024) and a GEMV (4096x4096, batch 1/4/8) with only the physical
              allocation varied (random pCtx per trial, a GEMM co-tenant on the complement),
              against the reshaping treatment (threads per row / split-K derived from the CU
-             count); then one decode state replayed with both treatments.
+             count); the co-tenant's GEMM at a compute-bound and an HBM-bound shape; then one
+             decode state replayed with both treatments.
 cotenancy    the mixed training-inference setting (Sec. 7.3.2) in synthetic form: a stream of
              8192^3 bf16 GEMMs as best-effort tenant, bursts of 128 decode steps at batch 8 as
              latency tenant; solo, fixed 128/128 split, and late-bound with lookahead hints.
@@ -172,6 +173,32 @@ def determinism(trials, replays, seed0=0):
             r["fixed_mismatched_bits_fp32"] += H.mismatched_bits(ref32, got32)[1]
         out["gemv_%dx4096_B%d" % (Nw, B)] = r
         vte.vte_desc_destroy(fixed); vte.vte_desc_destroy(fixed32)
+
+    # ---- operator 3: the co-tenant's own GEMM, at a compute-bound and at an HBM-bound shape -----------
+    for (gm, gn, gk) in ((4096, 4096, 4096), (32768, 256, 8192)):
+        ntr = max(1, trials // 5)
+        print("determinism: GEMM %dx%dx%d, %d trials" % (gm, gn, gk, ntr), file=sys.stderr, flush=True)
+        tA = H.to_dev(inputs.normal_bf16(seed0, inputs.T_GEMM_A, (gm, gk)))
+        tB = H.to_dev(inputs.normal_bf16(seed0, inputs.T_GEMM_B, (gn, gk)))
+        tC = H.dev_empty((gm, gn))
+        dg_ = vte.vte_desc_gemm(ctx, tA, tB, tC, gm, gn, gk)
+        H.run_on(ctx, dg_, p256)
+        ref = H.to_bits(tC).copy()
+        r = {"trials": ntr, "fixed_mismatched_bits": 0, "fixed_trials_with_mismatch": 0}
+        for t in range(ntr):
+            p = _rand_pctx(rng, ctx)
+            co = _complement_launch(ctx, gemm, p)
+            tC.fill_(0x7FC1)
+            H.run_on(ctx, dg_, p)
+            got = H.to_bits(tC)
+            if co:
+                vte.vte_token_wait(ctx, co)
+            b = H.mismatched_bits(ref, got)[1]
+            r["fixed_mismatched_bits"] += b
+            r["fixed_trials_with_mismatch"] += int(b > 0)
+        out["gemm_%dx%dx%d" % (gm, gn, gk)] = r
+        vte.vte_desc_destroy(dg_)
+        del tA, tB, tC
 
     # ---- decoding level: one state replayed (reduced vocabulary keeps it short) ------------------------
     print("determinism: decode state replay, %d replays" % replays, file=sys.stderr, flush=True)
