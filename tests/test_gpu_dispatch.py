@@ -89,3 +89,42 @@ def test_cotenant_gemm_does_not_change_decode_bits(H, setup):
     print("co-tenant GEMM ran at widths", sorted(widths))
     vte.vte_vstream_destroy(be)
     vte.vte_shutdown(ctx)
+
+
+def test_hbm_bound_gemm_is_exact_beside_a_stream_that_saturates_hbm(H):
+    """The GEMM's LDS fills really have to be waited for when its operands stream from HBM and a
+    neighbour takes most of the bandwidth: a skinny GEMM on one half of the device, a 1 GB GEMV
+    launched back to back on the other.  Small-integer inputs: every output bit must equal the
+    exact product, launch after launch."""
+    ctx = H.make_ctx(vte.VTE_MODE_PIPELINED)
+    M, N, K = 32768, 256, 8192
+    A = H.to_dev(inputs.int_bf16(71, inputs.T_GEMM_A, (M, K), -8, 8))
+    Bm = H.to_dev(inputs.int_bf16(71, inputs.T_GEMM_B, (N, K), -8, 8, -2))
+    C = H.dev_empty((M, N))
+    g = vte.vte_desc_gemm(ctx, A, Bm, C, M, N, K)
+    Bf = Bm.view(torch.bfloat16).float().t().contiguous()
+    ref = torch.cat([torch.matmul(A[r0:r0 + 4096].view(torch.bfloat16).float(), Bf).to(torch.bfloat16).view(torch.int16)
+                     for r0 in range(0, M, 4096)])
+    Nw, Kw, B = 65536, 8192, 8
+    W = H.to_dev(inputs.normal_bf16(71, inputs.T_W, (Nw, Kw), 0.0, Kw ** -0.5))
+    X = H.to_dev(inputs.normal_bf16(71, inputs.T_XB, (B, Kw)))
+    Y = H.dev_empty((B, Nw))
+    hog = vte.vte_desc_gemv(ctx, W, X, Y, B, Nw, Kw)
+    half0 = vte.vte_pool_find(ctx, vte.VTE_PCTX_NODE, 128, 0)
+    half1 = vte.vte_pool_find(ctx, vte.VTE_PCTX_NODE, 128, 1)
+    vs = vte.vte_vstream_create(ctx, vte.VTE_CLASS_BEST_EFFORT)
+    vte.vte_vstream_pin(vs, half0)
+    H.run_on(ctx, hog, half0)
+    y_ref = H.to_bits(Y).copy()
+    for rep in range(6):
+        C.fill_(0x7FC1)
+        torch.cuda.synchronize()
+        tail = [vte.vte_submit(vs, hog) for _ in range(24)][-1]      # several milliseconds of streaming next door
+        H.run_on(ctx, g, half1)
+        busy = not vte.vte_token_query(ctx, tail)
+        assert int((C != ref).sum()) == 0, rep
+        vte.vte_token_wait(ctx, tail)
+        assert busy, "the neighbour had finished before the GEMM did: nothing was shared"
+    assert np.array_equal(H.to_bits(Y), y_ref)
+    vte.vte_vstream_destroy(vs)
+    vte.vte_shutdown(ctx)
