@@ -65,6 +65,9 @@ enum {
   VTE_ETIMEOUT = -8   /* a bounded wait expired */
 };
 
+/* Every call returns VTE_OK or one of the codes above; nothing is thrown across the ABI.
+ * The message and, after VTE_EHIP, the failing HIP error code of the calling thread's last
+ * failed call (thread-local; the string stays valid until that thread's next failure). */
 const char* vte_last_error(void);
 int vte_last_hip_error(void);
 
@@ -147,6 +150,9 @@ typedef struct vte_pctx_info {
   int pipe;          /* dispatch pipe of its queue; pCtxs on one pipe dispatch one kernel at a time */
 } vte_pctx_info;
 
+/* The pool of Sec. 4.3: *count pCtxs with ids 0 .. *count - 1, fixed from vte_init to
+ * vte_shutdown.  vte_pool_info copies a snapshot of one pCtx (host struct owned by the
+ * caller); VTE_EINVAL for an id out of range. */
 int vte_pool_count(vte_ctx* ctx, int* count);
 int vte_pool_info(vte_ctx* ctx, int pctx_id, vte_pctx_info* info);
 /* The order in which the backend queues were created: ids[k] is the pCtx whose queue
@@ -349,9 +355,13 @@ typedef struct vte_desc_view {
   uint64_t bytes;       /* algorithmic HBM bytes of one launch */
   uint64_t flops;       /* algorithmic flops of one launch */
 } vte_desc_view;
+/* Read-only view of a descriptor (Sec. 4.2): the hash is recomputed from the bytes as they
+ * are now, so equal views before and after a launch show that it was submitted unchanged. */
 int vte_desc_info(const vte_desc* desc, vte_desc_view* view);
 /* Copies min(cap, arg_bytes) bytes of the argument block to `dst` (host). */
 int vte_desc_args(const vte_desc* desc, void* dst, size_t cap);
+/* The caller owns its descriptors.  VTE_EBUSY while a launch of this descriptor is queued or
+ * in flight; descriptors still alive at vte_shutdown are freed there. */
 int vte_desc_destroy(vte_desc* desc);
 
 /* ---- explicit binding (tests, width sweeps, profiling) ------------------------ */
@@ -387,6 +397,10 @@ int vte_submit_batch(vte_vstream* vs, const vte_desc* const* descs, int n, vte_t
  * from (a token of this context that was issued; VTE_EINVAL otherwise). */
 int vte_event_record(vte_vstream* vs, vte_token* event_out);
 int vte_vstream_wait_event(vte_vstream* vs, vte_token event);
+/* A token is satisfied when its launch has been observed complete (Sec. 4.2, 4.4); token 0
+ * and tokens of finished launches are satisfied.  query never blocks; wait blocks the caller
+ * (not the dispatcher) until the token is satisfied and makes the dispatcher record a
+ * completion behind the launch if none covers it yet.  Callable from any thread. */
 int vte_token_query(vte_ctx* ctx, vte_token token, int* done);
 int vte_token_wait(vte_ctx* ctx, vte_token token);
 int vte_vstream_sync(vte_vstream* vs); /* waits on the stream tail */
@@ -517,6 +531,7 @@ int vte_profile_measure(vte_ctx* ctx, const vte_desc* desc, int warmup, int reps
 /* Times `desc` on one pCtx only; *seconds = device time per launch.  Same conditions. */
 int vte_profile_measure_on(vte_ctx* ctx, const vte_desc* desc, int pctx_id, int warmup, int reps,
                            double* seconds);
+/* Stores a profile entry by hand (seconds > 0, width > 0: CUs; VTE_EINVAL otherwise). */
 int vte_profile_set(vte_ctx* ctx, uint64_t profile_key, int width, double seconds);
 /* VTE_EINVAL if no profile exists for (key,width). */
 int vte_profile_get(vte_ctx* ctx, uint64_t profile_key, int width, double* seconds);
@@ -536,9 +551,11 @@ typedef struct vte_stats_t {
       stale_proposals, submit_failures, gates_closed, reservations,
       completion_records; /* stream markers made to observe completions (PIPELINED: far fewer than launches) */
 } vte_stats_t;
+/* Copies the counters since vte_init or the last vte_stats_reset. */
 int vte_stats(vte_ctx* ctx, vte_stats_t* out);
 /* Copies up to `cap` most recent completed-op records, oldest first; *n_out = count. */
 int vte_stats_read(vte_ctx* ctx, vte_op_record* dst, int cap, int* n_out);
+/* Zeroes the counters and empties the record ring; launches in flight are still recorded. */
 int vte_stats_reset(vte_ctx* ctx);
 
 /* ---- fake backend hooks (VTE_BACKEND_FAKE only; VTE_ESTATE otherwise) ---------- */
@@ -552,6 +569,7 @@ typedef struct vte_fake_log_entry {
   uint64_t desc_hash;  /* hash of the descriptor bytes as seen by the backend */
   int waited_on_pctx;  /* device-side wait inserted on this pCtx's stream, or -1 */
 } vte_fake_log_entry;
+/* Copies up to `cap` entries of what the fake backend was handed, in submission order. */
 int vte_fake_log(vte_ctx* ctx, vte_fake_log_entry* dst, int cap, int* n_out);
 
 /* Blocks until the dispatcher has nothing left to do without outside input
