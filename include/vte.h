@@ -576,6 +576,28 @@ int vte_fake_log(vte_ctx* ctx, vte_fake_log_entry* dst, int cap, int* n_out);
  * (no ready op it could bind, no unobserved completion).  For tests. */
 int vte_dispatcher_quiesce(vte_ctx* ctx);
 
+/* ---- for callers that cannot allocate ---------------------------------------------------- */
+/* For code that may not call hipMalloc where it stands: a stream under HIP graph capture, a
+ * tight serving loop, a harness that forbids allocation.  vte_lmhead_argmax_static is
+ * vte_desc_lmhead_argmax (default plan) + vte_desc_argmax_finish as one call that enqueues three
+ * launches on `hip_stream` (a hipStream_t of the calling thread's current device; NULL = the
+ * null stream) and returns without waiting: tok[b] and, if given, logits[b,:] are valid once
+ * the stream has passed them, and hold the same bits as the descriptor pair's.  It needs no
+ * vte_ctx, builds no descriptor and calls no allocating routine: the per-workgroup candidates
+ * live in an array of vte_static_scratch_bytes() (1 MiB) inside the library's device image,
+ * one copy per GPU, held until the process ends, its address looked up once per device (at
+ * vte_init on that device, else on the first call there).
+ * W: device [V,K] bf16; H: device [B,K] bf16; tok: device [B] int32; logits_or_null: device
+ * [B,V] fp32 or NULL — all owned by the caller.  Same limits as vte_desc_lmhead_argmax.
+ * VTE_EINVAL if the shape's candidates do not fit the array (the message gives both sizes;
+ * every vocabulary up to 262144 rows fits at every batch), VTE_EHIP if a launch fails.
+ * Every call on a GPU uses that GPU's one array, which keeps the previous call's contents
+ * (what must start at zero is cleared by a fill launch in front, on the same stream): calls
+ * that overlap in time on one GPU — different streams without an edge between them — race. */
+int vte_static_scratch_bytes(size_t* bytes);
+int vte_lmhead_argmax_static(void* hip_stream, const void* W, const void* H, int32_t* tok,
+                             float* logits_or_null, int B, int V, int K);
+
 /* ---- device utilities -------------------------------------------------------------- */
 /* Host seconds since vte_init on the library's clock (the one the records use). */
 int vte_now(vte_ctx* ctx, double* seconds);

@@ -16,7 +16,7 @@ HIP_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wno-inline
              "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
              "-Wno-unused-command-line-argument"]
 SOURCES = ["norm_kernels.hip", "gemv_b1.hip", "gemv_b2.hip", "gemv_b4.hip", "gemv_b8.hip", "gemv_b16.hip", "gemv_mfma.hip", "gemv_mfma32.hip", "gemv_mfma64.hip", "gemv_rows.hip",
-           "misc_kernels.hip", "gemm_kernel.hip", "backend_hip.cpp", "backend_fake.cpp", "pool.cpp", "planner.cpp",
+           "misc_kernels.hip", "noalloc.hip", "gemm_kernel.hip", "backend_hip.cpp", "backend_fake.cpp", "pool.cpp", "planner.cpp",
            "desc.cpp", "runtime.cpp"]
 
 

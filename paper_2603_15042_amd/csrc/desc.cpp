@@ -54,15 +54,14 @@ namespace {
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// Fills *d (caller's storage: heap or stack) from the shape-derived launch parameters.
+// Allocates nothing and touches no context state.
 template <class Args>
-int finish_desc(vte_ctx* ctx, int kernel, const void* entry, const Args& a, uint32_t gx, uint32_t gy,
-                uint32_t threads, uint32_t lds, uint64_t shape_key, uint64_t bytes, uint64_t flops,
-                vte_desc** out, uint32_t gz = 1) {
+int fill_desc(vte_desc* d, vte_ctx* ctx, int kernel, const void* entry, const Args& a, uint32_t gx, uint32_t gy,
+              uint32_t threads, uint32_t lds, uint64_t shape_key, uint64_t bytes, uint64_t flops, uint32_t gz = 1) {
   static_assert(sizeof(Args) <= sizeof(vte_desc::args), "argument block too large");
   if (!entry) { set_error("no kernel instance for this configuration"); return VTE_EINVAL; }
   if (gx == 0 || gy == 0 || gz == 0 || gx > 0x7fffffffu || gy > 65535u || gz > 65535u) { set_error("grid out of range"); return VTE_EINVAL; }
-  vte_desc* d = new (std::nothrow) vte_desc;
-  if (!d) { set_error("out of host memory"); return VTE_ENOMEM; }
   std::memset(d, 0, sizeof *d);
   d->ctx = ctx;
   d->kernel = kernel;
@@ -79,6 +78,14 @@ int finish_desc(vte_ctx* ctx, int kernel, const void* entry, const Args& a, uint
   k = fnv1a(d->block, sizeof d->block, k);
   d->profile_key = fnv1a(&shape_key, sizeof shape_key, k);
   d->hash = desc_hash(d);
+  return VTE_OK;
+}
+
+// Copies a filled descriptor to the heap, applies its one-time kernel attributes and hands
+// ownership of the copy to the caller through *out (the context keeps it listed).
+int register_desc(vte_ctx* ctx, const vte_desc& filled, vte_desc** out) {
+  vte_desc* d = new (std::nothrow) vte_desc(filled);
+  if (!d) { set_error("out of host memory"); return VTE_ENOMEM; }
   int rc = ctx->backend->prepare_kernel(d);
   if (rc != VTE_OK) { delete d; return rc; }
   {
@@ -87,6 +94,16 @@ int finish_desc(vte_ctx* ctx, int kernel, const void* entry, const Args& a, uint
   }
   *out = d;
   return VTE_OK;
+}
+
+template <class Args>
+int finish_desc(vte_ctx* ctx, int kernel, const void* entry, const Args& a, uint32_t gx, uint32_t gy,
+                uint32_t threads, uint32_t lds, uint64_t shape_key, uint64_t bytes, uint64_t flops,
+                vte_desc** out, uint32_t gz = 1) {
+  vte_desc tmp;
+  int rc = fill_desc(&tmp, ctx, kernel, entry, a, gx, gy, threads, lds, shape_key, bytes, flops, gz);
+  if (rc != VTE_OK) return rc;
+  return register_desc(ctx, tmp, out);
 }
 
 int norm_threads(int cols) {
@@ -284,8 +301,9 @@ struct GemvBuild {
   int ldx = 0, ldy = 0;  // 0 = dense
 };
 
-int build_gemv(vte_ctx* ctx, const GemvBuild& g, vte_desc** out) {
-  if (!ctx || !out || !g.W || !g.X) { set_error("gemv: null argument"); return VTE_EINVAL; }
+// Validates the shape and the plan and fills *d; allocates nothing.
+int build_gemv_into(vte_ctx* ctx, const GemvBuild& g, vte_desc* d) {
+  if (!d || !g.W || !g.X) { set_error("gemv: null argument"); return VTE_EINVAL; }
   const bool lm = (g.epi_kernel == 2);
   if (!lm && !g.Y) { set_error("gemv: null output"); return VTE_EINVAL; }
   if (lm && (!g.tok || !g.ws)) { set_error("lmhead: tok and workspace are required"); return VTE_EINVAL; }
@@ -347,11 +365,54 @@ int build_gemv(vte_ctx* ctx, const GemvBuild& g, vte_desc** out) {
   uint64_t bytes = 2ull * g.N * g.K + 2ull * g.B * g.K + (lm ? 4ull * g.B : 2ull * g.B * n_out);
   if (lm && g.logits) bytes += 4ull * g.B * g.N;
   const uint64_t flops = 2ull * g.B * g.N * g.K;
-  return finish_desc(ctx, g.kernel, gemv_entry(p, g.epi_kernel, kps), a, gx, static_cast<uint32_t>(g.S),
-                     static_cast<uint32_t>(waves * 64), 0, shape, bytes, flops, out, static_cast<uint32_t>(zchunks));
+  return fill_desc(d, ctx, g.kernel, gemv_entry(p, g.epi_kernel, kps), a, gx, static_cast<uint32_t>(g.S),
+                   static_cast<uint32_t>(waves * 64), 0, shape, bytes, flops, static_cast<uint32_t>(zchunks));
+}
+
+int build_gemv(vte_ctx* ctx, const GemvBuild& g, vte_desc** out) {
+  if (!ctx || !out) { set_error("gemv: null argument"); return VTE_EINVAL; }
+  vte_desc tmp;
+  int rc = build_gemv_into(ctx, g, &tmp);
+  if (rc != VTE_OK) return rc;
+  return register_desc(ctx, tmp, out);
+}
+
+// The argmax-finish launch that reads the candidates the LM-head launch *lm leaves behind.
+int fill_argmax_finish(vte_ctx* ctx, const vte_desc* lm, vte_desc* d) {
+  GemvArgs g;
+  std::memcpy(&g, lm->args, sizeof g);
+  // candidates sit behind the ticket words: [1 + grid.x * grid.z] uint32, then values and indices [batch slots][grid.x]
+  ArgmaxFinishArgs a{};
+  a.pairs = g.ws + 1 + lm->grid[0] * lm->grid[2];
+  a.tok = g.tok;
+  a.nblocks = static_cast<int>(lm->grid[0]);
+  a.bt = g.bt;
+  a.B = g.B;
+  const uint64_t shape = (static_cast<uint64_t>(a.nblocks) << 32) | static_cast<uint32_t>(a.B * 64 + a.bt);
+  return fill_desc(d, ctx, VTE_K_ARGMAX_FINISH, vte_argmax_finish_entry(), a, static_cast<uint32_t>(a.B), 1, 1024, 0,
+                   shape, 8ull * a.nblocks * a.B + 4ull * a.B, 0);
 }
 
 }  // namespace
+
+// The LM head with its default plan and the finish launch behind it, filled into the caller's
+// storage with `ws` as the workspace; *ws_words = 32-bit words of `ws` the two launches touch
+// (ticket words first: *ticket_words of them).  Nothing is allocated or registered.
+int fill_lmhead_pair(const void* W, const void* H, int32_t* tok, float* logits_or_null, void* ws, int B, int V, int K,
+                     vte_desc* lm, vte_desc* fin, size_t* ticket_words, size_t* ws_words) {
+  if (!tok) { set_error("lmhead: tok is required"); return VTE_EINVAL; }
+  GemvBuild g{VTE_K_LMHEAD, 2, W, H, nullptr, logits_or_null, tok, ws, nullptr, B, V, K, VTE_EPI_NONE, 1, nullptr};
+  int rc = build_gemv_into(nullptr, g, lm);
+  if (rc != VTE_OK) return rc;
+  rc = fill_argmax_finish(nullptr, lm, fin);
+  if (rc != VTE_OK) return rc;
+  GemvArgs a;
+  std::memcpy(&a, lm->args, sizeof a);
+  *ticket_words = 1 + static_cast<size_t>(lm->grid[0]) * lm->grid[2];
+  *ws_words = *ticket_words + 2 * static_cast<size_t>(a.bt) * lm->grid[0];
+  return VTE_OK;
+}
+
 }  // namespace vte
 
 using namespace vte;
@@ -485,18 +546,10 @@ int vte_desc_argmax_finish(vte_ctx* ctx, const vte_desc* lmhead, vte_desc** out)
   if (lmhead->ctx != ctx || (lmhead->kernel != VTE_K_LMHEAD && lmhead->kernel != VTE_K_LMHEAD_SPLITK)) {
     set_error("argmax_finish: needs an LM-head descriptor of this context"); return VTE_EINVAL;
   }
-  GemvArgs g;
-  std::memcpy(&g, lmhead->args, sizeof g);
-  // candidates sit behind the ticket words: [1 + grid.x] uint32, then [grid.x][batch tile][2]
-  ArgmaxFinishArgs a{};
-  a.pairs = g.ws + 1 + lmhead->grid[0] * lmhead->grid[2];
-  a.tok = g.tok;
-  a.nblocks = static_cast<int>(lmhead->grid[0]);
-  a.bt = g.bt;
-  a.B = g.B;
-  const uint64_t shape = (static_cast<uint64_t>(a.nblocks) << 32) | static_cast<uint32_t>(a.B * 64 + a.bt);
-  return finish_desc(ctx, VTE_K_ARGMAX_FINISH, vte_argmax_finish_entry(), a, static_cast<uint32_t>(a.B), 1, 1024, 0,
-                     shape, 8ull * a.nblocks * a.B + 4ull * a.B, 0, out);
+  vte_desc tmp;
+  int rc = fill_argmax_finish(ctx, lmhead, &tmp);
+  if (rc != VTE_OK) return rc;
+  return register_desc(ctx, tmp, out);
 }
 
 int vte_desc_gather(vte_ctx* ctx, const void* E, const int32_t* tok, void* H, int B, int V, int K, vte_desc** out) {

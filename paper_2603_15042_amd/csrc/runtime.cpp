@@ -852,6 +852,7 @@ int vte_init(vte_ctx** out, int device, const vte_pool_cfg* user_cfg) {
   c->backend = cfg.backend == VTE_BACKEND_FAKE ? make_fake_backend() : make_hip_backend();
   int cus = cfg.total_cus;
   int rc = c->backend->init(device, &cus);
+  if (rc == VTE_OK && cfg.backend == VTE_BACKEND_HIP) rc = static_scratch_setup(device);  // the device is current here
   if (rc != VTE_OK) { delete c->backend; delete c; return rc; }
   c->cfg.total_cus = cus;
   std::string err;

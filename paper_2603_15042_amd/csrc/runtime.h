@@ -68,6 +68,10 @@ class Backend {
   virtual int prepare_kernel(const vte_desc* d) = 0;  // one-time per-kernel attributes
 };
 
+// Looks up, once per device, the device address of the library's static scratch array
+// (the calling thread's current device must be `device`).
+int static_scratch_setup(int device);
+
 Backend* make_hip_backend();
 Backend* make_fake_backend();
 

@@ -123,6 +123,7 @@ EXPORTS = [
     "vte_stats_reset", "vte_fake_complete", "vte_fake_set_autocomplete", "vte_fake_fail_next_submits",
     "vte_fake_log", "vte_dispatcher_quiesce", "vte_now", "vte_vstream_set_tpot", "vte_vstream_tpot_info", "vte_submit_batch", "vte_pool_creation_order", "vte_desc_memcpy", "vte_desc_memset32",
     "vte_event_record", "vte_vstream_wait_event", "vte_desc_softmax_prob",
+    "vte_static_scratch_bytes", "vte_lmhead_argmax_static",
 ]
 
 _lib = None
@@ -523,3 +524,15 @@ def vte_now(ctx):
     s = C.c_double()
     _check(load().vte_now(ctx, C.byref(s)))
     return s.value
+
+
+def vte_static_scratch_bytes():
+    n = C.c_size_t()
+    _check(load().vte_static_scratch_bytes(C.byref(n)))
+    return n.value
+
+
+def vte_lmhead_argmax_static(hip_stream, W, H, tok, logits_or_null, B, V, K):
+    """hip_stream: a hipStream_t as an integer (0 / None = the null stream)."""
+    _check(load().vte_lmhead_argmax_static(C.c_void_p(hip_stream or None), _ptr(W), _ptr(H), _ptr(tok),
+                                           _ptr(logits_or_null), int(B), int(V), int(K)))
