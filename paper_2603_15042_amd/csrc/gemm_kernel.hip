@@ -5,10 +5,13 @@
 //
 // Workgroup = 4 waves as 2 (M) x 2 (N); a wave owns 128 x 128 of the tile as
 // 4 x 4 MFMA blocks of 32x32 (v_mfma_f32_32x32x16_bf16): 16 MFMAs per 8 operand
-// reads from LDS, which keeps the LDS port at half the MFMA pipe's time (with
-// 4 x 2 blocks per wave and padded rows the kernel was LDS-bound at 36 % of the
-// MFMA peak).  The 256 accumulator registers leave one wave per SIMD, so operand
-// fragments for the next 16 K are read while the MFMAs of the current 16 run.
+// reads from LDS.  The 256 accumulator registers leave one wave per SIMD, so
+// nothing but the wave's own instruction order hides a latency: the K loop is
+// written out as groups of two MFMAs with at most one LDS read and one LDS fill
+// between them, and the order is pinned (sched_barrier), so that the matrix
+// pipe, which takes 32 cycles per instruction, always has the next one queued.
+// (An earlier version issued a step's 16 fills in one burst in front of its
+// MFMAs; the pipe ran dry for the length of the burst, every step.)
 // A and Bm tiles (256 rows x 64 K, 128 B per row) are staged in LDS unpadded;
 // the 16-byte pieces of a row are XOR-swizzled with (row / 2) % 8.  The LDS has 64
 // banks of 4 bytes: a 128-bit read is served 16 lanes (256 B) per cycle, two rows
@@ -20,11 +23,15 @@
 // write instructions) into a ring of five 32 KB slots, all of a CU's LDS: a step
 // requests the Bm tile of the next step and the A tile of the step after next while
 // it computes, and waits for all of its loads before the barrier that ends it.
+// The last 16 MFMAs of a step need registers only; they are issued behind the
+// barrier, among the first fragment reads of the next step, whose latency they cover.
 // Workgroups that share a band touch its lines in L2 a few steps ahead, so a fill
-// is an L2 hit that returns well within a K step (1.3 us of MFMA work).
+// is an L2 hit that returns well within a K step.
 // Tile order: consecutive workgroup ids are dealt round-robin to the 8 XCDs, so
 // id % 8 selects a band of tile rows and each XCD's L2 sees a compact set of
 // A rows and Bm columns.
+// Tree of one output: inside an MFMA the hardware's order over 16 K; MFMAs chained
+// through the accumulator in ascending K.  Fixed by K.
 #include "dev_util.h"
 #include "kargs.h"
 
@@ -81,15 +88,18 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs a) {
   // instruction lands at the instruction's LDS base + 16 L).  One instruction fills 8 rows;
   // lane L fetches, for row L / 8, the piece that belongs in slot L % 8 of the swizzled row.
   // Wave w fills rows [64 w, 64 w + 64) of both operands: 16 instructions per K step.
+  // Address = scalar base of the tile at this K step + one 32-bit lane offset per row group
+  // (the same eight offsets serve both operands): no vector arithmetic per fill.
   const int grow = lane >> 3;                                   // row within the 8-row group
   // swizzle key of a row: (row / 2) % 8.  Group i of a wave starts at row 64 w + 8 i, so the key
   // is (4 (i % 2) + grow / 2) % 8: one piece choice for even groups, one for odd ones.
   const int gpiece0 = (lane & 7) ^ (grow >> 1);
   const int gpiece1 = (lane & 7) ^ (4 + (grow >> 1));
-  const uint16_t* Ap = Ag + static_cast<size_t>(wave * 64 + grow) * a.K;
-  const uint16_t* Bp = Bg + static_cast<size_t>(wave * 64 + grow) * a.K;
-  const size_t group_step = static_cast<size_t>(8) * a.K;
-  typedef const __attribute__((address_space(1))) void* gptr_t;
+  uint32_t voff[8];                                             // byte offset of this lane's piece, group i
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+    voff[i] = static_cast<uint32_t>(wave * 64 + 8 * i + grow) * static_cast<uint32_t>(a.K) * 2u +
+              static_cast<uint32_t>((i & 1) ? gpiece1 : gpiece0) * 16u;
   typedef __attribute__((address_space(3))) void* lptr_t;
   // operand tile t of the sequence A(0), Bm(0), A(1), Bm(1), ... lives in ring slot t % 5.
   // The fills are written as instructions (LDS base in M0, one wait state before its use): with
@@ -97,29 +107,24 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs a) {
   // for all fills in flight -- also the reads in the middle of a step, right behind the fills the
   // step has just issued.  The only wait is the explicit s_waitcnt at the end of a step.
   const uint32_t smem_lds = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lptr_t)smem));
-  auto fill_tile = [&](int slot, bool is_b, int k0) {
-    const uint32_t base = smem_lds + slot * SLOT_BYTES + wave * 64 * ROW_BYTES;
-    const uint16_t* src = is_b ? Bp : Ap;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int gp = ((i & 1) ? gpiece1 : gpiece0) * 8;
-      const uint16_t* g = src + i * group_step + k0 + gp;
-      const uint32_t l = base + i * 8 * ROW_BYTES;
-      asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(g), "s"(l) : "memory", "m0");
-    }
+  const uint32_t wave_lds = smem_lds + wave * 64 * ROW_BYTES;
+  // one fill instruction: row group i of this wave's 64 rows of the tile at `src` (scalar) into ring slot `slot`
+  auto fill1 = [&](int slot, const uint16_t* src, int i) {
+    const uint32_t l = wave_lds + slot * SLOT_BYTES + i * 8 * ROW_BYTES;
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(voff[i]), "s"(src), "s"(l) : "memory", "m0");
   };
 
   // operand fragments: lane l supplies row l % 32 of a 32-row block and K pieces 2 kk + l / 32
   const int frow = lane & 31, fhalf = lane >> 5, fsw = (frow >> 1) & 7;
   const int a_row0 = (wm * 128 + frow) * ROW_BYTES;
   const int b_row0 = (wn * 128 + frow) * ROW_BYTES;
-  auto read_frags = [&](bf16x8_t(&af)[4], bf16x8_t(&bfr)[4], const uint8_t* sa, const uint8_t* sb, int kk) {
+  bf16x8_t af[2][4], bfr[2][4];
+  // r-th of the eight fragment reads of K piece kk of a step (Bm fragments first: the MFMAs run
+  // i-major, so af[3] is needed last)
+  auto read1 = [&](int buf, const uint8_t* sa, const uint8_t* sb, int kk, int r) {
     const int piece = 16 * ((2 * kk + fhalf) ^ fsw);
-    // Bm fragments first: the MFMAs run i-major, so af[3] is needed last
-#pragma unroll
-    for (int j = 0; j < 4; ++j) bfr[j] = *reinterpret_cast<const bf16x8_t*>(sb + b_row0 + j * 32 * ROW_BYTES + piece);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) af[i] = *reinterpret_cast<const bf16x8_t*>(sa + a_row0 + i * 32 * ROW_BYTES + piece);
+    if (r < 4) bfr[buf][r] = *reinterpret_cast<const bf16x8_t*>(sb + b_row0 + r * 32 * ROW_BYTES + piece);
+    else af[buf][r - 4] = *reinterpret_cast<const bf16x8_t*>(sa + a_row0 + (r - 4) * 32 * ROW_BYTES + piece);
   };
 
   // even waves touch the A rows, odd waves the Bm rows (one 4-byte load per row and step: a row's
@@ -136,106 +141,123 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs a) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  // One K step of 64: 64 MFMAs per wave.  The instruction stream is laid out by hand
-  // (sched_group_barrier): the LDS fills of the next step first, then two MFMAs for
-  // every fragment read of the following 16 K -- with one wave per SIMD nothing else
-  // would cover the LDS latency.  The last 16 MFMAs of a step need registers only, so
-  // the compiler may run them behind the barrier, over the first reads of the next stage.
   const int nk = a.K / TK;
-  bf16x8_t af[2][4], bfr[2][4];
-  auto mfma16 = [&](int buf) {
+  // MFMAs 2n and 2n + 1 of the 16 of one K piece (i-major).  The Bm fragment is the instruction's
+  // first operand: the products and their order are the same, and the 32x32 block comes out with
+  // a lane holding four consecutive columns of one C row per register quad (see the epilogue).
+  auto mfma2 = [&](int buf, int n) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-      for (int j = 0; j < 4; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][i], bfr[buf][j], acc[i][j], 0, 0, 0);
+    for (int m = 2 * n; m < 2 * n + 2; ++m)
+      acc[m >> 2][m & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[buf][m & 3], af[buf][m >> 2], acc[m >> 2][m & 3], 0, 0, 0);
   };
   // The touch is a 4-byte load whose value nobody needs.  Written as an instruction so that the
   // compiler neither drops it nor waits for it: pf_val is its own register for the whole loop (the
   // operand is read-write, and the value is consumed once after the loop, behind a full wait), so a
   // late return cannot land in a register that means something else.  Unconditional (a clamped
-  // step, row 0 without a duty): a K step stays one basic block.
+  // step, row 0 without a duty).
   auto touch = [&](int ks) {
     const int kpf = ks + kPrefetchSteps < nk ? ks + kPrefetchSteps : nk - 1;
     const uint16_t* p = pf_ptr + kpf * TK;
     asm volatile("global_load_dword %0, %1, off" : "+v"(pf_val) : "v"(p) : "memory");
   };
-  auto compute_step = [&](const uint8_t* sa, const uint8_t* sb) {  // frags of kk = 0 are already in af[0], bfr[0]
+  auto pin = [] { __builtin_amdgcn_sched_barrier(0); };
+
+  // One K step, entered with every wave past the barrier that ended the step before.  Ring: step i
+  // computes on tiles 2i (A) and 2i+1 (Bm); the slots of step i-1 are free now and take tiles 2i+3 (Bm of the next step) and
+  // 2i+4 (A of the step after).  Every step is the same straight line: the first one runs the
+  // "K piece 3 of the step before" on zeroed fragments (+0 added to +0), and the last two fetch
+  // a tile nobody reads (the source clamped to the last K step, the slot free) instead of branching.
+  auto step = [&](int ks, int sa, int sb, int sb_next, int sa_after) {
+    const uint8_t* pa = smem + sa * SLOT_BYTES;
+    const uint8_t* pb = smem + sb * SLOT_BYTES;
+    const uint16_t* src_b = Bg + static_cast<size_t>(ks + 1 < nk ? ks + 1 : nk - 1) * TK;
+    const uint16_t* src_a = Ag + static_cast<size_t>(ks + 2 < nk ? ks + 2 : nk - 1) * TK;
+    // K piece 3 of the step before (registers only) over this step's first fragment reads and the Bm fills
 #pragma unroll
-    for (int kk = 0; kk < 3; ++kk) {
-      read_frags(af[(kk + 1) & 1], bfr[(kk + 1) & 1], sa, sb, kk + 1);
-      mfma16(kk & 1);
+    for (int n = 0; n < 8; ++n) {
+      mfma2(1, n);
+      read1(0, pa, pb, 0, n);
+      fill1(sb_next, src_b, n);
+      pin();
     }
-    mfma16(1);
+#pragma unroll
+    for (int n = 0; n < 8; ++n) {
+      mfma2(0, n);
+      read1(1, pa, pb, 1, n);
+      fill1(sa_after, src_a, n);
+      pin();
+    }
+    // behind the last fill of the step (a touch in front of fills holds them up: loads return in
+    // order); on even steps, for two steps, so that every other step ends without waiting for one
+    if ((ks & 1) == 0) { touch(ks); touch(ks + 1); }
+#pragma unroll
+    for (int n = 0; n < 8; ++n) {
+      mfma2(1, n);
+      read1(0, pa, pb, 2, n);
+      pin();
+    }
+#pragma unroll
+    for (int n = 0; n < 8; ++n) {
+      mfma2(0, n);
+      read1(1, pa, pb, 3, n);
+      pin();
+    }
   };
-  // Ring schedule.  Step i computes on tiles 2i (A) and 2i+1 (Bm).  At its start the slots of
-  // step i-1 are free (every wave is past the barrier) and take tiles 2i+3 (Bm of the next step)
-  // and 2i+4 (A of the step after); at its end everything requested has landed.
-  fill_tile(0, false, 0);
-  fill_tile(1, true, 0);
-  if (nk > 1) fill_tile(2, false, TK);
+
+  // Prologue: A(0), Bm(0), A(1).
+#pragma unroll
+  for (int i = 0; i < 8; ++i) fill1(0, Ag, i);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) fill1(1, Bg, i);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) fill1(2, Ag + (nk > 1 ? TK : 0), i);
   __builtin_amdgcn_s_waitcnt(0);  // everything outstanding, the LDS fills included
   __syncthreads();
   int sa = 0, sb = 1;  // slots of the current step's tiles
-  read_frags(af[0], bfr[0], smem, smem + SLOT_BYTES, 0);
-  int ks = 0;
-  for (; ks + 2 < nk; ++ks) {
+#pragma unroll
+  for (int r = 0; r < 4; ++r)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { af[1][r][e] = 0; bfr[1][r][e] = 0; }
+  for (int ks = 0; ks + 1 < nk; ++ks) {
     const int sb_next = sb + 2 >= NSLOT ? sb + 2 - NSLOT : sb + 2;
     const int sa_next = sa + 2 >= NSLOT ? sa + 2 - NSLOT : sa + 2;
     const int sa_after = sa + 4 >= NSLOT ? sa + 4 - NSLOT : sa + 4;
-    fill_tile(sb_next, true, (ks + 1) * TK);
-    __builtin_amdgcn_sched_barrier(0);  // the Bm fills go first: they are read first
-    fill_tile(sa_after, false, (ks + 2) * TK);
-    touch(ks);
-    compute_step(smem + sa * SLOT_BYTES, smem + sb * SLOT_BYTES);
-#pragma unroll
-    for (int n = 0; n < 24; ++n) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);  // MFMA
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // DS read
-    }
-    __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);
+    step(ks, sa, sb, sb_next, sa_after);
     // LDS reads done, and every load of this wave has landed (vmcnt(0)), the A tile requested in
     // this step included.  A partial wait that left that tile and the touch out -- "all but the
     // newest nine", counting on loads retiring in issue order -- produced blocks of 32 wrong rows
     // whenever the kernel really waited here (operands streaming from HBM at full width): register
-    // loads and LDS fills do not retire in one order.  With L2 warmed by the touches the full wait
-    // costs nothing measurable at any width.
+    // loads and LDS fills do not retire in one order.
     __builtin_amdgcn_s_waitcnt(0x0070);
     __builtin_amdgcn_s_barrier();  // bare: __syncthreads() carries a release fence, i.e. a wait for every load in flight
     sa = sa_next;
     sb = sb_next;
-    read_frags(af[0], bfr[0], smem + sa * SLOT_BYTES, smem + sb * SLOT_BYTES, 0);
   }
-  if (ks + 1 < nk) {  // last but one step: only the last Bm tile is left to fetch
-    const int sb_next = sb + 2 >= NSLOT ? sb + 2 - NSLOT : sb + 2;
-    const int sa_next = sa + 2 >= NSLOT ? sa + 2 - NSLOT : sa + 2;
-    fill_tile(sb_next, true, (ks + 1) * TK);
-    compute_step(smem + sa * SLOT_BYTES, smem + sb * SLOT_BYTES);
-    __builtin_amdgcn_s_waitcnt(0);
-    __syncthreads();
-    sa = sa_next;
-    sb = sb_next;
-    read_frags(af[0], bfr[0], smem + sa * SLOT_BYTES, smem + sb * SLOT_BYTES, 0);
-    ++ks;
-  }
-  compute_step(smem + sa * SLOT_BYTES, smem + sb * SLOT_BYTES);  // last step: nothing left to fetch
+  step(nk - 1, sa, sb, sb + 2 >= NSLOT ? sb + 2 - NSLOT : sb + 2, sa + 4 >= NSLOT ? sa + 4 - NSLOT : sa + 4);
+#pragma unroll
+  for (int n = 0; n < 8; ++n) mfma2(1, n);  // K piece 3 of the last step
   __builtin_amdgcn_s_waitcnt(0);
   pf_sink ^= pf_val;
 
   if (pf_sink == 0x9e3779b9u && a.M < 0) a.C[0] = static_cast<uint16_t>(pf_sink);  // keeps the touches alive; never taken
 
   // ---- epilogue: fp32 -> bf16, row-major C ----
-  // 32x32 block layout: lane l, register v -> row 8*(v/4) + 4*(l/32) + v%4, column l%32
+  // With the Bm fragment as first operand a 32x32 block is held transposed: lane l has C row
+  // l % 32, register v column 8 (v / 4) + 4 (l / 32) + v % 4 -- four consecutive columns per
+  // register quad, one 8-byte store each (64 stores per lane instead of 256 two-byte ones).
   uint16_t* Cg = a.C + (static_cast<size_t>(tm) * TM + wm * 128) * a.N + static_cast<size_t>(tn) * TN + wn * 128;
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
     for (int j = 0; j < 4; ++j)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int row = i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-        const int col = j * 32 + (lane & 31);
-        Cg[static_cast<size_t>(row) * a.N + col] = (uint16_t)f32_to_bf16(acc[i][j][v]);
+      for (int q = 0; q < 4; ++q) {
+        const int row = i * 32 + (lane & 31);
+        const int col = j * 32 + 8 * q + 4 * (lane >> 5);
+        uint2 v;
+        v.x = pack_bf16(acc[i][j][4 * q], acc[i][j][4 * q + 1]);
+        v.y = pack_bf16(acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+        *reinterpret_cast<uint2*>(Cg + static_cast<size_t>(row) * a.N + col) = v;
       }
 }
 
