@@ -400,7 +400,16 @@ int vte_vstream_wait_event(vte_vstream* vs, vte_token event);
 /* A token is satisfied when its launch has been observed complete (Sec. 4.2, 4.4); token 0
  * and tokens of finished launches are satisfied.  query never blocks; wait blocks the caller
  * (not the dispatcher) until the token is satisfied and makes the dispatcher record a
- * completion behind the launch if none covers it yet.  Callable from any thread. */
+ * completion behind the launch if none covers it yet.  Callable from any thread.
+ * Failures.  A launch whose completion reports a device error, an operation whose backend
+ * submission failed 8 times in a row (Sec. 4.4: until then it stays ready), and every operation
+ * that depends on a failed one are retired as FAILED: their tokens count as done (nothing
+ * waits for ever), and vte_token_wait / vte_token_query (*done = 1) / vte_vstream_sync return
+ * the failure's code (VTE_EHIP) with its message and HIP code in vte_last_error() /
+ * vte_last_hip_error() of the calling thread.  vte_vstream_sync, having reported a failed
+ * tail, empties the tail: later submissions do not inherit the failure.  vte_device_sync
+ * returns the first failure that no earlier vte_device_sync has returned.  After a device
+ * fault HIP itself stays in error: expect every later launch of the process to fail. */
 int vte_token_query(vte_ctx* ctx, vte_token token, int* done);
 int vte_token_wait(vte_ctx* ctx, vte_token token);
 int vte_vstream_sync(vte_vstream* vs); /* waits on the stream tail */
@@ -549,7 +558,9 @@ typedef struct vte_op_record {
 typedef struct vte_stats_t {
   uint64_t submitted, completed, leases_opened, leases_reused, lease_conflicts,
       stale_proposals, submit_failures, gates_closed, reservations,
-      completion_records; /* stream markers made to observe completions (PIPELINED: far fewer than launches) */
+      completion_records, /* stream markers made to observe completions (PIPELINED: far fewer than launches) */
+      failed;             /* operations retired as failed (device error behind their completion, a submission
+                             that kept failing, a predecessor that failed) */
 } vte_stats_t;
 /* Copies the counters since vte_init or the last vte_stats_reset. */
 int vte_stats(vte_ctx* ctx, vte_stats_t* out);
@@ -561,6 +572,8 @@ int vte_stats_reset(vte_ctx* ctx);
 /* ---- fake backend hooks (VTE_BACKEND_FAKE only; VTE_ESTATE otherwise) ---------- */
 /* With the fake backend a submitted op stays in flight until completed here. */
 int vte_fake_complete(vte_ctx* ctx, vte_token token);
+/* Completes the op as vte_fake_complete does, with its completion reporting a device error. */
+int vte_fake_complete_error(vte_ctx* ctx, vte_token token);
 int vte_fake_set_autocomplete(vte_ctx* ctx, int on); /* 1: ops complete as soon as submitted */
 int vte_fake_fail_next_submits(vte_ctx* ctx, int n); /* next n backend submissions fail */
 typedef struct vte_fake_log_entry {

@@ -27,10 +27,11 @@ int FakeBackend::submit(const vte_desc* d, void*, int pctx, vte_token tok, bool,
   return VTE_OK;
 }
 
-bool FakeBackend::complete(vte_token tok) {
+bool FakeBackend::complete(vte_token tok, bool with_error) {
   for (size_t i = 0; i < open_.size(); ++i) {
     if (open_[i]->tok == tok) {
       open_[i]->done = true;
+      open_[i]->error = with_error;
       open_.erase(open_.begin() + i);
       return true;
     }

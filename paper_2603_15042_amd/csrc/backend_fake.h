@@ -10,7 +10,7 @@
 namespace vte {
 class FakeBackend : public Backend {
  public:
-  struct Completion { vte_token tok; bool done; };
+  struct Completion { vte_token tok; bool done; bool error = false; };
   bool is_fake() const override { return true; }
   int init(int, int* cu_count) override { if (cu_count && *cu_count <= 0) *cu_count = 256; return VTE_OK; }
   int make_current() override { return VTE_OK; }
@@ -23,14 +23,20 @@ class FakeBackend : public Backend {
   int record(void*, void**) override { return VTE_ESTATE; }
   double elapsed(void*) override { return -1.0; }
   int wait_on(void* stream, void* completion, int completion_pctx) override;
-  bool is_done(void* c) override { return static_cast<Completion*>(c)->done; }
+  int status(void* c) override {
+    const Completion* k = static_cast<Completion*>(c);
+    if (!k->done) return 0;
+    if (!k->error) return 1;
+    set_error("fake backend: injected device error", 719);
+    return VTE_EHIP;
+  }
   void release(void* c) override { delete static_cast<Completion*>(c); }
   int sync_stream(void*) override { return VTE_OK; }
   int time_launches(const vte_desc*, void*, int, int, double* sec) override { *sec = 0; return VTE_ESTATE; }
   int prepare_kernel(const vte_desc*) override { return VTE_OK; }
 
   // driven by the vte_fake_* calls (runtime lock held)
-  bool complete(vte_token tok);
+  bool complete(vte_token tok, bool with_error = false);
   bool autocomplete = false;
   int fail_next = 0;
   std::vector<vte_fake_log_entry> log;

@@ -135,9 +135,14 @@ class HipBackend : public Backend {
     VTE_HIP(hipStreamWaitEvent(static_cast<hipStream_t>(stream), static_cast<Completion*>(completion)->done, 0));
     return VTE_OK;
   }
-  bool is_done(void* completion) override {
+  int status(void* completion) override {
     SlowCall sc("hipEventQuery");
-    return hipEventQuery(static_cast<Completion*>(completion)->done) != hipErrorNotReady;
+    const hipError_t e = hipEventQuery(static_cast<Completion*>(completion)->done);
+    if (e == hipSuccess) return 1;
+    if (e == hipErrorNotReady) return 0;
+    // a launch failure or a fault behind this event: the work will not finish, and says why
+    set_error(std::string("hipEventQuery: ") + hipGetErrorString(e), (int)e);
+    return VTE_EHIP;
   }
   void release(void* completion) override {
     Completion* c = static_cast<Completion*>(completion);

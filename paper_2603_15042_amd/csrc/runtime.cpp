@@ -23,6 +23,28 @@ namespace {
 
 using Lock = std::unique_lock<std::mutex>;
 
+constexpr int kMaxSubmitRetries = 8;    // backend submissions of one op that may fail before the op is failed
+constexpr int kMaxRecordRetries = 8;    // the same for completion records on one pCtx
+constexpr size_t kMaxFailedKept = 1u << 16;
+
+// Runtime lock held, on the thread where the backend call just failed: the message and HIP code
+// that set_error left there are copied into the context, under the token they belong to.
+void note_failure(vte_ctx* c, vte_token tok, int rc, const char* fallback = nullptr) {
+  vte_ctx::Failure f{rc, rc == VTE_EHIP ? g_hip_err : 0, fallback ? std::string(fallback) : g_err};
+  c->failed[tok] = f;
+  if (c->failed.size() > kMaxFailedKept) c->failed.erase(c->failed.begin());  // oldest token first
+  if (!c->failure_unreported) { c->failure_unreported = true; c->first_unreported = tok; }
+  ++c->stats.failed;
+}
+
+// Hands the failure recorded for `tok` to the calling thread; VTE_OK if there is none.
+int report_failure(vte_ctx* c, vte_token tok) {
+  auto it = c->failed.find(tok);
+  if (it == c->failed.end()) return VTE_OK;
+  set_error(it->second.msg, it->second.hip);
+  return it->second.rc;
+}
+
 void bump(vte_ctx* c) {  // runtime lock held: something changed from outside
   ++c->change_seq;
   c->cv_work.notify_all();
@@ -164,9 +186,10 @@ void record_op(vte_ctx* c, const Op* op) {
   r.gpu_seconds = op->gpu_seconds;
 }
 
-void complete_op(vte_ctx* c, Op* op) {
+void complete_op(vte_ctx* c, Op* op, int rc = VTE_OK) {
   op->state = kDone;
   op->t_done = c->now();
+  if (rc != VTE_OK) note_failure(c, op->tok, rc);
   if (op->completion) {
     op->gpu_seconds = c->backend->elapsed(op->completion);
     c->backend->release(op->completion);
@@ -208,13 +231,29 @@ void complete_op(vte_ctx* c, Op* op) {
 bool poll_completions(vte_ctx* c) {
   if (c->inflight.empty()) return false;
   const int np = c->pool.size();
-  std::vector<int> frontier(np, -1);
+  std::vector<int> frontier(np, -1), first_bad(np, -1);
   std::vector<char> blocked(np, 0);
+  std::string bad_msg;
+  int bad_hip = 0;
   for (size_t i = 0; i < c->inflight.size(); ++i) {
     Op* op = c->inflight[i];
     if (blocked[op->pctx] || !op->completion) continue;
-    if (c->backend->is_done(op->completion)) frontier[op->pctx] = static_cast<int>(i);
-    else blocked[op->pctx] = 1;
+    const int st = c->backend->status(op->completion);
+    if (st == 0) { blocked[op->pctx] = 1; continue; }
+    frontier[op->pctx] = static_cast<int>(i);
+    if (st < 0 && first_bad[op->pctx] < 0) {
+      // The device reported an error behind this record.  The record covers this launch and the
+      // unrecorded ones of its pCtx in front of it (back to the record before): all of them are
+      // retired as failed, since which one faulted is not known.
+      int lo = static_cast<int>(i);
+      for (int k = static_cast<int>(i) - 1; k >= 0; --k) {
+        if (c->inflight[k]->pctx != op->pctx) continue;
+        if (c->inflight[k]->completion) break;
+        lo = k;
+      }
+      first_bad[op->pctx] = lo;
+      if (bad_msg.empty()) { bad_msg = g_err; bad_hip = g_hip_err; }
+    }
   }
   bool any = false;
   std::vector<Op*> keep;
@@ -226,12 +265,35 @@ bool poll_completions(vte_ctx* c) {
     else keep.push_back(op);
   }
   if (!done.empty()) {
+    std::vector<int> rcs;
+    rcs.reserve(done.size());
+    for (size_t i = 0; i < c->inflight.size(); ++i) {
+      const Op* op = c->inflight[i];
+      if (static_cast<int>(i) > frontier[op->pctx]) continue;
+      rcs.push_back(first_bad[op->pctx] >= 0 && static_cast<int>(i) >= first_bad[op->pctx] ? VTE_EHIP : VTE_OK);
+    }
     c->inflight.swap(keep);
-    for (Op* op : done) complete_op(c, op);
+    for (size_t i = 0; i < done.size(); ++i) {
+      if (rcs[i] != VTE_OK) set_error(bad_msg, bad_hip);  // what note_failure copies
+      complete_op(c, done[i], rcs[i]);
+    }
     any = true;
     c->cv_done.notify_all();
   }
   return any;
+}
+
+// Retires every in-flight launch of pCtx `p` as failed (its stream no longer takes a completion
+// record, so nothing would ever be observed).  The calling thread's error is what gets recorded.
+void fail_inflight_on(vte_ctx* c, int p, int rc) {
+  std::vector<Op*> keep, bad;
+  for (Op* op : c->inflight) (op->pctx == p ? bad : keep).push_back(op);
+  if (bad.empty()) return;
+  const std::string msg = g_err;
+  const int hip = g_hip_err;
+  c->inflight.swap(keep);
+  for (Op* op : bad) { set_error(msg, hip); complete_op(c, op, rc); }
+  c->cv_done.notify_all();
 }
 
 // Give the newest unrecorded launch of a pCtx a completion record when it is
@@ -258,10 +320,15 @@ void flush_records(vte_ctx* c) {
     if (!op) continue;
     if (recorded[p] > 0 && lazy[p] < pile && !urgent[p]) continue;
     void* comp = nullptr;
-    if (c->backend->record(c->pool.at(p).stream, &comp) == VTE_OK) {
+    const int rc = c->backend->record(c->pool.at(p).stream, &comp);
+    if (rc == VTE_OK) {
       op->completion = comp;
       c->lazy_tail[p] = nullptr;
       ++c->stats.completion_records;
+      c->record_failures[p] = 0;
+    } else if (rc == VTE_EHIP && ++c->record_failures[p] >= kMaxRecordRetries) {
+      c->record_failures[p] = 0;
+      fail_inflight_on(c, p, rc);  // the stream is dead: its launches are reported as failed instead of never
     }
   }
 }
@@ -472,9 +539,55 @@ void eligible_set(vte_ctx* c, const Op* op, int pinned, std::vector<int>* out) {
 
 bool planned_round(vte_ctx* c, const std::vector<vte_ready_op>& ready, const std::vector<Op*>& ready_ops);
 
+// Takes the head of a vstream's queue out as failed: its token is retired with the error, whoever
+// waits for it is woken.  The calling thread's error is what gets recorded unless `why` is given.
+void fail_head(vte_ctx* c, vte_vstream* vs, int rc, const char* why = nullptr) {
+  Op* op = vs->queue.front();
+  vs->queue.pop_front();
+  note_failure(c, op->tok, rc, why);
+  c->live.erase(op->tok);
+  delete op;
+  if (vs->tpot > 0 && vs->queue.empty() && vs->unfinished_bound == 0) vs->t_idle = c->now();
+  c->cv_done.notify_all();
+}
+
+// An op whose predecessor failed fails with it (Sec. 4.2: it may run only after its predecessors
+// completed, and they never will).  Returns true if anything was taken out.
+bool purge_failed_dependants(vte_ctx* c) {
+  if (c->failed.empty()) return false;
+  bool any = false;
+  for (vte_vstream* vs : c->vstreams) {
+    if (!vs) continue;
+    while (!vs->queue.empty()) {
+      const Op* op = vs->queue.front();
+      const vte_ctx::Failure* cause = nullptr;
+      for (vte_token t : op->deps) {
+        auto it = c->failed.find(t);
+        if (it != c->failed.end()) { cause = &it->second; break; }
+      }
+      if (!cause) break;
+      const std::string why = "a predecessor failed: " + cause->msg;
+      set_error(why, cause->hip);
+      fail_head(c, vs, cause->rc);
+      any = true;
+    }
+  }
+  return any;
+}
+
+// A backend submission of the head of `vs` failed: it stays ready (Sec. 4.4) until it has failed
+// kMaxSubmitRetries times, then it is failed for good so that its waiters return.
+void submission_failed(vte_ctx* c, Op* op, int rc) {
+  if (rc != VTE_EHIP || op->vs < 0) return;
+  if (++op->submit_failures < kMaxSubmitRetries) return;
+  vte_vstream* vs = c->vstreams[op->vs];
+  if (!vs->queue.empty() && vs->queue.front() == op) fail_head(c, vs, rc);
+}
+
 // One dispatch round: gather the ready heads, let the policy pick and select,
 // validate, submit.  Returns true if something was bound.
 bool dispatch_round(vte_ctx* c) {
+  if (purge_failed_dependants(c)) return true;
   std::vector<vte_ready_op> ready;
   std::vector<Op*> ready_ops;
   for (vte_vstream* vs : c->vstreams) {
@@ -531,7 +644,7 @@ bool dispatch_round(vte_ctx* c) {
     // the proposal is tentative: it must be one of E and still valid
     if (std::find(eligible.begin(), eligible.end(), sel) == eligible.end()) { ++c->stats.stale_proposals; continue; }
     int rc = bind_and_submit(c, op, sel, c->cfg.mode != VTE_MODE_PIPELINED);
-    if (rc != VTE_OK) continue;  // op remains ready for rescheduling
+    if (rc != VTE_OK) { submission_failed(c, op, rc); continue; }  // op remains ready for rescheduling (a bounded number of times)
     c->vstreams[op->vs]->queue.pop_front();
     bound_any = true;
     for (int i = 0; i < c->pool.size(); ++i) fill_info(c->pool, i, &infos[i]);
@@ -704,7 +817,8 @@ bool planned_round(vte_ctx* c, const std::vector<vte_ready_op>& ready, const std
   std::vector<char> handled(n, 0);
   auto bind = [&](int i, int pctx) {
     Op* op = ready_ops[i];
-    if (bind_and_submit(c, op, pctx, c->cfg.mode != VTE_MODE_PIPELINED) != VTE_OK) return false;
+    const int rc = bind_and_submit(c, op, pctx, c->cfg.mode != VTE_MODE_PIPELINED);
+    if (rc != VTE_OK) { submission_failed(c, op, rc); return false; }
     c->vstreams[op->vs]->queue.pop_front();
     bound_any = true;
     return true;
@@ -887,6 +1001,7 @@ int vte_init(vte_ctx** out, int device, const vte_pool_cfg* user_cfg) {
   }
   c->ring.resize(static_cast<size_t>(cfg.stats_capacity));
   c->lazy_tail.assign(c->pool.size(), nullptr);
+  c->record_failures.assign(c->pool.size(), 0);
   c->dispatcher = std::thread(dispatcher_main, c);
   *out = c;
   return VTE_OK;
@@ -904,6 +1019,10 @@ int vte_device_sync(vte_ctx* c) {
     return true;
   });
   --c->waiters_all;
+  if (c->failure_unreported) {  // something failed since the last device-wide wait: say so once, here
+    c->failure_unreported = false;
+    return report_failure(c, c->first_unreported);
+  }
   return VTE_OK;
 }
 
@@ -1134,19 +1253,19 @@ int vte_token_query(vte_ctx* c, vte_token t, int* done) {
   Lock lk(c->mu);
   if (t >= c->next_token) { set_error("token was never issued"); return VTE_EINVAL; }
   *done = token_done(c, t) ? 1 : 0;
-  return VTE_OK;
+  return *done ? report_failure(c, t) : VTE_OK;
 }
 
 int vte_token_wait(vte_ctx* c, vte_token t) {
   if (!c) { set_error("null ctx"); return VTE_EINVAL; }
   Lock lk(c->mu);
   if (t >= c->next_token) { set_error("token was never issued"); return VTE_EINVAL; }
-  if (token_done(c, t)) return VTE_OK;
+  if (token_done(c, t)) return report_failure(c, t);
   c->awaited.push_back(t);
   bump(c);  // the dispatcher sees to it that a completion record covers the awaited launch
   c->cv_done.wait(lk, [&] { return token_done(c, t); });
   c->awaited.erase(std::find(c->awaited.begin(), c->awaited.end(), t));
-  return VTE_OK;
+  return report_failure(c, t);
 }
 
 int vte_vstream_sync(vte_vstream* vs) {
@@ -1157,7 +1276,14 @@ int vte_vstream_sync(vte_vstream* vs) {
     Lock lk(c->mu);
     t = vs->tail;
   }
-  return vte_token_wait(c, t);
+  const int rc = vte_token_wait(c, t);
+  if (rc != VTE_OK && rc != VTE_EINVAL) {
+    // the failure has been handed to the caller: the stream starts again from an empty tail, so
+    // that what is submitted from now on does not inherit it
+    Lock lk(c->mu);
+    if (vs->tail == t) vs->tail = 0;
+  }
+  return rc;
 }
 
 int vte_vstream_destroy(vte_vstream* vs) {
@@ -1408,6 +1534,15 @@ int vte_fake_complete(vte_ctx* c, vte_token t) {
   if (!fb) return c ? VTE_ESTATE : VTE_EINVAL;
   Lock lk(c->mu);
   if (!fb->complete(t)) { set_error("fake_complete: token is not in flight"); return VTE_EINVAL; }
+  bump(c);
+  return VTE_OK;
+}
+
+int vte_fake_complete_error(vte_ctx* c, vte_token t) {
+  FakeBackend* fb = fake_of(c);
+  if (!fb) return c ? VTE_ESTATE : VTE_EINVAL;
+  Lock lk(c->mu);
+  if (!fb->complete(t, true)) { set_error("fake_complete_error: token is not in flight"); return VTE_EINVAL; }
   bump(c);
   return VTE_OK;
 }

@@ -60,7 +60,9 @@ class Backend {
   virtual double elapsed(void* completion) = 0;  // seconds, -1 if the launch was not timed
   // Make later work on `stream` wait (on the device) for `completion`.
   virtual int wait_on(void* stream, void* completion, int completion_pctx) = 0;
-  virtual bool is_done(void* completion) = 0;
+  // 0: not finished yet; 1: finished; < 0: the device reported an error for it (VTE_EHIP, message and
+  // HIP code left with set_error on the calling thread).  Never blocks.
+  virtual int status(void* completion) = 0;
   virtual void release(void* completion) = 0;
   virtual int sync_stream(void* stream) = 0;
   // Seconds per launch of `d` on `stream`, device-timed.
@@ -88,6 +90,7 @@ struct Op {
   int pctx = -1;
   void* completion = nullptr;
   bool ready_marked = false;
+  int submit_failures = 0;  // backend submissions of this op that failed so far
   double t_submit = 0, t_ready = 0, t_bound = 0, t_done = 0, gpu_seconds = -1;
 };
 
@@ -156,6 +159,15 @@ struct vte_ctx {
   int keep_free = 0;
 
   std::map<std::pair<uint64_t, int>, double> profiles;
+
+  // Failures observed by the dispatcher (a completion that reports a device error, a submission
+  // that keeps failing): the token is retired as failed, the error is kept here and handed to
+  // whoever waits for the token, its vstream or the device, on that caller's thread.
+  struct Failure { int rc; int hip; std::string msg; };
+  std::map<vte_token, Failure> failed;
+  bool failure_unreported = false;   // a failure no vte_device_sync has returned yet
+  vte_token first_unreported = 0;
+  std::vector<int> record_failures;  // per pCtx: consecutive completion records that could not be made
 
   vte_stats_t stats{};
   std::vector<vte_op_record> ring;

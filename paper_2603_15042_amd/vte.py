@@ -94,7 +94,7 @@ class vte_op_record(C.Structure):
 class vte_stats_t(C.Structure):
     _fields_ = [(n, C.c_uint64) for n in ("submitted", "completed", "leases_opened", "leases_reused",
                                            "lease_conflicts", "stale_proposals", "submit_failures", "gates_closed",
-                                           "reservations", "completion_records")]
+                                           "reservations", "completion_records", "failed")]
 
 
 class vte_tpot_info(C.Structure):
@@ -123,7 +123,7 @@ EXPORTS = [
     "vte_stats_reset", "vte_fake_complete", "vte_fake_set_autocomplete", "vte_fake_fail_next_submits",
     "vte_fake_log", "vte_dispatcher_quiesce", "vte_now", "vte_vstream_set_tpot", "vte_vstream_tpot_info", "vte_submit_batch", "vte_pool_creation_order", "vte_desc_memcpy", "vte_desc_memset32",
     "vte_event_record", "vte_vstream_wait_event", "vte_desc_softmax_prob",
-    "vte_static_scratch_bytes", "vte_lmhead_argmax_static",
+    "vte_static_scratch_bytes", "vte_lmhead_argmax_static", "vte_fake_complete_error",
 ]
 
 _lib = None
@@ -499,6 +499,10 @@ def vte_stats_reset(ctx):
 
 def vte_fake_complete(ctx, token):
     _check(load().vte_fake_complete(ctx, C.c_uint64(token)))
+
+
+def vte_fake_complete_error(ctx, token):
+    _check(load().vte_fake_complete_error(ctx, C.c_uint64(token)))
 
 
 def vte_fake_set_autocomplete(ctx, on):

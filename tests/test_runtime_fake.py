@@ -456,6 +456,81 @@ def test_failed_submission_leaves_op_ready(ctx):
     assert vte.vte_pool_info(ctx, 0).state == vte.VTE_PCTX_IDLE
 
 
+def test_submission_that_always_fails_fails_the_op_and_its_dependants(ctx):
+    """A failed submission leaves the op ready (Sec. 4.4), but not for ever: after a bounded number
+    of attempts the op is retired as failed, its waiters get the backend's error on their own
+    thread, and every op that depends on it fails with it."""
+    vs, other = vte.vte_vstream_create(ctx), vte.vte_vstream_create(ctx)
+    d = norm_desc(ctx)
+    vte.vte_fake_fail_next_submits(ctx, 1 << 20)
+    t1 = vte.vte_submit(vs, d)
+    t2 = vte.vte_submit(vs, d)                         # stream order: depends on t1
+    t3 = vte.vte_submit_after(other, d, [t1])          # cross-stream edge onto t1
+    for t in (t1, t2, t3):
+        with pytest.raises(vte.VteError) as e:
+            vte.vte_token_wait(ctx, t)                 # returns instead of blocking
+        assert e.value.code == vte.VTE_EHIP and "injected submission failure" in str(e.value)
+    with pytest.raises(vte.VteError) as e:
+        vte.vte_token_query(ctx, t2)
+    assert e.value.code == vte.VTE_EHIP and "predecessor failed" in str(e.value)
+    st = vte.vte_stats(ctx)
+    assert st.failed == 3 and st.submit_failures == 8 and st.completed == 0 and st.leases_opened == 0
+    assert vte.vte_fake_log(ctx) == []                 # nothing ever reached the backend
+    assert all(i.state == vte.VTE_PCTX_IDLE and i.outstanding == 0 for i in infos(ctx))
+    # the stream reports its failed tail once and is usable again; so is the device-wide wait
+    with pytest.raises(vte.VteError):
+        vte.vte_vstream_sync(vs)
+    with pytest.raises(vte.VteError) as e:
+        vte.vte_device_sync(ctx)
+    assert e.value.code == vte.VTE_EHIP
+    vte.vte_fake_fail_next_submits(ctx, 0)
+    vte.vte_fake_set_autocomplete(ctx, 1)
+    t4 = vte.vte_submit(vs, d)
+    vte.vte_token_wait(ctx, t4)
+    vte.vte_vstream_sync(vs)
+    vte.vte_device_sync(ctx)                           # the failure was reported; nothing new failed
+    assert vte.vte_stats(ctx).completed == 1
+
+
+def test_completion_that_reports_a_device_error_fails_the_token(ctx):
+    """A completion record that comes back with an error is not a successful launch: the token is
+    retired as failed with the backend's message and HIP code, the lease is released, successors
+    do not run, and the error reaches a caller that was already blocked in the wait."""
+    import threading
+    vs = vte.vte_vstream_create(ctx)
+    d = norm_desc(ctx)
+    t1 = vte.vte_submit(vs, d)
+    t2 = vte.vte_submit(vs, d)
+    vte.vte_dispatcher_quiesce(ctx)
+    assert [e.token for e in vte.vte_fake_log(ctx)] == [t1]     # STRICT: t2 waits for t1
+    got = {}
+
+    def waiter():
+        try:
+            vte.vte_token_wait(ctx, t1)
+            got["rc"] = 0
+        except vte.VteError as e:
+            got["rc"], got["msg"], got["hip"] = e.code, str(e), vte.vte_last_hip_error()
+
+    th = threading.Thread(target=waiter)
+    th.start()
+    vte.vte_fake_complete_error(ctx, t1)
+    th.join(10)
+    assert not th.is_alive()
+    assert got["rc"] == vte.VTE_EHIP and "injected device error" in got["msg"] and got["hip"] == 719
+    with pytest.raises(vte.VteError) as e:
+        vte.vte_token_wait(ctx, t2)                    # never submitted: its predecessor failed
+    assert e.value.code == vte.VTE_EHIP
+    assert [e.token for e in vte.vte_fake_log(ctx)] == [t1]
+    st = vte.vte_stats(ctx)
+    assert st.failed == 2 and st.completed == 1
+    assert all(i.state == vte.VTE_PCTX_IDLE and i.outstanding == 0 for i in infos(ctx))
+    with pytest.raises(vte.VteError) as e:
+        vte.vte_device_sync(ctx)
+    assert e.value.code == vte.VTE_EHIP
+    vte.vte_device_sync(ctx)                           # reported once
+
+
 def test_policy_callbacks_and_stale_proposal(ctx):
     calls = {"pick": 0, "select": 0, "bad": True}
     root = vte.vte_pool_find(ctx, vte.VTE_PCTX_NODE, 256)
