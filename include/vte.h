@@ -554,6 +554,9 @@ typedef struct vte_op_record {
   double t_bound;    /* descriptor submitted to the backend stream */
   double t_done;     /* completion observed by the dispatcher */
   double gpu_seconds; /* device time of the launch (event pair on its stream), or -1 */
+  double gpu_begin;   /* timed launches: begin and end of the kernel on the device clock, seconds since
+                         vte_init (float32 milliseconds inside: about 1 us of resolution per 8 s); else -1 */
+  double gpu_end;
 } vte_op_record;
 typedef struct vte_stats_t {
   uint64_t submitted, completed, leases_opened, leases_reused, lease_conflicts,

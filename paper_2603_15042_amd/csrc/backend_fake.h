@@ -22,6 +22,7 @@ class FakeBackend : public Backend {
              void** completion) override;  // always records: tests complete launches one by one
   int record(void*, void**) override { return VTE_ESTATE; }
   double elapsed(void*) override { return -1.0; }
+  double device_time(void*, bool) override { return -1.0; }
   int wait_on(void* stream, void* completion, int completion_pctx) override;
   int status(void* c) override {
     const Completion* k = static_cast<Completion*>(c);

@@ -45,6 +45,7 @@ class HipBackend : public Backend {
   ~HipBackend() override {
     for (hipEvent_t e : free_events_) (void)hipEventDestroy(e);
     for (hipEvent_t e : free_timing_events_) (void)hipEventDestroy(e);
+    if (ref_) (void)hipEventDestroy(ref_);
   }
   bool is_fake() const override { return false; }
   int init(int device, int* cu_count) override {
@@ -57,6 +58,10 @@ class HipBackend : public Backend {
     VTE_HIP(hipGetDeviceProperties(&prop, device));
     if (cu_count && *cu_count <= 0) *cu_count = prop.multiProcessorCount;
     max_lds_ = static_cast<uint32_t>(prop.sharedMemPerBlock);
+    // origin of the device clock that device_time() reports against
+    VTE_HIP(hipEventCreate(&ref_));
+    VTE_HIP(hipEventRecord(ref_, nullptr));
+    VTE_HIP(hipEventSynchronize(ref_));
     return VTE_OK;
   }
   int make_current() override { VTE_HIP(hipSetDevice(device_)); return VTE_OK; }
@@ -131,6 +136,13 @@ class HipBackend : public Backend {
     if (hipEventElapsedTime(&ms, c->start, c->done) != hipSuccess) return -1.0;
     return static_cast<double>(ms) * 1e-3;
   }
+  double device_time(void* completion, bool end) override {
+    Completion* c = static_cast<Completion*>(completion);
+    if (!c->start || !ref_) return -1.0;
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, ref_, end ? c->done : c->start) != hipSuccess) return -1.0;
+    return static_cast<double>(ms) * 1e-3;
+  }
   int wait_on(void* stream, void* completion, int) override {
     VTE_HIP(hipStreamWaitEvent(static_cast<hipStream_t>(stream), static_cast<Completion*>(completion)->done, 0));
     return VTE_OK;
@@ -197,6 +209,7 @@ class HipBackend : public Backend {
     return VTE_OK;
   }
   int device_ = 0;
+  hipEvent_t ref_ = nullptr;
   uint32_t max_lds_ = 65536;
   std::vector<hipEvent_t> free_events_;
   std::vector<hipEvent_t> free_timing_events_;

@@ -183,7 +183,7 @@ void record_op(vte_ctx* c, const Op* op) {
   r.token = op->tok; r.vstream = op->vs; r.klass = op->klass; r.kernel = op->desc->kernel;
   r.pctx = op->pctx; r.width = c->pool.at(op->pctx).width;
   r.t_submit = op->t_submit; r.t_ready = op->t_ready; r.t_bound = op->t_bound; r.t_done = op->t_done;
-  r.gpu_seconds = op->gpu_seconds;
+  r.gpu_seconds = op->gpu_seconds; r.gpu_begin = op->gpu_begin; r.gpu_end = op->gpu_end;
 }
 
 void complete_op(vte_ctx* c, Op* op, int rc = VTE_OK) {
@@ -192,6 +192,10 @@ void complete_op(vte_ctx* c, Op* op, int rc = VTE_OK) {
   if (rc != VTE_OK) note_failure(c, op->tok, rc);
   if (op->completion) {
     op->gpu_seconds = c->backend->elapsed(op->completion);
+    if (op->gpu_seconds >= 0) {
+      op->gpu_begin = c->backend->device_time(op->completion, false);
+      op->gpu_end = c->backend->device_time(op->completion, true);
+    }
     c->backend->release(op->completion);
     op->completion = nullptr;
   }

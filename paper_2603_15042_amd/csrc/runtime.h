@@ -58,6 +58,9 @@ class Backend {
                      void** completion) = 0;
   virtual int record(void* stream, void** completion) = 0;
   virtual double elapsed(void* completion) = 0;  // seconds, -1 if the launch was not timed
+  // Device-clock time of a timed launch's begin (end = false) or end, in seconds since the backend's
+  // init; -1 if the launch was not timed.
+  virtual double device_time(void* completion, bool end) = 0;
   // Make later work on `stream` wait (on the device) for `completion`.
   virtual int wait_on(void* stream, void* completion, int completion_pctx) = 0;
   // 0: not finished yet; 1: finished; < 0: the device reported an error for it (VTE_EHIP, message and
@@ -91,7 +94,7 @@ struct Op {
   void* completion = nullptr;
   bool ready_marked = false;
   int submit_failures = 0;  // backend submissions of this op that failed so far
-  double t_submit = 0, t_ready = 0, t_bound = 0, t_done = 0, gpu_seconds = -1;
+  double t_submit = 0, t_ready = 0, t_bound = 0, t_done = 0, gpu_seconds = -1, gpu_begin = -1, gpu_end = -1;
 };
 
 }  // namespace vte

@@ -47,7 +47,10 @@ def _complement_launch(ctx, gemm_desc, pctx):
         return None
 
 
-def determinism(trials, replays, seed0=0):
+ALL_SECTIONS = ("rmsnorm", "gemv", "gemv_wide", "gemm", "replay")
+
+
+def determinism(trials, replays, seed0=0, sections=ALL_SECTIONS):
     ctx = H.make_ctx(vte.VTE_MODE_STRICT)
     rng = np.random.default_rng(seed0)
     out = {}
@@ -61,13 +64,17 @@ def determinism(trials, replays, seed0=0):
 
     # ---- operator 1: the reduction (RMSNorm 8 x 1024) -------------------------------------------
     print("determinism: RMSNorm 8x1024, %d trials" % trials, file=sys.stderr, flush=True)
+    if "rmsnorm" not in sections:
+        trials_rms = 0
+    else:
+        trials_rms = trials
     rows, cols = 8, 1024
     dx, dg, dy = H.dev_empty((rows, cols)), H.dev_empty((cols,)), H.dev_empty((rows, cols))
     fixed = vte.vte_desc_rmsnorm(ctx, dx, dg, dy, rows, cols, 1e-6)
     resh = {w: vte.vte_desc_rmsnorm_reshaped(ctx, dx, dg, dy, rows, cols, 1e-6, w) for w in widths}
-    r = {"trials": trials, "fixed_mismatched_bits": 0, "fixed_trials_with_mismatch": 0,
+    r = {"trials": trials_rms, "fixed_mismatched_bits": 0, "fixed_trials_with_mismatch": 0,
          "reshaped_mismatched_bits": 0, "reshaped_trials_with_mismatch": 0, "reshaped_max_abs_diff": 0.0}
-    for t in range(trials):
+    for t in range(trials_rms):
         x, g = inputs.rmsnorm_case(seed=seed0 + t, rows=rows, cols=cols)
         dx.copy_(H.to_dev(x)); dg.copy_(H.to_dev(g))
         torch.cuda.synchronize()
@@ -92,13 +99,14 @@ def determinism(trials, replays, seed0=0):
         r["reshaped_trials_with_mismatch"] += int(b > 0)
         d = np.abs(inputs.bf16_to_f32(ref_r) - inputs.bf16_to_f32(got_r)).max()
         r["reshaped_max_abs_diff"] = max(r["reshaped_max_abs_diff"], float(d))
-    out["rmsnorm_8x1024"] = r
+    if trials_rms:
+        out["rmsnorm_8x1024"] = r
 
     # ---- operator 2: GEMV 4096 x 4096 (fp32 sums kept through the LM-head form) --------------------
     N = K = 4096
     W0 = inputs.normal_bf16(seed0, inputs.T_W, (N, K), 0.0, K ** -0.5)
     dW = H.to_dev(W0)
-    for B in (1, 4, 8):
+    for B in ((1, 4, 8) if "gemv" in sections else ()):
         print("determinism: GEMV 4096x4096 batch %d, %d trials" % (B, trials), file=sys.stderr, flush=True)
         dX, dY = H.dev_empty((B, K)), H.dev_empty((B, N))
         tok = torch.zeros(B, dtype=torch.int32, device="cuda")
@@ -145,7 +153,7 @@ def determinism(trials, replays, seed0=0):
         out["gemv_4096x4096_B%d" % B] = r
 
     # ---- operator 2b: the wide batches (fixed structure only: there is no split-K baseline above batch 32) ----
-    for B, Nw in ((32, 4096), (64, 4096), (64, 32064)):
+    for B, Nw in (((32, 4096), (64, 4096), (64, 32064)) if "gemv_wide" in sections else ()):
         print("determinism: GEMV %dx4096 batch %d, %d trials" % (Nw, B, trials), file=sys.stderr, flush=True)
         dWw = dW if Nw == N else H.to_dev(inputs.normal_bf16(seed0 + 7, inputs.T_W, (Nw, K), 0.0, K ** -0.5))
         dX, dY = H.dev_empty((B, K)), H.dev_empty((B, Nw))
@@ -175,7 +183,7 @@ def determinism(trials, replays, seed0=0):
         vte.vte_desc_destroy(fixed); vte.vte_desc_destroy(fixed32)
 
     # ---- operator 3: the co-tenant's own GEMM, at a compute-bound and at an HBM-bound shape -----------
-    for (gm, gn, gk) in ((4096, 4096, 4096), (32768, 256, 8192)):
+    for (gm, gn, gk) in (((4096, 4096, 4096), (32768, 256, 8192)) if "gemm" in sections else ()):
         ntr = max(1, trials // 5)
         print("determinism: GEMM %dx%dx%d, %d trials" % (gm, gn, gk, ntr), file=sys.stderr, flush=True)
         tA = H.to_dev(inputs.normal_bf16(seed0, inputs.T_GEMM_A, (gm, gk)))
@@ -201,6 +209,9 @@ def determinism(trials, replays, seed0=0):
         del tA, tB, tC
 
     # ---- decoding level: one state replayed (reduced vocabulary keeps it short) ------------------------
+    if "replay" not in sections or replays < 1:
+        vte.vte_shutdown(ctx)
+        return out
     print("determinism: decode state replay, %d replays" % replays, file=sys.stderr, flush=True)
     shp = inputs.DecodeShapes(D=4096, Nqkv=6144, F=14336, V=32064)
     w = inputs.decode_weights(seed0, shp)
@@ -258,20 +269,63 @@ def determinism(trials, replays, seed0=0):
 
 
 # ----------------------------------------------------------------------------------------------------
-def cotenancy(seconds, gap_ms, steps_per_burst=128, lead_ms=3.0):
-    shp = inputs.DecodeShapes()
-    w = inputs.decode_weights(0, shp)
+def step_latencies(recs, first_kernel, last_kernel):
+    """Device-clock latency of every decode step in `recs` (op records with timed first and last
+    launches): end of the step's last kernel minus begin of its first.  Seconds."""
+    out, begin = [], None
+    for r in sorted((r for r in recs if r.klass == vte.VTE_CLASS_LATENCY), key=lambda r: r.token):
+        if r.kernel == first_kernel and r.gpu_begin >= 0:
+            begin = r.gpu_begin
+        elif r.kernel == last_kernel and r.gpu_end >= 0 and begin is not None:
+            out.append(r.gpu_end - begin)
+            begin = None
+    return out
+
+
+def overlap_of_tenants(recs, first_kernel, last_kernel):
+    """From the device-clock intervals of the timed launches: how many best-effort launches ran on
+    fewer than all CUs while a decode step was in progress on another pCtx (spatial sharing), and
+    how many ran on the whole device (then the tenants can only have alternated in time)."""
+    steps, begin, pctx = [], None, -1
+    for r in sorted((r for r in recs if r.klass == vte.VTE_CLASS_LATENCY), key=lambda r: r.token):
+        if r.kernel == first_kernel and r.gpu_begin >= 0:
+            begin, pctx = r.gpu_begin, r.pctx
+        elif r.kernel == last_kernel and r.gpu_end >= 0 and begin is not None:
+            steps.append((begin, r.gpu_end, pctx))
+            begin = None
+    side_by_side = whole_device = 0
+    widths = set()
+    for r in recs:
+        if r.klass != vte.VTE_CLASS_BEST_EFFORT or r.gpu_begin < 0:
+            continue
+        if any(b < r.gpu_end and r.gpu_begin < e and p != r.pctx for b, e, p in steps):
+            side_by_side += 1
+            widths.add(int(r.width))
+        elif r.width >= 256:
+            whole_device += 1
+    return {"best_effort_launches_beside_a_decode_step": side_by_side, "their_widths": sorted(widths),
+            "best_effort_launches_alone_on_256": whole_device}
+
+
+def cotenancy(seconds, gap_ms, steps_per_burst=128, lead_ms=3.0, shared=None, modes=("fixed", "late", "late_nohint")):
+    """shared: optional dict with the config-3 weights already made ("w", "wd", "shp") and the GEMM
+    operands ("gA", "gB", "gC")."""
+    shared = shared or {}
+    shp = shared.get("shp") or inputs.DecodeShapes()
+    w = shared.get("w") or inputs.decode_weights(0, shp)
     B, M = 8, 8192
     cfg = vte.vte_pool_cfg_default()
     cfg.mode = vte.VTE_MODE_PIPELINED
     cfg.lookahead = 16
+    # device-clock begin of every step's first launch and end of its last, and the co-tenant's launches
+    cfg.device_timing_mask = (1 << vte.VTE_K_RMSNORM_GATHER) | (1 << vte.VTE_K_ARGMAX_FINISH) | (1 << vte.VTE_K_GEMM)
     torch.zeros(1, device="cuda")
     ctx = vte.vte_init(0, cfg)
-    wd = H.upload_weights(w)
+    wd = shared.get("wd") or H.upload_weights(w)
     ch = H.DecodeChain(ctx, wd, shp, B, feedback=True, fused_gather=True)
-    gA = H.to_dev(inputs.normal_bf16(0, inputs.T_GEMM_A, (M, M)))
-    gB = H.to_dev(inputs.normal_bf16(0, inputs.T_GEMM_B, (M, M)))
-    gC = H.dev_empty((M, M))
+    gA = shared["gA"] if "gA" in shared else H.to_dev(inputs.normal_bf16(0, inputs.T_GEMM_A, (M, M)))
+    gB = shared["gB"] if "gB" in shared else H.to_dev(inputs.normal_bf16(0, inputs.T_GEMM_B, (M, M)))
+    gC = shared["gC"] if "gC" in shared else H.dev_empty((M, M))
     gemm = vte.vte_desc_gemm(ctx, gA, gB, gC, M, M, M)
     tok0 = inputs.tokens(0, inputs.T_TOK0, B, shp.V)
     lat = vte.vte_vstream_create(ctx, vte.VTE_CLASS_LATENCY)
@@ -349,12 +403,18 @@ def cotenancy(seconds, gap_ms, steps_per_burst=128, lead_ms=3.0):
             first_lat.append(lat_recs[i + per - 1].t_done - lat_recs[i].t_submit)
         gw = [r.width for r in recs if r.klass == vte.VTE_CLASS_BEST_EFFORT]
         dw = [r.width for r in recs if r.klass == vte.VTE_CLASS_LATENCY]
-        return {"elapsed_s": elapsed, "gemm_done": gemm_done, "gemm_per_s": gemm_done / elapsed, "bursts": bursts,
+        sl = step_latencies(recs, vte.VTE_K_RMSNORM_GATHER, vte.VTE_K_ARGMAX_FINISH)
+        ov = overlap_of_tenants(recs, vte.VTE_K_RMSNORM_GATHER, vte.VTE_K_ARGMAX_FINISH) if with_gemm and with_decode else None
+        return {"elapsed_s": elapsed, "steps_timed": len(sl),
+                # per step on the device clock: begin of the step's first kernel to end of its last
+                "step_latency_ms_p50": float(np.percentile(sl, 50) * 1e3) if sl else None,
+                "step_latency_ms_p99": float(np.percentile(sl, 99) * 1e3) if sl else None,
+                "step_latency_ms_max": float(np.max(sl) * 1e3) if sl else None,
+                "overlap": ov, "gemm_done": gemm_done, "gemm_per_s": gemm_done / elapsed, "bursts": bursts,
                 "burst_ms_mean": float(np.mean(burst_times) * 1e3) if burst_times else None,
                 "burst_ms_max": float(np.max(burst_times) * 1e3) if burst_times else None,
                 "step_ms_mean": float(np.mean(burst_times) * 1e3 / steps_per_burst) if burst_times else None,
-                # a step's own completion is not observed under pipelined binding: per-step latency over bursts
-                "step_ms_p99": float(np.percentile(burst_times, 99) * 1e3 / steps_per_burst) if burst_times else None,
+                "burst_step_ms_p99": float(np.percentile(burst_times, 99) * 1e3 / steps_per_burst) if burst_times else None,
                 "first_step_ms_mean": float(np.mean(first_lat) * 1e3) if first_lat else None,
                 "first_step_ms_max": float(np.max(first_lat) * 1e3) if first_lat else None,
                 "gemm_widths": {str(k): int(v) for k, v in zip(*np.unique(gw, return_counts=True))} if gw else {},
@@ -364,11 +424,11 @@ def cotenancy(seconds, gap_ms, steps_per_burst=128, lead_ms=3.0):
     res = {"profiles_us": prof, "gap_ms": gap_ms, "steps_per_burst": steps_per_burst, "lead_ms": lead_ms}
     res["solo_gemm"] = run("solo", with_decode=False)
     res["solo_decode"] = run("solo", with_gemm=False)
-    for mode in ("fixed", "late", "late_nohint"):
+    for mode in modes:
         res[mode] = run(mode)
     g0 = res["solo_gemm"]["gemm_per_s"]
     d0 = res["solo_decode"]["burst_ms_mean"]
-    for mode in ("fixed", "late", "late_nohint"):
+    for mode in modes:
         r = res[mode]
         r["norm_gemm"] = r["gemm_per_s"] / g0
         r["norm_decode"] = d0 / r["burst_ms_mean"] if r["burst_ms_mean"] else None
@@ -376,17 +436,42 @@ def cotenancy(seconds, gap_ms, steps_per_burst=128, lead_ms=3.0):
     # the token stream is a function of the start tokens and the number of steps run alone:
     # whatever widths a mode used, the tokens after burst i must equal the solo run's
     ref = res["solo_decode"]["burst_tokens"]
-    for mode in ("fixed", "late", "late_nohint"):
+    for mode in modes:
         got = res[mode]["burst_tokens"]
         m = min(len(ref), len(got))
         res[mode]["bursts_compared"] = m
         res[mode]["bursts_with_token_mismatch"] = sum(int(ref[i] != got[i]) for i in range(m))
-    for mode in ("solo_gemm", "solo_decode", "fixed", "late", "late_nohint"):
+    for mode in ("solo_gemm", "solo_decode") + tuple(modes):
         bt = res[mode].pop("burst_tokens")
         res[mode]["final_tokens"] = bt[-1] if bt else None
     res["gemm_tflops_solo"] = 2 * M ** 3 * g0 / 1e12
     vte.vte_shutdown(ctx)
     return res
+
+
+def config1_latency(ctx, launches=200):
+    """BASELINE config 1: the fixed-structure RMSNorm 8 x 1024 (x ~ N(0,1), gamma ~ U(0.5,1.5), eps 1e-6,
+    seed 0) launched explicitly on one pCtx of every width: host-clock latency of bind + launch +
+    completion per launch (microseconds), and the bits against the 256-CU run."""
+    x, g = inputs.rmsnorm_case(seed=0, rows=8, cols=1024)
+    dx, dg, dy = H.to_dev(x), H.to_dev(g), H.dev_empty((8, 1024))
+    d = vte.vte_desc_rmsnorm(ctx, dx, dg, dy, 8, 1024, 1e-6)
+    out, ref = {}, None
+    for width in (256, 224, 192, 128, 64, 32):
+        p = H.pctx_of_width(ctx, width)
+        for _ in range(10):
+            H.run_on(ctx, d, p)
+        ts = []
+        for _ in range(launches):
+            t0 = time.perf_counter()
+            vte.vte_token_wait(ctx, vte.vte_bind_and_launch(ctx, d, p))
+            ts.append(time.perf_counter() - t0)
+        bits = H.to_bits(dy).copy()
+        ref = bits if ref is None else ref
+        out[str(width)] = {"p50_us": round(float(np.percentile(ts, 50)) * 1e6, 2), "p95_us": round(float(np.percentile(ts, 95)) * 1e6, 2),
+                           "mismatched_bits_vs_256": H.mismatched_bits(ref, bits)[1]}
+    vte.vte_desc_destroy(d)
+    return out
 
 
 def gemm_widths(reps, M=8192):

@@ -88,7 +88,8 @@ class vte_policy_vtbl(C.Structure):
 class vte_op_record(C.Structure):
     _fields_ = [("token", C.c_uint64), ("vstream", C.c_int), ("klass", C.c_int), ("kernel", C.c_int),
                 ("pctx", C.c_int), ("width", C.c_int), ("t_submit", C.c_double), ("t_ready", C.c_double),
-                ("t_bound", C.c_double), ("t_done", C.c_double), ("gpu_seconds", C.c_double)]
+                ("t_bound", C.c_double), ("t_done", C.c_double), ("gpu_seconds", C.c_double),
+                ("gpu_begin", C.c_double), ("gpu_end", C.c_double)]
 
 
 class vte_stats_t(C.Structure):
