@@ -295,16 +295,22 @@ def overlap_of_tenants(recs, first_kernel, last_kernel):
             begin = None
     side_by_side = whole_device = 0
     widths = set()
+    shared_step = [False] * len(steps)
     for r in recs:
         if r.klass != vte.VTE_CLASS_BEST_EFFORT or r.gpu_begin < 0:
             continue
-        if any(b < r.gpu_end and r.gpu_begin < e and p != r.pctx for b, e, p in steps):
+        hit = False
+        for i, (b, e, p) in enumerate(steps):
+            if b < r.gpu_end and r.gpu_begin < e and p != r.pctx:
+                hit = shared_step[i] = True
+        if hit:
             side_by_side += 1
             widths.add(int(r.width))
         elif r.width >= 256:
             whole_device += 1
     return {"best_effort_launches_beside_a_decode_step": side_by_side, "their_widths": sorted(widths),
-            "best_effort_launches_alone_on_256": whole_device}
+            "best_effort_launches_alone_on_256": whole_device,
+            "decode_steps": len(steps), "decode_steps_beside_a_best_effort_launch": int(sum(shared_step))}
 
 
 def cotenancy(seconds, gap_ms, steps_per_burst=128, lead_ms=3.0, shared=None, modes=("fixed", "late", "late_nohint")):
