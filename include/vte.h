@@ -289,6 +289,23 @@ int vte_desc_lmhead_argmax_planned(vte_ctx* ctx, const void* W, const void* H, i
                                    float* logits_or_null, void* workspace, int B, int V, int K,
                                    const vte_gemv_plan* plan, vte_desc** out);
 
+/* A GEMV as two launches, for outputs too narrow to fill the device at a large batch (Sec. 1
+ * "GEMV"; the structure stays a function of the shape, Sec. 3.1).  The K range is cut into S
+ * contiguous parts, S derived from the SHAPE (vte_gemv_fixed_split; never from a CU count): the
+ * split launch has N-tiles x S workgroups, each needing only its part of X, and leaves the fp32
+ * partial sums of every output in the workspace; the finish launch adds the S partial sums of an
+ * output in ascending part order, applies the epilogue and rounds to bf16 once.  No tickets, no
+ * atomics, no fences: the order between the two is the virtual stream's.
+ * Tree of an output: inside a part the K-split matrix-core tree of vte_desc_gemv (chunks of 256 or
+ * 512 elements chained per wave, waves added in order), then p[0] + p[1] + ... + p[S-1].
+ * workspace: device, vte_splitk_workspace_bytes(B, N, S) bytes, 16-byte aligned, private to launches
+ * of this pair that do not overlap in time; need not be zeroed.  X rows are ldx elements apart
+ * (0 = K), Y rows ldy (0 = outputs per row).  1 <= B <= 64, K % S == 0, (K / S) % 8 == 0. */
+int vte_gemv_fixed_split(int B, int N, int K, int epilogue, int* S); /* *S = 1: one launch (vte_desc_gemv) is the default */
+int vte_desc_gemv_split(vte_ctx* ctx, const void* W, const void* X, int ldx, void* workspace, int B, int N,
+                        int K, int epilogue, int S, const vte_gemv_plan* plan_or_null, vte_desc** out);
+int vte_desc_gemv_split_finish(vte_ctx* ctx, const vte_desc* split, void* Y, int ldy, vte_desc** out);
+
 /* H[b,:] = E[tok[b],:].  E: device [V,K] bf16; tok: device [B] int32 (values in
  * [0,V), clamped otherwise); H: device [B,K] bf16.  K % 8 == 0. */
 int vte_desc_gather(vte_ctx* ctx, const void* E, const int32_t* tok, void* H, int B, int V,
@@ -342,7 +359,7 @@ enum {
   VTE_K_RMSNORM = 1, VTE_K_LAYERNORM = 2, VTE_K_GEMV = 3, VTE_K_LMHEAD = 4, VTE_K_GATHER = 5,
   VTE_K_GEMM = 6, VTE_K_GEMV_SPLITK = 7, VTE_K_LMHEAD_SPLITK = 8, VTE_K_RMSNORM_RESHAPED = 9,
   VTE_K_ARGMAX_FINISH = 10, VTE_K_RMSNORM_GATHER = 11, VTE_K_RMSNORM_GATHER_ARGMAX = 12,
-  VTE_K_MEMCPY = 13, VTE_K_MEMSET = 14, VTE_K_SOFTMAX_PROB = 15
+  VTE_K_MEMCPY = 13, VTE_K_MEMSET = 14, VTE_K_SOFTMAX_PROB = 15, VTE_K_GEMV_SPLIT = 16, VTE_K_GEMV_SPLIT_FINISH = 17
 };
 typedef struct vte_desc_view {
   int kernel;           /* VTE_K_* */

@@ -27,6 +27,7 @@ const void* vte_gemv_entry_rows(int, int, int, int, int);
 const void* vte_gemv_entry_mfma64(int, int, int, int, int, int, int);
 const void* vte_gather_entry();
 const void* vte_argmax_finish_entry();
+const void* vte_split_finish_entry();
 const void* vte_gemm_entry();
 unsigned vte_gemm_lds_bytes();
 unsigned vte_gemm_threads();
@@ -299,17 +300,18 @@ struct GemvBuild {
   int B, N, K, epilogue, S;
   const vte_gemv_plan* plan;
   int ldx = 0, ldy = 0;  // 0 = dense
+  bool fixed_split = false;  // S is derived from the shape: partial sums only, no ticket array, a finish launch follows
 };
 
 // Validates the shape and the plan and fills *d; allocates nothing.
 int build_gemv_into(vte_ctx* ctx, const GemvBuild& g, vte_desc* d) {
   if (!d || !g.W || !g.X) { set_error("gemv: null argument"); return VTE_EINVAL; }
   const bool lm = (g.epi_kernel == 2);
-  if (!lm && !g.Y) { set_error("gemv: null output"); return VTE_EINVAL; }
+  if (!lm && !g.Y && !g.fixed_split) { set_error("gemv: null output"); return VTE_EINVAL; }
   if (lm && (!g.tok || !g.ws)) { set_error("lmhead: tok and workspace are required"); return VTE_EINVAL; }
   if (g.B < 1 || g.B > 64 || g.N < 1 || g.K < 8 || g.K % 8 != 0) { set_error("gemv: need 1 <= B <= 64, N >= 1, K % 8 == 0"); return VTE_EINVAL; }
   if (g.S < 1 || g.S > 64 || g.K % (g.S * 8) != 0) { set_error("gemv: K must split into S chunks of a multiple of 8"); return VTE_EINVAL; }
-  if (g.S > 1 && (!g.partials || !g.ws)) { set_error("split-K: partials and workspace are required"); return VTE_EINVAL; }
+  if (g.S > 1 && (!g.partials || (!g.ws && !g.fixed_split))) { set_error("split-K: partials and workspace are required"); return VTE_EINVAL; }
   if (g.epilogue == VTE_EPI_SILU_MUL && (g.N % 2 != 0)) { set_error("gemv: SiLU-mul needs an even N"); return VTE_EINVAL; }
   if (g.epilogue != VTE_EPI_NONE && g.epilogue != VTE_EPI_SILU_MUL) { set_error("gemv: unknown epilogue"); return VTE_EINVAL; }
   if (!aligned16(g.W) || !aligned16(g.X)) { set_error("gemv: W and X must be 16-byte aligned"); return VTE_EINVAL; }
@@ -327,7 +329,8 @@ int build_gemv_into(vte_ctx* ctx, const GemvBuild& g, vte_desc* d) {
   }
   const bool mfma = p.kind == VTE_GEMV_MFMA;
   if (p.kind != VTE_GEMV_DOT2 && !mfma && !by_rows) { set_error("gemv plan: unknown kind"); return VTE_EINVAL; }
-  if (g.B > 32 && !by_rows && !(mfma && p.batch_tile >= 32 && g.S == 1)) {
+  if (g.fixed_split && !mfma) { set_error("gemv plan: the shape-derived K split runs on the MFMA kind"); return VTE_EINVAL; }
+  if (g.B > 32 && !by_rows && !(mfma && p.batch_tile >= 32 && (g.S == 1 || g.fixed_split))) {
     set_error("gemv plan: batch 33 to 64 needs the row-split MFMA kind (batch_tile 64) or the MFMA kind with batch_tile 32 (two chunks), S = 1");
     return VTE_EINVAL;
   }
@@ -364,6 +367,7 @@ int build_gemv_into(vte_ctx* ctx, const GemvBuild& g, vte_desc* d) {
   const uint64_t shape = fnv1a(&a.B, sizeof(int) * 9);
   uint64_t bytes = 2ull * g.N * g.K + 2ull * g.B * g.K + (lm ? 4ull * g.B : 2ull * g.B * n_out);
   if (lm && g.logits) bytes += 4ull * g.B * g.N;
+  if (g.fixed_split) bytes = 2ull * g.N * g.K + 2ull * g.B * g.K + 4ull * g.S * g.B * g.N;
   const uint64_t flops = 2ull * g.B * g.N * g.K;
   return fill_desc(d, ctx, g.kernel, gemv_entry(p, g.epi_kernel, kps), a, gx, static_cast<uint32_t>(g.S),
                    static_cast<uint32_t>(waves * 64), 0, shape, bytes, flops, static_cast<uint32_t>(zchunks));
@@ -496,8 +500,8 @@ int vte_desc_gemv_planned(vte_ctx* ctx, const void* W, const void* X, void* Y, i
 static size_t splitk_ticket_bytes(int N) { return ((static_cast<size_t>(N) + 2) * 4 + 255) & ~static_cast<size_t>(255); }
 
 int vte_splitk_workspace_bytes(int B, int N, int S, size_t* bytes) {
-  if (!bytes || B < 1 || B > 32 || N < 1 || S < 1) { set_error("splitk workspace: bad argument"); return VTE_EINVAL; }
-  *bytes = splitk_ticket_bytes(N) + static_cast<size_t>(S) * (B > 16 ? 32 : 16) * N * 4;  // partials [S][batch tile][N]
+  if (!bytes || B < 1 || B > 64 || N < 1 || S < 1) { set_error("splitk workspace: bad argument"); return VTE_EINVAL; }
+  *bytes = splitk_ticket_bytes(N) + static_cast<size_t>(S) * (B > 32 ? 64 : (B > 16 ? 32 : 16)) * N * 4;  // partials [S][batch tile][N]
   return VTE_OK;
 }
 
@@ -508,6 +512,62 @@ int vte_desc_gemv_splitk(vte_ctx* ctx, const void* W, const void* X, void* Y, vo
   GemvBuild g{VTE_K_GEMV_SPLITK, epilogue == VTE_EPI_SILU_MUL ? 1 : 0, W, X, Y, nullptr, nullptr, workspace,
               partials, B, N, K, epilogue, S, nullptr};
   return build_gemv(ctx, g, out);
+}
+
+// Shape-derived K split for outputs too narrow to fill the device at a large batch: every
+// workgroup then needs only its K part of X.  1 = do not split.
+int vte_gemv_fixed_split(int B, int N, int K, int epilogue, int* S) {
+  if (!S || B < 1 || B > 64 || N < 1 || K < 8) { set_error("gemv_fixed_split: bad argument"); return VTE_EINVAL; }
+  const int n_out = (epilogue == VTE_EPI_SILU_MUL) ? N / 2 : N;
+  const int tiles = (n_out + (epilogue == VTE_EPI_SILU_MUL ? 8 : 16) - 1) / (epilogue == VTE_EPI_SILU_MUL ? 8 : 16);
+  *S = 1;
+  // Batch 33 to 64, fewer than 1024 row tiles and a long K (the down projection): parts of 2048 K
+  // elements, eight waves of one 256-element chunk each, X of a part fetched once per workgroup.
+  // Timed on cold weights at batch 64 against the single launch: 4096 x 14336 41 us against 45;
+  // with K = 4096 (QKV, O) the single launch wins (16 and 20 us against 19 and 24).
+  if (B > 32 && tiles < 1024 && K >= 8192 && K % 2048 == 0 && K / 2048 <= 64) *S = K / 2048;
+  return VTE_OK;
+}
+
+int vte_desc_gemv_split(vte_ctx* ctx, const void* W, const void* X, int ldx, void* workspace, int B, int N, int K,
+                        int epilogue, int S, const vte_gemv_plan* plan_or_null, vte_desc** out) {
+  if (!workspace || N < 1 || S < 2) { set_error("gemv_split: a workspace and S >= 2 are required"); return VTE_EINVAL; }
+  if (!aligned16(workspace)) { set_error("gemv_split: the workspace must be 16-byte aligned"); return VTE_EINVAL; }
+  if (S < 1 || K % S != 0) { set_error("gemv_split: S must divide K"); return VTE_EINVAL; }
+  void* partials = static_cast<unsigned char*>(workspace) + splitk_ticket_bytes(N);
+  vte_gemv_plan p;
+  if (plan_or_null) p = *plan_or_null;
+  else {
+    // parts of K / S elements in 256-element chunks (512 below batch 33), one per wave where that fits
+    const int n_out = (epilogue == VTE_EPI_SILU_MUL) ? N / 2 : N;
+    const int tiles = (n_out + (epilogue == VTE_EPI_SILU_MUL ? 8 : 16) - 1) / (epilogue == VTE_EPI_SILU_MUL ? 8 : 16);
+    p.kind = VTE_GEMV_MFMA; p.batch_tile = B > 32 ? 64 : (B > 16 ? 32 : 16);
+    p.ksteps = p.batch_tile == 64 ? 2 : 4; p.prefetch = p.batch_tile == 64 ? 2 : 4;
+    const int chunks = (K / S + 128 * p.ksteps - 1) / (128 * p.ksteps);
+    if (p.batch_tile == 64 && chunks > 4) { p.max_waves = 8; p.rows = 16; p.groups = tiles >= 256 ? 8 : 1; }  // timed best for 4096 x 14336
+    else { p.max_waves = 4; p.rows = 16 * (p.batch_tile == 64 ? 2 : 1); p.groups = tiles >= 512 ? 2 : 1; }
+  }
+  GemvBuild g{VTE_K_GEMV_SPLIT, epilogue == VTE_EPI_SILU_MUL ? 1 : 0, W, X, nullptr, nullptr, nullptr, nullptr,
+              partials, B, N, K, epilogue, S, &p};
+  g.ldx = ldx;
+  g.fixed_split = true;
+  return build_gemv(ctx, g, out);
+}
+
+int vte_desc_gemv_split_finish(vte_ctx* ctx, const vte_desc* split, void* Y, int ldy, vte_desc** out) {
+  if (!ctx || !split || !Y || !out) { set_error("gemv_split_finish: null argument"); return VTE_EINVAL; }
+  if (split->ctx != ctx || split->kernel != VTE_K_GEMV_SPLIT) { set_error("gemv_split_finish: needs a vte_desc_gemv_split descriptor of this context"); return VTE_EINVAL; }
+  GemvArgs g;
+  std::memcpy(&g, split->args, sizeof g);
+  if (ldy == 0) ldy = g.n_out;
+  if (ldy < g.n_out) { set_error("gemv_split_finish: ldy must hold a row of outputs"); return VTE_EINVAL; }
+  SplitFinishArgs a{};
+  a.partials = g.partials; a.Y = static_cast<uint16_t*>(Y);
+  a.B = g.B; a.N = g.N; a.n_out = g.n_out; a.ldy = ldy; a.S = g.S; a.bt = g.bt; a.silu = g.n_out != g.N ? 1 : 0;
+  const int v[4] = {a.B, a.N, a.n_out, a.S};
+  const uint32_t gx = static_cast<uint32_t>((a.n_out + 1023) / 1024);
+  return finish_desc(ctx, VTE_K_GEMV_SPLIT_FINISH, vte_split_finish_entry(), a, gx, static_cast<uint32_t>(a.B), 256, 0,
+                     fnv1a(v, sizeof v), 4ull * a.S * a.B * a.N + 2ull * a.B * a.n_out, 0, out);
 }
 
 int vte_lmhead_workspace_bytes(int B, int V, int K, size_t* bytes) {

@@ -92,10 +92,18 @@ __global__ __launch_bounds__(MAXW * 64) void gemv_mfma_kernel(const GemvArgs a) 
   // X: rows past B lie outside the resource and read as zero
   const __amdgpu_buffer_rsrc_t rs_x = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<uint16_t*>(a.X), 0, static_cast<int>((static_cast<uint32_t>(a.B - 1) * a.ldx + a.K) * 2u), kRsrcFlags);
-  uint32_t voff_x[CT];  // column tile ct holds batch rows row0 + 16 ct + c
+  // X is fetched like the weights, coalesced (an instruction takes 4 batch rows x 256 B) and turned
+  // into operand order through the wave's LDS area: fetched in operand order (lane = row + 16 x
+  // K group) every lane of an instruction sits on its own cache line and the address unit, not the
+  // cache, sets the pace -- a quarter of the coalesced rate.
+  uint32_t voff_x[CT][4];  // instruction u of column tile ct: batch row row0 + 16 ct + 4 u + lr, piece lp
 #pragma unroll
   for (int ct = 0; ct < CT; ++ct)
-    voff_x[ct] = row0 + 16 * ct + c < a.B ? (static_cast<uint32_t>(row0 + 16 * ct + c) * a.ldx + q * 8) * 2u : 0x80000000u;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int br = row0 + 16 * ct + 4 * u + lr;
+      voff_x[ct][u] = br < a.B ? (static_cast<uint32_t>(br) * a.ldx + lp * 8) * 2u : 0x80000000u;
+    }
 
   f32x4_t acc[G][CT];
   const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
@@ -113,14 +121,33 @@ __global__ __launch_bounds__(MAXW * 64) void gemv_mfma_kernel(const GemvArgs a) 
     for (int t = 0; t < 4; ++t)
       dst[t] = __builtin_amdgcn_raw_buffer_load_b128(rs_w[t], vo, soff + bi * 256, 2);  // streaming
   };
-  auto load_x_block = [&](int ch, int bi) {
+  auto load_x_block = [&](int ch, int bi) {  // block bi (128 K) of chunk ch, still in load order
     const int soff = (k_begin + ch * KC) * 2;
+    const bool in_k = ALLFULL || k_begin + ch * KC + bi * 128 + lp * 8 < k_end;
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct)
 #pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        const uint32_t vo = (ALLFULL || k_begin + ch * KC + bi * 128 + s * 32 + q * 8 < k_end) ? voff_x[ct] : 0x80000000u;
-        xs[ct][bi][s] = __builtin_amdgcn_raw_buffer_load_b128(rs_x, vo, soff + (bi * 128 + s * 32) * 2, 0);
+      for (int u = 0; u < 4; ++u)
+        xs[ct][bi][u] = __builtin_amdgcn_raw_buffer_load_b128(rs_x, in_k ? voff_x[ct][u] : 0x80000000u, soff + bi * 256, 0);
+  };
+  // load order -> operand order, in place, through the wave's transposition area (free between blocks)
+  auto transpose_x = [&]() {
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+      for (int bi = 0; bi < NBK; ++bi) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int r = 4 * u + lr;
+          stage[r * 16 + (lp ^ r)] = xs[ct][bi][u];
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+        for (int s = 0; s < 4; ++s) xs[ct][bi][s] = stage[c * 16 + ((4 * s + q) ^ c)];
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
       }
   };
   auto load_x = [&](int ch) {
@@ -175,6 +202,8 @@ __global__ __launch_bounds__(MAXW * 64) void gemv_mfma_kernel(const GemvArgs a) 
     if (active) {
       int ch = wave;
       while (true) {
+        // X of this chunk arrived in load order: once per launch when a wave has a single chunk, else per chunk pass
+        if (!ONECHUNK || rd == 0) transpose_x();
         const int chn = ch + nw;
         const bool more = !ONECHUNK && chn < nchunks;  // ONECHUNK: the launch has no more chunks than waves
         const bool next_round = rd + 1 < a.groups;
@@ -270,8 +299,10 @@ __global__ __launch_bounds__(MAXW * 64) void gemv_mfma_kernel(const GemvArgs a) 
     __syncthreads();  // the LDS areas are transposition space again
   }
 
-  // ---- split-K baseline: the last chunk-block of this row block adds the chunk sums ----
-  if (a.S > 1) {
+  // ---- split-K baseline: the last chunk-block of this row block adds the chunk sums.  Without a
+  // ticket array (the shape-derived split) the partial sums are all this launch leaves: a finish
+  // launch adds them in split order. ----
+  if (a.S > 1 && a.ws) {
     __threadfence();
     __syncthreads();
     if (threadIdx.x == 0) {

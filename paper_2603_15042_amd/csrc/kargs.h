@@ -75,6 +75,14 @@ struct GemmArgs {
   int tiles_m, tiles_n;
 };
 
+// Finish of a GEMV whose K range was split by a shape-derived factor S: adds the S partial sums
+// of every output in split order and applies the epilogue.
+struct SplitFinishArgs {
+  const float* partials;  // [S][bt][N] fp32 (SiLU: gate sums at [0,n_out), up sums at [n_out, 2 n_out) of a row)
+  uint16_t* Y;            // [B, ldy] bf16
+  int B, N, n_out, ldy, S, bt, silu;
+};
+
 // Second stage of the greedy token: reduce the per-workgroup (value, index)
 // candidates the LM head left in its workspace.
 struct ArgmaxFinishArgs {

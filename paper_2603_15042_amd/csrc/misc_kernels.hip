@@ -111,6 +111,37 @@ __global__ __launch_bounds__(1024) void softmax_prob_kernel(const SoftmaxArgs a)
   }
 }
 
+// Finish launch of the shape-derived K split: output n of batch row b is p[0] + p[1] + ... + p[S-1]
+// (fp32, ascending split index) of the partial sums the split launch left behind, then the epilogue
+// and one rounding to bf16.  One thread per four consecutive outputs of one batch row.
+__global__ __launch_bounds__(256) void split_finish_kernel(const SplitFinishArgs a) {
+  const int b = blockIdx.y;
+  const int n0 = (blockIdx.x * 256 + threadIdx.x) * 4;
+  if (b >= a.B || n0 >= a.n_out) return;
+  float g[4], u[4];
+#pragma unroll
+  for (int v = 0; v < 4; ++v) {
+    const int n = n0 + v < a.n_out ? n0 + v : a.n_out - 1;  // clamped: a tail thread re-reads the last output
+    const float* p = a.partials + static_cast<size_t>(b) * a.N + n;
+    const size_t stride = static_cast<size_t>(a.bt) * a.N;
+    float t = p[0];
+    for (int s = 1; s < a.S; ++s) t += p[s * stride];
+    g[v] = t;
+    if (a.silu) {
+      float t2 = p[a.n_out];
+      for (int s = 1; s < a.S; ++s) t2 += p[s * stride + a.n_out];
+      u[v] = t2;
+    }
+  }
+#pragma unroll
+  for (int v = 0; v < 4; ++v) {
+    if (n0 + v >= a.n_out) break;
+    const float r = a.silu ? (g[v] / (1.0f + expf(-g[v]))) * u[v] : g[v];
+    a.Y[static_cast<size_t>(b) * a.ldy + n0 + v] = (uint16_t)f32_to_bf16(r);
+  }
+}
+
+extern "C" const void* vte_split_finish_entry() { return (const void*)split_finish_kernel; }
 extern "C" const void* vte_softmax_prob_entry() { return (const void*)softmax_prob_kernel; }
 extern "C" const void* vte_copy_entry() { return (const void*)copy_kernel; }
 extern "C" const void* vte_fill_entry() { return (const void*)fill_kernel; }

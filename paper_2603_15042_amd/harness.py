@@ -75,7 +75,7 @@ class DecodeChain:
     first step (7 launches, no finish) + later steps (6 launches each) + one finish at the end."""
 
     def __init__(self, ctx, weights_dev, shp, B, eps=1e-6, want_logits=False, splitk=None, rms_active_cus=None,
-                 feedback=False, fused_gather=False, fused_argmax=False):
+                 feedback=False, fused_gather=False, fused_argmax=False, fixed_split=True):
         self.ctx, self.shp, self.B = ctx, shp, B
         D, Nq, F, V = shp.D, shp.Nqkv, shp.F, shp.V
         w = self.w = weights_dev
@@ -99,12 +99,29 @@ class DecodeChain:
             d["rmsnorm"] = vte.vte_desc_rmsnorm(ctx, self.h0, w["gamma"], self.n, B, D, eps)
         else:
             d["rmsnorm"] = vte.vte_desc_rmsnorm_reshaped(ctx, self.h0, w["gamma"], self.n, B, D, eps, rms_active_cus)
+        self.alg_bytes = {}  # algorithmic bytes of the projections that run as a split + finish pair
         if splitk is None:
-            d["qkv"] = vte.vte_desc_gemv(ctx, w["Wqkv"], self.n, self.qkv, B, Nq, D)
+            def proj(name, W, X, ldx, Y, N, K, epi=vte.VTE_EPI_NONE):
+                """One projection: a single launch, or where the shape asks for it (narrow output, batch
+                above 32) the shape-derived K split and its finish launch."""
+                S = vte.vte_gemv_fixed_split(B, N, K, epi) if fixed_split else 1
+                if S > 1:
+                    ws = dev_zeros_bytes(vte.vte_splitk_workspace_bytes(B, N, S))
+                    self.extra.append(ws)
+                    d[name] = vte.vte_desc_gemv_split(ctx, W, X, ldx, ws, B, N, K, epi, S)
+                    d[name + "_fin"] = vte.vte_desc_gemv_split_finish(ctx, d[name], Y)
+                    n_out = N // 2 if epi == vte.VTE_EPI_SILU_MUL else N
+                    self.alg_bytes[name] = 2 * N * K + 2 * B * K + 2 * B * n_out
+                    self.alg_bytes[name + "_fin"] = 0
+                elif ldx != K:
+                    d[name] = vte.vte_desc_gemv_strided(ctx, W, X, ldx, Y, N, B, N, K, epi)
+                else:
+                    d[name] = vte.vte_desc_gemv(ctx, W, X, Y, B, N, K, epi)
+            proj("qkv", w["Wqkv"], self.n, D, self.qkv, Nq, D)
             # the O projection consumes the Q slice (first D columns) of qkv in place
-            d["o"] = vte.vte_desc_gemv_strided(ctx, w["Wo"], self.qkv, Nq, self.o, D, B, D, D)
-            d["gateup"] = vte.vte_desc_gemv(ctx, w["Wgu"], self.o, self.act, B, 2 * F, D, vte.VTE_EPI_SILU_MUL)
-            d["down"] = vte.vte_desc_gemv(ctx, w["Wd"], self.act, self.d, B, D, F)
+            proj("o", w["Wo"], self.qkv, Nq, self.o, D, D)
+            proj("gateup", w["Wgu"], self.o, D, self.act, 2 * F, D, vte.VTE_EPI_SILU_MUL)
+            proj("down", w["Wd"], self.act, F, self.d, D, F)
             d["lmhead"] = vte.vte_desc_lmhead_argmax(ctx, w["Wlm"], self.d, self.next, self.logits, self.ws, B, V, D)
         else:
             S = splitk
@@ -124,7 +141,8 @@ class DecodeChain:
             d["lmhead"] = vte.vte_desc_lmhead_argmax_splitk(ctx, w["Wlm"], self.d, self.next, self.logits, self.ws,
                                                             ws(V), B, V, D, S)
         d["argmax"] = vte.vte_desc_argmax_finish(ctx, d["lmhead"])
-        self.order = [k for k in ("gather", "rmsnorm", "qkv", "q", "o", "gateup", "down", "lmhead", "argmax") if k in d]
+        self.order = [k for k in ("gather", "rmsnorm", "qkv", "qkv_fin", "q", "o", "o_fin", "gateup", "gateup_fin", "down", "down_fin",
+                                  "lmhead", "argmax") if k in d]
         self.fused_argmax = fused_argmax
         if fused_argmax:
             d["boundary"] = vte.vte_desc_rmsnorm_gather_argmax(ctx, w["E"], d["lmhead"], self.next, w["gamma"], self.n,
@@ -132,9 +150,9 @@ class DecodeChain:
             body = [k for k in self.order if k not in ("gather", "rmsnorm", "argmax")]
             self.order_first = [k for k in self.order if k != "argmax"]
             self.order_next = ["boundary"] + body
-            self.bytes_per_step = sum(vte.vte_desc_info(d[k]).bytes for k in self.order_next if k != "q")
+            self.bytes_per_step = sum(self.alg_bytes.get(k, vte.vte_desc_info(d[k]).bytes) for k in self.order_next if k != "q")
         else:
-            self.bytes_per_step = sum(vte.vte_desc_info(d[k]).bytes for k in self.order if k != "q")
+            self.bytes_per_step = sum(self.alg_bytes.get(k, vte.vte_desc_info(d[k]).bytes) for k in self.order if k != "q")
 
     def set_tokens(self, toks):
         self.tok.copy_(torch.from_numpy(np.ascontiguousarray(toks, dtype=np.int32)))

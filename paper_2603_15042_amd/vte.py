@@ -24,7 +24,8 @@ VTE_POLICY_WIDEST, VTE_POLICY_QUEUE_STATE, VTE_POLICY_TPUT_PLAN, VTE_POLICY_TPOT
 VTE_GEMV_DOT2, VTE_GEMV_MFMA, VTE_GEMV_MFMA_ROWS = 0, 1, 2
 (VTE_K_RMSNORM, VTE_K_LAYERNORM, VTE_K_GEMV, VTE_K_LMHEAD, VTE_K_GATHER, VTE_K_GEMM, VTE_K_GEMV_SPLITK,
  VTE_K_LMHEAD_SPLITK, VTE_K_RMSNORM_RESHAPED, VTE_K_ARGMAX_FINISH, VTE_K_RMSNORM_GATHER,
- VTE_K_RMSNORM_GATHER_ARGMAX, VTE_K_MEMCPY, VTE_K_MEMSET, VTE_K_SOFTMAX_PROB) = range(1, 16)
+ VTE_K_RMSNORM_GATHER_ARGMAX, VTE_K_MEMCPY, VTE_K_MEMSET, VTE_K_SOFTMAX_PROB, VTE_K_GEMV_SPLIT,
+ VTE_K_GEMV_SPLIT_FINISH) = range(1, 18)
 
 
 class VteError(RuntimeError):
@@ -125,6 +126,7 @@ EXPORTS = [
     "vte_fake_log", "vte_dispatcher_quiesce", "vte_now", "vte_vstream_set_tpot", "vte_vstream_tpot_info", "vte_submit_batch", "vte_pool_creation_order", "vte_desc_memcpy", "vte_desc_memset32",
     "vte_event_record", "vte_vstream_wait_event", "vte_desc_softmax_prob",
     "vte_static_scratch_bytes", "vte_lmhead_argmax_static", "vte_fake_complete_error",
+    "vte_gemv_fixed_split", "vte_desc_gemv_split", "vte_desc_gemv_split_finish",
 ]
 
 _lib = None
@@ -284,6 +286,21 @@ def vte_splitk_workspace_bytes(B, N, S):
 def vte_desc_gemv_splitk(ctx, W, X, Y, workspace, B, N, K, epilogue, S):
     return _desc_call(load().vte_desc_gemv_splitk, ctx, _ptr(W), _ptr(X), _ptr(Y), _ptr(workspace), int(B), int(N),
                       int(K), int(epilogue), int(S))
+
+
+def vte_gemv_fixed_split(B, N, K, epilogue=VTE_EPI_NONE):
+    S = C.c_int()
+    _check(load().vte_gemv_fixed_split(int(B), int(N), int(K), int(epilogue), C.byref(S)))
+    return S.value
+
+
+def vte_desc_gemv_split(ctx, W, X, ldx, workspace, B, N, K, epilogue, S, plan=None):
+    return _desc_call(load().vte_desc_gemv_split, ctx, _ptr(W), _ptr(X), int(ldx), _ptr(workspace), int(B), int(N), int(K),
+                      int(epilogue), int(S), C.byref(plan) if plan is not None else None)
+
+
+def vte_desc_gemv_split_finish(ctx, split_desc, Y, ldy=0):
+    return _desc_call(load().vte_desc_gemv_split_finish, ctx, split_desc, _ptr(Y), int(ldy))
 
 
 def vte_lmhead_workspace_bytes(B, V, K):

@@ -557,6 +557,80 @@ def test_lmhead_batch_33_to_64_tokens_and_logits(H, ctx, B, V, K, kind):
 
 
 # ---------- the matrix-core trees, emulated on the CPU ------------------------------------------------
+@pytest.mark.parametrize("B,N,K,S,epi", [(64, 4096, 4096, 4, 0), (40, 528, 2048, 2, 0), (64, 4096, 14336, 14, 0), (33, 6144, 4096, 4, 0),
+                                         (64, 1000, 2048, 2, 1), (16, 272, 1024, 2, 0)])
+def test_gemv_shape_derived_split_and_finish(H, ctx, B, N, K, S, epi):
+    """The two-launch GEMV for narrow outputs at a large batch: a K split whose factor comes from the
+    shape, partial sums in a workspace, a finish launch that adds them in order.  Against the oracle,
+    bit-equal on every width, and a row's bits do not depend on the rows beside it."""
+    W = inputs.normal_bf16(41, inputs.T_W, (N, K), 0.0, K ** -0.5)
+    X = inputs.normal_bf16(41, inputs.T_XB, (B, K))
+    dW, dX = H.to_dev(W), H.to_dev(X)
+    n_out = N // 2 if epi else N
+    dY = H.dev_empty((B, n_out))
+    ws = H.dev_zeros_bytes(vte.vte_splitk_workspace_bytes(B, N, S))
+    d1 = vte.vte_desc_gemv_split(ctx, dW, dX, 0, ws, B, N, K, epi, S)
+    d2 = vte.vte_desc_gemv_split_finish(ctx, d1, dY)
+    v1, v2 = vte.vte_desc_info(d1), vte.vte_desc_info(d2)
+    assert v1.kernel == vte.VTE_K_GEMV_SPLIT and v1.grid[1] == S and v2.kernel == vte.VTE_K_GEMV_SPLIT_FINISH
+    res = {}
+    for p in (H.pctx_of_width(ctx, 256), H.pctx_of_width(ctx, 32), H.pctx_of_width(ctx, 192)):
+        dY.fill_(0x7FC1)
+        ws.fill_(-1)                                    # stale partials of an earlier launch must not matter
+        torch.cuda.synchronize()
+        H.run_on(ctx, d1, p)
+        H.run_on(ctx, d2, H.pctx_of_width(ctx, 64))     # the finish launch may be bound elsewhere
+        res[p] = H.to_bits(dY).copy()
+    y = assert_all_equal(res)
+    ref = oracle.gemv_silu_mul(W, X) if epi else oracle.gemv(W, X)
+    bf16_close(y, ref, "split GEMV %dx%d batch %d S %d" % (N, K, B, S))
+    if B > 8:                                           # every second row alone: same bits
+        Xh = np.ascontiguousarray(X[::2])
+        Bh = Xh.shape[0]
+        dXh, dYh = H.to_dev(Xh), H.dev_empty((Bh, n_out))
+        wsh = H.dev_zeros_bytes(vte.vte_splitk_workspace_bytes(B, N, S))
+        plan = None
+        if (Bh > 32) != (B > 32) or (Bh > 16) != (B > 16):   # keep the batch tile of the full batch: the tree depends on the plan
+            plan = vte.vte_gemv_plan()
+            plan.kind, plan.batch_tile = vte.VTE_GEMV_MFMA, (64 if B > 32 else 32)
+            plan.ksteps, plan.prefetch, plan.max_waves = (2 if B > 32 else 4), (2 if B > 32 else 4), 4
+            plan.rows, plan.groups = (32 if B > 32 else 16), (2 if (n_out + (7 if epi else 15)) // (8 if epi else 16) >= 512 else 1)
+        e1 = vte.vte_desc_gemv_split(ctx, dW, dXh, 0, wsh, Bh, N, K, epi, S, plan)
+        e2 = vte.vte_desc_gemv_split_finish(ctx, e1, dYh)
+        H.run_on(ctx, e1, H.pctx_of_width(ctx, 128))
+        H.run_on(ctx, e2, H.pctx_of_width(ctx, 128))
+        assert np.array_equal(H.to_bits(dYh), y[::2])
+        vte.vte_desc_destroy(e2); vte.vte_desc_destroy(e1)
+    vte.vte_desc_destroy(d2); vte.vte_desc_destroy(d1)
+
+
+@pytest.mark.parametrize("B,N,K,S,binades", [(64, 48, 4096, 4, 0), (40, 32, 2048, 2, 6), (64, 16, 14336, 14, 0)])
+def test_shape_derived_split_equals_its_emulated_tree_bit_for_bit(H, ctx, B, N, K, S, binades):
+    """Partial sums and finished outputs of the two-launch GEMV against the CPU emulation of its tree:
+    per part the K-split matrix-core tree (256-element chunks, one per wave), then p[0] + p[1] + ..."""
+    import tree_emulator
+    W = inputs.normal_bf16(43, inputs.T_W, (N, K), 0.0, K ** -0.5)
+    if binades:
+        W = _spread(W, 43, binades)
+    X = inputs.normal_bf16(43, inputs.T_XB, (B, K))
+    parts, total = tree_emulator.gemv_fixed_split_sums(W, X, S, 2, 4)
+    dW, dX, dY = H.to_dev(W), H.to_dev(X), H.dev_empty((B, N))
+    nbytes = vte.vte_splitk_workspace_bytes(B, N, S)
+    ws = H.dev_zeros_bytes(nbytes)
+    d1 = vte.vte_desc_gemv_split(ctx, dW, dX, 0, ws, B, N, K, 0, S)
+    d2 = vte.vte_desc_gemv_split_finish(ctx, d1, dY)
+    for wdt in (256, 64):
+        ws.fill_(-1)
+        H.run_on(ctx, d1, H.pctx_of_width(ctx, wdt))
+        H.run_on(ctx, d2, H.pctx_of_width(ctx, wdt))
+        raw = ws.cpu().numpy().view(np.float32)
+        head = (nbytes - S * 64 * N * 4) // 4               # ticket words in front of the partials [S][64][N]
+        got = raw[head:head + S * 64 * N].reshape(S, 64, N)[:, :B, :]
+        assert np.array_equal(got.view(np.uint32), parts.view(np.uint32)), wdt
+        assert np.array_equal(H.to_bits(dY), tree_emulator._f32_to_bf16(total)), wdt
+    vte.vte_desc_destroy(d2); vte.vte_desc_destroy(d1)
+
+
 def _spread(Wbits, seed, binades):
     """bf16 weights times seeded powers of two: makes the alignment inside the instruction visible."""
     rng = np.random.default_rng(seed)

@@ -409,7 +409,19 @@ def test_plans_that_do_not_fit_are_rejected(ctx):
         assert e.value.code == vte.VTE_EINVAL
     vte.vte_desc_destroy(vte.vte_desc_gemv_planned(ctx, A, A, A, 8, 4096, 1 << 24, 0, _plan(M, 16, 16, 4, 2, 8, 1)))
     with pytest.raises(vte.VteError):                        # no split-K baseline above batch 32
-        vte.vte_splitk_workspace_bytes(33, 4096, 2)
+        vte.vte_desc_gemv_splitk(ctx, A, A, A, A, 33, 4096, 4096, 0, 2)
+    with pytest.raises(vte.VteError):
+        vte.vte_splitk_workspace_bytes(65, 4096, 2)
+    # the shape-derived split: a factor from the shape alone, a split launch with S workgroup rows, a finish launch
+    assert vte.vte_gemv_fixed_split(64, 4096, 4096) == 1 and vte.vte_gemv_fixed_split(64, 4096, 14336) == 7
+    assert vte.vte_gemv_fixed_split(32, 4096, 4096) == 1 and vte.vte_gemv_fixed_split(64, 128256, 4096) == 1
+    d1 = vte.vte_desc_gemv_split(ctx, A, A, 0, A, 64, 4096, 4096, 0, 4)
+    d2 = vte.vte_desc_gemv_split_finish(ctx, d1, A)
+    assert vte.vte_desc_info(d1).grid[1] == 4 and vte.vte_desc_info(d2).grid[1] == 64
+    with pytest.raises(vte.VteError):
+        vte.vte_desc_gemv_split_finish(ctx, d2, A)           # not a split descriptor
+    with pytest.raises(vte.VteError):
+        vte.vte_desc_gemv_split(ctx, A, A, 0, A, 64, 4096, 4096, 0, 3)   # S must divide K
 
 
 def test_bad_shapes_are_rejected(ctx):
