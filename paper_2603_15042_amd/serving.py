@@ -247,8 +247,52 @@ class Server:
             "tpot_first": [{"standing_width": vte.vte_pool_info(ctx, i.standing_pctx).width if i.standing_pctx >= 0 else None,
                             "tokens": int(i.tokens_done), "deadline_misses": int(i.deadline_misses),
                             "escalations": int(i.escalations)} for i in info] if mode == "tpot" else None,
+            "timeline": self.timeline(recs, ctx),
             "_reqs": reqs,
         }
+
+    @staticmethod
+    def timeline(recs, ctx):
+        """Where the launches of each virtual stream spent their time, from the op-record ring (the most
+        recent records of the run): per stream the share of its window with nothing in flight, the time
+        its ready launches waited for a pCtx (ready -> bound), the width its launches ran on weighted
+        by their time in flight, and per pCtx the time it was held (bound -> done, union over launches)."""
+        if not recs:
+            return None
+        out = {"records": len(recs), "streams": {}, "pctx": {}}
+        by_vs, by_p = {}, {}
+        for r in recs:
+            by_vs.setdefault((r.vstream, r.klass), []).append(r)
+            by_p.setdefault(r.pctx, []).append(r)
+        t_lo, t_hi = min(r.t_submit for r in recs), max(r.t_done for r in recs)
+
+        def union(iv):
+            tot, end = 0.0, -1.0
+            for a, b in sorted(iv):
+                if b <= end:
+                    continue
+                tot += b - max(a, end)
+                end = b
+            return tot
+        for (vs, klass), rs in sorted(by_vs.items()):
+            lo, hi = min(r.t_submit for r in rs), max(r.t_done for r in rs)
+            fl = sum(r.t_done - r.t_bound for r in rs)
+            w = {}
+            for r in rs:
+                w[r.width] = w.get(r.width, 0.0) + (r.t_done - r.t_bound)
+            out["streams"]["%d (%s)" % (vs, "latency" if klass == vte.VTE_CLASS_LATENCY else "best effort")] = {
+                "launches": len(rs), "window_ms": round((hi - lo) * 1e3, 2),
+                "share_of_window_with_a_launch_in_flight": round(union([(r.t_bound, r.t_done) for r in rs]) / max(hi - lo, 1e-9), 3),
+                "ready_to_bound_wait_ms_total": round(sum(r.t_bound - r.t_ready for r in rs) * 1e3, 2),
+                "ready_to_bound_wait_us_mean": round(float(np.mean([r.t_bound - r.t_ready for r in rs])) * 1e6, 2),
+                "ready_to_bound_wait_us_p99": round(float(np.percentile([r.t_bound - r.t_ready for r in rs], 99)) * 1e6, 2),
+                "time_in_flight_by_width_share": {str(k): round(v / fl, 3) for k, v in sorted(w.items())},
+                "mean_width_weighted_by_time_in_flight": round(sum(k * v for k, v in w.items()) / fl, 1)}
+        for p, rs in sorted(by_p.items()):
+            out["pctx"]["%d (%d CUs)" % (p, vte.vte_pool_info(ctx, p).width)] = {
+                "launches": len(rs), "held_share_of_run_window": round(union([(r.t_bound, r.t_done) for r in rs]) / max(t_hi - t_lo, 1e-9), 3),
+                "streams": sorted({r.vstream for r in rs})}
+        return out
 
     def check_tokens(self, result):
         """Every transition a run produced against the row computed alone at full width."""

@@ -474,3 +474,36 @@ def test_tput_plan_does_not_renew_a_lease_while_an_older_op_has_nowhere_to_go():
         finish(c, [t_late, t2])
     finally:
         vte.vte_shutdown(c)
+
+
+def test_tput_plan_keeps_a_stream_on_its_open_lease_and_packs_newcomers_beside_taken_buddies():
+    """Two seats of the plan that keep the pool whole: the next op of a vstream whose predecessor is
+    still in flight is seated where that predecessor runs (a narrower free pCtx would make the stream
+    hold two allocations), and a newcomer takes, among equally wide pCtxs on free pipes, the one
+    nearest to a block that is already broken up, so that a whole half stays free for a tenant that scales."""
+    c = make_ctx(vte.VTE_MODE_PIPELINED, remainders=vte.VTE_REMAINDERS_PER_LEVEL)
+    try:
+        flat = vte.vte_desc_rmsnorm(c, A, A, A, 8, 1024, 1e-6)
+        set_profile(c, flat, lambda w: 4e-6)                 # gains nothing from more CUs: MinBind decides
+        ps = infos(c)
+        quarters = [p.id for p in ps if p.kind == vte.VTE_PCTX_NODE and p.width == 64]
+        a, b = vte.vte_vstream_create(c, vte.VTE_CLASS_LATENCY), vte.vte_vstream_create(c, vte.VTE_CLASS_LATENCY)
+        vte.vte_set_builtin_policy(c, vte.VTE_POLICY_TPUT_PLAN)
+        # stream a sits on the first quarter of the SECOND half (pinned for its first op only)
+        vte.vte_vstream_pin(a, quarters[2])
+        t1 = vte.vte_submit(a, flat)
+        vte.vte_dispatcher_quiesce(c)
+        vte.vte_vstream_pin(a, -1)
+        t2 = vte.vte_submit(a, flat)                         # predecessor in flight on that quarter; every leaf elsewhere is free
+        vte.vte_dispatcher_quiesce(c)
+        assert bound(c)[t1] == quarters[2] and bound(c)[t2] == quarters[2]
+        # a newcomer that wants exactly a quarter: the other quarter of the second half, not one of the first
+        heavy = vte.vte_desc_gemv(c, A, A, A, 1, 4096, 4096, 0)
+        set_profile(c, heavy, {32: 2e-3, 64: 1e-3, 128: 1e-3, 192: 1e-3, 224: 1e-3, 256: 1e-3})
+        t3 = vte.vte_submit(b, heavy)
+        vte.vte_dispatcher_quiesce(c)
+        got = bound(c)[t3]
+        assert got == quarters[3], (got, quarters)           # completes the broken half instead of breaking the whole one
+        finish(c, [t1, t2, t3])
+    finally:
+        vte.vte_shutdown(c)
