@@ -234,7 +234,9 @@ def main():
         d = vte.vte_desc_gemm(ctx, gA, gB, gC, M, M, M)
         r = {}
         for width in WIDTHS:
-            t = vte.vte_profile_measure_on(ctx, d, H.pctx_of_width(ctx, width), 1, 6 if width >= 128 else 2)
+            # steady state: the first dozen back-to-back launches at full width run through a clock transient
+            # (0.84 ms, up to 1.05 ms around the fourth, 0.82 ms from the sixteenth on), so they are warm-up
+            t = vte.vte_profile_measure_on(ctx, d, H.pctx_of_width(ctx, width), 20 if width >= 128 else 3, 20 if width >= 128 else 4)
             r[str(width)] = {"TFLOP/s": round(2.0 * M ** 3 / t / 1e12, 1), "pct_mfma_peak": round(2.0 * M ** 3 / t / 1e12 / 25.0, 2),
                              "ms": round(t * 1e3, 3)}
         ops["gemm_8192_bf16"] = r

@@ -490,7 +490,9 @@ def gemm_widths(reps, M=8192):
     d = vte.vte_desc_gemm(ctx, gA, gB, gC, M, M, M)
     out = {"M": M, "reps": reps, "widths": {}}
     for width in (256, 224, 192, 128, 64, 32):
-        t = vte.vte_profile_measure_on(ctx, d, H.pctx_of_width(ctx, width), 1, reps)
+        # as many warm-up launches as timed ones: at full width the clock settles only after about
+        # fifteen back-to-back launches (a burst of six averages 15 % slower than the steady state)
+        t = vte.vte_profile_measure_on(ctx, d, H.pctx_of_width(ctx, width), reps, reps)
         out["widths"][str(width)] = {"ms": t * 1e3, "TFLOP/s": 2.0 * M ** 3 / t / 1e12, "pct_of_2.5_PFLOP/s": 2.0 * M ** 3 / t / 2.5e13}
     vte.vte_shutdown(ctx)
     return out
