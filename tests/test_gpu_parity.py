@@ -68,7 +68,7 @@ def test_rmsnorm_parity_and_width_invariance(H, ctx, rows, cols):
     dx, dg, dy = H.to_dev(x), H.to_dev(g), H.dev_empty((rows, cols))
     d = vte.vte_desc_rmsnorm(ctx, dx, dg, dy, rows, cols, 1e-6)
     res = run_everywhere(H, ctx, d, dy)
-    y = assert_all_equal(res).view(np.uint16)           # 0 mismatched bits on all 27 pCtxs
+    y = assert_all_equal(res).view(np.uint16)           # 0 mismatched bits on every pCtx of the pool
     bf16_close(y, oracle.rmsnorm(x, g, 1e-6), "rmsnorm %dx%d" % (rows, cols))
     vte.vte_desc_destroy(d)
 
