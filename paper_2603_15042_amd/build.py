@@ -1,6 +1,9 @@
 """Builds libvte.so (HIP kernels + runtime, gfx950) and the input generator, in-tree.
 
-    python -m paper_2603_15042_amd.build [--force]
+    python -m paper_2603_15042_amd.build [--force] [--trace]
+
+--trace also builds libvte_trace.so: the same library with the matrix-core GEMV (batch 5 to 16)
+compiled with device-side time stamps (csrc/trace_stamps.h), for `experiments ramp`.
 """
 import concurrent.futures as cf
 import os
@@ -10,6 +13,8 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libvte.so")
+OUT_TRACE = os.path.join(HERE, "libvte_trace.so")
+TRACED = "gemv_mfma.hip"            # the translation unit that carries stamps in the trace build
 OBJ = os.path.join(HERE, "_build")
 
 HIP_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wno-inline-asm",
@@ -27,14 +32,14 @@ def _newer(target, deps):
     return any(os.path.getmtime(d) > t for d in deps)
 
 
-def _compile(src, force):
-    obj = os.path.join(OBJ, src + ".o")
+def _compile(src, force, defines=(), tag=""):
+    obj = os.path.join(OBJ, src + tag + ".o")
     path = os.path.join(CSRC, src)
     headers = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h")]
     headers.append(os.path.join(HERE, "..", "include", "vte.h"))
     if not force and not _newer(obj, [path] + headers):
         return obj, ""
-    cmd = ["hipcc"] + HIP_FLAGS + (["-x", "hip"] if src.endswith(".cpp") else []) + ["-c", path, "-o", obj]
+    cmd = ["hipcc"] + HIP_FLAGS + ["-D" + d for d in defines] + (["-x", "hip"] if src.endswith(".cpp") else []) + ["-c", path, "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     log = "\n".join(l for l in (r.stdout + r.stderr).splitlines() if "not a recognized feature" not in l)
     if r.returncode != 0:
@@ -42,7 +47,14 @@ def _compile(src, force):
     return obj, log
 
 
-def build(force=False, jobs=None):
+def _link(out, objs):
+    cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", out] + objs + ["-lpthread"]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("link failed:\n" + r.stdout + r.stderr)
+
+
+def build(force=False, jobs=None, trace=False):
     os.makedirs(OBJ, exist_ok=True)
     jobs = jobs or min(8, os.cpu_count() or 1)
     with cf.ThreadPoolExecutor(jobs) as ex:
@@ -52,14 +64,18 @@ def build(force=False, jobs=None):
         if log.strip():
             sys.stderr.write(log + "\n")
     if force or _newer(OUT, objs):
-        cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", OUT] + objs + ["-lpthread"]
-        r = subprocess.run(cmd, capture_output=True, text=True)
-        if r.returncode != 0:
-            raise RuntimeError("link failed:\n" + r.stdout + r.stderr)
+        _link(OUT, objs)
+    if trace:
+        tobj, log = _compile(TRACED, force, defines=("VTE_TRACE_STAMPS",), tag=".trace")
+        if log.strip():
+            sys.stderr.write(log + "\n")
+        tobjs = [tobj if o.endswith(os.sep + TRACED + ".o") else o for o in objs]
+        if force or _newer(OUT_TRACE, tobjs):
+            _link(OUT_TRACE, tobjs)
     from . import inputs
     inputs.build(force)
     return OUT
 
 
 if __name__ == "__main__":
-    print(build(force="--force" in sys.argv))
+    print(build(force="--force" in sys.argv, trace="--trace" in sys.argv))

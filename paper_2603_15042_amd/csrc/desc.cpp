@@ -253,6 +253,8 @@ int plan_gemv(int B, int outputs, int kps, int epi, vte_gemv_plan* p) {
     else if (tiles >= 1024) { g = 8; }
     else if (tiles > 256 && kps <= 4096) { nbk = 8; g = 2; mw = 4; }  // X once per workgroup, as above
     else if (tiles > 256 && kps <= 8192) { g = 2; mw = 4; }
+    else if (kps > 2048 && kps <= 4096) { nbk = 8; mw = 4; }  // one 1024-element chunk per wave: X is fetched and turned once,
+                                                              // ahead of the weights; 6-8 % faster than 512-element chunks at every width
     else if (kps <= 4096) { nb = 4; mw = 4; }  // four-wave workgroups share a CU three at a time: as fast at full
                                                // width, up to 30 % faster on 32 to 128 CUs than eight waves
     p->batch_tile = 16; p->rows = 16 * g; p->ksteps = nbk; p->prefetch = nb; p->max_waves = mw; p->groups = rounds;

@@ -37,3 +37,11 @@ extern "C" const void* vte_gemv_entry_mfma(int nbk, int g, int nb, int maxw, int
   VTE_MFMA_CASE(8, 2, 2, 4)
   return nullptr;
 }
+
+#ifdef VTE_TRACE_STAMPS
+// Trace build only: copies the stamp table of this file's kernels (most recent launch) to the host.
+extern "C" int vte_trace_stamps_read(unsigned long long* host, size_t count) {
+  if (count > static_cast<size_t>(kTraceWorkgroups) * kTraceWaves * kTracePoints) return -1;
+  return static_cast<int>(hipMemcpyFromSymbol(host, HIP_SYMBOL(vte_trace_stamps), count * sizeof(unsigned long long)));
+}
+#endif

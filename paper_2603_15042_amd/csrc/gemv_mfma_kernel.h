@@ -38,6 +38,7 @@
 // same chain, so a row's result does not depend on its position or on the rows beside it.
 #pragma once
 #include "gemv_kernels.h"
+#include "trace_stamps.h"
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
@@ -58,6 +59,7 @@ __global__ __launch_bounds__(MAXW * 64) void gemv_mfma_kernel(const GemvArgs a) 
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int nw = blockDim.x >> 6;
   const int c = lane & 15, q = lane >> 4;    // MFMA operand coordinates
+  VTE_STAMP(0);  // entry
   const int lr = lane >> 4, lp = lane & 15;  // load coordinates: row within a 4-row group, 16-byte piece of 256 B
   const int split = blockIdx.y;
   const int row0 = blockIdx.z * 16 * CT;  // first batch row of this workgroup (a batch above 16 CT runs as chunks in z)
@@ -194,6 +196,7 @@ __global__ __launch_bounds__(MAXW * 64) void gemv_mfma_kernel(const GemvArgs a) 
 #pragma unroll
     for (int t = 0; t < NB; ++t) load_block(wbuf[t], 0, wave, t / NBK, t % NBK);
   }
+  VTE_STAMP(1);  // launch arguments in, first loads issued
   for (int rd = 0; rd < a.groups; ++rd) {
 #pragma unroll
     for (int g = 0; g < G; ++g)
@@ -204,6 +207,7 @@ __global__ __launch_bounds__(MAXW * 64) void gemv_mfma_kernel(const GemvArgs a) 
       while (true) {
         // X of this chunk arrived in load order: once per launch when a wave has a single chunk, else per chunk pass
         if (!ONECHUNK || rd == 0) transpose_x();
+        if (rd == 0 && ch == wave) VTE_STAMP(2);  // X arrived and turned
         const int chn = ch + nw;
         const bool more = !ONECHUNK && chn < nchunks;  // ONECHUNK: the launch has no more chunks than waves
         const bool next_round = rd + 1 < a.groups;
@@ -246,6 +250,7 @@ __global__ __launch_bounds__(MAXW * 64) void gemv_mfma_kernel(const GemvArgs a) 
           }
           __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
           __builtin_amdgcn_wave_barrier();
+          if (t == 0 && rd == 0 && ch == wave) VTE_STAMP(3);  // first block of weights multiplied
         }
         __builtin_amdgcn_sched_barrier(0);
         if (ONECHUNK || !more) break;
@@ -253,6 +258,7 @@ __global__ __launch_bounds__(MAXW * 64) void gemv_mfma_kernel(const GemvArgs a) 
       }
     }
 
+    if (rd == a.groups - 1) VTE_STAMP(4);  // the wave's share of the stream is through
     // wave partial tiles -> the wave's own LDS area (its transposes of this round are
     // done): lane (c, q), register v holds tile row 4 q + v of batch row c
 #pragma unroll
@@ -262,6 +268,7 @@ __global__ __launch_bounds__(MAXW * 64) void gemv_mfma_kernel(const GemvArgs a) 
 #pragma unroll
         for (int v = 0; v < 4; ++v) part_all[wave * WAVE_F + ((g * CT + ct) * 4 + v) * 64 + lane] = acc[g][ct][v];
     __syncthreads();
+    if (rd == a.groups - 1) VTE_STAMP(5);  // every wave of the workgroup is through
     for (int f = threadIdx.x; f < G * CT * 64; f += blockDim.x) {
       const int gc = f >> 6, g = gc / CT, ln = f & 63, col = 16 * (gc % CT) + (ln & 15), qq = ln >> 4;
       if (qq >= QOUT) continue;
@@ -296,7 +303,8 @@ __global__ __launch_bounds__(MAXW * 64) void gemv_mfma_kernel(const GemvArgs a) 
         }
       }
     }
-    __syncthreads();  // the LDS areas are transposition space again
+    if (rd + 1 < a.groups) __syncthreads();  // the LDS areas are transposition space again
+    else VTE_STAMP(6);  // cross-wave sums added, outputs stored
   }
 
   // ---- split-K baseline: the last chunk-block of this row block adds the chunk sums.  Without a

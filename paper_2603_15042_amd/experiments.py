@@ -2,6 +2,7 @@
 
     python -m paper_2603_15042_amd.experiments determinism [--trials 1000] [--replays 100]
     python -m paper_2603_15042_amd.experiments cotenancy   [--seconds 3] [--gap-ms 60]
+    python -m paper_2603_15042_amd.experiments gemm | operators | overhead | ramp
 
 determinism  Sec. 7.1 "Determinism Protocol" / Sec. 7.2: matched-input trials of a reduction
              (RMSNorm 8x1024) and a GEMV (4096x4096, batch 1/4/8) with only the physical
@@ -628,6 +629,62 @@ def overhead_pools(launches):
     return arms
 
 
+RAMP_POINTS = ("entry", "arguments in, first loads issued", "X arrived and turned", "first block of weights multiplied",
+               "wave's share of the stream through", "all waves of the workgroup through", "sums added, outputs stored")
+
+
+def ramp(batches=(8, 16), N=4096, K=4096, width=256, bursts=9):
+    """Where the time of one small GEMV launch goes (BASELINE config 2: 4096 x 4096; the matrix-core
+    kind, batch 5 to 16).  Needs the trace build of the library (`python -m paper_2603_15042_amd.build
+    --trace`), whose kernels stamp the device's 100 MHz clock per wave (csrc/trace_stamps.h): 128
+    launches back to back on a stream pinned to one pCtx, 32 weight buffers in rotation; reported are,
+    for the last launch of a burst, the stamps of all waves relative to the first wave's entry (each
+    statistic the median over several bursts), and the time per launch of the burst (which also holds
+    the gap between launches)."""
+    import ctypes as C
+    L = vte.load()
+    if not hasattr(L, "vte_trace_stamps_read"):
+        raise RuntimeError("ramp needs the trace build: python -m paper_2603_15042_amd.build --trace, then run with "
+                           "the ramp command first on the command line (it selects libvte_trace.so before the library loads)")
+    ctx = H.make_ctx(vte.VTE_MODE_PIPELINED, lookahead=64)
+    Ws = [H.to_dev(inputs.normal_bf16(i, inputs.T_W, (N, K), 0.0, K ** -0.5)) for i in range(32)]
+    out = {"shape": [N, K], "width": width, "points": list(RAMP_POINTS), "batches": {}}
+    for B in batches:
+        X = H.to_dev(inputs.normal_bf16(0, inputs.T_XB, (B, K)))
+        Y = torch.empty((B, N), dtype=torch.int16, device="cuda")
+        ds = [vte.vte_desc_gemv(ctx, W_, X, Y, B, N, K) for W_ in Ws]
+        info = vte.vte_desc_info(ds[0])
+        v = vte.vte_vstream_create(ctx, vte.VTE_CLASS_LATENCY)
+        vte.vte_vstream_pin(v, H.pctx_of_width(ctx, width))
+        vte.vte_token_wait(ctx, vte.vte_submit_batch(v, vte.desc_array(ds)))
+        wgs, waves = info.grid[0], info.block[0] // 64
+        per_launch, tables = [], []
+        for burst in range(bursts):
+            tb = time.perf_counter()
+            vte.vte_token_wait(ctx, vte.vte_submit_batch(v, vte.desc_array(ds * 4)))
+            per_launch.append((time.perf_counter() - tb) / (4 * len(ds)))
+            torch.cuda.synchronize()
+            buf = np.zeros(1024 * 8 * 8, dtype=np.uint64)
+            rc = L.vte_trace_stamps_read(buf.ctypes.data_as(C.c_void_p), C.c_size_t(buf.size))
+            if rc != 0:
+                raise RuntimeError("vte_trace_stamps_read: HIP error %d" % rc)
+            st = buf.reshape(1024, 8, 8).astype(np.int64)[:min(wgs, 1024), :waves, :len(RAMP_POINTS)]
+            rel = (st - st[:, :, 0].min()) * 0.01                 # us after the first wave's entry
+            tables.append([[float(f(rel[:, :, i])) for f in (np.min, lambda c: np.percentile(c, 10), np.median,
+                                                             lambda c: np.percentile(c, 90), np.max)] for i in range(len(RAMP_POINTS))])
+        vte.vte_vstream_destroy(v)
+        med = np.median(np.array(tables), axis=0)                 # per statistic, the median over the bursts' last launches
+        rows = {name: dict(zip(("min", "p10", "median", "p90", "max"), (round(float(x), 2) for x in med[i]))) for i, name in enumerate(RAMP_POINTS)}
+        t = float(np.median(per_launch)) * 1e6
+        out["batches"][str(B)] = {"workgroups": int(wgs), "waves_per_workgroup": int(waves), "bursts": bursts,
+                                  "us_per_launch_back_to_back": round(t, 2), "us_after_first_entry": rows,
+                                  "last_wave_done_to_next_launch_entry_us": round(t - float(med[len(RAMP_POINTS) - 1][4]), 2)}
+        for d in ds:
+            vte.vte_desc_destroy(d)
+    vte.vte_shutdown(ctx)
+    return out
+
+
 def main(argv=None):
     ap = argparse.ArgumentParser()
     sub = ap.add_subparsers(dest="cmd", required=True)
@@ -643,7 +700,13 @@ def main(argv=None):
     ov.add_argument("--launches", type=int, default=200)
     o = sub.add_parser("operators")
     o.add_argument("--reps", type=int, default=8)
+    sub.add_parser("ramp")
     a = ap.parse_args(argv)
+    if a.cmd == "ramp":                       # the trace build, selected before anything loads the library
+        import os
+        vte.LIB_PATH = os.path.join(os.path.dirname(vte.LIB_PATH), "libvte_trace.so")
+        print(json.dumps(ramp()))
+        return
     if a.cmd == "determinism":
         out = determinism(a.trials, a.replays)
     elif a.cmd == "gemm":
