@@ -588,6 +588,10 @@ int vte_stats(vte_ctx* ctx, vte_stats_t* out);
 int vte_stats_read(vte_ctx* ctx, vte_op_record* dst, int cap, int* n_out);
 /* Zeroes the counters and empties the record ring; launches in flight are still recorded. */
 int vte_stats_reset(vte_ctx* ctx);
+/* Changes which launches carry device timing events from now on (vte_pool_cfg.device_timing_mask and
+ * device_timing_stride; same meaning, same limits; the per-kernel sampling counters restart).
+ * Launches already submitted keep what they have.  VTE_EINVAL for a negative stride. */
+int vte_set_device_timing(vte_ctx* ctx, unsigned mask, int stride);
 
 /* ---- fake backend hooks (VTE_BACKEND_FAKE only; VTE_ESTATE otherwise) ---------- */
 /* With the fake backend a submitted op stays in flight until completed here. */

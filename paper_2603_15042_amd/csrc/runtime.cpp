@@ -1398,6 +1398,15 @@ int vte_set_builtin_policy(vte_ctx* c, int which, double slack, int keep_free_cu
   return VTE_OK;
 }
 
+int vte_set_device_timing(vte_ctx* c, unsigned mask, int stride) {
+  if (!c || stride < 0) { set_error("set_device_timing: bad argument"); return VTE_EINVAL; }
+  Lock lk(c->mu);
+  c->cfg.device_timing_mask = mask;
+  c->cfg.device_timing_stride = stride;
+  for (auto& n : c->timing_seen) n = 0;
+  return VTE_OK;
+}
+
 int vte_hint_submit(vte_ctx* c, const vte_hint* hint) {
   if (!c || !hint) { set_error("null argument"); return VTE_EINVAL; }
   Lock lk(c->mu);

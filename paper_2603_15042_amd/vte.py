@@ -126,7 +126,7 @@ EXPORTS = [
     "vte_fake_log", "vte_dispatcher_quiesce", "vte_now", "vte_vstream_set_tpot", "vte_vstream_tpot_info", "vte_submit_batch", "vte_pool_creation_order", "vte_desc_memcpy", "vte_desc_memset32",
     "vte_event_record", "vte_vstream_wait_event", "vte_desc_softmax_prob",
     "vte_static_scratch_bytes", "vte_lmhead_argmax_static", "vte_fake_complete_error",
-    "vte_gemv_fixed_split", "vte_desc_gemv_split", "vte_desc_gemv_split_finish",
+    "vte_gemv_fixed_split", "vte_desc_gemv_split", "vte_desc_gemv_split_finish", "vte_set_device_timing",
 ]
 
 _lib = None
@@ -458,6 +458,10 @@ def vte_pctx_unreserve(ctx, pctx_id):
 def vte_set_policy(ctx, vtbl, user=None):
     """vtbl: a vte_policy_vtbl the caller keeps alive (with its callbacks), or None."""
     _check(load().vte_set_policy(ctx, C.byref(vtbl) if vtbl is not None else None, user))
+
+
+def vte_set_device_timing(ctx, mask, stride):
+    _check(load().vte_set_device_timing(ctx, C.c_uint(mask), int(stride)))
 
 
 def vte_set_builtin_policy(ctx, which, slack=0.1, keep_free_cus=0):
