@@ -308,6 +308,22 @@ def main():
         strict_tok = ch2.tok.cpu().numpy().copy()
         out["strict"] = {"ms_per_step": round(e / n * 1e3, 4), "GB/s": round(step_bytes * n / e / 1e9, 1),
                          "pct_peak": round(100 * step_bytes * n / e / 1e9 / HBM_PEAK_GBS, 2), "steps": n}
+        # the same chain with the step boundary in the QKV launch's prologue (five launches per step, the
+        # same bits): a loss of about 2 % under pipelined binding, where a launch boundary is free, and a
+        # gain under strict binding, where each boundary is a host round trip
+        if B <= 16 and shp.D == 4096:
+            ch5 = H.DecodeChain(ctx2, wd, shp, B, feedback=True, fused_gather=True, fused_argmax=True, fused_qkv=True)
+            ch5.set_tokens(tok0)
+            run(ch5, 30, vs2)
+            ch5.set_tokens(tok0)
+            t = time.perf_counter()
+            run(ch5, n, vs2)
+            e5 = time.perf_counter() - t
+            out["strict"]["five_launches_per_step"] = {
+                "ms_per_step": round(e5 / n * 1e3, 4), "GB/s": round(ch5.bytes_per_step * n / e5 / 1e9, 1),
+                "pct_peak": round(100 * ch5.bytes_per_step * n / e5 / 1e9 / HBM_PEAK_GBS, 2),
+                "tokens_equal_six_launches": bool(np.array_equal(strict_tok, ch5.tok.cpu().numpy()))}
+            ch5.close()
         # the pipelined chain of the timed region, from the same tokens, after the same number of steps
         vte.vte_vstream_destroy(vs2)
         # ---- BASELINE config 1: launch latency of the 8 x 1024 RMSNorm per width -------------------
@@ -326,6 +342,19 @@ def main():
         ch3.set_tokens(tok0)
         run(ch3, n, vs3)
         out["strict"]["tokens_equal_pipelined"] = bool(np.array_equal(strict_tok, ch3.tok.cpu().numpy()))
+        if B <= 16 and shp.D == 4096:   # the five-launch chain under pipelined binding, beside the six-launch one
+            res5 = {}
+            for name, fq in (("six_launches", False), ("five_launches", True)):
+                c = ch3 if not fq else H.DecodeChain(ctx3, wd, shp, B, feedback=True, fused_gather=True, fused_argmax=True, fused_qkv=True)
+                c.set_tokens(tok0)
+                run(c, 100, vs3)
+                t = time.perf_counter()
+                run(c, n, vs3)
+                e6 = time.perf_counter() - t
+                res5[name] = {"ms_per_step": round(e6 / n * 1e3, 4), "GB/s": round(c.bytes_per_step * n / e6 / 1e9, 1)}
+                if fq:
+                    c.close()
+            out["boundary_in_qkv_launch_pipelined"] = res5
         vte.vte_vstream_destroy(vs3)
         ch3.close()
         vte.vte_shutdown(ctx3)

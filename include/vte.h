@@ -197,6 +197,26 @@ int vte_desc_rmsnorm_gather(vte_ctx* ctx, const void* E, const int32_t* tok, con
 int vte_desc_rmsnorm_gather_argmax(vte_ctx* ctx, const void* E, const vte_desc* lmhead,
                                    int32_t* tok_out_or_null, const void* gamma, void* y, void* h_or_null,
                                    int V, int cols, float eps, vte_desc** out);
+/* The step boundary folded into the launch that consumes it: Y[b,:] = W * rmsnorm(E[tok[b],:]) with
+ * the RMSNorm above (same tree, same single rounding to bf16) computed in the prologue of the GEMV,
+ * by every workgroup for itself, while the first weights are on their way; one launch fewer per
+ * decode step (Sec. 7.1 / 7.2 decode loop; Sec. 3.1: the structure depends on the shape alone).
+ * W: device [N,K] bf16; E: device [V,K] bf16, below 2 GiB; gamma: device [K] bf16; Y: device [B,N]
+ * bf16; h_or_null, n_or_null: optional device [B,K] bf16 copies of the gathered and of the
+ * normalised rows (for inspection; what vte_desc_rmsnorm_gather stores).  Built for K = 4096,
+ * 1 <= B <= 16, N >= 16; anything else returns VTE_EINVAL.  The GEMV is the matrix-core kind with
+ * one 1024-element chunk per wave: its output bits equal vte_desc_gemv_planned with that plan
+ * (batch_tile 16, ksteps 8, prefetch 2, max_waves 4, groups 1, rows 32 above 256 row tiles, else 16)
+ * on the output of vte_desc_rmsnorm_gather.
+ * _gather takes the tokens (device [B] int32, clamped to [0,V)); _gather_argmax finishes them from
+ * the candidates of `lmhead` first (as vte_desc_rmsnorm_gather_argmax; B is the LM head's batch) and
+ * stores them to tok_out_or_null. */
+int vte_desc_gemv_rmsnorm_gather(vte_ctx* ctx, const void* W, const void* E, const int32_t* tok, const void* gamma,
+                                 void* Y, void* h_or_null, void* n_or_null, int B, int V, int N, int K, float eps,
+                                 vte_desc** out);
+int vte_desc_gemv_rmsnorm_gather_argmax(vte_ctx* ctx, const void* W, const void* E, const vte_desc* lmhead,
+                                        int32_t* tok_out_or_null, const void* gamma, void* Y, void* h_or_null,
+                                        void* n_or_null, int V, int N, int K, float eps, vte_desc** out);
 /* y = (x - mu) * rsqrt(var + eps) * gamma + beta, biased variance, two fixed-tree
  * fp32 reductions (mean, then centred squares).  Same layout and limits. (Sec. 1) */
 int vte_desc_layernorm(vte_ctx* ctx, const void* x, const void* gamma, const void* beta,
@@ -359,7 +379,8 @@ enum {
   VTE_K_RMSNORM = 1, VTE_K_LAYERNORM = 2, VTE_K_GEMV = 3, VTE_K_LMHEAD = 4, VTE_K_GATHER = 5,
   VTE_K_GEMM = 6, VTE_K_GEMV_SPLITK = 7, VTE_K_LMHEAD_SPLITK = 8, VTE_K_RMSNORM_RESHAPED = 9,
   VTE_K_ARGMAX_FINISH = 10, VTE_K_RMSNORM_GATHER = 11, VTE_K_RMSNORM_GATHER_ARGMAX = 12,
-  VTE_K_MEMCPY = 13, VTE_K_MEMSET = 14, VTE_K_SOFTMAX_PROB = 15, VTE_K_GEMV_SPLIT = 16, VTE_K_GEMV_SPLIT_FINISH = 17
+  VTE_K_MEMCPY = 13, VTE_K_MEMSET = 14, VTE_K_SOFTMAX_PROB = 15, VTE_K_GEMV_SPLIT = 16, VTE_K_GEMV_SPLIT_FINISH = 17,
+  VTE_K_GEMV_NORM = 18
 };
 typedef struct vte_desc_view {
   int kernel;           /* VTE_K_* */

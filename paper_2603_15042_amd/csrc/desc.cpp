@@ -25,6 +25,7 @@ const void* vte_gemv_entry_mfma(int, int, int, int, int, int, int);
 const void* vte_gemv_entry_mfma32(int, int, int, int, int, int, int);
 const void* vte_gemv_entry_rows(int, int, int, int, int);
 const void* vte_gemv_entry_mfma64(int, int, int, int, int, int, int);
+const void* vte_gemv_entry_mfma_norm(int);
 const void* vte_gather_entry();
 const void* vte_argmax_finish_entry();
 const void* vte_split_finish_entry();
@@ -449,6 +450,60 @@ int vte_desc_rmsnorm_gather_argmax(vte_ctx* ctx, const void* E, const vte_desc* 
   const uint32_t* cand = g.ws + 1 + lmhead->grid[0] * lmhead->grid[2];
   return build_norm(ctx, VTE_K_RMSNORM_GATHER_ARGMAX, false, E, gamma, nullptr, y, g.B, cols, eps, norm_threads(cols),
                     out, nullptr, h_or_null, V, cand, static_cast<int>(lmhead->grid[0]), g.bt, tok_out_or_null);
+}
+
+// The first projection of a decode step with the step boundary in its prologue (kargs.h: GemvNormArgs).
+static int build_gemv_norm(vte_ctx* ctx, const void* W, const void* E, const int32_t* tok, const uint32_t* cand, int nblocks,
+                           int cand_bt, int32_t* tok_out, const void* gamma, void* Y, void* h_out, void* n_out, int B,
+                           int V, int N, int K, float eps, vte_desc** out) {
+  if (!ctx || !out || !W || !E || !gamma || !Y || (!tok && !cand)) { set_error("gemv_rmsnorm: null argument"); return VTE_EINVAL; }
+  if (B < 1 || B > 16 || N < 16 || V < 1) { set_error("gemv_rmsnorm: need 1 <= B <= 16, N >= 16, V >= 1"); return VTE_EINVAL; }
+  if (K != 4096) { set_error("gemv_rmsnorm: the fused form is built for K = 4096 (one 1024-element chunk for each of four waves)"); return VTE_EINVAL; }
+  if (static_cast<uint64_t>(V) * K * 2 >= (1ull << 31)) { set_error("gemv_rmsnorm: the embedding table spans 2 GiB or more"); return VTE_EINVAL; }
+  if (!aligned16(W) || !aligned16(E) || !aligned16(gamma) || (h_out && !aligned16(h_out)) || (n_out && !aligned16(n_out))) {
+    set_error("gemv_rmsnorm: pointers must be 16-byte aligned"); return VTE_EINVAL;
+  }
+  const int tiles = (N + 15) / 16;
+  const int g = tiles > 256 ? 2 : 1;  // the row tiles per workgroup of the default plan for these shapes
+  GemvNormArgs a{};
+  a.g.W = static_cast<const uint16_t*>(W);
+  a.g.Y = static_cast<uint16_t*>(Y);
+  a.g.B = B; a.g.N = N; a.g.K = K; a.g.n_out = N;
+  a.g.ldx = K; a.g.ldy = N;
+  a.g.groups = 1; a.g.S = 1; a.g.k_per_split = K; a.g.bt = 16;
+  a.E = static_cast<const uint16_t*>(E);
+  a.gamma = static_cast<const uint16_t*>(gamma);
+  a.tok = cand ? nullptr : tok;
+  a.cand = cand;
+  a.tok_out = tok_out;
+  a.h_out = static_cast<uint16_t*>(h_out);
+  a.n_out = static_cast<uint16_t*>(n_out);
+  a.V = V; a.nblocks = nblocks; a.cand_bt = cand_bt; a.eps = eps;
+  const int shape_v[5] = {B, N, K, V, nblocks};
+  const uint64_t bytes = 2ull * N * K + 2ull * B * N + 2ull * B * K + 2ull * K + (cand ? 8ull * nblocks * B : 0) + 4ull * B;
+  return finish_desc(ctx, VTE_K_GEMV_NORM, vte_gemv_entry_mfma_norm(g), a, static_cast<uint32_t>((N + 16 * g - 1) / (16 * g)),
+                     1, 256, 0, fnv1a(shape_v, sizeof shape_v), bytes, 2ull * B * N * K, out);
+}
+
+int vte_desc_gemv_rmsnorm_gather(vte_ctx* ctx, const void* W, const void* E, const int32_t* tok, const void* gamma,
+                                 void* Y, void* h_or_null, void* n_or_null, int B, int V, int N, int K, float eps,
+                                 vte_desc** out) {
+  if (!tok) { set_error("gemv_rmsnorm_gather: tok is required"); return VTE_EINVAL; }
+  return build_gemv_norm(ctx, W, E, tok, nullptr, 0, 0, nullptr, gamma, Y, h_or_null, n_or_null, B, V, N, K, eps, out);
+}
+
+int vte_desc_gemv_rmsnorm_gather_argmax(vte_ctx* ctx, const void* W, const void* E, const vte_desc* lmhead,
+                                        int32_t* tok_out_or_null, const void* gamma, void* Y, void* h_or_null,
+                                        void* n_or_null, int V, int N, int K, float eps, vte_desc** out) {
+  if (!ctx || !lmhead) { set_error("gemv_rmsnorm_gather_argmax: lmhead is required"); return VTE_EINVAL; }
+  if (lmhead->ctx != ctx || (lmhead->kernel != VTE_K_LMHEAD && lmhead->kernel != VTE_K_LMHEAD_SPLITK)) {
+    set_error("gemv_rmsnorm_gather_argmax: needs an LM-head descriptor of this context"); return VTE_EINVAL;
+  }
+  GemvArgs g;
+  std::memcpy(&g, lmhead->args, sizeof g);
+  const uint32_t* cand = g.ws + 1 + lmhead->grid[0] * lmhead->grid[2];
+  return build_gemv_norm(ctx, W, E, nullptr, cand, static_cast<int>(lmhead->grid[0]), g.bt, tok_out_or_null, gamma, Y,
+                         h_or_null, n_or_null, g.B, V, N, K, eps, out);
 }
 
 int vte_desc_layernorm(vte_ctx* ctx, const void* x, const void* gamma, const void* beta, void* y, int rows,

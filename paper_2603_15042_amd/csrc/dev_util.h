@@ -10,15 +10,15 @@ __device__ __forceinline__ float bf16_lo(uint32_t pair) { return __uint_as_float
 __device__ __forceinline__ float bf16_hi(uint32_t pair) { return __uint_as_float(pair & 0xffff0000u); }
 __device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float(static_cast<uint32_t>(h) << 16); }
 
-// fp32 -> bf16, round to nearest, ties to even; NaN stays NaN (quiet).
-__device__ __forceinline__ uint32_t f32_to_bf16(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
-  return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
-}
+// fp32 -> bf16, round to nearest, ties to even; NaN stays NaN (quiet, payload kept); denormals kept.
+// One v_cvt_pk_bf16_f32 per pair.  The instruction was checked on the device against the integer
+// formulation ((u + 0x7fff + ((u >> 16) & 1)) >> 16, NaN: (u >> 16) | 0x40) for every 16-bit upper half
+// with lower halves on both sides of the tie: no difference, NaN and denormal inputs included.
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
-  return f32_to_bf16(lo) | (f32_to_bf16(hi) << 16);
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2_t{lo, hi}, bf16x2_t));
 }
+__device__ __forceinline__ uint32_t f32_to_bf16(float f) { return pack_bf16(f, 0.f) & 0xffffu; }
 
 // acc + w.lo*x.lo + w.hi*x.hi on two packed bf16 pairs (v_dot2c_f32_bf16).
 __device__ __forceinline__ float dot2_bf16(uint32_t w, uint32_t x, float acc) {

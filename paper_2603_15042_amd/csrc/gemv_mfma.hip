@@ -38,6 +38,14 @@ extern "C" const void* vte_gemv_entry_mfma(int nbk, int g, int nb, int maxw, int
   return nullptr;
 }
 
+// The same kernel with the decode loop's step boundary in its prologue (K = 4096, batch <= 16):
+// g = row tiles per workgroup (1 or 2); nullptr otherwise.
+extern "C" const void* vte_gemv_entry_mfma_norm(int g) {
+  if (g == 1) return (const void*)gemv_mfma_kernel<8, 1, 2, 4, true, true, EPI_NONE, 1, true>;
+  if (g == 2) return (const void*)gemv_mfma_kernel<8, 2, 2, 4, true, true, EPI_NONE, 1, true>;
+  return nullptr;
+}
+
 #ifdef VTE_TRACE_STAMPS
 // Trace build only: copies the stamp table of this file's kernels (most recent launch) to the host.
 extern "C" int vte_trace_stamps_read(unsigned long long* host, size_t count) {

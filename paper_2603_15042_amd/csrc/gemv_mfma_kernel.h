@@ -36,6 +36,19 @@
 //   4. split-K baseline only: S chunk sums added in chunk order.
 // The batch columns of an MFMA are independent of each other and every column tile runs the
 // same chain, so a row's result does not depend on its position or on the rows beside it.
+//
+// PRO = true (one column tile, one 1024-element chunk per wave, K = 4096, 256 threads): the decode
+// loop's step boundary runs in the kernel's own prologue instead of in a launch of its own.  Every
+// workgroup finishes the greedy tokens from the LM head's candidates (a total order: no tree), fetches
+// the embedding rows, computes each row's sum of squares in exactly the tree of the stand-alone
+// RMSNorm launch for this row length (256 threads: thread t adds chunks t and t + 256 in ascending
+// order, fixed 64-lane butterfly, four wave sums added in wave order -- which is why the rows are
+// fetched a second time in that layout) and scales its own K range of every row with the same
+// expression, rounding to bf16 once: the B operand is then, bit for bit, what the RMSNorm launch
+// would have stored, and the GEMV proceeds as usual.  The weights are requested before anything
+// else, so the prologue's latencies (candidates, tokens, rows: three dependent fetches) run beside
+// the weight stream's first-byte latency.  Workgroup 0 stores the tokens and, if asked, the gathered
+// and the normalised rows.
 #pragma once
 #include "gemv_kernels.h"
 #include "trace_stamps.h"
@@ -43,8 +56,16 @@
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
-template <int NBK, int G, int NB, int MAXW, bool ALLFULL, bool ONECHUNK, int EPI, int CT>
-__global__ __launch_bounds__(MAXW * 64) void gemv_mfma_kernel(const GemvArgs a) {
+template <bool PRO> struct gemv_mfma_args { typedef GemvArgs type; };
+template <> struct gemv_mfma_args<true> { typedef GemvNormArgs type; };
+__device__ __forceinline__ const GemvArgs& gemv_part(const GemvArgs& a) { return a; }
+__device__ __forceinline__ const GemvArgs& gemv_part(const GemvNormArgs& a) { return a.g; }
+
+template <int NBK, int G, int NB, int MAXW, bool ALLFULL, bool ONECHUNK, int EPI, int CT, bool PRO = false>
+__global__ __launch_bounds__(MAXW * 64) void gemv_mfma_kernel(const typename gemv_mfma_args<PRO>::type aa) {
+  static_assert(!PRO || (CT == 1 && ONECHUNK && ALLFULL && NBK == 8 && MAXW == 4 && EPI == EPI_NONE),
+                "the fused prologue is built for one column tile and one 1024-element chunk per wave");
+  const GemvArgs& a = gemv_part(aa);
   constexpr int KC = 128 * NBK;
   constexpr int T = G * NBK;  // blocks of one chunk, tile-major
   static_assert(NB <= T && T % NB == 0, "the load window must divide a chunk's blocks");
@@ -92,8 +113,13 @@ __global__ __launch_bounds__(MAXW * 64) void gemv_mfma_kernel(const GemvArgs a) 
   }
   const uint32_t voff = (static_cast<uint32_t>(lr) * a.K + lp * 8) * 2u;  // bytes
   // X: rows past B lie outside the resource and read as zero
-  const __amdgpu_buffer_rsrc_t rs_x = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<uint16_t*>(a.X), 0, static_cast<int>((static_cast<uint32_t>(a.B - 1) * a.ldx + a.K) * 2u), kRsrcFlags);
+  __amdgpu_buffer_rsrc_t rs_x;
+  if constexpr (PRO)  // the rows come from the embedding table (the host checked that it stays below 2 GiB)
+    rs_x = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(aa.E), 0,
+                                             static_cast<int>(static_cast<uint32_t>(aa.V) * static_cast<uint32_t>(a.K) * 2u), kRsrcFlags);
+  else
+    rs_x = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(a.X), 0,
+                                             static_cast<int>((static_cast<uint32_t>(a.B - 1) * a.ldx + a.K) * 2u), kRsrcFlags);
   // X is fetched like the weights, coalesced (an instruction takes 4 batch rows x 256 B) and turned
   // into operand order through the wave's LDS area: fetched in operand order (lane = row + 16 x
   // K group) every lane of an instruction sits on its own cache line and the address unit, not the
@@ -191,7 +217,163 @@ __global__ __launch_bounds__(MAXW * 64) void gemv_mfma_kernel(const GemvArgs a) 
   constexpr int WAVE_F = WAVE_LDS * 4;  // floats per wave area
 
   const bool active = wave < nchunks;
-  if (active) {
+  if constexpr (PRO) {
+    __shared__ int s_tok[16];
+    __shared__ float s_part[4][16];
+    __shared__ float s_rstd[16];
+    // Publishes LDS stores to the other waves without a fence: a fence would also wait for the
+    // weight loads, which are meant to stay in flight through the whole prologue.
+    auto lds_barrier = [&]() {
+      asm volatile("" ::: "memory");
+      __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0)
+      __builtin_amdgcn_s_barrier();
+      asm volatile("" ::: "memory");
+    };
+    // The first weights are requested right behind the first loads of the prologue (loads return in
+    // order: in front of them they would hold the tokens back by an HBM round trip), and nothing
+    // below waits for them.
+    bool w_requested = false;
+    auto request_weights = [&]() {
+      if (w_requested) return;
+      w_requested = true;
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int t = 0; t < NB; ++t) load_block(wbuf[t], 0, wave, t / NBK, t % NBK);
+      __builtin_amdgcn_sched_barrier(0);
+    };
+    // 1. the tokens: from the LM head's candidates (best value, lowest index; a total order), or given
+    if (aa.cand) {
+      // wave w takes batch rows w, w + 4, ...; the candidates of all its rows are requested before the
+      // first is looked at (512 per row and pass), so the reduction costs one memory round trip
+      float bv[4];
+      int bi[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) { bv[j] = -INFINITY; bi[j] = INT_MAX; }
+      for (int base = 0; base < aa.nblocks; base += 512) {
+        float v[4][8];
+        int ix[4][8];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int r = wave + 4 * j;
+          const uint32_t* cv = aa.cand + static_cast<size_t>(r) * aa.nblocks;
+          const uint32_t* ci = aa.cand + static_cast<size_t>(aa.cand_bt) * aa.nblocks + static_cast<size_t>(r) * aa.nblocks;
+#pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            const int blk = base + 64 * i + lane;
+            const bool ok = r < a.B && blk < aa.nblocks;
+            v[j][i] = ok ? __uint_as_float(cv[blk]) : -INFINITY;
+            ix[j][i] = ok ? static_cast<int>(ci[blk]) : INT_MAX;
+          }
+        }
+        request_weights();
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+          for (int i = 0; i < 8; ++i)
+            if (better(v[j][i], ix[j][i], bv[j], bi[j])) { bv[j] = v[j][i]; bi[j] = ix[j][i]; }
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int r = wave + 4 * j;
+        if (r >= a.B) break;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+          const float ov = __shfl_xor(bv[j], d, 64);
+          const int oi = __shfl_xor(bi[j], d, 64);
+          if (better(ov, oi, bv[j], bi[j])) { bv[j] = ov; bi[j] = oi; }
+        }
+        const int t = (bi[j] == INT_MAX) ? 0 : bi[j];  // all-NaN row
+        if (lane == 0) {
+          s_tok[r] = t < 0 ? 0 : (t >= aa.V ? aa.V - 1 : t);
+          if (blockIdx.x == 0 && aa.tok_out) aa.tok_out[r] = t;
+        }
+      }
+    } else {
+      int t = 0;
+      if (static_cast<int>(threadIdx.x) < a.B) t = aa.tok[threadIdx.x];
+      request_weights();
+      if (static_cast<int>(threadIdx.x) < a.B) s_tok[threadIdx.x] = t < 0 ? 0 : (t >= aa.V ? aa.V - 1 : t);
+    }
+    request_weights();
+    lds_barrier();
+    // 2. this wave's K range of the raw rows, in the load layout of the B operand
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int br = 4 * u + lr;
+      voff_x[0][u] = br < a.B ? (static_cast<uint32_t>(s_tok[br]) * a.K + lp * 8) * 2u : 0x80000000u;
+    }
+    load_x(wave);
+    u32x4 gam[NBK];
+#pragma unroll
+    for (int bi = 0; bi < NBK; ++bi) gam[bi] = ld16(aa.gamma + wave * KC + bi * 128 + lp * 8);
+    // 3. every row's sum of squares in the tree of the stand-alone RMSNorm launch for this row length
+    const int nch = a.K >> 3;
+    const bool two = static_cast<int>(threadIdx.x) + 256 < nch;
+    for (int half = 0; half < 2; ++half) {
+      if (half * 8 >= a.B) break;
+      u32x4 v0[8], v1[8];
+#pragma unroll
+      for (int r8 = 0; r8 < 8; ++r8) {
+        const int r = half * 8 + r8;
+        const bool live = r < a.B;
+        const uint16_t* xr = aa.E + static_cast<size_t>(s_tok[live ? r : 0]) * a.K;
+        v0[r8] = live ? ld16(xr + threadIdx.x * 8) : zero;
+        v1[r8] = (live && two) ? ld16(xr + (threadIdx.x + 256) * 8) : zero;
+      }
+#pragma unroll
+      for (int r8 = 0; r8 < 8; ++r8) {
+        float ss = 0.f;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float lo = bf16_lo(v0[r8][e]), hi = bf16_hi(v0[r8][e]);
+          ss = fmaf(lo, lo, ss);
+          ss = fmaf(hi, hi, ss);
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float lo = bf16_lo(v1[r8][e]), hi = bf16_hi(v1[r8][e]);
+          ss = two ? fmaf(lo, lo, ss) : ss;
+          ss = two ? fmaf(hi, hi, ss) : ss;
+        }
+        ss = wave_sum(ss);
+        if (lane == 0) s_part[wave][half * 8 + r8] = ss;
+      }
+    }
+    lds_barrier();
+    if (static_cast<int>(threadIdx.x) < a.B) {
+      float s = s_part[0][threadIdx.x];
+#pragma unroll
+      for (int w = 1; w < 4; ++w) s += s_part[w][threadIdx.x];
+      s_rstd[threadIdx.x] = 1.0f / sqrtf(s / static_cast<float>(a.K) + aa.eps);
+    }
+    lds_barrier();
+    // 4. scale this wave's K range of every row, one rounding: the B operand, still in load order
+    const bool keep = blockIdx.x == 0;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (4 * u >= a.B) break;  // nothing but padding from here on: those registers already hold zeros
+      const int br = 4 * u + lr;
+      const float rstd = br < a.B ? s_rstd[br] : 0.f;
+#pragma unroll
+      for (int bi = 0; bi < NBK; ++bi) {
+        const u32x4 raw = xs[0][bi][u];
+        u32x4 o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float lo = bf16_lo(raw[e]) * rstd * bf16_lo(gam[bi][e]);
+          const float hi = bf16_hi(raw[e]) * rstd * bf16_hi(gam[bi][e]);
+          o[e] = pack_bf16(lo, hi);
+        }
+        if (br >= a.B) o = zero;
+        xs[0][bi][u] = o;
+        if (keep && br < a.B) {
+          const size_t at = static_cast<size_t>(br) * a.K + wave * KC + bi * 128 + lp * 8;
+          if (aa.h_out) st16(aa.h_out + at, raw);
+          if (aa.n_out) st16(aa.n_out + at, o);
+        }
+      }
+    }
+  } else if (active) {
     load_x(wave);  // the first chunk; with several chunks per wave the next one's X follows block by block below
 #pragma unroll
     for (int t = 0; t < NB; ++t) load_block(wbuf[t], 0, wave, t / NBK, t % NBK);

@@ -41,6 +41,21 @@ struct GemvArgs {
   int k_per_split;        // K / S
 };
 
+// A GEMV whose input rows are produced in its own prologue: the decode loop's step boundary
+// (greedy-token finish, embedding gather, RMSNorm) fused in front of the first projection.
+struct GemvNormArgs {
+  GemvArgs g;             // g.X is unused: the rows come from E
+  const uint16_t* E;      // embedding table [V,K] bf16
+  const uint16_t* gamma;  // [K] bf16
+  const int32_t* tok;     // tokens [B], or null when they come from the candidates
+  const uint32_t* cand;   // LM-head candidates: values [cand_bt][nblocks] (fp32 bits), then indices; or null
+  int32_t* tok_out;       // optional: where the finished tokens are also stored
+  uint16_t* h_out;        // optional [B,K]: the gathered rows
+  uint16_t* n_out;        // optional [B,K]: the normalised rows
+  int V, nblocks, cand_bt;
+  float eps;
+};
+
 struct GatherArgs {
   const uint16_t* E;
   const int32_t* tok;

@@ -45,6 +45,15 @@ __global__ __launch_bounds__(T) void norm_kernel(const NormArgs a) {
   const int row = blockIdx.x;
   if (row >= a.rows) return;
   const int nchunks = a.cols >> 3;
+  // gamma (and beta) do not depend on anything this launch computes: requested first, so that their
+  // latency is covered by the token reduction and the row fetch instead of following the row sum
+  u32x4 gv[kMaxChunks], bv4[kMaxChunks];
+#pragma unroll
+  for (int j = 0; j < kMaxChunks; ++j) {
+    const int c = threadIdx.x + j * T;
+    gv[j] = (c < nchunks) ? ld16(a.gamma + c * 8) : u32x4{0u, 0u, 0u, 0u};
+    if constexpr (LAYER) bv4[j] = (c < nchunks) ? ld16(a.beta + c * 8) : u32x4{0u, 0u, 0u, 0u};
+  }
   size_t src_row = row;
   if (a.cand) {
     // greedy token of this batch row: best (value, lowest index) over the candidates;
@@ -121,9 +130,9 @@ __global__ __launch_bounds__(T) void norm_kernel(const NormArgs a) {
   for (int j = 0; j < kMaxChunks; ++j) {
     const int c = threadIdx.x + j * T;
     if (c < nchunks) {
-      const u32x4 g = ld16(a.gamma + c * 8);
+      const u32x4 g = gv[j];
       u32x4 b = u32x4{0u, 0u, 0u, 0u};
-      if constexpr (LAYER) b = ld16(a.beta + c * 8);
+      if constexpr (LAYER) b = bv4[j];
       u32x4 o;
 #pragma unroll
       for (int e = 0; e < 4; ++e) {

@@ -27,7 +27,7 @@ struct vte_desc {
   uint32_t block[3];
   uint32_t lds_bytes;
   uint32_t arg_bytes;
-  alignas(16) unsigned char args[160];
+  alignas(16) unsigned char args[192];
   uint64_t hash;
   uint64_t profile_key;
   uint64_t bytes;

@@ -72,10 +72,13 @@ class DecodeChain:
     (eight launches; seven with fused_gather).  splitk=S builds the reshaped variant of every
     GEMV instead (the negative control).  fused_argmax adds the step-boundary descriptor that
     finishes the previous step's token, gathers and normalises in one launch: a burst is then
-    first step (7 launches, no finish) + later steps (6 launches each) + one finish at the end."""
+    first step (7 launches, no finish) + later steps (6 launches each) + one finish at the end.
+    fused_qkv (with fused_argmax; hidden size 4096, batch <= 16) folds that boundary into the QKV launch:
+    5 launches per step.  With want_logits the fused launch also stores the gathered and the normalised
+    rows, so that snapshot() shows the same buffers as the other forms."""
 
     def __init__(self, ctx, weights_dev, shp, B, eps=1e-6, want_logits=False, splitk=None, rms_active_cus=None,
-                 feedback=False, fused_gather=False, fused_argmax=False, fixed_split=True):
+                 feedback=False, fused_gather=False, fused_argmax=False, fixed_split=True, fused_qkv=False):
         self.ctx, self.shp, self.B = ctx, shp, B
         D, Nq, F, V = shp.D, shp.Nqkv, shp.F, shp.V
         w = self.w = weights_dev
@@ -150,6 +153,15 @@ class DecodeChain:
             body = [k for k in self.order if k not in ("gather", "rmsnorm", "argmax")]
             self.order_first = [k for k in self.order if k != "argmax"]
             self.order_next = ["boundary"] + body
+            if fused_qkv:
+                keep = (self.h0, self.n) if want_logits else (None, None)
+                d["qkv_first"] = vte.vte_desc_gemv_rmsnorm_gather(ctx, w["Wqkv"], w["E"], self.tok, w["gamma"], self.qkv,
+                                                                  keep[0], keep[1], B, V, Nq, D, eps)
+                d["qkv_next"] = vte.vte_desc_gemv_rmsnorm_gather_argmax(ctx, w["Wqkv"], w["E"], d["lmhead"], self.next,
+                                                                        w["gamma"], self.qkv, keep[0], keep[1], V, Nq, D, eps)
+                rest = [k for k in body if k not in ("qkv", "qkv_fin")]
+                self.order_first = ["qkv_first"] + rest
+                self.order_next = ["qkv_next"] + rest
             self.bytes_per_step = sum(self.alg_bytes.get(k, vte.vte_desc_info(d[k]).bytes) for k in self.order_next if k != "q")
         else:
             self.bytes_per_step = sum(self.alg_bytes.get(k, vte.vte_desc_info(d[k]).bytes) for k in self.order if k != "q")

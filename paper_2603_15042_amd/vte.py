@@ -25,7 +25,7 @@ VTE_GEMV_DOT2, VTE_GEMV_MFMA, VTE_GEMV_MFMA_ROWS = 0, 1, 2
 (VTE_K_RMSNORM, VTE_K_LAYERNORM, VTE_K_GEMV, VTE_K_LMHEAD, VTE_K_GATHER, VTE_K_GEMM, VTE_K_GEMV_SPLITK,
  VTE_K_LMHEAD_SPLITK, VTE_K_RMSNORM_RESHAPED, VTE_K_ARGMAX_FINISH, VTE_K_RMSNORM_GATHER,
  VTE_K_RMSNORM_GATHER_ARGMAX, VTE_K_MEMCPY, VTE_K_MEMSET, VTE_K_SOFTMAX_PROB, VTE_K_GEMV_SPLIT,
- VTE_K_GEMV_SPLIT_FINISH) = range(1, 18)
+ VTE_K_GEMV_SPLIT_FINISH, VTE_K_GEMV_NORM) = range(1, 19)
 
 
 class VteError(RuntimeError):
@@ -127,6 +127,7 @@ EXPORTS = [
     "vte_event_record", "vte_vstream_wait_event", "vte_desc_softmax_prob",
     "vte_static_scratch_bytes", "vte_lmhead_argmax_static", "vte_fake_complete_error",
     "vte_gemv_fixed_split", "vte_desc_gemv_split", "vte_desc_gemv_split_finish", "vte_set_device_timing",
+    "vte_desc_gemv_rmsnorm_gather", "vte_desc_gemv_rmsnorm_gather_argmax",
 ]
 
 _lib = None
@@ -245,6 +246,16 @@ def vte_desc_rmsnorm_gather(ctx, E, tok, gamma, y, h_or_null, B, V, cols, eps):
 def vte_desc_rmsnorm_gather_argmax(ctx, E, lmhead, tok_out_or_null, gamma, y, h_or_null, V, cols, eps):
     return _desc_call(load().vte_desc_rmsnorm_gather_argmax, ctx, _ptr(E), lmhead, _ptr(tok_out_or_null), _ptr(gamma),
                       _ptr(y), _ptr(h_or_null), int(V), int(cols), C.c_float(eps))
+
+
+def vte_desc_gemv_rmsnorm_gather(ctx, W, E, tok, gamma, Y, h_or_null, n_or_null, B, V, N, K, eps):
+    return _desc_call(load().vte_desc_gemv_rmsnorm_gather, ctx, _ptr(W), _ptr(E), _ptr(tok), _ptr(gamma), _ptr(Y),
+                      _ptr(h_or_null), _ptr(n_or_null), int(B), int(V), int(N), int(K), C.c_float(eps))
+
+
+def vte_desc_gemv_rmsnorm_gather_argmax(ctx, W, E, lmhead, tok_out_or_null, gamma, Y, h_or_null, n_or_null, V, N, K, eps):
+    return _desc_call(load().vte_desc_gemv_rmsnorm_gather_argmax, ctx, _ptr(W), _ptr(E), lmhead, _ptr(tok_out_or_null),
+                      _ptr(gamma), _ptr(Y), _ptr(h_or_null), _ptr(n_or_null), int(V), int(N), int(K), C.c_float(eps))
 
 
 def vte_desc_layernorm(ctx, x, gamma, beta, y, rows, cols, eps):

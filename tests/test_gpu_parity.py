@@ -1330,6 +1330,142 @@ def test_fused_step_boundary_rejects_a_non_lmhead_descriptor(H, ctx, small_chain
     ch.close()
 
 
+@pytest.fixture(scope="module")
+def chain_4096(H, ctx):
+    """Hidden size 4096 (what the fused QKV launch is built for), everything else small."""
+    shp = inputs.DecodeShapes(D=4096, Nqkv=6144, F=1024, V=4099)
+    w = inputs.decode_weights(12, shp)
+    for k in ("Wqkv", "Wo", "Wgu", "Wd"):
+        w[k] = inputs.normal_bf16(12, 100 + len(k), w[k].shape, 0.0, 1.5 * w[k].shape[1] ** -0.5)
+    return shp, w, H.upload_weights(w)
+
+
+@pytest.mark.parametrize("B,N", [(8, 6144), (1, 6144), (16, 6144), (11, 4096), (3, 1000), (16, 16)])
+def test_gemv_with_the_step_boundary_in_its_prologue(H, ctx, chain_4096, B, N):
+    """vte_desc_gemv_rmsnorm_gather: tokens -> embedding rows -> RMSNorm -> GEMV in one launch.  Against the
+    oracle; against the two launches it replaces (gather+norm, then the GEMV with the same plan): every
+    bit of the gathered rows, the normalised rows and the output; and on every pCtx."""
+    shp, w, wd = chain_4096
+    K, V = shp.D, shp.V
+    tok = inputs.tokens(21 + B, inputs.T_TOK0, B, V)
+    tok[0] = V - 1                                                # the last row of the table
+    W = np.ascontiguousarray(w["Wqkv"][:N])
+    dW, dtok = H.to_dev(W), torch.from_numpy(tok.astype(np.int32)).cuda()
+    Y, h, n = H.dev_empty((B, N)), H.dev_empty((B, K)), H.dev_empty((B, K))
+    fused = vte.vte_desc_gemv_rmsnorm_gather(ctx, dW, wd["E"], dtok, wd["gamma"], Y, h, n, B, V, N, K, 1e-6)
+    info = vte.vte_desc_info(fused)
+    assert info.kernel == vte.VTE_K_GEMV_NORM and list(info.block) == [256, 1, 1]
+    res = run_everywhere(H, ctx, fused, Y)
+    y_f = assert_all_equal(res).view(np.uint16)
+    h_f, n_f = H.to_bits(h), H.to_bits(n)
+    # the two launches it replaces
+    Y2, h2, n2 = H.dev_empty((B, N)), H.dev_empty((B, K)), H.dev_empty((B, K))
+    d1 = vte.vte_desc_rmsnorm_gather(ctx, wd["E"], dtok, wd["gamma"], n2, h2, B, V, K, 1e-6)
+    pl = vte.vte_gemv_plan()
+    pl.kind, pl.batch_tile, pl.ksteps, pl.prefetch, pl.max_waves, pl.groups = vte.VTE_GEMV_MFMA, 16, 8, 2, 4, 1
+    pl.rows = 32 if (N + 15) // 16 > 256 else 16
+    d2 = vte.vte_desc_gemv_planned(ctx, dW, n2, Y2, B, N, K, vte.VTE_EPI_NONE, pl)
+    p = H.pctx_of_width(ctx, 128)
+    H.run_on(ctx, d1, p)
+    H.run_on(ctx, d2, p)
+    assert np.array_equal(h_f, H.to_bits(h2)) and np.array_equal(h_f, w["E"][tok])
+    assert np.array_equal(n_f, H.to_bits(n2))
+    assert np.array_equal(y_f, H.to_bits(Y2))
+    # the oracle, each operator on the GPU's own input
+    bf16_close(n_f, oracle.rmsnorm(w["E"][tok], w["gamma"], 1e-6), "fused norm, batch %d" % B)
+    bf16_close(y_f, oracle.gemv(W, n_f), "fused gemv, batch %d, N %d" % (B, N))
+    for d in (fused, d1, d2):
+        vte.vte_desc_destroy(d)
+
+
+@pytest.mark.parametrize("B", [1, 4, 8, 16])
+def test_chain_with_the_boundary_in_the_qkv_launch_teacher_forced(H, ctx, chain_4096, B):
+    """The five-launch step against the oracle, operator by operator on the GPU's own inputs, six
+    teacher-forced steps; the first step takes its tokens from the buffer, the later ones finish them
+    from the LM head's candidates (the token buffer is overwritten with the oracle's to check that)."""
+    shp, w, wd = chain_4096
+    ch = H.DecodeChain(ctx, wd, shp, B, want_logits=True, feedback=True, fused_gather=True, fused_argmax=True, fused_qkv=True)
+    vs = vte.vte_vstream_create(ctx, vte.VTE_CLASS_LATENCY)
+    tok = inputs.tokens(23, inputs.T_TOK0, B, shp.V)
+    ch.set_tokens(tok)
+    near = 0
+    for step in range(6):
+        for k in (ch.order_first if step == 0 else ch.order_next):
+            last = vte.vte_submit(vs, ch.desc[k])
+        vte.vte_token_wait(ctx, last)
+        s = ch.snapshot()
+        if step > 0:                                       # the tokens the launch finished from the candidates
+            assert np.array_equal(ch.tok.cpu().numpy(), prev_next)
+            tok = prev_next
+        o = oracle.decode_step(w, tok, shp, want_logits=True)
+        assert np.array_equal(s["h0"], o["h0"])
+        bf16_close(s["n"], oracle.rmsnorm(s["h0"], w["gamma"]), "n")
+        bf16_close(s["qkv"], oracle.gemv(w["Wqkv"], s["n"]), "qkv")
+        bf16_close(s["o"], oracle.gemv(w["Wo"], np.ascontiguousarray(s["qkv"][:, :shp.D])), "o")
+        bf16_close(s["act"], oracle.gemv_silu_mul(w["Wgu"], s["o"]), "act")
+        bf16_close(s["d"], oracle.gemv(w["Wd"], s["act"]), "d")
+        lg, t_ref, margin = oracle.lmhead_argmax(w["Wlm"], s["d"])
+        eps_logit = np.abs(s["logits"].astype(np.float64) - lg).max()
+        assert eps_logit < 1e-3
+        # what the next launch must find: the greedy token of these logits (ties to the lowest index)
+        prev_next = np.array([int(np.flatnonzero(r == r.max())[0]) for r in s["logits"]], dtype=np.int32)
+        for b in range(B):
+            if prev_next[b] != t_ref[b]:
+                assert margin[b] <= 2 * eps_logit
+                near += 1
+    assert near <= 1
+    vte.vte_vstream_destroy(vs)
+    ch.close()
+
+
+@pytest.mark.parametrize("B", [5, 8, 16])
+def test_chain_with_the_boundary_in_the_qkv_launch_equals_the_six_launch_chain(H, ctx, chain_4096, B):
+    """Five launches per step (token finish, gather and RMSNorm in the QKV launch's prologue) leave the same
+    tokens, activations and logits as the chain whose boundary is a launch of its own, step after step
+    (from batch 5 the stand-alone QKV launch runs the same matrix-core plan; below that it is the
+    dot-product kind, another tree)."""
+    shp, w, wd = chain_4096
+    tok = inputs.tokens(17, inputs.T_TOK0, B, shp.V)
+    steps = 6
+    snaps, toks = [], []
+    for fused in (False, True):
+        ch = H.DecodeChain(ctx, wd, shp, B, want_logits=True, feedback=True, fused_gather=True, fused_argmax=True, fused_qkv=fused)
+        if fused:
+            assert ch.order_next == ["qkv_next", "o", "gateup", "down", "lmhead"] and ch.order_first[0] == "qkv_first"
+        ch.set_tokens(tok)
+        vs = vte.vte_vstream_create(ctx, vte.VTE_CLASS_LATENCY)
+        vte.vte_vstream_pin(vs, H.pctx_of_width(ctx, 64 if fused else 256))
+        ch.submit_burst(vs, steps)
+        vte.vte_vstream_sync(vs)
+        snaps.append(ch.snapshot())
+        toks.append(ch.tok.cpu().numpy().copy())
+        vte.vte_vstream_destroy(vs)
+        ch.close()
+    assert np.array_equal(toks[0], toks[1])
+    for k in ("h0", "n", "qkv", "o", "act", "d"):
+        assert np.array_equal(snaps[0][k], snaps[1][k]), k
+    assert np.array_equal(snaps[0]["logits"].view(np.uint32), snaps[1]["logits"].view(np.uint32))
+    assert not np.array_equal(toks[0], tok)
+
+
+def test_fused_qkv_launch_rejects_what_it_is_not_built_for(H, ctx, chain_4096, small_chain):
+    shp, w, wd = chain_4096
+    Y = H.dev_empty((17, 64))
+    tok = torch.zeros(17, dtype=torch.int32, device="cuda")
+    with pytest.raises(vte.VteError):                             # batch above 16
+        vte.vte_desc_gemv_rmsnorm_gather(ctx, wd["Wqkv"], wd["E"], tok, wd["gamma"], Y, None, None, 17, shp.V, 64, shp.D, 1e-6)
+    with pytest.raises(vte.VteError):                             # fewer than one tile of outputs
+        vte.vte_desc_gemv_rmsnorm_gather(ctx, wd["Wqkv"], wd["E"], tok, wd["gamma"], Y, None, None, 8, shp.V, 8, shp.D, 1e-6)
+    s_shp, s_w, s_wd = small_chain
+    with pytest.raises(vte.VteError):                             # another hidden size
+        vte.vte_desc_gemv_rmsnorm_gather(ctx, s_wd["Wqkv"], s_wd["E"], tok, s_wd["gamma"], Y, None, None, 8, s_shp.V, 64, s_shp.D, 1e-6)
+    ch = H.DecodeChain(ctx, wd, shp, 2, fused_gather=True)
+    with pytest.raises(vte.VteError):                             # candidates must come from an LM-head descriptor
+        vte.vte_desc_gemv_rmsnorm_gather_argmax(ctx, wd["Wqkv"], wd["E"], ch.desc["qkv"], None, wd["gamma"], ch.qkv, None, None,
+                                                shp.V, shp.Nqkv, shp.D, 1e-6)
+    ch.close()
+
+
 def test_chain_bits_do_not_depend_on_allocation(H, ctx, small_chain):
     shp, w, wd = small_chain
     B = 8
