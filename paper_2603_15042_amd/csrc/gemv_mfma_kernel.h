@@ -45,10 +45,10 @@
 // order, fixed 64-lane butterfly, four wave sums added in wave order -- which is why the rows are
 // fetched a second time in that layout) and scales its own K range of every row with the same
 // expression, rounding to bf16 once: the B operand is then, bit for bit, what the RMSNorm launch
-// would have stored, and the GEMV proceeds as usual.  The weights are requested before anything
-// else, so the prologue's latencies (candidates, tokens, rows: three dependent fetches) run beside
-// the weight stream's first-byte latency.  Workgroup 0 stores the tokens and, if asked, the gathered
-// and the normalised rows.
+// would have stored, and the GEMV proceeds as usual.  The first weights are requested right behind
+// the prologue's first loads and nothing in the prologue waits for them, so its latencies (candidates,
+// then rows: two dependent fetches) run beside the weight stream's first-byte latency.  Workgroup 0
+// stores the tokens and, if asked, the gathered and the normalised rows.
 #pragma once
 #include "gemv_kernels.h"
 #include "trace_stamps.h"

@@ -424,6 +424,35 @@ def test_plans_that_do_not_fit_are_rejected(ctx):
         vte.vte_desc_gemv_split(ctx, A, A, 0, A, 64, 4096, 4096, 0, 3)   # S must divide K
 
 
+def test_the_qkv_launch_with_the_step_boundary_in_its_prologue_has_a_shape_derived_geometry(ctx):
+    """vte_desc_gemv_rmsnorm_gather{,_argmax}: 256 threads, 16 or 32 rows per workgroup from N alone; built for
+    K = 4096 and batch <= 16; the candidates come from an LM-head descriptor of the same context."""
+    d = vte.vte_desc_gemv_rmsnorm_gather(ctx, A, A, A, A, A, None, None, 8, 128256, 6144, 4096, 1e-6)
+    v = vte.vte_desc_info(d)
+    assert v.kernel == vte.VTE_K_GEMV_NORM and list(v.grid) == [192, 1, 1] and list(v.block) == [256, 1, 1]
+    d2 = vte.vte_desc_gemv_rmsnorm_gather(ctx, A, A, A, A, A, A, A, 16, 1000, 4096, 4096, 1e-6)
+    assert list(vte.vte_desc_info(d2).grid) == [256, 1, 1]
+    assert vte.vte_desc_info(d2).profile_key != v.profile_key
+    lm = vte.vte_desc_lmhead_argmax(ctx, A, A, A, None, A, 8, 128256, 4096)
+    d3 = vte.vte_desc_gemv_rmsnorm_gather_argmax(ctx, A, A, lm, A, A, A, None, None, 128256, 6144, 4096, 1e-6)
+    assert list(vte.vte_desc_info(d3).grid) == [192, 1, 1] and vte.vte_desc_info(d3).bytes > v.bytes   # the candidates are read too
+    plain = vte.vte_desc_gemv(ctx, A, A, A, 8, 6144, 4096, 0)
+    for call in (
+        lambda: vte.vte_desc_gemv_rmsnorm_gather(ctx, A, A, A, A, A, None, None, 17, 1000, 6144, 4096, 1e-6),    # batch
+        lambda: vte.vte_desc_gemv_rmsnorm_gather(ctx, A, A, A, A, A, None, None, 8, 1000, 6144, 2048, 1e-6),     # hidden size
+        lambda: vte.vte_desc_gemv_rmsnorm_gather(ctx, A, A, A, A, A, None, None, 8, 1000, 8, 4096, 1e-6),        # less than a tile
+        lambda: vte.vte_desc_gemv_rmsnorm_gather(ctx, A, A, A, A, A, None, None, 8, 1 << 18, 6144, 4096, 1e-6),  # table of 2 GiB
+        lambda: vte.vte_desc_gemv_rmsnorm_gather(ctx, A, A, None, A, A, None, None, 8, 1000, 6144, 4096, 1e-6),  # no tokens
+        lambda: vte.vte_desc_gemv_rmsnorm_gather(ctx, A, A + 2, A, A, A, None, None, 8, 1000, 6144, 4096, 1e-6), # alignment
+        lambda: vte.vte_desc_gemv_rmsnorm_gather_argmax(ctx, A, A, plain, A, A, A, None, None, 1000, 6144, 4096, 1e-6),
+    ):
+        with pytest.raises(vte.VteError) as e:
+            call()
+        assert e.value.code == vte.VTE_EINVAL
+    for x in (d, d2, d3, lm, plain):
+        vte.vte_desc_destroy(x)
+
+
 def test_bad_shapes_are_rejected(ctx):
     for call in (
         lambda: vte.vte_desc_rmsnorm(ctx, A, A, A, 8, 1020, 1e-6),          # cols % 8
