@@ -237,11 +237,13 @@ int plan_gemv(int B, int outputs, int kps, int epi, vte_gemv_plan* p) {
     p->kind = VTE_GEMV_MFMA;
     return VTE_OK;
   }
-  if (outputs >= tile_out && (B >= 5 || (B >= 3 && silu && tiles >= 1024))) {
-    // Batch 5 and up (and the wide SiLU projection from batch 3): matrix-core tiles; the
-    // dot-product kernels are ALU-bound there.  Found by timing every built combination
-    // on the Llama-8B shapes.  Large outputs walk several rounds so that X is fetched once
-    // per many rows.
+  if (outputs >= tile_out && B >= 3) {
+    // Batch 3 and up: matrix-core tiles.  From batch 8 the dot-product kernels are ALU-bound; at
+    // batch 3 and 4 their four-row batch tile already loses to the matrix cores on every Llama-8B
+    // shape and width (O 9.6 -> 8.8 us, QKV 13.4 -> 11.4, LM head 153 -> 151 us at 256 CUs, 231 -> 190 at
+    // 128); at batch 1 and 2 the two-row dot-product tile is as fast at full width and faster on a
+    // narrow pCtx for the small projections, and stays.  Found by timing every built combination on
+    // the Llama-8B shapes.  Large outputs walk several rounds so that X is fetched once per many rows.
     int g = 1, nb = 2, mw = 8, rounds = 1, nbk = 4;
     if (tiles >= 4096 && kps <= 4096) {
       // the LM head: 1024-element chunks, so that four waves hold all of X (fetched once per

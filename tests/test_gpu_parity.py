@@ -708,20 +708,22 @@ def test_dot_product_kernels_equal_their_emulated_tree_bit_for_bit(H, ctx, B, N,
         W = _spread(W, 33, binades)
     X = inputs.normal_bf16(33, inputs.T_XB, (B, K))
     plan = vte.vte_gemv_default_plan(B, N, K, 0, 1)
+    if B > 2:                         # from batch 3 the default is the matrix-core kind: ask for the four-row dot-product tile
+        plan = vte.vte_gemv_plan(4, 8, 2, 1, 8, 1, vte.VTE_GEMV_DOT2)
     assert plan.kind == vte.VTE_GEMV_DOT2
     want = tree_emulator.gemv_dot2_sums(W, X, plan.ksteps)
     dW, dX = H.to_dev(W), H.to_dev(X)
     tok = torch.zeros(B, dtype=torch.int32, device="cuda")
     lg = torch.zeros((B, N), dtype=torch.float32, device="cuda")
     ws = H.dev_zeros_bytes(vte.vte_lmhead_workspace_bytes(B, N, K))
-    d = vte.vte_desc_lmhead_argmax(ctx, dW, dX, tok, lg, ws, B, N, K)
+    d = vte.vte_desc_lmhead_argmax_planned(ctx, dW, dX, tok, lg, ws, B, N, K, plan)
     for w in (32, 128, 256):
         lg.fill_(-1.0)
         H.run_on(ctx, d, H.pctx_of_width(ctx, w))
         assert np.array_equal(lg.cpu().numpy().view(np.uint32), want.view(np.uint32)), w
     vte.vte_desc_destroy(d)
     dY = H.dev_empty((B, N))
-    d = vte.vte_desc_gemv(ctx, dW, dX, dY, B, N, K)
+    d = vte.vte_desc_gemv_planned(ctx, dW, dX, dY, B, N, K, vte.VTE_EPI_NONE, plan)
     H.run_on(ctx, d, H.pctx_of_width(ctx, 64))
     assert np.array_equal(H.to_bits(dY), tree_emulator._f32_to_bf16(want))
     vte.vte_desc_destroy(d)
@@ -836,9 +838,9 @@ def test_gemv_mfma_plans(H, ctx, G, NB, MW, rounds, B, N, K):
     vte.vte_desc_destroy(fin)
 
 
-def test_gemv_mfma_plan_is_the_default_from_batch_5_and_rejects_what_is_not_built(H, ctx):
-    assert vte.vte_gemv_default_plan(4, 4096, 4096).kind == vte.VTE_GEMV_DOT2
-    p = vte.vte_gemv_default_plan(5, 4096, 4096)
+def test_gemv_mfma_plan_is_the_default_from_batch_3_and_rejects_what_is_not_built(H, ctx):
+    assert vte.vte_gemv_default_plan(2, 4096, 4096).kind == vte.VTE_GEMV_DOT2
+    p = vte.vte_gemv_default_plan(3, 4096, 4096)
     assert p.kind == vte.VTE_GEMV_MFMA and p.batch_tile == 16 and p.rows % 16 == 0
     assert vte.vte_gemv_default_plan(8, 8, 4096).kind == vte.VTE_GEMV_DOT2        # less than one tile of outputs
     W, X, Y = H.dev_empty((64, 512)), H.dev_empty((8, 512)), H.dev_empty((8, 64))
@@ -1418,11 +1420,11 @@ def test_chain_with_the_boundary_in_the_qkv_launch_teacher_forced(H, ctx, chain_
     ch.close()
 
 
-@pytest.mark.parametrize("B", [5, 8, 16])
+@pytest.mark.parametrize("B", [3, 4, 8, 16])
 def test_chain_with_the_boundary_in_the_qkv_launch_equals_the_six_launch_chain(H, ctx, chain_4096, B):
     """Five launches per step (token finish, gather and RMSNorm in the QKV launch's prologue) leave the same
     tokens, activations and logits as the chain whose boundary is a launch of its own, step after step
-    (from batch 5 the stand-alone QKV launch runs the same matrix-core plan; below that it is the
+    (from batch 3 the stand-alone QKV launch runs the same matrix-core plan; below that it is the
     dot-product kind, another tree)."""
     shp, w, wd = chain_4096
     tok = inputs.tokens(17, inputs.T_TOK0, B, shp.V)
