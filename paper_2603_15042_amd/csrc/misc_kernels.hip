@@ -59,11 +59,18 @@ __global__ __launch_bounds__(1024) void argmax_finish_kernel(const ArgmaxFinishA
 // the byte count alone.
 __global__ __launch_bounds__(256) void copy_kernel(const CopyArgs a) {
   const size_t base = (static_cast<size_t>(blockIdx.x) * 4 * 256 + threadIdx.x) * 16;
+  // all four loads before the first store (dst and src may not overlap, but the compiler cannot know:
+  // written one by one, every load waits for the store before it)
+  u32x4 v[4];
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     const size_t off = base + static_cast<size_t>(j) * 256 * 16;
-    if (off < a.bytes)
-      *reinterpret_cast<u32x4*>(a.dst + off) = *reinterpret_cast<const u32x4*>(a.src + off);
+    v[j] = off < a.bytes ? __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(a.src + off)) : u32x4{0u, 0u, 0u, 0u};
+  }
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const size_t off = base + static_cast<size_t>(j) * 256 * 16;
+    if (off < a.bytes) __builtin_nontemporal_store(v[j], reinterpret_cast<u32x4*>(a.dst + off));
   }
 }
 
