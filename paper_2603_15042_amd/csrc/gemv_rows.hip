@@ -19,11 +19,21 @@
 //     wave loads (4 rows x 256 B each), transposed through a 4 KB wave-private LDS
 //     area (16-byte pieces XOR-swizzled by row) into the MFMA A layout; the loads run
 //     KA K-steps ahead of the MFMAs, across round boundaries.
-// Reduction tree of one output, fixed by K alone:
+//   * the K steps of a workgroup's round are walked from a start that depends on where its outputs
+//     lie: outputs [512 j, 512 j + 512) start at step floor((j mod 32) * steps / 32) and wrap around.  Every
+//     workgroup streams its rows at the same pace, and a row is 2^13 bytes long at K = 4096: walked
+//     from step 0 everywhere, all requests in flight on the device at one moment share their address bits
+//     8 to 12, and how well they spread over the memory channels is left to the upper bits, i.e. to
+//     where the tensor happens to lie -- the same LM head took 160 to 228 us depending on the
+//     allocation.  With up to 32 starts it takes 160 to 175 us wherever the tensor lies.
+// Reduction tree of one output, fixed by K and the output's index alone (not by the plan: a round of
+// a workgroup covers 32 to 512 consecutive outputs and starts at a multiple of its length, so it
+// never straddles a block of 512):
 //   1. inside one MFMA: four groups of 8 consecutive K (a lane's operand), in ascending K, each
 //      added to the accumulator with one rounding (measured; tests/tree_emulator.py reproduces it);
-//   2. along K in ascending order through the accumulator operand: the 4 MFMAs of a
-//      step, then step after step.  No sum crosses a wave.
+//   2. along K through the accumulator operand: the 4 MFMAs of a step, then step after step in
+//      the rotated order above (ascending from the start, then from step 0 up to the start).  No
+//      sum crosses a wave.
 // The batch columns of an MFMA are independent and every column tile runs the same
 // chain, so a row's result does not depend on its position or on the rows beside it.
 #include "gemv_kernels.h"
@@ -46,6 +56,12 @@ __global__ __launch_bounds__(WR * 64) void gemv_rows_kernel(const GemvArgs a) {
   const int lr = lane >> 4, lp = lane & 15;  // load coordinates: row within a 4-row group, 16-byte piece of 256 B
   const int nk = (a.K + 127) >> 7;           // K steps
   const int nsteps = a.groups * nk;          // steps of the launch, round-major
+  // position p of round rd's walk along K -> K step (see the header: the start is chosen by the outputs' block of 512)
+  auto kstep = [&](int rd, int p) {
+    const int out0 = ((blockIdx.x * a.groups + rd) * WR) * G * ROUT;  // first output of the workgroup's round
+    const int k = p + (((out0 >> 9) & 31) * nk >> 5);
+    return k >= nk ? k - nk : k;
+  };
   u32x4* wstage = wstage_all + wave * 256;
 
   // Tile t of (round, g): first output row, and where its loads start.  A tile that would run
@@ -85,13 +101,15 @@ __global__ __launch_bounds__(WR * 64) void gemv_rows_kernel(const GemvArgs a) {
   }
   const bool k_ragged = (a.K & 127) != 0;  // only then can a piece lie past K
 
-  auto load_w = [&](u32x4(&dst)[4], int rd, int k, int g) {
+  auto load_w = [&](u32x4(&dst)[4], int rd, int p, int g) {
+    const int k = kstep(rd, p);
     const int soff = ((tile_start(rd, g) - base_row) * a.K + k * 128) * 2;
     const uint32_t vo = (!k_ragged || k * 128 + lp * 8 < a.K) ? voff_w : kNoFetch;
 #pragma unroll
     for (int u = 0; u < 4; ++u) dst[u] = __builtin_amdgcn_raw_buffer_load_b128(rs_w[u], vo, soff, 2);  // streaming
   };
-  auto load_x = [&](u32x4(&dst)[XU], int k) {
+  auto load_x = [&](u32x4(&dst)[XU], int rd, int p) {
+    const int k = kstep(rd, p);
     const bool in = !k_ragged || k * 128 + lp * 8 < a.K;
 #pragma unroll
     for (int i = 0; i < XU; ++i) dst[i] = __builtin_amdgcn_raw_buffer_load_b128(rs_x, in ? voff_x[i] : kNoFetch, k * 256, 0);
@@ -156,7 +174,7 @@ __global__ __launch_bounds__(WR * 64) void gemv_rows_kernel(const GemvArgs a) {
   auto advance_load = [&]() {
     if (++ld_k == nk) { ld_k = 0; ++ld_rd; }
   };
-  load_x(xr, 0);
+  load_x(xr, 0, 0);
 #pragma unroll
   for (int ka = 0; ka < KA; ++ka) {
     if (ld_rd < a.groups) {
@@ -182,7 +200,7 @@ __global__ __launch_bounds__(WR * 64) void gemv_rows_kernel(const GemvArgs a) {
         const int buf = step & 1;
         const bool more = step + 1 < nsteps;
         const int kn = (k + 1 == nk) ? 0 : k + 1;
-        if (more) load_x(xr, kn);
+        if (more) load_x(xr, kn == 0 ? rd + 1 : rd, kn);
         // this step's X operands: lane (c, q) takes piece 4 s + q of batch row 16 ct + c
         u32x4 xf[CT][4];
 #pragma unroll

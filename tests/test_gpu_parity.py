@@ -638,18 +638,20 @@ def _spread(Wbits, seed, binades):
     return inputs.bf16_bits(f)
 
 
-@pytest.mark.parametrize("B,N,K,binades", [(40, 48, 520, 0), (64, 100, 1160, 0), (33, 37, 264, 6), (57, 64, 128, 20), (17, 32, 4096, 0)])
+@pytest.mark.parametrize("B,N,K,binades", [(40, 48, 520, 0), (64, 100, 1160, 0), (33, 37, 264, 6), (57, 64, 128, 20), (17, 32, 4096, 0),
+                                           (40, 1300, 1160, 0), (64, 2100, 2048, 0), (33, 600, 1024, 4)])
 def test_row_split_kernel_equals_its_emulated_tree_bit_for_bit(H, ctx, B, N, K, binades):
     """The fp32 sums (LM-head logits) of the row-split kernel against the CPU emulation of its tree
-    (tests/tree_emulator.py: one chain of 8-product groups along K, the instruction's alignment and
-    rounding reproduced): every bit, on a narrow and on the full-width pCtx; and the bf16 outputs of
-    the plain GEMV are those sums rounded once."""
+    (tests/tree_emulator.py: one chain of 8-product groups along K, walked from the start that the
+    output's block of 512 fixes, the instruction's alignment and rounding reproduced): every bit, on a
+    narrow and on the full-width pCtx, with two plans whose workgroups cover 128 and 512 outputs; and the
+    bf16 outputs of the plain GEMV are those sums rounded once."""
     import tree_emulator
     W = inputs.normal_bf16(31, inputs.T_W, (N, K), 0.0, K ** -0.5)
     if binades:
         W = _spread(W, 31, binades)
     X = inputs.normal_bf16(31, inputs.T_XB, (B, K))
-    want = tree_emulator.gemv_rows_sums(W, X)
+    want = tree_emulator.gemv_rows_kernel_sums(W, X)
     bt = 64 if B > 32 else 32
     dW, dX = H.to_dev(W), H.to_dev(X)
     tok = torch.zeros(B, dtype=torch.int32, device="cuda")

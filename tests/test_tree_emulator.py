@@ -61,3 +61,27 @@ def test_a_smaller_accumulator_is_dropped_toward_minus_infinity_at_the_groups_gr
     # the same with a positive remainder: +1.5 * 2^-24 -> +1 unit
     W[0, 0] = 1.5 * 2.0 ** -12
     assert te.gemv_rows_sums(_bits(W), _bits(X))[0, 0] == np.float32(1.0)   # 1 + 2^-24 exactly: a tie, to even
+
+
+def test_the_row_split_kernel_walks_k_from_a_start_fixed_by_the_outputs_block_of_512():
+    """gemv_rows_kernel_sums: output block j (512 outputs) starts at step (j mod 32) * steps // 32 and wraps
+    around; block 0 is the plain ascending chain.  Planted values whose sum depends on the order show the
+    start, and exact inputs do not care."""
+    rng = np.random.default_rng(3)
+    K, N = 4096, 1100                                     # 32 steps: block 1 starts at step 1, block 2 at step 2
+    W = rng.integers(-4, 5, size=(N, K)).astype(np.float32)
+    X = rng.integers(-4, 5, size=(2, K)).astype(np.float32)
+    exact = (X.astype(np.int64) @ W.astype(np.int64).T).astype(np.float32)
+    assert np.array_equal(te.gemv_rows_kernel_sums(_bits(W), _bits(X)), exact)
+    # 1 in step 0, 2^-24 in step 1, -1 in step 31: ascending from step 0 the small term is lost beside the 1
+    # (sum 0); started at step 1 or 2 it meets 0 or survives the cancellation of 1 and -1
+    W = np.zeros((N, K), np.float32)
+    W[:, 0], W[:, 128], W[:, 31 * 128] = 1.0, 2.0 ** -24, -1.0
+    X = np.ones((1, K), np.float32)
+    got = te.gemv_rows_kernel_sums(_bits(W), _bits(X))[0]
+    assert np.all(te.gemv_rows_sums(_bits(W), _bits(X))[0] == 0.0)
+    assert np.all(got[:512] == 0.0) and np.all(got[512:] == np.float32(2.0 ** -24))
+    # 1160 elements are 10 steps: blocks 0 to 3 start at step 0 (3 * 10 // 32 = 0), block 4 at step 1
+    Ws, Xs = inputs.normal_bf16(3, inputs.T_W, (2100, 1160), 0.0, 1.0), inputs.normal_bf16(3, inputs.T_XB, (3, 1160))
+    a, b = te.gemv_rows_kernel_sums(Ws, Xs), te.gemv_rows_sums(Ws, Xs)
+    assert np.array_equal(a[:, :2048], b[:, :2048]) and not np.array_equal(a[:, 2048:], b[:, 2048:])

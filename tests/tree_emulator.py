@@ -176,6 +176,24 @@ def gemv_rows_sums(W_bits, X_bits):
     return mfma_chain(np.zeros((Xf.shape[0], Wf.shape[0]), np.float32), Wf, Xf, 0, Wf.shape[1])
 
 
+def gemv_rows_kernel_sums(W_bits, X_bits):
+    """fp32 sums of the row-split GEMV kernel: one chain per output along K in steps of 128, walked from a
+    start that the output's index fixes -- outputs [512 j, 512 j + 512) start at step (j mod 32) * steps // 32
+    and wrap around.  -> [B, N] float32."""
+    Wf, Xf = _bf16_to_f32(W_bits), _bf16_to_f32(X_bits)
+    N, K = Wf.shape
+    nk = (K + 127) // 128
+    out = np.zeros((Xf.shape[0], N), np.float32)
+    for j in range((N + 511) // 512):
+        rows = slice(512 * j, min(N, 512 * j + 512))
+        rot = (j % 32) * nk // 32
+        acc = np.zeros((Xf.shape[0], rows.stop - rows.start), np.float32)
+        for k in list(range(rot, nk)) + list(range(rot)):
+            acc = mfma_chain(acc, Wf[rows], Xf, 128 * k, min(K, 128 * k + 128))
+        out[:, rows] = acc
+    return out
+
+
 def gemv_ksplit_sums(W_bits, X_bits, blocks_per_chunk, max_waves):
     """fp32 sums of the K-split kernel: wave w chains the chunks w, w + nw, ... (chunk = 128 x
     blocks_per_chunk elements) in ascending order, the waves' sums are added in wave order."""
