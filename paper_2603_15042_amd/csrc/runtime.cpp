@@ -235,8 +235,11 @@ void complete_op(vte_ctx* c, Op* op, int rc = VTE_OK) {
 bool poll_completions(vte_ctx* c) {
   if (c->inflight.empty()) return false;
   const int np = c->pool.size();
-  std::vector<int> frontier(np, -1), first_bad(np, -1);
-  std::vector<char> blocked(np, 0);
+  std::vector<int>&frontier = c->scratch.frontier, &first_bad = c->scratch.first_bad;
+  std::vector<char>& blocked = c->scratch.blocked;
+  frontier.assign(np, -1);
+  first_bad.assign(np, -1);
+  blocked.assign(np, 0);
   std::string bad_msg;
   int bad_hip = 0;
   for (size_t i = 0; i < c->inflight.size(); ++i) {
@@ -260,17 +263,20 @@ bool poll_completions(vte_ctx* c) {
     }
   }
   bool any = false;
-  std::vector<Op*> keep;
-  keep.reserve(c->inflight.size());
-  std::vector<Op*> done;
+  bool none_done = true;
+  for (int p = 0; p < np; ++p) none_done = none_done && frontier[p] < 0;
+  if (none_done) return false;  // the common answer while a launch is running
+  std::vector<Op*>&keep = c->scratch.keep, &done = c->scratch.done;
+  keep.clear();
+  done.clear();
   for (size_t i = 0; i < c->inflight.size(); ++i) {
     Op* op = c->inflight[i];
     if (static_cast<int>(i) <= frontier[op->pctx]) done.push_back(op);
     else keep.push_back(op);
   }
   if (!done.empty()) {
-    std::vector<int> rcs;
-    rcs.reserve(done.size());
+    std::vector<int>& rcs = c->scratch.rcs;
+    rcs.clear();
     for (size_t i = 0; i < c->inflight.size(); ++i) {
       const Op* op = c->inflight[i];
       if (static_cast<int>(i) > frontier[op->pctx]) continue;
@@ -592,8 +598,10 @@ void submission_failed(vte_ctx* c, Op* op, int rc) {
 // validate, submit.  Returns true if something was bound.
 bool dispatch_round(vte_ctx* c) {
   if (purge_failed_dependants(c)) return true;
-  std::vector<vte_ready_op> ready;
-  std::vector<Op*> ready_ops;
+  std::vector<vte_ready_op>& ready = c->scratch.ready;
+  std::vector<Op*>& ready_ops = c->scratch.ready_ops;
+  ready.clear();
+  ready_ops.clear();
   for (vte_vstream* vs : c->vstreams) {
     if (!vs || vs->queue.empty()) continue;
     Op* op = vs->queue.front();
@@ -611,7 +619,8 @@ bool dispatch_round(vte_ctx* c) {
   if (ready.empty()) return false;
   if (!c->custom_policy && c->builtin >= VTE_POLICY_TPUT_PLAN) return planned_round(c, ready, ready_ops);
 
-  std::vector<vte_pctx_info> infos(c->pool.size());
+  std::vector<vte_pctx_info>& infos = c->scratch.infos;
+  infos.resize(c->pool.size());
   for (int i = 0; i < c->pool.size(); ++i) fill_info(c->pool, i, &infos[i]);
   vte_pool_view S;
   S.count = c->pool.size();
@@ -623,10 +632,13 @@ bool dispatch_round(vte_ctx* c) {
 
   bool bound_any = false;
   // each ready op gets at most one proposal per round
-  std::vector<char> tried(ready.size(), 0);
+  std::vector<char>& tried = c->scratch.tried;
+  tried.assign(ready.size(), 0);
+  std::vector<vte_ready_op>& q = c->scratch.q;
+  std::vector<int>& qi = c->scratch.qi;
   for (size_t round = 0; round < ready.size(); ++round) {
-    std::vector<vte_ready_op> q;
-    std::vector<int> qi;
+    q.clear();
+    qi.clear();
     for (size_t i = 0; i < ready.size(); ++i)
       if (!tried[i]) { q.push_back(ready[i]); qi.push_back(static_cast<int>(i)); }
     if (q.empty()) break;
@@ -638,7 +650,8 @@ bool dispatch_round(vte_ctx* c) {
     tried[ri] = 1;
     Op* op = ready_ops[ri];
     const vte_ready_op& ro = ready[ri];
-    std::vector<int> eligible;
+    std::vector<int>& eligible = c->scratch.eligible;
+    eligible.clear();
     eligible_set(c, op, ro.pinned_pctx, &eligible);
     if (eligible.empty()) continue;
     int sel = c->custom_policy && c->policy.select

@@ -146,6 +146,15 @@ struct vte_ctx {
   uint64_t next_age = 0;
   std::unordered_map<vte_token, vte::Op*> live;  // not yet done
   std::vector<vte::Op*> inflight;                // in bind order
+  // Working storage of the dispatcher thread (poll_completions, dispatch_round): kept between rounds so
+  // that the dispatch path makes no heap allocation of its own per launch.  Dispatcher thread only, lock held.
+  struct Scratch {
+    std::vector<int> frontier, first_bad, rcs, qi, eligible;
+    std::vector<char> blocked, tried;
+    std::vector<vte::Op*> keep, done, ready_ops;
+    std::vector<vte_ready_op> ready, q;
+    std::vector<vte_pctx_info> infos;
+  } scratch;
   unsigned timing_seen[32] = {};                 // launches of each kernel id that device_timing_mask selected so far
   std::vector<vte::Op*> lazy_tail;               // per pCtx: newest in-flight op without a completion record
   std::vector<vte_vstream*> vstreams;
