@@ -42,6 +42,25 @@ def _log(msg):
     print("[bench] " + msg, file=sys.stderr, flush=True)
 
 
+class _section:
+    """One of the measurements behind the headline: announced on stderr; if it raises, the error goes into
+    out["errors"] and the run goes on, so that the JSON line with the metric is printed whatever happens
+    to the extras."""
+
+    def __init__(self, out, name):
+        self.out, self.name = out, name
+
+    def __enter__(self):
+        _log(self.name)
+
+    def __exit__(self, et, ev, tb):
+        if et is None or not issubclass(et, Exception):
+            return False
+        self.out.setdefault("errors", {})[self.name] = "%s: %s" % (et.__name__, ev)
+        _log("FAILED %s: %s: %s" % (self.name, et.__name__, ev))
+        return True
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -169,120 +188,120 @@ def main():
 
     # ---- per CU width: throughput and bit mismatches (outside the timed region) -------------
     if not a.no_width_sweep:
-        _log("chain per width")
-        per_width, mism = {}, 0
-        ref_snap = None
-        for width in WIDTHS:
-            p = H.pctx_of_width(ctx, width)
-            v = vte.vte_vstream_create(ctx, vte.VTE_CLASS_LATENCY)
-            vte.vte_vstream_pin(v, p)
-            ch.set_tokens(tok0)
-            n = max(16, a.steps // 8)
-            run(ch, 4, v)
-            ch.set_tokens(tok0)
-            t = time.perf_counter()
-            run(ch, n, v)
-            e = time.perf_counter() - t
-            snap = ch.snapshot()
-            snap["tok"] = ch.tok.cpu().numpy().copy()
-            if ref_snap is None:
-                ref_snap = snap
-            else:
-                for k in ("n", "qkv", "o", "act", "d"):
-                    mism += H.mismatched_bits(ref_snap[k], snap[k])[1]
-                mism += H.mismatched_bits(ref_snap["tok"].astype(np.uint32), snap["tok"].astype(np.uint32))[1]
-            gbs = step_bytes * n / e / 1e9
-            per_width[str(width)] = {"GB/s": round(gbs, 1), "pct_peak": round(100 * gbs / HBM_PEAK_GBS, 2),
-                                     "ms_per_step": round(e / n * 1e3, 4), "steps": n}
-            vte.vte_vstream_destroy(v)
-        out["per_width"] = per_width
-        out["bit_mismatches_across_widths"] = int(mism)
+        with _section(out, "chain per width"):
+            per_width, mism = {}, 0
+            ref_snap = None
+            for width in WIDTHS:
+                p = H.pctx_of_width(ctx, width)
+                v = vte.vte_vstream_create(ctx, vte.VTE_CLASS_LATENCY)
+                vte.vte_vstream_pin(v, p)
+                ch.set_tokens(tok0)
+                n = max(16, a.steps // 8)
+                run(ch, 4, v)
+                ch.set_tokens(tok0)
+                t = time.perf_counter()
+                run(ch, n, v)
+                e = time.perf_counter() - t
+                snap = ch.snapshot()
+                snap["tok"] = ch.tok.cpu().numpy().copy()
+                if ref_snap is None:
+                    ref_snap = snap
+                else:
+                    for k in ("n", "qkv", "o", "act", "d"):
+                        mism += H.mismatched_bits(ref_snap[k], snap[k])[1]
+                    mism += H.mismatched_bits(ref_snap["tok"].astype(np.uint32), snap["tok"].astype(np.uint32))[1]
+                gbs = step_bytes * n / e / 1e9
+                per_width[str(width)] = {"GB/s": round(gbs, 1), "pct_peak": round(100 * gbs / HBM_PEAK_GBS, 2),
+                                         "ms_per_step": round(e / n * 1e3, 4), "steps": n}
+                vte.vte_vstream_destroy(v)
+            out["per_width"] = per_width
+            out["bit_mismatches_across_widths"] = int(mism)
 
     # ---- the metric's single operators per CU width (outside the timed region) ----
     shared = {"w": w, "wd": wd, "shp": shp}
     if not a.no_width_sweep and not a.small:
-        _log("operators per width")
-        ops = {}
-        rows, cols = 32768, 4096                       # RMSNorm at a size HBM has to serve: 256 MiB in, 256 MiB out
-        x = H.to_dev(inputs.normal_bf16(0, inputs.T_X, (rows, cols)))           # x ~ N(0,1)
-        gam = H.to_dev(inputs.uniform_bf16(0, inputs.T_GAMMA, (cols,), 0.5, 1.5))  # gamma ~ U(0.5,1.5)
-        y = torch.empty_like(x)
-        d = vte.vte_desc_rmsnorm(ctx, x, gam, y, rows, cols, 1e-6)
-        r = {}
-        for width in WIDTHS:
-            t = vte.vte_profile_measure_on(ctx, d, H.pctx_of_width(ctx, width), 2, 6)
-            r[str(width)] = {"GB/s": round(rows * cols * 4 / t / 1e9, 1), "pct_peak": round(rows * cols * 4 / t / 1e9 / 80, 2)}
-        ops["rmsnorm_32768x4096"] = r
-        vte.vte_desc_destroy(d)
-        del x, y
-        N = K = 4096                                   # GEMV 4096x4096 (BASELINE config 2): W ~ N(0, 1/K), X ~ N(0,1);
-        Ws = [H.to_dev(inputs.normal_bf16(i, inputs.T_W, (N, K), 0.0, K ** -0.5)) for i in range(32)]  # 32 buffers in rotation (1 GiB > caches)
-        for b2 in (1, 4, 8):
-            X = H.to_dev(inputs.normal_bf16(0, inputs.T_XB, (b2, K)))
-            Y = torch.empty((b2, N), dtype=torch.int16, device="cuda")
-            plans = {"default": None}
-            if b2 == 8:                                # the dot-product plan beside the matrix-core default
-                pl = vte.vte_gemv_plan()
-                pl.batch_tile, pl.rows, pl.ksteps, pl.prefetch, pl.max_waves, pl.groups, pl.kind = 8, 2, 4, 0, 8, 8, vte.VTE_GEMV_DOT2
-                plans["dot2_plan"] = pl
-            for pname, pl in plans.items():
-                ds = [vte.vte_desc_gemv(ctx, W_, X, Y, b2, N, K) if pl is None else
-                      vte.vte_desc_gemv_planned(ctx, W_, X, Y, b2, N, K, vte.VTE_EPI_NONE, pl) for W_ in Ws]
-                r = {}
-                for width in WIDTHS:
-                    # 128 launches back to back on a virtual stream pinned to the pCtx, each on the next weight
-                    # buffer; wall time per launch (a single launch between two events would add their cost)
-                    v = vte.vte_vstream_create(ctx, vte.VTE_CLASS_LATENCY)
-                    vte.vte_vstream_pin(v, H.pctx_of_width(ctx, width))
-                    vte.vte_token_wait(ctx, vte.vte_submit_batch(v, vte.desc_array(ds)))
-                    burst = vte.desc_array(ds * 4)
-                    tb = time.perf_counter()
-                    vte.vte_token_wait(ctx, vte.vte_submit_batch(v, burst))
-                    t = (time.perf_counter() - tb) / (4 * len(ds))
-                    vte.vte_vstream_destroy(v)
-                    r[str(width)] = {"GB/s": round(N * K * 2 / t / 1e9, 1), "pct_peak": round(N * K * 2 / t / 1e9 / 80, 2),
-                                     "us": round(t * 1e6, 2)}
-                ops["gemv_4096x4096_B%d" % b2 + ("" if pl is None else "_" + pname)] = r
-                for dd in ds:
-                    vte.vte_desc_destroy(dd)
-        del Ws
-        torch.cuda.empty_cache()
-        M = 8192                                       # the co-tenant: bf16 MFMA GEMM 8192^3, N(0,1) inputs
-        gA = H.to_dev(inputs.normal_bf16(0, inputs.T_GEMM_A, (M, M)))
-        gB = H.to_dev(inputs.normal_bf16(0, inputs.T_GEMM_B, (M, M)))
-        gC = H.dev_empty((M, M))
-        shared.update(gA=gA, gB=gB, gC=gC)
-        d = vte.vte_desc_gemm(ctx, gA, gB, gC, M, M, M)
-        r = {}
-        for width in WIDTHS:
-            # steady state: the first dozen back-to-back launches at full width run through a clock transient
-            # (0.84 ms, up to 1.05 ms around the fourth, 0.82 ms from the sixteenth on), so they are warm-up
-            t = vte.vte_profile_measure_on(ctx, d, H.pctx_of_width(ctx, width), 20 if width >= 128 else 3, 20 if width >= 128 else 4)
-            r[str(width)] = {"TFLOP/s": round(2.0 * M ** 3 / t / 1e12, 1), "pct_mfma_peak": round(2.0 * M ** 3 / t / 1e12 / 25.0, 2),
-                             "ms": round(t * 1e3, 3)}
-        ops["gemm_8192_bf16"] = r
-        ops["gemm_8192_bf16"]["roofline"] = {"bound": "mfma", "achieved": r["256"]["TFLOP/s"], "peak": 2500.0, "unit": "TFLOP/s",
-                                             "frac": round(r["256"]["TFLOP/s"] / 2500.0, 4)}
-        vte.vte_desc_destroy(d)
-        out["per_operator"] = ops
+        with _section(out, "operators per width"):
+            ops = {}
+            rows, cols = 32768, 4096                       # RMSNorm at a size HBM has to serve: 256 MiB in, 256 MiB out
+            x = H.to_dev(inputs.normal_bf16(0, inputs.T_X, (rows, cols)))           # x ~ N(0,1)
+            gam = H.to_dev(inputs.uniform_bf16(0, inputs.T_GAMMA, (cols,), 0.5, 1.5))  # gamma ~ U(0.5,1.5)
+            y = torch.empty_like(x)
+            d = vte.vte_desc_rmsnorm(ctx, x, gam, y, rows, cols, 1e-6)
+            r = {}
+            for width in WIDTHS:
+                t = vte.vte_profile_measure_on(ctx, d, H.pctx_of_width(ctx, width), 2, 6)
+                r[str(width)] = {"GB/s": round(rows * cols * 4 / t / 1e9, 1), "pct_peak": round(rows * cols * 4 / t / 1e9 / 80, 2)}
+            ops["rmsnorm_32768x4096"] = r
+            vte.vte_desc_destroy(d)
+            del x, y
+            N = K = 4096                                   # GEMV 4096x4096 (BASELINE config 2): W ~ N(0, 1/K), X ~ N(0,1);
+            Ws = [H.to_dev(inputs.normal_bf16(i, inputs.T_W, (N, K), 0.0, K ** -0.5)) for i in range(32)]  # 32 buffers in rotation (1 GiB > caches)
+            for b2 in (1, 4, 8):
+                X = H.to_dev(inputs.normal_bf16(0, inputs.T_XB, (b2, K)))
+                Y = torch.empty((b2, N), dtype=torch.int16, device="cuda")
+                plans = {"default": None}
+                if b2 == 8:                                # the dot-product plan beside the matrix-core default
+                    pl = vte.vte_gemv_plan()
+                    pl.batch_tile, pl.rows, pl.ksteps, pl.prefetch, pl.max_waves, pl.groups, pl.kind = 8, 2, 4, 0, 8, 8, vte.VTE_GEMV_DOT2
+                    plans["dot2_plan"] = pl
+                for pname, pl in plans.items():
+                    ds = [vte.vte_desc_gemv(ctx, W_, X, Y, b2, N, K) if pl is None else
+                          vte.vte_desc_gemv_planned(ctx, W_, X, Y, b2, N, K, vte.VTE_EPI_NONE, pl) for W_ in Ws]
+                    r = {}
+                    for width in WIDTHS:
+                        # 128 launches back to back on a virtual stream pinned to the pCtx, each on the next weight
+                        # buffer; wall time per launch (a single launch between two events would add their cost)
+                        v = vte.vte_vstream_create(ctx, vte.VTE_CLASS_LATENCY)
+                        vte.vte_vstream_pin(v, H.pctx_of_width(ctx, width))
+                        vte.vte_token_wait(ctx, vte.vte_submit_batch(v, vte.desc_array(ds)))
+                        burst = vte.desc_array(ds * 4)
+                        tb = time.perf_counter()
+                        vte.vte_token_wait(ctx, vte.vte_submit_batch(v, burst))
+                        t = (time.perf_counter() - tb) / (4 * len(ds))
+                        vte.vte_vstream_destroy(v)
+                        r[str(width)] = {"GB/s": round(N * K * 2 / t / 1e9, 1), "pct_peak": round(N * K * 2 / t / 1e9 / 80, 2),
+                                         "us": round(t * 1e6, 2)}
+                    ops["gemv_4096x4096_B%d" % b2 + ("" if pl is None else "_" + pname)] = r
+                    for dd in ds:
+                        vte.vte_desc_destroy(dd)
+            del Ws
+            torch.cuda.empty_cache()
+            M = 8192                                       # the co-tenant: bf16 MFMA GEMM 8192^3, N(0,1) inputs
+            gA = H.to_dev(inputs.normal_bf16(0, inputs.T_GEMM_A, (M, M)))
+            gB = H.to_dev(inputs.normal_bf16(0, inputs.T_GEMM_B, (M, M)))
+            gC = H.dev_empty((M, M))
+            shared.update(gA=gA, gB=gB, gC=gC)
+            d = vte.vte_desc_gemm(ctx, gA, gB, gC, M, M, M)
+            r = {}
+            for width in WIDTHS:
+                # steady state: the first dozen back-to-back launches at full width run through a clock transient
+                # (0.84 ms, up to 1.05 ms around the fourth, 0.82 ms from the sixteenth on), so they are warm-up
+                t = vte.vte_profile_measure_on(ctx, d, H.pctx_of_width(ctx, width), 20 if width >= 128 else 3, 20 if width >= 128 else 4)
+                r[str(width)] = {"TFLOP/s": round(2.0 * M ** 3 / t / 1e12, 1), "pct_mfma_peak": round(2.0 * M ** 3 / t / 1e12 / 25.0, 2),
+                                 "ms": round(t * 1e3, 3)}
+            ops["gemm_8192_bf16"] = r
+            ops["gemm_8192_bf16"]["roofline"] = {"bound": "mfma", "achieved": r["256"]["TFLOP/s"], "peak": 2500.0, "unit": "TFLOP/s",
+                                                 "frac": round(r["256"]["TFLOP/s"] / 2500.0, 4)}
+            vte.vte_desc_destroy(d)
+            out["per_operator"] = ops
 
     # ---- other batch sizes of the same chain, full width (outside the timed region) -------------
     if not a.no_width_sweep:
-        _log("chain per batch")
-        per_batch = {}
-        for b2 in (1, 2, 4, 16, 32, 64):
-            c2 = H.DecodeChain(ctx, wd, shp, b2, feedback=True, fused_gather=True, fused_argmax=True)
-            c2.set_tokens(inputs.tokens(0, inputs.T_TOK0, b2, shp.V))
-            n = max(50, a.steps // 4)
-            run(c2, 20, vs)
-            t = time.perf_counter()
-            run(c2, n, vs)
-            e = time.perf_counter() - t
-            gbs = c2.bytes_per_step * n / e / 1e9
-            per_batch[str(b2)] = {"GB/s": round(gbs, 1), "pct_peak": round(100 * gbs / HBM_PEAK_GBS, 2),
-                                  "ms_per_step": round(e / n * 1e3, 4)}
-            c2.close()
-        out["per_batch"] = per_batch
+        with _section(out, "chain per batch"):
+            per_batch = {}
+            for b2 in (1, 2, 4, 16, 32, 64):
+                c2 = H.DecodeChain(ctx, wd, shp, b2, feedback=True, fused_gather=True, fused_argmax=True)
+                c2.set_tokens(inputs.tokens(0, inputs.T_TOK0, b2, shp.V))
+                n = max(50, a.steps // 4)
+                run(c2, 20, vs)
+                t = time.perf_counter()
+                run(c2, n, vs)
+                e = time.perf_counter() - t
+                gbs = c2.bytes_per_step * n / e / 1e9
+                per_batch[str(b2)] = {"GB/s": round(gbs, 1), "pct_peak": round(100 * gbs / HBM_PEAK_GBS, 2),
+                                      "ms_per_step": round(e / n * 1e3, 4)}
+                c2.close()
+            out["per_batch"] = per_batch
 
     out["final_tokens_checksum"] = int(tokens_end.astype(np.int64).sum())
     vte.vte_vstream_destroy(vs)
@@ -292,163 +311,163 @@ def main():
     if not a.no_extras:
         from paper_2603_15042_amd import experiments as E
         # ---- strict binding (readiness before binding, literally): same chain, same steps -------
-        _log("strict binding")
-        cfg2 = vte.vte_pool_cfg_default()
-        cfg2.mode = vte.VTE_MODE_STRICT
-        ctx2 = vte.vte_init(0, cfg2)
-        ch2 = H.DecodeChain(ctx2, wd, shp, B, feedback=True, fused_gather=True, fused_argmax=True)
-        vs2 = vte.vte_vstream_create(ctx2, vte.VTE_CLASS_LATENCY)
-        n = max(100, min(a.steps, 400))
-        ch2.set_tokens(tok0)
-        run(ch2, 30, vs2)
-        ch2.set_tokens(tok0)
-        t = time.perf_counter()
-        run(ch2, n, vs2)
-        e = time.perf_counter() - t
-        strict_tok = ch2.tok.cpu().numpy().copy()
-        out["strict"] = {"ms_per_step": round(e / n * 1e3, 4), "GB/s": round(step_bytes * n / e / 1e9, 1),
-                         "pct_peak": round(100 * step_bytes * n / e / 1e9 / HBM_PEAK_GBS, 2), "steps": n}
-        # the same chain with the step boundary in the QKV launch's prologue (five launches per step, the
-        # same bits): a loss of about 2 % under pipelined binding, where a launch boundary is free, and a
-        # gain under strict binding, where each boundary is a host round trip
-        if B <= 16 and shp.D == 4096:
-            ch5 = H.DecodeChain(ctx2, wd, shp, B, feedback=True, fused_gather=True, fused_argmax=True, fused_qkv=True)
-            ch5.set_tokens(tok0)
-            run(ch5, 30, vs2)
-            ch5.set_tokens(tok0)
+        with _section(out, "strict binding"):
+            cfg2 = vte.vte_pool_cfg_default()
+            cfg2.mode = vte.VTE_MODE_STRICT
+            ctx2 = vte.vte_init(0, cfg2)
+            ch2 = H.DecodeChain(ctx2, wd, shp, B, feedback=True, fused_gather=True, fused_argmax=True)
+            vs2 = vte.vte_vstream_create(ctx2, vte.VTE_CLASS_LATENCY)
+            n = max(100, min(a.steps, 400))
+            ch2.set_tokens(tok0)
+            run(ch2, 30, vs2)
+            ch2.set_tokens(tok0)
             t = time.perf_counter()
-            run(ch5, n, vs2)
-            e5 = time.perf_counter() - t
-            out["strict"]["five_launches_per_step"] = {
-                "ms_per_step": round(e5 / n * 1e3, 4), "GB/s": round(ch5.bytes_per_step * n / e5 / 1e9, 1),
-                "pct_peak": round(100 * ch5.bytes_per_step * n / e5 / 1e9 / HBM_PEAK_GBS, 2),
-                "tokens_equal_six_launches": bool(np.array_equal(strict_tok, ch5.tok.cpu().numpy()))}
-            ch5.close()
-        # the pipelined chain of the timed region, from the same tokens, after the same number of steps
-        vte.vte_vstream_destroy(vs2)
-        # ---- BASELINE config 1: launch latency of the 8 x 1024 RMSNorm per width -------------------
-        _log("config 1 latency")
-        out["config1_rmsnorm_8x1024"] = E.config1_latency(ctx2, 200)
-        ch2.close()
-        vte.vte_shutdown(ctx2)
-        cfg3 = vte.vte_pool_cfg_default()
-        cfg3.mode = vte.VTE_MODE_PIPELINED
-        cfg3.lookahead = a.lookahead
-        ctx3 = vte.vte_init(0, cfg3)
-        ch3 = H.DecodeChain(ctx3, wd, shp, B, feedback=True, fused_gather=True, fused_argmax=True)
-        vs3 = vte.vte_vstream_create(ctx3, vte.VTE_CLASS_LATENCY)
-        ch3.set_tokens(tok0)
-        run(ch3, 30, vs3)
-        ch3.set_tokens(tok0)
-        run(ch3, n, vs3)
-        out["strict"]["tokens_equal_pipelined"] = bool(np.array_equal(strict_tok, ch3.tok.cpu().numpy()))
-        if B <= 16 and shp.D == 4096:   # the five-launch chain under pipelined binding, beside the six-launch one
-            res5 = {}
-            for name, fq in (("six_launches", False), ("five_launches", True)):
-                c = ch3 if not fq else H.DecodeChain(ctx3, wd, shp, B, feedback=True, fused_gather=True, fused_argmax=True, fused_qkv=True)
-                c.set_tokens(tok0)
-                run(c, 100, vs3)
+            run(ch2, n, vs2)
+            e = time.perf_counter() - t
+            strict_tok = ch2.tok.cpu().numpy().copy()
+            out["strict"] = {"ms_per_step": round(e / n * 1e3, 4), "GB/s": round(step_bytes * n / e / 1e9, 1),
+                             "pct_peak": round(100 * step_bytes * n / e / 1e9 / HBM_PEAK_GBS, 2), "steps": n}
+            # the same chain with the step boundary in the QKV launch's prologue (five launches per step, the
+            # same bits): a loss of about 2 % under pipelined binding, where a launch boundary is free, and a
+            # gain under strict binding, where each boundary is a host round trip
+            if B <= 16 and shp.D == 4096:
+                ch5 = H.DecodeChain(ctx2, wd, shp, B, feedback=True, fused_gather=True, fused_argmax=True, fused_qkv=True)
+                ch5.set_tokens(tok0)
+                run(ch5, 30, vs2)
+                ch5.set_tokens(tok0)
                 t = time.perf_counter()
-                run(c, n, vs3)
-                e6 = time.perf_counter() - t
-                res5[name] = {"ms_per_step": round(e6 / n * 1e3, 4), "GB/s": round(c.bytes_per_step * n / e6 / 1e9, 1)}
-                if fq:
-                    c.close()
-            out["boundary_in_qkv_launch_pipelined"] = res5
-        vte.vte_vstream_destroy(vs3)
-        ch3.close()
-        vte.vte_shutdown(ctx3)
+                run(ch5, n, vs2)
+                e5 = time.perf_counter() - t
+                out["strict"]["five_launches_per_step"] = {
+                    "ms_per_step": round(e5 / n * 1e3, 4), "GB/s": round(ch5.bytes_per_step * n / e5 / 1e9, 1),
+                    "pct_peak": round(100 * ch5.bytes_per_step * n / e5 / 1e9 / HBM_PEAK_GBS, 2),
+                    "tokens_equal_six_launches": bool(np.array_equal(strict_tok, ch5.tok.cpu().numpy()))}
+                ch5.close()
+            # the pipelined chain of the timed region, from the same tokens, after the same number of steps
+            vte.vte_vstream_destroy(vs2)
+            # ---- BASELINE config 1: launch latency of the 8 x 1024 RMSNorm per width -------------------
+            _log("config 1 latency")
+            out["config1_rmsnorm_8x1024"] = E.config1_latency(ctx2, 200)
+            ch2.close()
+            vte.vte_shutdown(ctx2)
+            cfg3 = vte.vte_pool_cfg_default()
+            cfg3.mode = vte.VTE_MODE_PIPELINED
+            cfg3.lookahead = a.lookahead
+            ctx3 = vte.vte_init(0, cfg3)
+            ch3 = H.DecodeChain(ctx3, wd, shp, B, feedback=True, fused_gather=True, fused_argmax=True)
+            vs3 = vte.vte_vstream_create(ctx3, vte.VTE_CLASS_LATENCY)
+            ch3.set_tokens(tok0)
+            run(ch3, 30, vs3)
+            ch3.set_tokens(tok0)
+            run(ch3, n, vs3)
+            out["strict"]["tokens_equal_pipelined"] = bool(np.array_equal(strict_tok, ch3.tok.cpu().numpy()))
+            if B <= 16 and shp.D == 4096:   # the five-launch chain under pipelined binding, beside the six-launch one
+                res5 = {}
+                for name, fq in (("six_launches", False), ("five_launches", True)):
+                    c = ch3 if not fq else H.DecodeChain(ctx3, wd, shp, B, feedback=True, fused_gather=True, fused_argmax=True, fused_qkv=True)
+                    c.set_tokens(tok0)
+                    run(c, 100, vs3)
+                    t = time.perf_counter()
+                    run(c, n, vs3)
+                    e6 = time.perf_counter() - t
+                    res5[name] = {"ms_per_step": round(e6 / n * 1e3, 4), "GB/s": round(c.bytes_per_step * n / e6 / 1e9, 1)}
+                    if fq:
+                        c.close()
+                out["boundary_in_qkv_launch_pipelined"] = res5
+            vte.vte_vstream_destroy(vs3)
+            ch3.close()
+            vte.vte_shutdown(ctx3)
 
         # ---- co-tenancy (BASELINE config 4): decode bursts beside the 8192^3 GEMM -----------------
         if not a.small:
-            _log("co-tenancy")
-            r = E.cotenancy(a.cotenancy_seconds, 60.0, shared=shared, modes=("fixed", "late"))
-            keep = ("gemm_per_s", "norm_gemm", "norm_decode", "aggregate_normalized_throughput", "bursts", "bursts_compared",
-                    "bursts_with_token_mismatch", "step_ms_mean", "step_latency_ms_p50", "step_latency_ms_p99", "steps_timed",
-                    "first_step_ms_mean", "gemm_widths", "decode_widths", "overlap")
-            out["cotenancy"] = {
-                "seconds_per_mode": a.cotenancy_seconds, "gemm_tflops_solo": round(r["gemm_tflops_solo"], 1),
-                "solo_decode": {k: r["solo_decode"].get(k) for k in ("step_ms_mean", "step_latency_ms_p50", "step_latency_ms_p99", "bursts")},
-                "fixed_128_128": {k: r["fixed"].get(k) for k in keep},
-                "late_bound": {k: r["late"].get(k) for k in keep},
-                "late_bound_beats_fixed_split": bool(r["late"]["aggregate_normalized_throughput"] > r["fixed"]["aggregate_normalized_throughput"]),
-            }
+            with _section(out, "co-tenancy"):
+                r = E.cotenancy(a.cotenancy_seconds, 60.0, shared=shared, modes=("fixed", "late"))
+                keep = ("gemm_per_s", "norm_gemm", "norm_decode", "aggregate_normalized_throughput", "bursts", "bursts_compared",
+                        "bursts_with_token_mismatch", "step_ms_mean", "step_latency_ms_p50", "step_latency_ms_p99", "steps_timed",
+                        "first_step_ms_mean", "gemm_widths", "decode_widths", "overlap")
+                out["cotenancy"] = {
+                    "seconds_per_mode": a.cotenancy_seconds, "gemm_tflops_solo": round(r["gemm_tflops_solo"], 1),
+                    "solo_decode": {k: r["solo_decode"].get(k) for k in ("step_ms_mean", "step_latency_ms_p50", "step_latency_ms_p99", "bursts")},
+                    "fixed_128_128": {k: r["fixed"].get(k) for k in keep},
+                    "late_bound": {k: r["late"].get(k) for k in keep},
+                    "late_bound_beats_fixed_split": bool(r["late"]["aggregate_normalized_throughput"] > r["fixed"]["aggregate_normalized_throughput"]),
+                }
         for k in ("gA", "gB", "gC"):
             shared.pop(k, None)
         torch.cuda.empty_cache()
 
         # ---- determinism protocol at a reduced trial count -----------------------------------------
-        _log("determinism")
-        dres = E.determinism(a.determinism_trials, 0, sections=("rmsnorm", "gemv"))
-        fixed_bits = sum(v.get("fixed_mismatched_bits", 0) + v.get("fixed_mismatched_bits_bf16", 0) + v.get("fixed_mismatched_bits_fp32", 0)
-                         for v in dres.values())
-        out["determinism"] = {"trials_per_operator": a.determinism_trials, "fixed_mismatched_bits": int(fixed_bits),
-                              "reshaped_trials_that_drift": {k: int(v.get("reshaped_trials_with_mismatch", v.get("reshaped_trials_with_mismatch_fp32", 0)))
-                                                             for k, v in dres.items()},
-                              "reshaped_trials_that_drift_in_bf16": {k: int(v.get("reshaped_trials_with_mismatch", v.get("reshaped_trials_with_mismatch_bf16", 0)))
-                                                                     for k, v in dres.items()}}
+        with _section(out, "determinism"):
+            dres = E.determinism(a.determinism_trials, 0, sections=("rmsnorm", "gemv"))
+            fixed_bits = sum(v.get("fixed_mismatched_bits", 0) + v.get("fixed_mismatched_bits_bf16", 0) + v.get("fixed_mismatched_bits_fp32", 0)
+                             for v in dres.values())
+            out["determinism"] = {"trials_per_operator": a.determinism_trials, "fixed_mismatched_bits": int(fixed_bits),
+                                  "reshaped_trials_that_drift": {k: int(v.get("reshaped_trials_with_mismatch", v.get("reshaped_trials_with_mismatch_fp32", 0)))
+                                                                 for k, v in dres.items()},
+                                  "reshaped_trials_that_drift_in_bf16": {k: int(v.get("reshaped_trials_with_mismatch", v.get("reshaped_trials_with_mismatch_bf16", 0)))
+                                                                         for k, v in dres.items()}}
 
     # ---- the oracle timed on the host cores (a baseline for scale only) -----------------------
     if not a.no_cpu_baseline:
-        _log("cpu baseline")
-        import oracle
-        thr = oracle.default_threads()
-        t = time.perf_counter()
-        tok_c, n_cpu, first = tok0, 0, None
-        while True:                                   # free-running oracle decode, about 10 s of CPU work
-            o = oracle.decode_step(w, tok_c, shp, threads=thr)
-            first = first if first is not None else o["next"].copy()
-            tok_c = o["next"]
-            n_cpu += 1
-            ct = time.perf_counter() - t
-            if ct > 8.0 or n_cpu >= 64:
-                break
-        cpu = {"value": round(step_bytes * n_cpu / ct / 1e9, 3), "unit": "GB/s", "cores": thr, "kind": "oracle",
-               "sample": "%d free-running decode steps at batch %d (whole chain, double precision), %.1f s" % (n_cpu, B, ct),
-               "hardware_threads": oracle.hardware_threads()}
+        with _section(out, "cpu baseline"):
+            import oracle
+            thr = oracle.default_threads()
+            t = time.perf_counter()
+            tok_c, n_cpu, first = tok0, 0, None
+            while True:                                   # free-running oracle decode, about 10 s of CPU work
+                o = oracle.decode_step(w, tok_c, shp, threads=thr)
+                first = first if first is not None else o["next"].copy()
+                tok_c = o["next"]
+                n_cpu += 1
+                ct = time.perf_counter() - t
+                if ct > 8.0 or n_cpu >= 64:
+                    break
+            cpu = {"value": round(step_bytes * n_cpu / ct / 1e9, 3), "unit": "GB/s", "cores": thr, "kind": "oracle",
+                   "sample": "%d free-running decode steps at batch %d (whole chain, double precision), %.1f s" % (n_cpu, B, ct),
+                   "hardware_threads": oracle.hardware_threads()}
 
-        def timed(fn, reps=1):
-            tb = time.perf_counter()
-            for _ in range(reps):
-                fn()
-            return (time.perf_counter() - tb) / reps
-        t1c = timed(lambda: oracle.decode_step(w, tok0, shp, threads=1))
-        cpu["one_core"] = {"value": round(step_bytes / t1c / 1e9, 4), "unit": "GB/s", "sample": "1 decode step at batch %d, %.1f s" % (B, t1c)}
-        if not a.small:
-            per_op = {}
-            x8, g8 = inputs.rmsnorm_case(seed=0, rows=8, cols=1024)
-            per_op["rmsnorm_8x1024_us"] = round(timed(lambda: oracle.rmsnorm(x8, g8, threads=thr), 20) * 1e6, 1)
-            xs = inputs.normal_bf16(0, inputs.T_X, (2048, 4096))
-            per_op["rmsnorm_2048x4096_ms (a 1/16 sample of 32768x4096)"] = round(timed(lambda: oracle.rmsnorm(xs, w["gamma"], threads=thr)) * 1e3, 2)
-            Wc, _ = inputs.gemv_case(seed=0, B=1, N=4096, K=4096)
-            for b2 in (1, 4, 8):
-                Xc = inputs.normal_bf16(0, inputs.T_XB, (b2, 4096))
-                per_op["gemv_4096x4096_B%d_ms" % b2] = round(timed(lambda: oracle.gemv(Wc, Xc, threads=thr), 3) * 1e3, 2)
-            for b2 in (1, 16):
+            def timed(fn, reps=1):
+                tb = time.perf_counter()
+                for _ in range(reps):
+                    fn()
+                return (time.perf_counter() - tb) / reps
+            t1c = timed(lambda: oracle.decode_step(w, tok0, shp, threads=1))
+            cpu["one_core"] = {"value": round(step_bytes / t1c / 1e9, 4), "unit": "GB/s", "sample": "1 decode step at batch %d, %.1f s" % (B, t1c)}
+            if not a.small:
+                per_op = {}
+                x8, g8 = inputs.rmsnorm_case(seed=0, rows=8, cols=1024)
+                per_op["rmsnorm_8x1024_us"] = round(timed(lambda: oracle.rmsnorm(x8, g8, threads=thr), 20) * 1e6, 1)
+                xs = inputs.normal_bf16(0, inputs.T_X, (2048, 4096))
+                per_op["rmsnorm_2048x4096_ms (a 1/16 sample of 32768x4096)"] = round(timed(lambda: oracle.rmsnorm(xs, w["gamma"], threads=thr)) * 1e3, 2)
+                Wc, _ = inputs.gemv_case(seed=0, B=1, N=4096, K=4096)
+                for b2 in (1, 4, 8):
+                    Xc = inputs.normal_bf16(0, inputs.T_XB, (b2, 4096))
+                    per_op["gemv_4096x4096_B%d_ms" % b2] = round(timed(lambda: oracle.gemv(Wc, Xc, threads=thr), 3) * 1e3, 2)
+                for b2 in (1, 16):
+                    tb2 = inputs.tokens(0, inputs.T_TOK0, b2, shp.V)
+                    per_op["decode_step_B%d_ms" % b2] = round(timed(lambda: oracle.decode_step(w, tb2, shp, threads=thr)) * 1e3, 1)
+                per_op["decode_step_B%d_ms" % B] = round(ct / n_cpu * 1e3, 1)
+                Ag = inputs.normal_bf16(0, inputs.T_GEMM_A, (1024, 1024))
+                Bg = inputs.normal_bf16(0, inputs.T_GEMM_B, (1024, 1024))
+                per_op["gemm_1024^3_ms"] = round(timed(lambda: oracle.gemm_rows(Ag, Bg, np.arange(1024), threads=thr)) * 1e3, 1)
+                cpu["per_operator_all_cores"] = per_op
+            out["cpu_baseline"] = cpu
+            # the GPU chain from the same start tokens must pick the oracle's tokens, at every batch the sweep timed
+            ctx4 = vte.vte_init(0, cfg)
+            vs4 = vte.vte_vstream_create(ctx4, vte.VTE_CLASS_LATENCY)
+            match = {}
+            for b2 in ((1, 2, 4, 8, 16) if not a.small else (B,)):
+                c4 = H.DecodeChain(ctx4, wd, shp, b2, feedback=True, fused_gather=True, fused_argmax=True)
                 tb2 = inputs.tokens(0, inputs.T_TOK0, b2, shp.V)
-                per_op["decode_step_B%d_ms" % b2] = round(timed(lambda: oracle.decode_step(w, tb2, shp, threads=thr)) * 1e3, 1)
-            per_op["decode_step_B%d_ms" % B] = round(ct / n_cpu * 1e3, 1)
-            Ag = inputs.normal_bf16(0, inputs.T_GEMM_A, (1024, 1024))
-            Bg = inputs.normal_bf16(0, inputs.T_GEMM_B, (1024, 1024))
-            per_op["gemm_1024^3_ms"] = round(timed(lambda: oracle.gemm_rows(Ag, Bg, np.arange(1024), threads=thr)) * 1e3, 1)
-            cpu["per_operator_all_cores"] = per_op
-        out["cpu_baseline"] = cpu
-        # the GPU chain from the same start tokens must pick the oracle's tokens, at every batch the sweep timed
-        ctx4 = vte.vte_init(0, cfg)
-        vs4 = vte.vte_vstream_create(ctx4, vte.VTE_CLASS_LATENCY)
-        match = {}
-        for b2 in ((1, 2, 4, 8, 16) if not a.small else (B,)):
-            c4 = H.DecodeChain(ctx4, wd, shp, b2, feedback=True, fused_gather=True, fused_argmax=True)
-            tb2 = inputs.tokens(0, inputs.T_TOK0, b2, shp.V)
-            c4.set_tokens(tb2)
-            run(c4, 1, vs4)
-            ref = first if b2 == B else oracle.decode_step(w, tb2, shp, threads=thr)["next"]
-            match[str(b2)] = bool(np.array_equal(c4.tok.cpu().numpy(), ref))
-            c4.close()
-        vte.vte_vstream_destroy(vs4)
-        vte.vte_shutdown(ctx4)
-        out["first_step_tokens_match_oracle"] = match[str(B)]
-        out["first_step_tokens_match_oracle_per_batch"] = match
+                c4.set_tokens(tb2)
+                run(c4, 1, vs4)
+                ref = first if b2 == B else oracle.decode_step(w, tb2, shp, threads=thr)["next"]
+                match[str(b2)] = bool(np.array_equal(c4.tok.cpu().numpy(), ref))
+                c4.close()
+            vte.vte_vstream_destroy(vs4)
+            vte.vte_shutdown(ctx4)
+            out["first_step_tokens_match_oracle"] = match[str(B)]
+            out["first_step_tokens_match_oracle_per_batch"] = match
     out["gen_seconds"] = round(gen_s, 1)
     print(json.dumps(out))
 
