@@ -2,7 +2,7 @@
 
     python -m paper_2603_15042_amd.build [--force] [--trace]
 
---trace also builds libvte_trace.so: the same library with the matrix-core GEMV (batch 5 to 16)
+--trace also builds libvte_trace.so: the same library with the matrix-core GEMV (batch 3 to 16)
 compiled with device-side time stamps (csrc/trace_stamps.h), for `experiments ramp`.
 """
 import concurrent.futures as cf

@@ -635,7 +635,7 @@ RAMP_POINTS = ("entry", "arguments in, first loads issued", "X arrived and turne
 
 def ramp(batches=(8, 16), N=4096, K=4096, width=256, bursts=9):
     """Where the time of one small GEMV launch goes (BASELINE config 2: 4096 x 4096; the matrix-core
-    kind, batch 5 to 16).  Needs the trace build of the library (`python -m paper_2603_15042_amd.build
+    kind, batch 3 to 16).  Needs the trace build of the library (`python -m paper_2603_15042_amd.build
     --trace`), whose kernels stamp the device's 100 MHz clock per wave (csrc/trace_stamps.h): 128
     launches back to back on a stream pinned to one pCtx, 32 weight buffers in rotation; reported are,
     for the last launch of a burst, the stamps of all waves relative to the first wave's entry (each

@@ -794,7 +794,7 @@ def test_strided_gemv_in_every_kernel_family(H, ctx, B, N, K, ld, ldy):
     vte.vte_desc_destroy(d)
 
 
-# ---------- matrix-core GEMV plans (batch 5-16) ---------------------------------------------------------
+# ---------- matrix-core GEMV plans (batch 3-16) ---------------------------------------------------------
 MFMA_PLANS = [(1, 2, 8, 1), (2, 4, 4, 3), (4, 2, 8, 2), (8, 2, 8, 1), (4, 4, 4, 1), (8, 4, 4, 2), (2, 2, 4, 2)]
 
 
