@@ -50,6 +50,49 @@ void bump(vte_ctx* c) {  // runtime lock held: something changed from outside
   c->cv_work.notify_all();
 }
 
+void notify_done(vte_ctx* c) {  // runtime lock held: launches retired, were bound, or the dispatcher went quiet
+  c->done_epoch.fetch_add(1, std::memory_order_release);
+  c->cv_done.notify_all();
+}
+
+inline void cpu_relax() {
+#if defined(__x86_64__)
+  __builtin_ia32_pause();
+#else
+  std::this_thread::yield();
+#endif
+}
+
+// A condition-variable wake costs tens of microseconds on the hosts this runs on, twice per burst
+// (the idle dispatcher at its start, the caller at its end): 100 to 140 us on a 5 ms burst.  Both
+// sides therefore poll for a bounded time where the event they wait for is close, and sleep otherwise.
+constexpr double kWaiterPollSeconds = 20e-3;     // per wait call, while what it waits for is on the device
+constexpr double kDispatcherPollSeconds = 2e-3;  // after the dispatcher ran out of work, before it sleeps
+
+// Runtime lock held.  Returns when done() holds.  While on_device() says that everything awaited has
+// been handed to the device the caller polls the notification epoch without the lock (up to
+// kWaiterPollSeconds in total); before that, and past the budget, it sleeps on cv_done.
+template <class Done, class OnDevice>
+void wait_done(vte_ctx* c, Lock& lk, Done done, OnDevice on_device) {
+  double polled = 0;
+  while (!done()) {
+    if (c->backend->is_fake() || polled >= kWaiterPollSeconds || !on_device()) {
+      c->cv_done.wait(lk);  // every state change that done() or on_device() look at is notified with the lock held
+      continue;
+    }
+    const uint64_t e = c->done_epoch.load(std::memory_order_acquire);
+    lk.unlock();
+    const auto t0 = std::chrono::steady_clock::now();
+    double dt = 0;
+    while (c->done_epoch.load(std::memory_order_acquire) == e && dt < 500e-6) {
+      for (int i = 0; i < 32; ++i) cpu_relax();
+      dt = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
+    }
+    polled += dt;
+    lk.lock();
+  }
+}
+
 bool token_done(vte_ctx* c, vte_token t) {
   if (t == 0) return true;
   return c->live.find(t) == c->live.end();
@@ -288,7 +331,7 @@ bool poll_completions(vte_ctx* c) {
       complete_op(c, done[i], rcs[i]);
     }
     any = true;
-    c->cv_done.notify_all();
+    notify_done(c);
   }
   return any;
 }
@@ -303,7 +346,7 @@ void fail_inflight_on(vte_ctx* c, int p, int rc) {
   const int hip = g_hip_err;
   c->inflight.swap(keep);
   for (Op* op : bad) { set_error(msg, hip); complete_op(c, op, rc); }
-  c->cv_done.notify_all();
+  notify_done(c);
 }
 
 // Give the newest unrecorded launch of a pCtx a completion record when it is
@@ -558,7 +601,7 @@ void fail_head(vte_ctx* c, vte_vstream* vs, int rc, const char* why = nullptr) {
   c->live.erase(op->tok);
   delete op;
   if (vs->tpot > 0 && vs->queue.empty() && vs->unfinished_bound == 0) vs->t_idle = c->now();
-  c->cv_done.notify_all();
+  notify_done(c);
 }
 
 // An op whose predecessor failed fails with it (Sec. 4.2: it may run only after its predecessors
@@ -916,13 +959,16 @@ void dispatcher_main(vte_ctx* c) {
     bool progress = poll_completions(c);
     if (!c->custom_policy && c->builtin == VTE_POLICY_TPOT_FIRST) tpot_maintain(c);
     // keep binding while ops become bindable (PIPELINED chains, freed leases)
-    while (dispatch_round(c)) progress = true;
+    bool bound = false;
+    while (dispatch_round(c)) bound = true;
+    progress = progress || bound;
     flush_records(c);  // PIPELINED: one completion record per burst and pCtx instead of one per launch
+    if (bound && (!c->awaited.empty() || c->waiters_all)) notify_done(c);  // a waiter may start polling now
     if (c->stop && c->live.empty()) break;
     if (progress) continue;
     if (c->change_seq == seen) {
       c->quiesced_seq = seen;
-      c->cv_done.notify_all();
+      c->cv_done.notify_all();  // for vte_dispatcher_quiesce only: no launch changed state, pollers need not look
     }
     if (!c->inflight.empty() && !c->backend->is_fake()) {
       // device work outstanding: poll again soon, letting callers in
@@ -933,8 +979,21 @@ void dispatcher_main(vte_ctx* c) {
       // nothing can change without outside input (or a policy that deferred)
       bool pending = false;
       for (vte_vstream* vs : c->vstreams) if (vs && !vs->queue.empty()) pending = true;
-      if (pending && c->inflight.empty()) c->cv_work.wait_for(lk, std::chrono::microseconds(200));
-      else c->cv_work.wait(lk, [&] { return c->change_seq != seen || c->stop; });
+      if (pending && c->inflight.empty()) {
+        c->cv_work.wait_for(lk, std::chrono::microseconds(200));
+      } else {
+        if (!c->backend->is_fake() && !c->stop) {
+          // just ran out of work: the next submission often follows within the millisecond (the caller
+          // synchronised and submits the next burst); poll for it before going to sleep
+          lk.unlock();
+          const auto t0 = std::chrono::steady_clock::now();
+          while (c->change_seq.load(std::memory_order_acquire) == seen &&
+                 std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count() < kDispatcherPollSeconds)
+            for (int i = 0; i < 32; ++i) cpu_relax();
+          lk.lock();
+        }
+        c->cv_work.wait(lk, [&] { return c->change_seq != seen || c->stop; });
+      }
     }
   }
 }
@@ -1031,10 +1090,12 @@ int vte_device_sync(vte_ctx* c) {
   const vte_token upto = c->next_token;
   ++c->waiters_all;
   bump(c);  // the dispatcher records a completion behind every pCtx's newest launch while somebody waits for all
-  c->cv_done.wait(lk, [&] {
-    for (auto& kv : c->live) if (kv.first < upto) return false;
-    return true;
-  });
+  wait_done(c, lk,
+            [&] {
+              for (auto& kv : c->live) if (kv.first < upto) return false;
+              return true;
+            },
+            [&] { return c->live.size() == c->inflight.size(); });  // nothing is left unbound
   --c->waiters_all;
   if (c->failure_unreported) {  // something failed since the last device-wide wait: say so once, here
     c->failure_unreported = false;
@@ -1280,7 +1341,11 @@ int vte_token_wait(vte_ctx* c, vte_token t) {
   if (token_done(c, t)) return report_failure(c, t);
   c->awaited.push_back(t);
   bump(c);  // the dispatcher sees to it that a completion record covers the awaited launch
-  c->cv_done.wait(lk, [&] { return token_done(c, t); });
+  wait_done(c, lk, [&] { return token_done(c, t); },
+            [&] {
+              auto it = c->live.find(t);
+              return it != c->live.end() && it->second->state == kInflight;
+            });
   c->awaited.erase(std::find(c->awaited.begin(), c->awaited.end(), t));
   return report_failure(c, t);
 }

@@ -139,7 +139,8 @@ struct vte_ctx {
   std::condition_variable cv_done;  // waiters sleep here
   std::thread dispatcher;
   bool stop = false;
-  uint64_t change_seq = 0;    // bumped by every outside input
+  std::atomic<uint64_t> change_seq{0};  // bumped by every outside input (written with the lock held; the idle dispatcher polls it without)
+  std::atomic<uint64_t> done_epoch{0};  // bumped with every cv_done notification: what a polling waiter watches without the lock
   uint64_t quiesced_seq = ~0ull;
 
   vte_token next_token = 1;
