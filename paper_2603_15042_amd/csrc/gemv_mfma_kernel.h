@@ -155,8 +155,15 @@ __global__ __launch_bounds__(MAXW * 64) void gemv_mfma_kernel(const typename gem
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct)
 #pragma unroll
-      for (int u = 0; u < 4; ++u)
-        xs[ct][bi][u] = __builtin_amdgcn_raw_buffer_load_b128(rs_x, in_k ? voff_x[ct][u] : 0x80000000u, soff + bi * 256, 0);
+      for (int u = 0; u < 4; ++u) {
+        // an instruction whose four batch rows all lie past B is not issued at all (uniform over the
+        // workgroup): it would fetch nothing, but still take the CU's address unit for as long as a
+        // full one, in front of the first weights
+        if (row0 + 16 * ct + 4 * u < a.B)
+          xs[ct][bi][u] = __builtin_amdgcn_raw_buffer_load_b128(rs_x, in_k ? voff_x[ct][u] : 0x80000000u, soff + bi * 256, 0);
+        else
+          xs[ct][bi][u] = zero;
+      }
   };
   // load order -> operand order, in place, through the wave's transposition area (free between blocks)
   auto transpose_x = [&]() {
