@@ -93,11 +93,13 @@ __global__ __launch_bounds__(WR * 64) void gemv_rows_kernel(const GemvArgs a) {
       const_cast<uint16_t*>(a.X), 0, static_cast<int>((static_cast<uint32_t>(a.B - 1) * a.ldx + a.K) * 2u), kRsrcFlags);
   uint32_t voff_x[XU];  // unit j = wave XU + i: column tile j / 4, rows 4 (j % 4) + lr of it
   int xdst[XU];         // where the unit's piece goes in a stage buffer
+  bool x_live[XU];      // wave-uniform: some of the unit's four batch rows exist (else its load is not issued at all)
 #pragma unroll
   for (int i = 0; i < XU; ++i) {
     const int j = wave * XU + i, ct = j >> 2, r = 4 * (j & 3) + lr, row = 16 * ct + r;
     voff_x[i] = row < a.B ? (static_cast<uint32_t>(row) * a.ldx + lp * 8) * 2u : kNoFetch;
     xdst[i] = ct * 256 + r * 16 + (lp ^ r);
+    x_live[i] = 16 * ct + 4 * (j & 3) < a.B;
   }
   const bool k_ragged = (a.K & 127) != 0;  // only then can a piece lie past K
 
@@ -112,7 +114,10 @@ __global__ __launch_bounds__(WR * 64) void gemv_rows_kernel(const GemvArgs a) {
     const int k = kstep(rd, p);
     const bool in = !k_ragged || k * 128 + lp * 8 < a.K;
 #pragma unroll
-    for (int i = 0; i < XU; ++i) dst[i] = __builtin_amdgcn_raw_buffer_load_b128(rs_x, in ? voff_x[i] : kNoFetch, k * 256, 0);
+    for (int i = 0; i < XU; ++i) {
+      if (x_live[i]) dst[i] = __builtin_amdgcn_raw_buffer_load_b128(rs_x, in ? voff_x[i] : kNoFetch, k * 256, 0);
+      else dst[i] = u32x4{0u, 0u, 0u, 0u};
+    }
   };
   auto store_x = [&](const u32x4(&src)[XU], int buf) {
 #pragma unroll
