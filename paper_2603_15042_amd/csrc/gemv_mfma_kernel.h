@@ -18,7 +18,11 @@
 //     one chunk per wave X is loaded once per workgroup, so rounds are what keeps
 //     the X re-reads (L2 -> CU traffic that competes with the weight stream) small;
 //     with several chunks per wave a chunk's X is requested block by block while the
-//     last row tile of the chunk before it is being multiplied;
+//     last row tile of the chunk before it is being multiplied.  With one chunk per wave
+//     and one column tile the first NB weight blocks are requested in front of X (theirs is the longer round
+//     trip, and a CU's address unit needs about 0.6 us for a workgroup's X requests), and
+//     X is turned into operand order block by block, right before a block's first use:
+//     turned all at once in front of the stream it held the stream's window still;
 //   * a block is fetched with four coalesced wave loads (4 rows x 256 B each; the
 //     MFMA operand layout itself would make every load touch 16 cache lines,
 //     which the texture addresser cannot sustain), transposed through a 4 KB
@@ -166,25 +170,34 @@ __global__ __launch_bounds__(MAXW * 64) void gemv_mfma_kernel(const typename gem
       }
   };
   // load order -> operand order, in place, through the wave's transposition area (free between blocks)
+  auto transpose_x_block = [&](int bi) {
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int r = 4 * u + lr;
+        stage[r * 16 + (lp ^ r)] = xs[ct][bi][u];
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+      for (int s = 0; s < 4; ++s) xs[ct][bi][s] = stage[c * 16 + ((4 * s + q) ^ c)];
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+    }
+  };
   auto transpose_x = [&]() {
 #pragma unroll
-    for (int ct = 0; ct < CT; ++ct)
-#pragma unroll
-      for (int bi = 0; bi < NBK; ++bi) {
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const int r = 4 * u + lr;
-          stage[r * 16 + (lp ^ r)] = xs[ct][bi][u];
-        }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-#pragma unroll
-        for (int s = 0; s < 4; ++s) xs[ct][bi][s] = stage[c * 16 + ((4 * s + q) ^ c)];
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-      }
+    for (int bi = 0; bi < NBK; ++bi) transpose_x_block(bi);
   };
+  // One chunk per wave, no fused prologue: the first weights are requested in front of X (their HBM
+  // round trip is the longer one), and X is turned block by block right before its first use
+  // instead of all at once in front of the stream (which holds the stream's window still).  Timed
+  // in an interleaved A/B of two builds: 0.6 % of a batch-8 step; with several chunks per wave, or
+  // with two or four column tiles (more X than weights in a wave's first requests), it loses
+  // (0.5 to 1.7 % of a batch-64 step) and is not used.
+  constexpr bool WFIRST = ONECHUNK && !PRO && CT == 1;
   auto load_x = [&](int ch) {
 #pragma unroll
     for (int bi = 0; bi < NBK; ++bi) load_x_block(ch, bi);
@@ -381,9 +394,16 @@ __global__ __launch_bounds__(MAXW * 64) void gemv_mfma_kernel(const typename gem
       }
     }
   } else if (active) {
-    load_x(wave);  // the first chunk; with several chunks per wave the next one's X follows block by block below
+    if constexpr (WFIRST) {
 #pragma unroll
-    for (int t = 0; t < NB; ++t) load_block(wbuf[t], 0, wave, t / NBK, t % NBK);
+      for (int t = 0; t < NB; ++t) load_block(wbuf[t], 0, wave, t / NBK, t % NBK);
+      __builtin_amdgcn_sched_barrier(0);
+      load_x(wave);
+    } else {
+      load_x(wave);  // the first chunk; with several chunks per wave the next one's X follows block by block below
+#pragma unroll
+      for (int t = 0; t < NB; ++t) load_block(wbuf[t], 0, wave, t / NBK, t % NBK);
+    }
   }
   VTE_STAMP(1);  // launch arguments in, first loads issued
   for (int rd = 0; rd < a.groups; ++rd) {
@@ -395,8 +415,8 @@ __global__ __launch_bounds__(MAXW * 64) void gemv_mfma_kernel(const typename gem
       int ch = wave;
       while (true) {
         // X of this chunk arrived in load order: once per launch when a wave has a single chunk, else per chunk pass
-        if (!ONECHUNK || rd == 0) transpose_x();
-        if (rd == 0 && ch == wave) VTE_STAMP(2);  // X arrived and turned
+        if (!WFIRST && (!ONECHUNK || rd == 0)) transpose_x();
+        if (!WFIRST && rd == 0 && ch == wave) VTE_STAMP(2);  // X arrived and turned
         const int chn = ch + nw;
         const bool more = !ONECHUNK && chn < nchunks;  // ONECHUNK: the launch has no more chunks than waves
         const bool next_round = rd + 1 < a.groups;
@@ -406,6 +426,12 @@ __global__ __launch_bounds__(MAXW * 64) void gemv_mfma_kernel(const typename gem
           // keep the written order (the scheduler would otherwise sink the loads
           // next to their uses and leave two or three in flight)
           __builtin_amdgcn_sched_barrier(0);
+          if constexpr (WFIRST) {
+            if (rd == 0 && g == 0) {  // the first use of this block of X
+              transpose_x_block(bi);
+              if (bi == 0) VTE_STAMP(2);  // the first block of X arrived and turned
+            }
+          }
 #pragma unroll
           for (int u = 0; u < 4; ++u) {
             const int r = 4 * u + lr;
