@@ -629,7 +629,7 @@ def overhead_pools(launches):
     return arms
 
 
-RAMP_POINTS = ("entry", "arguments in, first loads issued", "X arrived and turned", "first block of weights multiplied",
+RAMP_POINTS = ("entry", "arguments in, first loads issued", "X (its first block) arrived and turned", "first block of weights multiplied",
                "wave's share of the stream through", "all waves of the workgroup through", "sums added, outputs stored")
 
 
