@@ -490,13 +490,22 @@ __global__ __launch_bounds__(MAXW * 64) void gemv_mfma_kernel(const typename gem
       float s[4], u[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int v = 0; v < 4; ++v) {
+        // every wave area exists in LDS whether or not its wave does, so all MAXW partial sums are
+        // read at once (one LDS latency instead of one per wave) and those of absent waves left out
         const float* pp = part_all + (gc * 4 + v) * 64 + ln;
-        float t = pp[0];
-        for (int w = 1; w < nw; ++w) t += pp[w * WAVE_F];  // ascending wave (K) order
+        float pw[MAXW];
+#pragma unroll
+        for (int w = 0; w < MAXW; ++w) pw[w] = pp[w * WAVE_F];
+        float t = pw[0];
+#pragma unroll
+        for (int w = 1; w < MAXW; ++w) t = w < nw ? t + pw[w] : t;  // ascending wave (K) order
         s[v] = t;
         if constexpr (EPI == EPI_SILU) {
-          float t2 = pp[32];
-          for (int w = 1; w < nw; ++w) t2 += pp[w * WAVE_F + 32];
+#pragma unroll
+          for (int w = 0; w < MAXW; ++w) pw[w] = pp[w * WAVE_F + 32];
+          float t2 = pw[0];
+#pragma unroll
+          for (int w = 1; w < MAXW; ++w) t2 = w < nw ? t2 + pw[w] : t2;
           u[v] = t2;
         }
       }
