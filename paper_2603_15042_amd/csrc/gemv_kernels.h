@@ -193,8 +193,14 @@ __global__ __launch_bounds__(MAXW * 64) void gemv_kernel(const GemvArgs a) {
     if (wave == g % nw) {
       float s = 0.f;
       if (lane < NV) {
-        s = part[g & 1][0][lane];
-        for (int ww = 1; ww < nw; ++ww) s += part[g & 1][ww][lane];
+        // all MAXW slots exist in LDS: read them at once (one LDS latency, not one per wave), then
+        // add those of the waves there are, in ascending order
+        float pw[MAXW];
+#pragma unroll
+        for (int ww = 0; ww < MAXW; ++ww) pw[ww] = part[g & 1][ww][lane];
+        s = pw[0];
+#pragma unroll
+        for (int ww = 1; ww < MAXW; ++ww) s = ww < nw ? s + pw[ww] : s;
       }
       if (a.S == 1) {
         finish(g, s);
@@ -250,10 +256,15 @@ __global__ __launch_bounds__(MAXW * 64) void gemv_kernel(const GemvArgs a) {
     uint32_t* cand_v = a.ws + 1 + gridDim.x * gridDim.z;
     uint32_t* cand_i = cand_v + static_cast<size_t>(a.bt) * gridDim.x;
     if (threadIdx.x < BT) {
-      float bv = s_bv[0][threadIdx.x];
-      int bi = s_bi[0][threadIdx.x];
-      for (int ww = 1; ww < nw; ++ww)
-        if (better(s_bv[ww][threadIdx.x], s_bi[ww][threadIdx.x], bv, bi)) { bv = s_bv[ww][threadIdx.x]; bi = s_bi[ww][threadIdx.x]; }
+      float wv[MAXW];
+      int wi[MAXW];
+#pragma unroll
+      for (int ww = 0; ww < MAXW; ++ww) { wv[ww] = s_bv[ww][threadIdx.x]; wi[ww] = s_bi[ww][threadIdx.x]; }
+      float bv = wv[0];
+      int bi = wi[0];
+#pragma unroll
+      for (int ww = 1; ww < MAXW; ++ww)
+        if (ww < nw && better(wv[ww], wi[ww], bv, bi)) { bv = wv[ww]; bi = wi[ww]; }
       cand_v[static_cast<size_t>(b0 + threadIdx.x) * gridDim.x + blockIdx.x] = __float_as_uint(bv);
       cand_i[static_cast<size_t>(b0 + threadIdx.x) * gridDim.x + blockIdx.x] = static_cast<uint32_t>(bi);
     }

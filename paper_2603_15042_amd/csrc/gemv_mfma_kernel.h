@@ -583,10 +583,15 @@ __global__ __launch_bounds__(MAXW * 64) void gemv_mfma_kernel(const typename gem
     uint32_t* cand_v = a.ws + 1 + gridDim.x * gridDim.z;
     uint32_t* cand_i = cand_v + static_cast<size_t>(a.bt) * gridDim.x;
     if (threadIdx.x < 16 * CT && row0 + static_cast<int>(threadIdx.x) < a.B) {
-      float bv = s_bv[0][threadIdx.x];
-      int bi = s_bi[0][threadIdx.x];
-      for (int w = 1; w < nw; ++w)
-        if (better(s_bv[w][threadIdx.x], s_bi[w][threadIdx.x], bv, bi)) { bv = s_bv[w][threadIdx.x]; bi = s_bi[w][threadIdx.x]; }
+      float wv[MAXW];
+      int wi[MAXW];
+#pragma unroll
+      for (int w = 0; w < MAXW; ++w) { wv[w] = s_bv[w][threadIdx.x]; wi[w] = s_bi[w][threadIdx.x]; }
+      float bv = wv[0];
+      int bi = wi[0];
+#pragma unroll
+      for (int w = 1; w < MAXW; ++w)
+        if (w < nw && better(wv[w], wi[w], bv, bi)) { bv = wv[w]; bi = wi[w]; }
       cand_v[static_cast<size_t>(row0 + threadIdx.x) * gridDim.x + blockIdx.x] = __float_as_uint(bv);
       cand_i[static_cast<size_t>(row0 + threadIdx.x) * gridDim.x + blockIdx.x] = static_cast<uint32_t>(bi);
     }

@@ -274,13 +274,18 @@ __global__ __launch_bounds__(WR * 64) void gemv_rows_kernel(const GemvArgs a) {
     uint32_t* cand_v = a.ws + 1 + gridDim.x;
     uint32_t* cand_i = cand_v + static_cast<size_t>(a.bt) * gridDim.x;
     if (threadIdx.x < 16 * CT && static_cast<int>(threadIdx.x) < a.B) {
-      float bv = reinterpret_cast<const float*>(wstage_all)[threadIdx.x];
-      int bi = reinterpret_cast<const int*>(wstage_all)[64 + threadIdx.x];
-      for (int w = 1; w < WR; ++w) {
-        const float ov = reinterpret_cast<const float*>(wstage_all + w * 256)[threadIdx.x];
-        const int oi = reinterpret_cast<const int*>(wstage_all + w * 256)[64 + threadIdx.x];
-        if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+      float wv[WR];  // every wave's candidate, read at once
+      int wi[WR];
+#pragma unroll
+      for (int w = 0; w < WR; ++w) {
+        wv[w] = reinterpret_cast<const float*>(wstage_all + w * 256)[threadIdx.x];
+        wi[w] = reinterpret_cast<const int*>(wstage_all + w * 256)[64 + threadIdx.x];
       }
+      float bv = wv[0];
+      int bi = wi[0];
+#pragma unroll
+      for (int w = 1; w < WR; ++w)
+        if (better(wv[w], wi[w], bv, bi)) { bv = wv[w]; bi = wi[w]; }
       cand_v[static_cast<size_t>(threadIdx.x) * gridDim.x + blockIdx.x] = __float_as_uint(bv);
       cand_i[static_cast<size_t>(threadIdx.x) * gridDim.x + blockIdx.x] = static_cast<uint32_t>(bi);
     }

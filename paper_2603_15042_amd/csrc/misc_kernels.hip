@@ -126,20 +126,37 @@ __global__ __launch_bounds__(256) void split_finish_kernel(const SplitFinishArgs
   const int n0 = (blockIdx.x * 256 + threadIdx.x) * 4;
   if (b >= a.B || n0 >= a.n_out) return;
   float g[4], u[4];
+  const size_t stride = static_cast<size_t>(a.bt) * a.N;
+  int off[4];  // clamped: a tail thread re-reads the last output
 #pragma unroll
-  for (int v = 0; v < 4; ++v) {
-    const int n = n0 + v < a.n_out ? n0 + v : a.n_out - 1;  // clamped: a tail thread re-reads the last output
-    const float* p = a.partials + static_cast<size_t>(b) * a.N + n;
-    const size_t stride = static_cast<size_t>(a.bt) * a.N;
-    float t = p[0];
-    for (int s = 1; s < a.S; ++s) t += p[s * stride];
-    g[v] = t;
-    if (a.silu) {
-      float t2 = p[a.n_out];
-      for (int s = 1; s < a.S; ++s) t2 += p[s * stride + a.n_out];
-      u[v] = t2;
+  for (int v = 0; v < 4; ++v) off[v] = (n0 + v < a.n_out ? n0 + v : a.n_out - 1) - n0;
+  // The parts of an output are added in ascending order; their loads do not depend on one another
+  // and are requested eight parts at a time (a loop of load-then-add pays a memory round trip per part).
+  auto sum_parts = [&](const float* p0, float(&out)[4]) {
+    const bool vec = n0 + 3 < a.n_out && (reinterpret_cast<uintptr_t>(p0) & 15) == 0 && (stride & 3) == 0;
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+#pragma unroll
+    for (int v = 0; v < 4; ++v) out[v] = 0.f;
+    for (int s0 = 0; s0 < a.S; s0 += 8) {
+      f32x4 t[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const float* q = p0 + static_cast<size_t>(s0 + j) * stride;
+        if (s0 + j >= a.S) t[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+        else if (vec) t[j] = *reinterpret_cast<const f32x4*>(q);
+        else t[j] = f32x4{q[off[0]], q[off[1]], q[off[2]], q[off[3]]};
+      }
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        if (s0 + j >= a.S) break;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) out[v] = (s0 + j == 0) ? t[j][v] : out[v] + t[j][v];
+      }
     }
-  }
+  };
+  const float* p = a.partials + static_cast<size_t>(b) * a.N + n0;
+  sum_parts(p, g);
+  if (a.silu) sum_parts(p + a.n_out, u);
 #pragma unroll
   for (int v = 0; v < 4; ++v) {
     if (n0 + v >= a.n_out) break;

@@ -62,10 +62,21 @@ __global__ __launch_bounds__(T) void norm_kernel(const NormArgs a) {
     const uint32_t* ci = a.cand + static_cast<size_t>(a.cand_bt) * a.nblocks + static_cast<size_t>(row) * a.nblocks;
     float bv = -INFINITY;
     int bi = INT_MAX;
-    for (int blk = threadIdx.x; blk < a.nblocks; blk += T) {
-      const float v = __uint_as_float(cv[blk]);
-      const int i = static_cast<int>(ci[blk]);
-      if (better(v, i, bv, bi)) { bv = v; bi = i; }
+    // four candidates per thread are requested before the first is looked at: for up to 4 T
+    // workgroups of the LM head (501 at the Llama-8B shape) the reduction costs one memory round trip
+    for (int base = 0; base < a.nblocks; base += 4 * T) {
+      float v[4];
+      int ix[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int blk = base + u * T + static_cast<int>(threadIdx.x);
+        const bool ok = blk < a.nblocks;
+        v[u] = ok ? __uint_as_float(cv[blk]) : -INFINITY;
+        ix[u] = ok ? static_cast<int>(ci[blk]) : INT_MAX;
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (better(v[u], ix[u], bv, bi)) { bv = v[u]; bi = ix[u]; }
     }
 #pragma unroll
     for (int d = 1; d < 64; d <<= 1) {
