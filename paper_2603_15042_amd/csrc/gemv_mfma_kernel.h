@@ -398,6 +398,7 @@ __global__ __launch_bounds__(MAXW * 64) void gemv_mfma_kernel(const typename gem
 #pragma unroll
       for (int t = 0; t < NB; ++t) load_block(wbuf[t], 0, wave, t / NBK, t % NBK);
       __builtin_amdgcn_sched_barrier(0);
+      VTE_STAMP(7);  // first weights requested
       load_x(wave);
     } else {
       load_x(wave);  // the first chunk; with several chunks per wave the next one's X follows block by block below

@@ -633,8 +633,10 @@ def overhead_pools(launches):
     return arms
 
 
-RAMP_POINTS = ("entry", "arguments in, first loads issued", "X (its first block) arrived and turned", "first block of weights multiplied",
-               "wave's share of the stream through", "all waves of the workgroup through", "sums added, outputs stored")
+RAMP_POINTS = ("entry", "first weights requested", "all first loads issued (weights, then X)", "X (its first block) arrived and turned",
+               "first block of weights multiplied", "wave's share of the stream through", "all waves of the workgroup through",
+               "sums added, outputs stored")
+RAMP_SLOTS = (0, 7, 1, 2, 3, 4, 5, 6)   # the stamp slot (csrc/gemv_mfma_kernel.h) behind each point, in the order of the timeline
 
 
 def ramp(batches=(8, 16), N=4096, K=4096, width=256, bursts=9):
@@ -672,7 +674,7 @@ def ramp(batches=(8, 16), N=4096, K=4096, width=256, bursts=9):
             rc = L.vte_trace_stamps_read(buf.ctypes.data_as(C.c_void_p), C.c_size_t(buf.size))
             if rc != 0:
                 raise RuntimeError("vte_trace_stamps_read: HIP error %d" % rc)
-            st = buf.reshape(1024, 8, 8).astype(np.int64)[:min(wgs, 1024), :waves, :len(RAMP_POINTS)]
+            st = buf.reshape(1024, 8, 8).astype(np.int64)[:min(wgs, 1024), :waves][:, :, list(RAMP_SLOTS)]
             rel = (st - st[:, :, 0].min()) * 0.01                 # us after the first wave's entry
             tables.append([[float(f(rel[:, :, i])) for f in (np.min, lambda c: np.percentile(c, 10), np.median,
                                                              lambda c: np.percentile(c, 90), np.max)] for i in range(len(RAMP_POINTS))])
