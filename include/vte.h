@@ -447,7 +447,10 @@ int vte_vstream_wait_event(vte_vstream* vs, vte_token event);
  * vte_last_hip_error() of the calling thread.  vte_vstream_sync, having reported a failed
  * tail, empties the tail: later submissions do not inherit the failure.  vte_device_sync
  * returns the first failure that no earlier vte_device_sync has returned.  After a device
- * fault HIP itself stays in error: expect every later launch of the process to fail. */
+ * fault HIP itself stays in error: expect every later launch of the process to fail.
+ * A waiting call sleeps while what it waits for is still queued; once all of it has been handed to
+ * the device the calling thread polls instead (for 20 ms at most per call, then it sleeps again):
+ * the completion of a short launch is then seen a wake-up sooner, at the price of a busy core. */
 int vte_token_query(vte_ctx* ctx, vte_token token, int* done);
 int vte_token_wait(vte_ctx* ctx, vte_token token);
 int vte_vstream_sync(vte_vstream* vs); /* waits on the stream tail */
