@@ -938,8 +938,15 @@ bool planned_round(vte_ctx* c, const std::vector<vte_ready_op>& ready, const std
   for (size_t o = 0; o < ops.size(); ++o)
     if (ops[o].eligible.empty() && ops[o].later.empty() && ready[idx[o]].pinned_pctx < 0)
       oldest_starved = std::min(oldest_starved, ops[o].age);
+  // An op stands for the recurring chain its vstream runs (Sec. 5 "Performance Profiles"): the plan
+  // weighs the chain's profiled time at a width, not the time of the launch that happens to be ready
+  // when the plan is made.  Planned per launch, a stream whose ready op was a norm (flat profile) or
+  // a small projection was left on a leaf while the co-tenant took the remainder, and the leases
+  // then kept it there: decode on 32 + 32 CUs beside a GEMM on 192, sum 1.10 against 1.21 for the
+  // fixed split at 80 requests/s.
   const std::vector<int> A = tput_plan(c->pool, ops, [&](int o, int width) {
-    return profile_time(c, ready[idx[o]].desc.profile_key, width);
+    const double t = chain_time(c, &ready[idx[o]], width);
+    return t > 0 ? t : profile_time(c, ready[idx[o]].desc.profile_key, width);
   });
   std::vector<int> order(ops.size());
   for (size_t o = 0; o < order.size(); ++o) order[o] = static_cast<int>(o);

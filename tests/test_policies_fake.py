@@ -74,6 +74,37 @@ def test_tput_plan_flat_ops_stay_narrow_and_scaling_ops_widen():
         vte.vte_shutdown(c)
 
 
+def test_tput_plan_weighs_a_stream_by_its_recurring_chain_not_by_the_launch_at_hand():
+    """Sec. 5 "Performance Profiles": a stream that alternates a flat launch (a norm) with one that scales
+    (a projection) is planned by the profile of the chain.  Planned by the launch that happens to be ready,
+    the flat one would keep the stream on a leaf while a co-tenant takes the rest of the device."""
+    c = make_ctx(remainders=vte.VTE_REMAINDERS_NONE)
+    try:
+        flat = vte.vte_desc_rmsnorm(c, A, A, A, 8, 1024, 1e-6)
+        lin = vte.vte_desc_gemv(c, A, A, A, 1, 4096, 4096, 0)
+        ten = vte.vte_desc_gemv(c, A, A, A, 1, 6144, 4096, 0)
+        set_profile(c, flat, lambda w: 4e-6)                      # gains nothing from more CUs
+        set_profile(c, lin, lambda w: 1e-3 * 32 / w)              # scales perfectly
+        set_profile(c, ten, lambda w: 1e-3 * (32 / w) ** 0.3)     # the co-tenant: sublinear
+        chain, other = vte.vte_vstream_create(c, vte.VTE_CLASS_BEST_EFFORT), vte.vte_vstream_create(c, vte.VTE_CLASS_BEST_EFFORT)
+        first = vte.vte_submit(chain, lin)                        # the chain's history: the scaling launch has run
+        vte.vte_dispatcher_quiesce(c)
+        finish(c, [first])
+        keep = park(c)
+        t_flat, t_ten = vte.vte_submit(chain, flat), vte.vte_submit(other, ten)
+        vte.vte_dispatcher_quiesce(c)
+        vte.vte_set_builtin_policy(c, vte.VTE_POLICY_TPUT_PLAN)
+        vte.vte_dispatcher_quiesce(c)
+        b, ps = bound(c), infos(c)
+        assert ps[b[t_flat]].width == 128 and ps[b[t_ten]].width == 128, (ps[b[t_flat]].width, ps[b[t_ten]].width)
+        assert_disjoint(c, [b[t_flat], b[t_ten]])
+        finish(c, [t_flat, t_ten])
+        # a stream whose whole history is flat stays narrow (the first test of this file), chain or not
+        del keep
+    finally:
+        vte.vte_shutdown(c)
+
+
 def test_tput_plan_prefers_the_steeper_profile():
     c = make_ctx(remainders=vte.VTE_REMAINDERS_NONE)
     try:
