@@ -389,7 +389,7 @@ def main():
         # ---- co-tenancy (BASELINE config 4): decode bursts beside the 8192^3 GEMM -----------------
         if not a.small:
             with _section(out, "co-tenancy"):
-                r = E.cotenancy(a.cotenancy_seconds, 60.0, shared=shared, modes=("fixed", "late"))
+                r = E.cotenancy(a.cotenancy_seconds, 60.0, shared=shared, modes=("fixed", "late", "late_nohint"))
                 keep = ("gemm_per_s", "norm_gemm", "norm_decode", "aggregate_normalized_throughput", "bursts", "bursts_compared",
                         "bursts_with_token_mismatch", "step_ms_mean", "step_latency_ms_p50", "step_latency_ms_p99", "steps_timed",
                         "first_step_ms_mean", "gemm_widths", "decode_widths", "overlap")
@@ -397,7 +397,8 @@ def main():
                     "seconds_per_mode": a.cotenancy_seconds, "gemm_tflops_solo": round(r["gemm_tflops_solo"], 1),
                     "solo_decode": {k: r["solo_decode"].get(k) for k in ("step_ms_mean", "step_latency_ms_p50", "step_latency_ms_p99", "bursts")},
                     "fixed_128_128": {k: r["fixed"].get(k) for k in keep},
-                    "late_bound": {k: r["late"].get(k) for k in keep},
+                    "late_bound": {k: r["late"].get(k) for k in keep},                    # with a 3 ms arrival hint per burst
+                    "late_bound_no_hint": {k: r["late_nohint"].get(k) for k in keep},  # the policy alone
                     "late_bound_beats_fixed_split": bool(r["late"]["aggregate_normalized_throughput"] > r["fixed"]["aggregate_normalized_throughput"]),
                 }
         for k in ("gA", "gB", "gC"):

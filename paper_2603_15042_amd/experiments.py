@@ -354,6 +354,11 @@ def cotenancy(seconds, gap_ms, steps_per_burst=128, lead_ms=3.0, shared=None, mo
         """mode: 'solo' | 'fixed' | 'late' | 'late_nohint'.  Returns dict of raw measurements."""
         vte.vte_device_sync(ctx)
         vte.vte_stats_reset(ctx)
+        # a hint of the mode before may have been submitted and not used (the run ended before its burst): its
+        # reservation would keep the GEMM off the full device for this whole mode
+        for i in range(vte.vte_pool_count(ctx)):
+            if vte.vte_pool_info(ctx, i).reserved_for == vte.vte_vstream_id(lat):
+                vte.vte_pctx_unreserve(ctx, i)
         vte.vte_vstream_pin(lat, a128 if mode == "fixed" else -1)
         vte.vte_vstream_pin(be, b128 if mode == "fixed" else -1)
         # slack 0.4: beside the GEMM the decode chain takes the narrowest pCtx whose profiled chain time is within
